@@ -1,0 +1,260 @@
+"""Pins of the oracle's accept / resample step (CPU only).
+
+What the paper fixes (Section 2): the emitted tokens are distributed as if sampled from the
+target alone; a draft with q <= p is always kept; otherwise it is dropped with probability
+1 - p/q and replaced by a draw from norm(max(0, p - q)); one extra token follows a fully
+accepted block.  Section 3.1 adds lenience and the greedy rule; Theorem 4.1 gives the law of
+the number of tokens per step under i.i.d. acceptance.  Every test below checks one of these
+by exact counting over uniform grids, by a fixed-seed chi-square, or by a closed form.
+"""
+import numpy as np
+import pytest
+
+import csd_inputs as I
+from oracle import csd_oracle as O
+
+
+def _dist(rng, V, zeros=0):
+    x = rng.random(V).astype(np.float64) ** 2
+    if zeros:
+        x[rng.choice(V, zeros, replace=False)] = 0.0
+    x /= x.sum()
+    return x.astype(np.float32)
+
+
+def _grid(n):
+    return (np.arange(n, dtype=np.float64) / n).astype(np.float32)      # exact multiples of 1/n
+
+
+def test_dyadic_inverse_cdf_is_exact_and_ordered_by_token_id():
+    p = np.array([0.5, 0.0, 0.25, 0.125, 0.125], np.float32)
+    N = 1024
+    u = _grid(N)
+    P = np.broadcast_to(p, (N, 1, 5))
+    n_acc, nxt = O.accept(P, None, np.zeros((N, 0), np.int32), np.zeros((N, 0), np.float32), u)
+    assert (n_acc == 0).all()
+    cdf = np.cumsum(p.astype(np.float64))
+    want = np.searchsorted(cdf, u.astype(np.float64), side="right")
+    np.testing.assert_array_equal(nxt, want)
+    np.testing.assert_array_equal(np.bincount(nxt, minlength=5), [512, 0, 256, 128, 128])
+
+
+def test_first_emitted_token_follows_target_exactly_on_a_grid():
+    """Sum over the draft token (weight q(x)) and over grids of both uniforms: the law of the
+    first emitted token is p_1 up to the grid resolution."""
+    rng = np.random.default_rng(2)
+    V, N = 5, 256
+    for trial in range(3):
+        p1, p2, q1 = _dist(rng, V, zeros=trial), _dist(rng, V), _dist(rng, V, zeros=1 if trial == 2 else 0)
+        law = np.zeros(V)
+        ua, us = np.meshgrid(_grid(N), _grid(N), indexing="ij")
+        for x in range(V):
+            if q1[x] == 0:
+                continue
+            B = N * N
+            P = np.broadcast_to(np.stack([p1, p2]), (B, 2, V))
+            Q = np.broadcast_to(q1[None, :], (B, 1, V))
+            n_acc, nxt = O.accept(P, Q, np.full((B, 1), x, np.int32), ua.reshape(B, 1), us.reshape(B))
+            first = np.where(n_acc == 1, x, nxt)
+            law += q1[x] * np.bincount(first, minlength=V) / B
+        np.testing.assert_allclose(law, p1, atol=2.5 / N)
+
+
+def test_two_token_joint_law_chi_square():
+    """Context-dependent target and draft tables over V = 4; k = 2 drafts per step.  The first
+    two emitted tokens (running a second step when the first emits only one) must follow
+    p(y1) p(y2 | y1).  Fixed seeds; chi-square with 15 degrees of freedom."""
+    V, B = 4, 400_000
+    rng = np.random.default_rng(7)
+    p0, q0 = _dist(rng, V), _dist(rng, V)
+    p1 = np.stack([_dist(rng, V) for _ in range(V)])     # p(. | y1)
+    q1 = np.stack([_dist(rng, V) for _ in range(V)])
+    p2 = np.stack([_dist(rng, V) for _ in range(V)])     # third row: any distribution
+
+    def draw(q_rows, u):                                 # inverse CDF of per-trial rows
+        cdf = np.cumsum(q_rows.astype(np.float64), axis=1)
+        cdf[:, -1] = 1.0
+        return (u[:, None] >= cdf).sum(axis=1).astype(np.int32)
+
+    U = [I.uniforms(B, 99, s).numpy() for s in range(8)]
+    x1 = draw(np.broadcast_to(q0, (B, V)), U[0])
+    x2 = draw(q1[x1], U[1])
+    P = np.stack([np.broadcast_to(p0, (B, V)), p1[x1], p2[x2]], axis=1)
+    Q = np.stack([np.broadcast_to(q0, (B, V)), q1[x1]], axis=1)
+    n_acc, nxt = O.accept(P, Q, np.stack([x1, x2], 1), np.stack([U[2], U[3]], 1), U[4])
+    y1 = np.where(n_acc >= 1, x1, nxt)
+    y2 = np.where(n_acc == 2, x2, nxt)
+    # trials that emitted a single token run a second step (k = 1) from the new context
+    idx = np.nonzero(n_acc == 0)[0]
+    xb = draw(q1[y1[idx]], U[5][idx])
+    Pb = np.stack([p1[y1[idx]], p2[xb]], axis=1)
+    Qb = q1[y1[idx]][:, None, :]
+    nb, tb = O.accept(Pb, Qb, xb[:, None], U[6][idx][:, None], U[7][idx])
+    y2[idx] = np.where(nb == 1, xb, tb)
+    counts = np.bincount(y1 * V + y2, minlength=V * V).astype(np.float64)
+    expect = (p0[:, None].astype(np.float64) * p1.astype(np.float64)).reshape(-1) * B
+    chi2 = ((counts - expect) ** 2 / expect).sum()
+    assert chi2 < 37.7, chi2            # 99.9 % quantile of chi-square(15)
+    # and the marginal of the first token alone
+    c1 = np.bincount(y1, minlength=V)
+    assert (((c1 - p0 * B) ** 2) / (p0 * B)).sum() < 16.3     # chi-square(3), 99.9 %
+
+
+def test_identical_draft_is_always_accepted():
+    rng = np.random.default_rng(3)
+    V, k, N = 7, 3, 4096
+    p = np.stack([_dist(rng, V) for _ in range(k + 1)])
+    u = np.concatenate([_grid(N - 1), np.array([1 - 2.0 ** -24], np.float32)])   # includes the largest uniform
+    for x in range(V):
+        if (p[:k, x] == 0).any():
+            continue
+        P = np.broadcast_to(p, (N, k + 1, V))
+        n_acc, _ = O.accept(P, P[:, :k], np.full((N, k), x, np.int32), np.repeat(u[:, None], k, 1), u)
+        assert (n_acc == k).all()
+
+
+def test_zero_target_probability_is_never_accepted():
+    p = np.array([[0.0, 0.6, 0.4], [0.2, 0.3, 0.5]], np.float32)
+    q = np.array([[0.5, 0.25, 0.25]], np.float32)
+    n_acc, nxt = O.accept(p[None], q[None], [[0]], [[0.0]], [0.0])
+    assert n_acc[0] == 0 and nxt[0] == 1          # residual max(0,p-q) = [0,.35,.15] -> first non-zero id at u=0
+    n_acc, _ = O.accept(p[None], None, [[0]], [[0.0]], [0.0])
+    assert n_acc[0] == 0
+
+
+def test_acceptance_frequency_is_min_p_q_and_one_hot_gives_p():
+    rng = np.random.default_rng(4)
+    V, N = 6, 8192
+    p, q = np.stack([_dist(rng, V), _dist(rng, V)]), _dist(rng, V)
+    u = _grid(N)
+    total = 0.0
+    for x in range(V):
+        P = np.broadcast_to(p, (N, 2, V))
+        n_acc, _ = O.accept(P, np.broadcast_to(q, (N, 1, V)), np.full((N, 1), x, np.int32), u[:, None], u)
+        freq = n_acc.mean()
+        assert abs(freq - min(1.0, p[0, x] / q[x])) <= 1.0 / N + 1e-7
+        total += q[x] * freq
+        n1, _ = O.accept(P, None, np.full((N, 1), x, np.int32), u[:, None], u)   # one-hot draft
+        assert abs(n1.mean() - p[0, x]) <= 1.0 / N + 1e-7
+    assert abs(total - np.minimum(p[0], q).sum()) < 1e-3
+
+
+@pytest.mark.parametrize("lenience", [1.0, 1.5, 3.0])
+def test_residual_law_with_and_without_lenience(lenience):
+    """After a rejection the replacement follows norm(max(0, l*p - q)); the acceptance
+    frequency is min(1, l*p/q) (Section 3.1)."""
+    rng = np.random.default_rng(5)
+    V, N = 6, 4096
+    p, q = np.stack([_dist(rng, V), _dist(rng, V)]), _dist(rng, V)
+    x = int(np.argmax(q / np.maximum(p[0], 1e-9)))     # a token the draft over-proposes
+    res = np.maximum(0.0, lenience * p[0].astype(np.float64) - q)
+    if res.sum() == 0:
+        pytest.skip("no rejection possible")
+    P = np.broadcast_to(p, (N, 2, V))
+    Q = np.broadcast_to(q, (N, 1, V))
+    n_acc, nxt = O.accept(P, Q, np.full((N, 1), x, np.int32), np.full((N, 1), 1 - 2.0 ** -24, np.float32),
+                          _grid(N), lenience=lenience)
+    if lenience * p[0, x] >= q[x]:
+        assert (n_acc == 1).all()
+        return
+    assert (n_acc == 0).all()
+    law = np.bincount(nxt, minlength=V) / N
+    np.testing.assert_allclose(law, res / res.sum(), atol=(V + 1) / N)
+    n2, _ = O.accept(P, Q, np.full((N, 1), x, np.int32), _grid(N)[:, None], _grid(N), lenience=lenience)
+    assert abs(n2.mean() - min(1.0, lenience * p[0, x] / q[x])) <= 1.0 / N + 1e-7
+
+
+def test_all_zero_residual_falls_back_to_target_row():
+    p = np.array([[0.25, 0.75], [0.5, 0.5]], np.float32)
+    # u*q < p fails only through rounding-free equality: force a rejection with p == q by u = 1 (not a
+    # legal uniform, used here only to reach the guarded branch)
+    n_acc, nxt = O.accept(p[None], p[None, :1], [[1]], [[1.0]], [0.3])
+    assert n_acc[0] == 0 and nxt[0] == 1      # cdf of p row 0: [.25, 1.0]; u_s = .3 -> id 1
+
+
+@pytest.mark.parametrize("alpha,k", [(0.6, 1), (0.6, 2), (0.6, 4), (0.6, 8), (0.6, 16), (0.3, 5), (0.9, 3)])
+def test_tokens_per_step_law_matches_theorem_4_1(alpha, k):
+    """I.i.d. acceptance with probability alpha: P(i tokens) = alpha^(i-1)(1-alpha) for i <= k and
+    alpha^k for i = k+1 (proof of Theorem 4.1); the generating function is Eq. 1 and its mean
+    (1 - alpha^(k+1)) / (1 - alpha) (corollary)."""
+    B, V = 1 << 18, 3
+    a32 = np.float32(alpha)
+    row = np.array([a32, 1 - a32, 0], np.float32)
+    P = np.broadcast_to(row, (B, k + 1, V))
+    U = I.uniforms(B * k, 1234 + k, 1).numpy().reshape(B, k)
+    n_acc, _ = O.accept(P, None, np.zeros((B, k), np.int32), U, I.uniforms(B, 77, 2).numpy())
+    n_tok = n_acc + 1
+    freq = np.bincount(n_tok, minlength=k + 2)[1:] / B
+    a = float(a32)
+    want = np.array([a ** (i - 1) * (1 - a) for i in range(1, k + 1)] + [a ** k])
+    chi2 = (B * (freq - want) ** 2 / np.maximum(want, 1e-300))[want * B > 5].sum()
+    assert chi2 < 45.0, chi2                         # chi-square(<=16 dof) 99.9 % is 39.3
+    assert abs(n_tok.mean() - (1 - a ** (k + 1)) / (1 - a)) < 0.01
+    for x in (0.5, 0.9, 1.0):                        # Eq. 1 evaluated at a few points
+        phi_emp = (freq * x ** np.arange(1, k + 2)).sum()
+        phi = 1 + (x - 1) * (1 - a ** (k + 1) * x ** (k + 1)) / (1 - a * x)
+        assert abs(phi_emp - phi) < 5e-3
+    # exact identity between the proof's coefficients and Eq. 1
+    for x in (0.3, 0.7):
+        lhs = sum(w * x ** (i + 1) for i, w in enumerate(want))
+        rhs = 1 + (x - 1) * (1 - a ** (k + 1) * x ** (k + 1)) / (1 - a * x)
+        assert abs(lhs - rhs) < 1e-12
+
+
+def test_tokens_after_first_rejection_are_discarded():
+    """Section 2: any token following a rejected one is dropped, even if it would pass."""
+    p = np.array([[0.9, 0.1], [0.0, 1.0], [0.9, 0.1], [0.5, 0.5]], np.float32)
+    n_acc, nxt = O.accept(p[None], None, [[0, 0, 0]], [[0.0, 0.0, 0.0]], [0.0])
+    assert n_acc[0] == 1 and nxt[0] == 1      # draft 2 has p = 0 -> rejected; residual = p row 1 minus one-hot
+
+
+def test_greedy_rule_and_ties():
+    """Temperature 0 (Section 5.1): a draft is kept iff it is the reviewer's arg-max (Section 3.1);
+    the emitted token is the arg-max of the row after the accepted drafts; ties -> smallest id."""
+    lg = np.array([[0.1, 2.0, 2.0, -1.0],
+                   [5.0, 1.0, 0.0, 0.0],
+                   [0.0, 0.0, 0.0, 3.0]], np.float32)
+    n_acc, nxt = O.accept(lg[None], None, [[1, 0]], np.zeros((1, 2)), [0.0], mode=1)
+    assert (n_acc[0], nxt[0]) == (2, 3)
+    n_acc, nxt = O.accept(lg[None], None, [[2, 0]], np.zeros((1, 2)), [0.0], mode=1)
+    assert (n_acc[0], nxt[0]) == (0, 1)       # token 2 ties with 1 but is not the first arg-max
+    n_acc, nxt = O.accept(lg[None], None, [[1, 3]], np.zeros((1, 2)), [0.0], mode=1)
+    assert (n_acc[0], nxt[0]) == (1, 0)
+
+
+def test_greedy_lenience_uses_probabilities():
+    """Greedy with l > 1 also keeps a non-arg-max draft when q(x) <= l * p(x) (Section 3.1)."""
+    p = np.array([[0.5, 0.3, 0.2], [0.1, 0.1, 0.8]], np.float32)
+    q = np.array([[0.1, 0.5, 0.4]], np.float32)
+    n_acc, _ = O.accept(p[None], q[None], [[1]], [[0.0]], [0.0], lenience=1.0, mode=1)
+    assert n_acc[0] == 0
+    n_acc, nxt = O.accept(p[None], q[None], [[1]], [[0.0]], [0.0], lenience=2.0, mode=1)
+    assert (n_acc[0], nxt[0]) == (1, 2)       # 0.5 <= 2 * 0.3
+    n_acc, _ = O.accept(p[None], None, [[1]], [[0.0]], [0.0], lenience=2.0, mode=1)
+    assert n_acc[0] == 0                      # one-hot draft: needs 1 <= 2 * 0.3
+
+
+def test_mixed_dense_and_one_hot_positions():
+    """A horizontal cascade hands over a block whose first tokens carry draft distributions and
+    whose tail (Max-Gram) is deterministic: per-position one-hot flags."""
+    rng = np.random.default_rng(8)
+    V, N = 5, 2048
+    p = np.stack([_dist(rng, V) for _ in range(3)])
+    q = np.stack([_dist(rng, V) for _ in range(2)])
+    u = _grid(N)
+    P = np.broadcast_to(p, (N, 3, V))
+    Q = np.broadcast_to(q, (N, 2, V))
+    d = np.broadcast_to(np.array([[1, 2]], np.int32), (N, 2))
+    U = np.stack([np.zeros(N, np.float32), u], 1)          # first always passes (if p>0)
+    n_acc, _ = O.accept(P, Q, d, U, u, q_onehot=np.array([0, 1], np.uint8))
+    assert abs((n_acc == 2).mean() - p[1, 2]) <= 1.0 / N + 1e-7
+    n_acc, _ = O.accept(P, Q, d, U, u, q_onehot=np.array([0, 0], np.uint8))
+    assert abs((n_acc == 2).mean() - min(1.0, p[1, 2] / q[1, 2])) <= 1.0 / N + 1e-7
+
+
+def test_argument_errors():
+    p = np.full((1, 2, 3), 1 / 3, np.float32)
+    with pytest.raises(RuntimeError):
+        O.accept(p, None, [[5]], [[0.1]], [0.1])          # draft id out of range
+    with pytest.raises(RuntimeError):
+        O.accept(p, None, [[1]], [[0.1]], [0.1], lenience=0.5)
