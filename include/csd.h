@@ -1,0 +1,180 @@
+/*
+ * csd.h — C ABI of the MI355X (gfx950) verify path of Cascade Speculative Drafting.
+ *
+ * One verify step of the cascade is three calls:
+ *   csd_bigram_draft   the statistical model at the bottom of both cascades drafts k tokens
+ *                      (Max-Gram with a bigram fallback; Section 3.3, Appendix A);
+ *   csd_verify_block   the reviewing model runs once over the whole drafted block against
+ *                      its KV cache and yields one distribution per position (Section 2);
+ *   csd_accept         speculative-sampling review: keep a prefix of the drafts, replace the
+ *                      first rejected one, or append one extra token (Section 2), with
+ *                      lenience and the greedy rule of Section 3.1.
+ *
+ * Conventions that hold for every call:
+ *   - The return value is a status: CSD_OK, or a negative CSD_E* code.  Nothing throws, logs
+ *     or synchronises the host with the device.
+ *   - Every array argument is a DEVICE pointer owned by the caller and must stay valid until
+ *     the stream has executed the work, unless the comment says "host".
+ *   - `stream` is a hipStream_t passed as void*; all work is enqueued on it, in order.
+ *   - Outputs are fully overwritten.  Inputs are never modified, except the KV cache.
+ *   - After csd_model_create nothing allocates device memory; scratch lives in the model, so
+ *     two calls that use the same model must not overlap (use one stream per model).
+ *   - Arguments are validated on the host before anything is enqueued; on error nothing is
+ *     enqueued.  Values that live on the device (token ids, lengths) cannot be validated by
+ *     the host: kernels clamp their own accesses and out-of-range ids give -1 outputs
+ *     (draft) or an all-zero embedding row (verify).
+ */
+#ifndef CSD_H
+#define CSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CSD_OK       0
+#define CSD_EINVAL  (-1)  /* a scalar argument is out of its domain                         */
+#define CSD_ESHAPE  (-2)  /* a size exceeds what the model / kernel was created for         */
+#define CSD_ENULL   (-3)  /* a required pointer is NULL                                     */
+#define CSD_EHIP    (-4)  /* a HIP call failed; see csd_last_hip_error()                    */
+#define CSD_EUNSUPPORTED (-5) /* configuration not implemented (e.g. arch != 0)             */
+
+#define CSD_DTYPE_FP32 0
+#define CSD_DTYPE_BF16 1
+#define CSD_MODE_SAMPLE 0
+#define CSD_MODE_GREEDY 1
+
+/* Reviewing-model description.  arch 0 is the LLaMA-style decoder of the benchmark
+ * configurations: RMSNorm, rotary embedding (half-split pairing, K cached after rotation),
+ * causal attention scaled by 1/sqrt(head_dim), SwiGLU, no biases, untied LM head. */
+typedef struct csd_model_cfg {
+    int32_t arch;        /* 0 only                                                          */
+    int32_t dtype;       /* CSD_DTYPE_*: storage type of the matrices and of the KV cache;  */
+                         /* norm gains, logits and probabilities are always fp32            */
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    int32_t max_batch;   /* most sequences per call                                         */
+    int32_t max_seq;     /* rows per sequence in the KV cache                               */
+    int32_t max_block;   /* most block rows m = k+1 per sequence per call                   */
+    int32_t enc_len;     /* reserved (encoder-decoder reviewers); must be 0                 */
+    float   rms_eps, rope_theta;
+} csd_model_cfg;
+
+typedef struct csd_model csd_model;   /* opaque; owns its packed copy of the weights + scratch */
+
+/* Library identification (host string, static storage). */
+const char *csd_version(void);
+/* hipError_t of the most recent failing HIP call made by this library on this thread's
+ * behalf (0 if none). */
+int32_t csd_last_hip_error(void);
+
+/*
+ * Build a model from caller-owned device tensors.  weight_ptrs is a HOST array of n_weights
+ * device pointers in canonical order:
+ *   embed[V][d], then per layer: attn_norm[d], wq[d][H*dh], wk, wv, wo[H*dh][d], ffn_norm[d],
+ *   w_gate[d][F], w_up[d][F], w_down[F][d]; then final_norm[d], lm_head[d][V].
+ * Matrices are row-major [in][out] in cfg->dtype; norm gains are fp32.  The weights are
+ * copied (re-tiled for the MFMA kernels when dtype is bf16); the caller may free its tensors
+ * once the stream has passed this call.  Allocates weights + scratch; this is the only
+ * allocating call besides destroy.  n_weights must be 3 + 9*n_layers.
+ */
+int32_t csd_model_create(const csd_model_cfg *cfg, const void *const *weight_ptrs, int32_t n_weights,
+                         void *stream, csd_model **out);
+/* Frees everything the model owns.  The caller synchronises its streams first. */
+int32_t csd_model_destroy(csd_model *model);
+
+/* Size in bytes of the KV cache the caller must allocate (256-byte aligned) for
+ * max_batch x max_seq rows.  The layout is private to the library; use csd_kv_write /
+ * csd_kv_read to move rows in canonical form. */
+size_t csd_kv_bytes(const csd_model *model);
+
+/* Copy n rows [pos0, pos0+n) of sequence b, layer `layer` into / out of the cache.
+ * K and V are fp32 [n][H*dh] (K as cached, i.e. after rotation); values are rounded to the
+ * cache dtype on write (round-to-nearest-even). */
+int32_t csd_kv_write(const csd_model *model, void *kv, int32_t layer, int32_t b, int32_t pos0, int32_t n,
+                     const float *K, const float *V, void *stream);
+int32_t csd_kv_read(const csd_model *model, const void *kv, int32_t layer, int32_t b, int32_t pos0, int32_t n,
+                    float *K, float *V, void *stream);
+
+/*
+ * Fit the bigram fallback table of Max-Gram on a token stream (Section 3.3; one parameter per
+ * vocabulary entry, Section 5.2): next_table[a] = the successor of a with the highest count;
+ * equal counts: the pair whose last occurrence is latest.  Entries of tokens with no
+ * successor in the stream keep the value the caller pre-filled.  n <= 8192.
+ */
+int32_t csd_bigram_fit(const int32_t *tokens, int32_t n, int32_t vocab, int32_t *next_table, void *stream);
+
+/*
+ * Max-Gram draft (Section 3.3, Appendix A).  ctx[B][ctx_stride] holds each sequence (prompt
+ * + generation so far), ctx_len[B] its length (1 <= len <= ctx_stride).  For each sequence:
+ * find the longest suffix that also ends at an earlier position e <= len-2 (the left-most e
+ * among the longest; match length optionally capped by max_match > 0) and emit the k tokens
+ * that follow e, reading on into the draft itself when the sequence ends.  If even the last
+ * token never occurred before, chain next_table from it.  out_tokens[B][k];
+ * out_match_len[B] (optional) receives the match length, 0 for the fallback.
+ */
+int32_t csd_bigram_draft(const int32_t *ctx, const int32_t *ctx_len, int32_t B, int32_t ctx_stride,
+                         const int32_t *next_table, int32_t vocab, int32_t k, int32_t max_match,
+                         int32_t *out_tokens, int32_t *out_match_len, void *stream);
+
+/*
+ * Review forward (Section 2: the reviewer scores all drafted positions in one run).
+ * tokens[B][m]: row 0 is the last committed token of the sequence (not yet in the cache),
+ * rows 1..m-1 are the drafts.  cache_len[B]: rows of the cache that are valid.  Row i sits at
+ * position cache_len[b]+i, attends cache rows 0..cache_len[b]+i, and its K/V are written
+ * there unconditionally; rows beyond what the caller later commits are simply overwritten
+ * by the next block (no rollback needed after a rejection).
+ * logits[B][m][V] fp32 (row i = distribution of the token after row i).  probs: optional
+ * softmax(logits / temperature), temperature > 0 required when probs != NULL.
+ * 1 <= B <= max_batch, 1 <= m <= max_block; cache_len[b]+m <= max_seq is the caller's duty.
+ */
+int32_t csd_verify_block(csd_model *model, void *kv, const int32_t *tokens, const int32_t *cache_len,
+                         int32_t B, int32_t m, float temperature, float *logits, float *probs, void *stream);
+
+/*
+ * Speculative-sampling review of k drafts per sequence (Section 2; lenience and greedy rule:
+ * Section 3.1).  p[B][k+1][V]: reviewer rows (row i scores draft i; row k is the extra
+ * token); probabilities for CSD_MODE_SAMPLE; logits are enough for CSD_MODE_GREEDY with
+ * lenience 1.  q[B][k][V]: draft distributions, or NULL when every draft was deterministic;
+ * q_onehot[k] (optional, device) marks positions whose draft was deterministic (Max-Gram)
+ * although q is given.  draft[B][k]; u_acc[B][k] and u_samp[B]: uniforms in [0,1).
+ *   sample: keep draft i iff fl32(u_i*q_i(x_i)) < fl32(l*p_i(x_i)); at the first rejection
+ *           draw from norm(max(0, l*p_i - q_i)) (all-zero: from p_i); no rejection: draw the
+ *           extra token from row k.  Draws use an exact 40-bit fixed-point inverse CDF in
+ *           increasing token id, so the result does not depend on reduction order.
+ *   greedy: keep draft i iff it is the arg-max of row i (ties: smallest id) or, for l > 1
+ *           (p must then hold probabilities), q_i(x_i) <= fl32(l*p_i(x_i)); emit the arg-max
+ *           of the row after the kept drafts.
+ * n_accepted[B] in [0,k]; next_token[B].  1 <= lenience <= 256; k >= 0; V >= 1.
+ */
+int32_t csd_accept(const float *p, const float *q, const uint8_t *q_onehot, const int32_t *draft,
+                   const float *u_acc, const float *u_samp, int32_t B, int32_t k, int32_t V,
+                   float lenience, int32_t mode, int32_t *n_accepted, int32_t *next_token, void *stream);
+
+/*
+ * csd_verify_block followed by csd_accept on the block's own rows, in one enqueue
+ * (k = m-1 drafts = tokens[b][1..m-1]).  logits and probs are optional outputs here.
+ */
+int32_t csd_verify_accept(csd_model *model, void *kv, const int32_t *tokens, const int32_t *cache_len,
+                          int32_t B, int32_t m, float temperature,
+                          const float *q, const uint8_t *q_onehot, const float *u_acc, const float *u_samp,
+                          float lenience, int32_t mode, float *logits, float *probs,
+                          int32_t *n_accepted, int32_t *next_token, void *stream);
+
+/* Test hook: when trace != NULL the next verify calls also copy the residual stream of all
+ * B*m rows after the embedding and after every layer to trace[(n_layers+1)][B*m][d] (fp32). */
+int32_t csd_debug_set_trace(csd_model *model, float *trace);
+
+/* Kernel timing hook for benchmarks.  While enabled, each verify call brackets every kernel
+ * it launches with a pair of HIP events on the caller's stream (this perturbs the step, so
+ * throughput is timed with the hook off).  After the caller has synchronised the stream,
+ * csd_prof_read adds up the bracketed milliseconds and launch counts per kernel class since
+ * the last reset: class 0 = weight-streaming GEMMs, 1 = attention, 2 = everything else. */
+int32_t csd_prof_enable(csd_model *model, int32_t on);
+int32_t csd_prof_read(csd_model *model, int32_t kernel_class, double *ms, int64_t *launches, int32_t reset);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSD_H */

@@ -1,0 +1,190 @@
+"""ctypes binding of libcsd.so: same names as the C ABI, torch tensors in, torch tensors out.
+
+Only marshalling happens here; every step of the verify path runs in the HIP kernels.
+`import torch` must come before the library is loaded so that the library binds to the HIP
+runtime PyTorch already brought into the process (one runtime, shared streams and pointers).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcsd.so")
+
+EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
+           "csd_kv_write", "csd_kv_read", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
+           "csd_accept", "csd_verify_accept", "csd_debug_set_trace", "csd_prof_enable", "csd_prof_read"]
+
+_STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}
+
+
+class CsdError(RuntimeError):
+    def __init__(self, what, status, hip=0):
+        super().__init__(f"{what}: {_STATUS.get(status, status)}" + (f" (hipError {hip})" if status == -4 else ""))
+        self.status = status
+
+
+class Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("arch", "dtype", "n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
+                 "max_batch", "max_seq", "max_block", "enc_len")] + \
+               [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(_LIB_PATH)
+        L.csd_version.restype = C.c_char_p
+        L.csd_kv_bytes.restype = C.c_size_t
+        L.csd_kv_bytes.argtypes = [C.c_void_p]
+        for n in EXPORTS:
+            if n not in ("csd_version", "csd_kv_bytes"):
+                getattr(L, n).restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise CsdError(what, rc, lib().csd_last_hip_error())
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError("device tensor required")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor required")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Model:
+    """csd_model plus the KV cache tensor the caller owns."""
+
+    def __init__(self, shape, weights, max_batch=1, max_seq=2048, max_block=16):
+        dtype = 1 if shape.dtype == "bf16" else 0
+        self.shape = shape
+        self.cfg = Cfg(shape.arch, dtype, shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim,
+                       shape.d_ffn, shape.vocab, max_batch, max_seq, max_block, 0,
+                       shape.rms_eps, shape.rope_theta)
+        want = torch.bfloat16 if dtype == 1 else torch.float32
+        ptrs = []
+        for w in weights:
+            ptrs.append(_ptr(w, want if w.ndim == 2 else torch.float32).value)
+        arr = (C.c_void_p * len(ptrs))(*ptrs)
+        self._h = C.c_void_p()
+        _chk(lib().csd_model_create(C.byref(self.cfg), arr, len(ptrs), _stream(), C.byref(self._h)), "csd_model_create")
+        torch.cuda.current_stream().synchronize()     # the caller's weights may now be freed
+        self.kv = torch.zeros(lib().csd_kv_bytes(self._h), dtype=torch.uint8, device="cuda")
+        self.max_batch, self.max_seq, self.max_block = max_batch, max_seq, max_block
+
+    def close(self):
+        if getattr(self, "_h", None):
+            torch.cuda.synchronize()
+            lib().csd_model_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def kv_write(self, layer, b, pos0, K, V):
+        n = K.shape[0]
+        _chk(lib().csd_kv_write(self._h, _ptr(self.kv), layer, b, pos0, n, _ptr(K, torch.float32),
+                                _ptr(V, torch.float32), _stream()), "csd_kv_write")
+
+    def kv_read(self, layer, b, pos0, n):
+        hd = self.shape.n_heads * self.shape.head_dim
+        K = torch.empty((n, hd), dtype=torch.float32, device="cuda")
+        V = torch.empty((n, hd), dtype=torch.float32, device="cuda")
+        _chk(lib().csd_kv_read(self._h, _ptr(self.kv), layer, b, pos0, n, _ptr(K), _ptr(V), _stream()), "csd_kv_read")
+        return K, V
+
+    def verify_block(self, tokens, cache_len, temperature=1.0, want_probs=False, logits=None, probs=None):
+        """tokens [B][m] int32, cache_len [B] int32 (device) -> logits [B][m][V] (and probs)."""
+        B, m = tokens.shape
+        V = self.shape.vocab
+        if logits is None:
+            logits = torch.empty((B, m, V), dtype=torch.float32, device="cuda")
+        if want_probs and probs is None:
+            probs = torch.empty((B, m, V), dtype=torch.float32, device="cuda")
+        _chk(lib().csd_verify_block(self._h, _ptr(self.kv), _ptr(tokens, torch.int32), _ptr(cache_len, torch.int32),
+                                    B, m, C.c_float(temperature), _ptr(logits), _ptr(probs), _stream()),
+             "csd_verify_block")
+        return (logits, probs) if want_probs else logits
+
+    def verify_accept(self, tokens, cache_len, u_acc, u_samp, q=None, q_onehot=None, temperature=1.0,
+                      lenience=1.0, mode=0, logits=None, probs=None, n_accepted=None, next_token=None):
+        B, m = tokens.shape
+        if n_accepted is None:
+            n_accepted = torch.empty(B, dtype=torch.int32, device="cuda")
+        if next_token is None:
+            next_token = torch.empty(B, dtype=torch.int32, device="cuda")
+        _chk(lib().csd_verify_accept(self._h, _ptr(self.kv), _ptr(tokens, torch.int32), _ptr(cache_len, torch.int32),
+                                     B, m, C.c_float(temperature), _ptr(q), _ptr(q_onehot), _ptr(u_acc), _ptr(u_samp),
+                                     C.c_float(lenience), mode, _ptr(logits), _ptr(probs), _ptr(n_accepted),
+                                     _ptr(next_token), _stream()), "csd_verify_accept")
+        return n_accepted, next_token
+
+    def set_trace(self, trace):
+        _chk(lib().csd_debug_set_trace(self._h, _ptr(trace)), "csd_debug_set_trace")
+
+    def prof_enable(self, on=True):
+        _chk(lib().csd_prof_enable(self._h, 1 if on else 0), "csd_prof_enable")
+
+    def prof_read(self, kernel_class, reset=False):
+        ms, n = C.c_double(), C.c_int64()
+        _chk(lib().csd_prof_read(self._h, kernel_class, C.byref(ms), C.byref(n), 1 if reset else 0), "csd_prof_read")
+        return ms.value, n.value
+
+
+def bigram_fit(tokens, vocab, next_table):
+    """In-place fit of next_table [vocab] int32 (pre-filled with the default successors)."""
+    _chk(lib().csd_bigram_fit(_ptr(tokens, torch.int32), tokens.shape[0], vocab, _ptr(next_table, torch.int32),
+                              _stream()), "csd_bigram_fit")
+    return next_table
+
+
+def bigram_draft(ctx, ctx_len, next_table, k, max_match=0, want_match_len=True):
+    if ctx.ndim == 1:
+        ctx = ctx[None, :]
+    B, stride = ctx.shape
+    out = torch.empty((B, k), dtype=torch.int32, device="cuda")
+    mlen = torch.empty(B, dtype=torch.int32, device="cuda") if want_match_len else None
+    _chk(lib().csd_bigram_draft(_ptr(ctx, torch.int32), _ptr(ctx_len, torch.int32), B, stride,
+                                _ptr(next_table, torch.int32), next_table.shape[0], k, max_match, _ptr(out),
+                                _ptr(mlen), _stream()), "csd_bigram_draft")
+    return (out, mlen) if want_match_len else out
+
+
+def accept(p, q, draft, u_acc, u_samp, lenience=1.0, mode=0, q_onehot=None):
+    B, k1, V = p.shape
+    k = k1 - 1
+    n_acc = torch.empty(B, dtype=torch.int32, device="cuda")
+    nxt = torch.empty(B, dtype=torch.int32, device="cuda")
+    _chk(lib().csd_accept(_ptr(p, torch.float32), _ptr(q), _ptr(q_onehot), _ptr(draft), _ptr(u_acc), _ptr(u_samp),
+                          B, k, V, C.c_float(lenience), mode, _ptr(n_acc), _ptr(nxt), _stream()), "csd_accept")
+    return n_acc, nxt

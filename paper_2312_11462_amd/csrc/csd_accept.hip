@@ -1,0 +1,213 @@
+// Softmax per position and the speculative-sampling review: accept / resample / extra token
+// (Section 2), lenience and the greedy rule (Section 3.1).  One workgroup per sequence.
+//
+// Every fp32 step that decides an integer is a single rounded IEEE operation (__fmul_rn,
+// __fsub_rn: never fused), and the draw is exact integer arithmetic on 40-bit fixed-point
+// weights summed in increasing token id, so the outputs do not depend on reduction order.
+#include "csd_internal.h"
+
+#pragma clang fp contract(off)
+
+#define ACC_THREADS 256
+
+// floor(r * 2^40) for a finite fp32 r in [0, 2^24): exact, by shifting the significand
+__device__ __forceinline__ unsigned long long fixed40(float r) {
+    const uint32_t bits = __float_as_uint(r);
+    if ((int32_t)bits <= 0) return 0ull;                    // zero or negative
+    const int e = (int)(bits >> 23);                        // sign is 0 here
+    if (e == 0) return 0ull;                                // subnormal: below 2^-126
+    const unsigned long long mant = (unsigned long long)((bits & 0x7FFFFFu) | 0x800000u);
+    const int shift = e - 150 + 40;                         // value = mant * 2^(e-150)
+    if (shift >= 0) return shift > 39 ? 0xFFFFFFFFFFFFFFFFull : (mant << shift);
+    return shift <= -24 ? 0ull : (mant >> (-shift));
+}
+
+// residual weight of token v at a rejected position: max(0, l*p_v - q_v) in fp32, or p_v itself
+__device__ __forceinline__ float weight_at(const float *__restrict__ prow, const float *__restrict__ qrow, int x,
+                                           float lenience, bool residual, int v) {
+    const float pv = prow[v];
+    if (!residual) return pv;
+    const float lp = __fmul_rn(lenience, pv);
+    const float qv = qrow ? qrow[v] : (v == x ? 1.0f : 0.0f);
+    const float df = __fsub_rn(lp, qv);
+    return df > 0.0f ? df : 0.0f;
+}
+
+struct ArgMax {
+    float v;
+    int i;
+};
+__device__ __forceinline__ ArgMax better(ArgMax a, ArgMax b) {     // larger value; ties: smaller index
+    return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
+}
+
+__device__ int block_argmax(const float *__restrict__ row, int V, ArgMax *red) {
+    ArgMax best = {-INFINITY, 0x7FFFFFFF};
+    for (int v = threadIdx.x; v < V; v += blockDim.x) {
+        const float x = row[v];
+        // NaN never wins; the first finite-or-inf value does
+        if (x > best.v || (x == best.v && v < best.i)) best = {x, v};
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ArgMax other = {__shfl_xor(best.v, o, 64), __shfl_xor(best.i, o, 64)};
+        best = better(best, other);
+    }
+    const int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = best;
+    __syncthreads();
+    ArgMax t = red[0];
+    for (int i = 1; i < nw; i++) t = better(t, red[i]);
+    return t.i == 0x7FFFFFFF ? 0 : t.i;
+}
+
+__global__ __launch_bounds__(ACC_THREADS) void k_accept(
+    const float *__restrict__ p, const float *__restrict__ q, const uint8_t *__restrict__ q_onehot,
+    const int32_t *__restrict__ draft, int32_t draft_stride, const float *__restrict__ u_acc,
+    const float *__restrict__ u_samp, int32_t k, int32_t V, float lenience, int32_t mode,
+    int32_t *__restrict__ n_accepted, int32_t *__restrict__ next_token) {
+    __shared__ ArgMax red_am[ACC_THREADS / 64];
+    __shared__ unsigned long long part[ACC_THREADS];
+    __shared__ int s_n;
+    const int b = blockIdx.x;
+    const float *pb = p + (size_t)b * (k + 1) * V;
+    const float *qb = q ? q + (size_t)b * k * V : nullptr;
+    const int32_t *db = draft + (size_t)b * draft_stride;
+
+    if (mode == CSD_MODE_GREEDY) {
+        int n = 0, am = 0;
+        for (; n <= k; n++) {
+            am = block_argmax(pb + (size_t)n * V, V, red_am);
+            if (n == k) break;
+            const int x = db[n];
+            bool ok = (x == am);
+            if (!ok && lenience > 1.0f && x >= 0 && x < V) {
+                const bool dense = qb && !(q_onehot && q_onehot[n]);
+                const float qx = dense ? qb[(size_t)n * V + x] : 1.0f;
+                ok = qx <= __fmul_rn(lenience, pb[(size_t)n * V + x]);
+            }
+            if (!ok) break;
+        }
+        if (threadIdx.x == 0) {
+            n_accepted[b] = n;
+            next_token[b] = am;
+        }
+        return;
+    }
+
+    if (threadIdx.x == 0) {
+        int n = 0;
+        for (; n < k; n++) {
+            const int x = db[n];
+            if (x < 0 || x >= V) break;                      // an invalid draft id is a rejection
+            const bool dense = qb && !(q_onehot && q_onehot[n]);
+            const float qx = dense ? qb[(size_t)n * V + x] : 1.0f;
+            const float lhs = __fmul_rn(u_acc[(size_t)b * k + n], qx);
+            const float rhs = __fmul_rn(lenience, pb[(size_t)n * V + x]);
+            if (!(lhs < rhs)) break;
+        }
+        s_n = n;
+    }
+    __syncthreads();
+    const int n = s_n;
+    const float *prow = pb + (size_t)n * V;
+    bool residual = n < k;
+    int x = residual ? db[n] : -1;
+    const float *qrow = nullptr;
+    if (residual && qb && !(q_onehot && q_onehot[n])) qrow = qb + (size_t)n * V;
+
+    const int chunk = (V + ACC_THREADS - 1) / ACC_THREADS;
+    const int v0 = threadIdx.x * chunk, v1 = min(V, v0 + chunk);
+    unsigned long long Z = 0ull, excl = 0ull;
+    for (int pass = 0; pass < 2; pass++) {
+        unsigned long long local = 0ull;
+        for (int v = v0; v < v1; v++) local += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
+        __syncthreads();
+        part[threadIdx.x] = local;
+        __syncthreads();
+        Z = 0ull;
+        excl = 0ull;
+        for (int i = 0; i < ACC_THREADS; i++) {              // 256 adds per thread: exact, order-free
+            if (i == threadIdx.x) excl = Z;
+            Z += part[i];
+        }
+        if (Z != 0ull || !residual) break;
+        residual = false;                                    // all-zero residual: draw from the reviewer's row
+    }
+    if (Z == 0ull) {                                         // not a distribution: signal with -1
+        if (threadIdx.x == 0) {
+            n_accepted[b] = n;
+            next_token[b] = -1;
+        }
+        return;
+    }
+    // T = floor(floor(u * 2^24) * Z / 2^24), 128-bit product
+    const unsigned long long u24 = fixed40(u_samp[b]) >> 16;
+    const unsigned long long hi = __umul64hi(u24, Z), lo = u24 * Z;
+    const unsigned long long T = (hi << 40) | (lo >> 24);
+    unsigned long long mine = 0ull;
+    for (int v = v0; v < v1; v++) mine += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
+    if (T >= excl && T < excl + mine) {                      // exactly one thread owns T
+        unsigned long long cum = excl;
+        int tok = v1 - 1;
+        for (int v = v0; v < v1; v++) {
+            cum += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
+            if (cum > T) { tok = v; break; }
+        }
+        n_accepted[b] = n;
+        next_token[b] = tok;
+    }
+}
+
+// one workgroup per row: p = exp((x - max) / T) / sum
+__global__ __launch_bounds__(256) void k_softmax(const float *logits, float *probs, int32_t V,
+                                                 float inv_t) {
+    __shared__ float red[16];
+    const float *x = logits + (size_t)blockIdx.x * V;
+    float *y = probs + (size_t)blockIdx.x * V;
+    float mx = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) mx = fmaxf(mx, x[v] * inv_t);
+    mx = block_max(mx, red);
+    float s = 0.f;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) {
+        const float e = expf(x[v] * inv_t - mx);
+        y[v] = e;
+        s += e;
+    }
+    s = block_sum(s, red);
+    const float r = 1.0f / s;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) y[v] *= r;
+}
+
+int32_t csd_softmax_enqueue(const float *logits, float *probs, int64_t rows, int32_t V, float temperature,
+                            hipStream_t st) {
+    if (rows <= 0) return CSD_OK;
+    hipLaunchKernelGGL(k_softmax, dim3((unsigned)rows), dim3(256), 0, st, logits, probs, V, 1.0f / temperature);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+int32_t csd_accept_enqueue(const float *p, const float *q, const uint8_t *q_onehot, const int32_t *draft,
+                           int32_t draft_stride, const float *u_acc, const float *u_samp, int32_t B, int32_t k,
+                           int32_t V, float lenience, int32_t mode, int32_t *n_accepted, int32_t *next_token,
+                           hipStream_t st) {
+    if (B <= 0) return CSD_OK;
+    hipLaunchKernelGGL(k_accept, dim3(B), dim3(ACC_THREADS), 0, st, p, q, q_onehot, draft, draft_stride, u_acc, u_samp,
+                       k, V, lenience, mode, n_accepted, next_token);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_accept(const float *p, const float *q, const uint8_t *q_onehot, const int32_t *draft,
+                              const float *u_acc, const float *u_samp, int32_t B, int32_t k, int32_t V,
+                              float lenience, int32_t mode, int32_t *n_accepted, int32_t *next_token, void *stream) {
+    if (!p || !n_accepted || !next_token) return CSD_ENULL;
+    if (k > 0 && !draft) return CSD_ENULL;
+    if (mode == CSD_MODE_SAMPLE && (!u_samp || (k > 0 && !u_acc))) return CSD_ENULL;
+    if (B < 0 || k < 0 || V < 1) return CSD_EINVAL;
+    if (!(lenience >= 1.0f) || lenience > 256.0f) return CSD_EINVAL;
+    if (mode != CSD_MODE_SAMPLE && mode != CSD_MODE_GREEDY) return CSD_EINVAL;
+    return csd_accept_enqueue(p, q, q_onehot, draft, k, u_acc, u_samp, B, k, V, lenience, mode, n_accepted,
+                              next_token, (hipStream_t)stream);
+}

@@ -1,0 +1,195 @@
+// C-ABI entry points of libcsd: argument validation, model lifetime, and the verify step
+// (review forward + softmax + accept) enqueued on the caller's stream.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "csd_internal.h"
+
+thread_local int32_t g_csd_last_hip_error = 0;
+
+extern "C" const char *csd_version(void) { return "csd-mi355x 0.1 (gfx950)"; }
+extern "C" int32_t csd_last_hip_error(void) { return g_csd_last_hip_error; }
+
+static bool env_is(const char *name, const char *val) {
+    const char *e = getenv(name);
+    return e && strcmp(e, val) == 0;
+}
+
+static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    mod->hd = c.n_heads * c.head_dim;
+    mod->seq_pad = (c.max_seq + 63) / 64 * 64;
+    mod->m_max = c.max_batch * c.max_block;
+    const int d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab;
+    // The MFMA path needs whole 16-feature tiles and 32-wide k-steps everywhere.
+    const bool tiles_ok = d % 32 == 0 && hd % 32 == 0 && F % 32 == 0 && V % 16 == 0;
+    mod->mfma = c.dtype == CSD_DTYPE_BF16 && tiles_ok && !env_is("CSD_GEMM", "generic");
+    mod->mfma_attn = mod->mfma && (c.head_dim == 64 || c.head_dim == 128) && !env_is("CSD_ATTN", "generic");
+    if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + mod->seq_pad) > 64 * 1024) return CSD_ESHAPE;
+    int32_t rc;
+    if ((rc = csd_pack_weights(mod, weights, st)) != CSD_OK) return rc;
+
+    const size_t asz = mod->mfma ? 2 : 4;
+    const int m_pad = (mod->m_max + 15) / 16 * 16;
+    int wmax = d > F ? d : F;
+    if (hd > wmax) wmax = hd;
+    int nmax = 3 * hd;
+    if (2 * F > nmax) nmax = 2 * F;
+    if (V > nmax) nmax = V;
+    if (d > nmax) nmax = d;
+    void *p;
+    CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->m_max * d));
+    mod->allocs.push_back(p);
+    mod->h = (float *)p;
+    CSD_HIP(hipMalloc(&p, asz * (size_t)m_pad * wmax));
+    mod->allocs.push_back(p);
+    mod->act = p;
+    CSD_HIP(hipMalloc(&p, asz * (size_t)m_pad * hd));
+    mod->allocs.push_back(p);
+    mod->qbuf = p;
+    CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->s_max * mod->m_max * nmax));
+    mod->allocs.push_back(p);
+    mod->part = (float *)p;
+    CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->m_max * V));
+    mod->allocs.push_back(p);
+    mod->probs = (float *)p;
+    if (mod->mfma_attn) {
+        // per (sequence, head, key chunk): 16*ceil(m/16) rows x (dh accumulators + max + sum)
+        mod->attn_chunks_max = (mod->seq_pad + 127) / 128;
+        const int row_tiles = (c.max_block + 15) / 16;
+        const size_t per = (size_t)row_tiles * 16 * (c.head_dim + 4);
+        CSD_HIP(hipMalloc(&p, sizeof(float) * per * mod->attn_chunks_max * c.n_heads * c.max_batch));
+        mod->allocs.push_back(p);
+        mod->attn_part = (float *)p;
+    }
+    mod->ev.resize(8192);
+    for (auto &e : mod->ev) CSD_HIP(hipEventCreate(&e));
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_model_create(const csd_model_cfg *cfg, const void *const *weight_ptrs, int32_t n_weights,
+                                    void *stream, csd_model **out) {
+    if (!cfg || !weight_ptrs || !out) return CSD_ENULL;
+    *out = nullptr;
+    if (cfg->arch != 0 || cfg->enc_len != 0) return CSD_EUNSUPPORTED;
+    if (cfg->dtype != CSD_DTYPE_FP32 && cfg->dtype != CSD_DTYPE_BF16) return CSD_EINVAL;
+    if (cfg->n_layers < 1 || cfg->d_model < 1 || cfg->n_heads < 1 || cfg->head_dim < 2 || cfg->head_dim % 2 ||
+        cfg->d_ffn < 1 || cfg->vocab < 1 || cfg->max_batch < 1 || cfg->max_seq < 1 || cfg->max_block < 1)
+        return CSD_EINVAL;
+    if (!(cfg->rms_eps > 0.f) || !(cfg->rope_theta > 0.f)) return CSD_EINVAL;
+    if (cfg->max_block > cfg->max_seq) return CSD_ESHAPE;
+    if ((long long)cfg->max_batch * cfg->max_block > 4096) return CSD_ESHAPE;
+    if (n_weights != 3 + 9 * cfg->n_layers) return CSD_EINVAL;
+    for (int i = 0; i < n_weights; i++)
+        if (!weight_ptrs[i]) return CSD_ENULL;
+    csd_model *mod = new (std::nothrow) csd_model();
+    if (!mod) return CSD_EHIP;
+    mod->cfg = *cfg;
+    const int32_t rc = create_impl(mod, weight_ptrs, (hipStream_t)stream);
+    if (rc != CSD_OK) {
+        csd_model_destroy(mod);
+        return rc;
+    }
+    *out = mod;
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_model_destroy(csd_model *mod) {
+    if (!mod) return CSD_ENULL;
+    for (void *p : mod->allocs) (void)hipFree(p);
+    for (auto &e : mod->ev)
+        if (e) (void)hipEventDestroy(e);
+    delete mod;
+    return CSD_OK;
+}
+
+static int32_t check_block(const csd_model *mod, const void *kv, const int32_t *tokens, const int32_t *cache_len,
+                           int32_t B, int32_t m) {
+    if (!mod || !kv || !tokens || !cache_len) return CSD_ENULL;
+    if (B < 1 || m < 1) return CSD_EINVAL;
+    if (B > mod->cfg.max_batch || m > mod->cfg.max_block) return CSD_ESHAPE;
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_verify_block(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
+                                    int32_t B, int32_t m, float temperature, float *logits, float *probs,
+                                    void *stream) {
+    int32_t rc = check_block(mod, kv, tokens, cache_len, B, m);
+    if (rc != CSD_OK) return rc;
+    if (!logits) return CSD_ENULL;
+    if (probs && !(temperature > 0.f)) return CSD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = csd_forward_enqueue(mod, kv, tokens, cache_len, B, m, logits, st)) != CSD_OK) return rc;
+    if (probs) {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        if ((rc = csd_softmax_enqueue(logits, probs, (int64_t)B * m, mod->cfg.vocab, temperature, st)) != CSD_OK) return rc;
+    }
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_verify_accept(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
+                                     int32_t B, int32_t m, float temperature, const float *q, const uint8_t *q_onehot,
+                                     const float *u_acc, const float *u_samp, float lenience, int32_t mode,
+                                     float *logits, float *probs, int32_t *n_accepted, int32_t *next_token,
+                                     void *stream) {
+    int32_t rc = check_block(mod, kv, tokens, cache_len, B, m);
+    if (rc != CSD_OK) return rc;
+    if (!n_accepted || !next_token) return CSD_ENULL;
+    if (mode != CSD_MODE_SAMPLE && mode != CSD_MODE_GREEDY) return CSD_EINVAL;
+    if (!(lenience >= 1.0f) || lenience > 256.0f) return CSD_EINVAL;
+    const bool need_probs = mode == CSD_MODE_SAMPLE || lenience > 1.0f;
+    if (need_probs && !(temperature > 0.f)) return CSD_EINVAL;
+    if (mode == CSD_MODE_SAMPLE && (!u_samp || (m > 1 && !u_acc))) return CSD_ENULL;
+    hipStream_t st = (hipStream_t)stream;
+    const int V = mod->cfg.vocab;
+    // logits of this call live in the model's scratch when the caller does not ask for them
+    float *lg = logits ? logits : mod->probs;   // softmax may then run in place: each thread rewrites what it read
+    if ((rc = csd_forward_enqueue(mod, kv, tokens, cache_len, B, m, lg, st)) != CSD_OK) return rc;
+    const float *p = lg;
+    if (need_probs || probs) {
+        float *pr = probs ? probs : mod->probs;
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        if ((rc = csd_softmax_enqueue(lg, pr, (int64_t)B * m, V, temperature > 0.f ? temperature : 1.0f, st)) != CSD_OK)
+            return rc;
+        if (need_probs) p = pr;
+    }
+    ProfScope ps(mod, st, CSD_PROF_OTHER);
+    return csd_accept_enqueue(p, q, q_onehot, tokens + 1, m, u_acc, u_samp, B, m - 1, V, lenience, mode, n_accepted,
+                              next_token, st);
+}
+
+extern "C" int32_t csd_debug_set_trace(csd_model *mod, float *trace) {
+    if (!mod) return CSD_ENULL;
+    mod->trace = trace;
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_prof_enable(csd_model *mod, int32_t on) {
+    if (!mod) return CSD_ENULL;
+    mod->prof = on != 0;
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_prof_read(csd_model *mod, int32_t cls, double *ms, int64_t *launches, int32_t reset) {
+    if (!mod || !ms || !launches) return CSD_ENULL;
+    if (cls < 0 || cls >= CSD_PROF_CLASSES) return CSD_EINVAL;
+    // fold finished event pairs into the per-class totals (the caller has synchronised the stream)
+    for (size_t i = 0; i + 1 < mod->ev_used; i += 2) {
+        float t = 0.f;
+        CSD_HIP(hipEventElapsedTime(&t, mod->ev[i], mod->ev[i + 1]));
+        const int k = mod->ev_class[i / 2];
+        mod->prof_ms[k] += t;
+        mod->prof_n[k] += 1;
+    }
+    mod->ev_used = 0;
+    mod->ev_class.clear();
+    *ms = mod->prof_ms[cls];
+    *launches = mod->prof_n[cls];
+    if (reset)
+        for (int k = 0; k < CSD_PROF_CLASSES; k++) {
+            mod->prof_ms[k] = 0;
+            mod->prof_n[k] = 0;
+        }
+    return CSD_OK;
+}

@@ -1,0 +1,185 @@
+// Causal block attention of the drafted block over the cached prefix, on the matrix cores.
+//
+// One wave per (sequence, head, 128-key chunk, 16-row tile of the block).  Both contractions
+// are written transposed so that no operand ever needs a shuffle through LDS:
+//   S^T = K * q^T   A = K rows (16 keys x 32 of dh), B = q (32 of dh x 16 block rows)
+//   O^T = V^T * P^T A = V^T (16 of dh x 32 keys),     B = P^T (32 keys x 16 block rows)
+// The result layout of the first product (lane = block row, 4 consecutive A-rows per register
+// group) becomes the B operand of the second directly, because the keys are assigned to A-rows
+// so that every lane ends up holding 8 consecutive keys; V is cached transposed so that the
+// matching A operand is one 16-byte load.  Chunks keep an online-softmax state (max, sum,
+// un-normalised output) that a small merge kernel combines.
+#include "csd_internal.h"
+
+struct KvGeomA {
+    int Bmax, H, dh, seq_pad, L;
+};
+__device__ __forceinline__ size_t a_head_elems(const KvGeomA &g) { return (size_t)g.seq_pad * g.dh; }
+__device__ __forceinline__ size_t a_k_off(const KvGeomA &g, int l, int b, int hh) {
+    return (((size_t)l * g.Bmax + b) * g.H + hh) * a_head_elems(g);
+}
+__device__ __forceinline__ size_t a_v_off(const KvGeomA &g, int l, int b, int hh) {
+    return (size_t)g.L * g.Bmax * g.H * a_head_elems(g) + a_k_off(g, l, b, hh);
+}
+
+#define ATT_CHUNK 128
+
+template <int DH>
+__global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, int m, int row_tiles,
+                                                  const int32_t *__restrict__ cache_len, KvGeomA geo, int layer,
+                                                  const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
+                                                  int chunks_max) {
+    constexpr int PS = DH + 4;   // floats per partial row: DH outputs, running max, running sum, pad
+    const int c = blockIdx.x, hh = blockIdx.y, b = blockIdx.z / row_tiles, rt = blockIdx.z % row_tiles;
+    const int lane = threadIdx.x, col = lane & 15, g = lane >> 4;
+    const int hd = geo.H * DH;
+    const int t = cache_len[b];
+    const int nk = max(0, min(t + m, geo.seq_pad));          // cache rows in play for this block
+    float *po = part + ((((size_t)b * geo.H + hh) * chunks_max + c) * row_tiles + rt) * 16 * PS;
+    float *pr = po + (size_t)col * PS;
+    const int key0 = c * ATT_CHUNK;
+    if (key0 >= nk) {                                        // chunk past the end: neutral element
+        if (g == 0) {
+            pr[DH] = -INFINITY;
+            pr[DH + 1] = 0.f;
+        }
+        return;
+    }
+    const int row = rt * 16 + col;                           // this lane's block row
+    const int qpos = t + row;                                // it sees cache rows 0..qpos
+    u32x4 qf[DH / 32];
+#pragma unroll
+    for (int s = 0; s < DH / 32; s++) {
+        qf[s] = u32x4{0u, 0u, 0u, 0u};
+        if (row < m)
+            qf[s] = *reinterpret_cast<const u32x4 *>(q + (size_t)(b * m + row) * hd + hh * DH + s * 32 + 8 * g);
+    }
+    const bf16_t *kc = kv + a_k_off(geo, layer, b, hh);
+    const bf16_t *vc = kv + a_v_off(geo, layer, b, hh);
+
+    f32x4 oacc[DH / 16];
+#pragma unroll
+    for (int dt = 0; dt < DH / 16; dt++) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun = -INFINITY, lrun = 0.f;
+
+    for (int sub = 0; sub < ATT_CHUNK / 32; sub++) {
+        const int kb = key0 + sub * 32;
+        if (kb >= nk) break;
+        // scores: A-row r of tile T is key kb + 8*(r/4) + 4*T + r%4, so lane group g ends up with keys kb+8g..kb+8g+7
+        f32x4 sT[2];
+#pragma unroll
+        for (int T = 0; T < 2; T++) {
+            sT[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int key = kb + 8 * (col >> 2) + 4 * T + (col & 3);
+            const bf16_t *kp = kc + (size_t)key * DH + 8 * g;
+#pragma unroll
+            for (int s = 0; s < DH / 32; s++) {
+                const u32x4 a = *reinterpret_cast<const u32x4 *>(kp + s * 32);
+                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                                __builtin_bit_cast(bf16x8, qf[s]), sT[T], 0, 0, 0);
+            }
+        }
+        float sv[8];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int key = kb + 8 * g + j;
+            const float s = sT[j >> 2][j & 3] * scale;
+            sv[j] = (key <= qpos && key < nk) ? s : -INFINITY;
+            mx = fmaxf(mx, sv[j]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mnew = fmaxf(mrun, mx);
+        const float alpha = (mnew == -INFINITY) ? 1.0f : expf(mrun - mnew);
+        float pv[8];
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            pv[j] = (sv[j] == -INFINITY) ? 0.f : expf(sv[j] - mnew);
+            psum += pv[j];
+        }
+        psum += __shfl_xor(psum, 16, 64);
+        psum += __shfl_xor(psum, 32, 64);
+        lrun = lrun * alpha + psum;
+        mrun = mnew;
+        u32x4 pf;
+#pragma unroll
+        for (int w = 0; w < 4; w++)
+            pf[w] = (uint32_t)f32_to_bf16(pv[2 * w]) | ((uint32_t)f32_to_bf16(pv[2 * w + 1]) << 16);
+        const bool tail = kb + 32 > nk;                      // rows past nk may hold anything: zero them
+#pragma unroll
+        for (int dt = 0; dt < DH / 16; dt++) {
+            u32x4 vf = *reinterpret_cast<const u32x4 *>(vc + (size_t)(dt * 16 + col) * geo.seq_pad + kb + 8 * g);
+            if (tail) {
+#pragma unroll
+                for (int w = 0; w < 4; w++) {
+                    const int k0 = kb + 8 * g + 2 * w;
+                    const uint32_t keep = (k0 < nk ? 0x0000FFFFu : 0u) | (k0 + 1 < nk ? 0xFFFF0000u : 0u);
+                    vf[w] &= keep;
+                }
+            }
+            oacc[dt] = oacc[dt] * alpha;
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                               __builtin_bit_cast(bf16x8, pf), oacc[dt], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int dt = 0; dt < DH / 16; dt++) *reinterpret_cast<f32x4 *>(pr + dt * 16 + 4 * g) = oacc[dt];
+    if (g == 0) {
+        pr[DH] = mrun;
+        pr[DH + 1] = lrun;
+    }
+}
+
+// out[r][hh*DH + x] = sum_c acc_c[x] e^(m_c - m*) / sum_c l_c e^(m_c - m*)
+template <int DH>
+__global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ part, int m, int row_tiles,
+                                                   const int32_t *__restrict__ cache_len, int H, int seq_pad,
+                                                   int chunks_max, bf16_t *__restrict__ out, int ldo) {
+    constexpr int PS = DH + 4;
+    const int r = blockIdx.x, hh = blockIdx.y, x = threadIdx.x;
+    const int b = r / m, i = r % m, rt = i / 16, ri = i % 16;
+    const int nk = max(1, min(cache_len[b] + m, seq_pad));
+    const int nch = (nk + ATT_CHUNK - 1) / ATT_CHUNK;
+    const float *base = part + (((size_t)b * H + hh) * chunks_max * row_tiles + rt) * 16 * PS + (size_t)ri * PS;
+    const size_t cstride = (size_t)row_tiles * 16 * PS;
+    float mstar = -INFINITY;
+    for (int c = 0; c < nch; c++) mstar = fmaxf(mstar, base[c * cstride + DH]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < nch; c++) {
+        const float mc = base[c * cstride + DH];
+        if (mc == -INFINITY) continue;
+        const float w = expf(mc - mstar);
+        num += base[c * cstride + x] * w;
+        den += base[c * cstride + DH + 1] * w;
+    }
+    out[(size_t)r * ldo + hh * DH + x] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+}
+
+int32_t csd_attn_mfma_enqueue(csd_model *mod, const void *kv, const int32_t *cache_len, int B, int m, int layer,
+                              hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    const KvGeomA geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, c.n_layers};
+    const int row_tiles = (m + 15) / 16;
+    const int chunks = mod->attn_chunks_max;
+    const float scale = 1.0f / sqrtf((float)c.head_dim);
+    const dim3 grid(chunks, c.n_heads, B * row_tiles);
+    const dim3 mgrid(B * m, c.n_heads);
+    ProfScope ps(mod, st, CSD_PROF_ATTN);
+    if (c.head_dim == 128) {
+        hipLaunchKernelGGL((k_attn_mfma<128>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, m, row_tiles, cache_len, geo,
+                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks);
+        CSD_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_attn_merge<128>), mgrid, dim3(128), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
+                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd);
+    } else {
+        hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, m, row_tiles, cache_len, geo,
+                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks);
+        CSD_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_attn_merge<64>), mgrid, dim3(64), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
+                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd);
+    }
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}

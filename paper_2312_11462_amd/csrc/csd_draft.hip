@@ -1,0 +1,121 @@
+// Statistical draft model at the bottom of the cascade: Max-Gram matching with a bigram
+// fallback (Section 3.3, Appendix A).  Integer-only; one workgroup per sequence.
+#include "csd_internal.h"
+
+#define DRAFT_THREADS 256
+#define FIT_THREADS 1024
+
+// Max over the block of a 64-bit key; every thread gets the result.
+__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long *red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        unsigned long long other = __shfl_xor(v, o, 64);
+        v = other > v ? other : v;
+    }
+    const int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    unsigned long long t = red[0];
+    for (int i = 1; i < nw; i++) t = red[i] > t ? red[i] : t;
+    return t;
+}
+
+// Each thread scores candidate match ends e = tid, tid+256, ... <= len-2 by comparing
+// backwards against the suffix; the key (match length, ~e) makes the block maximum the
+// longest match and, among equals, the left-most end.
+__global__ __launch_bounds__(DRAFT_THREADS) void k_bigram_draft(
+    const int32_t *__restrict__ ctx, const int32_t *__restrict__ ctx_len, int32_t ctx_stride,
+    const int32_t *__restrict__ next_table, int32_t vocab, int32_t k, int32_t max_match,
+    int32_t *__restrict__ out_tokens, int32_t *__restrict__ out_match_len) {
+    __shared__ unsigned long long red[DRAFT_THREADS / 64];
+    const int b = blockIdx.x;
+    const int32_t *s = ctx + (size_t)b * ctx_stride;
+    int len = ctx_len[b];
+    int32_t *out = out_tokens + (size_t)b * k;
+    if (len < 1 || len > ctx_stride) {   // device-side guard: no valid context
+        for (int j = threadIdx.x; j < k; j += blockDim.x) out[j] = -1;
+        if (out_match_len && threadIdx.x == 0) out_match_len[b] = 0;
+        return;
+    }
+    unsigned long long best = 0ull;
+    for (int e = threadIdx.x; e <= len - 2; e += blockDim.x) {
+        int r = 0;
+        while (r <= e && (max_match <= 0 || r < max_match) && s[e - r] == s[len - 1 - r]) r++;
+        if (r > 0) {
+            unsigned long long key = ((unsigned long long)(uint32_t)r << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+            best = key > best ? key : best;
+        }
+    }
+    best = block_max_u64(best, red);
+    const int mlen = (int)(best >> 32);
+    if (out_match_len && threadIdx.x == 0) out_match_len[b] = mlen;
+    if (mlen == 0) {
+        if (threadIdx.x == 0) {          // bigram chain from the last token
+            int32_t cur = s[len - 1];
+            for (int j = 0; j < k; j++) {
+                cur = (cur >= 0 && cur < vocab) ? next_table[cur] : -1;
+                out[j] = cur;
+            }
+        }
+        return;
+    }
+    const int e = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+    const int period = len - (e + 1);   // >= 1: the sequence extended by its own draft repeats with this period
+    for (int j = threadIdx.x; j < k; j += blockDim.x) out[j] = s[e + 1 + (j % period)];
+}
+
+// Bigram fit, one workgroup.  Pass 1: for every position i the pair (s[i], s[i+1]) gets the key
+// (count of the pair, index of its last occurrence).  Pass 2: the last occurrence of a pair
+// writes next[a] if no other pair with the same first token has a larger key.
+__global__ __launch_bounds__(FIT_THREADS) void k_bigram_fit(const int32_t *__restrict__ s, int32_t n, int32_t vocab,
+                                                            int32_t *__restrict__ next_table) {
+    extern __shared__ unsigned long long key[];
+    for (int i = threadIdx.x; i < n - 1; i += blockDim.x) {
+        const int32_t a = s[i], b = s[i + 1];
+        uint32_t cnt = 0, last = (uint32_t)i;
+        for (int j = 0; j < n - 1; j++)
+            if (s[j] == a && s[j + 1] == b) { cnt++; last = (uint32_t)j; }
+        const bool ok = a >= 0 && a < vocab && b >= 0 && b < vocab;
+        key[i] = ok ? (((unsigned long long)cnt << 32) | last) : 0ull;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n - 1; i += blockDim.x) {
+        const unsigned long long mine = key[i];
+        if (mine == 0ull || (uint32_t)(mine & 0xFFFFFFFFull) != (uint32_t)i) continue;   // not the pair's last occurrence
+        const int32_t a = s[i];
+        bool best = true;
+        for (int j = 0; j < n - 1; j++)
+            if (s[j] == a && key[j] > mine) { best = false; break; }
+        if (best) next_table[a] = s[i + 1];
+    }
+}
+
+extern "C" int32_t csd_bigram_fit(const int32_t *tokens, int32_t n, int32_t vocab, int32_t *next_table, void *stream) {
+    if (!tokens || !next_table) return CSD_ENULL;
+    if (n < 0 || vocab < 1) return CSD_EINVAL;
+    if (n > 8192) return CSD_ESHAPE;
+    if (n < 2) return CSD_OK;
+    hipLaunchKernelGGL(k_bigram_fit, dim3(1), dim3(FIT_THREADS), (size_t)n * sizeof(unsigned long long),
+                       (hipStream_t)stream, tokens, n, vocab, next_table);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_bigram_draft(const int32_t *ctx, const int32_t *ctx_len, int32_t B, int32_t ctx_stride,
+                                    const int32_t *next_table, int32_t vocab, int32_t k, int32_t max_match,
+                                    int32_t *out_tokens, int32_t *out_match_len, void *stream) {
+    if (!ctx || !ctx_len || !next_table || !out_tokens) return CSD_ENULL;
+    if (B < 0 || k < 0 || vocab < 1 || ctx_stride < 1) return CSD_EINVAL;
+    if (B == 0 || k == 0) {
+        if (B > 0 && out_match_len) {
+            // match lengths are still defined for k == 0: run with k = 0 (kernel writes only them)
+        } else {
+            return CSD_OK;
+        }
+    }
+    hipLaunchKernelGGL(k_bigram_draft, dim3(B), dim3(DRAFT_THREADS), 0, (hipStream_t)stream, ctx, ctx_len, ctx_stride,
+                       next_table, vocab, k, max_match, out_tokens, out_match_len);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}

@@ -1,0 +1,614 @@
+// Review forward of the reviewing model over a drafted block (Section 2: one run scores all
+// drafted positions), LLaMA-style decoder as the benchmark configurations describe it.
+//
+// Data flow per layer (M = B*m block rows, everything stays on the device):
+//   a = rmsnorm(h) -> [QKV GEMM] -> rotate q,k; append K,V to the cache -> block attention
+//   -> [O GEMM] -> h += ; a = rmsnorm(h) -> [gate/up GEMM] -> f = silu(g)*u -> [down GEMM] -> h +=
+// The GEMMs stream each weight matrix from HBM exactly once.  With M <= 136 rows they are
+// bandwidth-bound, so the work is split over (output-tile group, K slice) per wavefront, each
+// wave streaming its own contiguous run of pre-tiled 1 KB weight fragments straight into MFMA
+// operands; K slices write partial-sum planes that the small epilogue kernels add up in a fixed
+// order (deterministic, no float atomics) while applying residual / norm / rotation / SwiGLU.
+#include "csd_internal.h"
+
+// ------------------------------------------------------------------------------ weight tiling
+
+// One 16-byte chunk per thread: tile (nt, ks), lane (i = lane%16 -> output feature, g = lane/16)
+// holds W[ks*32 + 8g + j][nt*16 + i], j = 0..7, the A operand of v_mfma_f32_16x16x32_bf16.
+__global__ void k_pack_tiles(const bf16_t *__restrict__ src, int K, int N_src, bf16_t *__restrict__ dst, int KS,
+                             int dst_tile_base, int dst_tile_stride) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)(N_src / 16) * KS * 64;
+    if (idx >= total) return;
+    const int lane = (int)(idx & 63);
+    const int ks = (int)((idx >> 6) % KS);
+    const int nt = (int)((idx >> 6) / KS);
+    const int i = lane & 15, g = lane >> 4;
+    const int dt = dst_tile_base + dst_tile_stride * nt;
+    bf16_t *o = dst + (((size_t)dt * KS + ks) * 64 + lane) * 8;
+    const bf16_t *s = src + (size_t)(ks * 32 + 8 * g) * N_src + nt * 16 + i;
+#pragma unroll
+    for (int j = 0; j < 8; j++) o[j] = s[(size_t)j * N_src];
+}
+
+template <typename T>
+__global__ void k_copy_cols(const T *__restrict__ src, int K, int N_src, T *__restrict__ dst, int N_dst, int col0) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)K * N_src) return;
+    const size_t k = idx / N_src, n = idx % N_src;
+    dst[k * N_dst + col0 + n] = src[idx];
+}
+
+// ------------------------------------------------------------------------------------ GEMMs
+
+// Skinny weight-streaming GEMM on the matrix cores.
+//   A operand = weight fragment (16 output features x 32 k), B operand = activations
+//   (32 k x 16 block rows), D = 16 features x 16 rows: lane (row = lane%16, features 4g..4g+3).
+// A wave owns NT adjacent output tiles and one K slice; it double-buffers U k-steps of
+// fragments in registers so that 2*U*NT KB per wave are in flight.
+template <int NT, int MT, int U>
+__global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act,
+                                                   float *__restrict__ part, int M, int K, int N, int S) {
+    const int wave = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    const int lane = threadIdx.x & 63;
+    const int n_groups = N / (16 * NT);
+    if (wave >= n_groups * S) return;
+    const int s = wave % S, grp = wave / S;
+    const int KS = K / 32;
+    const int ks0 = (int)((long long)KS * s / S), ks1 = (int)((long long)KS * (s + 1) / S);
+    const int t = lane & 15, g = lane >> 4;
+
+    const u32x4 *wp[NT];
+#pragma unroll
+    for (int j = 0; j < NT; j++) wp[j] = Wp + ((size_t)(grp * NT + j) * KS) * 64 + lane;
+    const u32x4 *ap[MT];
+    bool valid[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        const int row = mt * 16 + t;
+        valid[mt] = row < M;
+        ap[mt] = reinterpret_cast<const u32x4 *>(act + (size_t)(valid[mt] ? row : 0) * K + 8 * g);
+    }
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 wa[U][NT], wb[U][NT], ba[U][MT], bb[U][MT];
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+
+#define CSD_LOAD_BATCH(WF, BF, KS_AT)                                                             \
+    _Pragma("unroll") for (int u = 0; u < U; u++) {                                               \
+        const int ksu_ = (KS_AT) + u;                                                             \
+        const bool in_ = ksu_ < ks1;                                                              \
+        _Pragma("unroll") for (int j = 0; j < NT; j++)                                            \
+            WF[u][j] = in_ ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero;        \
+        _Pragma("unroll") for (int mt = 0; mt < MT; mt++)                                         \
+            BF[u][mt] = (in_ && valid[mt]) ? ap[mt][(size_t)ksu_ * 4] : zero;                     \
+    }
+#define CSD_MMA_BATCH(WF, BF)                                                                     \
+    _Pragma("unroll") for (int u = 0; u < U; u++)                                                 \
+        _Pragma("unroll") for (int mt = 0; mt < MT; mt++)                                         \
+            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
+                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, BF[u][mt]),  \
+                    acc[mt][j], 0, 0, 0);
+
+    CSD_LOAD_BATCH(wa, ba, ks0)
+    for (int ks = ks0; ks < ks1; ks += 2 * U) {
+        CSD_LOAD_BATCH(wb, bb, ks + U)
+        CSD_MMA_BATCH(wa, ba)
+        CSD_LOAD_BATCH(wa, ba, ks + 2 * U)
+        CSD_MMA_BATCH(wb, bb)
+    }
+#undef CSD_LOAD_BATCH
+#undef CSD_MMA_BATCH
+
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        const int row = mt * 16 + t;
+        if (row < M) {
+#pragma unroll
+            for (int j = 0; j < NT; j++) {
+                float *o = part + ((size_t)s * M + row) * N + (size_t)(grp * NT + j) * 16 + 4 * g;
+                *reinterpret_cast<f32x4 *>(o) = acc[mt][j];
+            }
+        }
+    }
+}
+
+// Generic GEMM (fp32 models and the debugging path): one thread per output column, fp32
+// activations [M][K], row-major weights [K][N]; writes partial plane 0.
+template <typename TW>
+__global__ __launch_bounds__(256) void k_gemm_simple(const TW *__restrict__ W, const float *__restrict__ act,
+                                                     float *__restrict__ part, int M, int K, int N) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    for (int r0 = 0; r0 < M; r0 += 8) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const int rn = min(8, M - r0);
+        for (int k = 0; k < K; k++) {
+            const float w = to_f32<TW>(W[(size_t)k * N + n]);
+#pragma unroll
+            for (int r = 0; r < 8; r++)
+                if (r < rn) acc[r] = fmaf(act[(size_t)(r0 + r) * K + k], w, acc[r]);
+        }
+        for (int r = 0; r < rn; r++) part[(size_t)(r0 + r) * N + n] = acc[r];
+    }
+}
+
+// ------------------------------------------------------------------------------- epilogues
+
+// h[r] = E[token[r]];  a[r] = rmsnorm(h[r]) * g
+template <typename TW, typename TA>
+__global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ tokens, const TW *__restrict__ E, int V,
+                                                    int d, const float *__restrict__ g, float eps,
+                                                    float *__restrict__ h, TA *__restrict__ a, int lda) {
+    __shared__ float red[16];
+    const int r = blockIdx.x;
+    const int tok = tokens[r];
+    const bool ok = tok >= 0 && tok < V;
+    float ss = 0.f;
+    for (int x = threadIdx.x; x < d; x += blockDim.x) {
+        const float v = ok ? to_f32<TW>(E[(size_t)tok * d + x]) : 0.f;
+        h[(size_t)r * d + x] = v;
+        ss += v * v;
+    }
+    ss = block_sum(ss, red);
+    const float rs = rsqrtf(ss / (float)d + eps);
+    for (int x = threadIdx.x; x < d; x += blockDim.x)
+        a[(size_t)r * lda + x] = from_f32<TA>(h[(size_t)r * d + x] * rs * g[x]);
+}
+
+// h[r] += sum_s part[s][r];  a[r] = rmsnorm(h[r]) * g
+template <typename TA>
+__global__ __launch_bounds__(256) void k_residual_norm(const float *__restrict__ part, int S, int M, int d,
+                                                       const float *__restrict__ g, float eps, float *__restrict__ h,
+                                                       TA *__restrict__ a, int lda) {
+    __shared__ float red[16];
+    const int r = blockIdx.x;
+    float ss = 0.f;
+    for (int x = threadIdx.x; x < d; x += blockDim.x) {
+        float v = 0.f;
+        for (int s = 0; s < S; s++) v += part[((size_t)s * M + r) * d + x];
+        v += h[(size_t)r * d + x];
+        h[(size_t)r * d + x] = v;
+        ss += v * v;
+    }
+    ss = block_sum(ss, red);
+    const float rs = rsqrtf(ss / (float)d + eps);
+    for (int x = threadIdx.x; x < d; x += blockDim.x)
+        a[(size_t)r * lda + x] = from_f32<TA>(h[(size_t)r * d + x] * rs * g[x]);
+}
+
+// KV cache addressing.  K: [L][Bmax][H][seq_pad][dh];  V is stored transposed, [L][Bmax][H][dh][seq_pad],
+// so that the P*V contraction reads 8 consecutive keys per lane.
+struct KvGeom {
+    int Bmax, H, dh, seq_pad, L;
+};
+__host__ __device__ inline size_t kv_head_elems(const KvGeom &g) { return (size_t)g.seq_pad * g.dh; }
+__host__ __device__ inline size_t kv_k_off(const KvGeom &g, int l, int b, int hh) {
+    return (((size_t)l * g.Bmax + b) * g.H + hh) * kv_head_elems(g);
+}
+__host__ __device__ inline size_t kv_v_off(const KvGeom &g, int l, int b, int hh) {
+    return (size_t)g.L * g.Bmax * g.H * kv_head_elems(g) + kv_k_off(g, l, b, hh);
+}
+
+// Sum the QKV partial planes, rotate q and k (half-split pairs, angle pos * theta^(-2x/dh)), write q for
+// the attention kernel and append K (rotated) and V to the cache at position cache_len[b] + i.
+template <typename TA, typename TC>
+__global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, int S, int M, int m,
+                                                const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
+                                                float theta, TA *__restrict__ qout, TC *__restrict__ kv) {
+    const int r = blockIdx.x, hh = blockIdx.y;
+    const int b = r / m, i = r % m;
+    const int dh = geo.dh, half = dh / 2, hd = geo.H * dh, N = 3 * hd;
+    const int pos = cache_len[b] + i;
+    const bool pos_ok = pos >= 0 && pos < geo.seq_pad;
+    TC *kc = kv + kv_k_off(geo, layer, b, hh);
+    TC *vc = kv + kv_v_off(geo, layer, b, hh);
+    for (int x = threadIdx.x; x < half; x += blockDim.x) {
+        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+        for (int s = 0; s < S; s++) {
+            const float *p = part + ((size_t)s * M + r) * N + hh * dh + x;
+            q0 += p[0];
+            q1 += p[half];
+            k0 += p[hd];
+            k1 += p[hd + half];
+            v0 += p[2 * hd];
+            v1 += p[2 * hd + half];
+        }
+        const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
+        const float c = (float)cos(ang), sn = (float)sin(ang);
+        qout[(size_t)r * hd + hh * dh + x] = from_f32<TA>(q0 * c - q1 * sn);
+        qout[(size_t)r * hd + hh * dh + x + half] = from_f32<TA>(q0 * sn + q1 * c);
+        if (pos_ok) {
+            kc[(size_t)pos * dh + x] = from_f32<TC>(k0 * c - k1 * sn);
+            kc[(size_t)pos * dh + x + half] = from_f32<TC>(k0 * sn + k1 * c);
+            vc[(size_t)x * geo.seq_pad + pos] = from_f32<TC>(v0);
+            vc[(size_t)(x + half) * geo.seq_pad + pos] = from_f32<TC>(v1);
+        }
+    }
+}
+
+// f = silu(sum_s gate) * (sum_s up).  Tiled weights interleave gate and up tiles of 16 columns
+// (gate tile j at packed tile 2j, up tile at 2j+1); row-major weights concatenate [gate | up].
+template <typename TA>
+__global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, int S, int M, int F, int interleaved,
+                                                TA *__restrict__ f, int ldf) {
+    const int r = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= F) return;
+    const int gc = interleaved ? (j / 16) * 32 + (j % 16) : j;
+    const int uc = interleaved ? gc + 16 : F + j;
+    float gsum = 0.f, usum = 0.f;
+    for (int s = 0; s < S; s++) {
+        const float *p = part + ((size_t)s * M + r) * (2 * (size_t)F);
+        gsum += p[gc];
+        usum += p[uc];
+    }
+    const float sg = gsum / (1.0f + expf(-gsum));
+    f[(size_t)r * ldf + j] = from_f32<TA>(sg * usum);
+}
+
+__global__ __launch_bounds__(256) void k_fix_logits(const float *__restrict__ part, int S, int M, int V,
+                                                    float *__restrict__ logits) {
+    const int r = blockIdx.y;
+    const int v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= V) return;
+    float acc = 0.f;
+    for (int s = 0; s < S; s++) acc += part[((size_t)s * M + r) * V + v];
+    logits[(size_t)r * V + v] = acc;
+}
+
+// Generic causal block attention: one wave per (block row, head).  Scores of the visible cache
+// rows 0..pos go through LDS; softmax in fp32 with max subtraction; o = sum_j p_j V_j.
+template <typename TA, typename TC>
+__global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, int m, const int32_t *__restrict__ cache_len,
+                                                    KvGeom geo, int layer, const TC *__restrict__ kv, float scale,
+                                                    TA *__restrict__ out, int ldo) {
+    extern __shared__ float sm[];
+    const int r = blockIdx.x, hh = blockIdx.y;
+    const int b = r / m, i = r % m;
+    const int dh = geo.dh, hd = geo.H * dh;
+    float *qs = sm;           // [dh]
+    float *sc = sm + dh;      // [nk]
+    int nk = cache_len[b] + i + 1;
+    nk = max(1, min(nk, geo.seq_pad));
+    const TC *kc = kv + kv_k_off(geo, layer, b, hh);
+    const TC *vc = kv + kv_v_off(geo, layer, b, hh);
+    for (int x = threadIdx.x; x < dh; x += 64) qs[x] = to_f32<TA>(q[(size_t)r * hd + hh * dh + x]);
+    __syncthreads();
+    float mx = -INFINITY;
+    for (int j = threadIdx.x; j < nk; j += 64) {
+        float s = 0.f;
+        for (int x = 0; x < dh; x++) s = fmaf(qs[x], to_f32<TC>(kc[(size_t)j * dh + x]), s);
+        s *= scale;
+        sc[j] = s;
+        mx = fmaxf(mx, s);
+    }
+    mx = wave_max(mx);
+    float z = 0.f;
+    for (int j = threadIdx.x; j < nk; j += 64) {
+        const float e = expf(sc[j] - mx);
+        sc[j] = e;
+        z += e;
+    }
+    z = wave_sum(z);
+    __syncthreads();
+    const float rz = 1.0f / z;
+    for (int x = threadIdx.x; x < dh; x += 64) {
+        float o = 0.f;
+        for (int j = 0; j < nk; j++) o = fmaf(sc[j], to_f32<TC>(vc[(size_t)x * geo.seq_pad + j]), o);
+        out[(size_t)r * ldo + hh * dh + x] = from_f32<TA>(o * rz);
+    }
+}
+
+// cache row import / export in canonical [n][H*dh] fp32 form
+template <typename TC>
+__global__ void k_kv_write(TC *__restrict__ kv, KvGeom geo, int layer, int b, int pos0, int n,
+                           const float *__restrict__ K, const float *__restrict__ V) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int hd = geo.H * geo.dh;
+    if (idx >= (size_t)n * hd) return;
+    const int i = (int)(idx / hd), c = (int)(idx % hd), hh = c / geo.dh, x = c % geo.dh;
+    kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + x] = from_f32<TC>(K[idx]);
+    kv[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos0 + i] = from_f32<TC>(V[idx]);
+}
+template <typename TC>
+__global__ void k_kv_read(const TC *__restrict__ kv, KvGeom geo, int layer, int b, int pos0, int n,
+                          float *__restrict__ K, float *__restrict__ V) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int hd = geo.H * geo.dh;
+    if (idx >= (size_t)n * hd) return;
+    const int i = (int)(idx / hd), c = (int)(idx % hd), hh = c / geo.dh, x = c % geo.dh;
+    K[idx] = to_f32<TC>(kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + x]);
+    V[idx] = to_f32<TC>(kv[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos0 + i]);
+}
+
+// ------------------------------------------------------------------------------- host driver
+
+static KvGeom geom(const csd_model *mod) {
+    return KvGeom{mod->cfg.max_batch, mod->cfg.n_heads, mod->cfg.head_dim, mod->seq_pad, mod->cfg.n_layers};
+}
+
+ProfScope::ProfScope(csd_model *mod, hipStream_t s, int cls) : m(mod), st(s), on(false) {
+    if (!mod->prof || mod->ev_used + 2 > mod->ev.size()) return;
+    on = true;
+    mod->ev_class.push_back(cls);
+    (void)hipEventRecord(mod->ev[mod->ev_used], st);
+}
+ProfScope::~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(m->ev[m->ev_used + 1], st);
+    m->ev_used += 2;
+}
+
+template <int NT, int U>
+static void launch_gemm_mfma_nt(const GemmW &w, const bf16_t *act, float *part, int M, hipStream_t st) {
+    const int waves = w.N / (16 * NT) * w.S;
+    const int blocks = (waves + 3) / 4;
+    const int MT = (M + 15) / 16;
+    const u32x4 *Wp = reinterpret_cast<const u32x4 *>(w.data);
+    if (MT <= 1)
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 1, U>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M, w.K, w.N, w.S);
+    else if (MT <= 2)
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 2, U>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M, w.K, w.N, w.S);
+    else if (MT <= 4)
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 4, (U > 2 ? U / 2 : U)>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M,
+                           w.K, w.N, w.S);
+    else
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 9, 1>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M, w.K, w.N, w.S);
+}
+
+// act: [M][w.K] in the path's activation type; part: [w.S][M][w.N]
+static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, hipStream_t st) {
+    ProfScope ps(mod, st, CSD_PROF_GEMM);
+    if (mod->mfma) {
+        if (w.nt == 2)
+            launch_gemm_mfma_nt<2, 4>(w, (const bf16_t *)act, mod->part, M, st);
+        else
+            launch_gemm_mfma_nt<1, 8>(w, (const bf16_t *)act, mod->part, M, st);
+    } else if (mod->cfg.dtype == CSD_DTYPE_BF16) {
+        hipLaunchKernelGGL((k_gemm_simple<bf16_t>), dim3((w.N + 255) / 256), dim3(256), 0, st, (const bf16_t *)w.data,
+                           (const float *)act, mod->part, M, w.K, w.N);
+    } else {
+        hipLaunchKernelGGL((k_gemm_simple<float>), dim3((w.N + 255) / 256), dim3(256), 0, st, (const float *)w.data,
+                           (const float *)act, mod->part, M, w.K, w.N);
+    }
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+int32_t csd_attn_mfma_enqueue(csd_model *mod, const void *kv, const int32_t *cache_len, int B, int m, int layer,
+                              hipStream_t st);   // csd_attention.hip
+
+template <typename TW, typename TA, typename TC>
+static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
+                             int32_t m, float *logits, hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    const int M = B * m, d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab, L = c.n_layers;
+    const KvGeom geo = geom(mod);
+    TA *act = (TA *)mod->act;
+    TA *qb = (TA *)mod->qbuf;
+    const int lda = d > F ? (d > hd ? d : hd) : (F > hd ? F : hd);   // rows of `act` are reused at several widths
+    (void)lda;
+    const float scale = 1.0f / sqrtf((float)c.head_dim);
+    {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
+                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d);
+        CSD_LAUNCH_CHECK();
+    }
+    if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
+    for (int l = 0; l < L; l++) {
+        const LayerW &lw = mod->layers[l];
+        int32_t rc;
+        if ((rc = run_gemm(mod, lw.qkv, act, M, st)) != CSD_OK) return rc;
+        {
+            ProfScope ps(mod, st, CSD_PROF_OTHER);
+            hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, lw.qkv.S, M, m,
+                               cache_len, geo, l, c.rope_theta, qb, (TC *)kv);
+            CSD_LAUNCH_CHECK();
+        }
+        if (mod->mfma_attn) {
+            if ((rc = csd_attn_mfma_enqueue(mod, kv, cache_len, B, m, l, st)) != CSD_OK) return rc;
+        } else {
+            ProfScope ps(mod, st, CSD_PROF_ATTN);
+            const size_t lds = sizeof(float) * (size_t)(c.head_dim + mod->seq_pad);
+            hipLaunchKernelGGL((k_attn_simple<TA, TC>), dim3(M, c.n_heads), dim3(64), lds, st, qb, m, cache_len, geo, l,
+                               (const TC *)kv, scale, act, hd);
+            CSD_LAUNCH_CHECK();
+        }
+        if ((rc = run_gemm(mod, lw.o, act, M, st)) != CSD_OK) return rc;
+        {
+            ProfScope ps(mod, st, CSD_PROF_OTHER);
+            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, lw.o.S, M, d, lw.ffn_norm,
+                               c.rms_eps, mod->h, act, d);
+            CSD_LAUNCH_CHECK();
+        }
+        if ((rc = run_gemm(mod, lw.gu, act, M, st)) != CSD_OK) return rc;
+        {
+            ProfScope ps(mod, st, CSD_PROF_OTHER);
+            hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, lw.gu.S, M, F,
+                               mod->mfma ? 1 : 0, act, F);
+            CSD_LAUNCH_CHECK();
+        }
+        if ((rc = run_gemm(mod, lw.down, act, M, st)) != CSD_OK) return rc;
+        {
+            ProfScope ps(mod, st, CSD_PROF_OTHER);
+            const float *g = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
+            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, lw.down.S, M, d, g,
+                               c.rms_eps, mod->h, act, d);
+            CSD_LAUNCH_CHECK();
+        }
+        if (mod->trace)
+            CSD_HIP(hipMemcpyAsync(mod->trace + (size_t)(l + 1) * M * d, mod->h, sizeof(float) * (size_t)M * d,
+                                   hipMemcpyDeviceToDevice, st));
+    }
+    int32_t rc;
+    if ((rc = run_gemm(mod, mod->lm, act, M, st)) != CSD_OK) return rc;
+    {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, mod->lm.S, M, V, logits);
+        CSD_LAUNCH_CHECK();
+    }
+    return CSD_OK;
+}
+
+int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
+                            int32_t m, float *logits, hipStream_t st) {
+    if (mod->cfg.dtype == CSD_DTYPE_FP32)
+        return forward_typed<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);
+    if (mod->mfma) return forward_typed<bf16_t, bf16_t, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
+    return forward_typed<bf16_t, float, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
+}
+
+// --------------------------------------------------------------------------- model building
+
+static int pick_splits(int n_groups, int KS) {
+    // enough waves to cover 256 CUs several times over, slices of at least 8 k-steps
+    int S = 1;
+    while (n_groups * S < 2048 && KS / (S * 2) >= 8 && S < 16) S *= 2;
+    return S;
+}
+
+template <typename T>
+static int32_t copy_cols(const void *src, int K, int N_src, void *dst, int N_dst, int col0, hipStream_t st) {
+    const size_t total = (size_t)K * N_src;
+    hipLaunchKernelGGL((k_copy_cols<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T *)src, K, N_src,
+                       (T *)dst, N_dst, col0);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+static int32_t pack_tiles(const void *src, int K, int N_src, void *dst, int base, int stride, hipStream_t st) {
+    const size_t total = (size_t)(N_src / 16) * (K / 32) * 64;
+    hipLaunchKernelGGL(k_pack_tiles, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)src, K, N_src,
+                       (bf16_t *)dst, K / 32, base, stride);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+static int32_t dev_alloc(csd_model *mod, void **p, size_t bytes) {
+    CSD_HIP(hipMalloc(p, bytes ? bytes : 256));
+    mod->allocs.push_back(*p);
+    return CSD_OK;
+}
+
+struct Piece {
+    const void *src;
+    int N_src;
+    int base, stride;   // tile placement (MFMA) ; col0 = base*16 (row-major)
+};
+
+static int32_t build_gemm(csd_model *mod, GemmW *g, int K, int N, const Piece *pieces, int n_pieces, bool interleave,
+                          hipStream_t st) {
+    const size_t esz = mod->cfg.dtype == CSD_DTYPE_BF16 ? 2 : 4;
+    g->K = K;
+    g->N = N;
+    int32_t rc;
+    if ((rc = dev_alloc(mod, &g->data, (size_t)K * N * esz)) != CSD_OK) return rc;
+    if (mod->mfma) {
+        g->nt = (N / 16) % 2 == 0 && (N / 32) >= 512 ? 2 : 1;
+        g->S = pick_splits(N / (16 * g->nt), K / 32);
+        for (int i = 0; i < n_pieces; i++)
+            if ((rc = pack_tiles(pieces[i].src, K, pieces[i].N_src, g->data, pieces[i].base, pieces[i].stride, st)) != CSD_OK)
+                return rc;
+    } else {
+        g->nt = 1;
+        g->S = 1;
+        (void)interleave;
+        int col0 = 0;
+        for (int i = 0; i < n_pieces; i++) {
+            if (esz == 2)
+                rc = copy_cols<bf16_t>(pieces[i].src, K, pieces[i].N_src, g->data, N, col0, st);
+            else
+                rc = copy_cols<float>(pieces[i].src, K, pieces[i].N_src, g->data, N, col0, st);
+            if (rc != CSD_OK) return rc;
+            col0 += pieces[i].N_src;
+        }
+    }
+    if (g->S > mod->s_max) mod->s_max = g->S;
+    return CSD_OK;
+}
+
+int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    const int d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab, L = c.n_layers;
+    const size_t esz = c.dtype == CSD_DTYPE_BF16 ? 2 : 4;
+    int32_t rc;
+    if ((rc = dev_alloc(mod, &mod->embed, (size_t)V * d * esz)) != CSD_OK) return rc;
+    CSD_HIP(hipMemcpyAsync(mod->embed, w[0], (size_t)V * d * esz, hipMemcpyDeviceToDevice, st));
+    mod->layers.resize(L);
+    for (int l = 0; l < L; l++) {
+        const void *const *lw = w + 1 + 9 * l;
+        LayerW &o = mod->layers[l];
+        if ((rc = dev_alloc(mod, (void **)&o.attn_norm, sizeof(float) * d)) != CSD_OK) return rc;
+        if ((rc = dev_alloc(mod, (void **)&o.ffn_norm, sizeof(float) * d)) != CSD_OK) return rc;
+        CSD_HIP(hipMemcpyAsync(o.attn_norm, lw[0], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
+        CSD_HIP(hipMemcpyAsync(o.ffn_norm, lw[5], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
+        const Piece qkv[3] = {{lw[1], hd, 0, 1}, {lw[2], hd, hd / 16, 1}, {lw[3], hd, 2 * hd / 16, 1}};
+        if ((rc = build_gemm(mod, &o.qkv, d, 3 * hd, qkv, 3, false, st)) != CSD_OK) return rc;
+        const Piece wo[1] = {{lw[4], d, 0, 1}};
+        if ((rc = build_gemm(mod, &o.o, hd, d, wo, 1, false, st)) != CSD_OK) return rc;
+        const Piece gu[2] = {{lw[6], F, 0, 2}, {lw[7], F, 1, 2}};
+        if ((rc = build_gemm(mod, &o.gu, d, 2 * F, gu, 2, true, st)) != CSD_OK) return rc;
+        const Piece dn[1] = {{lw[8], d, 0, 1}};
+        if ((rc = build_gemm(mod, &o.down, F, d, dn, 1, false, st)) != CSD_OK) return rc;
+    }
+    if ((rc = dev_alloc(mod, (void **)&mod->final_norm, sizeof(float) * d)) != CSD_OK) return rc;
+    CSD_HIP(hipMemcpyAsync(mod->final_norm, w[1 + 9 * L], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
+    const Piece lm[1] = {{w[2 + 9 * L], V, 0, 1}};
+    if ((rc = build_gemm(mod, &mod->lm, d, V, lm, 1, false, st)) != CSD_OK) return rc;
+    return CSD_OK;
+}
+
+// ------------------------------------------------------------------------------ cache access
+
+extern "C" size_t csd_kv_bytes(const csd_model *mod) {
+    if (!mod) return 0;
+    const csd_model_cfg &c = mod->cfg;
+    const size_t esz = c.dtype == CSD_DTYPE_BF16 ? 2 : 4;
+    return (size_t)2 * c.n_layers * c.max_batch * c.n_heads * mod->seq_pad * c.head_dim * esz;
+}
+
+extern "C" int32_t csd_kv_write(const csd_model *mod, void *kv, int32_t layer, int32_t b, int32_t pos0, int32_t n,
+                                const float *K, const float *V, void *stream) {
+    if (!mod || !kv || !K || !V) return CSD_ENULL;
+    const csd_model_cfg &c = mod->cfg;
+    if (layer < 0 || layer >= c.n_layers || b < 0 || b >= c.max_batch || pos0 < 0 || n < 0) return CSD_EINVAL;
+    if (pos0 + n > c.max_seq) return CSD_ESHAPE;
+    if (n == 0) return CSD_OK;
+    const size_t total = (size_t)n * mod->hd;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (c.dtype == CSD_DTYPE_BF16)
+        hipLaunchKernelGGL((k_kv_write<bf16_t>), grid, dim3(256), 0, (hipStream_t)stream, (bf16_t *)kv, geom(mod), layer, b,
+                           pos0, n, K, V);
+    else
+        hipLaunchKernelGGL((k_kv_write<float>), grid, dim3(256), 0, (hipStream_t)stream, (float *)kv, geom(mod), layer, b,
+                           pos0, n, K, V);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_kv_read(const csd_model *mod, const void *kv, int32_t layer, int32_t b, int32_t pos0, int32_t n,
+                               float *K, float *V, void *stream) {
+    if (!mod || !kv || !K || !V) return CSD_ENULL;
+    const csd_model_cfg &c = mod->cfg;
+    if (layer < 0 || layer >= c.n_layers || b < 0 || b >= c.max_batch || pos0 < 0 || n < 0) return CSD_EINVAL;
+    if (pos0 + n > c.max_seq) return CSD_ESHAPE;
+    if (n == 0) return CSD_OK;
+    const size_t total = (size_t)n * mod->hd;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (c.dtype == CSD_DTYPE_BF16)
+        hipLaunchKernelGGL((k_kv_read<bf16_t>), grid, dim3(256), 0, (hipStream_t)stream, (const bf16_t *)kv, geom(mod), layer,
+                           b, pos0, n, K, V);
+    else
+        hipLaunchKernelGGL((k_kv_read<float>), grid, dim3(256), 0, (hipStream_t)stream, (const float *)kv, geom(mod), layer, b,
+                           pos0, n, K, V);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}

@@ -1,0 +1,148 @@
+// Internal declarations shared by the HIP translation units of libcsd (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "../../include/csd.h"
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define CSD_WAVE 64
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// sum over a block of up to 1024 threads; every thread gets the result; `red` holds >= 16 floats
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    const int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < nw; i++) t += red[i];
+    return t;
+}
+__device__ __forceinline__ float block_max(float v, float *red) {
+    v = wave_max(v);
+    const int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = red[0];
+    for (int i = 1; i < nw; i++) t = fmaxf(t, red[i]);
+    return t;
+}
+
+// ---------------------------------------------------------------------------------- host side
+
+extern thread_local int32_t g_csd_last_hip_error;
+
+#define CSD_HIP(expr)                                   \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) {                        \
+            g_csd_last_hip_error = (int32_t)e__;        \
+            return CSD_EHIP;                            \
+        }                                               \
+    } while (0)
+
+#define CSD_LAUNCH_CHECK() CSD_HIP(hipGetLastError())
+
+struct GemmW {
+    void *data = nullptr;   // MFMA path: bf16 tiles [N/16][K/32][64 lanes][8]; generic path: row-major [K][N]
+    int K = 0, N = 0;
+    int nt = 1;             // n-tiles (of 16 output features) per wave
+    int S = 1;              // K splits (partial-sum planes)
+};
+
+struct LayerW {
+    float *attn_norm = nullptr, *ffn_norm = nullptr;
+    GemmW qkv, o, gu, down;
+};
+
+enum { CSD_PROF_GEMM = 0, CSD_PROF_ATTN = 1, CSD_PROF_OTHER = 2, CSD_PROF_CLASSES = 3 };
+
+struct csd_model {
+    csd_model_cfg cfg;
+    bool mfma = false;        // bf16 tiles + MFMA GEMMs; otherwise generic kernels on row-major weights
+    bool mfma_attn = false;
+    int hd = 0;               // n_heads * head_dim
+    int seq_pad = 0;          // cache rows per sequence, padded to 64
+    int m_max = 0;            // max_batch * max_block
+    int s_max = 1;            // most K splits of any GEMM
+    void *embed = nullptr;    // [V][d] in cfg.dtype, row-major
+    float *final_norm = nullptr;
+    GemmW lm;
+    std::vector<LayerW> layers;
+    // scratch (device)
+    float *h = nullptr;          // residual stream [m_max][d] fp32
+    void *act = nullptr;         // GEMM input rows [m_pad][max(d, F, hd)] (bf16 on the MFMA path, else fp32)
+    void *qbuf = nullptr;        // rotated queries [m_pad][hd], same type as act
+    float *part = nullptr;       // split-K partial sums [s_max][m_max][n_max]
+    float *attn_part = nullptr;  // attention partials (MFMA attention)
+    float *probs = nullptr;      // [m_max][V] when the caller does not want them
+    int attn_chunks_max = 0;
+    float *trace = nullptr;
+    // profiling
+    bool prof = false;
+    std::vector<hipEvent_t> ev;
+    std::vector<int> ev_class;
+    size_t ev_used = 0;
+    double prof_ms[CSD_PROF_CLASSES] = {0, 0, 0};
+    int64_t prof_n[CSD_PROF_CLASSES] = {0, 0, 0};
+    std::vector<void *> allocs;
+};
+
+// csd_forward.hip
+int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
+                            int32_t B, int32_t m, float *logits, hipStream_t st);
+int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st);
+// csd_accept.hip
+int32_t csd_softmax_enqueue(const float *logits, float *probs, int64_t rows, int32_t V, float temperature,
+                            hipStream_t st);
+int32_t csd_accept_enqueue(const float *p, const float *q, const uint8_t *q_onehot, const int32_t *draft,
+                           int32_t draft_stride, const float *u_acc, const float *u_samp, int32_t B, int32_t k,
+                           int32_t V, float lenience, int32_t mode, int32_t *n_accepted, int32_t *next_token,
+                           hipStream_t st);
+
+// profiling bracket used by the forward driver
+struct ProfScope {
+    csd_model *m;
+    hipStream_t st;
+    bool on;
+    ProfScope(csd_model *mod, hipStream_t s, int cls);
+    ~ProfScope();
+};

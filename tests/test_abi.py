@@ -1,0 +1,58 @@
+"""Host-side checks that need no GPU: the library loads and exports every symbol that
+include/csd.h declares, and host-side argument validation returns the documented codes."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2312_11462_amd as P
+    if not os.path.exists(P.library_path()):
+        from paper_2312_11462_amd import build
+        build.build()
+    return P.lib()
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "csd.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(csd_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    import paper_2312_11462_amd as P
+    names = _declared()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(P.EXPORTS) == names
+    assert b"gfx950" in L.csd_version()
+
+
+def test_null_and_domain_errors_without_a_device(L):
+    from paper_2312_11462_amd.binding import Cfg
+    out = C.c_void_p()
+    cfg = Cfg(0, 1, 2, 64, 4, 16, 256, 512, 1, 64, 8, 0, 1e-5, 10000.0)
+    assert L.csd_model_create(None, None, 0, None, C.byref(out)) == -3
+    ptrs = (C.c_void_p * 21)(*([1] * 21))
+    assert L.csd_model_create(C.byref(cfg), ptrs, 20, None, C.byref(out)) == -1          # wrong weight count
+    bad = Cfg(1, 1, 2, 64, 4, 16, 256, 512, 1, 64, 8, 0, 1e-5, 10000.0)
+    assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -5          # arch
+    bad = Cfg(0, 1, 2, 64, 4, 15, 256, 512, 1, 64, 8, 0, 1e-5, 10000.0)
+    assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -1          # odd head_dim
+    bad = Cfg(0, 1, 2, 64, 4, 16, 256, 512, 1, 4, 8, 0, 1e-5, 10000.0)
+    assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -2          # block > seq
+    assert L.csd_accept(None, None, None, None, None, None, 1, 1, 8, C.c_float(1.0), 0, None, None, None) == -3
+    one = C.c_void_p(1)
+    assert L.csd_accept(one, None, None, one, one, one, 1, 1, 8, C.c_float(0.5), 0, one, one, None) == -1
+    assert L.csd_accept(one, None, None, one, one, one, 1, 1, 8, C.c_float(1.0), 7, one, one, None) == -1
+    assert L.csd_bigram_fit(one, 9000, 10, one, None) == -2
+    assert L.csd_bigram_draft(None, one, 1, 8, one, 10, 2, 0, one, None, None) == -3
+    assert L.csd_bigram_draft(one, one, 1, 0, one, 10, 2, 0, one, None, None) == -1
+    assert L.csd_kv_bytes(None) == 0
+    assert L.csd_verify_block(None, one, one, one, 1, 1, C.c_float(1.0), one, None, None) == -3

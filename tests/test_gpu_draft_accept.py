@@ -1,0 +1,107 @@
+"""GPU parity of the integer paths through the C ABI: Max-Gram / bigram draft and the
+accept / resample step must match the oracle bit for bit on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import csd_inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2312_11462_amd as P
+    P.lib()
+    return P
+
+
+def _O():
+    from oracle import csd_oracle as O
+    return O
+
+
+def test_bigram_draft_matches_oracle(P):
+    O = _O()
+    for V, n_max, seed in [(3, 40, 1), (5, 300, 2), (300, 700, 3), (32000, 2048, 4)]:
+        B, stride = 7, n_max
+        ctx = torch.zeros((B, stride), dtype=torch.int32)
+        lens = []
+        for b in range(B):
+            n = max(1, (n_max * (b + 1)) // B - (b % 3))
+            s = I.repeat_stream(n, V, seed, b) if V > 5 else I.token_ids(n, V, seed, b)
+            ctx[b, :n] = s
+            lens.append(n)
+        lens[0] = 1                                   # degenerate: single token -> fallback
+        table = I.default_next_table(V, seed)
+        for k, cap in [(1, 0), (6, 0), (10, 0), (10, 3), (0, 0)]:
+            want, wlen = O.bigram_draft(ctx.numpy(), lens, table.numpy(), k, cap)
+            got, glen = P.bigram_draft(ctx.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), table.cuda(), k, cap)
+            assert np.array_equal(got.cpu().numpy(), want), (V, k, cap)
+            assert np.array_equal(glen.cpu().numpy(), wlen), (V, k, cap)
+
+
+def test_bigram_fit_matches_oracle(P):
+    O = _O()
+    for V, n, seed in [(8, 50, 1), (64, 1000, 2), (32000, 2048, 3), (32000, 8192, 4), (10, 2, 5), (10, 1, 6)]:
+        s = I.repeat_stream(n, V, seed, 9) if n > 4 else I.token_ids(n, V, seed, 9)
+        default = I.default_next_table(V, seed)
+        want = O.bigram_fit(s.numpy(), V, default.numpy())
+        got = P.bigram_fit(s.cuda(), V, default.cuda().clone())
+        assert np.array_equal(got.cpu().numpy(), want), (V, n)
+
+
+def _rand_dist(shape, seed, stream, sharp):
+    x = I.normal(shape, sharp, seed, stream)
+    return torch.softmax(x.double(), dim=-1).float().contiguous()
+
+
+@pytest.mark.parametrize("V,B,k", [(7, 64, 3), (1000, 16, 5), (32000, 8, 16), (32000, 1, 5), (32128, 3, 1), (5, 9, 0)])
+def test_accept_matches_oracle_bit_exact(P, V, B, k):
+    O = _O()
+    seed = 1000 + V + k
+    p = _rand_dist((B, k + 1, V), seed, 1, 2.0)
+    q = _rand_dist((B, max(k, 1), V), seed, 2, 2.0)[:, :k].contiguous()
+    # drafts drawn from q so that acceptance is neither rare nor certain
+    u = I.uniforms(B * max(k, 1), seed, 3).reshape(B, max(k, 1))[:, :k]
+    draft = (torch.cumsum(q.double(), -1) <= u[..., None].double()).sum(-1).clamp(max=V - 1).int().contiguous()
+    u_acc = I.uniforms(B * max(k, 1), seed, 4).reshape(B, max(k, 1))[:, :k].contiguous()
+    u_s = I.uniforms(B, seed, 5)
+    onehot = (I.token_ids(max(k, 1), 2, seed, 6)[:k]).to(torch.uint8)
+    cases = [dict(q=q, lenience=1.0, mode=0, oh=None), dict(q=None, lenience=1.0, mode=0, oh=None),
+             dict(q=q, lenience=2.5, mode=0, oh=None), dict(q=q, lenience=1.0, mode=0, oh=onehot),
+             dict(q=None, lenience=1.0, mode=1, oh=None), dict(q=q, lenience=3.0, mode=1, oh=onehot)]
+    for c in cases:
+        if k == 0 and c["q"] is not None:
+            continue
+        qn = None if c["q"] is None else c["q"].numpy()
+        ohn = None if c["oh"] is None else c["oh"].numpy()
+        wn, wt = O.accept(p.numpy(), qn, draft.numpy(), u_acc.numpy(), u_s.numpy(), c["lenience"], c["mode"], ohn)
+        gn, gt = P.accept(p.cuda(), None if c["q"] is None else c["q"].cuda(), draft.cuda(), u_acc.cuda(), u_s.cuda(),
+                          c["lenience"], c["mode"], None if c["oh"] is None else c["oh"].cuda())
+        assert np.array_equal(gn.cpu().numpy(), wn), c
+        assert np.array_equal(gt.cpu().numpy(), wt), c
+
+
+def test_accept_greedy_on_logits_with_ties(P):
+    O = _O()
+    V, B, k = 515, 6, 4
+    lg = torch.round(I.normal((B, k + 1, V), 3.0, 5, 1))        # integers: many exact ties
+    draft = lg[:, :k].argmax(-1).int()                           # torch picks some arg-max; only the first must pass
+    draft[2, 1] = 3
+    wn, wt = O.accept(lg.numpy(), None, draft.numpy(), np.zeros((B, k), np.float32), np.zeros(B, np.float32), 1.0, 1)
+    gn, gt = P.accept(lg.cuda(), None, draft.cuda(), torch.zeros((B, k)).cuda(), torch.zeros(B).cuda(), 1.0, 1)
+    assert np.array_equal(gn.cpu().numpy(), wn) and np.array_equal(gt.cpu().numpy(), wt)
+
+
+def test_identical_draft_accepts_all_and_errors_are_reported(P):
+    V, B, k = 1000, 4, 6
+    p = _rand_dist((B, k + 1, V), 77, 1, 1.0)
+    draft = I.token_ids(B * k, V, 77, 2).reshape(B, k).contiguous()
+    u = torch.full((B, k), 1 - 2.0 ** -24)
+    gn, _ = P.accept(p.cuda(), p[:, :k].contiguous().cuda(), draft.cuda(), u.cuda(), torch.zeros(B).cuda())
+    assert (gn.cpu().numpy() == k).all()
+    with pytest.raises(P.CsdError):
+        P.accept(p.cuda(), None, draft.cuda(), u.cuda(), torch.zeros(B).cuda(), lenience=0.5)

@@ -1,0 +1,162 @@
+"""GPU parity of the review forward through the C ABI against the CPU oracle.
+
+Tolerances are the ones the task states: |gpu - oracle| <= 1e-4 (+1e-4 relative) for the fp32
+configuration and <= 1e-2 + 2e-2 |oracle| for bf16 configurations, element by element on
+logits; token decisions are compared through csd_accept on identical probabilities elsewhere.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import csd_inputs as I
+from gpu_util import import_synthetic_kv, make_pair, prefill_both, tol_ok
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2312_11462_amd as P
+    P.lib()
+
+
+def _dev(x, dtype=torch.int32):
+    return torch.as_tensor(np.asarray(x), dtype=dtype).cuda()
+
+
+def _check_block(gm, om, block, cache_len, rtol, atol, what):
+    block = np.asarray(block, np.int32)
+    lg, pr = gm.verify_block(_dev(block), _dev(cache_len), want_probs=True)
+    ref, refp = om.verify_block(block, cache_len, want_probs=True)
+    ok, err = tol_ok(lg.cpu().numpy().astype(np.float64), ref, rtol, atol)
+    assert ok, f"{what}: logits max abs err {err}"
+    okp, errp = tol_ok(pr.cpu().numpy().astype(np.float64), refp, 5 * rtol, 1e-6)
+    assert okp, f"{what}: probs max abs err {errp}"
+    return err
+
+
+def test_tiny_fp32_config_prefix_then_block():
+    """Configuration 1: tiny fp32 decoder, 32-token prefix in the cache, k = 4 drafts."""
+    wl = I.WORKLOADS["tiny"]
+    shape, seed = wl["shape"], wl["seed"]
+    gm, om = make_pair(shape, seed, 1, 64, 8)
+    prefix = I.token_ids(33, shape.vocab, seed, 1)
+    prefill_both(gm, om, prefix[:32][None], 8)
+    from oracle import csd_oracle as O
+    table = O.bigram_fit(prefix.numpy(), shape.vocab, I.default_next_table(shape.vocab, seed).numpy())
+    draft, _ = O.bigram_draft(prefix.numpy(), [33], table, 4)
+    block = np.concatenate([prefix[-1:].numpy(), draft[0]])[None]
+    err = _check_block(gm, om, block, [32], 1e-4, 1e-4, "tiny")
+    # the cache rows written by the block and by the prefill agree with the oracle's
+    for l in range(shape.n_layers):
+        K, V = gm.kv_read(l, 0, 0, 37)
+        Ko, Vo = om.kv_read(l, 0, 0, 37)
+        assert np.abs(K.cpu().numpy() - Ko).max() < 1e-4 and np.abs(V.cpu().numpy() - Vo).max() < 1e-4
+    print("tiny max err", err)
+
+
+def test_fp32_ragged_shapes_batch_and_block_vs_incremental():
+    """Odd sizes on the generic path: d, F, V not multiples of the tile sizes; batch of 3 with
+    different cache lengths; and the block result equals one-row-at-a-time on the GPU itself."""
+    shape = I.ModelShape("odd", 0, "fp32", 2, 48, 3, 16, 100, 301)
+    gm, om = make_pair(shape, 5, 3, 80, 7, std=0.1)
+    toks = I.token_ids(3 * 40, shape.vocab, 5, 1).reshape(3, 40)
+    prefill_both(gm, om, toks[:, :21], 7)
+    # ragged: sequence b keeps only 21 - 3b rows committed
+    cl = [21, 18, 15]
+    block = np.stack([toks[b, cl[b]:cl[b] + 6].numpy() for b in range(3)])
+    _check_block(gm, om, block, cl, 1e-4, 1e-4, "ragged batch")
+    one = []
+    for i in range(6):
+        lg = gm.verify_block(_dev(block[:, i:i + 1].copy()), _dev([c + i for c in cl]))
+        one.append(lg.cpu().numpy())
+    whole = gm.verify_block(_dev(block), _dev(cl)).cpu().numpy()
+    assert np.abs(np.concatenate(one, axis=1) - whole).max() < 1e-4
+
+
+BF = I.ModelShape("bf_small", 0, "bf16", 2, 256, 4, 64, 512, 1024)
+BF128 = I.ModelShape("bf_dh128", 0, "bf16", 2, 256, 2, 128, 512, 1024)
+
+
+@pytest.mark.parametrize("gemm,attn", [("generic", "generic"), ("mfma", "generic"), ("mfma", "mfma")])
+@pytest.mark.parametrize("shape", [BF, BF128], ids=["dh64", "dh128"])
+def test_bf16_paths_small_model(shape, gemm, attn):
+    """Several key chunks and a ragged tail (prefix 200 = 128 + 72 keys; 5 and 13 block rows);
+    the MFMA kernels against the oracle, with the generic kernels as a cross-check."""
+    os.environ["CSD_GEMM"], os.environ["CSD_ATTN"] = gemm, attn
+    try:
+        gm, om = make_pair(shape, 7, 2, 300, 16, std=0.05)
+    finally:
+        del os.environ["CSD_GEMM"], os.environ["CSD_ATTN"]
+    toks = I.token_ids(2 * 260, shape.vocab, 7, 1).reshape(2, 260)
+    prefill_both(gm, om, toks[:, :200], 16)
+    e1 = _check_block(gm, om, toks[:, 200:205].numpy(), [200, 200], 2e-2, 1e-2, f"{gemm}/{attn} m=5")
+    e2 = _check_block(gm, om, toks[:, 190:203].numpy(), [190, 187], 2e-2, 1e-2, f"{gemm}/{attn} m=13 ragged")
+    print(shape.name, gemm, attn, "max err", e1, e2)
+
+
+def test_bf16_block_of_17_rows_two_row_tiles():
+    gm, om = make_pair(BF, 9, 1, 200, 17, std=0.05)
+    toks = I.token_ids(160, BF.vocab, 9, 1).reshape(1, 160)
+    prefill_both(gm, om, toks[:, :130], 17)
+    _check_block(gm, om, toks[:, 130:147].numpy(), [130], 2e-2, 1e-2, "m=17")
+
+
+def test_draft160m_config_synthetic_cache():
+    """Configuration 2: 160M-shaped bf16 model, 512 cached rows (seeded stand-in K/V, since the
+    oracle needs minutes to prefill them), k = 8 drafts from the Max-Gram model."""
+    wl = I.WORKLOADS["draft160m"]
+    shape, seed = wl["shape"], wl["seed"]
+    gm, om = make_pair(shape, seed, 1, 640, 16)
+    import_synthetic_kv(gm, om, shape, 512, seed)
+    import paper_2312_11462_amd as P
+    prefix = I.repeat_stream(513, shape.vocab, seed, 1)
+    table = P.bigram_fit(prefix.cuda(), shape.vocab, I.default_next_table(shape.vocab, seed).cuda())
+    draft, _ = P.bigram_draft(prefix.cuda(), _dev([513]), table, 8)
+    block = torch.cat([prefix[-1:].cuda(), draft[0]])[None].cpu().numpy()
+    err = _check_block(gm, om, block, [512], 2e-2, 1e-2, "160M")
+    print("160M max err", err)
+
+
+def test_run_to_run_determinism():
+    gm, _ = make_pair(BF, 11, 2, 300, 16, std=0.05)
+    toks = I.token_ids(2 * 150, BF.vocab, 11, 1).reshape(2, 150)
+    cl = _dev([0, 0])
+    outs = []
+    for _ in range(2):
+        for pos in range(0, 144, 16):
+            lg = gm.verify_block(toks[:, pos:pos + 16].contiguous().cuda(), cl + pos)
+        outs.append(lg.cpu().numpy().copy())
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_verify_accept_equals_the_two_calls():
+    import paper_2312_11462_amd as P
+    gm, _ = make_pair(BF, 13, 2, 128, 8, std=0.05)
+    toks = I.token_ids(2 * 70, BF.vocab, 13, 1).reshape(2, 70)
+    for pos in range(0, 64, 8):
+        gm.verify_block(toks[:, pos:pos + 8].contiguous().cuda(), _dev([pos, pos]))
+    block = toks[:, 64:70].contiguous().cuda()
+    cl = _dev([64, 64])
+    u_acc = I.uniforms(10, 13, 2).reshape(2, 5).contiguous().cuda()
+    u_s = I.uniforms(2, 13, 3).cuda()
+    for mode in (0, 1):
+        lg, pr = gm.verify_block(block, cl, want_probs=True)
+        a = P.accept(pr if mode == 0 else lg, None, block[:, 1:].contiguous(), u_acc, u_s, mode=mode)
+        b = gm.verify_accept(block, cl, u_acc, u_s, mode=mode)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_argument_errors_enqueue_nothing():
+    import paper_2312_11462_amd as P
+    gm, _ = make_pair(I.TINY, 1, 1, 64, 8)
+    with pytest.raises(P.CsdError):
+        gm.verify_block(_dev(np.zeros((1, 9))), _dev([0]))          # m > max_block
+    with pytest.raises(P.CsdError):
+        gm.verify_block(_dev(np.zeros((2, 4))), _dev([0, 0]))       # B > max_batch
+    with pytest.raises(P.CsdError):
+        gm.kv_write(0, 0, 60, torch.zeros((8, 64)).cuda(), torch.zeros((8, 64)).cuda())
