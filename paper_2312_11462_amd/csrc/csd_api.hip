@@ -42,10 +42,13 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->m_max * d));
     mod->allocs.push_back(p);
     mod->h = (float *)p;
-    CSD_HIP(hipMalloc(&p, asz * (size_t)m_pad * wmax));
+    const int planes = mod->mfma ? 2 : 1;
+    mod->act_plane = (size_t)m_pad * wmax;
+    mod->q_plane = (size_t)m_pad * hd;
+    CSD_HIP(hipMalloc(&p, asz * planes * mod->act_plane));
     mod->allocs.push_back(p);
     mod->act = p;
-    CSD_HIP(hipMalloc(&p, asz * (size_t)m_pad * hd));
+    CSD_HIP(hipMalloc(&p, asz * planes * mod->q_plane));
     mod->allocs.push_back(p);
     mod->qbuf = p;
     CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->s_max * mod->m_max * nmax));

@@ -25,7 +25,7 @@ __device__ __forceinline__ size_t a_v_off(const KvGeomA &g, int l, int b, int hh
 #define ATT_CHUNK 128
 
 template <int DH>
-__global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, int m, int row_tiles,
+__global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, size_t qplane, int m, int row_tiles,
                                                   const int32_t *__restrict__ cache_len, KvGeomA geo, int layer,
                                                   const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
                                                   int chunks_max) {
@@ -47,12 +47,15 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
     }
     const int row = rt * 16 + col;                           // this lane's block row
     const int qpos = t + row;                                // it sees cache rows 0..qpos
-    u32x4 qf[DH / 32];
+    u32x4 qf[DH / 32][2];                                    // hi and lo planes of the query
 #pragma unroll
     for (int s = 0; s < DH / 32; s++) {
-        qf[s] = u32x4{0u, 0u, 0u, 0u};
-        if (row < m)
-            qf[s] = *reinterpret_cast<const u32x4 *>(q + (size_t)(b * m + row) * hd + hh * DH + s * 32 + 8 * g);
+        qf[s][0] = qf[s][1] = u32x4{0u, 0u, 0u, 0u};
+        if (row < m) {
+            const bf16_t *qp = q + (size_t)(b * m + row) * hd + hh * DH + s * 32 + 8 * g;
+            qf[s][0] = *reinterpret_cast<const u32x4 *>(qp);
+            qf[s][1] = *reinterpret_cast<const u32x4 *>(qp + qplane);
+        }
     }
     const bf16_t *kc = kv + a_k_off(geo, layer, b, hh);
     const bf16_t *vc = kv + a_v_off(geo, layer, b, hh);
@@ -76,7 +79,9 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
             for (int s = 0; s < DH / 32; s++) {
                 const u32x4 a = *reinterpret_cast<const u32x4 *>(kp + s * 32);
                 sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                                __builtin_bit_cast(bf16x8, qf[s]), sT[T], 0, 0, 0);
+                                                                __builtin_bit_cast(bf16x8, qf[s][0]), sT[T], 0, 0, 0);
+                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                                __builtin_bit_cast(bf16x8, qf[s][1]), sT[T], 0, 0, 0);
             }
         }
         float sv[8];
@@ -103,10 +108,14 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
         psum += __shfl_xor(psum, 32, 64);
         lrun = lrun * alpha + psum;
         mrun = mnew;
-        u32x4 pf;
+        u32x4 pf, pl;                                        // hi and lo planes of the probabilities
 #pragma unroll
-        for (int w = 0; w < 4; w++)
-            pf[w] = (uint32_t)f32_to_bf16(pv[2 * w]) | ((uint32_t)f32_to_bf16(pv[2 * w + 1]) << 16);
+        for (int w = 0; w < 4; w++) {
+            const bf16_t h0 = f32_to_bf16(pv[2 * w]), h1 = f32_to_bf16(pv[2 * w + 1]);
+            pf[w] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            pl[w] = (uint32_t)f32_to_bf16(pv[2 * w] - bf16_to_f32(h0)) |
+                    ((uint32_t)f32_to_bf16(pv[2 * w + 1] - bf16_to_f32(h1)) << 16);
+        }
         const bool tail = kb + 32 > nk;                      // rows past nk may hold anything: zero them
 #pragma unroll
         for (int dt = 0; dt < DH / 16; dt++) {
@@ -122,6 +131,8 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
             oacc[dt] = oacc[dt] * alpha;
             oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
                                                                __builtin_bit_cast(bf16x8, pf), oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                               __builtin_bit_cast(bf16x8, pl), oacc[dt], 0, 0, 0);
         }
     }
 #pragma unroll
@@ -136,7 +147,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
 template <int DH>
 __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ part, int m, int row_tiles,
                                                    const int32_t *__restrict__ cache_len, int H, int seq_pad,
-                                                   int chunks_max, bf16_t *__restrict__ out, int ldo) {
+                                                   int chunks_max, bf16_t *__restrict__ out, int ldo, size_t plane) {
     constexpr int PS = DH + 4;
     const int r = blockIdx.x, hh = blockIdx.y, x = threadIdx.x;
     const int b = r / m, i = r % m, rt = i / 16, ri = i % 16;
@@ -154,7 +165,7 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
         num += base[c * cstride + x] * w;
         den += base[c * cstride + DH + 1] * w;
     }
-    out[(size_t)r * ldo + hh * DH + x] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+    store_act<bf16_t>(out, plane, (size_t)r * ldo + hh * DH + x, den > 0.f ? num / den : 0.f);
 }
 
 int32_t csd_attn_mfma_enqueue(csd_model *mod, const void *kv, const int32_t *cache_len, int B, int m, int layer,
@@ -168,17 +179,17 @@ int32_t csd_attn_mfma_enqueue(csd_model *mod, const void *kv, const int32_t *cac
     const dim3 mgrid(B * m, c.n_heads);
     ProfScope ps(mod, st, CSD_PROF_ATTN);
     if (c.head_dim == 128) {
-        hipLaunchKernelGGL((k_attn_mfma<128>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, m, row_tiles, cache_len, geo,
+        hipLaunchKernelGGL((k_attn_mfma<128>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo,
                            layer, (const bf16_t *)kv, scale, mod->attn_part, chunks);
         CSD_LAUNCH_CHECK();
         hipLaunchKernelGGL((k_attn_merge<128>), mgrid, dim3(128), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
-                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd);
+                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane);
     } else {
-        hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, m, row_tiles, cache_len, geo,
+        hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo,
                            layer, (const bf16_t *)kv, scale, mod->attn_part, chunks);
         CSD_LAUNCH_CHECK();
         hipLaunchKernelGGL((k_attn_merge<64>), mgrid, dim3(64), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
-                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd);
+                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane);
     }
     CSD_LAUNCH_CHECK();
     return CSD_OK;

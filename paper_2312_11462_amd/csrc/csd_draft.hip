@@ -105,15 +105,10 @@ extern "C" int32_t csd_bigram_fit(const int32_t *tokens, int32_t n, int32_t voca
 extern "C" int32_t csd_bigram_draft(const int32_t *ctx, const int32_t *ctx_len, int32_t B, int32_t ctx_stride,
                                     const int32_t *next_table, int32_t vocab, int32_t k, int32_t max_match,
                                     int32_t *out_tokens, int32_t *out_match_len, void *stream) {
-    if (!ctx || !ctx_len || !next_table || !out_tokens) return CSD_ENULL;
+    if (!ctx || !ctx_len || !next_table) return CSD_ENULL;
     if (B < 0 || k < 0 || vocab < 1 || ctx_stride < 1) return CSD_EINVAL;
-    if (B == 0 || k == 0) {
-        if (B > 0 && out_match_len) {
-            // match lengths are still defined for k == 0: run with k = 0 (kernel writes only them)
-        } else {
-            return CSD_OK;
-        }
-    }
+    if (k > 0 && !out_tokens) return CSD_ENULL;
+    if (B == 0 || (k == 0 && !out_match_len)) return CSD_OK;   // k == 0 still reports match lengths
     hipLaunchKernelGGL(k_bigram_draft, dim3(B), dim3(DRAFT_THREADS), 0, (hipStream_t)stream, ctx, ctx_len, ctx_stride,
                        next_table, vocab, k, max_match, out_tokens, out_match_len);
     CSD_LAUNCH_CHECK();

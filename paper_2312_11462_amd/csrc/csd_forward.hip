@@ -48,7 +48,7 @@ __global__ void k_copy_cols(const T *__restrict__ src, int K, int N_src, T *__re
 // fragments in registers so that 2*U*NT KB per wave are in flight.
 template <int NT, int MT, int U>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act,
-                                                   float *__restrict__ part, int M, int K, int N, int S) {
+                                                   size_t plane, float *__restrict__ part, int M, int K, int N, int S) {
     const int wave = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int lane = threadIdx.x & 63;
     const int n_groups = N / (16 * NT);
@@ -76,8 +76,9 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp,
 #pragma unroll
         for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 wa[U][NT], wb[U][NT], ba[U][MT], bb[U][MT];
+    u32x4 wa[U][NT], wb[U][NT], ba[U][MT][2], bb[U][MT][2];   // [2]: hi and lo activation planes
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    const size_t plane16 = plane / 8;                         // plane stride in 16-byte units
 
 #define CSD_LOAD_BATCH(WF, BF, KS_AT)                                                             \
     _Pragma("unroll") for (int u = 0; u < U; u++) {                                               \
@@ -85,16 +86,22 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp,
         const bool in_ = ksu_ < ks1;                                                              \
         _Pragma("unroll") for (int j = 0; j < NT; j++)                                            \
             WF[u][j] = in_ ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero;        \
-        _Pragma("unroll") for (int mt = 0; mt < MT; mt++)                                         \
-            BF[u][mt] = (in_ && valid[mt]) ? ap[mt][(size_t)ksu_ * 4] : zero;                     \
+        _Pragma("unroll") for (int mt = 0; mt < MT; mt++) {                                       \
+            BF[u][mt][0] = (in_ && valid[mt]) ? ap[mt][(size_t)ksu_ * 4] : zero;                  \
+            BF[u][mt][1] = (in_ && valid[mt]) ? ap[mt][(size_t)ksu_ * 4 + plane16] : zero;        \
+        }                                                                                         \
     }
 #define CSD_MMA_BATCH(WF, BF)                                                                     \
     _Pragma("unroll") for (int u = 0; u < U; u++)                                                 \
         _Pragma("unroll") for (int mt = 0; mt < MT; mt++)                                         \
-            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
+            _Pragma("unroll") for (int j = 0; j < NT; j++) {                                      \
                 acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
-                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, BF[u][mt]),  \
-                    acc[mt][j], 0, 0, 0);
+                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, BF[u][mt][0]), \
+                    acc[mt][j], 0, 0, 0);                                                         \
+                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, BF[u][mt][1]), \
+                    acc[mt][j], 0, 0, 0);                                                         \
+            }
 
     CSD_LOAD_BATCH(wa, ba, ks0)
     for (int ks = ks0; ks < ks1; ks += 2 * U) {
@@ -145,7 +152,7 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const TW *__restrict__ W, c
 template <typename TW, typename TA>
 __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ tokens, const TW *__restrict__ E, int V,
                                                     int d, const float *__restrict__ g, float eps,
-                                                    float *__restrict__ h, TA *__restrict__ a, int lda) {
+                                                    float *__restrict__ h, TA *__restrict__ a, int lda, size_t plane) {
     __shared__ float red[16];
     const int r = blockIdx.x;
     const int tok = tokens[r];
@@ -159,14 +166,14 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ 
     ss = block_sum(ss, red);
     const float rs = rsqrtf(ss / (float)d + eps);
     for (int x = threadIdx.x; x < d; x += blockDim.x)
-        a[(size_t)r * lda + x] = from_f32<TA>(h[(size_t)r * d + x] * rs * g[x]);
+        store_act<TA>(a, plane, (size_t)r * lda + x, h[(size_t)r * d + x] * rs * g[x]);
 }
 
 // h[r] += sum_s part[s][r];  a[r] = rmsnorm(h[r]) * g
 template <typename TA>
 __global__ __launch_bounds__(256) void k_residual_norm(const float *__restrict__ part, int S, int M, int d,
                                                        const float *__restrict__ g, float eps, float *__restrict__ h,
-                                                       TA *__restrict__ a, int lda) {
+                                                       TA *__restrict__ a, int lda, size_t plane) {
     __shared__ float red[16];
     const int r = blockIdx.x;
     float ss = 0.f;
@@ -180,7 +187,7 @@ __global__ __launch_bounds__(256) void k_residual_norm(const float *__restrict__
     ss = block_sum(ss, red);
     const float rs = rsqrtf(ss / (float)d + eps);
     for (int x = threadIdx.x; x < d; x += blockDim.x)
-        a[(size_t)r * lda + x] = from_f32<TA>(h[(size_t)r * d + x] * rs * g[x]);
+        store_act<TA>(a, plane, (size_t)r * lda + x, h[(size_t)r * d + x] * rs * g[x]);
 }
 
 // KV cache addressing.  K: [L][Bmax][H][seq_pad][dh];  V is stored transposed, [L][Bmax][H][dh][seq_pad],
@@ -201,7 +208,8 @@ __host__ __device__ inline size_t kv_v_off(const KvGeom &g, int l, int b, int hh
 template <typename TA, typename TC>
 __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, int S, int M, int m,
                                                 const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
-                                                float theta, TA *__restrict__ qout, TC *__restrict__ kv) {
+                                                float theta, TA *__restrict__ qout, size_t qplane,
+                                                TC *__restrict__ kv) {
     const int r = blockIdx.x, hh = blockIdx.y;
     const int b = r / m, i = r % m;
     const int dh = geo.dh, half = dh / 2, hd = geo.H * dh, N = 3 * hd;
@@ -222,8 +230,8 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
         }
         const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
         const float c = (float)cos(ang), sn = (float)sin(ang);
-        qout[(size_t)r * hd + hh * dh + x] = from_f32<TA>(q0 * c - q1 * sn);
-        qout[(size_t)r * hd + hh * dh + x + half] = from_f32<TA>(q0 * sn + q1 * c);
+        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + x, q0 * c - q1 * sn);
+        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + x + half, q0 * sn + q1 * c);
         if (pos_ok) {
             kc[(size_t)pos * dh + x] = from_f32<TC>(k0 * c - k1 * sn);
             kc[(size_t)pos * dh + x + half] = from_f32<TC>(k0 * sn + k1 * c);
@@ -237,7 +245,7 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
 // (gate tile j at packed tile 2j, up tile at 2j+1); row-major weights concatenate [gate | up].
 template <typename TA>
 __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, int S, int M, int F, int interleaved,
-                                                TA *__restrict__ f, int ldf) {
+                                                TA *__restrict__ f, int ldf, size_t plane) {
     const int r = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= F) return;
@@ -250,7 +258,7 @@ __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, 
         usum += p[uc];
     }
     const float sg = gsum / (1.0f + expf(-gsum));
-    f[(size_t)r * ldf + j] = from_f32<TA>(sg * usum);
+    store_act<TA>(f, plane, (size_t)r * ldf + j, sg * usum);
 }
 
 __global__ __launch_bounds__(256) void k_fix_logits(const float *__restrict__ part, int S, int M, int V,
@@ -268,7 +276,7 @@ __global__ __launch_bounds__(256) void k_fix_logits(const float *__restrict__ pa
 template <typename TA, typename TC>
 __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, int m, const int32_t *__restrict__ cache_len,
                                                     KvGeom geo, int layer, const TC *__restrict__ kv, float scale,
-                                                    TA *__restrict__ out, int ldo) {
+                                                    size_t qplane, TA *__restrict__ out, int ldo, size_t plane) {
     extern __shared__ float sm[];
     const int r = blockIdx.x, hh = blockIdx.y;
     const int b = r / m, i = r % m;
@@ -279,7 +287,10 @@ __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, in
     nk = max(1, min(nk, geo.seq_pad));
     const TC *kc = kv + kv_k_off(geo, layer, b, hh);
     const TC *vc = kv + kv_v_off(geo, layer, b, hh);
-    for (int x = threadIdx.x; x < dh; x += 64) qs[x] = to_f32<TA>(q[(size_t)r * hd + hh * dh + x]);
+    for (int x = threadIdx.x; x < dh; x += 64) {
+        const size_t qi = (size_t)r * hd + hh * dh + x;
+        qs[x] = to_f32<TA>(q[qi]) + (sizeof(TA) == 2 ? to_f32<TA>(q[qi + qplane]) : 0.f);
+    }
     __syncthreads();
     float mx = -INFINITY;
     for (int j = threadIdx.x; j < nk; j += 64) {
@@ -302,7 +313,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, in
     for (int x = threadIdx.x; x < dh; x += 64) {
         float o = 0.f;
         for (int j = 0; j < nk; j++) o = fmaf(sc[j], to_f32<TC>(vc[(size_t)x * geo.seq_pad + j]), o);
-        out[(size_t)r * ldo + hh * dh + x] = from_f32<TA>(o * rz);
+        store_act<TA>(out, plane, (size_t)r * ldo + hh * dh + x, o * rz);
     }
 }
 
@@ -347,20 +358,20 @@ ProfScope::~ProfScope() {
 }
 
 template <int NT, int U>
-static void launch_gemm_mfma_nt(const GemmW &w, const bf16_t *act, float *part, int M, hipStream_t st) {
+static void launch_gemm_mfma_nt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, hipStream_t st) {
     const int waves = w.N / (16 * NT) * w.S;
     const int blocks = (waves + 3) / 4;
     const int MT = (M + 15) / 16;
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(w.data);
     if (MT <= 1)
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 1, U>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M, w.K, w.N, w.S);
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 1, U>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
     else if (MT <= 2)
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 2, U>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M, w.K, w.N, w.S);
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 2, U>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
     else if (MT <= 4)
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 4, (U > 2 ? U / 2 : U)>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M,
-                           w.K, w.N, w.S);
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 4, (U > 2 ? U / 2 : U)>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part,
+                           M, w.K, w.N, w.S);
     else
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 9, 1>), dim3(blocks), dim3(256), 0, st, Wp, act, part, M, w.K, w.N, w.S);
+        hipLaunchKernelGGL((k_gemm_mfma<NT, 9, 1>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
 }
 
 // act: [M][w.K] in the path's activation type; part: [w.S][M][w.N]
@@ -368,9 +379,9 @@ static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, 
     ProfScope ps(mod, st, CSD_PROF_GEMM);
     if (mod->mfma) {
         if (w.nt == 2)
-            launch_gemm_mfma_nt<2, 4>(w, (const bf16_t *)act, mod->part, M, st);
+            launch_gemm_mfma_nt<2, 4>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);
         else
-            launch_gemm_mfma_nt<1, 8>(w, (const bf16_t *)act, mod->part, M, st);
+            launch_gemm_mfma_nt<1, 8>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);
     } else if (mod->cfg.dtype == CSD_DTYPE_BF16) {
         hipLaunchKernelGGL((k_gemm_simple<bf16_t>), dim3((w.N + 255) / 256), dim3(256), 0, st, (const bf16_t *)w.data,
                            (const float *)act, mod->part, M, w.K, w.N);
@@ -399,7 +410,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
-                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d);
+                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane);
         CSD_LAUNCH_CHECK();
     }
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
@@ -410,7 +421,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, lw.qkv.S, M, m,
-                               cache_len, geo, l, c.rope_theta, qb, (TC *)kv);
+                               cache_len, geo, l, c.rope_theta, qb, mod->q_plane, (TC *)kv);
             CSD_LAUNCH_CHECK();
         }
         if (mod->mfma_attn) {
@@ -419,21 +430,21 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
             ProfScope ps(mod, st, CSD_PROF_ATTN);
             const size_t lds = sizeof(float) * (size_t)(c.head_dim + mod->seq_pad);
             hipLaunchKernelGGL((k_attn_simple<TA, TC>), dim3(M, c.n_heads), dim3(64), lds, st, qb, m, cache_len, geo, l,
-                               (const TC *)kv, scale, act, hd);
+                               (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.o, act, M, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, lw.o.S, M, d, lw.ffn_norm,
-                               c.rms_eps, mod->h, act, d);
+                               c.rms_eps, mod->h, act, d, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.gu, act, M, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, lw.gu.S, M, F,
-                               mod->mfma ? 1 : 0, act, F);
+                               mod->mfma ? 1 : 0, act, F, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.down, act, M, st)) != CSD_OK) return rc;
@@ -441,7 +452,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             const float *g = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
             hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, lw.down.S, M, d, g,
-                               c.rms_eps, mod->h, act, d);
+                               c.rms_eps, mod->h, act, d, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
         if (mod->trace)

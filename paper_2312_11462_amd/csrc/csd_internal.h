@@ -33,6 +33,18 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
 
+// GEMM / attention inputs on the MFMA path are kept as two bf16 planes, hi = bf16(v) and
+// lo = bf16(v - hi): the pair carries ~16 significant bits, and the matrix cores multiply the
+// exact bf16 weights by both planes.  This keeps the forward within the logit tolerance of an
+// exact-arithmetic reference at no cost in HBM traffic (the path is bandwidth-bound).
+template <typename TA> __device__ __forceinline__ void store_act(TA *p, size_t plane, size_t idx, float v);
+template <> __device__ __forceinline__ void store_act<float>(float *p, size_t, size_t idx, float v) { p[idx] = v; }
+template <> __device__ __forceinline__ void store_act<bf16_t>(bf16_t *p, size_t plane, size_t idx, float v) {
+    const bf16_t hi = f32_to_bf16(v);
+    p[idx] = hi;
+    p[idx + plane] = f32_to_bf16(v - bf16_to_f32(hi));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -109,8 +121,10 @@ struct csd_model {
     std::vector<LayerW> layers;
     // scratch (device)
     float *h = nullptr;          // residual stream [m_max][d] fp32
-    void *act = nullptr;         // GEMM input rows [m_pad][max(d, F, hd)] (bf16 on the MFMA path, else fp32)
-    void *qbuf = nullptr;        // rotated queries [m_pad][hd], same type as act
+    void *act = nullptr;         // GEMM input rows [m_pad][max(d, F, hd)]: fp32, or two bf16 planes (hi, lo) on the MFMA path
+    void *qbuf = nullptr;        // rotated queries [m_pad][hd], same representation as act
+    size_t act_plane = 0;        // elements between the hi and lo planes of act
+    size_t q_plane = 0;          // ... and of qbuf
     float *part = nullptr;       // split-K partial sums [s_max][m_max][n_max]
     float *attn_part = nullptr;  // attention partials (MFMA attention)
     float *probs = nullptr;      // [m_max][V] when the caller does not want them
