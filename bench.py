@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of one verify+accept step of Cascade Speculative Drafting on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input, all resident in HBM:
+Max-Gram draft of the block's tail -> review forward of the 7B-shaped target over the k+1 block
+rows against a 1024-row KV cache -> softmax -> accept / resample.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload target7b|draft160m|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes(shape, B, t, m):
+    """Bytes one step must move: every streamed weight once, the visible K/V rows once, the new
+    K/V rows, the gathered embedding rows and the logits written once for the caller."""
+    d, L, V = shape.d_model, shape.n_layers, shape.vocab
+    esz = 2 if shape.dtype == "bf16" else 4
+    weights = shape.streamed_params() * esz
+    kv_read = L * B * 2 * (t + m) * d * esz
+    kv_write = L * B * 2 * m * d * esz
+    return dict(weights=weights, total=weights + kv_read + kv_write + B * m * d * esz + 4 * B * m * V)
+
+
+def algorithmic_flops(shape, B, t, m):
+    d, L = shape.d_model, shape.n_layers
+    return 2 * shape.streamed_params() * B * m + L * B * 4 * (t + m) * d * m
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="target7b")
+    ap.add_argument("--prof-steps", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", default="sample", choices=["sample", "greedy"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (sequences are independent, "
+              "so N GPUs would each run this same step on their own share); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import csd_inputs as I
+    import paper_2312_11462_amd as P
+
+    P.lib()                                   # fail loudly when the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = I.WORKLOADS[args.workload]
+    shape, B, t, k, seed = wl["shape"], wl["B"], wl["prefix"], wl["k"], wl["seed"]
+    m = k + 1
+    n_from_draft_model = 2 if args.workload == "target7b" else 0     # horizontal cascade: 2 neural drafts, tail from Max-Gram
+    k_tail = k - n_from_draft_model
+
+    # ---- setup (untimed): weights, model, cache, context, tables
+    t0 = time.time()
+    w = I.make_weights(shape, seed, device="cuda")
+    model = P.Model(shape, w, max_batch=B, max_seq=t + 64, max_block=max(m, 8))
+    host_w = None
+    if not args.no_cpu_baseline:
+        host_w = [x.cpu() for x in w]
+    del w
+    torch.cuda.empty_cache()
+    for l in range(shape.n_layers):
+        for b in range(B):
+            K, V = I.synthetic_kv(shape, t, seed, l, b, device="cuda")
+            model.kv_write(l, b, 0, K, V)
+    stride = t + 64
+    ctx = torch.zeros((B, stride), dtype=torch.int32)
+    for b in range(B):
+        ctx[b, :t + 1] = I.repeat_stream(t + 1, shape.vocab, seed, 10 + b)
+    # the first drafts of the block stand in for the neural draft level's tokens
+    neural = I.token_ids(B * max(1, n_from_draft_model), shape.vocab, seed, 99).reshape(B, -1)[:, :n_from_draft_model]
+    ctx[:, t + 1:t + 1 + n_from_draft_model] = neural
+    ctx_len = torch.full((B,), t + 1 + n_from_draft_model, dtype=torch.int32)
+    ctx, ctx_len = ctx.cuda(), ctx_len.cuda()
+    table = I.default_next_table(shape.vocab, seed).cuda()
+    for b in range(B):
+        P.bigram_fit(ctx[b, :t + 1].contiguous(), shape.vocab, table)
+    block = torch.zeros((B, m), dtype=torch.int32, device="cuda")
+    block[:, :1 + n_from_draft_model] = ctx[:, t:t + 1 + n_from_draft_model]
+    tail = torch.zeros((B, k_tail), dtype=torch.int32, device="cuda")
+    cache_len = torch.full((B,), t, dtype=torch.int32, device="cuda")
+    u_acc = I.uniforms(B * k, seed, 7).reshape(B, k).contiguous().cuda()
+    u_samp = I.uniforms(B, seed, 8).cuda()
+    onehot = torch.ones(k, dtype=torch.uint8, device="cuda")
+    n_acc = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
+    mode = 0 if args.mode == "sample" else 1
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step():
+        if B == 1:       # the draft lands directly in the block's tail
+            P.bigram_draft(ctx, ctx_len, table, k_tail, want_match_len=False, out=block[:, 1 + n_from_draft_model:])
+        else:
+            P.bigram_draft(ctx, ctx_len, table, k_tail, want_match_len=False, out=tail)
+            block[:, 1 + n_from_draft_model:] = tail
+        model.verify_accept(block, cache_len, u_acc, u_samp, q=None, q_onehot=onehot, mode=mode,
+                            n_accepted=n_acc, next_token=nxt)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    gpu_ms_per_step = e0.elapsed_time(e1) / args.steps
+    emitted = float((n_acc + 1).sum().item())
+
+    # ---- per-kernel timing with HIP events on the launch stream (separate loop: the events perturb the step)
+    model.prof_enable(True)
+    cls_ms, cls_n = [0.0, 0.0, 0.0], [0, 0, 0]
+    for _ in range(args.prof_steps):
+        step()
+        torch.cuda.synchronize()
+        for c in range(3):
+            ms, n = model.prof_read(c, reset=(c == 2))
+            cls_ms[c] += ms
+            cls_n[c] += n
+    model.prof_enable(False)
+    ab = algorithmic_bytes(shape, B, t, m)
+    fl = algorithmic_flops(shape, B, t, m)
+    gemm_ms_step = cls_ms[0] / max(1, args.prof_steps)
+    gemm_launches_step = cls_n[0] / max(1, args.prof_steps)
+    achieved = ab["weights"] / 1e9 / (gemm_ms_step / 1e3) if gemm_ms_step > 0 else 0.0
+    roofline = {
+        "bound": "hbm", "kernel": "k_gemm_mfma (all weight-streaming GEMMs of a step)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "bytes_per_launch": round(ab["weights"] / max(1.0, gemm_launches_step)),
+        "avg_launch_us": round(1e3 * gemm_ms_step / max(1.0, gemm_launches_step), 2),
+        "launches_per_step": gemm_launches_step,
+        "step_frac": round(ab["total"] / 1e9 / (gpu_ms_per_step / 1e3) / HBM_PEAK_GBS, 4),
+        "mfma_frac": round(fl / 1e12 / (gpu_ms_per_step / 1e3) / MFMA_BF16_PEAK_TFLOPS, 5),
+        "class_ms_per_step": {"gemm": round(gemm_ms_step, 4),
+                              "attention": round(cls_ms[1] / max(1, args.prof_steps), 4),
+                              "other": round(cls_ms[2] / max(1, args.prof_steps), 4)},
+    }
+
+    # ---- CPU baseline: the oracle as it stands, one whole step on the host cores
+    cpu = None
+    if host_w is not None:
+        import numpy as np
+
+        from oracle import csd_oracle as O
+        om = O.Model(shape, host_w, max_batch=1, max_seq=t + 64, max_block=max(m, 8))
+        for l in range(shape.n_layers):
+            K, V = I.synthetic_kv(shape, t, seed, l, 0, device="cuda")
+            om.kv_write(l, 0, 0, K.cpu().numpy(), V.cpu().numpy())
+        hctx = ctx[:1].cpu().numpy()
+        htab = table.cpu().numpy()
+        c0 = time.perf_counter()
+        d, _ = O.bigram_draft(hctx, ctx_len[:1].cpu().numpy(), htab, k_tail)
+        hb = block[:1].cpu().numpy().copy()
+        hb[:, 1 + n_from_draft_model:] = d
+        lg = om.verify_block(hb, [t])
+        pr = O.probs_f32(lg)
+        on, ot = O.accept(pr, None, hb[:, 1:], u_acc[:1].cpu().numpy(), u_samp[:1].cpu().numpy(), 1.0, mode)
+        cpu_s = time.perf_counter() - c0
+        cpu = {"value": round(k / cpu_s, 3), "unit": "verified tokens/s", "cores": O.threads(), "kind": "oracle",
+               "sample": f"one whole step of sequence 0 (k={k} drafts, {t}-row cache): {cpu_s:.2f} s",
+               "agrees_with_gpu": bool(int(on[0]) == int(n_acc[0].item()) and int(ot[0]) == int(nxt[0].item()))}
+
+    out = {
+        "metric": "verified tokens/s per verify+accept step, 7B-shaped bf16; % HBM/MFMA roofline",
+        "value": round(B * k / (wall / args.steps), 2), "unit": "verified tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "gpu_ms_per_step": round(gpu_ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {shape.n_layers} layers, d_model {shape.d_model}, batch {B}, "
+                               f"{t}-row KV cache, block of k={k} drafts ({n_from_draft_model} stand-ins for the neural "
+                               f"draft level + {k_tail} from Max-Gram), mode {args.mode}",
+                   "batch": B, "prefix": t, "k": k},
+        "emitted_tokens_per_s": round(emitted / (wall / args.steps), 2),
+        "setup_s": round(setup_s, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

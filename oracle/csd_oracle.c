@@ -16,11 +16,14 @@
  * embedding (half-split pairing), causal attention scaled by 1/sqrt(head_dim), SwiGLU,
  * no biases, untied LM head.
  *
- * Arithmetic: every floating-point step of the forward is fp64 on the stored weight
- * values (bf16 or fp32, widened exactly).  The accept test and the residual are fp32,
- * one rounded operation at a time, because they decide integers and both sides must
- * take that decision in the same precision; sampling is exact integer arithmetic on
- * 40-bit fixed-point weights.
+ * Arithmetic: every floating-point step of the forward is fp64 on the stored values.
+ * Stored values are the weights and the KV-cache rows, both in the configuration's storage
+ * type: bf16 configurations keep K and V in the cache rounded to bf16 (round-to-nearest-even,
+ * straight from the fp64 value), exactly as the weights are bf16; attention reads every row,
+ * the block's own included, back from the cache.  fp32 configurations store the fp64 value.
+ * The accept test and the residual are fp32, one rounded operation at a time, because they
+ * decide integers and both sides must take that decision in the same precision; sampling is
+ * exact integer arithmetic on 40-bit fixed-point weights.
  *
  * Parity pins (tests/test_oracle_*.py): library attention / norm / activation routines,
  * closed forms for degenerate weights, block-vs-incremental and cache-vs-no-cache
@@ -97,15 +100,34 @@ static double *kv_row(const csdo_model *m, double *kv, int which, int l, int b, 
     return kv + which * per + (((size_t)l * c->max_batch + b) * c->max_seq + pos) * hd;
 }
 
-/* copy rows in/out of the cache (fp32 at the interface) */
+/* nearest bf16 (ties to even) of an fp64 value, returned as fp64 */
+static double round_bf16(double x) {
+    if (x == 0.0 || !isfinite(x)) return x;
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t lo = u & 0xFFFF0000u;      /* neighbour towards zero (or f itself) */
+    uint32_t hi = lo + 0x10000u;        /* next bf16 away from zero */
+    float flo, fhi;
+    memcpy(&flo, &lo, 4);
+    memcpy(&fhi, &hi, 4);
+    double dlo = fabs(x - (double)flo), dhi = fabs((double)fhi - x);
+    if (dlo < dhi) return (double)flo;
+    if (dhi < dlo) return (double)fhi;
+    return ((lo >> 16) & 1u) ? (double)fhi : (double)flo;
+}
+
+static double to_cache(const csdo_model *m, double x) { return m->c.dtype == 1 ? round_bf16(x) : x; }
+
+/* copy rows in/out of the cache (fp32 at the interface; rounded to the cache type on write) */
 int32_t csdo_kv_write(const csdo_model *m, double *kv, int32_t l, int32_t b, int32_t pos0, int32_t n,
                       const float *K, const float *V) {
     size_t hd = (size_t)m->c.n_heads * m->c.head_dim;
     if (pos0 < 0 || pos0 + n > m->c.max_seq) return -2;
     for (int i = 0; i < n; i++)
         for (size_t x = 0; x < hd; x++) {
-            kv_row(m, kv, 0, l, b, pos0 + i)[x] = K[i * hd + x];
-            kv_row(m, kv, 1, l, b, pos0 + i)[x] = V[i * hd + x];
+            kv_row(m, kv, 0, l, b, pos0 + i)[x] = to_cache(m, K[i * hd + x]);
+            kv_row(m, kv, 1, l, b, pos0 + i)[x] = to_cache(m, V[i * hd + x]);
         }
     return 0;
 }
@@ -238,8 +260,10 @@ int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, co
                     csdo_rope(q + (size_t)i * hd + hh * dh, dh, t + i, c->rope_theta);
                     csdo_rope(kk + (size_t)i * hd + hh * dh, dh, t + i, c->rope_theta);
                 }
-                memcpy(kv_row(mod, kv, 0, l, b, t + i), kk + (size_t)i * hd, sizeof(double) * hd);
-                memcpy(kv_row(mod, kv, 1, l, b, t + i), vv + (size_t)i * hd, sizeof(double) * hd);
+                for (int x = 0; x < hd; x++) {      /* the cache holds the configuration's storage type */
+                    kv_row(mod, kv, 0, l, b, t + i)[x] = to_cache(mod, kk[(size_t)i * hd + x]);
+                    kv_row(mod, kv, 1, l, b, t + i)[x] = to_cache(mod, vv[(size_t)i * hd + x]);
+                }
             }
             /* causal attention: row i sees cache rows 0 .. t+i */
             for (int i = 0; i < m; i++)

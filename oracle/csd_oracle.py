@@ -99,9 +99,12 @@ class Model:
         self._trace = None
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().csdo_model_destroy(self._h)
-            self._h = None
+        try:
+            if getattr(self, "_h", None):
+                lib().csdo_model_destroy(self._h)
+                self._h = None
+        except Exception:      # interpreter shutdown
+            pass
 
     def reset_cache(self):
         self.kv[:] = 0.0

@@ -168,11 +168,14 @@ def bigram_fit(tokens, vocab, next_table):
     return next_table
 
 
-def bigram_draft(ctx, ctx_len, next_table, k, max_match=0, want_match_len=True):
+def bigram_draft(ctx, ctx_len, next_table, k, max_match=0, want_match_len=True, out=None):
     if ctx.ndim == 1:
         ctx = ctx[None, :]
     B, stride = ctx.shape
-    out = torch.empty((B, k), dtype=torch.int32, device="cuda")
+    if out is None:
+        out = torch.empty((B, k), dtype=torch.int32, device="cuda")
+    elif tuple(out.shape) != (B, k):
+        raise ValueError("out must be [B][k]")
     mlen = torch.empty(B, dtype=torch.int32, device="cuda") if want_match_len else None
     _chk(lib().csd_bigram_draft(_ptr(ctx, torch.int32), _ptr(ctx_len, torch.int32), B, stride,
                                 _ptr(next_table, torch.int32), next_table.shape[0], k, max_match, _ptr(out),

@@ -1,0 +1,106 @@
+"""Full-size GPU parity: the 7B-shaped bf16 target at the benchmark's launch configuration
+(batch 1, 1024 cached rows, block of k = 5 drafts) and at the batch-8 / 2048-row configuration,
+against the CPU oracle on the same seeded weights and the same seeded stand-in cache rows
+(a real prefill of 1024+ rows is hours of oracle time).  The oracle computes one sequence of
+the batch; sequences are independent, so any one of them is a fair sample."""
+import numpy as np
+import pytest
+import torch
+
+import csd_inputs as I
+from gpu_util import tol_ok
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def big():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2312_11462_amd as P
+    from oracle import csd_oracle as O
+    wl = I.WORKLOADS["target7b"]
+    shape, seed = wl["shape"], wl["seed"]
+    w = I.make_weights(shape, seed, device="cuda")
+    gm = P.Model(shape, w, max_batch=8, max_seq=2048 + 64, max_block=17)
+    host = [x.cpu() for x in w]
+    del w
+    torch.cuda.empty_cache()
+    om = O.Model(shape, host, max_batch=1, max_seq=2048 + 64, max_block=17)
+    print("7B-shaped pair ready; oracle threads", O.threads(), flush=True)
+    return P, O, gm, om, shape, seed
+
+
+def _fill(gm, om, shape, seed, n_rows, B, oracle_b):
+    for l in range(shape.n_layers):
+        for b in range(B):
+            K, V = I.synthetic_kv(shape, n_rows, seed, l, b, device="cuda")
+            gm.kv_write(l, b, 0, K, V)
+            if b == oracle_b:
+                om.kv_write(l, 0, 0, K.cpu().numpy(), V.cpu().numpy())
+    torch.cuda.synchronize()
+
+
+def _compare(gm, om, block, cache_len, oracle_b, what):
+    B, m = block.shape
+    L, d = gm.shape.n_layers, gm.shape.d_model
+    tr = torch.zeros((L + 1, B * m, d), dtype=torch.float32, device="cuda")
+    gm.set_trace(tr)
+    lg, pr = gm.verify_block(block.cuda(), torch.tensor(cache_len, dtype=torch.int32).cuda(), want_probs=True)
+    gm.set_trace(None)
+    torch.cuda.synchronize()
+    print(what, "gpu done; oracle running", flush=True)
+    ref, otr = om.verify_block(block[oracle_b:oracle_b + 1].numpy(), [cache_len[oracle_b]], trace=True)
+    got = lg[oracle_b].cpu().numpy().astype(np.float64)
+    ok, err = tol_ok(got, ref[0], 2e-2, 1e-2)
+    g = tr.cpu().numpy()[:, oracle_b * m:(oracle_b + 1) * m, :].astype(np.float64)
+    rel = max(np.linalg.norm(g[l] - otr[l]) / np.linalg.norm(otr[l]) for l in range(L + 1))
+    print(f"{what}: max |dlogit| {err:.3e}, worst residual-stream relative error {rel:.3e}", flush=True)
+    assert ok, f"{what}: logits max abs err {err}"
+    assert rel < 5e-3
+    return lg, pr, ref
+
+
+def test_target7b_batch1_prefix1024_k5(big):
+    """The benchmark configuration itself: the block mixes 2 stand-in neural drafts and 3 Max-Gram
+    drafts; logits of all 6 rows x 32000 entries are compared, then the accept decision."""
+    P, O, gm, om, shape, seed = big
+    t, k = 1024, 5
+    _fill(gm, om, shape, seed, t, 1, 0)
+    ctx = torch.zeros(t + 64, dtype=torch.int32)
+    ctx[:t + 1] = I.repeat_stream(t + 1, shape.vocab, seed, 10)
+    ctx[t + 1:t + 3] = I.token_ids(2, shape.vocab, seed, 99)
+    table = P.bigram_fit(ctx[:t + 1].cuda(), shape.vocab, I.default_next_table(shape.vocab, seed).cuda())
+    tail, mlen = P.bigram_draft(ctx.cuda(), torch.tensor([t + 3], dtype=torch.int32).cuda(), table, 3)
+    otab = O.bigram_fit(ctx[:t + 1].numpy(), shape.vocab, I.default_next_table(shape.vocab, seed).numpy())
+    otail, omlen = O.bigram_draft(ctx.numpy(), [t + 3], otab, 3)
+    assert np.array_equal(tail.cpu().numpy(), otail) and int(mlen[0]) == int(omlen[0])
+    block = torch.cat([ctx[t:t + 3], tail[0].cpu()])[None].contiguous()
+    lg, pr, ref = _compare(gm, om, block, [t], 0, "7B b1 t1024 k5")
+    # accept on identical probabilities must agree bit for bit; on each side's own probabilities the
+    # decisions are reported (they can differ only within the logit tolerance of a threshold)
+    u_acc = I.uniforms(k, seed, 7)[None].contiguous()
+    u_s = I.uniforms(1, seed, 8)
+    drafts = block[:, 1:].contiguous()
+    gn, gt = P.accept(pr, None, drafts.cuda(), u_acc.cuda(), u_s.cuda())
+    on, ot = O.accept(pr.cpu().numpy(), None, drafts.numpy(), u_acc.numpy(), u_s.numpy())
+    assert int(gn[0]) == int(on[0]) and int(gt[0]) == int(ot[0])
+    on2, ot2 = O.accept(O.probs_f32(ref), None, drafts.numpy(), u_acc.numpy(), u_s.numpy())
+    print("accept on gpu probs:", int(gn[0]), int(gt[0]), " on oracle probs:", int(on2[0]), int(ot2[0]), flush=True)
+    # greedy: arg-max tokens of all rows agree unless the oracle's top-2 gap is inside the tolerance
+    gam = lg[0].argmax(-1).cpu().numpy()
+    for i in range(k + 1):
+        top2 = np.sort(ref[0, i])[-2:]
+        if top2[1] - top2[0] > 2 * (1e-2 + 2e-2 * abs(top2[1])):
+            assert gam[i] == int(np.argmax(ref[0, i]))
+
+
+@pytest.mark.parametrize("k,oracle_b", [(4, 3), (16, 6)])
+def test_target7b_batch8_prefix2048(big, k, oracle_b):
+    """Batch of 8 independent sequences with 2048 cached rows each; 40 and 136 block rows exercise
+    the multi-row-tile GEMM paths; one sampled sequence is checked against the oracle."""
+    P, O, gm, om, shape, seed = big
+    t, B, m = 2048, 8, k + 1
+    _fill(gm, om, shape, seed, t, B, oracle_b)
+    block = I.token_ids(B * m, shape.vocab, seed, 200 + k).reshape(B, m).contiguous()
+    _compare(gm, om, block, [t] * B, oracle_b, f"7B b8 t2048 k{k} seq{oracle_b}")

@@ -31,8 +31,9 @@ def _weights(shape=SHAPE, seed=11, std=0.3, **override):
     return w
 
 
-def _torch_forward(shape, w, tokens):
-    """Whole-sequence forward without a cache, from library routines, in fp64."""
+def _torch_forward(shape, w, tokens, kv_bf16=False):
+    """Whole-sequence forward without a cache, from library routines, in fp64.  With kv_bf16 the
+    keys and values pass through the library's bf16 conversion, as a bf16 cache stores them."""
     names = I.weight_names(shape)
     W = {n: t.double() for n, t in zip(names, w)}
     T = len(tokens)
@@ -51,6 +52,8 @@ def _torch_forward(shape, w, tokens):
         q = rot((a @ W[f"l{l}.wq"]).view(T, H, dh)).transpose(0, 1)
         k = rot((a @ W[f"l{l}.wk"]).view(T, H, dh)).transpose(0, 1)
         v = (a @ W[f"l{l}.wv"]).view(T, H, dh).transpose(0, 1)
+        if kv_bf16:
+            k, v = k.float().bfloat16().double(), v.float().bfloat16().double()
         o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(0, 1).reshape(T, H * dh)
         h = h + o @ W[f"l{l}.wo"]
         a = F.rms_norm(h, (shape.d_model,), W[f"l{l}.ffn_norm"], EPS)
@@ -76,14 +79,36 @@ def test_matches_library_routines_whole_sequence():
     np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-10)
 
 
-def test_bf16_weights_are_widened_exactly():
+def test_bf16_configuration_widens_weights_exactly_and_stores_kv_as_bf16():
+    """bf16 configurations: the weights are bf16 values widened exactly, and the KV cache holds
+    bf16 values (the configuration's storage type), everything else stays fp64.  The reference
+    rounds K and V with the library's conversion; a cache left unrounded differs visibly."""
     shape = I.ModelShape("pinb", 0, "bf16", 2, 32, 4, 8, 48, 40)
     w = _weights(shape)
     w = [t.to(torch.bfloat16) if t.ndim == 2 else t for t in w]
     tokens = I.token_ids(9, shape.vocab, 4, 1).tolist()
-    ref = _torch_forward(shape, [t.float() for t in w], tokens)
-    got, _ = _oracle_full(shape, w, tokens, chunk=9)
-    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-10)
+    ref = _torch_forward(shape, [t.float() for t in w], tokens, kv_bf16=True)
+    got, m = _oracle_full(shape, w, tokens, chunk=4)
+    np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-9)
+    unrounded = _torch_forward(shape, [t.float() for t in w], tokens, kv_bf16=False)
+    assert np.abs(unrounded - ref).max() > 1e-5
+    K, V = m.kv_read(1, 0, 0, 9)
+    assert np.array_equal(K, torch.tensor(K).float().bfloat16().double().numpy())
+    assert np.array_equal(V, torch.tensor(V).float().bfloat16().double().numpy())
+
+
+def test_round_to_bf16_ties_to_even_and_is_not_double_rounded():
+    """kv_write rounds fp32 inputs to the cache type: exact ties go to the even significand."""
+    shape = I.ModelShape("pinb", 0, "bf16", 1, 32, 4, 8, 48, 40)
+    m = O.Model(shape, [t.to(torch.bfloat16) if t.ndim == 2 else t for t in _weights(shape)],
+                max_batch=1, max_seq=8, max_block=4)
+    vals = np.zeros((1, 32), np.float32)
+    vals[0, :6] = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -(1.0 + 2.0 ** -8), 3.1415926, 1e-30]
+    m.kv_write(0, 0, 0, vals, vals)
+    K, _ = m.kv_read(0, 0, 0, 1)
+    want = torch.tensor(vals).bfloat16().double().numpy()
+    assert np.array_equal(K, want)
+    assert K[0, 0] == 1.0 and K[0, 1] == 1.0 + 2.0 ** -6 and K[0, 2] == 1.0 + 2.0 ** -7
 
 
 @pytest.mark.parametrize("chunk", [1, 4, 7])
