@@ -166,6 +166,21 @@ int32_t csd_verify_accept(csd_model *model, void *kv, const int32_t *tokens, con
  * B*m rows after the embedding and after every layer to trace[(n_layers+1)][B*m][d] (fp32). */
 int32_t csd_debug_set_trace(csd_model *model, float *trace);
 
+/* Test hook, synchronous: *flag (HOST) receives 1 if a device-wide barrier of the single-launch
+ * path ever gave up waiting (its wait is bounded so that every wave exits), else 0. */
+int32_t csd_debug_error_flag(const csd_model *model, uint32_t *flag);
+
+/* Profiling hook of the single-launch kernel: when marks != NULL (device, uint64
+ * [5 * (2 + 5*n_layers)][grid] with grid = number of compute units), workgroup w stores the 100 MHz
+ * wall clock at five points of every phase p in marks[5p + i][w]: i = 0 phase start, 1 after the
+ * activation prologue, 2 after its last weight tile, 3 after the epilogue, 4 after the barrier. */
+int32_t csd_debug_set_timestamps(csd_model *model, uint64_t *marks);
+
+/* Which forward csd_verify_block would run for B sequences of m rows: 0 = one kernel per operation
+ * (any shape), 1 = one kernel per phase, 2 = the single-launch persistent kernel (B*m <= 16 rows that
+ * fit LDS).  The environment variable CSD_PATH=multikernel|phases at csd_model_create forces 0 or 1. */
+int32_t csd_debug_path(const csd_model *model, int32_t B, int32_t m);
+
 /* Kernel timing hook for benchmarks.  While enabled, each verify call brackets every kernel
  * it launches with a pair of HIP events on the caller's stream (this perturbs the step, so
  * throughput is timed with the hook off).  After the caller has synchronised the stream,

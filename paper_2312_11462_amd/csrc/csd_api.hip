@@ -23,8 +23,9 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->m_max = c.max_batch * c.max_block;
     const int d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab;
     // The MFMA path needs whole 16-feature tiles and 32-wide k-steps everywhere.
-    const bool tiles_ok = d % 32 == 0 && hd % 32 == 0 && F % 32 == 0 && V % 16 == 0;
+    const bool tiles_ok = d % 32 == 0 && hd % 32 == 0 && F % 32 == 0 && V % 16 == 0 && c.head_dim % 16 == 0;
     mod->mfma = c.dtype == CSD_DTYPE_BF16 && tiles_ok && !env_is("CSD_GEMM", "generic");
+    mod->kperm = mod->mfma;
     mod->mfma_attn = mod->mfma && (c.head_dim == 64 || c.head_dim == 128) && !env_is("CSD_ATTN", "generic");
     if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + mod->seq_pad) > 64 * 1024) return CSD_ESHAPE;
     int32_t rc;
@@ -68,7 +69,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     }
     mod->ev.resize(8192);
     for (auto &e : mod->ev) CSD_HIP(hipEventCreate(&e));
-    return CSD_OK;
+    return csd_fused_init(mod, st);
 }
 
 extern "C" int32_t csd_model_create(const csd_model_cfg *cfg, const void *const *weight_ptrs, int32_t n_weights,
@@ -100,6 +101,7 @@ extern "C" int32_t csd_model_create(const csd_model_cfg *cfg, const void *const 
 
 extern "C" int32_t csd_model_destroy(csd_model *mod) {
     if (!mod) return CSD_ENULL;
+    csd_fused_free(mod);
     for (void *p : mod->allocs) (void)hipFree(p);
     for (auto &e : mod->ev)
         if (e) (void)hipEventDestroy(e);
@@ -166,6 +168,22 @@ extern "C" int32_t csd_debug_set_trace(csd_model *mod, float *trace) {
     if (!mod) return CSD_ENULL;
     mod->trace = trace;
     return CSD_OK;
+}
+
+extern "C" int32_t csd_debug_error_flag(const csd_model *mod, uint32_t *flag) {
+    if (!mod || !flag) return CSD_ENULL;
+    return csd_fused_error(mod, flag);
+}
+
+extern "C" int32_t csd_debug_set_timestamps(csd_model *mod, uint64_t *marks) {
+    if (!mod) return CSD_ENULL;
+    mod->fused_ts = marks;
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_debug_path(const csd_model *mod, int32_t B, int32_t m) {
+    if (!mod) return CSD_ENULL;
+    return csd_fused_path(mod, B, m);
 }
 
 extern "C" int32_t csd_prof_enable(csd_model *mod, int32_t on) {

@@ -11,22 +11,11 @@
 // un-normalised output) that a small merge kernel combines.
 #include "csd_internal.h"
 
-struct KvGeomA {
-    int Bmax, H, dh, seq_pad, L;
-};
-__device__ __forceinline__ size_t a_head_elems(const KvGeomA &g) { return (size_t)g.seq_pad * g.dh; }
-__device__ __forceinline__ size_t a_k_off(const KvGeomA &g, int l, int b, int hh) {
-    return (((size_t)l * g.Bmax + b) * g.H + hh) * a_head_elems(g);
-}
-__device__ __forceinline__ size_t a_v_off(const KvGeomA &g, int l, int b, int hh) {
-    return (size_t)g.L * g.Bmax * g.H * a_head_elems(g) + a_k_off(g, l, b, hh);
-}
-
 #define ATT_CHUNK 128
 
 template <int DH>
 __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, size_t qplane, int m, int row_tiles,
-                                                  const int32_t *__restrict__ cache_len, KvGeomA geo, int layer,
+                                                  const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
                                                   const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
                                                   int chunks_max) {
     constexpr int PS = DH + 4;   // floats per partial row: DH outputs, running max, running sum, pad
@@ -57,8 +46,8 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
             qf[s][1] = *reinterpret_cast<const u32x4 *>(qp + qplane);
         }
     }
-    const bf16_t *kc = kv + a_k_off(geo, layer, b, hh);
-    const bf16_t *vc = kv + a_v_off(geo, layer, b, hh);
+    const bf16_t *kc = kv + kv_k_off(geo, layer, b, hh);
+    const bf16_t *vc = kv + kv_v_off(geo, layer, b, hh);
 
     f32x4 oacc[DH / 16];
 #pragma unroll
@@ -171,7 +160,7 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
 int32_t csd_attn_mfma_enqueue(csd_model *mod, const void *kv, const int32_t *cache_len, int B, int m, int layer,
                               hipStream_t st) {
     const csd_model_cfg &c = mod->cfg;
-    const KvGeomA geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, c.n_layers};
+    const KvGeom geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, c.n_layers, mod->kperm ? 1 : 0};
     const int row_tiles = (m + 15) / 16;
     const int chunks = mod->attn_chunks_max;
     const float scale = 1.0f / sqrtf((float)c.head_dim);

@@ -15,8 +15,9 @@
 
 // One 16-byte chunk per thread: tile (nt, ks), lane (i = lane%16 -> output feature, g = lane/16)
 // holds W[ks*32 + 8g + j][nt*16 + i], j = 0..7, the A operand of v_mfma_f32_16x16x32_bf16.
+// perm_dh > 0: the piece is a q or k projection whose output features are taken in rotary pair order.
 __global__ void k_pack_tiles(const bf16_t *__restrict__ src, int K, int N_src, bf16_t *__restrict__ dst, int KS,
-                             int dst_tile_base, int dst_tile_stride) {
+                             int dst_tile_base, int dst_tile_stride, int perm_dh) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t total = (size_t)(N_src / 16) * KS * 64;
     if (idx >= total) return;
@@ -26,7 +27,12 @@ __global__ void k_pack_tiles(const bf16_t *__restrict__ src, int K, int N_src, b
     const int i = lane & 15, g = lane >> 4;
     const int dt = dst_tile_base + dst_tile_stride * nt;
     bf16_t *o = dst + (((size_t)dt * KS + ks) * 64 + lane) * 8;
-    const bf16_t *s = src + (size_t)(ks * 32 + 8 * g) * N_src + nt * 16 + i;
+    int col = nt * 16 + i;
+    if (perm_dh > 0) {
+        const int head = (nt * 16) / perm_dh, ti = nt % (perm_dh / 16);
+        col = head * perm_dh + (i < 8 ? 8 * ti + i : perm_dh / 2 + 8 * ti + (i - 8));
+    }
+    const bf16_t *s = src + (size_t)(ks * 32 + 8 * g) * N_src + col;
 #pragma unroll
     for (int j = 0; j < 8; j++) o[j] = s[(size_t)j * N_src];
 }
@@ -190,19 +196,6 @@ __global__ __launch_bounds__(256) void k_residual_norm(const float *__restrict__
         store_act<TA>(a, plane, (size_t)r * lda + x, h[(size_t)r * d + x] * rs * g[x]);
 }
 
-// KV cache addressing.  K: [L][Bmax][H][seq_pad][dh];  V is stored transposed, [L][Bmax][H][dh][seq_pad],
-// so that the P*V contraction reads 8 consecutive keys per lane.
-struct KvGeom {
-    int Bmax, H, dh, seq_pad, L;
-};
-__host__ __device__ inline size_t kv_head_elems(const KvGeom &g) { return (size_t)g.seq_pad * g.dh; }
-__host__ __device__ inline size_t kv_k_off(const KvGeom &g, int l, int b, int hh) {
-    return (((size_t)l * g.Bmax + b) * g.H + hh) * kv_head_elems(g);
-}
-__host__ __device__ inline size_t kv_v_off(const KvGeom &g, int l, int b, int hh) {
-    return (size_t)g.L * g.Bmax * g.H * kv_head_elems(g) + kv_k_off(g, l, b, hh);
-}
-
 // Sum the QKV partial planes, rotate q and k (half-split pairs, angle pos * theta^(-2x/dh)), write q for
 // the attention kernel and append K (rotated) and V to the cache at position cache_len[b] + i.
 template <typename TA, typename TC>
@@ -219,22 +212,23 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
     TC *vc = kv + kv_v_off(geo, layer, b, hh);
     for (int x = threadIdx.x; x < half; x += blockDim.x) {
         float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+        const int p0 = rope_perm(x, dh, geo.kperm), p1 = rope_perm(x + half, dh, geo.kperm);
         for (int s = 0; s < S; s++) {
-            const float *p = part + ((size_t)s * M + r) * N + hh * dh + x;
-            q0 += p[0];
-            q1 += p[half];
-            k0 += p[hd];
-            k1 += p[hd + half];
-            v0 += p[2 * hd];
-            v1 += p[2 * hd + half];
+            const float *p = part + ((size_t)s * M + r) * N + hh * dh;
+            q0 += p[p0];
+            q1 += p[p1];
+            k0 += p[hd + p0];
+            k1 += p[hd + p1];
+            v0 += p[2 * hd + x];
+            v1 += p[2 * hd + x + half];
         }
         const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
         const float c = (float)cos(ang), sn = (float)sin(ang);
-        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + x, q0 * c - q1 * sn);
-        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + x + half, q0 * sn + q1 * c);
+        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p0, q0 * c - q1 * sn);
+        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p1, q0 * sn + q1 * c);
         if (pos_ok) {
-            kc[(size_t)pos * dh + x] = from_f32<TC>(k0 * c - k1 * sn);
-            kc[(size_t)pos * dh + x + half] = from_f32<TC>(k0 * sn + k1 * c);
+            kc[(size_t)pos * dh + p0] = from_f32<TC>(k0 * c - k1 * sn);
+            kc[(size_t)pos * dh + p1] = from_f32<TC>(k0 * sn + k1 * c);
             vc[(size_t)x * geo.seq_pad + pos] = from_f32<TC>(v0);
             vc[(size_t)(x + half) * geo.seq_pad + pos] = from_f32<TC>(v1);
         }
@@ -325,7 +319,7 @@ __global__ void k_kv_write(TC *__restrict__ kv, KvGeom geo, int layer, int b, in
     const int hd = geo.H * geo.dh;
     if (idx >= (size_t)n * hd) return;
     const int i = (int)(idx / hd), c = (int)(idx % hd), hh = c / geo.dh, x = c % geo.dh;
-    kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + x] = from_f32<TC>(K[idx]);
+    kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + rope_perm(x, geo.dh, geo.kperm)] = from_f32<TC>(K[idx]);
     kv[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos0 + i] = from_f32<TC>(V[idx]);
 }
 template <typename TC>
@@ -335,14 +329,15 @@ __global__ void k_kv_read(const TC *__restrict__ kv, KvGeom geo, int layer, int 
     const int hd = geo.H * geo.dh;
     if (idx >= (size_t)n * hd) return;
     const int i = (int)(idx / hd), c = (int)(idx % hd), hh = c / geo.dh, x = c % geo.dh;
-    K[idx] = to_f32<TC>(kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + x]);
+    K[idx] = to_f32<TC>(kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + rope_perm(x, geo.dh, geo.kperm)]);
     V[idx] = to_f32<TC>(kv[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos0 + i]);
 }
 
 // ------------------------------------------------------------------------------- host driver
 
 static KvGeom geom(const csd_model *mod) {
-    return KvGeom{mod->cfg.max_batch, mod->cfg.n_heads, mod->cfg.head_dim, mod->seq_pad, mod->cfg.n_layers};
+    return KvGeom{mod->cfg.max_batch, mod->cfg.n_heads, mod->cfg.head_dim, mod->seq_pad, mod->cfg.n_layers,
+                  mod->kperm ? 1 : 0};
 }
 
 ProfScope::ProfScope(csd_model *mod, hipStream_t s, int cls) : m(mod), st(s), on(false) {
@@ -471,6 +466,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
 
 int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
                             int32_t m, float *logits, hipStream_t st) {
+    if (csd_fused_eligible(mod, B, m)) return csd_fused_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->cfg.dtype == CSD_DTYPE_FP32)
         return forward_typed<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->mfma) return forward_typed<bf16_t, bf16_t, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
@@ -495,10 +491,11 @@ static int32_t copy_cols(const void *src, int K, int N_src, void *dst, int N_dst
     return CSD_OK;
 }
 
-static int32_t pack_tiles(const void *src, int K, int N_src, void *dst, int base, int stride, hipStream_t st) {
+static int32_t pack_tiles(const void *src, int K, int N_src, void *dst, int base, int stride, int perm_dh,
+                          hipStream_t st) {
     const size_t total = (size_t)(N_src / 16) * (K / 32) * 64;
     hipLaunchKernelGGL(k_pack_tiles, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)src, K, N_src,
-                       (bf16_t *)dst, K / 32, base, stride);
+                       (bf16_t *)dst, K / 32, base, stride, perm_dh);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }
@@ -513,6 +510,7 @@ struct Piece {
     const void *src;
     int N_src;
     int base, stride;   // tile placement (MFMA) ; col0 = base*16 (row-major)
+    int perm_dh;        // > 0: take the piece's output features in rotary pair order (q and k projections)
 };
 
 static int32_t build_gemm(csd_model *mod, GemmW *g, int K, int N, const Piece *pieces, int n_pieces, bool interleave,
@@ -526,7 +524,8 @@ static int32_t build_gemm(csd_model *mod, GemmW *g, int K, int N, const Piece *p
         g->nt = (N / 16) % 2 == 0 && (N / 32) >= 512 ? 2 : 1;
         g->S = pick_splits(N / (16 * g->nt), K / 32);
         for (int i = 0; i < n_pieces; i++)
-            if ((rc = pack_tiles(pieces[i].src, K, pieces[i].N_src, g->data, pieces[i].base, pieces[i].stride, st)) != CSD_OK)
+            if ((rc = pack_tiles(pieces[i].src, K, pieces[i].N_src, g->data, pieces[i].base, pieces[i].stride,
+                                 mod->kperm ? pieces[i].perm_dh : 0, st)) != CSD_OK)
                 return rc;
     } else {
         g->nt = 1;
@@ -561,18 +560,18 @@ int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st) {
         if ((rc = dev_alloc(mod, (void **)&o.ffn_norm, sizeof(float) * d)) != CSD_OK) return rc;
         CSD_HIP(hipMemcpyAsync(o.attn_norm, lw[0], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
         CSD_HIP(hipMemcpyAsync(o.ffn_norm, lw[5], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
-        const Piece qkv[3] = {{lw[1], hd, 0, 1}, {lw[2], hd, hd / 16, 1}, {lw[3], hd, 2 * hd / 16, 1}};
+        const Piece qkv[3] = {{lw[1], hd, 0, 1, c.head_dim}, {lw[2], hd, hd / 16, 1, c.head_dim}, {lw[3], hd, 2 * hd / 16, 1, 0}};
         if ((rc = build_gemm(mod, &o.qkv, d, 3 * hd, qkv, 3, false, st)) != CSD_OK) return rc;
-        const Piece wo[1] = {{lw[4], d, 0, 1}};
+        const Piece wo[1] = {{lw[4], d, 0, 1, 0}};
         if ((rc = build_gemm(mod, &o.o, hd, d, wo, 1, false, st)) != CSD_OK) return rc;
-        const Piece gu[2] = {{lw[6], F, 0, 2}, {lw[7], F, 1, 2}};
+        const Piece gu[2] = {{lw[6], F, 0, 2, 0}, {lw[7], F, 1, 2, 0}};
         if ((rc = build_gemm(mod, &o.gu, d, 2 * F, gu, 2, true, st)) != CSD_OK) return rc;
-        const Piece dn[1] = {{lw[8], d, 0, 1}};
+        const Piece dn[1] = {{lw[8], d, 0, 1, 0}};
         if ((rc = build_gemm(mod, &o.down, F, d, dn, 1, false, st)) != CSD_OK) return rc;
     }
     if ((rc = dev_alloc(mod, (void **)&mod->final_norm, sizeof(float) * d)) != CSD_OK) return rc;
     CSD_HIP(hipMemcpyAsync(mod->final_norm, w[1 + 9 * L], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
-    const Piece lm[1] = {{w[2 + 9 * L], V, 0, 1}};
+    const Piece lm[1] = {{w[2 + 9 * L], V, 0, 1, 0}};
     if ((rc = build_gemm(mod, &mod->lm, d, V, lm, 1, false, st)) != CSD_OK) return rc;
     return CSD_OK;
 }

@@ -3,6 +3,8 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
 #include <vector>
 
 #include "../../include/csd.h"
@@ -18,12 +20,13 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// round-to-nearest-even through the hardware conversion (v_cvt_pk_bf16_f32 on gfx950)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values packed into one dword, a in the low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
 }
 
 template <typename T> __device__ __forceinline__ float to_f32(T v);
@@ -43,6 +46,27 @@ template <> __device__ __forceinline__ void store_act<bf16_t>(bf16_t *p, size_t 
     const bf16_t hi = f32_to_bf16(v);
     p[idx] = hi;
     p[idx + plane] = f32_to_bf16(v - bf16_to_f32(hi));
+}
+
+// KV cache addressing.  K: [L][Bmax][H][seq_pad][dh];  V is stored transposed, [L][Bmax][H][dh][seq_pad],
+// so that the P*V contraction reads 8 consecutive keys per lane.  When kperm is set (MFMA models), the dh
+// entries of a K row (and of a query row) are stored in "pair order": 16-entry tile ti holds the 8 entries
+// 8ti..8ti+7 of the first half followed by their rotary partners 8ti+dh/2.. of the second half, so that a
+// 16-feature MFMA output tile contains whole rotary pairs.  q.k is invariant under a common permutation.
+struct KvGeom {
+    int Bmax, H, dh, seq_pad, L, kperm;
+};
+__host__ __device__ inline int rope_perm(int x, int dh, int kperm) {
+    if (!kperm) return x;
+    const int half = dh / 2, xp = x < half ? x : x - half;
+    return 16 * (xp / 8) + (xp % 8) + (x < half ? 0 : 8);
+}
+__host__ __device__ inline size_t kv_head_elems(const KvGeom &g) { return (size_t)g.seq_pad * g.dh; }
+__host__ __device__ inline size_t kv_k_off(const KvGeom &g, int l, int b, int hh) {
+    return (((size_t)l * g.Bmax + b) * g.H + hh) * kv_head_elems(g);
+}
+__host__ __device__ inline size_t kv_v_off(const KvGeom &g, int l, int b, int hh) {
+    return (size_t)g.L * g.Bmax * g.H * kv_head_elems(g) + kv_k_off(g, l, b, hh);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -111,6 +135,7 @@ struct csd_model {
     csd_model_cfg cfg;
     bool mfma = false;        // bf16 tiles + MFMA GEMMs; otherwise generic kernels on row-major weights
     bool mfma_attn = false;
+    bool kperm = false;       // q / K rows kept in rotary pair order (see KvGeom)
     int hd = 0;               // n_heads * head_dim
     int seq_pad = 0;          // cache rows per sequence, padded to 64
     int m_max = 0;            // max_batch * max_block
@@ -130,6 +155,9 @@ struct csd_model {
     float *probs = nullptr;      // [m_max][V] when the caller does not want them
     int attn_chunks_max = 0;
     float *trace = nullptr;
+    void *fused = nullptr;           // state of the single-launch path (csd_fused.hip), or null
+    float *fused_attn_part = nullptr;
+    void *fused_ts = nullptr;        // optional timing marks of the single-launch kernel (debug hook)
     // profiling
     bool prof = false;
     std::vector<hipEvent_t> ev;
@@ -144,6 +172,14 @@ struct csd_model {
 int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
                             int32_t B, int32_t m, float *logits, hipStream_t st);
 int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st);
+// csd_fused.hip: single-launch forward for small blocks
+int32_t csd_fused_init(csd_model *mod, hipStream_t st);
+void csd_fused_free(csd_model *mod);
+bool csd_fused_eligible(const csd_model *mod, int32_t B, int32_t m);
+int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
+                          int32_t m, float *logits, hipStream_t st);
+int32_t csd_fused_error(const csd_model *mod, uint32_t *flag);
+int32_t csd_fused_path(const csd_model *mod, int32_t B, int32_t m);
 // csd_accept.hip
 int32_t csd_softmax_enqueue(const float *logits, float *probs, int64_t rows, int32_t V, float temperature,
                             hipStream_t st);

@@ -92,21 +92,26 @@ BF = I.ModelShape("bf_small", 0, "bf16", 2, 256, 4, 64, 512, 1024)
 BF128 = I.ModelShape("bf_dh128", 0, "bf16", 2, 256, 2, 128, 512, 1024)
 
 
-@pytest.mark.parametrize("gemm,attn", [("generic", "generic"), ("mfma", "generic"), ("mfma", "mfma")])
+@pytest.mark.parametrize("gemm,attn,path", [("generic", "generic", "multikernel"), ("mfma", "generic", "multikernel"),
+                                            ("mfma", "mfma", "multikernel"), ("mfma", "mfma", "phases"),
+                                            ("mfma", "mfma", "persistent")])
 @pytest.mark.parametrize("shape", [BF, BF128], ids=["dh64", "dh128"])
-def test_bf16_paths_small_model(shape, gemm, attn):
+def test_bf16_paths_small_model(shape, gemm, attn, path):
     """Several key chunks and a ragged tail (prefix 200 = 128 + 72 keys; 5 and 13 block rows);
-    the MFMA kernels against the oracle, with the generic kernels as a cross-check."""
-    os.environ["CSD_GEMM"], os.environ["CSD_ATTN"] = gemm, attn
+    every forward implementation against the oracle: generic kernels, the per-operation MFMA
+    kernels, one kernel per phase, and the single-launch persistent kernel."""
+    os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"] = gemm, attn, path
     try:
         gm, om = make_pair(shape, 7, 2, 300, 16, std=0.05)
     finally:
-        del os.environ["CSD_GEMM"], os.environ["CSD_ATTN"]
+        del os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"]
+    assert gm.path(2, 5) == {"multikernel": 0, "phases": 1, "persistent": 2}[path]
     toks = I.token_ids(2 * 260, shape.vocab, 7, 1).reshape(2, 260)
     prefill_both(gm, om, toks[:, :200], 16)
     e1 = _check_block(gm, om, toks[:, 200:205].numpy(), [200, 200], 2e-2, 1e-2, f"{gemm}/{attn} m=5", 5e-3)
     e2 = _check_block(gm, om, toks[:, 190:203].numpy(), [190, 187], 2e-2, 1e-2, f"{gemm}/{attn} m=13 ragged", 5e-3)
-    print(shape.name, gemm, attn, "max err", e1, e2)
+    assert gm.error_flag() == 0
+    print(shape.name, gemm, attn, path, "max err", e1, e2)
 
 
 def test_bf16_block_of_17_rows_two_row_tiles():
