@@ -21,15 +21,26 @@ def build(verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link the C-ABI shared library."""
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-function",
+           "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
+    lines = (res.stdout + res.stderr).splitlines()
+    remarks = [l for l in lines if "-Rpass-analysis=kernel-resource-usage" in l]
+    others = [l for l in lines if l not in remarks and "packed-fp32-ops" not in l]
     if verbose or res.returncode != 0:
         # the host pass does not know the packed-fp32 feature and says so; that is harmless
-        print("\n".join(l for l in (res.stdout + res.stderr).splitlines()
-                        if "packed-fp32-ops" not in l))
+        print("\n".join(others))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed")
+    # a kernel that spills registers is a performance bug: say so at build time
+    name = None
+    for l in remarks:
+        if "Function Name:" in l or " Name: " in l:
+            name = l.split("Name:")[1].split("[")[0].strip()
+        if "VGPRs Spill:" in l:
+            n = int(l.split("VGPRs Spill:")[1].split("[")[0])
+            if n > 0:
+                print(f"warning: kernel {name} spills {n} VGPRs")
     return LIB
 
 

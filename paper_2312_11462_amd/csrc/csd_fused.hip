@@ -3,18 +3,23 @@
 // between phases, so the weights stream from HBM without kernel boundaries in between.
 //
 // Phases of a layer (five barriers):
-//   1. QKV projection.  Prologue: rmsnorm(h) into LDS as two bf16 planes.  Epilogue: rotate q and k
-//      (the projection's output features are tiled in rotary pair order, so a 16-feature MFMA tile
-//      holds whole pairs), append K and V to the cache, store q.
+//   1. QKV projection; epilogue: scale by the row's RMS factor, rotate q and k (the projection's
+//      output features are tiled in rotary pair order, so a 16-feature MFMA tile holds whole pairs),
+//      append K and V to the cache, store q.
 //   2. Block attention over the cached prefix: a workgroup takes (sequence, head, 256 keys), its 8
 //      waves one 32-key tile each; partial softmax states merge in LDS, then across workgroups by
 //      the last one to arrive.
-//   3. Output projection; epilogue h += .
-//   4. Gate/up projection (prologue rmsnorm(h) into LDS); epilogue f = silu(gate) * up.
-//   5. Down projection; epilogue h += .
+//   3. Output projection; epilogue h += , and the next GEMM's input h*gain as two bf16 planes.
+//   4. Gate/up projection; epilogue f = silu(gate) * up (after the RMS factor).
+//   5. Down projection; epilogue as in 3.
+// RMSNorm is folded around the GEMM: rmsnorm(h)*g @ W = rstd(row) * ((h*g) @ W), so the producer of h
+// writes h*g (two bf16 planes) plus per-tile sums of squares, and the consumer multiplies its output
+// rows by rstd = 1/sqrt(sum/d + eps).  No phase needs a normalisation pass over the activations.
 // A GEMM work item is a group of TG adjacent 16-feature tiles over the whole K; the 8 waves of the
-// workgroup split K, reduce through LDS in a fixed order (deterministic) and one wave per tile
-// applies the epilogue, so no partial sums ever travel through HBM.
+// workgroup split K, stream their weight fragments through a register ring that runs ahead across
+// items and across the barrier, read the activation fragments (L2-resident) through a second ring,
+// reduce through LDS in a fixed order (deterministic), and one wave per tile applies the epilogue,
+// so no partial sums ever travel through HBM.
 //
 // The same phase functions are also launchable one kernel per phase (debugging / comparison).
 #include "csd_internal.h"
@@ -34,7 +39,8 @@ struct FusedParams {
     int M, m, B, d, hd, H, dh, F, V, L, seq_pad, Bmax, kperm;
     int kg_max;        // key groups (256 keys each) covered by the attention phase's item list
     int tg_qkv, tg_lm;
-    int lds_red_off, lds_rstd_off;
+    int lds_red_off, lds_rstd_off;   // LDS: [0, red_off) activation fragments (or the attention merge area),
+                                     // then the split-K reduction scratch, then 16 floats of rstd
     float eps, scale, theta;
     const int32_t *tokens, *cache_len;
     const bf16_t *embed;
@@ -46,6 +52,9 @@ struct FusedParams {
     size_t q_plane;
     bf16_t *act;       // attention output (row stride hd) and SwiGLU output (row stride F), two planes
     size_t act_plane;
+    bf16_t *hg;        // h * gain of the next norm, row stride d, two planes: input of QKV / gate-up / LM head
+    size_t hg_plane;
+    float *ssq;        // [16 rows][d/16 tiles] sums of squares of h, per tile
     float *cs;         // rotary table [M][dh/2][cos, sin]
     bf16_t *kv;
     float *attn_part;
@@ -114,15 +123,30 @@ __device__ __forceinline__ void co_st16(__amdgpu_buffer_rsrc_t r, int off, bf16_
 #define BAR_GROUP 32
 #define BAR_STRIDE 32   /* unsigned long longs between counters: 256 bytes */
 
-__device__ __forceinline__ void grid_barrier(const FusedParams &P, unsigned long long epoch) {
-    __syncthreads();            // all of this workgroup's coherent stores have been acknowledged
+// service_only: only the service wave (wave 0) stored to global memory in this phase (GEMM phases: the
+// other waves hand their partial sums over through LDS), so only it waits for its store acknowledgements
+// and the streaming waves run straight on to prefetch the next phase's weights.
+__device__ __forceinline__ void grid_arrive(const FusedParams &P, unsigned long long epoch, bool service_only) {
+    if (service_only) {
+        if (threadIdx.x < 64) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's stores are acknowledged
+    } else {
+        __syncthreads();        // all of this workgroup's write-through stores have been acknowledged
+    }
     if (threadIdx.x == 0) {
-        const int G = gridDim.x, grp = blockIdx.x / BAR_GROUP, ngrp = (G + BAR_GROUP - 1) / BAR_GROUP;
+        const int G = gridDim.x, grp = blockIdx.x / BAR_GROUP;
         const int gsize = min(BAR_GROUP, G - grp * BAR_GROUP);
         const unsigned long long old =
             __hip_atomic_fetch_add(P.bar + BAR_STRIDE * (1 + grp), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (old + 1 == epoch * (unsigned long long)gsize)
             __hip_atomic_fetch_add(P.bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Between arrive and wait a wave may issue loads that do not depend on other workgroups (the next
+// phase's weights); the closing workgroup barrier orders LDS only, so those loads stay in flight.
+__device__ __forceinline__ void grid_wait(const FusedParams &P, unsigned long long epoch) {
+    if (threadIdx.x == 0) {
+        const int ngrp = (gridDim.x + BAR_GROUP - 1) / BAR_GROUP;
         unsigned spins = 0;
         bool give_up = __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
         while (!give_up && __hip_atomic_load(P.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch * (unsigned long long)ngrp) {
@@ -138,7 +162,7 @@ __device__ __forceinline__ void grid_barrier(const FusedParams &P, unsigned long
         // barrier is read with ordinary, L2-cached loads afterwards
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
-    __syncthreads();
+    lds_sync();
 }
 
 // ------------------------------------------------------------------------------------ helpers
@@ -162,28 +186,47 @@ __device__ __forceinline__ void split4(const float *v, u32x2 &hi, u32x2 &lo) {
 
 // ------------------------------------------------------------------------------------- phases
 
-// h[r] = E[token[r]] and the rotary table of this call's positions
-__device__ void phase_embed(const FusedParams &P, int wg, int nwg) {
-    const size_t gtid = (size_t)wg * FUSED_THREADS + threadIdx.x, gsz = (size_t)nwg * FUSED_THREADS;
+// Residual-stream tile hand-over used by the embedding and by the residual epilogues: lane (t, g) holds
+// 4 consecutive features of row t of 16-feature tile T.  Writes h, the next GEMM's input h*gain as two
+// bf16 planes, and the tile's sum of squares per row.
+__device__ __forceinline__ void publish_h_tile(const FusedParams &P, const float *__restrict__ gain, int T, int t, int g,
+                                               f32x4 hv, bool valid) {
     const __amdgpu_buffer_rsrc_t rh = co_rsrc(P.h, sizeof(float) * (size_t)P.M * P.d);
-    const __amdgpu_buffer_rsrc_t rc = co_rsrc(P.cs, sizeof(float) * (size_t)P.M * P.dh);
-    const int d8 = P.d / 8;
-    for (size_t c = gtid; c < (size_t)P.M * d8; c += gsz) {
-        const int r = (int)(c / d8), x8 = (int)(c % d8);
-        const int tok = P.tokens[r];
-        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const __amdgpu_buffer_rsrc_t rg = co_rsrc(P.hg, 2 * (P.hg_plane * 2));
+    const __amdgpu_buffer_rsrc_t rs = co_rsrc(P.ssq, sizeof(float) * (size_t)(P.d / 16) * 16);
+    float ss = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (!valid) return;
+    const int col = T * 16 + 4 * g;
+    const f32x4 gv = *reinterpret_cast<const f32x4 *>(gain + col);
+    co_st128f(rh, (int)(((size_t)t * P.d + col) * 4), hv);
+    float v[4] = {hv[0] * gv[0], hv[1] * gv[1], hv[2] * gv[2], hv[3] * gv[3]};
+    u32x2 hi, lo;
+    split4(v, hi, lo);
+    const int off = (int)(((size_t)t * P.d + col) * 2);
+    co_st64(rg, off, hi);
+    co_st64(rg, off + (int)(P.hg_plane * 2), lo);
+    if (g == 0) co_st32f(rs, (int)(((size_t)t * (P.d / 16) + T) * 4), ss);
+}
+
+// h[r] = E[token[r]] (published as above for the first QKV) and the rotary table of this call's positions
+__device__ void phase_embed(const FusedParams &P, int wg, int nwg) {
+    const int lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
+    const int gw = wg * FUSED_WAVES + (threadIdx.x >> 6), nw = nwg * FUSED_WAVES;
+    const bool valid = t < P.M;
+    const int tok = valid ? P.tokens[t] : -1;
+    for (int T = gw; T < P.d / 16; T += nw) {         // one wave per 16-feature tile, all rows
+        f32x4 hv = f32x4{0.f, 0.f, 0.f, 0.f};
         if (tok >= 0 && tok < P.V) {
-            const u32x4 e = *reinterpret_cast<const u32x4 *>(P.embed + (size_t)tok * P.d + x8 * 8);
-#pragma unroll
-            for (int w = 0; w < 4; w++) {
-                v[2 * w] = __uint_as_float(e[w] << 16);
-                v[2 * w + 1] = __uint_as_float(e[w] & 0xFFFF0000u);
-            }
+            const u32x2 e = *reinterpret_cast<const u32x2 *>(P.embed + (size_t)tok * P.d + T * 16 + 4 * g);
+            hv = f32x4{__uint_as_float(e[0] << 16), __uint_as_float(e[0] & 0xFFFF0000u), __uint_as_float(e[1] << 16),
+                       __uint_as_float(e[1] & 0xFFFF0000u)};
         }
-        const int off = (int)(((size_t)r * P.d + x8 * 8) * 4);
-        co_st128f(rh, off, f32x4{v[0], v[1], v[2], v[3]});
-        co_st128f(rh, off + 16, f32x4{v[4], v[5], v[6], v[7]});
+        publish_h_tile(P, P.layers[0].attn_norm, T, t, g, hv, valid);
     }
+    const __amdgpu_buffer_rsrc_t rc = co_rsrc(P.cs, sizeof(float) * (size_t)P.M * P.dh);
+    const size_t gtid = (size_t)wg * FUSED_THREADS + threadIdx.x, gsz = (size_t)nwg * FUSED_THREADS;
     const int half = P.dh / 2;
     for (size_t c = gtid; c < (size_t)P.M * half; c += gsz) {
         const int r = (int)(c / half), x = (int)(c % half);
@@ -194,92 +237,24 @@ __device__ void phase_embed(const FusedParams &P, int wg, int nwg) {
     }
 }
 
-// rmsnorm(h) * gain for all M rows into LDS as fragment-ordered hi/lo planes:
-// 16-byte unit ((ks*2 + plane)*4 + g)*M + row holds k = 32 ks + 8 g .. +7 of that row.
-// One round trip to memory: the fp32 chunk of 8 values is parked in the very two units that later
-// receive its hi and lo halves, row sums are taken from LDS, then each thread converts its own units.
-__device__ void norm_to_lds(const FusedParams &P, const float *__restrict__ gain, char *smem) {
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int M = P.M, d = P.d, d8 = d / 8;
-    float *rstd = reinterpret_cast<float *>(smem + P.lds_rstd_off);
-    f32x4 *act = reinterpret_cast<f32x4 *>(smem);
-    for (int kc = tid; kc < d8; kc += FUSED_THREADS) {
-        const int ks = kc >> 2, g = kc & 3;
-        for (int r0 = 0; r0 < M; r0 += 4) {
-            f32x4 a[4][2];
-#pragma unroll
-            for (int u = 0; u < 4; u++)
-                if (r0 + u < M) {
-                    a[u][0] = *reinterpret_cast<const f32x4 *>(P.h + (size_t)(r0 + u) * d + kc * 8);
-                    a[u][1] = *reinterpret_cast<const f32x4 *>(P.h + (size_t)(r0 + u) * d + kc * 8 + 4);
-                }
-#pragma unroll
-            for (int u = 0; u < 4; u++)
-                if (r0 + u < M) {
-                    act[((ks * 2 + 0) * 4 + g) * M + r0 + u] = a[u][0];
-                    act[((ks * 2 + 1) * 4 + g) * M + r0 + u] = a[u][1];
-                }
-        }
-    }
-    __syncthreads();
-    for (int r = w; r < M; r += FUSED_WAVES) {
-        float ss = 0.f;
-#pragma unroll 4
-        for (int u = lane; u < d8 * 2; u += 64) {          // unit (kc, plane) of row r
-            const int kc = u >> 1, pl = u & 1, ks = kc >> 2, g = kc & 3;
-            const f32x4 v = act[((ks * 2 + pl) * 4 + g) * M + r];
-            ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-        }
-        ss = wave_sum(ss);
-        if (lane == 0) rstd[r] = rsqrtf(ss / (float)d + P.eps);
-    }
-    __syncthreads();
-    for (int kc = tid; kc < d8; kc += FUSED_THREADS) {
-        const int ks = kc >> 2, g = kc & 3;
-        const f32x4 g0 = *reinterpret_cast<const f32x4 *>(gain + kc * 8);
-        const f32x4 g1 = *reinterpret_cast<const f32x4 *>(gain + kc * 8 + 4);
-#pragma unroll 2
-        for (int r = 0; r < M; r++) {
-            const float rs = rstd[r];
-            const int u0 = ((ks * 2 + 0) * 4 + g) * M + r, u1 = ((ks * 2 + 1) * 4 + g) * M + r;
-            const f32x4 a0 = act[u0], a1 = act[u1];
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                v[j] = a0[j] * rs * g0[j];
-                v[4 + j] = a1[j] * rs * g1[j];
-            }
-            u32x4 hi, lo;
-            split8(v, hi, lo);
-            act[u0] = __builtin_bit_cast(f32x4, hi);
-            act[u1] = __builtin_bit_cast(f32x4, lo);
-        }
-    }
-    __syncthreads();
-}
-
 struct GemmArgs {
     const u32x4 *Wp;       // tiles [n_tiles][KS][64]
     int KS, n_items;       // k-steps of 32; work items (groups of TG tiles)
-    const bf16_t *bsrc;    // B operand rows in global memory (two planes) when not from LDS
+    const bf16_t *bsrc;    // B operand rows [M][ldb] in global memory, two planes
     size_t bplane;
     int ldb;
-    const float *gain;     // norm gain for the LDS prologue
+    bool scaled;           // the input is h*gain: multiply output rows by rstd
+    const float *next_gain;   // residual epilogue: gain of the norm that follows
     int layer;
 };
 
 template <int TG, int EPI>
-__device__ __forceinline__ void gemm_epilogue(const FusedParams &P, const GemmArgs &A, int item, int j, f32x4 v, int lane) {
+__device__ __forceinline__ void gemm_epilogue(const FusedParams &P, const GemmArgs &A, int item, int j, f32x4 v, int lane,
+                                              f32x4 hcur) {
     const int t = lane & 15, g = lane >> 4;
     const int T = item * TG + j;     // global tile index
     if (EPI == EPI_RESID) {
-        const __amdgpu_buffer_rsrc_t rh = co_rsrc(P.h, sizeof(float) * (size_t)P.M * P.d);
-        if (t < P.M) {
-            const int off = (int)(((size_t)t * P.d + T * 16 + 4 * g) * 4);
-            f32x4 cur = *reinterpret_cast<const f32x4 *>(P.h + (size_t)t * P.d + T * 16 + 4 * g);
-            cur += v;
-            co_st128f(rh, off, cur);
-        }
+        publish_h_tile(P, A.next_gain, T, t, g, hcur + v, t < P.M);
     } else if (EPI == EPI_LOGITS) {
         if (t < P.M) *reinterpret_cast<f32x4 *>(P.logits + (size_t)t * P.V + T * 16 + 4 * g) = v;
     } else if (EPI == EPI_QKV) {
@@ -314,8 +289,8 @@ __device__ __forceinline__ void gemm_epilogue(const FusedParams &P, const GemmAr
                     co_st64(rq, off + (int)(P.q_plane * 2), lo);
                 } else if (pos >= 0 && pos < P.seq_pad) {
                     u32x2 kk;
-                    kk[0] = (uint32_t)f32_to_bf16(out[0]) | ((uint32_t)f32_to_bf16(out[1]) << 16);
-                    kk[1] = (uint32_t)f32_to_bf16(out[2]) | ((uint32_t)f32_to_bf16(out[3]) << 16);
+                    kk[0] = pack_bf16x2(out[0], out[1]);
+                    kk[1] = pack_bf16x2(out[2], out[3]);
                     const __amdgpu_buffer_rsrc_t rk = co_rsrc(P.kv + kv_k_off(geo, A.layer, b, head), head_bytes);
                     co_st64(rk, (int)(((size_t)pos * P.dh + p0) * 2), kk);
                 }
@@ -329,93 +304,241 @@ __device__ __forceinline__ void gemm_epilogue(const FusedParams &P, const GemmAr
     }
 }
 
-// One weight-streaming GEMM phase.  B_LDS: the B operand (activations) sits in LDS (after norm_to_lds),
-// otherwise it is read from the two global planes at A.bsrc.
-template <int TG, int EPI, bool B_LDS, int U>
-__device__ void gemm_phase(const FusedParams &P, const GemmArgs &A, char *smem, int wg, int nwg) {
+// Copy the two planes of a row-major activation buffer [M][ld] into LDS in fragment order:
+// 16-byte unit ((ks*2 + plane)*4 + g)*M + row holds k = 32 ks + 8 g .. +7 of that row.
+__device__ __forceinline__ void copy_to_lds(const FusedParams &P, const bf16_t *__restrict__ src, size_t plane, int ld,
+                                            char *smem) {
+    const int tid = threadIdx.x, M = P.M, ld8 = ld / 8;
+    u32x4 *act = reinterpret_cast<u32x4 *>(smem);
+    for (int kc = tid; kc < ld8; kc += FUSED_THREADS) {
+        const int ks = kc >> 2, g = kc & 3;
+        for (int r0 = 0; r0 < M; r0 += 4) {
+            u32x4 a[4][2];
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                if (r0 + u < M) {
+                    const bf16_t *sp = src + (size_t)(r0 + u) * ld + kc * 8;
+                    a[u][0] = *reinterpret_cast<const u32x4 *>(sp);
+                    a[u][1] = *reinterpret_cast<const u32x4 *>(sp + plane);
+                }
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                if (r0 + u < M) {
+                    act[((ks * 2 + 0) * 4 + g) * M + r0 + u] = a[u][0];
+                    act[((ks * 2 + 1) * 4 + g) * M + r0 + u] = a[u][1];
+                }
+        }
+    }
+}
+
+#define W_RING 32   /* 16-byte fragments per lane held by the weight ring: 32 KB per wave, 256 KB per CU */
+
+// Wave 0 of a workgroup is its service wave: it signals and polls the device-wide barrier, computes
+// the row scales, and applies the reduction + epilogue of each work item while the other seven waves
+// already stream the next item.  Loads return in order, so a wave with a weight burst in flight would
+// see its barrier polls delayed by the whole burst; the service wave never streams weights.
+#define STREAM_WAVES (FUSED_WAVES - 1)
+
+// The weight stream of one streaming wave.  It owns the K slice [ks0, ks1) of every work item its
+// workgroup takes (item = wg, wg + nwg, ...).  The slice is cut into batches of U k-steps x TG tiles;
+// batch n of the wave is batch n % nbpi of its item n / nbpi.  NW batches live in a register ring; the
+// loads of batch n + NW are issued right after batch n has been multiplied, so the stream runs ahead
+// across item boundaries, and the first NW batches of a phase are issued before the device-wide
+// barrier that precedes it (they depend on nothing but the weights).
+template <int TG, int U, int NW>
+struct WStream {
+    const u32x4 *Wp;
+    int KS, n_items, wg, nwg, ks0, ks1, nbpi, lane;
+    __device__ __forceinline__ void init(const u32x4 *Wp_, int KS_, int n_items_, int wg_, int nwg_) {
+        Wp = Wp_;
+        KS = KS_;
+        n_items = n_items_;
+        wg = wg_;
+        nwg = nwg_;
+        lane = threadIdx.x & 63;
+        const int sw = (int)(threadIdx.x >> 6) - 1;           // streaming wave index; -1 for the service wave
+        ks0 = sw < 0 ? 0 : KS * sw / STREAM_WAVES;
+        ks1 = sw < 0 ? 0 : KS * (sw + 1) / STREAM_WAVES;
+        const int nb_max = ((KS + STREAM_WAVES - 1) / STREAM_WAVES + U - 1) / U;   // same for every wave
+        nbpi = (nb_max + NW - 1) / NW * NW;      // padded: the ring turns a whole number of times per item
+        if (nbpi == 0) nbpi = NW;
+    }
+    // load cursor: the next batch to issue is batch l_b of item l_item
+    int l_item, l_b;
+    __device__ __forceinline__ void rewind() {
+        l_item = wg;
+        l_b = 0;
+    }
+    // after the first NW batches have been issued (by prefetch(), possibly before the barrier)
+    __device__ __forceinline__ void skip_prefetched() {
+        l_item = NW == nbpi ? wg + nwg : wg;
+        l_b = NW == nbpi ? 0 : NW;
+    }
+    // issue the loads of the cursor's batch into ring slot `slot` (a constant once the caller's loop is
+    // unrolled) and advance the cursor
+    __device__ __forceinline__ void load_next(u32x4 (&W)[W_RING], int slot) {
+        const int item = l_item, ks = ks0 + l_b * U;
+        if (++l_b == nbpi) {
+            l_b = 0;
+            l_item += nwg;
+        }
+        if (item >= n_items) return;             // stream exhausted (uniform)
+        const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < U; u++)
+#pragma unroll
+            for (int j = 0; j < TG; j++)
+                W[(slot * U + u) * TG + j] =
+                    (ks + u < ks1) ? __builtin_nontemporal_load(Wp + ((size_t)(item * TG + j) * KS + ks + u) * 64 + lane) : zero;
+    }
+    __device__ __forceinline__ void prefetch(u32x4 (&W)[W_RING]) {
+        rewind();
+#pragma unroll
+        for (int s = 0; s < NW; s++) load_next(W, s);
+    }
+};
+
+// One weight-streaming GEMM phase.
+// B_LDS: the activation rows (two bf16 planes) are first copied into LDS in fragment order and the
+// whole register ring holds weights.  Otherwise (K too long for LDS) the activations come from L2
+// through a two-batch ring that takes the upper half of the registers.
+// `prefetched`: the first NW weight batches were already issued into W before the barrier.
+template <int TG, int EPI, bool B_LDS, int U, int NW>
+__device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs &A, char *smem, int wg, int nwg,
+                                           u32x4 (&W)[W_RING], bool prefetched) {
+    static_assert(NW * U * TG <= (B_LDS ? W_RING : W_RING / 2), "weight ring does not fit");
+    static_assert(B_LDS || 4 * U <= W_RING / 2, "activation ring does not fit");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const bool service = w == 0;
+    const int sw = w - 1;
     const int t = lane & 15, g = lane >> 4;
-    const int M = P.M, KS = A.KS;
+    const int M = P.M;
     const u32x4 *lds_act = reinterpret_cast<const u32x4 *>(smem);
-    f32x4 *red = reinterpret_cast<f32x4 *>(smem + P.lds_red_off);
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem + P.lds_red_off);      // [2 buffers][7 waves][TG][64 lanes]
+    constexpr int RED_BUF = STREAM_WAVES * 3 * 64;
     if (wg >= A.n_items) return;      // whole workgroup idle in this phase (uniform)
-    if (B_LDS) norm_to_lds(P, A.gain, smem);
-    ts_mark(P, TS_PROLOGUE);
-    const int ks0 = KS * w / FUSED_WAVES, ks1 = KS * (w + 1) / FUSED_WAVES;
+    WStream<TG, U, NW> ws;
+    ws.init(A.Wp, A.KS, A.n_items, wg, nwg);
     const bool valid = t < M;
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    const u32x4 *bp = B_LDS ? nullptr : reinterpret_cast<const u32x4 *>(A.bsrc + (size_t)(valid ? t : 0) * A.ldb + 8 * g);
+    const u32x4 *bp = reinterpret_cast<const u32x4 *>(A.bsrc + (size_t)(valid ? t : 0) * A.ldb + 8 * g);
     const size_t bplane16 = A.bplane / 8;
+    constexpr int BQ = W_RING / 2;    // activation ring lives in W[BQ ..]: slot*2U + 2u + plane
 
-    for (int item = wg; item < A.n_items; item += nwg) {
-        f32x4 acc[TG];
-        const u32x4 *wp[TG];
-#pragma unroll
-        for (int j = 0; j < TG; j++) {
-            acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            wp[j] = A.Wp + ((size_t)(item * TG + j) * KS) * 64 + lane;
-        }
-        u32x4 wa[U][TG], wb[U][TG], ba[U][2], bb[U][2];
-
-#define FUSED_LOAD(WF, BF, KS_AT)                                                                   \
-    _Pragma("unroll") for (int u = 0; u < U; u++) {                                                 \
-        const int ksu_ = (KS_AT) + u;                                                               \
-        const bool in_ = ksu_ < ks1;                                                                \
-        _Pragma("unroll") for (int j = 0; j < TG; j++)                                              \
-            WF[u][j] = in_ ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero;          \
-        if (!B_LDS) {                                                                               \
-            BF[u][0] = (in_ && valid) ? bp[(size_t)ksu_ * 4] : zero;                                \
-            BF[u][1] = (in_ && valid) ? bp[(size_t)ksu_ * 4 + bplane16] : zero;                     \
+#define FUSED_LOAD_B(SLOT, BATCH)   /* BATCH >= nbpi: the next item, same K slice */                \
+    if (!B_LDS) {                                                                                   \
+        const int bq_ = (BATCH) >= ws.nbpi ? (BATCH) - ws.nbpi : (BATCH);                           \
+        const int ksb_ = ws.ks0 + bq_ * U;                                                          \
+        _Pragma("unroll") for (int u = 0; u < U; u++) {                                             \
+            const bool in_ = valid && ksb_ + u < ws.ks1;                                            \
+            W[BQ + ((SLOT) * U + u) * 2 + 0] = in_ ? bp[(size_t)(ksb_ + u) * 4] : zero;             \
+            W[BQ + ((SLOT) * U + u) * 2 + 1] = in_ ? bp[(size_t)(ksb_ + u) * 4 + bplane16] : zero;  \
         }                                                                                           \
     }
-#define FUSED_MMA(WF, BF, KS_AT)                                                                    \
-    _Pragma("unroll") for (int u = 0; u < U; u++) {                                                 \
-        const int ksu_ = (KS_AT) + u;                                                               \
-        u32x4 bh_ = zero, bl_ = zero;                                                               \
-        if (B_LDS) {                                                                                \
-            if (valid && ksu_ < ks1) {                                                              \
-                bh_ = lds_act[((ksu_ * 2 + 0) * 4 + g) * M + t];                                    \
-                bl_ = lds_act[((ksu_ * 2 + 1) * 4 + g) * M + t];                                    \
+#define FUSED_MMA(SLOT, BSLOT, BATCH)                                                               \
+    {                                                                                               \
+        const int ksm_ = ws.ks0 + __builtin_amdgcn_readfirstlane(BATCH) * U;                        \
+        _Pragma("unroll") for (int u = 0; u < U; u++) {                                             \
+            u32x4 bh_ = zero, bl_ = zero;                                                           \
+            if (B_LDS) {                                                                            \
+                if (valid && ksm_ + u < ws.ks1) {                                                   \
+                    bh_ = lds_act[(((ksm_ + u) * 2 + 0) * 4 + g) * M + t];                          \
+                    bl_ = lds_act[(((ksm_ + u) * 2 + 1) * 4 + g) * M + t];                          \
+                }                                                                                   \
+            } else {                                                                                \
+                bh_ = W[BQ + ((BSLOT) * U + u) * 2 + 0];                                            \
+                bl_ = W[BQ + ((BSLOT) * U + u) * 2 + 1];                                            \
             }                                                                                       \
-        } else {                                                                                    \
-            bh_ = BF[u][0];                                                                         \
-            bl_ = BF[u][1];                                                                         \
-        }                                                                                           \
-        _Pragma("unroll") for (int j = 0; j < TG; j++) {                                            \
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, WF[u][j]),  \
-                                                             __builtin_bit_cast(bf16x8, bh_), acc[j], 0, 0, 0); \
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, WF[u][j]),  \
-                                                             __builtin_bit_cast(bf16x8, bl_), acc[j], 0, 0, 0); \
+            _Pragma("unroll") for (int j = 0; j < TG; j++) {                                        \
+                const bf16x8 wf_ = __builtin_bit_cast(bf16x8, W[((SLOT) * U + u) * TG + j]);        \
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf_, __builtin_bit_cast(bf16x8, bh_), acc[j], 0, 0, 0); \
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf_, __builtin_bit_cast(bf16x8, bl_), acc[j], 0, 0, 0); \
+            }                                                                                       \
         }                                                                                           \
     }
 
-        FUSED_LOAD(wa, ba, ks0)
-        for (int ks = ks0; ks < ks1; ks += 2 * U) {
-            FUSED_LOAD(wb, bb, ks + U)
-            FUSED_MMA(wa, ba, ks)
-            FUSED_LOAD(wa, ba, ks + 2 * U)
-            FUSED_MMA(wb, bb, ks + U)
+    if (B_LDS) {
+        copy_to_lds(P, A.bsrc, A.bplane, A.ldb, smem);
+        if (!prefetched && !service) ws.prefetch(W);
+    } else if (!service) {
+        FUSED_LOAD_B(0, 0)
+        FUSED_LOAD_B(1, 1)
+        if (!prefetched) ws.prefetch(W);
+    }
+    ws.skip_prefetched();
+    // service wave: the first item's residual tiles (they do not change during the phase) and the row scales
+    f32x4 hfirst[TG];
+#pragma unroll
+    for (int j = 0; j < TG; j++) hfirst[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (service) {
+        if (EPI == EPI_RESID && valid) {
+#pragma unroll
+            for (int j = 0; j < TG; j++)
+                hfirst[j] = *reinterpret_cast<const f32x4 *>(P.h + (size_t)t * P.d + (wg * TG + j) * 16 + 4 * g);
         }
-#undef FUSED_LOAD
-#undef FUSED_MMA
-
-        if (item + nwg >= A.n_items) ts_mark(P, TS_LOOP);
-        // fixed-order reduction of the 8 K slices through LDS, then one wave per tile applies the epilogue
+    }
+    if (B_LDS) lds_sync();
+    // row scale of this lane's row (service wave only; needed at the first epilogue, so it overlaps the
+    // streaming): rstd = 1/sqrt(sum of the per-tile sums of squares / d + eps); lane group g adds tiles
+    // g, g+4, ... in a fixed order, 16 loads in flight at a time
+    float rs_row = 1.0f;
+    if (service && A.scaled) {
+        // ssq is [row][tile]; lane group g adds tiles [g*per, (g+1)*per) of row t, four at a time, in order
+        const int nt = P.d / 16, per = nt / 4;
+        const f32x4 *sp = reinterpret_cast<const f32x4 *>(P.ssq + (size_t)t * nt + g * per);
+        float ss = 0.f;
+        for (int c0 = 0; c0 < per / 4; c0 += 16) {
+            f32x4 v[16];
 #pragma unroll
-        for (int j = 0; j < TG; j++) red[(w * TG + j) * 64 + lane] = acc[j];
-        __syncthreads();
-        if (EPI == EPI_SWIGLU) {
-            if (w == 0) {                         // TG == 2: tile 0 = gate, tile 1 = up, same 16 features
-                f32x4 gsum = red[lane], usum = red[64 + lane];
+            for (int u = 0; u < 16; u++) v[u] = (valid && c0 + u < per / 4) ? sp[c0 + u] : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ww = 1; ww < FUSED_WAVES; ww++) {
-                    gsum += red[(ww * TG) * 64 + lane];
-                    usum += red[(ww * TG + 1) * 64 + lane];
+            for (int u = 0; u < 16; u++) ss += (v[u][0] + v[u][1]) + (v[u][2] + v[u][3]);
+        }
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        rs_row = rsqrtf(ss / (float)P.d + P.eps);
+    }
+    ts_mark(P, TS_PROLOGUE);
+    int parity = 0;
+#pragma unroll 1
+    for (int item = wg; item < A.n_items; item += nwg, parity ^= 1) {
+        f32x4 *rb = red + parity * RED_BUF;
+        if (!service) {
+            f32x4 acc[TG];
+#pragma unroll
+            for (int j = 0; j < TG; j++) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+            for (int bb = 0; bb < ws.nbpi; bb += NW) {
+#pragma unroll
+                for (int sl = 0; sl < NW; sl++) {
+                    FUSED_MMA(sl, sl & 1, bb + sl)
+                    ws.load_next(W, sl);
+                    FUSED_LOAD_B(sl & 1, bb + sl + 2)
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < TG; j++) rb[(sw * TG + j) * 64 + lane] = acc[j];
+        }
+        // partial sums of this item are in red[parity]; the streaming waves go straight on to the next item
+        // (which uses the other buffer) while the service wave reduces in a fixed order and applies the epilogue
+        lds_sync();
+        if (service) {
+            if (item + nwg >= A.n_items) ts_mark(P, TS_LOOP);
+            const float rs = rs_row;
+            if (EPI == EPI_SWIGLU) {              // TG == 2: tile 0 = gate, tile 1 = up, same 16 features
+                f32x4 gsum = rb[lane], usum = rb[64 + lane];
+#pragma unroll
+                for (int ww = 1; ww < STREAM_WAVES; ww++) {
+                    gsum += rb[(ww * TG) * 64 + lane];
+                    usum += rb[(ww * TG + 1) * 64 + lane];
                 }
                 if (valid) {
                     float f[4];
 #pragma unroll
-                    for (int r = 0; r < 4; r++) f[r] = gsum[r] / (1.0f + expf(-gsum[r])) * usum[r];
+                    for (int r = 0; r < 4; r++) {
+                        const float gg = gsum[r] * rs;
+                        f[r] = gg / (1.0f + expf(-gg)) * (usum[r] * rs);
+                    }
                     u32x2 hi, lo;
                     split4(f, hi, lo);
                     const __amdgpu_buffer_rsrc_t rf = co_rsrc(P.act, 2 * (P.act_plane * 2));
@@ -423,15 +546,23 @@ __device__ void gemm_phase(const FusedParams &P, const GemmArgs &A, char *smem, 
                     co_st64(rf, off, hi);
                     co_st64(rf, off + (int)(P.act_plane * 2), lo);
                 }
-            }
-        } else if (w < TG) {
-            f32x4 sum = red[w * 64 + lane];
+            } else {
 #pragma unroll
-            for (int ww = 1; ww < FUSED_WAVES; ww++) sum += red[(ww * TG + w) * 64 + lane];
-            gemm_epilogue<TG, EPI>(P, A, item, w, sum, lane);
+                for (int j = 0; j < TG; j++) {
+                    f32x4 sum = rb[j * 64 + lane];
+#pragma unroll
+                    for (int ww = 1; ww < STREAM_WAVES; ww++) sum += rb[(ww * TG + j) * 64 + lane];
+                    sum *= rs;
+                    f32x4 hcur = hfirst[j];
+                    if (EPI == EPI_RESID && item != wg && valid)
+                        hcur = *reinterpret_cast<const f32x4 *>(P.h + (size_t)t * P.d + (item * TG + j) * 16 + 4 * g);
+                    gemm_epilogue<TG, EPI>(P, A, item, j, sum, lane, hcur);
+                }
+            }
         }
-        __syncthreads();
     }
+#undef FUSED_LOAD_B
+#undef FUSED_MMA
 }
 
 // Block attention for one 16-row tile per sequence (m <= 16).
@@ -610,64 +741,116 @@ __device__ void phase_trace(const FusedParams &P, int slot, int wg, int nwg) {
         P.trace[(size_t)slot * n + i] = P.h[i];
 }
 
-template <int DH>
-__device__ void run_phase(const FusedParams &P, int phase, int layer, char *smem, int wg, int nwg) {
+// Per-phase GEMM shapes: TG tiles per item, U k-steps per batch, NW batches in the register ring.
+#define QKV3 3, EPI_QKV, true, 2, 5
+#define QKV1 1, EPI_QKV, true, 4, 8
+#define OPRJ 1, EPI_RESID, true, 4, 8
+#define GUPR 2, EPI_SWIGLU, true, 4, 4
+#define DOWN 1, EPI_RESID, false, 4, 4
+#define LMH2 2, EPI_LOGITS, true, 4, 4
+#define LMH1 1, EPI_LOGITS, true, 4, 8
+
+__device__ __forceinline__ GemmArgs gemm_args(const FusedParams &P, int phase, int layer) {
     GemmArgs A;
     A.layer = layer;
-    A.gain = nullptr;
-    A.bsrc = nullptr;
-    A.bplane = 0;
-    A.ldb = 0;
-    if (phase == PH_EMBED) {
-        phase_embed(P, wg, nwg);
-    } else if (phase == PH_QKV) {
-        const FusedLayer lw = P.layers[layer];
-        A.Wp = lw.qkv;
+    A.next_gain = nullptr;
+    A.scaled = false;
+    A.bsrc = P.hg;          // h * gain: input of the projections that follow a norm
+    A.bplane = P.hg_plane;
+    A.ldb = P.d;
+    A.Wp = nullptr;
+    A.KS = 0;
+    A.n_items = 0;
+    if (phase == PH_QKV) {
+        A.Wp = P.layers[layer].qkv;
         A.KS = P.d / 32;
-        A.gain = lw.attn_norm;
+        A.scaled = true;
         A.n_items = (3 * P.hd / 16) / P.tg_qkv;
-        if (P.tg_qkv == 3)
-            gemm_phase<3, EPI_QKV, true, 2>(P, A, smem, wg, nwg);
-        else
-            gemm_phase<1, EPI_QKV, true, 8>(P, A, smem, wg, nwg);
-    } else if (phase == PH_ATTN) {
-        phase_attn<DH>(P, layer, smem, wg, nwg);
     } else if (phase == PH_O) {
-        const FusedLayer lw = P.layers[layer];
-        A.Wp = lw.o;
+        A.Wp = P.layers[layer].o;
         A.KS = P.hd / 32;
         A.n_items = P.d / 16;
         A.bsrc = P.act;
         A.bplane = P.act_plane;
         A.ldb = P.hd;
-        gemm_phase<1, EPI_RESID, false, 4>(P, A, smem, wg, nwg);
+        A.next_gain = P.layers[layer].ffn_norm;
     } else if (phase == PH_GU) {
-        const FusedLayer lw = P.layers[layer];
-        A.Wp = lw.gu;
+        A.Wp = P.layers[layer].gu;
         A.KS = P.d / 32;
-        A.gain = lw.ffn_norm;
+        A.scaled = true;
         A.n_items = P.F / 16;
-        gemm_phase<2, EPI_SWIGLU, true, 4>(P, A, smem, wg, nwg);
     } else if (phase == PH_DOWN) {
-        const FusedLayer lw = P.layers[layer];
-        A.Wp = lw.down;
+        A.Wp = P.layers[layer].down;
         A.KS = P.F / 32;
         A.n_items = P.d / 16;
         A.bsrc = P.act;
         A.bplane = P.act_plane;
         A.ldb = P.F;
-        gemm_phase<1, EPI_RESID, false, 4>(P, A, smem, wg, nwg);
+        A.next_gain = layer + 1 < P.L ? P.layers[layer + 1].attn_norm : P.final_norm;
     } else if (phase == PH_LM) {
         A.Wp = P.lm;
         A.KS = P.d / 32;
-        A.gain = P.final_norm;
+        A.scaled = true;
         A.n_items = (P.V / 16) / P.tg_lm;
-        if (P.tg_lm == 2)
-            gemm_phase<2, EPI_LOGITS, true, 4>(P, A, smem, wg, nwg);
-        else
-            gemm_phase<1, EPI_LOGITS, true, 8>(P, A, smem, wg, nwg);
+    }
+    return A;
+}
+
+// issue the first weight batches of a GEMM phase (nothing for the other phases)
+__device__ __forceinline__ void prefetch_phase(const FusedParams &P, int phase, int layer, int wg, int nwg, u32x4 (&W)[W_RING]) {
+    if (phase != PH_QKV && phase != PH_O && phase != PH_GU && phase != PH_DOWN && phase != PH_LM) return;
+    const GemmArgs A = gemm_args(P, phase, layer);
+    if (wg >= A.n_items || threadIdx.x < 64) return;     // wave 0 polls the barrier: see gemm_phase
+#define FUSED_PF(SHAPE) FUSED_PF_I(SHAPE)
+#define FUSED_PF_I(TGv, EPIv, BLv, Uv, NWv)                  \
+    {                                                        \
+        WStream<TGv, Uv, NWv> ws;                            \
+        ws.init(A.Wp, A.KS, A.n_items, wg, nwg);             \
+        ws.prefetch(W);                                      \
+    }
+    if (phase == PH_QKV) {
+        if (P.tg_qkv == 3) FUSED_PF(QKV3) else FUSED_PF(QKV1)
+    } else if (phase == PH_O) {
+        FUSED_PF(OPRJ)
+    } else if (phase == PH_GU) {
+        FUSED_PF(GUPR)
+    } else if (phase == PH_DOWN) {
+        FUSED_PF(DOWN)
+    } else {
+        if (P.tg_lm == 2) FUSED_PF(LMH2) else FUSED_PF(LMH1)
+    }
+#undef FUSED_PF
+#undef FUSED_PF_I
+}
+
+template <int DH>
+__device__ __forceinline__ void run_phase(const FusedParams &P, int phase, int layer, char *smem, int wg, int nwg, u32x4 (&W)[W_RING],
+                          bool prefetched) {
+    if (phase == PH_EMBED) {
+        phase_embed(P, wg, nwg);
+    } else if (phase == PH_ATTN) {
+        phase_attn<DH>(P, layer, smem, wg, nwg);
     } else if (phase == PH_TRACE) {
         phase_trace(P, layer, wg, nwg);
+    } else {
+        const GemmArgs A = gemm_args(P, phase, layer);
+        if (phase == PH_QKV) {
+            if (P.tg_qkv == 3)
+                gemm_phase<QKV3>(P, A, smem, wg, nwg, W, prefetched);
+            else
+                gemm_phase<QKV1>(P, A, smem, wg, nwg, W, prefetched);
+        } else if (phase == PH_O) {
+            gemm_phase<OPRJ>(P, A, smem, wg, nwg, W, prefetched);
+        } else if (phase == PH_GU) {
+            gemm_phase<GUPR>(P, A, smem, wg, nwg, W, prefetched);
+        } else if (phase == PH_DOWN) {
+            gemm_phase<DOWN>(P, A, smem, wg, nwg, W, prefetched);
+        } else if (phase == PH_LM) {
+            if (P.tg_lm == 2)
+                gemm_phase<LMH2>(P, A, smem, wg, nwg, W, prefetched);
+            else
+                gemm_phase<LMH1>(P, A, smem, wg, nwg, W, prefetched);
+        }
     }
 }
 
@@ -675,7 +858,8 @@ __device__ void run_phase(const FusedParams &P, int phase, int layer, char *smem
 template <int DH>
 __global__ __launch_bounds__(FUSED_THREADS, 1) void k_fused_phase(FusedParams P, int phase, int layer) {
     extern __shared__ __align__(16) char smem[];
-    run_phase<DH>(P, phase, layer, smem, blockIdx.x, gridDim.x);
+    u32x4 W[W_RING];
+    run_phase<DH>(P, phase, layer, smem, blockIdx.x, gridDim.x, W, false);
 }
 
 // the whole forward in one launch
@@ -684,27 +868,41 @@ __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(FusedPar
     extern __shared__ __align__(16) char smem[];
     const int wg = blockIdx.x, nwg = gridDim.x;
     unsigned long long epoch = P.bar_base;   // device-wide barriers completed before this launch
+    u32x4 W[W_RING];                             // weight ring, carried across phases
     P.ts_slot = 0;
-#define FUSED_STEP(PHASE, LAYER)                      \
-    ts_mark(P, TS_START);                             \
-    run_phase<DH>(P, PHASE, LAYER, smem, wg, nwg);    \
-    ts_mark(P, TS_EPILOGUE);                          \
-    grid_barrier(P, ++epoch);                         \
-    ts_mark(P, TS_BARRIER);                           \
+    // run a phase, start streaming the next phase's weights, then wait for everyone
+#define FUSED_STEP(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER)          \
+    FUSED_STEP_I(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER, ((PHASE) != PH_EMBED && (PHASE) != PH_ATTN))
+#define FUSED_STEP_I(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER, GEMM)  \
+    ts_mark(P, TS_START);                                              \
+    run_phase<DH>(P, PHASE, LAYER, smem, wg, nwg, W, PRE);             \
+    ts_mark(P, TS_EPILOGUE);                                           \
+    grid_arrive(P, ++epoch, GEMM);                                     \
+    prefetch_phase(P, NEXT_PHASE, NEXT_LAYER, wg, nwg, W);             \
+    grid_wait(P, epoch);                                               \
+    ts_mark(P, TS_BARRIER);                                            \
     P.ts_slot += TS_PER_PHASE;
-    FUSED_STEP(PH_EMBED, 0)
-    if (P.trace) run_phase<DH>(P, PH_TRACE, 0, smem, wg, nwg);
+    FUSED_STEP(PH_EMBED, 0, false, PH_QKV, 0)
+    if (P.trace) phase_trace(P, 0, wg, nwg);
     for (int l = 0; l < P.L; l++) {
-        FUSED_STEP(PH_QKV, l)
-        FUSED_STEP(PH_ATTN, l)
-        FUSED_STEP(PH_O, l)
-        FUSED_STEP(PH_GU, l)
-        FUSED_STEP(PH_DOWN, l)
-        if (P.trace) run_phase<DH>(P, PH_TRACE, l + 1, smem, wg, nwg);
+        FUSED_STEP(PH_QKV, l, true, PH_ATTN, l)
+        // the ring is empty here: say so, or its registers stay reserved through the attention phase
+#pragma unroll
+        for (int i = 0; i < W_RING; i++) W[i] = u32x4{0u, 0u, 0u, 0u};
+        FUSED_STEP(PH_ATTN, l, false, PH_O, l)
+        FUSED_STEP(PH_O, l, true, PH_GU, l)
+        FUSED_STEP(PH_GU, l, true, PH_DOWN, l)
+        if (l + 1 < P.L) {
+            FUSED_STEP(PH_DOWN, l, true, PH_QKV, l + 1)
+        } else {
+            FUSED_STEP(PH_DOWN, l, true, PH_LM, 0)
+        }
+        if (P.trace) phase_trace(P, l + 1, wg, nwg);
     }
 #undef FUSED_STEP
+#undef FUSED_STEP_I
     ts_mark(P, TS_START);
-    run_phase<DH>(P, PH_LM, 0, smem, wg, nwg);
+    run_phase<DH>(P, PH_LM, 0, smem, wg, nwg, W, true);
     ts_mark(P, TS_EPILOGUE);
 }
 
@@ -720,6 +918,8 @@ struct FusedState {
     int grid = 0, kg_max = 0, tg_qkv = 1, tg_lm = 1;
     size_t lds_bytes = 0;
     int lds_red_off = 0, lds_rstd_off = 0;
+    bf16_t *hg = nullptr;
+    float *ssq = nullptr;
     int m_limit = 0;
     int mode = 2;      // 0: off, 1: one launch per phase, 2: persistent
 };
@@ -745,22 +945,24 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     CSD_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     CSD_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
     const int d = c.d_model, hd = mod->hd, F = c.d_ffn, V = c.vocab, dh = c.head_dim;
-    // rows the LDS-resident activations allow: M*d*4 bytes + reduction scratch + attention merge area
-    const int red_bytes = FUSED_WAVES * 3 * 64 * 16;
+    // LDS: activation fragments M * max(d, hd) * 4 bytes (or the attention merge area), reduction scratch
+    // (8 waves x 3 tiles x 1 KB), rstd[16]
+    const int red_bytes = 2 * (FUSED_WAVES - 1) * 3 * 64 * 16;   // two buffers of 7 waves x 3 tiles x 1 KB
     const int attn_bytes = FUSED_WAVES * 16 * (dh + 4) * 4;
+    const int kmax = d > hd ? d : hd;
     int m_limit = 16;
-    while (m_limit > 0 && (size_t)m_limit * d * 4 + red_bytes + 256 > (size_t)lds_max) m_limit--;
-    if (m_limit < 1 || attn_bytes > lds_max) return CSD_OK;
-    if (d % 32 || hd % 32 || F % 32 || V % 16 || (F / 16) < 1) return CSD_OK;
+    while (m_limit > 0 && (size_t)m_limit * kmax * 4 + red_bytes + 256 > (size_t)lds_max) m_limit--;
+    if (m_limit < 1 || attn_bytes + red_bytes + 256 > lds_max) return CSD_OK;
+    if (d % 256 || hd % 32 || F % 32 || V % 16 || (F / 16) < 1) return CSD_OK;
     FusedState *fs = new FusedState();
     fs->mode = mode;
     fs->m_limit = m_limit < mod->m_max ? m_limit : mod->m_max;
     const int m_cap = fs->m_limit;
-    size_t act_bytes = (size_t)m_cap * d * 4;
+    size_t act_bytes = (size_t)m_cap * kmax * 4;
+    if (act_bytes < (size_t)attn_bytes) act_bytes = attn_bytes;
     fs->lds_red_off = (int)((act_bytes + 255) / 256 * 256);
     fs->lds_rstd_off = fs->lds_red_off + red_bytes;
     fs->lds_bytes = (size_t)fs->lds_rstd_off + 256;
-    if (fs->lds_bytes < (size_t)attn_bytes) fs->lds_bytes = attn_bytes;
     fs->grid = cus;
     fs->kg_max = (mod->seq_pad + 255) / 256;
     fs->tg_qkv = ((3 * hd / 16) / 3 >= cus) ? 3 : 1;
@@ -775,6 +977,8 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     if ((rc = fused_alloc(mod, (void **)&fs->layers, sizeof(FusedLayer) * c.n_layers, false, st)) != CSD_OK) return rc;
     CSD_HIP(hipMemcpy(fs->layers, hl.data(), sizeof(FusedLayer) * c.n_layers, hipMemcpyHostToDevice));
     if ((rc = fused_alloc(mod, (void **)&fs->cs, sizeof(float) * 16 * dh, false, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->hg, sizeof(bf16_t) * 2 * 16 * (size_t)d, true, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->ssq, sizeof(float) * 16 * (size_t)(d / 16), true, st)) != CSD_OK) return rc;
     if ((rc = fused_alloc(mod, (void **)&fs->attn_cnt, sizeof(unsigned) * c.max_batch * c.n_heads, true, st)) != CSD_OK) return rc;
     if ((rc = fused_alloc(mod, (void **)&fs->bar, 8 * BAR_STRIDE * 64, true, st)) != CSD_OK) return rc;
     if ((rc = fused_alloc(mod, (void **)&fs->err, 256, true, st)) != CSD_OK) return rc;
@@ -838,6 +1042,9 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     P.tg_lm = fs->tg_lm;
     P.lds_red_off = fs->lds_red_off;
     P.lds_rstd_off = fs->lds_rstd_off;
+    P.hg = fs->hg;
+    P.hg_plane = (size_t)16 * c.d_model;
+    P.ssq = fs->ssq;
     P.eps = c.rms_eps;
     P.scale = 1.0f / sqrtf((float)c.head_dim);
     P.theta = c.rope_theta;

@@ -69,6 +69,14 @@ __host__ __device__ inline size_t kv_v_off(const KvGeom &g, int l, int b, int hh
     return (size_t)g.L * g.Bmax * g.H * kv_head_elems(g) + kv_k_off(g, l, b, hh);
 }
 
+// Workgroup barrier that orders LDS traffic only: global loads already issued (the weight stream)
+// stay in flight across it, where __syncthreads() would wait for every outstanding memory operation.
+__device__ __forceinline__ void lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
