@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the dominant kernel, from rocprofv3 counter runs of this same command
+# (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a copy of known size); the
+# summaries and the commands are under profiles/.  Keyed by (workload, forward path).
+TRAFFIC_BYTES_PER_LAUNCH = {("target7b", 2): 14_708_000_000}
 
 
 def algorithmic_bytes(shape, B, t, m):
@@ -47,6 +51,9 @@ def main():
     ap.add_argument("--prof-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy"])
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
+                    help="after the benchmark, launch N plain 1 GiB copies (kernel k_copy_calib) so that a "
+                         "rocprofv3 counter run of this command also reads the counters for known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (sequences are independent, "
@@ -144,12 +151,21 @@ def main():
     fl = algorithmic_flops(shape, B, t, m)
     gemm_ms_step = cls_ms[0] / max(1, args.prof_steps)
     gemm_launches_step = cls_n[0] / max(1, args.prof_steps)
-    achieved = ab["weights"] / 1e9 / (gemm_ms_step / 1e3) if gemm_ms_step > 0 else 0.0
+    path = model.path(B, m)
+    if path == 2:
+        # the whole review forward is one persistent launch: it moves every algorithmic byte of the step
+        # except the softmax/accept re-read of the logits
+        kernel, launch_bytes = "k_verify_persistent (whole review forward, one launch per step)", ab["total"]
+    else:
+        kernel = "k_fused_phase (one launch per GEMM phase)" if path == 1 else \
+                 "k_gemm_mfma (all weight-streaming GEMMs of a step)"
+        launch_bytes = ab["weights"]
+    achieved = launch_bytes / 1e9 / (gemm_ms_step / 1e3) if gemm_ms_step > 0 else 0.0
     roofline = {
-        "bound": "hbm", "kernel": "k_gemm_mfma (all weight-streaming GEMMs of a step)",
+        "bound": "hbm", "kernel": kernel,
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-        "bytes_per_launch": round(ab["weights"] / max(1.0, gemm_launches_step)),
+        "bytes_per_launch": round(launch_bytes / max(1.0, gemm_launches_step)),
         "avg_launch_us": round(1e3 * gemm_ms_step / max(1.0, gemm_launches_step), 2),
         "launches_per_step": gemm_launches_step,
         "step_frac": round(ab["total"] / 1e9 / (gpu_ms_per_step / 1e3) / HBM_PEAK_GBS, 4),
@@ -158,6 +174,16 @@ def main():
                               "attention": round(cls_ms[1] / max(1, args.prof_steps), 4),
                               "other": round(cls_ms[2] / max(1, args.prof_steps), 4)},
     }
+    if TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, path)):
+        roofline["traffic"] = TRAFFIC_BYTES_PER_LAUNCH[(args.workload, path)]
+
+    if args.copy_calibration > 0:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            P.debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- CPU baseline: the oracle as it stands, one whole step on the host cores
     cpu = None

@@ -181,6 +181,12 @@ int32_t csd_debug_set_timestamps(csd_model *model, uint64_t *marks);
  * fit LDS).  The environment variable CSD_PATH=multikernel|phases at csd_model_create forces 0 or 1. */
 int32_t csd_debug_path(const csd_model *model, int32_t B, int32_t m);
 
+/* Counter calibration for benchmarks: a plain streaming copy of `bytes` bytes (a multiple of 16; dst and
+ * src are device pointers, 16-byte aligned, not overlapping), launched as kernel k_copy_calib, so that a
+ * hardware counter's reading for exactly 2 x bytes of HBM traffic (one read, one write) can be taken
+ * in the same profiler run as the kernels being measured. */
+int32_t csd_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Kernel timing hook for benchmarks.  While enabled, each verify call brackets every kernel
  * it launches with a pair of HIP events on the caller's stream (this perturbs the step, so
  * throughput is timed with the hook off).  After the caller has synchronised the stream,

@@ -16,7 +16,8 @@ _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
            "csd_kv_write", "csd_kv_read", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
-           "csd_accept", "csd_verify_accept", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_prof_enable", "csd_prof_read"]
+           "csd_accept", "csd_verify_accept", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_debug_copy",
+           "csd_prof_enable", "csd_prof_read"]
 
 _STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}
 
@@ -171,6 +172,15 @@ class Model:
         ms, n = C.c_double(), C.c_int64()
         _chk(lib().csd_prof_read(self._h, kernel_class, C.byref(ms), C.byref(n), 1 if reset else 0), "csd_prof_read")
         return ms.value, n.value
+
+
+def debug_copy(dst, src):
+    """Streaming copy of src into dst (same byte size, a multiple of 16): counter calibration."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("debug_copy: size mismatch")
+    _chk(lib().csd_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), C.c_size_t(nbytes), _stream()),
+         "csd_debug_copy")
 
 
 def bigram_fit(tokens, vocab, next_table):

@@ -186,6 +186,21 @@ extern "C" int32_t csd_debug_path(const csd_model *mod, int32_t B, int32_t m) {
     return csd_fused_path(mod, B, m);
 }
 
+__global__ __launch_bounds__(256) void k_copy_calib(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+extern "C" int32_t csd_debug_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src) return CSD_ENULL;
+    if (bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16) return CSD_EINVAL;
+    if (bytes == 0) return CSD_OK;
+    hipLaunchKernelGGL(k_copy_calib, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (u32x4 *)dst, (const u32x4 *)src,
+                       bytes / 16);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
 extern "C" int32_t csd_prof_enable(csd_model *mod, int32_t on) {
     if (!mod) return CSD_ENULL;
     mod->prof = on != 0;

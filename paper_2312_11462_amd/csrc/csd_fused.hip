@@ -39,6 +39,7 @@ struct FusedParams {
     int M, m, B, d, hd, H, dh, F, V, L, seq_pad, Bmax, kperm;
     int kg_max;        // key groups (256 keys each) covered by the attention phase's item list
     int tg_qkv, tg_lm;
+    int pf;            // ring slots of the next phase's weights issued before the barrier wait
     int lds_red_off, lds_rstd_off;   // LDS: [0, red_off) activation fragments (or the attention merge area),
                                      // then the split-K reduction scratch, then 16 floats of rstd
     float eps, scale, theta;
@@ -376,13 +377,13 @@ struct WStream {
     }
     // issue the loads of the cursor's batch into ring slot `slot` (a constant once the caller's loop is
     // unrolled) and advance the cursor
-    __device__ __forceinline__ void load_next(u32x4 (&W)[W_RING], int slot) {
+    __device__ __forceinline__ void load_next(u32x4 (&W)[W_RING], int slot, bool issue = true) {
         const int item = l_item, ks = ks0 + l_b * U;
         if (++l_b == nbpi) {
             l_b = 0;
             l_item += nwg;
         }
-        if (item >= n_items) return;             // stream exhausted (uniform)
+        if (item >= n_items || !issue) return;   // stream exhausted (uniform)
         const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int u = 0; u < U; u++)
@@ -391,10 +392,11 @@ struct WStream {
                 W[(slot * U + u) * TG + j] =
                     (ks + u < ks1) ? __builtin_nontemporal_load(Wp + ((size_t)(item * TG + j) * KS + ks + u) * 64 + lane) : zero;
     }
-    __device__ __forceinline__ void prefetch(u32x4 (&W)[W_RING]) {
+    // issue ring slots [from, to) of the first NW batches
+    __device__ __forceinline__ void prefetch(u32x4 (&W)[W_RING], int from = 0, int to = NW) {
         rewind();
 #pragma unroll
-        for (int s = 0; s < NW; s++) load_next(W, s);
+        for (int s = 0; s < NW; s++) load_next(W, s, s >= from && s < to);
     }
 };
 
@@ -405,7 +407,7 @@ struct WStream {
 // `prefetched`: the first NW weight batches were already issued into W before the barrier.
 template <int TG, int EPI, bool B_LDS, int U, int NW>
 __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs &A, char *smem, int wg, int nwg,
-                                           u32x4 (&W)[W_RING], bool prefetched) {
+                                           u32x4 (&W)[W_RING], int prefetched) {
     static_assert(NW * U * TG <= (B_LDS ? W_RING : W_RING / 2), "weight ring does not fit");
     static_assert(B_LDS || 4 * U <= W_RING / 2, "activation ring does not fit");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -459,11 +461,11 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
 
     if (B_LDS) {
         copy_to_lds(P, A.bsrc, A.bplane, A.ldb, smem);
-        if (!prefetched && !service) ws.prefetch(W);
+        if (prefetched < NW && !service) ws.prefetch(W, prefetched, NW);
     } else if (!service) {
         FUSED_LOAD_B(0, 0)
         FUSED_LOAD_B(1, 1)
-        if (!prefetched) ws.prefetch(W);
+        if (prefetched < NW) ws.prefetch(W, prefetched, NW);
     }
     ws.skip_prefetched();
     // service wave: the first item's residual tiles (they do not change during the phase) and the row scales
@@ -806,7 +808,7 @@ __device__ __forceinline__ void prefetch_phase(const FusedParams &P, int phase, 
     {                                                        \
         WStream<TGv, Uv, NWv> ws;                            \
         ws.init(A.Wp, A.KS, A.n_items, wg, nwg);             \
-        ws.prefetch(W);                                      \
+        ws.prefetch(W, 0, P.pf);                             \
     }
     if (phase == PH_QKV) {
         if (P.tg_qkv == 3) FUSED_PF(QKV3) else FUSED_PF(QKV1)
@@ -825,7 +827,7 @@ __device__ __forceinline__ void prefetch_phase(const FusedParams &P, int phase, 
 
 template <int DH>
 __device__ __forceinline__ void run_phase(const FusedParams &P, int phase, int layer, char *smem, int wg, int nwg, u32x4 (&W)[W_RING],
-                          bool prefetched) {
+                          int prefetched) {
     if (phase == PH_EMBED) {
         phase_embed(P, wg, nwg);
     } else if (phase == PH_ATTN) {
@@ -859,7 +861,7 @@ template <int DH>
 __global__ __launch_bounds__(FUSED_THREADS, 1) void k_fused_phase(FusedParams P, int phase, int layer) {
     extern __shared__ __align__(16) char smem[];
     u32x4 W[W_RING];
-    run_phase<DH>(P, phase, layer, smem, blockIdx.x, gridDim.x, W, false);
+    run_phase<DH>(P, phase, layer, smem, blockIdx.x, gridDim.x, W, 0);
 }
 
 // the whole forward in one launch
@@ -875,7 +877,7 @@ __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(FusedPar
     FUSED_STEP_I(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER, ((PHASE) != PH_EMBED && (PHASE) != PH_ATTN))
 #define FUSED_STEP_I(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER, GEMM)  \
     ts_mark(P, TS_START);                                              \
-    run_phase<DH>(P, PHASE, LAYER, smem, wg, nwg, W, PRE);             \
+    run_phase<DH>(P, PHASE, LAYER, smem, wg, nwg, W, (PRE) ? P.pf : 0); \
     ts_mark(P, TS_EPILOGUE);                                           \
     grid_arrive(P, ++epoch, GEMM);                                     \
     prefetch_phase(P, NEXT_PHASE, NEXT_LAYER, wg, nwg, W);             \
@@ -902,7 +904,7 @@ __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(FusedPar
 #undef FUSED_STEP
 #undef FUSED_STEP_I
     ts_mark(P, TS_START);
-    run_phase<DH>(P, PH_LM, 0, smem, wg, nwg, W, true);
+    run_phase<DH>(P, PH_LM, 0, smem, wg, nwg, W, P.pf);
     ts_mark(P, TS_EPILOGUE);
 }
 
@@ -921,6 +923,7 @@ struct FusedState {
     bf16_t *hg = nullptr;
     float *ssq = nullptr;
     int m_limit = 0;
+    int pf = 64;       // tuning knob (env CSD_FUSED_PF): ring slots prefetched across a barrier
     int mode = 2;      // 0: off, 1: one launch per phase, 2: persistent
 };
 
@@ -956,6 +959,7 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     if (d % 256 || hd % 32 || F % 32 || V % 16 || (F / 16) < 1) return CSD_OK;
     FusedState *fs = new FusedState();
     fs->mode = mode;
+    if (const char *e = getenv("CSD_FUSED_PF")) fs->pf = atoi(e) < 0 ? 0 : atoi(e);
     fs->m_limit = m_limit < mod->m_max ? m_limit : mod->m_max;
     const int m_cap = fs->m_limit;
     size_t act_bytes = (size_t)m_cap * kmax * 4;
@@ -1040,6 +1044,7 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     P.kg_max = fs->kg_max;
     P.tg_qkv = fs->tg_qkv;
     P.tg_lm = fs->tg_lm;
+    P.pf = fs->pf;
     P.lds_red_off = fs->lds_red_off;
     P.lds_rstd_off = fs->lds_rstd_off;
     P.hg = fs->hg;
