@@ -22,7 +22,7 @@ def build(verbose: bool = False) -> str:
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
-           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+           "-o", LIB] + os.environ.get("CSD_HIPCC_FLAGS", "").split() + [os.path.join(CSRC, s) for s in SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     lines = (res.stdout + res.stderr).splitlines()
     remarks = [l for l in lines if "-Rpass-analysis=kernel-resource-usage" in l]

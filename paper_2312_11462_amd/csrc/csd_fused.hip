@@ -39,6 +39,7 @@ struct FusedParams {
     int M, m, B, d, hd, H, dh, F, V, L, seq_pad, Bmax, kperm;
     int kg_max;        // key groups (256 keys each) covered by the attention phase's item list
     int tg_qkv, tg_lm;
+    int fresh;         // 1: every phase writes its own instance of the exchange buffers (no L2 invalidate)
     int pf;            // ring slots of the next phase's weights issued before the barrier wait
     int lds_red_off, lds_rstd_off;   // LDS: [0, red_off) activation fragments (or the attention merge area),
                                      // then the split-K reduction scratch, then 16 floats of rstd
@@ -48,30 +49,82 @@ struct FusedParams {
     const FusedLayer *layers;
     const float *final_norm;
     const u32x4 *lm;
-    float *h;
-    bf16_t *q;
-    size_t q_plane;
-    bf16_t *act;       // attention output (row stride hd) and SwiGLU output (row stride F), two planes
-    size_t act_plane;
-    bf16_t *hg;        // h * gain of the next norm, row stride d, two planes: input of QKV / gate-up / LM head
-    size_t hg_plane;
-    float *ssq;        // [16 rows][d/16 tiles] sums of squares of h, per tile
+    // Exchange buffers, one instance per producing phase of the whole forward (never reused inside a
+    // launch): xh/xhg/xssq have 2L+1 slots (embedding, then after the output and the down projection of
+    // every layer), xq/xattn/xffn one per layer.  All hold 16 rows.
+    float *xh;         // residual stream, fp32 [slot][16][d]
+    bf16_t *xhg;       // h * gain of the next norm, two bf16 planes [slot][2][16][d]: input of QKV / gate-up / LM head
+    float *xssq;       // [slot][16 rows][d/16 tiles] sums of squares of h, per tile
+    bf16_t *xq;        // rotated queries, two planes [layer][2][16][hd]
+    bf16_t *xattn;     // attention output, two planes [layer][2][16][hd]
+    bf16_t *xffn;      // SwiGLU output, two planes [layer][2][16][F]
+    size_t q_plane, hg_plane, ffn_plane;      // elements between the two planes (16 rows)
     float *cs;         // rotary table [M][dh/2][cos, sin]
     bf16_t *kv;
     float *attn_part;
     unsigned *attn_cnt;
     float *logits;
-    unsigned long long *bar;
-    unsigned long long bar_base;
+    unsigned char *bar;       // barrier flags: BAR_REPLICAS copies of one byte per workgroup
+    unsigned bar_base;
     unsigned *err;
     float *trace;
     unsigned long long *ts;   // optional timing marks [mark][workgroup] (100 MHz wall clock), see TS_*
-    int ts_slot;              // first mark index of the current phase (set by the persistent kernel)
 };
 
 enum { TS_START = 0, TS_PROLOGUE = 1, TS_LOOP = 2, TS_EPILOGUE = 3, TS_BARRIER = 4, TS_PER_PHASE = 5 };
-__device__ __forceinline__ void ts_mark(const FusedParams &P, int which) {
-    if (P.ts && threadIdx.x == 0) P.ts[(size_t)(P.ts_slot + which) * gridDim.x + blockIdx.x] = wall_clock64();
+// Device code takes the launch parameters by reference to the kernel argument and never writes to
+// them.  (Attempts to keep them wholly in scalar registers, by inlining every phase or by reading the
+// kernel-argument segment directly, made the register allocator spill thousands of vector registers
+// in the single-launch kernel; with the three small phases left as real calls it spills none.)
+typedef const FusedParams CParams;
+
+// What changes from phase to phase: the instances of the exchange buffers the phase reads and writes,
+// and where its timing marks go.  Kept apart from FusedParams, which stays a read-only kernel argument
+// (anything mutable in it would move the whole structure into scratch memory, and scratch accesses
+// queue behind the weight stream like every other vector memory access).
+struct PhaseBufs {
+    const float *h_in;
+    float *h_out;
+    const bf16_t *hg_in;
+    bf16_t *hg_out;
+    const float *ssq_in;
+    float *ssq_out;
+    bf16_t *q, *attn_o, *ffn_a;
+    int ts_slot;              // first mark index of the phase
+};
+
+__device__ __forceinline__ void ts_mark(CParams &P, const PhaseBufs &X, int which) {
+    if (P.ts && threadIdx.x == 0) P.ts[(size_t)(X.ts_slot + which) * gridDim.x + blockIdx.x] = wall_clock64();
+}
+
+// A buffer instance is written in exactly one phase and read only in later phases; with P.fresh every
+// phase of the forward has its own, so no cache ever holds a stale line of it during the launch.
+__device__ __forceinline__ PhaseBufs make_bufs(CParams &P, int phase, int layer, int ts_slot) {
+    PhaseBufs X;
+    X.ts_slot = ts_slot;
+    if (!P.fresh) {       // one instance of each buffer, reused by every layer (the barrier then invalidates L2)
+        X.h_in = X.h_out = P.xh;
+        X.hg_in = X.hg_out = P.xhg;
+        X.ssq_in = X.ssq_out = P.xssq;
+        X.q = P.xq;
+        X.attn_o = P.xattn;
+        X.ffn_a = P.xffn;
+        return X;
+    }
+    // slot of the residual stream entering the phase: 2l for the attention half, 2l+1 for the FFN half
+    const int s_in = phase == PH_EMBED ? 0 : phase == PH_LM ? 2 * P.L : (phase == PH_GU || phase == PH_DOWN) ? 2 * layer + 1 : 2 * layer;
+    const int s_out = phase == PH_EMBED ? 0 : s_in + 1;
+    const size_t hs = (size_t)16 * P.d;
+    X.h_in = P.xh + hs * s_in;
+    X.h_out = P.xh + hs * s_out;
+    X.hg_in = P.xhg + 2 * hs * s_in;
+    X.hg_out = P.xhg + 2 * hs * s_out;
+    X.ssq_in = P.xssq + (size_t)(P.d / 16) * 16 * s_in;
+    X.ssq_out = P.xssq + (size_t)(P.d / 16) * 16 * s_out;
+    X.q = P.xq + (size_t)2 * 16 * P.hd * layer;
+    X.attn_o = P.xattn + (size_t)2 * 16 * P.hd * layer;
+    X.ffn_a = P.xffn + (size_t)2 * 16 * P.F * layer;
+    return X;
 }
 
 // ------------------------------------------------------------------- coherent device memory
@@ -117,54 +170,71 @@ __device__ __forceinline__ void co_st16(__amdgpu_buffer_rsrc_t r, int off, bf16_
 
 // ------------------------------------------------------------------------------ grid barrier
 
-// Two-level arrival counter (groups of BAR_GROUP workgroups, then one top counter) so that no single
-// address takes 256 serialized atomics.  Counters only grow: the host passes the number of barriers
-// completed by earlier launches (bar_base), so nothing is ever reset.  The wait is bounded: when it
-// gives up it raises the error flag, which also releases every later wait, so each wave still exits.
-#define BAR_GROUP 32
-#define BAR_STRIDE 32   /* unsigned long longs between counters: 256 bytes */
+// Flag barrier without read-modify-write atomics: workgroup w stores the number of the barrier it has
+// reached into its one-byte flag, and the service wave of every workgroup polls all flags with one
+// 4-byte load per lane (4 flags each, up to 256 workgroups).  Polling is what loads the memory
+// channel that holds the flags, and the weight stream needs every channel, so the flags exist in
+// BAR_REPLICAS copies on different channels: an arriving workgroup writes all copies (one store
+// instruction, one lane per copy) and polls only copy (workgroup index mod BAR_REPLICAS).
+// Barrier numbers only grow (the host passes the number completed by earlier launches) and two
+// workgroups are never more than one barrier apart, so the comparison is done modulo 256.
+// The wait is bounded: when it gives up it raises the error flag, which also releases every later
+// wait, so each wave still exits.
+// No cache maintenance is needed here: everything read after a barrier lives in a buffer instance that
+// was never read before in this launch (see make_bufs), and the flags themselves are polled with
+// loads that bypass the non-coherent caches.
+#define BAR_MAX_WG 256
+#define BAR_REPLICAS 8
+#define BAR_REPLICA_STRIDE (4096 + 256)   /* bytes */
+#define BAR_BYTES (BAR_REPLICAS * BAR_REPLICA_STRIDE)
 
 // service_only: only the service wave (wave 0) stored to global memory in this phase (GEMM phases: the
 // other waves hand their partial sums over through LDS), so only it waits for its store acknowledgements
 // and the streaming waves run straight on to prefetch the next phase's weights.
-__device__ __forceinline__ void grid_arrive(const FusedParams &P, unsigned long long epoch, bool service_only) {
+__device__ __forceinline__ void grid_arrive(CParams &P, unsigned epoch, bool service_only) {
     if (service_only) {
         if (threadIdx.x < 64) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's stores are acknowledged
     } else {
         __syncthreads();        // all of this workgroup's write-through stores have been acknowledged
     }
-    if (threadIdx.x == 0) {
-        const int G = gridDim.x, grp = blockIdx.x / BAR_GROUP;
-        const int gsize = min(BAR_GROUP, G - grp * BAR_GROUP);
-        const unsigned long long old =
-            __hip_atomic_fetch_add(P.bar + BAR_STRIDE * (1 + grp), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old + 1 == epoch * (unsigned long long)gsize)
-            __hip_atomic_fetch_add(P.bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x < BAR_REPLICAS) {
+        const __amdgpu_buffer_rsrc_t rb = co_rsrc(P.bar, BAR_BYTES);
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)epoch, rb, (int)(threadIdx.x * BAR_REPLICA_STRIDE + blockIdx.x), 0,
+                                             CSD_SC1);
     }
 }
 
 // Between arrive and wait a wave may issue loads that do not depend on other workgroups (the next
 // phase's weights); the closing workgroup barrier orders LDS only, so those loads stay in flight.
-__device__ __forceinline__ void grid_wait(const FusedParams &P, unsigned long long epoch) {
-    if (threadIdx.x == 0) {
-        const int ngrp = (gridDim.x + BAR_GROUP - 1) / BAR_GROUP;
+__device__ __forceinline__ void grid_wait(CParams &P, unsigned epoch) {
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const __amdgpu_buffer_rsrc_t rb = co_rsrc(P.bar, BAR_BYTES);
+        const int G = gridDim.x;
+        const int off = (int)((blockIdx.x % BAR_REPLICAS) * BAR_REPLICA_STRIDE) + lane * 4;
         unsigned spins = 0;
         bool give_up = __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-        while (!give_up && __hip_atomic_load(P.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch * (unsigned long long)ngrp) {
+        while (!give_up) {
+            const unsigned f = __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, CSD_SC1);
+            bool ok = true;
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                ok = ok && (4 * lane + i >= G || (signed char)(unsigned char)(((f >> (8 * i)) & 0xFFu) - (epoch & 0xFFu)) >= 0);
+            if (__all(ok)) break;
             ++spins;
             if ((spins & 1023u) == 0u && __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
                 give_up = true;
             if (spins > (1u << 20)) {
-                __hip_atomic_store(P.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (lane == 0) __hip_atomic_store(P.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 give_up = true;
             }
         }
-        // drop this XCD's possibly stale lines: data other workgroups wrote (write-through) before the
-        // barrier is read with ordinary, L2-cached loads afterwards
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
+    // with reused exchange buffers this XCD's L2 may hold the previous layer's lines: drop them
+    if (!P.fresh && threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     lds_sync();
 }
+
 
 // ------------------------------------------------------------------------------------ helpers
 
@@ -190,11 +260,11 @@ __device__ __forceinline__ void split4(const float *v, u32x2 &hi, u32x2 &lo) {
 // Residual-stream tile hand-over used by the embedding and by the residual epilogues: lane (t, g) holds
 // 4 consecutive features of row t of 16-feature tile T.  Writes h, the next GEMM's input h*gain as two
 // bf16 planes, and the tile's sum of squares per row.
-__device__ __forceinline__ void publish_h_tile(const FusedParams &P, const float *__restrict__ gain, int T, int t, int g,
+__device__ __forceinline__ void publish_h_tile(CParams &P, const PhaseBufs &X, const float *__restrict__ gain, int T, int t, int g,
                                                f32x4 hv, bool valid) {
-    const __amdgpu_buffer_rsrc_t rh = co_rsrc(P.h, sizeof(float) * (size_t)P.M * P.d);
-    const __amdgpu_buffer_rsrc_t rg = co_rsrc(P.hg, 2 * (P.hg_plane * 2));
-    const __amdgpu_buffer_rsrc_t rs = co_rsrc(P.ssq, sizeof(float) * (size_t)(P.d / 16) * 16);
+    const __amdgpu_buffer_rsrc_t rh = co_rsrc(X.h_out, sizeof(float) * (size_t)P.M * P.d);
+    const __amdgpu_buffer_rsrc_t rg = co_rsrc(X.hg_out, 2 * (P.hg_plane * 2));
+    const __amdgpu_buffer_rsrc_t rs = co_rsrc(X.ssq_out, sizeof(float) * (size_t)(P.d / 16) * 16);
     float ss = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
     ss += __shfl_xor(ss, 16, 64);
     ss += __shfl_xor(ss, 32, 64);
@@ -212,7 +282,8 @@ __device__ __forceinline__ void publish_h_tile(const FusedParams &P, const float
 }
 
 // h[r] = E[token[r]] (published as above for the first QKV) and the rotary table of this call's positions
-__device__ void phase_embed(const FusedParams &P, int wg, int nwg) {
+__device__ __noinline__ void phase_embed(CParams &P, int wg, int nwg) {
+    const PhaseBufs X = make_bufs(P, PH_EMBED, 0, 0);
     const int lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
     const int gw = wg * FUSED_WAVES + (threadIdx.x >> 6), nw = nwg * FUSED_WAVES;
     const bool valid = t < P.M;
@@ -224,7 +295,7 @@ __device__ void phase_embed(const FusedParams &P, int wg, int nwg) {
             hv = f32x4{__uint_as_float(e[0] << 16), __uint_as_float(e[0] & 0xFFFF0000u), __uint_as_float(e[1] << 16),
                        __uint_as_float(e[1] & 0xFFFF0000u)};
         }
-        publish_h_tile(P, P.layers[0].attn_norm, T, t, g, hv, valid);
+        publish_h_tile(P, X, P.layers[0].attn_norm, T, t, g, hv, valid);
     }
     const __amdgpu_buffer_rsrc_t rc = co_rsrc(P.cs, sizeof(float) * (size_t)P.M * P.dh);
     const size_t gtid = (size_t)wg * FUSED_THREADS + threadIdx.x, gsz = (size_t)nwg * FUSED_THREADS;
@@ -250,12 +321,12 @@ struct GemmArgs {
 };
 
 template <int TG, int EPI>
-__device__ __forceinline__ void gemm_epilogue(const FusedParams &P, const GemmArgs &A, int item, int j, f32x4 v, int lane,
+__device__ __forceinline__ void gemm_epilogue(CParams &P, const PhaseBufs &X, const GemmArgs &A, int item, int j, f32x4 v, int lane,
                                               f32x4 hcur) {
     const int t = lane & 15, g = lane >> 4;
     const int T = item * TG + j;     // global tile index
     if (EPI == EPI_RESID) {
-        publish_h_tile(P, A.next_gain, T, t, g, hcur + v, t < P.M);
+        publish_h_tile(P, X, A.next_gain, T, t, g, hcur + v, t < P.M);
     } else if (EPI == EPI_LOGITS) {
         if (t < P.M) *reinterpret_cast<f32x4 *>(P.logits + (size_t)t * P.V + T * 16 + 4 * g) = v;
     } else if (EPI == EPI_QKV) {
@@ -284,7 +355,7 @@ __device__ __forceinline__ void gemm_epilogue(const FusedParams &P, const GemmAr
                 if (region == 0) {
                     u32x2 hi, lo;
                     split4(out, hi, lo);
-                    const __amdgpu_buffer_rsrc_t rq = co_rsrc(P.q, 2 * (P.q_plane * 2));
+                    const __amdgpu_buffer_rsrc_t rq = co_rsrc(X.q, 2 * (P.q_plane * 2));
                     const int off = (int)(((size_t)t * P.hd + head * P.dh + p0) * 2);
                     co_st64(rq, off, hi);
                     co_st64(rq, off + (int)(P.q_plane * 2), lo);
@@ -307,7 +378,7 @@ __device__ __forceinline__ void gemm_epilogue(const FusedParams &P, const GemmAr
 
 // Copy the two planes of a row-major activation buffer [M][ld] into LDS in fragment order:
 // 16-byte unit ((ks*2 + plane)*4 + g)*M + row holds k = 32 ks + 8 g .. +7 of that row.
-__device__ __forceinline__ void copy_to_lds(const FusedParams &P, const bf16_t *__restrict__ src, size_t plane, int ld,
+__device__ __forceinline__ void copy_to_lds(CParams &P, const bf16_t *__restrict__ src, size_t plane, int ld,
                                             char *smem) {
     const int tid = threadIdx.x, M = P.M, ld8 = ld / 8;
     u32x4 *act = reinterpret_cast<u32x4 *>(smem);
@@ -357,7 +428,7 @@ struct WStream {
         wg = wg_;
         nwg = nwg_;
         lane = threadIdx.x & 63;
-        const int sw = (int)(threadIdx.x >> 6) - 1;           // streaming wave index; -1 for the service wave
+        const int sw = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) - 1;   // streaming wave index (scalar); -1 for the service wave
         ks0 = sw < 0 ? 0 : KS * sw / STREAM_WAVES;
         ks1 = sw < 0 ? 0 : KS * (sw + 1) / STREAM_WAVES;
         const int nb_max = ((KS + STREAM_WAVES - 1) / STREAM_WAVES + U - 1) / U;   // same for every wave
@@ -406,11 +477,11 @@ struct WStream {
 // through a two-batch ring that takes the upper half of the registers.
 // `prefetched`: the first NW weight batches were already issued into W before the barrier.
 template <int TG, int EPI, bool B_LDS, int U, int NW>
-__device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs &A, char *smem, int wg, int nwg,
+__device__ __forceinline__ void gemm_phase(CParams &P, const PhaseBufs &X, const GemmArgs &A, char *smem, int wg, int nwg,
                                            u32x4 (&W)[W_RING], int prefetched) {
     static_assert(NW * U * TG <= (B_LDS ? W_RING : W_RING / 2), "weight ring does not fit");
     static_assert(B_LDS || 4 * U <= W_RING / 2, "activation ring does not fit");
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool service = w == 0;
     const int sw = w - 1;
     const int t = lane & 15, g = lane >> 4;
@@ -476,7 +547,7 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
         if (EPI == EPI_RESID && valid) {
 #pragma unroll
             for (int j = 0; j < TG; j++)
-                hfirst[j] = *reinterpret_cast<const f32x4 *>(P.h + (size_t)t * P.d + (wg * TG + j) * 16 + 4 * g);
+                hfirst[j] = *reinterpret_cast<const f32x4 *>(X.h_in + (size_t)t * P.d + (wg * TG + j) * 16 + 4 * g);
         }
     }
     if (B_LDS) lds_sync();
@@ -487,7 +558,7 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
     if (service && A.scaled) {
         // ssq is [row][tile]; lane group g adds tiles [g*per, (g+1)*per) of row t, four at a time, in order
         const int nt = P.d / 16, per = nt / 4;
-        const f32x4 *sp = reinterpret_cast<const f32x4 *>(P.ssq + (size_t)t * nt + g * per);
+        const f32x4 *sp = reinterpret_cast<const f32x4 *>(X.ssq_in + (size_t)t * nt + g * per);
         float ss = 0.f;
         for (int c0 = 0; c0 < per / 4; c0 += 16) {
             f32x4 v[16];
@@ -500,7 +571,7 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
         ss += __shfl_xor(ss, 32, 64);
         rs_row = rsqrtf(ss / (float)P.d + P.eps);
     }
-    ts_mark(P, TS_PROLOGUE);
+    ts_mark(P, X, TS_PROLOGUE);
     int parity = 0;
 #pragma unroll 1
     for (int item = wg; item < A.n_items; item += nwg, parity ^= 1) {
@@ -525,7 +596,7 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
         // (which uses the other buffer) while the service wave reduces in a fixed order and applies the epilogue
         lds_sync();
         if (service) {
-            if (item + nwg >= A.n_items) ts_mark(P, TS_LOOP);
+            if (item + nwg >= A.n_items) ts_mark(P, X, TS_LOOP);
             const float rs = rs_row;
             if (EPI == EPI_SWIGLU) {              // TG == 2: tile 0 = gate, tile 1 = up, same 16 features
                 f32x4 gsum = rb[lane], usum = rb[64 + lane];
@@ -543,10 +614,10 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
                     }
                     u32x2 hi, lo;
                     split4(f, hi, lo);
-                    const __amdgpu_buffer_rsrc_t rf = co_rsrc(P.act, 2 * (P.act_plane * 2));
+                    const __amdgpu_buffer_rsrc_t rf = co_rsrc(X.ffn_a, 2 * (P.ffn_plane * 2));
                     const int off = (int)(((size_t)t * P.F + item * 16 + 4 * g) * 2);
                     co_st64(rf, off, hi);
-                    co_st64(rf, off + (int)(P.act_plane * 2), lo);
+                    co_st64(rf, off + (int)(P.ffn_plane * 2), lo);
                 }
             } else {
 #pragma unroll
@@ -557,8 +628,8 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
                     sum *= rs;
                     f32x4 hcur = hfirst[j];
                     if (EPI == EPI_RESID && item != wg && valid)
-                        hcur = *reinterpret_cast<const f32x4 *>(P.h + (size_t)t * P.d + (item * TG + j) * 16 + 4 * g);
-                    gemm_epilogue<TG, EPI>(P, A, item, j, sum, lane, hcur);
+                        hcur = *reinterpret_cast<const f32x4 *>(X.h_in + (size_t)t * P.d + (item * TG + j) * 16 + 4 * g);
+                    gemm_epilogue<TG, EPI>(P, X, A, item, j, sum, lane, hcur);
                 }
             }
         }
@@ -569,14 +640,15 @@ __device__ __forceinline__ void gemm_phase(const FusedParams &P, const GemmArgs 
 
 // Block attention for one 16-row tile per sequence (m <= 16).
 template <int DH>
-__device__ void phase_attn(const FusedParams &P, int layer, char *smem, int wg, int nwg) {
+__device__ __noinline__ void phase_attn(CParams &P, int layer, char *smem, int wg, int nwg) {
+    const PhaseBufs X = make_bufs(P, PH_ATTN, layer, 0);
     constexpr int PS = DH + 4;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int col = lane & 15, g = lane >> 4;
     float *lacc = reinterpret_cast<float *>(smem);              // [8 waves][16 rows][PS]
     __shared__ int s_last;
     const KvGeom geo{P.Bmax, P.H, P.dh, P.seq_pad, P.L, P.kperm};
-    const __amdgpu_buffer_rsrc_t ro = co_rsrc(P.act, 2 * (P.act_plane * 2));
+    const __amdgpu_buffer_rsrc_t ro = co_rsrc(X.attn_o, 2 * (P.q_plane * 2));
     const int items = P.B * P.H * P.kg_max;
     for (int item = wg; item < items; item += nwg) {
         const int kg = item % P.kg_max, hh = (item / P.kg_max) % P.H, b = item / (P.kg_max * P.H);
@@ -599,7 +671,7 @@ __device__ void phase_attn(const FusedParams &P, int layer, char *smem, int wg, 
             for (int s = 0; s < DH / 32; s++) {
                 qf[s][0] = qf[s][1] = u32x4{0u, 0u, 0u, 0u};
                 if (col < P.m) {
-                    const bf16_t *qp = P.q + (size_t)(b * P.m + col) * P.hd + hh * DH + s * 32 + 8 * g;
+                    const bf16_t *qp = X.q + (size_t)(b * P.m + col) * P.hd + hh * DH + s * 32 + 8 * g;
                     qf[s][0] = *reinterpret_cast<const u32x4 *>(qp);
                     qf[s][1] = *reinterpret_cast<const u32x4 *>(qp + P.q_plane);
                 }
@@ -729,7 +801,7 @@ __device__ void phase_attn(const FusedParams &P, int layer, char *smem, int wg, 
                 split4(o, hi, lo);
                 const int off = (int)(((size_t)(b * P.m + r) * P.hd + hh * DH + x4 * 4) * 2);
                 co_st64(ro, off, hi);
-                co_st64(ro, off + (int)(P.act_plane * 2), lo);
+                co_st64(ro, off + (int)(P.q_plane * 2), lo);
             }
             if (tid == 0) __hip_atomic_store(P.attn_cnt + b * P.H + hh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -737,10 +809,10 @@ __device__ void phase_attn(const FusedParams &P, int layer, char *smem, int wg, 
     }
 }
 
-__device__ void phase_trace(const FusedParams &P, int slot, int wg, int nwg) {
+__device__ __noinline__ void phase_trace(CParams &P, int slot, int wg, int nwg) {
     const size_t n = (size_t)P.M * P.d;
     for (size_t i = (size_t)wg * FUSED_THREADS + threadIdx.x; i < n; i += (size_t)nwg * FUSED_THREADS)
-        P.trace[(size_t)slot * n + i] = P.h[i];
+        P.trace[(size_t)slot * n + i] = P.xh[(size_t)16 * P.d * (P.fresh ? 2 * slot : 0) + i];
 }
 
 // Per-phase GEMM shapes: TG tiles per item, U k-steps per batch, NW batches in the register ring.
@@ -752,12 +824,12 @@ __device__ void phase_trace(const FusedParams &P, int slot, int wg, int nwg) {
 #define LMH2 2, EPI_LOGITS, true, 4, 4
 #define LMH1 1, EPI_LOGITS, true, 4, 8
 
-__device__ __forceinline__ GemmArgs gemm_args(const FusedParams &P, int phase, int layer) {
+__device__ __forceinline__ GemmArgs gemm_args(CParams &P, const PhaseBufs &X, int phase, int layer) {
     GemmArgs A;
     A.layer = layer;
     A.next_gain = nullptr;
     A.scaled = false;
-    A.bsrc = P.hg;          // h * gain: input of the projections that follow a norm
+    A.bsrc = X.hg_in;       // h * gain: input of the projections that follow a norm
     A.bplane = P.hg_plane;
     A.ldb = P.d;
     A.Wp = nullptr;
@@ -772,8 +844,8 @@ __device__ __forceinline__ GemmArgs gemm_args(const FusedParams &P, int phase, i
         A.Wp = P.layers[layer].o;
         A.KS = P.hd / 32;
         A.n_items = P.d / 16;
-        A.bsrc = P.act;
-        A.bplane = P.act_plane;
+        A.bsrc = X.attn_o;
+        A.bplane = P.q_plane;
         A.ldb = P.hd;
         A.next_gain = P.layers[layer].ffn_norm;
     } else if (phase == PH_GU) {
@@ -785,8 +857,8 @@ __device__ __forceinline__ GemmArgs gemm_args(const FusedParams &P, int phase, i
         A.Wp = P.layers[layer].down;
         A.KS = P.F / 32;
         A.n_items = P.d / 16;
-        A.bsrc = P.act;
-        A.bplane = P.act_plane;
+        A.bsrc = X.ffn_a;
+        A.bplane = P.ffn_plane;
         A.ldb = P.F;
         A.next_gain = layer + 1 < P.L ? P.layers[layer + 1].attn_norm : P.final_norm;
     } else if (phase == PH_LM) {
@@ -799,9 +871,10 @@ __device__ __forceinline__ GemmArgs gemm_args(const FusedParams &P, int phase, i
 }
 
 // issue the first weight batches of a GEMM phase (nothing for the other phases)
-__device__ __forceinline__ void prefetch_phase(const FusedParams &P, int phase, int layer, int wg, int nwg, u32x4 (&W)[W_RING]) {
+__device__ __forceinline__ void prefetch_phase(CParams &P, int phase, int layer, int wg, int nwg, u32x4 (&W)[W_RING]) {
     if (phase != PH_QKV && phase != PH_O && phase != PH_GU && phase != PH_DOWN && phase != PH_LM) return;
-    const GemmArgs A = gemm_args(P, phase, layer);
+    const PhaseBufs X{};      // only the weight side of the arguments is used here
+    const GemmArgs A = gemm_args(P, X, phase, layer);
     if (wg >= A.n_items || threadIdx.x < 64) return;     // wave 0 polls the barrier: see gemm_phase
 #define FUSED_PF(SHAPE) FUSED_PF_I(SHAPE)
 #define FUSED_PF_I(TGv, EPIv, BLv, Uv, NWv)                  \
@@ -826,7 +899,7 @@ __device__ __forceinline__ void prefetch_phase(const FusedParams &P, int phase, 
 }
 
 template <int DH>
-__device__ __forceinline__ void run_phase(const FusedParams &P, int phase, int layer, char *smem, int wg, int nwg, u32x4 (&W)[W_RING],
+__device__ __forceinline__ void run_phase(CParams &P, const PhaseBufs &X, int phase, int layer, char *smem, int wg, int nwg, u32x4 (&W)[W_RING],
                           int prefetched) {
     if (phase == PH_EMBED) {
         phase_embed(P, wg, nwg);
@@ -835,55 +908,64 @@ __device__ __forceinline__ void run_phase(const FusedParams &P, int phase, int l
     } else if (phase == PH_TRACE) {
         phase_trace(P, layer, wg, nwg);
     } else {
-        const GemmArgs A = gemm_args(P, phase, layer);
+        const GemmArgs A = gemm_args(P, X, phase, layer);
         if (phase == PH_QKV) {
             if (P.tg_qkv == 3)
-                gemm_phase<QKV3>(P, A, smem, wg, nwg, W, prefetched);
+                gemm_phase<QKV3>(P, X, A, smem, wg, nwg, W, prefetched);
             else
-                gemm_phase<QKV1>(P, A, smem, wg, nwg, W, prefetched);
+                gemm_phase<QKV1>(P, X, A, smem, wg, nwg, W, prefetched);
         } else if (phase == PH_O) {
-            gemm_phase<OPRJ>(P, A, smem, wg, nwg, W, prefetched);
+            gemm_phase<OPRJ>(P, X, A, smem, wg, nwg, W, prefetched);
         } else if (phase == PH_GU) {
-            gemm_phase<GUPR>(P, A, smem, wg, nwg, W, prefetched);
+            gemm_phase<GUPR>(P, X, A, smem, wg, nwg, W, prefetched);
         } else if (phase == PH_DOWN) {
-            gemm_phase<DOWN>(P, A, smem, wg, nwg, W, prefetched);
+            gemm_phase<DOWN>(P, X, A, smem, wg, nwg, W, prefetched);
         } else if (phase == PH_LM) {
             if (P.tg_lm == 2)
-                gemm_phase<LMH2>(P, A, smem, wg, nwg, W, prefetched);
+                gemm_phase<LMH2>(P, X, A, smem, wg, nwg, W, prefetched);
             else
-                gemm_phase<LMH1>(P, A, smem, wg, nwg, W, prefetched);
+                gemm_phase<LMH1>(P, X, A, smem, wg, nwg, W, prefetched);
         }
     }
 }
 
 // one launch per phase
 template <int DH>
-__global__ __launch_bounds__(FUSED_THREADS, 1) void k_fused_phase(FusedParams P, int phase, int layer) {
+__global__ __launch_bounds__(FUSED_THREADS, 1) void k_fused_phase(const FusedParams P_arg, int phase, int layer) {
     extern __shared__ __align__(16) char smem[];
+    CParams &P = P_arg;
     u32x4 W[W_RING];
-    run_phase<DH>(P, phase, layer, smem, blockIdx.x, gridDim.x, W, 0);
+    const PhaseBufs X = make_bufs(P, phase, layer, 0);
+    run_phase<DH>(P, X, phase, layer, smem, blockIdx.x, gridDim.x, W, 0);
 }
 
 // the whole forward in one launch
 template <int DH>
-__global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(FusedParams P) {
+__global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(const FusedParams P_arg) {
     extern __shared__ __align__(16) char smem[];
+    CParams &P = P_arg;
     const int wg = blockIdx.x, nwg = gridDim.x;
-    unsigned long long epoch = P.bar_base;   // device-wide barriers completed before this launch
+    unsigned epoch = P.bar_base;             // device-wide barriers completed before this launch
     u32x4 W[W_RING];                             // weight ring, carried across phases
-    P.ts_slot = 0;
+    int ts_slot = 0;
+    // Lines an earlier launch left in this XCD's L2 or this CU's L1 may be stale now (other XCDs have
+    // rewritten the exchange buffers and cache rows since): drop them once, before the first barrier.
+    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     // run a phase, start streaming the next phase's weights, then wait for everyone
 #define FUSED_STEP(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER)          \
     FUSED_STEP_I(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER, ((PHASE) != PH_EMBED && (PHASE) != PH_ATTN))
 #define FUSED_STEP_I(PHASE, LAYER, PRE, NEXT_PHASE, NEXT_LAYER, GEMM)  \
-    ts_mark(P, TS_START);                                              \
-    run_phase<DH>(P, PHASE, LAYER, smem, wg, nwg, W, (PRE) ? P.pf : 0); \
-    ts_mark(P, TS_EPILOGUE);                                           \
-    grid_arrive(P, ++epoch, GEMM);                                     \
-    prefetch_phase(P, NEXT_PHASE, NEXT_LAYER, wg, nwg, W);             \
-    grid_wait(P, epoch);                                               \
-    ts_mark(P, TS_BARRIER);                                            \
-    P.ts_slot += TS_PER_PHASE;
+    {                                                                  \
+        const PhaseBufs X = make_bufs(P, PHASE, LAYER, ts_slot);       \
+        ts_mark(P, X, TS_START);                                       \
+        run_phase<DH>(P, X, PHASE, LAYER, smem, wg, nwg, W, (PRE) ? P.pf : 0); \
+        ts_mark(P, X, TS_EPILOGUE);                                    \
+        grid_arrive(P, ++epoch, GEMM);                                 \
+        prefetch_phase(P, NEXT_PHASE, NEXT_LAYER, wg, nwg, W);         \
+        grid_wait(P, epoch);                                           \
+        ts_mark(P, X, TS_BARRIER);                                     \
+        ts_slot += TS_PER_PHASE;                                       \
+    }
     FUSED_STEP(PH_EMBED, 0, false, PH_QKV, 0)
     if (P.trace) phase_trace(P, 0, wg, nwg);
     for (int l = 0; l < P.L; l++) {
@@ -903,9 +985,12 @@ __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(FusedPar
     }
 #undef FUSED_STEP
 #undef FUSED_STEP_I
-    ts_mark(P, TS_START);
-    run_phase<DH>(P, PH_LM, 0, smem, wg, nwg, W, P.pf);
-    ts_mark(P, TS_EPILOGUE);
+    {
+        const PhaseBufs X = make_bufs(P, PH_LM, 0, ts_slot);
+        ts_mark(P, X, TS_START);
+        run_phase<DH>(P, X, PH_LM, 0, smem, wg, nwg, W, P.pf);
+        ts_mark(P, X, TS_EPILOGUE);
+    }
 }
 
 // ------------------------------------------------------------------------------- host side
@@ -914,15 +999,16 @@ struct FusedState {
     FusedLayer *layers = nullptr;
     float *cs = nullptr;
     unsigned *attn_cnt = nullptr;
-    unsigned long long *bar = nullptr;
+    unsigned char *bar = nullptr;
     unsigned *err = nullptr;
-    unsigned long long bar_epoch = 0;
+    unsigned bar_epoch = 0;
     int grid = 0, kg_max = 0, tg_qkv = 1, tg_lm = 1;
     size_t lds_bytes = 0;
     int lds_red_off = 0, lds_rstd_off = 0;
-    bf16_t *hg = nullptr;
-    float *ssq = nullptr;
+    float *xh = nullptr, *xssq = nullptr;
+    bf16_t *xhg = nullptr, *xq = nullptr, *xattn = nullptr, *xffn = nullptr;
     int m_limit = 0;
+    int fresh = 1;     // tuning knob (env CSD_FUSED_FRESH)
     int pf = 64;       // tuning knob (env CSD_FUSED_PF): ring slots prefetched across a barrier
     int mode = 2;      // 0: off, 1: one launch per phase, 2: persistent
 };
@@ -959,6 +1045,7 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     if (d % 256 || hd % 32 || F % 32 || V % 16 || (F / 16) < 1) return CSD_OK;
     FusedState *fs = new FusedState();
     fs->mode = mode;
+    if (const char *e = getenv("CSD_FUSED_FRESH")) fs->fresh = atoi(e) ? 1 : 0;
     if (const char *e = getenv("CSD_FUSED_PF")) fs->pf = atoi(e) < 0 ? 0 : atoi(e);
     fs->m_limit = m_limit < mod->m_max ? m_limit : mod->m_max;
     const int m_cap = fs->m_limit;
@@ -967,7 +1054,7 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     fs->lds_red_off = (int)((act_bytes + 255) / 256 * 256);
     fs->lds_rstd_off = fs->lds_red_off + red_bytes;
     fs->lds_bytes = (size_t)fs->lds_rstd_off + 256;
-    fs->grid = cus;
+    fs->grid = cus < BAR_MAX_WG ? cus : BAR_MAX_WG;
     fs->kg_max = (mod->seq_pad + 255) / 256;
     fs->tg_qkv = ((3 * hd / 16) / 3 >= cus) ? 3 : 1;
     fs->tg_lm = ((V / 16) % 2 == 0) ? 2 : 1;
@@ -981,10 +1068,16 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     if ((rc = fused_alloc(mod, (void **)&fs->layers, sizeof(FusedLayer) * c.n_layers, false, st)) != CSD_OK) return rc;
     CSD_HIP(hipMemcpy(fs->layers, hl.data(), sizeof(FusedLayer) * c.n_layers, hipMemcpyHostToDevice));
     if ((rc = fused_alloc(mod, (void **)&fs->cs, sizeof(float) * 16 * dh, false, st)) != CSD_OK) return rc;
-    if ((rc = fused_alloc(mod, (void **)&fs->hg, sizeof(bf16_t) * 2 * 16 * (size_t)d, true, st)) != CSD_OK) return rc;
-    if ((rc = fused_alloc(mod, (void **)&fs->ssq, sizeof(float) * 16 * (size_t)(d / 16), true, st)) != CSD_OK) return rc;
+    // exchange buffers: one instance per producing phase (see FusedParams), 16 rows each
+    const size_t L = (size_t)c.n_layers, slots = 2 * L + 1;
+    if ((rc = fused_alloc(mod, (void **)&fs->xh, sizeof(float) * slots * 16 * d, true, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->xhg, sizeof(bf16_t) * slots * 2 * 16 * d, true, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->xssq, sizeof(float) * slots * 16 * (d / 16), true, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->xq, sizeof(bf16_t) * L * 2 * 16 * hd, true, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->xattn, sizeof(bf16_t) * L * 2 * 16 * hd, true, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->xffn, sizeof(bf16_t) * L * 2 * 16 * F, true, st)) != CSD_OK) return rc;
     if ((rc = fused_alloc(mod, (void **)&fs->attn_cnt, sizeof(unsigned) * c.max_batch * c.n_heads, true, st)) != CSD_OK) return rc;
-    if ((rc = fused_alloc(mod, (void **)&fs->bar, 8 * BAR_STRIDE * 64, true, st)) != CSD_OK) return rc;
+    if ((rc = fused_alloc(mod, (void **)&fs->bar, BAR_BYTES > 16384 ? BAR_BYTES : 16384, true, st)) != CSD_OK) return rc;
     if ((rc = fused_alloc(mod, (void **)&fs->err, 256, true, st)) != CSD_OK) return rc;
     // attention partials: [Bmax][H][kg_max][16][dh+4]; reuse the model's buffer when large enough
     const size_t need = sizeof(float) * (size_t)c.max_batch * c.n_heads * fs->kg_max * 16 * (dh + 4);
@@ -1045,11 +1138,18 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     P.tg_qkv = fs->tg_qkv;
     P.tg_lm = fs->tg_lm;
     P.pf = fs->pf;
+    P.fresh = fs->fresh;
     P.lds_red_off = fs->lds_red_off;
     P.lds_rstd_off = fs->lds_rstd_off;
-    P.hg = fs->hg;
+    P.xh = fs->xh;
+    P.xhg = fs->xhg;
+    P.xssq = fs->xssq;
+    P.xq = fs->xq;
+    P.xattn = fs->xattn;
+    P.xffn = fs->xffn;
     P.hg_plane = (size_t)16 * c.d_model;
-    P.ssq = fs->ssq;
+    P.q_plane = (size_t)16 * mod->hd;
+    P.ffn_plane = (size_t)16 * c.d_ffn;
     P.eps = c.rms_eps;
     P.scale = 1.0f / sqrtf((float)c.head_dim);
     P.theta = c.rope_theta;
@@ -1059,11 +1159,6 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     P.layers = fs->layers;
     P.final_norm = mod->final_norm;
     P.lm = (const u32x4 *)mod->lm.data;
-    P.h = mod->h;
-    P.q = (bf16_t *)mod->qbuf;
-    P.q_plane = mod->q_plane;
-    P.act = (bf16_t *)mod->act;
-    P.act_plane = mod->act_plane;
     P.cs = fs->cs;
     P.kv = (bf16_t *)kv;
     P.attn_part = mod->fused_attn_part;
@@ -1073,11 +1168,10 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     P.err = fs->err;
     P.trace = mod->trace;
     P.ts = (unsigned long long *)mod->fused_ts;
-    P.ts_slot = 0;
     const dim3 grid(fs->grid), block(FUSED_THREADS);
     if (fs->mode == 2) {
         P.bar_base = fs->bar_epoch;
-        fs->bar_epoch += (unsigned long long)(1 + 5 * c.n_layers);
+        fs->bar_epoch += (unsigned)(1 + 5 * c.n_layers);
         ProfScope ps(mod, st, CSD_PROF_GEMM);
         if (c.head_dim == 128)
             hipLaunchKernelGGL((k_verify_persistent<128>), grid, block, fs->lds_bytes, st, P);
