@@ -8,7 +8,7 @@
 
 #pragma clang fp contract(off)
 
-#define ACC_THREADS 256
+#define ACC_THREADS 1024
 
 // floor(r * 2^40) for a finite fp32 r in [0, 2^24): exact, by shifting the significand
 __device__ __forceinline__ unsigned long long fixed40(float r) {
@@ -62,13 +62,67 @@ __device__ int block_argmax(const float *__restrict__ row, int V, ArgMax *red) {
     return t.i == 0x7FFFFFFF ? 0 : t.i;
 }
 
+// Sum of the fixed-point weights of tokens [v0, v1) (v0 a multiple of 4): 16-byte loads when the rows
+// allow it.  Exact integer arithmetic, so the grouping does not matter.
+__device__ __forceinline__ unsigned long long range_weight(const float *__restrict__ prow, const float *__restrict__ qrow,
+                                                           int x, float lenience, bool residual, int v0, int v1, bool vec) {
+    unsigned long long sum = 0ull;
+    int v = v0;
+    if (vec) {
+        for (; v + 4 <= v1; v += 4) {
+            const float4 pv = *reinterpret_cast<const float4 *>(prow + v);
+            float w[4] = {pv.x, pv.y, pv.z, pv.w};
+            if (residual) {
+                float qv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (qrow) {
+                    const float4 t = *reinterpret_cast<const float4 *>(qrow + v);
+                    qv[0] = t.x, qv[1] = t.y, qv[2] = t.z, qv[3] = t.w;
+                } else if (x >= v && x < v + 4) {
+                    qv[x - v] = 1.0f;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const float df = __fsub_rn(__fmul_rn(lenience, w[i]), qv[i]);
+                    w[i] = df > 0.0f ? df : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; i++) sum += fixed40(w[i]);
+        }
+    }
+    for (; v < v1; v++) sum += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
+    return sum;
+}
+
+// Exclusive prefix of one 64-bit value per thread over the block, in thread order, and the block total.
+__device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long mine, unsigned long long *wave_tot,
+                                                                   unsigned long long &total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    unsigned long long incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    __syncthreads();
+    if (lane == 63) wave_tot[w] = incl;
+    __syncthreads();
+    unsigned long long before = 0ull;
+    total = 0ull;
+    for (int i = 0; i < nw; i++) {
+        if (i == w) before = total;
+        total += wave_tot[i];
+    }
+    return before + incl - mine;
+}
+
 __global__ __launch_bounds__(ACC_THREADS) void k_accept(
     const float *__restrict__ p, const float *__restrict__ q, const uint8_t *__restrict__ q_onehot,
     const int32_t *__restrict__ draft, int32_t draft_stride, const float *__restrict__ u_acc,
     const float *__restrict__ u_samp, int32_t k, int32_t V, float lenience, int32_t mode,
     int32_t *__restrict__ n_accepted, int32_t *__restrict__ next_token) {
     __shared__ ArgMax red_am[ACC_THREADS / 64];
-    __shared__ unsigned long long part[ACC_THREADS];
+    __shared__ unsigned long long wave_tot[ACC_THREADS / 64];
     __shared__ int s_n;
     const int b = blockIdx.x;
     const float *pb = p + (size_t)b * (k + 1) * V;
@@ -96,18 +150,27 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
         return;
     }
 
-    if (threadIdx.x == 0) {
-        int n = 0;
-        for (; n < k; n++) {
-            const int x = db[n];
-            if (x < 0 || x >= V) break;                      // an invalid draft id is a rejection
-            const bool dense = qb && !(q_onehot && q_onehot[n]);
-            const float qx = dense ? qb[(size_t)n * V + x] : 1.0f;
-            const float lhs = __fmul_rn(u_acc[(size_t)b * k + n], qx);
-            const float rhs = __fmul_rn(lenience, pb[(size_t)n * V + x]);
-            if (!(lhs < rhs)) break;
+    // acceptance tests of all k positions at once (one lane each); the first failure ends the prefix
+    if (threadIdx.x < 64) {
+        int n = k;
+        for (int base = 0; base < k && n == k; base += 64) {
+            const int i = base + (int)threadIdx.x;
+            bool ok = true;
+            if (i < k) {
+                const int x = db[i];
+                ok = false;
+                if (x >= 0 && x < V) {                           // an invalid draft id is a rejection
+                    const bool dense = qb && !(q_onehot && q_onehot[i]);
+                    const float qx = dense ? qb[(size_t)i * V + x] : 1.0f;
+                    const float lhs = __fmul_rn(u_acc[(size_t)b * k + i], qx);
+                    const float rhs = __fmul_rn(lenience, pb[(size_t)i * V + x]);
+                    ok = lhs < rhs;
+                }
+            }
+            const unsigned long long bad = __ballot(!ok);
+            if (bad) n = base + __ffsll((long long)bad) - 1;
         }
-        s_n = n;
+        if (threadIdx.x == 0) s_n = n;
     }
     __syncthreads();
     const int n = s_n;
@@ -116,22 +179,15 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
     int x = residual ? db[n] : -1;
     const float *qrow = nullptr;
     if (residual && qb && !(q_onehot && q_onehot[n])) qrow = qb + (size_t)n * V;
+    const bool vec = ((uintptr_t)prow % 16 == 0) && (!qrow || (uintptr_t)qrow % 16 == 0);
 
-    const int chunk = (V + ACC_THREADS - 1) / ACC_THREADS;
-    const int v0 = threadIdx.x * chunk, v1 = min(V, v0 + chunk);
-    unsigned long long Z = 0ull, excl = 0ull;
+    // thread t owns tokens [v0, v1), a whole number of 4-token groups
+    const int chunk = ((V + ACC_THREADS - 1) / ACC_THREADS + 3) / 4 * 4;
+    const int v0 = min(V, (int)threadIdx.x * chunk), v1 = min(V, v0 + chunk);
+    unsigned long long Z = 0ull, excl = 0ull, mine = 0ull;
     for (int pass = 0; pass < 2; pass++) {
-        unsigned long long local = 0ull;
-        for (int v = v0; v < v1; v++) local += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
-        __syncthreads();
-        part[threadIdx.x] = local;
-        __syncthreads();
-        Z = 0ull;
-        excl = 0ull;
-        for (int i = 0; i < ACC_THREADS; i++) {              // 256 adds per thread: exact, order-free
-            if (i == threadIdx.x) excl = Z;
-            Z += part[i];
-        }
+        mine = range_weight(prow, qrow, x, lenience, residual, v0, v1, vec);
+        excl = block_exclusive_scan(mine, wave_tot, Z);
         if (Z != 0ull || !residual) break;
         residual = false;                                    // all-zero residual: draw from the reviewer's row
     }
@@ -146,8 +202,6 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
     const unsigned long long u24 = fixed40(u_samp[b]) >> 16;
     const unsigned long long hi = __umul64hi(u24, Z), lo = u24 * Z;
     const unsigned long long T = (hi << 40) | (lo >> 24);
-    unsigned long long mine = 0ull;
-    for (int v = v0; v < v1; v++) mine += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
     if (T >= excl && T < excl + mine) {                      // exactly one thread owns T
         unsigned long long cum = excl;
         int tok = v1 - 1;
@@ -160,12 +214,39 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
     }
 }
 
-// one workgroup per row: p = exp((x - max) / T) / sum
-__global__ __launch_bounds__(256) void k_softmax(const float *logits, float *probs, int32_t V,
-                                                 float inv_t) {
-    __shared__ float red[16];
+// one workgroup per row: p = exp((x - max) / T) / sum.  Each thread keeps its SM_PER elements in
+// registers between the three steps (rows longer than SM_THREADS * SM_PER take the generic loop).
+#define SM_THREADS 1024
+#define SM_PER 32
+__global__ __launch_bounds__(SM_THREADS) void k_softmax(const float *logits, float *probs, int32_t V, float inv_t) {
+    __shared__ float red[SM_THREADS / 64];
     const float *x = logits + (size_t)blockIdx.x * V;
     float *y = probs + (size_t)blockIdx.x * V;
+    if (V <= SM_THREADS * SM_PER) {
+        float val[SM_PER];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < SM_PER; i++) {
+            const int v = i * SM_THREADS + (int)threadIdx.x;
+            val[i] = v < V ? x[v] * inv_t : -INFINITY;
+            mx = fmaxf(mx, val[i]);
+        }
+        mx = block_max(mx, red);
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < SM_PER; i++) {
+            val[i] = expf(val[i] - mx);          // exp(-inf) = 0 for the padding
+            s += val[i];
+        }
+        s = block_sum(s, red);
+        const float r = 1.0f / s;
+#pragma unroll
+        for (int i = 0; i < SM_PER; i++) {
+            const int v = i * SM_THREADS + (int)threadIdx.x;
+            if (v < V) y[v] = val[i] * r;
+        }
+        return;
+    }
     float mx = -INFINITY;
     for (int v = threadIdx.x; v < V; v += blockDim.x) mx = fmaxf(mx, x[v] * inv_t);
     mx = block_max(mx, red);
@@ -183,7 +264,7 @@ __global__ __launch_bounds__(256) void k_softmax(const float *logits, float *pro
 int32_t csd_softmax_enqueue(const float *logits, float *probs, int64_t rows, int32_t V, float temperature,
                             hipStream_t st) {
     if (rows <= 0) return CSD_OK;
-    hipLaunchKernelGGL(k_softmax, dim3((unsigned)rows), dim3(256), 0, st, logits, probs, V, 1.0f / temperature);
+    hipLaunchKernelGGL(k_softmax, dim3((unsigned)rows), dim3(SM_THREADS), 0, st, logits, probs, V, 1.0f / temperature);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }

@@ -378,23 +378,25 @@ __device__ __forceinline__ void gemm_epilogue(CParams &P, const PhaseBufs &X, co
 
 // Copy the two planes of a row-major activation buffer [M][ld] into LDS in fragment order:
 // 16-byte unit ((ks*2 + plane)*4 + g)*M + row holds k = 32 ks + 8 g .. +7 of that row.
+#define COPY_ROWS 6
 __device__ __forceinline__ void copy_to_lds(CParams &P, const bf16_t *__restrict__ src, size_t plane, int ld,
                                             char *smem) {
     const int tid = threadIdx.x, M = P.M, ld8 = ld / 8;
     u32x4 *act = reinterpret_cast<u32x4 *>(smem);
     for (int kc = tid; kc < ld8; kc += FUSED_THREADS) {
         const int ks = kc >> 2, g = kc & 3;
-        for (int r0 = 0; r0 < M; r0 += 4) {
-            u32x4 a[4][2];
+        // COPY_ROWS rows x 2 planes in flight per thread: the usual block (k+1 <= 6 rows) takes one memory round trip
+        for (int r0 = 0; r0 < M; r0 += COPY_ROWS) {
+            u32x4 a[COPY_ROWS][2];
 #pragma unroll
-            for (int u = 0; u < 4; u++)
+            for (int u = 0; u < COPY_ROWS; u++)
                 if (r0 + u < M) {
                     const bf16_t *sp = src + (size_t)(r0 + u) * ld + kc * 8;
                     a[u][0] = *reinterpret_cast<const u32x4 *>(sp);
                     a[u][1] = *reinterpret_cast<const u32x4 *>(sp + plane);
                 }
 #pragma unroll
-            for (int u = 0; u < 4; u++)
+            for (int u = 0; u < COPY_ROWS; u++)
                 if (r0 + u < M) {
                     act[((ks * 2 + 0) * 4 + g) * M + r0 + u] = a[u][0];
                     act[((ks * 2 + 1) * 4 + g) * M + r0 + u] = a[u][1];
