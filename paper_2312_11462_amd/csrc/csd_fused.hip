@@ -379,6 +379,7 @@ __device__ __forceinline__ void gemm_epilogue(CParams &P, const PhaseBufs &X, co
 // Copy the two planes of a row-major activation buffer [M][ld] into LDS in fragment order:
 // 16-byte unit ((ks*2 + plane)*4 + g)*M + row holds k = 32 ks + 8 g .. +7 of that row.
 #define COPY_ROWS 6
+#define COPY_ROWS 6
 __device__ __forceinline__ void copy_to_lds(CParams &P, const bf16_t *__restrict__ src, size_t plane, int ld,
                                             char *smem) {
     const int tid = threadIdx.x, M = P.M, ld8 = ld / 8;
