@@ -786,17 +786,35 @@ __device__ __noinline__ void phase_attn(CParams &P, int layer, char *smem, int w
         if (s_last) {           // the last key group to finish merges all of them
             for (int idx = tid; idx < P.m * (DH / 4); idx += FUSED_THREADS) {
                 const int r = idx / (DH / 4), x4 = idx % (DH / 4);
-                float mstar = -INFINITY;
-                for (int c = 0; c < n_groups; c++)
-                    mstar = fmaxf(mstar, co_ld32f(rp, (int)(((size_t)c * part_elems + (size_t)r * PS + DH) * 4)));
+                // eight groups' states in flight together (one memory round trip for the usual case), groups
+                // combined in index order
+                float mstar = -INFINITY, den = 0.f;
                 f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
-                float den = 0.f;
-                for (int c = 0; c < n_groups; c++) {
-                    const int base = (int)(((size_t)c * part_elems + (size_t)r * PS) * 4);
-                    const float mc = co_ld32f(rp, base + DH * 4);
-                    const float wgt = (mc == -INFINITY) ? 0.f : expf(mc - mstar);
-                    num += co_ld128f(rp, base + x4 * 16) * wgt;
-                    den += co_ld32f(rp, base + (DH + 1) * 4) * wgt;
+                for (int c0 = 0; c0 < n_groups; c0 += 8) {
+                    float mc[8], dc[8];
+                    f32x4 nc[8];
+#pragma unroll
+                    for (int u = 0; u < 8; u++) {
+                        const int c = min(c0 + u, n_groups - 1);
+                        const int base = (int)(((size_t)c * part_elems + (size_t)r * PS) * 4);
+                        mc[u] = co_ld32f(rp, base + DH * 4);
+                        dc[u] = co_ld32f(rp, base + (DH + 1) * 4);
+                        nc[u] = co_ld128f(rp, base + x4 * 16);
+                    }
+                    float mchunk = mstar;
+#pragma unroll
+                    for (int u = 0; u < 8; u++)
+                        if (c0 + u < n_groups) mchunk = fmaxf(mchunk, mc[u]);
+                    const float a = (mstar == -INFINITY) ? 0.f : expf(mstar - mchunk);
+                    num *= a;
+                    den *= a;
+#pragma unroll
+                    for (int u = 0; u < 8; u++) {
+                        const float wgt = (c0 + u >= n_groups || mc[u] == -INFINITY) ? 0.f : expf(mc[u] - mchunk);
+                        num += nc[u] * wgt;
+                        den += dc[u] * wgt;
+                    }
+                    mstar = mchunk;
                 }
                 const float inv = den > 0.f ? 1.0f / den : 0.f;
                 float o[4] = {num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
