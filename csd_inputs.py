@@ -145,7 +145,7 @@ def default_next_table(vocab: int, seed: int, device="cpu") -> torch.Tensor:
 @dataclass
 class ModelShape:
     name: str
-    arch: int          # 0: LLaMA-style (RMSNorm, RoPE, SwiGLU)
+    arch: int          # 0: LLaMA-style (RMSNorm, RoPE, SwiGLU); 1: T5-style decoder (relative bias, cross-attention, gated GELU)
     dtype: str         # "fp32" | "bf16"  (weights and KV cache)
     n_layers: int
     d_model: int
@@ -155,13 +155,19 @@ class ModelShape:
     vocab: int
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
+    enc_len: int = 0   # arch 1: rows of the encoder output the decoder cross-attends
 
     def n_weights(self) -> int:
-        return 3 + 9 * self.n_layers
+        return 3 + 9 * self.n_layers if self.arch == 0 else 4 + 14 * self.n_layers
 
     def streamed_params(self) -> int:
+        """Matrix elements one review forward reads (the embedding is gathered, not streamed; the
+        cross-attention key/value projections run once per prompt, not per step)."""
         d, f, v, L = self.d_model, self.d_ffn, self.vocab, self.n_layers
-        return L * (4 * d * d + 3 * d * f) + d * v
+        hd = self.n_heads * self.head_dim
+        if self.arch == 0:
+            return L * (4 * d * hd + 3 * d * f) + d * v
+        return L * (6 * d * hd + 3 * d * f) + d * v
 
     def as_dict(self):
         return asdict(self)
@@ -170,6 +176,8 @@ class ModelShape:
 TINY = ModelShape("tiny", 0, "fp32", 2, 64, 4, 16, 256, 512)
 DRAFT_160M = ModelShape("draft160m", 0, "bf16", 12, 768, 12, 64, 3072, 32000)
 TARGET_7B = ModelShape("target7b", 0, "bf16", 32, 4096, 32, 128, 11008, 32000)
+T5_TINY = ModelShape("t5tiny", 1, "fp32", 2, 64, 4, 16, 128, 512, rms_eps=1e-6, enc_len=24)
+T5XXL_DEC = ModelShape("t5xxl_dec", 1, "bf16", 24, 4096, 64, 64, 10240, 32128, rms_eps=1e-6, enc_len=512)
 
 # Workloads named after the benchmark configurations: batch, cached prefix, drafted tokens.
 WORKLOADS = {
@@ -177,38 +185,59 @@ WORKLOADS = {
     "draft160m":   dict(shape=DRAFT_160M, B=1, prefix=512, k=8, seed=0xC5D00002),
     "target7b":    dict(shape=TARGET_7B, B=1, prefix=1024, k=5, seed=0xC5D00003),
     "target7b_b8": dict(shape=TARGET_7B, B=8, prefix=2048, k=16, seed=0xC5D00003),
+    "t5xxl":       dict(shape=T5XXL_DEC, B=1, prefix=256, k=4, seed=0xC5D00004),
 }
+
+
+REL_BUCKETS = 32     # rows of the relative-position bias table of an arch-1 model
 
 
 def weight_names(shape: ModelShape):
     names = ["embed"]
+    per_layer = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down") if shape.arch == 0 else \
+                ("self_norm", "wq", "wk", "wv", "wo", "cross_norm", "cq", "ck", "cv", "co", "ffn_norm", "w0", "w1", "w_out")
     for l in range(shape.n_layers):
-        names += [f"l{l}.{w}" for w in
-                  ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
+        names += [f"l{l}.{w}" for w in per_layer]
     names += ["final_norm", "lm_head"]
+    if shape.arch == 1:
+        names.append("rel_bias")
     return names
 
 
 def weight_shapes(shape: ModelShape):
     d, f, v = shape.d_model, shape.d_ffn, shape.vocab
     hd = shape.n_heads * shape.head_dim
-    per_layer = [(d,), (d, hd), (d, hd), (d, hd), (hd, d), (d,), (d, f), (d, f), (f, d)]
-    return [(v, d)] + per_layer * shape.n_layers + [(d,), (d, v)]
+    if shape.arch == 0:
+        per_layer = [(d,), (d, hd), (d, hd), (d, hd), (hd, d), (d,), (d, f), (d, f), (f, d)]
+        return [(v, d)] + per_layer * shape.n_layers + [(d,), (d, v)]
+    per_layer = [(d,), (d, hd), (d, hd), (d, hd), (hd, d), (d,), (d, hd), (d, hd), (d, hd), (hd, d),
+                 (d,), (d, f), (d, f), (f, d)]
+    return [(v, d)] + per_layer * shape.n_layers + [(d,), (d, v), (REL_BUCKETS, shape.n_heads)]
 
 
 def make_weights(shape: ModelShape, seed: int, device="cpu", std: float = 0.02):
     """Canonical-order weight list.  Matrices are row-major [in][out] in the model
     dtype (bf16 = round-to-nearest-even of the fp32 draw); norm gains are fp32 ones."""
     out = []
+    names = weight_names(shape)
     for idx, shp in enumerate(weight_shapes(shape)):
         if len(shp) == 1:
             out.append(torch.ones(shp, dtype=torch.float32, device=device))
             continue
         w = normal(shp, std, seed, 0x1000 + idx, device)
-        if shape.dtype == "bf16":
+        if shape.dtype == "bf16" and names[idx] != "rel_bias":     # the small bias table stays fp32
             w = w.to(torch.bfloat16)
         out.append(w.contiguous())
     return out
+
+
+def encoder_output(shape: ModelShape, B: int, seed: int, device="cpu", std: float = 1.0):
+    """Seeded stand-in for the encoder's final hidden states [B][enc_len][d] of an arch-1 model (fp32
+    holding values exact in the model dtype)."""
+    x = normal((B, shape.enc_len, shape.d_model), std, seed, 0x300000, device)
+    if shape.dtype == "bf16":
+        x = x.to(torch.bfloat16).to(torch.float32)
+    return x.contiguous()
 
 
 def synthetic_kv(shape: ModelShape, n_rows: int, seed: int, layer: int, b: int, device="cpu",

@@ -11,10 +11,14 @@
  *   - accept / reject / resample / extra token of speculative sampling  (Section 2)
  *   - lenience in sampling and in greedy review                         (Section 3.1)
  *   - Max-Gram matching with a bigram fallback                  (Section 3.3, App. A)
- * The paper names model families only (Section 5.1); the decoder here is the
- * LLaMA-style one the benchmark configurations spell out: RMSNorm, rotary position
- * embedding (half-split pairing), causal attention scaled by 1/sqrt(head_dim), SwiGLU,
- * no biases, untied LM head.
+ * The paper names model families only (Section 5.1); the decoders here are the two the
+ * benchmark configurations spell out.  arch 0, LLaMA-style: RMSNorm, rotary position
+ * embedding (half-split pairing), causal attention scaled by 1/sqrt(head_dim), SwiGLU, no
+ * biases, untied LM head.  arch 1, T5-style decoder (the FLAN-T5 reviewers of Section 5.1):
+ * RMS layer norm, no rotary embedding, unscaled causal self-attention with the bucketed
+ * relative-position bias of the T5 paper (32 buckets, maximum distance 128, one table for all
+ * layers), unmasked cross-attention over a fixed encoder output, gated tanh-GELU FFN, untied
+ * LM head.
  *
  * Arithmetic: every floating-point step of the forward is fp64 on the stored values.
  * Stored values are the weights and the KV-cache rows, both in the configuration's storage
@@ -39,7 +43,7 @@
 #endif
 
 typedef struct {
-    int32_t arch;      /* 0: LLaMA-style */
+    int32_t arch;      /* 0: LLaMA-style, 1: T5-style decoder with cross-attention */
     int32_t dtype;     /* 0: fp32 weights, 1: bf16 weights */
     int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
     int32_t max_batch, max_seq, max_block, enc_len;
@@ -55,6 +59,9 @@ typedef struct {
 
 enum { W_EMBED = 0, W_FINAL_NORM_FROM_END = 2, W_LM_HEAD_FROM_END = 1 };
 enum { L_ATTN_NORM = 0, L_WQ, L_WK, L_WV, L_WO, L_FFN_NORM, L_WGATE, L_WUP, L_WDOWN, L_COUNT };
+/* arch 1: 14 tensors per layer; after the LM head comes the relative-position bias table fp32 [32][H] */
+enum { T_SELF_NORM = 0, T_WQ, T_WK, T_WV, T_WO, T_CROSS_NORM, T_CQ, T_CK, T_CV, T_CO, T_FFN_NORM, T_W0, T_W1, T_WOUT, T_COUNT };
+enum { REL_BUCKETS = 32, REL_MAX_DISTANCE = 128 };
 
 int32_t csdo_threads(void) {
 #ifdef _OPENMP
@@ -66,8 +73,9 @@ int32_t csdo_threads(void) {
 
 int32_t csdo_model_create(const csdo_cfg *cfg, const void *const *weights, int32_t n_w, csdo_model **out) {
     if (!cfg || !weights || !out) return -1;
-    if (cfg->arch != 0) return -2;
-    if (n_w != 3 + L_COUNT * cfg->n_layers) return -2;
+    if (cfg->arch != 0 && cfg->arch != 1) return -2;
+    if (cfg->arch == 0 && n_w != 3 + L_COUNT * cfg->n_layers) return -2;
+    if (cfg->arch == 1 && (n_w != 4 + T_COUNT * cfg->n_layers || cfg->enc_len < 1)) return -2;
     if (cfg->head_dim % 2) return -2;
     csdo_model *m = (csdo_model *)calloc(1, sizeof *m);
     m->c = *cfg;
@@ -87,10 +95,23 @@ int32_t csdo_model_destroy(csdo_model *m) {
 
 void csdo_set_trace(csdo_model *m, double *trace) { m->trace = trace; }
 
-/* cache: double K[L][B][max_seq][H*dh] followed by V of the same shape */
+/* cache: double K[L][B][max_seq][H*dh] followed by V of the same shape; arch 1 appends the
+ * cross-attention keys and values Kc[L][B][enc_len][H*dh], Vc[...] (filled by csdo_cross_kv_init) */
+static size_t self_kv_elems(const csdo_cfg *c) {
+    return (size_t)2 * c->n_layers * c->max_batch * c->max_seq * c->n_heads * c->head_dim;
+}
 size_t csdo_kv_bytes(const csdo_model *m) {
     const csdo_cfg *c = &m->c;
-    return (size_t)2 * c->n_layers * c->max_batch * c->max_seq * c->n_heads * c->head_dim * sizeof(double);
+    size_t n = self_kv_elems(c);
+    if (c->arch == 1) n += (size_t)2 * c->n_layers * c->max_batch * c->enc_len * c->n_heads * c->head_dim;
+    return n * sizeof(double);
+}
+
+static double *cross_row(const csdo_model *m, double *kv, int which, int l, int b, int pos) {
+    const csdo_cfg *c = &m->c;
+    size_t hd = (size_t)c->n_heads * c->head_dim;
+    size_t per = (size_t)c->n_layers * c->max_batch * c->enc_len * hd;
+    return kv + self_kv_elems(c) + which * per + (((size_t)l * c->max_batch + b) * c->enc_len + pos) * hd;
 }
 
 static double *kv_row(const csdo_model *m, double *kv, int which, int l, int b, int pos) {
@@ -206,6 +227,48 @@ void csdo_rope(double *x, int dh, int pos, double theta) {
 
 static double silu(double z) { return z / (1.0 + exp(-z)); }
 
+/* tanh form of GELU: 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) */
+static double gelu_tanh(double z) {
+    return 0.5 * z * (1.0 + tanh(0.79788456080286535588 * (z + 0.044715 * z * z * z)));
+}
+
+/*
+ * Bucket of the T5 relative-position bias for a decoder (a query only looks back):
+ * distance n = query position - key position >= 0.  The first half of the buckets holds the
+ * distances 0 .. 15 exactly; the second half spaces the distances 16 .. 127 logarithmically,
+ * bucket 16 + floor(16 * ln(n/16) / ln(128/16)); anything farther shares the last bucket.
+ */
+int32_t csdo_rel_bucket(int32_t n) {
+    const int half = REL_BUCKETS / 2;
+    if (n < 0) n = 0;
+    if (n < half) return n;
+    int32_t b = half + (int32_t)(log((double)n / half) / log((double)REL_MAX_DISTANCE / half) * (REL_BUCKETS - half));
+    return b < REL_BUCKETS - 1 ? b : REL_BUCKETS - 1;
+}
+
+/* arch 1, once per prompt: project the encoder output [B][enc_len][d] (fp32 at the interface) to the
+ * cross-attention keys and values of every layer and store them in the cache's storage type */
+int32_t csdo_cross_kv_init(const csdo_model *mod, double *kv, const float *enc_out, int32_t B) {
+    const csdo_cfg *c = &mod->c;
+    if (c->arch != 1 || B < 1 || B > c->max_batch) return -2;
+    const int d = c->d_model, hd = c->n_heads * c->head_dim, E = c->enc_len;
+    double *x = (double *)malloc(sizeof(double) * (size_t)E * d);
+    double *y = (double *)malloc(sizeof(double) * (size_t)E * hd);
+    for (int b = 0; b < B; b++) {
+        for (size_t i = 0; i < (size_t)E * d; i++) x[i] = (double)enc_out[(size_t)b * E * d + i];
+        for (int l = 0; l < c->n_layers; l++) {
+            const void **lw = mod->w + 1 + (size_t)l * T_COUNT;
+            for (int which = 0; which < 2; which++) {
+                matmul(x, E, d, lw[which == 0 ? T_CK : T_CV], c->dtype, hd, y);
+                for (int j = 0; j < E; j++)
+                    for (int z = 0; z < hd; z++) cross_row(mod, kv, which, l, b, j)[z] = to_cache(mod, y[(size_t)j * hd + z]);
+            }
+        }
+    }
+    free(x); free(y);
+    return 0;
+}
+
 /* numerically plain softmax with max subtraction */
 void csdo_softmax(const double *logits, int n, double inv_temperature, double *p) {
     double mx = -INFINITY;
@@ -213,6 +276,122 @@ void csdo_softmax(const double *logits, int n, double inv_temperature, double *p
     double s = 0.0;
     for (int i = 0; i < n; i++) { p[i] = exp(logits[i] * inv_temperature - mx); s += p[i]; }
     for (int i = 0; i < n; i++) p[i] /= s;
+}
+
+/* softmax(scores) . V over rows 0 .. nk-1 given by an accessor; scores already complete in sc[] */
+static void weighted_sum(const double *sc_exp, double z, int nk, int dh, int hh, const csdo_model *mod, double *kv, int cross,
+                         int l, int b, double *oi) {
+    for (int x = 0; x < dh; x++) oi[x] = 0.0;
+    for (int j = 0; j < nk; j++) {
+        const double *vj = (cross ? cross_row(mod, kv, 1, l, b, j) : kv_row(mod, kv, 1, l, b, j)) + hh * dh;
+        double p = sc_exp[j] / z;
+        for (int x = 0; x < dh; x++) oi[x] += p * vj[x];
+    }
+}
+
+/*
+ * arch 1: T5-style decoder layer stack over the block rows of one sequence.
+ *   h += SelfAttn(norm(h))   causal over cache rows 0 .. t+i, scores q.k + bias[bucket(i_pos - j_pos)][head], no scaling
+ *   h += CrossAttn(norm(h))  over all enc_len projected encoder rows, no mask, no bias, no scaling
+ *   h += (gelu_tanh(norm(h) W0) * (norm(h) W1)) Wout
+ */
+static int32_t verify_block_t5(csdo_model *mod, double *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
+                               int32_t m, double temperature, double *logits, double *probs) {
+    const csdo_cfg *c = &mod->c;
+    const int d = c->d_model, H = c->n_heads, dh = c->head_dim, F = c->d_ffn, V = c->vocab, L = c->n_layers, E = c->enc_len;
+    const int hd = H * dh, dt = c->dtype;
+    const void **w = mod->w;
+    const float *rel = (const float *)w[mod->n_w - 1];          /* [REL_BUCKETS][H] */
+    const int wide = d > hd ? d : hd;
+    double *h = (double *)malloc(sizeof(double) * (size_t)m * d);
+    double *a = (double *)malloc(sizeof(double) * (size_t)m * wide);
+    double *q = (double *)malloc(sizeof(double) * (size_t)m * hd);
+    double *kk = (double *)malloc(sizeof(double) * (size_t)m * hd);
+    double *vv = (double *)malloc(sizeof(double) * (size_t)m * hd);
+    double *o = (double *)malloc(sizeof(double) * (size_t)m * hd);
+    double *t1 = (double *)malloc(sizeof(double) * (size_t)m * (F > d ? F : d));
+    double *t2 = (double *)malloc(sizeof(double) * (size_t)m * (F > d ? F : d));
+    const int scn = c->max_seq > E ? c->max_seq : E;
+    double *sc = (double *)malloc(sizeof(double) * (size_t)scn);
+    for (int b = 0; b < B; b++) {
+        const int t = cache_len[b];
+        for (int i = 0; i < m; i++)
+            for (int x = 0; x < d; x++)
+                h[(size_t)i * d + x] = wval(w[W_EMBED], dt, (size_t)tokens[b * m + i] * d + x);
+        if (mod->trace && b == 0) memcpy(mod->trace, h, sizeof(double) * (size_t)m * d);
+        for (int l = 0; l < L; l++) {
+            const void **lw = w + 1 + (size_t)l * T_COUNT;
+            /* self-attention */
+            for (int i = 0; i < m; i++)
+                csdo_rmsnorm(h + (size_t)i * d, (const float *)lw[T_SELF_NORM], d, c->rms_eps, a + (size_t)i * d);
+            matmul(a, m, d, lw[T_WQ], dt, hd, q);
+            matmul(a, m, d, lw[T_WK], dt, hd, kk);
+            matmul(a, m, d, lw[T_WV], dt, hd, vv);
+            for (int i = 0; i < m; i++)
+                for (int x = 0; x < hd; x++) {
+                    kv_row(mod, kv, 0, l, b, t + i)[x] = to_cache(mod, kk[(size_t)i * hd + x]);
+                    kv_row(mod, kv, 1, l, b, t + i)[x] = to_cache(mod, vv[(size_t)i * hd + x]);
+                }
+            for (int i = 0; i < m; i++)
+                for (int hh = 0; hh < H; hh++) {
+                    const double *qi = q + (size_t)i * hd + hh * dh;
+                    const int nk = t + i + 1;
+                    double mx = -INFINITY;
+                    for (int j = 0; j < nk; j++) {
+                        const double *kj = kv_row(mod, kv, 0, l, b, j) + hh * dh;
+                        double s = 0.0;
+                        for (int x = 0; x < dh; x++) s += qi[x] * kj[x];
+                        sc[j] = s + (double)rel[(size_t)csdo_rel_bucket(t + i - j) * H + hh];
+                        if (sc[j] > mx) mx = sc[j];
+                    }
+                    double z = 0.0;
+                    for (int j = 0; j < nk; j++) { sc[j] = exp(sc[j] - mx); z += sc[j]; }
+                    weighted_sum(sc, z, nk, dh, hh, mod, kv, 0, l, b, o + (size_t)i * hd + hh * dh);
+                }
+            matmul(o, m, hd, lw[T_WO], dt, d, t1);
+            for (size_t x = 0; x < (size_t)m * d; x++) h[x] += t1[x];
+            /* cross-attention over the projected encoder rows */
+            for (int i = 0; i < m; i++)
+                csdo_rmsnorm(h + (size_t)i * d, (const float *)lw[T_CROSS_NORM], d, c->rms_eps, a + (size_t)i * d);
+            matmul(a, m, d, lw[T_CQ], dt, hd, q);
+            for (int i = 0; i < m; i++)
+                for (int hh = 0; hh < H; hh++) {
+                    const double *qi = q + (size_t)i * hd + hh * dh;
+                    double mx = -INFINITY;
+                    for (int j = 0; j < E; j++) {
+                        const double *kj = cross_row(mod, kv, 0, l, b, j) + hh * dh;
+                        double s = 0.0;
+                        for (int x = 0; x < dh; x++) s += qi[x] * kj[x];
+                        sc[j] = s;
+                        if (s > mx) mx = s;
+                    }
+                    double z = 0.0;
+                    for (int j = 0; j < E; j++) { sc[j] = exp(sc[j] - mx); z += sc[j]; }
+                    weighted_sum(sc, z, E, dh, hh, mod, kv, 1, l, b, o + (size_t)i * hd + hh * dh);
+                }
+            matmul(o, m, hd, lw[T_CO], dt, d, t1);
+            for (size_t x = 0; x < (size_t)m * d; x++) h[x] += t1[x];
+            /* gated tanh-GELU feed-forward */
+            for (int i = 0; i < m; i++)
+                csdo_rmsnorm(h + (size_t)i * d, (const float *)lw[T_FFN_NORM], d, c->rms_eps, a + (size_t)i * d);
+            matmul(a, m, d, lw[T_W0], dt, F, t1);
+            matmul(a, m, d, lw[T_W1], dt, F, t2);
+            for (size_t x = 0; x < (size_t)m * F; x++) t1[x] = gelu_tanh(t1[x]) * t2[x];
+            matmul(t1, m, F, lw[T_WOUT], dt, d, t2);
+            for (size_t x = 0; x < (size_t)m * d; x++) h[x] += t2[x];
+            if (mod->trace && b == 0)
+                memcpy(mod->trace + (size_t)(l + 1) * m * d, h, sizeof(double) * (size_t)m * d);
+        }
+        for (int i = 0; i < m; i++)
+            csdo_rmsnorm(h + (size_t)i * d, (const float *)w[mod->n_w - 3], d, c->rms_eps, a + (size_t)i * d);
+        double *lg = logits + (size_t)b * m * V;
+        matmul(a, m, d, w[mod->n_w - 2], dt, V, lg);
+        if (probs)
+            for (int i = 0; i < m; i++)
+                csdo_softmax(lg + (size_t)i * V, V, 1.0 / temperature, probs + ((size_t)b * m + i) * V);
+    }
+    free(h); free(a); free(q); free(kk); free(vv); free(o); free(t1); free(t2); free(sc);
+    return 0;
 }
 
 /*
@@ -232,6 +411,8 @@ int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, co
         for (int i = 0; i < m; i++)
             if (tokens[b * m + i] < 0 || tokens[b * m + i] >= V) return -2;
     }
+    if (probs && !(temperature > 0.0)) return -2;
+    if (c->arch == 1) return verify_block_t5(mod, kv, tokens, cache_len, B, m, temperature, logits, probs);
     double *h = (double *)malloc(sizeof(double) * (size_t)m * d);
     double *a = (double *)malloc(sizeof(double) * (size_t)m * (d > hd ? d : hd));
     double *q = (double *)malloc(sizeof(double) * (size_t)m * hd);

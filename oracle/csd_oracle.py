@@ -44,7 +44,8 @@ def lib():
         _lib.csdo_kv_bytes.restype = C.c_size_t
         _lib.csdo_threads.restype = C.c_int32
         for name in ("csdo_model_create", "csdo_model_destroy", "csdo_kv_write", "csdo_kv_read",
-                     "csdo_verify_block", "csdo_bigram_fit", "csdo_bigram_draft", "csdo_accept"):
+                     "csdo_verify_block", "csdo_bigram_fit", "csdo_bigram_draft", "csdo_accept",
+                     "csdo_cross_kv_init", "csdo_rel_bucket"):
             getattr(_lib, name).restype = C.c_int32
         for name in ("csdo_set_trace", "csdo_rmsnorm", "csdo_rope", "csdo_softmax", "csdo_probs_f32"):
             getattr(_lib, name).restype = None
@@ -84,11 +85,12 @@ class Model:
         dtype = 1 if shape.dtype == "bf16" else 0
         self.shape = shape
         self.cfg = Cfg(shape.arch, dtype, shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim,
-                       shape.d_ffn, shape.vocab, max_batch, max_seq, max_block, 0,
+                       shape.d_ffn, shape.vocab, max_batch, max_seq, max_block, getattr(shape, "enc_len", 0),
                        shape.rms_eps, shape.rope_theta)
         self._w = [_as_host(w) for w in weights]
-        for a in self._w:
-            want = np.uint16 if (dtype == 1 and a.ndim == 2) else np.float32
+        for i, a in enumerate(self._w):
+            bias_table = shape.arch == 1 and i == len(self._w) - 1      # relative-position bias stays fp32
+            want = np.uint16 if (dtype == 1 and a.ndim == 2 and not bias_table) else np.float32
             if a.dtype != want:
                 raise TypeError(f"weight dtype {a.dtype}, expected {want}")
         arr = (C.c_void_p * len(self._w))(*[a.ctypes.data for a in self._w])
@@ -120,6 +122,11 @@ class Model:
         V = np.empty((n, hd), dtype=np.float64)
         _chk(lib().csdo_kv_read(self._h, _p(self.kv), layer, b, pos0, n, _p(K), _p(V)), "kv_read")
         return K, V
+
+    def cross_kv_init(self, enc_out):
+        """arch 1: enc_out [B][enc_len][d] -> cross-attention keys/values of every layer, in the cache."""
+        x = np.ascontiguousarray(enc_out, dtype=np.float32)
+        _chk(lib().csdo_cross_kv_init(self._h, _p(self.kv), _p(x), x.shape[0]), "cross_kv_init")
 
     def verify_block(self, tokens, cache_len, temperature=1.0, want_probs=False, trace=False):
         """tokens [B][m] int32, cache_len [B] -> logits [B][m][V] fp64 (and probs)."""
@@ -191,6 +198,11 @@ def accept(p, q, draft, u_acc, u_samp, lenience=1.0, mode=0, q_onehot=None):
     _chk(lib().csdo_accept(_p(p), _p(q), _p(oh), _p(draft), _p(u_acc), _p(u_samp), B, k, V,
                            C.c_float(lenience), mode, _p(n_acc), _p(nxt)), "accept")
     return n_acc, nxt
+
+
+def rel_bucket(n):
+    """Bucket of the arch-1 relative-position bias for the distance n = query position - key position."""
+    return int(lib().csdo_rel_bucket(int(n)))
 
 
 def rmsnorm(x, g, eps):
