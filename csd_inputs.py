@@ -224,7 +224,13 @@ def make_weights(shape: ModelShape, seed: int, device="cpu", std: float = 0.02):
         if len(shp) == 1:
             out.append(torch.ones(shp, dtype=torch.float32, device=device))
             continue
-        w = normal(shp, std, seed, 0x1000 + idx, device)
+        s_w = std
+        if shape.arch == 1 and names[idx].endswith((".wq", ".cq")):
+            # T5 attention has no 1/sqrt(head_dim) factor: the family folds it into the initialisation of the
+            # query projections.  Without it a random-init model's softmaxes are near one-hot and rounding
+            # differences double per layer, so no finite-precision forward could be compared at full depth.
+            s_w = std / float(shape.head_dim) ** 0.5
+        w = normal(shp, s_w, seed, 0x1000 + idx, device)
         if shape.dtype == "bf16" and names[idx] != "rel_bias":     # the small bias table stays fp32
             w = w.to(torch.bfloat16)
         out.append(w.contiguous())

@@ -39,25 +39,29 @@ extern "C" {
 #define CSD_ESHAPE  (-2)  /* a size exceeds what the model / kernel was created for         */
 #define CSD_ENULL   (-3)  /* a required pointer is NULL                                     */
 #define CSD_EHIP    (-4)  /* a HIP call failed; see csd_last_hip_error()                    */
-#define CSD_EUNSUPPORTED (-5) /* configuration not implemented (e.g. arch != 0)             */
+#define CSD_EUNSUPPORTED (-5) /* configuration not implemented (e.g. arch > 1)              */
 
 #define CSD_DTYPE_FP32 0
 #define CSD_DTYPE_BF16 1
 #define CSD_MODE_SAMPLE 0
 #define CSD_MODE_GREEDY 1
 
-/* Reviewing-model description.  arch 0 is the LLaMA-style decoder of the benchmark
- * configurations: RMSNorm, rotary embedding (half-split pairing, K cached after rotation),
- * causal attention scaled by 1/sqrt(head_dim), SwiGLU, no biases, untied LM head. */
+/* Reviewing-model description (Section 5.1 names the families; the benchmark configurations give
+ * the shapes).  arch 0 is the LLaMA-style decoder: RMSNorm, rotary embedding (half-split pairing,
+ * K cached after rotation), causal attention scaled by 1/sqrt(head_dim), SwiGLU, no biases, untied
+ * LM head.  arch 1 is the T5-style decoder: RMS layer norm, no rotary embedding, unscaled causal
+ * self-attention with a bucketed relative-position bias (32 buckets, maximum distance 128, one
+ * table for all layers), unmasked cross-attention over a fixed encoder output of enc_len rows, gated
+ * tanh-GELU feed-forward, untied LM head. */
 typedef struct csd_model_cfg {
-    int32_t arch;        /* 0 only                                                          */
+    int32_t arch;        /* 0 or 1                                                          */
     int32_t dtype;       /* CSD_DTYPE_*: storage type of the matrices and of the KV cache;  */
                          /* norm gains, logits and probabilities are always fp32            */
     int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
     int32_t max_batch;   /* most sequences per call                                         */
     int32_t max_seq;     /* rows per sequence in the KV cache                               */
     int32_t max_block;   /* most block rows m = k+1 per sequence per call                   */
-    int32_t enc_len;     /* reserved (encoder-decoder reviewers); must be 0                 */
+    int32_t enc_len;     /* arch 1: rows of the encoder output per sequence (>= 1); arch 0: 0 */
     float   rms_eps, rope_theta;
 } csd_model_cfg;
 
@@ -78,6 +82,9 @@ int32_t csd_last_hip_error(void);
  * copied (re-tiled for the MFMA kernels when dtype is bf16); the caller may free its tensors
  * once the stream has passed this call.  Allocates weights + scratch; this is the only
  * allocating call besides destroy.  n_weights must be 3 + 9*n_layers.
+ * arch 1: per layer self_norm[d], wq, wk, wv, wo, cross_norm[d], cq[d][H*dh], ck, cv, co[H*dh][d],
+ * ffn_norm[d], w0[d][F] (through the GELU), w1[d][F], w_out[F][d]; then final_norm[d], lm_head[d][V],
+ * rel_bias[32][H] (fp32 whatever dtype is); n_weights must be 4 + 14*n_layers.
  */
 int32_t csd_model_create(const csd_model_cfg *cfg, const void *const *weight_ptrs, int32_t n_weights,
                          void *stream, csd_model **out);
@@ -89,9 +96,16 @@ int32_t csd_model_destroy(csd_model *model);
  * csd_kv_read to move rows in canonical form. */
 size_t csd_kv_bytes(const csd_model *model);
 
+/* arch 1, once per prompt (Section 5.1's encoder-decoder reviewers attend a fixed encoder output):
+ * project enc_out (device, fp32 [B][enc_len][d_model], values taken as exact in the model dtype) to
+ * the cross-attention keys and values of every layer and store them in the second part of the cache
+ * `kv` (sequences 0..B-1).  Must precede the first csd_verify_block on that cache.
+ * CSD_EUNSUPPORTED for arch 0. */
+int32_t csd_cross_kv_init(csd_model *model, void *kv, const float *enc_out, int32_t B, void *stream);
+
 /* Copy n rows [pos0, pos0+n) of sequence b, layer `layer` into / out of the cache.
  * K and V are fp32 [n][H*dh] (K as cached, i.e. after rotation); values are rounded to the
- * cache dtype on write (round-to-nearest-even). */
+ * cache dtype on write (round-to-nearest-even).  These address the self-attention rows only. */
 int32_t csd_kv_write(const csd_model *model, void *kv, int32_t layer, int32_t b, int32_t pos0, int32_t n,
                      const float *K, const float *V, void *stream);
 int32_t csd_kv_read(const csd_model *model, const void *kv, int32_t layer, int32_t b, int32_t pos0, int32_t n,

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
-           "csd_kv_write", "csd_kv_read", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
+           "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
            "csd_accept", "csd_verify_accept", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_debug_copy",
            "csd_prof_enable", "csd_prof_read"]
 
@@ -87,12 +87,13 @@ class Model:
         dtype = 1 if shape.dtype == "bf16" else 0
         self.shape = shape
         self.cfg = Cfg(shape.arch, dtype, shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim,
-                       shape.d_ffn, shape.vocab, max_batch, max_seq, max_block, 0,
+                       shape.d_ffn, shape.vocab, max_batch, max_seq, max_block, getattr(shape, "enc_len", 0),
                        shape.rms_eps, shape.rope_theta)
         want = torch.bfloat16 if dtype == 1 else torch.float32
         ptrs = []
-        for w in weights:
-            ptrs.append(_ptr(w, want if w.ndim == 2 else torch.float32).value)
+        for i, w in enumerate(weights):
+            bias_table = shape.arch == 1 and i == len(weights) - 1       # relative-position bias: always fp32
+            ptrs.append(_ptr(w, want if (w.ndim == 2 and not bias_table) else torch.float32).value)
         arr = (C.c_void_p * len(ptrs))(*ptrs)
         self._h = C.c_void_p()
         _chk(lib().csd_model_create(C.byref(self.cfg), arr, len(ptrs), _stream(), C.byref(self._h)), "csd_model_create")
@@ -111,6 +112,11 @@ class Model:
             self.close()
         except Exception:
             pass
+
+    def cross_kv_init(self, enc_out):
+        """arch 1: enc_out [B][enc_len][d] fp32 on the device -> cross-attention keys/values in the cache."""
+        _chk(lib().csd_cross_kv_init(self._h, _ptr(self.kv), _ptr(enc_out, torch.float32), enc_out.shape[0], _stream()),
+             "csd_cross_kv_init")
 
     def kv_write(self, layer, b, pos0, K, V):
         n = K.shape[0]

@@ -20,14 +20,16 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     const csd_model_cfg &c = mod->cfg;
     mod->hd = c.n_heads * c.head_dim;
     mod->seq_pad = (c.max_seq + 63) / 64 * 64;
+    mod->enc_pad = c.arch == 1 ? (c.enc_len + 63) / 64 * 64 : 0;
     mod->m_max = c.max_batch * c.max_block;
     const int d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab;
     // The MFMA path needs whole 16-feature tiles and 32-wide k-steps everywhere.
     const bool tiles_ok = d % 32 == 0 && hd % 32 == 0 && F % 32 == 0 && V % 16 == 0 && c.head_dim % 16 == 0;
     mod->mfma = c.dtype == CSD_DTYPE_BF16 && tiles_ok && !env_is("CSD_GEMM", "generic");
-    mod->kperm = mod->mfma;
+    mod->kperm = mod->mfma && c.arch == 0;     // rotary pair order only where there is a rotary embedding
     mod->mfma_attn = mod->mfma && (c.head_dim == 64 || c.head_dim == 128) && !env_is("CSD_ATTN", "generic");
-    if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + mod->seq_pad) > 64 * 1024) return CSD_ESHAPE;
+    const int keys_pad = mod->seq_pad > mod->enc_pad ? mod->seq_pad : mod->enc_pad;
+    if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + keys_pad) > 64 * 1024) return CSD_ESHAPE;
     int32_t rc;
     if ((rc = csd_pack_weights(mod, weights, st)) != CSD_OK) return rc;
 
@@ -60,7 +62,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->probs = (float *)p;
     if (mod->mfma_attn) {
         // per (sequence, head, key chunk): 16*ceil(m/16) rows x (dh accumulators + max + sum)
-        mod->attn_chunks_max = (mod->seq_pad + 127) / 128;
+        mod->attn_chunks_max = (keys_pad + 127) / 128;
         const int row_tiles = (c.max_block + 15) / 16;
         const size_t per = (size_t)row_tiles * 16 * (c.head_dim + 4);
         CSD_HIP(hipMalloc(&p, sizeof(float) * per * mod->attn_chunks_max * c.n_heads * c.max_batch));
@@ -69,6 +71,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     }
     mod->ev.resize(8192);
     for (auto &e : mod->ev) CSD_HIP(hipEventCreate(&e));
+    if (c.arch != 0) return CSD_OK;      // the single-launch kernel covers the LLaMA-style decoder only
     return csd_fused_init(mod, st);
 }
 
@@ -76,15 +79,16 @@ extern "C" int32_t csd_model_create(const csd_model_cfg *cfg, const void *const 
                                     void *stream, csd_model **out) {
     if (!cfg || !weight_ptrs || !out) return CSD_ENULL;
     *out = nullptr;
-    if (cfg->arch != 0 || cfg->enc_len != 0) return CSD_EUNSUPPORTED;
+    if (cfg->arch != 0 && cfg->arch != 1) return CSD_EUNSUPPORTED;
+    if ((cfg->arch == 0 && cfg->enc_len != 0) || (cfg->arch == 1 && cfg->enc_len < 1)) return CSD_EINVAL;
     if (cfg->dtype != CSD_DTYPE_FP32 && cfg->dtype != CSD_DTYPE_BF16) return CSD_EINVAL;
     if (cfg->n_layers < 1 || cfg->d_model < 1 || cfg->n_heads < 1 || cfg->head_dim < 2 || cfg->head_dim % 2 ||
         cfg->d_ffn < 1 || cfg->vocab < 1 || cfg->max_batch < 1 || cfg->max_seq < 1 || cfg->max_block < 1)
         return CSD_EINVAL;
-    if (!(cfg->rms_eps > 0.f) || !(cfg->rope_theta > 0.f)) return CSD_EINVAL;
+    if (!(cfg->rms_eps > 0.f) || (cfg->arch == 0 && !(cfg->rope_theta > 0.f))) return CSD_EINVAL;
     if (cfg->max_block > cfg->max_seq) return CSD_ESHAPE;
     if ((long long)cfg->max_batch * cfg->max_block > 4096) return CSD_ESHAPE;
-    if (n_weights != 3 + 9 * cfg->n_layers) return CSD_EINVAL;
+    if (n_weights != (cfg->arch == 0 ? 3 + 9 * cfg->n_layers : 4 + 14 * cfg->n_layers)) return CSD_EINVAL;
     for (int i = 0; i < n_weights; i++)
         if (!weight_ptrs[i]) return CSD_ENULL;
     csd_model *mod = new (std::nothrow) csd_model();

@@ -17,13 +17,14 @@ template <int DH>
 __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, size_t qplane, int m, int row_tiles,
                                                   const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
                                                   const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
-                                                  int chunks_max) {
+                                                  int chunks_max, AttnMode mode) {
     constexpr int PS = DH + 4;   // floats per partial row: DH outputs, running max, running sum, pad
     const int c = blockIdx.x, hh = blockIdx.y, b = blockIdx.z / row_tiles, rt = blockIdx.z % row_tiles;
     const int lane = threadIdx.x, col = lane & 15, g = lane >> 4;
     const int hd = geo.H * DH;
-    const int t = cache_len[b];
-    const int nk = max(0, min(t + m, geo.seq_pad));          // cache rows in play for this block
+    const bool causal = mode.fixed_nk <= 0;
+    const int t = causal ? cache_len[b] : 0;
+    const int nk = max(0, min(causal ? t + m : mode.fixed_nk, geo.seq_pad));   // cache rows in play for this block
     float *po = part + ((((size_t)b * geo.H + hh) * chunks_max + c) * row_tiles + rt) * 16 * PS;
     float *pr = po + (size_t)col * PS;
     const int key0 = c * ATT_CHUNK;
@@ -78,8 +79,10 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const int key = kb + 8 * g + j;
-            const float s = sT[j >> 2][j & 3] * scale;
-            sv[j] = (key <= qpos && key < nk) ? s : -INFINITY;
+            float s = sT[j >> 2][j & 3] * scale;
+            const bool seen = (!causal || key <= qpos) && key < nk;
+            if (mode.rel_bias && seen) s += mode.rel_bias[mode.bucket[min(qpos - key, 127)] * geo.H + hh];
+            sv[j] = seen ? s : -INFINITY;
             mx = fmaxf(mx, sv[j]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -136,11 +139,12 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
 template <int DH>
 __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ part, int m, int row_tiles,
                                                    const int32_t *__restrict__ cache_len, int H, int seq_pad,
-                                                   int chunks_max, bf16_t *__restrict__ out, int ldo, size_t plane) {
+                                                   int chunks_max, bf16_t *__restrict__ out, int ldo, size_t plane,
+                                                   int fixed_nk) {
     constexpr int PS = DH + 4;
     const int r = blockIdx.x, hh = blockIdx.y, x = threadIdx.x;
     const int b = r / m, i = r % m, rt = i / 16, ri = i % 16;
-    const int nk = max(1, min(cache_len[b] + m, seq_pad));
+    const int nk = max(1, min(fixed_nk > 0 ? fixed_nk : cache_len[b] + m, seq_pad));
     const int nch = (nk + ATT_CHUNK - 1) / ATT_CHUNK;
     const float *base = part + (((size_t)b * H + hh) * chunks_max * row_tiles + rt) * 16 * PS + (size_t)ri * PS;
     const size_t cstride = (size_t)row_tiles * 16 * PS;
@@ -157,28 +161,27 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
     store_act<bf16_t>(out, plane, (size_t)r * ldo + hh * DH + x, den > 0.f ? num / den : 0.f);
 }
 
-int32_t csd_attn_mfma_enqueue(csd_model *mod, const void *kv, const int32_t *cache_len, int B, int m, int layer,
-                              hipStream_t st) {
+// geo / kv: the cache being attended (the self-attention cache, or arch 1's cross-attention part of it)
+int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
+                              int layer, float scale, const AttnMode &mode, hipStream_t st) {
     const csd_model_cfg &c = mod->cfg;
-    const KvGeom geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, c.n_layers, mod->kperm ? 1 : 0};
     const int row_tiles = (m + 15) / 16;
     const int chunks = mod->attn_chunks_max;
-    const float scale = 1.0f / sqrtf((float)c.head_dim);
     const dim3 grid(chunks, c.n_heads, B * row_tiles);
     const dim3 mgrid(B * m, c.n_heads);
     ProfScope ps(mod, st, CSD_PROF_ATTN);
     if (c.head_dim == 128) {
         hipLaunchKernelGGL((k_attn_mfma<128>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo,
-                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks);
+                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks, mode);
         CSD_LAUNCH_CHECK();
         hipLaunchKernelGGL((k_attn_merge<128>), mgrid, dim3(128), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
-                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane);
+                           geo.seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane, mode.fixed_nk);
     } else {
         hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo,
-                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks);
+                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks, mode);
         CSD_LAUNCH_CHECK();
         hipLaunchKernelGGL((k_attn_merge<64>), mgrid, dim3(64), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
-                           mod->seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane);
+                           geo.seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane, mode.fixed_nk);
     }
     CSD_LAUNCH_CHECK();
     return CSD_OK;

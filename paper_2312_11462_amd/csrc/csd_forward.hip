@@ -9,6 +9,8 @@
 // wave streaming its own contiguous run of pre-tiled 1 KB weight fragments straight into MFMA
 // operands; K slices write partial-sum planes that the small epilogue kernels add up in a fixed
 // order (deterministic, no float atomics) while applying residual / norm / rotation / SwiGLU.
+#include <cmath>
+
 #include "csd_internal.h"
 
 // ------------------------------------------------------------------------------ weight tiling
@@ -222,8 +224,12 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
             v0 += p[2 * hd + x];
             v1 += p[2 * hd + x + half];
         }
-        const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
-        const float c = (float)cos(ang), sn = (float)sin(ang);
+        float c = 1.f, sn = 0.f;                         // theta <= 0: a model without rotary embedding
+        if (theta > 0.f) {
+            const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
+            c = (float)cos(ang);
+            sn = (float)sin(ang);
+        }
         store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p0, q0 * c - q1 * sn);
         store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p1, q0 * sn + q1 * c);
         if (pos_ok) {
@@ -239,7 +245,7 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
 // (gate tile j at packed tile 2j, up tile at 2j+1); row-major weights concatenate [gate | up].
 template <typename TA>
 __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, int S, int M, int F, int interleaved,
-                                                TA *__restrict__ f, int ldf, size_t plane) {
+                                                TA *__restrict__ f, int ldf, size_t plane, int gelu) {
     const int r = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= F) return;
@@ -251,7 +257,9 @@ __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, 
         gsum += p[gc];
         usum += p[uc];
     }
-    const float sg = gsum / (1.0f + expf(-gsum));
+    // gate activation: SiLU, or (arch 1) the tanh form of GELU
+    const float sg = gelu ? 0.5f * gsum * (1.0f + tanhf(0.7978845608028654f * (gsum + 0.044715f * gsum * gsum * gsum)))
+                          : gsum / (1.0f + expf(-gsum));
     store_act<TA>(f, plane, (size_t)r * ldf + j, sg * usum);
 }
 
@@ -265,19 +273,62 @@ __global__ __launch_bounds__(256) void k_fix_logits(const float *__restrict__ pa
     logits[(size_t)r * V + v] = acc;
 }
 
+// out[r][j] = sum_s part[s][r][j] (two bf16 planes on the MFMA path): the cross-attention queries of arch 1
+template <typename TA>
+__global__ __launch_bounds__(256) void k_fix_plain(const float *__restrict__ part, int S, int M, int N, TA *__restrict__ out,
+                                                   int ldo, size_t plane) {
+    const int r = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= N) return;
+    float acc = 0.f;
+    for (int s = 0; s < S; s++) acc += part[((size_t)s * M + r) * N + j];
+    store_act<TA>(out, plane, (size_t)r * ldo + j, acc);
+}
+
+// arch 1, once per prompt: rows [row0, row0 + M) of the projected encoder output, part[s][r][0..hd) = keys and
+// [hd..2hd) = values, go into the cross-attention part of the cache (keys row-major, values transposed)
+template <typename TC>
+__global__ __launch_bounds__(256) void k_fix_cross_kv(const float *__restrict__ part, int S, int M, KvGeom geo, int layer,
+                                                      int b, int row0, TC *__restrict__ kvc) {
+    const int r = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int hd = geo.H * geo.dh;
+    if (j >= hd) return;
+    float k = 0.f, v = 0.f;
+    for (int s = 0; s < S; s++) {
+        const float *p = part + ((size_t)s * M + r) * (2 * (size_t)hd);
+        k += p[j];
+        v += p[hd + j];
+    }
+    const int hh = j / geo.dh, x = j % geo.dh, pos = row0 + r;
+    kvc[kv_k_off(geo, layer, b, hh) + (size_t)pos * geo.dh + x] = from_f32<TC>(k);
+    kvc[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos] = from_f32<TC>(v);
+}
+
+// a[r][x] = src[r][x] as GEMM input rows (two bf16 planes on the MFMA path)
+template <typename TA>
+__global__ __launch_bounds__(256) void k_rows_to_act(const float *__restrict__ src, int M, int d, TA *__restrict__ a, int lda,
+                                                     size_t plane) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)M * d) return;
+    store_act<TA>(a, plane, (idx / d) * lda + idx % d, src[idx]);
+}
+
 // Generic causal block attention: one wave per (block row, head).  Scores of the visible cache
 // rows 0..pos go through LDS; softmax in fp32 with max subtraction; o = sum_j p_j V_j.
 template <typename TA, typename TC>
 __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, int m, const int32_t *__restrict__ cache_len,
                                                     KvGeom geo, int layer, const TC *__restrict__ kv, float scale,
-                                                    size_t qplane, TA *__restrict__ out, int ldo, size_t plane) {
+                                                    size_t qplane, TA *__restrict__ out, int ldo, size_t plane,
+                                                    AttnMode mode) {
     extern __shared__ float sm[];
     const int r = blockIdx.x, hh = blockIdx.y;
     const int b = r / m, i = r % m;
     const int dh = geo.dh, hd = geo.H * dh;
     float *qs = sm;           // [dh]
     float *sc = sm + dh;      // [nk]
-    int nk = cache_len[b] + i + 1;
+    const int qpos = mode.fixed_nk > 0 ? 0 : cache_len[b] + i;
+    int nk = mode.fixed_nk > 0 ? mode.fixed_nk : qpos + 1;
     nk = max(1, min(nk, geo.seq_pad));
     const TC *kc = kv + kv_k_off(geo, layer, b, hh);
     const TC *vc = kv + kv_v_off(geo, layer, b, hh);
@@ -291,6 +342,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, in
         float s = 0.f;
         for (int x = 0; x < dh; x++) s = fmaf(qs[x], to_f32<TC>(kc[(size_t)j * dh + x]), s);
         s *= scale;
+        if (mode.rel_bias) s += mode.rel_bias[mode.bucket[min(qpos - j, 127)] * geo.H + hh];
         sc[j] = s;
         mx = fmaxf(mx, s);
     }
@@ -388,8 +440,8 @@ static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, 
     return CSD_OK;
 }
 
-int32_t csd_attn_mfma_enqueue(csd_model *mod, const void *kv, const int32_t *cache_len, int B, int m, int layer,
-                              hipStream_t st);   // csd_attention.hip
+int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
+                              int layer, float scale, const AttnMode &mode, hipStream_t st);   // csd_attention.hip
 
 template <typename TW, typename TA, typename TC>
 static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
@@ -420,12 +472,12 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
             CSD_LAUNCH_CHECK();
         }
         if (mod->mfma_attn) {
-            if ((rc = csd_attn_mfma_enqueue(mod, kv, cache_len, B, m, l, st)) != CSD_OK) return rc;
+            if ((rc = csd_attn_mfma_enqueue(mod, geo, kv, cache_len, B, m, l, scale, AttnMode{}, st)) != CSD_OK) return rc;
         } else {
             ProfScope ps(mod, st, CSD_PROF_ATTN);
             const size_t lds = sizeof(float) * (size_t)(c.head_dim + mod->seq_pad);
             hipLaunchKernelGGL((k_attn_simple<TA, TC>), dim3(M, c.n_heads), dim3(64), lds, st, qb, m, cache_len, geo, l,
-                               (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane);
+                               (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane, AttnMode{});
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.o, act, M, st)) != CSD_OK) return rc;
@@ -439,7 +491,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, lw.gu.S, M, F,
-                               mod->mfma ? 1 : 0, act, F, mod->act_plane);
+                               mod->mfma ? 1 : 0, act, F, mod->act_plane, 0);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.down, act, M, st)) != CSD_OK) return rc;
@@ -464,8 +516,147 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     return CSD_OK;
 }
 
+static KvGeom cross_geom(const csd_model *mod) {
+    return KvGeom{mod->cfg.max_batch, mod->cfg.n_heads, mod->cfg.head_dim, mod->enc_pad, mod->cfg.n_layers, 0};
+}
+
+template <typename TA, typename TC>
+static int32_t attention_any(csd_model *mod, const KvGeom &geo, const void *kvbase, const int32_t *cache_len, int B, int m,
+                             int layer, float scale, const AttnMode &mode, hipStream_t st) {
+    if (mod->mfma_attn) return csd_attn_mfma_enqueue(mod, geo, kvbase, cache_len, B, m, layer, scale, mode, st);
+    ProfScope ps(mod, st, CSD_PROF_ATTN);
+    const size_t lds = sizeof(float) * (size_t)(mod->cfg.head_dim + geo.seq_pad);
+    hipLaunchKernelGGL((k_attn_simple<TA, TC>), dim3(B * m, mod->cfg.n_heads), dim3(64), lds, st, (const TA *)mod->qbuf, m,
+                       cache_len, geo, layer, (const TC *)kvbase, scale, mod->q_plane, (TA *)mod->act, mod->hd, mod->act_plane,
+                       mode);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+// arch 1: T5-style decoder.  Per layer: self-attention (no rotary embedding, unscaled scores plus the
+// bucketed relative-position bias), cross-attention over the projected encoder rows in the cache's second
+// part (no mask, no bias), gated tanh-GELU feed-forward; each sub-layer is norm -> op -> residual add.
+template <typename TW, typename TA, typename TC>
+static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B, int32_t m,
+                          float *logits, hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    const int M = B * m, d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab, L = c.n_layers;
+    const KvGeom geo = geom(mod), cgeo = cross_geom(mod);
+    TA *act = (TA *)mod->act;
+    TA *qb = (TA *)mod->qbuf;
+    const void *kv_cross = (const char *)kv + csd_self_kv_bytes(mod);
+    AttnMode self_mode, cross_mode;
+    self_mode.rel_bias = mod->rel_bias;
+    self_mode.bucket = mod->rel_bucket;
+    cross_mode.fixed_nk = c.enc_len;
+    int32_t rc;
+    auto resid_norm = [&](const GemmW &w, const float *gain) -> int32_t {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, w.S, M, d, gain, c.rms_eps, mod->h, act,
+                           d, mod->act_plane);
+        CSD_LAUNCH_CHECK();
+        return CSD_OK;
+    };
+    {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
+                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane);
+        CSD_LAUNCH_CHECK();
+    }
+    if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
+    for (int l = 0; l < L; l++) {
+        const LayerW &lw = mod->layers[l];
+        if ((rc = run_gemm(mod, lw.qkv, act, M, st)) != CSD_OK) return rc;
+        {
+            ProfScope ps(mod, st, CSD_PROF_OTHER);
+            hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, lw.qkv.S, M, m, cache_len,
+                               geo, l, 0.0f, qb, mod->q_plane, (TC *)kv);
+            CSD_LAUNCH_CHECK();
+        }
+        if ((rc = attention_any<TA, TC>(mod, geo, kv, cache_len, B, m, l, 1.0f, self_mode, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.o, act, M, st)) != CSD_OK) return rc;
+        if ((rc = resid_norm(lw.o, lw.cross_norm)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.cq, act, M, st)) != CSD_OK) return rc;
+        {
+            ProfScope ps(mod, st, CSD_PROF_OTHER);
+            hipLaunchKernelGGL((k_fix_plain<TA>), dim3((hd + 255) / 256, M), dim3(256), 0, st, mod->part, lw.cq.S, M, hd, qb, hd,
+                               mod->q_plane);
+            CSD_LAUNCH_CHECK();
+        }
+        if ((rc = attention_any<TA, TC>(mod, cgeo, kv_cross, cache_len, B, m, l, 1.0f, cross_mode, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.co, act, M, st)) != CSD_OK) return rc;
+        if ((rc = resid_norm(lw.co, lw.ffn_norm)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.gu, act, M, st)) != CSD_OK) return rc;
+        {
+            ProfScope ps(mod, st, CSD_PROF_OTHER);
+            hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, lw.gu.S, M, F,
+                               mod->mfma ? 1 : 0, act, F, mod->act_plane, 1);
+            CSD_LAUNCH_CHECK();
+        }
+        if ((rc = run_gemm(mod, lw.down, act, M, st)) != CSD_OK) return rc;
+        if ((rc = resid_norm(lw.down, (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm)) != CSD_OK) return rc;
+        if (mod->trace)
+            CSD_HIP(hipMemcpyAsync(mod->trace + (size_t)(l + 1) * M * d, mod->h, sizeof(float) * (size_t)M * d,
+                                   hipMemcpyDeviceToDevice, st));
+    }
+    if ((rc = run_gemm(mod, mod->lm, act, M, st)) != CSD_OK) return rc;
+    {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, mod->lm.S, M, V, logits);
+        CSD_LAUNCH_CHECK();
+    }
+    return CSD_OK;
+}
+
+// arch 1: project the encoder output of B sequences to every layer's cross-attention keys and values.
+template <typename TA, typename TC>
+static int32_t cross_init_typed(csd_model *mod, void *kv, const float *enc_out, int32_t B, hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    const int d = c.d_model, hd = mod->hd, E = c.enc_len;
+    const KvGeom cgeo = cross_geom(mod);
+    TC *kvc = (TC *)((char *)kv + csd_self_kv_bytes(mod));
+    const int chunk = mod->m_max;       // the activation and partial-sum buffers hold this many rows
+    int32_t rc;
+    for (int b = 0; b < B; b++)
+        for (int row0 = 0; row0 < E; row0 += chunk) {
+            const int rows = E - row0 < chunk ? E - row0 : chunk;
+            {
+                ProfScope ps(mod, st, CSD_PROF_OTHER);
+                const size_t total = (size_t)rows * d;
+                hipLaunchKernelGGL((k_rows_to_act<TA>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                                   enc_out + ((size_t)b * E + row0) * d, rows, d, (TA *)mod->act, d, mod->act_plane);
+                CSD_LAUNCH_CHECK();
+            }
+            for (int l = 0; l < c.n_layers; l++) {
+                const LayerW &lw = mod->layers[l];
+                if ((rc = run_gemm(mod, lw.ckv, mod->act, rows, st)) != CSD_OK) return rc;
+                ProfScope ps(mod, st, CSD_PROF_OTHER);
+                hipLaunchKernelGGL((k_fix_cross_kv<TC>), dim3((hd + 255) / 256, rows), dim3(256), 0, st, mod->part, lw.ckv.S, rows,
+                                   cgeo, l, b, row0, kvc);
+                CSD_LAUNCH_CHECK();
+            }
+        }
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_cross_kv_init(csd_model *mod, void *kv, const float *enc_out, int32_t B, void *stream) {
+    if (!mod || !kv || !enc_out) return CSD_ENULL;
+    if (mod->cfg.arch != 1) return CSD_EUNSUPPORTED;
+    if (B < 1) return CSD_EINVAL;
+    if (B > mod->cfg.max_batch) return CSD_ESHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    if (mod->cfg.dtype == CSD_DTYPE_FP32) return cross_init_typed<float, float>(mod, kv, enc_out, B, st);
+    if (mod->mfma) return cross_init_typed<bf16_t, bf16_t>(mod, kv, enc_out, B, st);
+    return cross_init_typed<float, bf16_t>(mod, kv, enc_out, B, st);
+}
+
 int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
                             int32_t m, float *logits, hipStream_t st) {
+    if (mod->cfg.arch == 1) {
+        if (mod->cfg.dtype == CSD_DTYPE_FP32) return forward_t5<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);
+        if (mod->mfma) return forward_t5<bf16_t, bf16_t, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
+        return forward_t5<bf16_t, float, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
+    }
     if (csd_fused_eligible(mod, B, m)) return csd_fused_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->cfg.dtype == CSD_DTYPE_FP32)
         return forward_typed<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);
@@ -553,6 +744,55 @@ int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st) {
     if ((rc = dev_alloc(mod, &mod->embed, (size_t)V * d * esz)) != CSD_OK) return rc;
     CSD_HIP(hipMemcpyAsync(mod->embed, w[0], (size_t)V * d * esz, hipMemcpyDeviceToDevice, st));
     mod->layers.resize(L);
+    if (c.arch == 1) {
+        // canonical order per layer: self_norm, wq, wk, wv, wo, cross_norm, cq, ck, cv, co, ffn_norm, w0, w1, w_out;
+        // then final_norm, lm_head, rel_bias [32][H] fp32
+        for (int l = 0; l < L; l++) {
+            const void *const *lw = w + 1 + 14 * l;
+            LayerW &o = mod->layers[l];
+            float **norms[3] = {&o.attn_norm, &o.cross_norm, &o.ffn_norm};
+            const int norm_idx[3] = {0, 5, 10};
+            for (int i = 0; i < 3; i++) {
+                if ((rc = dev_alloc(mod, (void **)norms[i], sizeof(float) * d)) != CSD_OK) return rc;
+                CSD_HIP(hipMemcpyAsync(*norms[i], lw[norm_idx[i]], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
+            }
+            const Piece qkv[3] = {{lw[1], hd, 0, 1, 0}, {lw[2], hd, hd / 16, 1, 0}, {lw[3], hd, 2 * hd / 16, 1, 0}};
+            if ((rc = build_gemm(mod, &o.qkv, d, 3 * hd, qkv, 3, false, st)) != CSD_OK) return rc;
+            const Piece wo[1] = {{lw[4], d, 0, 1, 0}};
+            if ((rc = build_gemm(mod, &o.o, hd, d, wo, 1, false, st)) != CSD_OK) return rc;
+            const Piece cq[1] = {{lw[6], hd, 0, 1, 0}};
+            if ((rc = build_gemm(mod, &o.cq, d, hd, cq, 1, false, st)) != CSD_OK) return rc;
+            const Piece ckv[2] = {{lw[7], hd, 0, 1, 0}, {lw[8], hd, hd / 16, 1, 0}};
+            if ((rc = build_gemm(mod, &o.ckv, d, 2 * hd, ckv, 2, false, st)) != CSD_OK) return rc;
+            const Piece co[1] = {{lw[9], d, 0, 1, 0}};
+            if ((rc = build_gemm(mod, &o.co, hd, d, co, 1, false, st)) != CSD_OK) return rc;
+            const Piece gu[2] = {{lw[11], F, 0, 2, 0}, {lw[12], F, 1, 2, 0}};
+            if ((rc = build_gemm(mod, &o.gu, d, 2 * F, gu, 2, true, st)) != CSD_OK) return rc;
+            const Piece dn[1] = {{lw[13], d, 0, 1, 0}};
+            if ((rc = build_gemm(mod, &o.down, F, d, dn, 1, false, st)) != CSD_OK) return rc;
+        }
+        if ((rc = dev_alloc(mod, (void **)&mod->final_norm, sizeof(float) * d)) != CSD_OK) return rc;
+        CSD_HIP(hipMemcpyAsync(mod->final_norm, w[1 + 14 * L], sizeof(float) * d, hipMemcpyDeviceToDevice, st));
+        const Piece lm[1] = {{w[2 + 14 * L], V, 0, 1, 0}};
+        if ((rc = build_gemm(mod, &mod->lm, d, V, lm, 1, false, st)) != CSD_OK) return rc;
+        if ((rc = dev_alloc(mod, (void **)&mod->rel_bias, sizeof(float) * 32 * c.n_heads)) != CSD_OK) return rc;
+        CSD_HIP(hipMemcpyAsync(mod->rel_bias, w[3 + 14 * L], sizeof(float) * 32 * c.n_heads, hipMemcpyDeviceToDevice, st));
+        // bucket of a look-back distance n (T5's unidirectional scheme with 32 buckets, maximum distance 128):
+        // n itself below 16, then 16 logarithmically spaced buckets up to 128, farther keys in the last one
+        int32_t tab[128];
+        for (int n = 0; n < 128; n++) {
+            int bkt = n;
+            if (n >= 16) {
+                bkt = 16 + (int)(std::log((double)n / 16.0) / std::log(128.0 / 16.0) * 16.0);
+                if (bkt > 31) bkt = 31;
+            }
+            tab[n] = bkt;
+        }
+        tab[127] = 31;
+        if ((rc = dev_alloc(mod, (void **)&mod->rel_bucket, sizeof(tab))) != CSD_OK) return rc;
+        CSD_HIP(hipMemcpy(mod->rel_bucket, tab, sizeof(tab), hipMemcpyHostToDevice));
+        return CSD_OK;
+    }
     for (int l = 0; l < L; l++) {
         const void *const *lw = w + 1 + 9 * l;
         LayerW &o = mod->layers[l];
@@ -578,11 +818,19 @@ int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st) {
 
 // ------------------------------------------------------------------------------ cache access
 
+size_t csd_self_kv_bytes(const csd_model *mod) {
+    const csd_model_cfg &c = mod->cfg;
+    const size_t esz = c.dtype == CSD_DTYPE_BF16 ? 2 : 4;
+    return (size_t)2 * c.n_layers * c.max_batch * c.n_heads * mod->seq_pad * c.head_dim * esz;
+}
+
 extern "C" size_t csd_kv_bytes(const csd_model *mod) {
     if (!mod) return 0;
     const csd_model_cfg &c = mod->cfg;
     const size_t esz = c.dtype == CSD_DTYPE_BF16 ? 2 : 4;
-    return (size_t)2 * c.n_layers * c.max_batch * c.n_heads * mod->seq_pad * c.head_dim * esz;
+    // arch 1 appends the cross-attention keys and values of every layer (filled by csd_cross_kv_init)
+    const size_t cross = c.arch == 1 ? (size_t)2 * c.n_layers * c.max_batch * c.n_heads * mod->enc_pad * c.head_dim * esz : 0;
+    return csd_self_kv_bytes(mod) + cross;
 }
 
 extern "C" int32_t csd_kv_write(const csd_model *mod, void *kv, int32_t layer, int32_t b, int32_t pos0, int32_t n,

@@ -135,6 +135,20 @@ struct GemmW {
 struct LayerW {
     float *attn_norm = nullptr, *ffn_norm = nullptr;
     GemmW qkv, o, gu, down;
+    // arch 1 (T5-style decoder): cross-attention norm, query and output projections, and the fused
+    // key|value projection of the encoder output (used once per prompt)
+    float *cross_norm = nullptr;
+    GemmW cq, co, ckv;
+};
+
+// How an attention launch sees its keys.  Default: causal over the cache (block row i of a sequence
+// with t cached rows sees rows 0 .. t+i).  fixed_nk > 0: every row sees rows 0 .. fixed_nk-1 (cross-
+// attention).  rel_bias != null: add rel_bias[bucket[min(query pos - key pos, 127)] * H + head] to the
+// scaled score (T5-style relative-position bias; bucket is a 128-entry table, farther keys share entry 127).
+struct AttnMode {
+    int fixed_nk = 0;
+    const float *rel_bias = nullptr;
+    const int32_t *bucket = nullptr;
 };
 
 enum { CSD_PROF_GEMM = 0, CSD_PROF_ATTN = 1, CSD_PROF_OTHER = 2, CSD_PROF_CLASSES = 3 };
@@ -162,6 +176,10 @@ struct csd_model {
     float *attn_part = nullptr;  // attention partials (MFMA attention)
     float *probs = nullptr;      // [m_max][V] when the caller does not want them
     int attn_chunks_max = 0;
+    // arch 1
+    int enc_pad = 0;                 // encoder rows padded to 64
+    float *rel_bias = nullptr;       // [32][H] fp32
+    int32_t *rel_bucket = nullptr;   // [128] bucket of distance n (n >= 127 shares the last entry)
     float *trace = nullptr;
     void *fused = nullptr;           // state of the single-launch path (csd_fused.hip), or null
     float *fused_attn_part = nullptr;
@@ -180,6 +198,7 @@ struct csd_model {
 int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
                             int32_t B, int32_t m, float *logits, hipStream_t st);
 int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st);
+size_t csd_self_kv_bytes(const csd_model *mod);     // the self-attention part of the cache (arch 1 appends the cross part)
 // csd_fused.hip: single-launch forward for small blocks
 int32_t csd_fused_init(csd_model *mod, hipStream_t st);
 void csd_fused_free(csd_model *mod);

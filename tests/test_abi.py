@@ -41,8 +41,15 @@ def test_null_and_domain_errors_without_a_device(L):
     assert L.csd_model_create(None, None, 0, None, C.byref(out)) == -3
     ptrs = (C.c_void_p * 21)(*([1] * 21))
     assert L.csd_model_create(C.byref(cfg), ptrs, 20, None, C.byref(out)) == -1          # wrong weight count
-    bad = Cfg(1, 1, 2, 64, 4, 16, 256, 512, 1, 64, 8, 0, 1e-5, 10000.0)
+    bad = Cfg(2, 1, 2, 64, 4, 16, 256, 512, 1, 64, 8, 0, 1e-5, 10000.0)
     assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -5          # arch
+    bad = Cfg(1, 1, 2, 64, 4, 16, 256, 512, 1, 64, 8, 0, 1e-6, 0.0)
+    assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -1          # arch 1 needs enc_len
+    bad = Cfg(1, 1, 2, 64, 4, 16, 256, 512, 1, 64, 8, 16, 1e-6, 0.0)
+    assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -1          # arch 1: 4 + 14 L tensors
+    bad = Cfg(0, 1, 2, 64, 4, 16, 256, 512, 1, 64, 8, 16, 1e-5, 10000.0)
+    assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -1          # arch 0 has no encoder
+    assert L.csd_cross_kv_init(None, None, None, 1, None) == -3
     bad = Cfg(0, 1, 2, 64, 4, 15, 256, 512, 1, 64, 8, 0, 1e-5, 10000.0)
     assert L.csd_model_create(C.byref(bad), ptrs, 21, None, C.byref(out)) == -1          # odd head_dim
     bad = Cfg(0, 1, 2, 64, 4, 16, 256, 512, 1, 4, 8, 0, 1e-5, 10000.0)
