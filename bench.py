@@ -5,7 +5,7 @@ A step is one pass of the whole hot path over one batch of synthetic input, all 
 Max-Gram draft of the block's tail -> review forward of the 7B-shaped target over the k+1 block
 rows against a 1024-row KV cache -> softmax -> accept / resample.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload target7b|draft160m|tiny]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload target7b|t5xxl|draft160m|tiny]
 """
 from __future__ import annotations
 
@@ -27,19 +27,22 @@ TRAFFIC_BYTES_PER_LAUNCH = {("target7b", 2): 14_867_000_000}
 
 
 def algorithmic_bytes(shape, B, t, m):
-    """Bytes one step must move: every streamed weight once, the visible K/V rows once, the new
-    K/V rows, the gathered embedding rows and the logits written once for the caller."""
+    """Bytes one step must move: every streamed weight once, the visible K/V rows once (for an arch-1
+    reviewer also the projected encoder rows), the new K/V rows, the gathered embedding rows and the
+    logits written once for the caller."""
     d, L, V = shape.d_model, shape.n_layers, shape.vocab
+    hd = shape.n_heads * shape.head_dim
     esz = 2 if shape.dtype == "bf16" else 4
     weights = shape.streamed_params() * esz
-    kv_read = L * B * 2 * (t + m) * d * esz
-    kv_write = L * B * 2 * m * d * esz
+    kv_read = L * B * 2 * (t + m + shape.enc_len) * hd * esz
+    kv_write = L * B * 2 * m * hd * esz
     return dict(weights=weights, total=weights + kv_read + kv_write + B * m * d * esz + 4 * B * m * V)
 
 
 def algorithmic_flops(shape, B, t, m):
-    d, L = shape.d_model, shape.n_layers
-    return 2 * shape.streamed_params() * B * m + L * B * 4 * (t + m) * d * m
+    L = shape.n_layers
+    hd = shape.n_heads * shape.head_dim
+    return 2 * shape.streamed_params() * B * m + L * B * 4 * (t + m + shape.enc_len) * hd * m
 
 
 def main():
@@ -71,13 +74,17 @@ def main():
     wl = I.WORKLOADS[args.workload]
     shape, B, t, k, seed = wl["shape"], wl["B"], wl["prefix"], wl["k"], wl["seed"]
     m = k + 1
-    n_from_draft_model = 2 if args.workload == "target7b" else 0     # horizontal cascade: 2 neural drafts, tail from Max-Gram
+    n_from_draft_model = 2 if args.workload in ("target7b", "t5xxl") else 0     # horizontal cascade: 2 neural drafts, tail from Max-Gram
     k_tail = k - n_from_draft_model
 
     # ---- setup (untimed): weights, model, cache, context, tables
     t0 = time.time()
     w = I.make_weights(shape, seed, device="cuda")
     model = P.Model(shape, w, max_batch=B, max_seq=t + 64, max_block=max(m, 8))
+    enc = None
+    if shape.arch == 1:      # encoder-decoder reviewer: the encoder output is projected once per prompt (setup)
+        enc = I.encoder_output(shape, B, seed, device="cuda")
+        model.cross_kv_init(enc)
     host_w = None
     if not args.no_cpu_baseline:
         host_w = [x.cpu() for x in w]
@@ -192,6 +199,8 @@ def main():
 
         from oracle import csd_oracle as O
         om = O.Model(shape, host_w, max_batch=1, max_seq=t + 64, max_block=max(m, 8))
+        if shape.arch == 1:
+            om.cross_kv_init(enc[:1].cpu().numpy())          # setup, not part of the timed step
         for l in range(shape.n_layers):
             K, V = I.synthetic_kv(shape, t, seed, l, 0, device="cuda")
             om.kv_write(l, 0, 0, K.cpu().numpy(), V.cpu().numpy())
@@ -210,14 +219,16 @@ def main():
                "agrees_with_gpu": bool(int(on[0]) == int(n_acc[0].item()) and int(ot[0]) == int(nxt[0].item()))}
 
     out = {
-        "metric": "verified tokens/s per verify+accept step, 7B-shaped bf16; % HBM/MFMA roofline",
+        "metric": "verified tokens/s per verify+accept step, 7B-shaped bf16; % HBM/MFMA roofline" if args.workload.startswith("target7b")
+                  else f"verified tokens/s per verify+accept step, {shape.name}; % HBM/MFMA roofline",
         "value": round(B * k / (wall / args.steps), 2), "unit": "verified tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "gpu_ms_per_step": round(gpu_ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {shape.n_layers} layers, d_model {shape.d_model}, batch {B}, "
-                               f"{t}-row KV cache, block of k={k} drafts ({n_from_draft_model} stand-ins for the neural "
+                               f"{t}-row KV cache" + (f", {shape.enc_len} encoder rows" if shape.arch == 1 else "") +
+                               f", block of k={k} drafts ({n_from_draft_model} stand-ins for the neural "
                                f"draft level + {k_tail} from Max-Gram), mode {args.mode}",
                    "batch": B, "prefix": t, "k": k},
         "emitted_tokens_per_s": round(emitted / (wall / args.steps), 2),

@@ -177,14 +177,45 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ 
         store_act<TA>(a, plane, (size_t)r * lda + x, h[(size_t)r * d + x] * rs * g[x]);
 }
 
-// h[r] += sum_s part[s][r];  a[r] = rmsnorm(h[r]) * g
+// h[r] += sum_s part[s][r];  a[r] = rmsnorm(h[r]) * g.  One workgroup of 1024 threads per row, four
+// consecutive features per thread and pass (16-byte loads when d allows), the new h kept in registers
+// between the sum of squares and the scaling for rows of up to RN_THREADS * 4 * RN_PASSES features.
+#define RN_THREADS 1024
+#define RN_PASSES 2
 template <typename TA>
-__global__ __launch_bounds__(256) void k_residual_norm(const float *__restrict__ part, int S, int M, int d,
-                                                       const float *__restrict__ g, float eps, float *__restrict__ h,
-                                                       TA *__restrict__ a, int lda, size_t plane) {
-    __shared__ float red[16];
+__global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__restrict__ part, int S, int M, int d,
+                                                              const float *__restrict__ g, float eps, float *__restrict__ h,
+                                                              TA *__restrict__ a, int lda, size_t plane) {
+    __shared__ float red[RN_THREADS / 64];
     const int r = blockIdx.x;
     float ss = 0.f;
+    if (d % 4 == 0 && d <= RN_THREADS * 4 * RN_PASSES) {
+        f32x4 keep[RN_PASSES];
+#pragma unroll
+        for (int p = 0; p < RN_PASSES; p++) {
+            const int x = (p * RN_THREADS + (int)threadIdx.x) * 4;
+            keep[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (x < d) {
+                f32x4 v = *reinterpret_cast<const f32x4 *>(h + (size_t)r * d + x);
+                for (int s = 0; s < S; s++) v += *reinterpret_cast<const f32x4 *>(part + ((size_t)s * M + r) * d + x);
+                *reinterpret_cast<f32x4 *>(h + (size_t)r * d + x) = v;
+                keep[p] = v;
+                ss += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+            }
+        }
+        ss = block_sum(ss, red);
+        const float rs = rsqrtf(ss / (float)d + eps);
+#pragma unroll
+        for (int p = 0; p < RN_PASSES; p++) {
+            const int x = (p * RN_THREADS + (int)threadIdx.x) * 4;
+            if (x < d) {
+                const f32x4 gv = *reinterpret_cast<const f32x4 *>(g + x);
+#pragma unroll
+                for (int i = 0; i < 4; i++) store_act<TA>(a, plane, (size_t)r * lda + x + i, keep[p][i] * rs * gv[i]);
+            }
+        }
+        return;
+    }
     for (int x = threadIdx.x; x < d; x += blockDim.x) {
         float v = 0.f;
         for (int s = 0; s < S; s++) v += part[((size_t)s * M + r) * d + x];
@@ -483,7 +514,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         if ((rc = run_gemm(mod, lw.o, act, M, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
-            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, lw.o.S, M, d, lw.ffn_norm,
+            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, lw.o.S, M, d, lw.ffn_norm,
                                c.rms_eps, mod->h, act, d, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
@@ -498,7 +529,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             const float *g = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
-            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, lw.down.S, M, d, g,
+            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, lw.down.S, M, d, g,
                                c.rms_eps, mod->h, act, d, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
@@ -552,7 +583,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
     int32_t rc;
     auto resid_norm = [&](const GemmW &w, const float *gain) -> int32_t {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
-        hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(256), 0, st, mod->part, w.S, M, d, gain, c.rms_eps, mod->h, act,
+        hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, w.S, M, d, gain, c.rms_eps, mod->h, act,
                            d, mod->act_plane);
         CSD_LAUNCH_CHECK();
         return CSD_OK;
