@@ -22,6 +22,9 @@
 // so no partial sums ever travel through HBM.
 //
 // The same phase functions are also launchable one kernel per phase (debugging / comparison).
+#include <mutex>
+#include <vector>
+
 #include "csd_internal.h"
 
 #define FUSED_THREADS 512
@@ -39,6 +42,8 @@ struct FusedParams {
     int M, m, B, d, hd, H, dh, F, V, L, seq_pad, Bmax, kperm;
     int kg_max;        // key groups (256 keys each) covered by the attention phase's item list
     int tg_qkv, tg_lm;
+    int arrive_first;  // 1: streaming waves hold their prefetch until the service wave has signalled the barrier
+    int bar_scalar;    // 1: the barrier flags live in uncached memory and are polled with scalar loads
     int fresh;         // 1: every phase writes its own instance of the exchange buffers (no L2 invalidate)
     int pf;            // ring slots of the next phase's weights issued before the barrier wait
     int lds_red_off, lds_rstd_off;   // LDS: [0, red_off) activation fragments (or the attention merge area),
@@ -206,21 +211,62 @@ __device__ __forceinline__ void grid_arrive(CParams &P, unsigned epoch, bool ser
 
 // Between arrive and wait a wave may issue loads that do not depend on other workgroups (the next
 // phase's weights); the closing workgroup barrier orders LDS only, so those loads stay in flight.
+typedef unsigned u32x16 __attribute__((ext_vector_type(16)));
+
+// Are all flags of replica `fp` (64 dwords of 4 one-byte flags) equal to `pat` in their first n_dw dwords?
+// Read with scalar loads that bypass the scalar cache (glc): they do not go through the vector memory
+// pipeline, so they never queue behind the weight prefetch the compute unit has in flight.  The flag
+// memory is allocated uncached, so the loads reach memory whichever L2 serves them.
+__device__ __forceinline__ bool flags_all_equal_scalar(const unsigned char *fp_any, unsigned pat, int n_dw) {
+    // the address is the same in every lane, but the compiler may hold it in vector registers
+    const unsigned long long a64 = (unsigned long long)fp_any;
+    const unsigned lo32 = __builtin_amdgcn_readfirstlane((unsigned)a64);
+    const unsigned hi32 = __builtin_amdgcn_readfirstlane((unsigned)(a64 >> 32));
+    const unsigned char *fp = reinterpret_cast<const unsigned char *>(((unsigned long long)hi32 << 32) | lo32);
+    pat = __builtin_amdgcn_readfirstlane(pat);
+    n_dw = __builtin_amdgcn_readfirstlane(n_dw);
+    u32x16 a, b, c, d;
+    asm volatile("s_load_dwordx16 %0, %4, 0x0 glc\n\t"
+                 "s_load_dwordx16 %1, %4, 0x40 glc\n\t"
+                 "s_load_dwordx16 %2, %4, 0x80 glc\n\t"
+                 "s_load_dwordx16 %3, %4, 0xc0 glc\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d)
+                 : "s"(fp)
+                 : "memory");
+    unsigned diff = 0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        diff |= (i < n_dw ? a[i] ^ pat : 0u) | (16 + i < n_dw ? b[i] ^ pat : 0u) | (32 + i < n_dw ? c[i] ^ pat : 0u) |
+                (48 + i < n_dw ? d[i] ^ pat : 0u);
+    }
+    return diff == 0u;
+}
+
 __device__ __forceinline__ void grid_wait(CParams &P, unsigned epoch) {
     if (threadIdx.x < 64) {
         const int lane = threadIdx.x;
         const __amdgpu_buffer_rsrc_t rb = co_rsrc(P.bar, BAR_BYTES);
         const int G = gridDim.x;
-        const int off = (int)((blockIdx.x % BAR_REPLICAS) * BAR_REPLICA_STRIDE) + lane * 4;
+        const int rep = (int)((blockIdx.x % BAR_REPLICAS) * BAR_REPLICA_STRIDE);
+        const int off = rep + lane * 4;
+        // scalar polling needs whole dwords of flags; a workgroup is never more than one barrier ahead of
+        // another, so "every flag has reached the barrier" is "every flag equals its number"
+        const bool scalar = P.bar_scalar && G % 4 == 0;
+        const unsigned pat = (epoch & 0xFFu) * 0x01010101u;
         unsigned spins = 0;
         bool give_up = __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
         while (!give_up) {
-            const unsigned f = __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, CSD_SC1);
-            bool ok = true;
+            if (scalar) {
+                if (flags_all_equal_scalar(P.bar + rep, pat, G / 4)) break;
+            } else {
+                const unsigned f = __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, CSD_SC1);
+                bool ok = true;
 #pragma unroll
-            for (int i = 0; i < 4; i++)
-                ok = ok && (4 * lane + i >= G || (signed char)(unsigned char)(((f >> (8 * i)) & 0xFFu) - (epoch & 0xFFu)) >= 0);
-            if (__all(ok)) break;
+                for (int i = 0; i < 4; i++)
+                    ok = ok && (4 * lane + i >= G || (signed char)(unsigned char)(((f >> (8 * i)) & 0xFFu) - (epoch & 0xFFu)) >= 0);
+                if (__all(ok)) break;
+            }
             ++spins;
             if ((spins & 1023u) == 0u && __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
                 give_up = true;
@@ -234,7 +280,6 @@ __device__ __forceinline__ void grid_wait(CParams &P, unsigned epoch) {
     if (!P.fresh && threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     lds_sync();
 }
-
 
 // ------------------------------------------------------------------------------------ helpers
 
@@ -982,6 +1027,7 @@ __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(const Fu
         run_phase<DH>(P, X, PHASE, LAYER, smem, wg, nwg, W, (PRE) ? P.pf : 0); \
         ts_mark(P, X, TS_EPILOGUE);                                    \
         grid_arrive(P, ++epoch, GEMM);                                 \
+        if (P.arrive_first) lds_sync();   /* the flag store is issued before this compute unit's prefetch burst */ \
         prefetch_phase(P, NEXT_PHASE, NEXT_LAYER, wg, nwg, W);         \
         grid_wait(P, epoch);                                           \
         ts_mark(P, X, TS_BARRIER);                                     \
@@ -1021,6 +1067,8 @@ struct FusedState {
     float *cs = nullptr;
     unsigned *attn_cnt = nullptr;
     unsigned char *bar = nullptr;
+    int bar_scalar = 0;
+    int arrive_first = 1;   // tuning knob (env CSD_FUSED_ARRIVE_FIRST)
     unsigned *err = nullptr;
     unsigned bar_epoch = 0;
     int grid = 0, kg_max = 0, tg_qkv = 1, tg_lm = 1;
@@ -1033,6 +1081,30 @@ struct FusedState {
     int pf = 64;       // tuning knob (env CSD_FUSED_PF): ring slots prefetched across a barrier
     int mode = 2;      // 0: off, 1: one launch per phase, 2: persistent
 };
+
+// Barrier flags live in uncached device memory.  Such memory is never freed once a kernel has read it
+// (tensors allocated after such a free have held wrong values on this platform): buffers of destroyed
+// models go back to a process-wide pool and are handed out again.
+static std::mutex g_flag_pool_mutex;
+static std::vector<void *> g_flag_pool;
+static int32_t flag_buffer_acquire(void **p, hipStream_t st) {
+    {
+        std::lock_guard<std::mutex> lock(g_flag_pool_mutex);
+        if (!g_flag_pool.empty()) {
+            *p = g_flag_pool.back();
+            g_flag_pool.pop_back();
+        } else {
+            *p = nullptr;
+        }
+    }
+    if (!*p) CSD_HIP(hipExtMallocWithFlags(p, BAR_BYTES, hipDeviceMallocUncached));
+    CSD_HIP(hipMemsetAsync(*p, 0, BAR_BYTES, st));
+    return CSD_OK;
+}
+static void flag_buffer_release(void *p) {
+    std::lock_guard<std::mutex> lock(g_flag_pool_mutex);
+    g_flag_pool.push_back(p);
+}
 
 static int32_t fused_alloc(csd_model *mod, void **p, size_t bytes, bool zero, hipStream_t st) {
     CSD_HIP(hipMalloc(p, bytes));
@@ -1067,6 +1139,7 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     FusedState *fs = new FusedState();
     fs->mode = mode;
     if (const char *e = getenv("CSD_FUSED_FRESH")) fs->fresh = atoi(e) ? 1 : 0;
+    if (const char *e = getenv("CSD_FUSED_ARRIVE_FIRST")) fs->arrive_first = atoi(e) ? 1 : 0;
     if (const char *e = getenv("CSD_FUSED_PF")) fs->pf = atoi(e) < 0 ? 0 : atoi(e);
     fs->m_limit = m_limit < mod->m_max ? m_limit : mod->m_max;
     const int m_cap = fs->m_limit;
@@ -1098,7 +1171,12 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     if ((rc = fused_alloc(mod, (void **)&fs->xattn, sizeof(bf16_t) * L * 2 * 16 * hd, true, st)) != CSD_OK) return rc;
     if ((rc = fused_alloc(mod, (void **)&fs->xffn, sizeof(bf16_t) * L * 2 * 16 * F, true, st)) != CSD_OK) return rc;
     if ((rc = fused_alloc(mod, (void **)&fs->attn_cnt, sizeof(unsigned) * c.max_batch * c.n_heads, true, st)) != CSD_OK) return rc;
-    if ((rc = fused_alloc(mod, (void **)&fs->bar, BAR_BYTES > 16384 ? BAR_BYTES : 16384, true, st)) != CSD_OK) return rc;
+    if (getenv("CSD_FUSED_VECTOR_POLL")) {
+        if ((rc = fused_alloc(mod, (void **)&fs->bar, BAR_BYTES, true, st)) != CSD_OK) return rc;
+    } else {
+        if ((rc = flag_buffer_acquire((void **)&fs->bar, st)) != CSD_OK) return rc;
+        fs->bar_scalar = 1;
+    }
     if ((rc = fused_alloc(mod, (void **)&fs->err, 256, true, st)) != CSD_OK) return rc;
     // attention partials: [Bmax][H][kg_max][16][dh+4]; reuse the model's buffer when large enough
     const size_t need = sizeof(float) * (size_t)c.max_batch * c.n_heads * fs->kg_max * 16 * (dh + 4);
@@ -1115,7 +1193,9 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
 }
 
 void csd_fused_free(csd_model *mod) {
-    delete (FusedState *)mod->fused;
+    FusedState *fs = (FusedState *)mod->fused;
+    if (fs && fs->bar_scalar && fs->bar) flag_buffer_release(fs->bar);
+    delete fs;
     mod->fused = nullptr;
 }
 
@@ -1186,6 +1266,8 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     P.attn_cnt = fs->attn_cnt;
     P.logits = logits;
     P.bar = fs->bar;
+    P.bar_scalar = fs->bar_scalar;
+    P.arrive_first = fs->arrive_first;
     P.err = fs->err;
     P.trace = mod->trace;
     P.ts = (unsigned long long *)mod->fused_ts;
