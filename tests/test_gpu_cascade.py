@@ -1,0 +1,116 @@
+"""The cascade generation loop (Algorithm 1) on the GPU.
+
+What the paper fixes (Sections 2, 3.1, 5.1): with temperature 0 and no lenience where the target
+reviews, cascaded decoding emits exactly the target's own greedy continuation, whatever the draft
+levels, K and the lenience between draft levels are; a draft identical to its reviewer is accepted
+whole.  Both are checked on the GPU's own outputs (cascade vs plain decoding with the same kernels),
+and the fp32 configuration also against the CPU oracle's cascade driver."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import csd_inputs as I
+
+pytestmark = pytest.mark.gpu
+
+TARGET = I.ModelShape("t", 0, "fp32", 2, 64, 4, 16, 256, 512)
+DRAFT1 = I.ModelShape("d1", 0, "fp32", 1, 32, 2, 16, 64, 512)
+DRAFT2 = I.ModelShape("d2", 0, "fp32", 1, 16, 2, 8, 32, 512)
+TARGET_BF = I.ModelShape("tb", 0, "bf16", 2, 256, 4, 64, 512, 1024)
+DRAFT_BF = I.ModelShape("db", 0, "bf16", 1, 256, 4, 64, 512, 1024)
+MAX_CTX = 160
+
+
+def _gpu_level(shape, seed, std):
+    import paper_2312_11462_amd as P
+    from paper_2312_11462_amd.cascade import Level
+    w = I.make_weights(shape, seed, device="cuda", std=std)
+    return Level(P.Model(shape, w, max_batch=1, max_seq=MAX_CTX, max_block=16), 16)
+
+
+def _prompt(vocab, seed):
+    p = I.token_ids(24, vocab, seed, 1).tolist()
+    return p[:12] + p[:12]            # a repeated phrase so that Max-Gram has matches
+
+
+def _table(prompt, vocab):
+    import paper_2312_11462_amd as P
+    t = I.default_next_table(vocab, 1).cuda()
+    P.bigram_fit(torch.tensor(prompt, dtype=torch.int32).cuda(), vocab, t)
+    return t
+
+
+@pytest.mark.parametrize("K,lenience,n_drafts", [
+    ([[4]], 1.0, 0),
+    ([[2, 6], [0, 6]], 1.0, 1),
+    ([[2, 6], [0, 6]], 3.0, 1),
+    ([[2, 2, 4], [0, 1, 3], [0, 0, 3]], 2.0, 2),
+])
+def test_greedy_cascade_equals_target_greedy_fp32_and_matches_the_oracle_driver(K, lenience, n_drafts):
+    from paper_2312_11462_amd.cascade import Cascade, autoregressive
+    from oracle import csd_oracle as O
+    from oracle import cascade as OC
+    prompt = _prompt(512, 21)
+    table = _table(prompt, 512)
+    shapes = [TARGET, DRAFT1, DRAFT2][:n_drafts + 1]
+    levels = [_gpu_level(s, 1 + i, 0.2) for i, s in enumerate(shapes)]
+    want = autoregressive(levels[0], prompt, 40, MAX_CTX)
+    got, steps = Cascade(levels, table, K, MAX_CTX, lenience=lenience, mode=1).generate(prompt, 40)
+    assert got == want
+    assert steps <= 40
+    assert all(lv.model.error_flag() == 0 for lv in levels)
+    # the CPU oracle's driver on the same weights emits the same tokens (fp64 vs fp32 arg-maxes agree
+    # at this weight scale)
+    olevels = []
+    for i, s in enumerate(shapes):
+        w = I.make_weights(s, 1 + i, std=0.2)
+        lv = OC.Level(O.Model(s, w, max_batch=1, max_seq=MAX_CTX, max_block=16), 16)
+        lv._keep = w
+        olevels.append(lv)
+    otable = O.bigram_fit(np.array(prompt, np.int32), 512, I.default_next_table(512, 1).numpy())
+    assert np.array_equal(otable, table.cpu().numpy())
+    ogot, osteps = OC.cascade_generate(olevels, otable, prompt, 40, K, lenience=lenience, mode=1)
+    assert got == ogot and steps == osteps
+
+
+def test_greedy_cascade_bf16_on_the_single_launch_kernel():
+    """bf16 models whose blocks (<= 16 rows) take the persistent kernel: the cascade still reproduces the
+    target's greedy continuation, because reviewer and plain decoding run the same kernels."""
+    from paper_2312_11462_amd.cascade import Cascade, autoregressive
+    prompt = _prompt(1024, 31)
+    table = _table(prompt, 1024)
+    target, draft = _gpu_level(TARGET_BF, 5, 0.05), _gpu_level(DRAFT_BF, 6, 0.05)
+    assert target.model.path(1, 9) == 2
+    want = autoregressive(target, prompt, 32, MAX_CTX)
+    got, steps = Cascade([target, draft], table, [[2, 6], [0, 6]], MAX_CTX, lenience=2.0, mode=1).generate(prompt, 32)
+    # block shape changes the summation order inside the kernels; an arg-max tie within rounding could
+    # legitimately differ, so report rather than hide: the seeded models here have no such tie
+    assert got == want
+    assert target.model.error_flag() == 0 and draft.model.error_flag() == 0
+
+
+def test_identical_draft_is_accepted_whole():
+    from paper_2312_11462_amd.cascade import Cascade, autoregressive
+    prompt = I.token_ids(10, 512, 22, 1).tolist()
+    table = I.default_next_table(512, 1).cuda()
+    target, twin = _gpu_level(TARGET, 1, 0.2), _gpu_level(TARGET, 1, 0.2)
+    want = autoregressive(target, prompt, 24, MAX_CTX)
+    got, steps = Cascade([target, twin], table, [[3, 0], [0, 1]], MAX_CTX, mode=1).generate(prompt, 24)
+    assert got == want
+    assert steps <= 24 // 4 + 1        # every target review keeps the twin's 3 drafts and adds one token
+
+
+def test_sampling_cascade_is_reproducible_and_emits_valid_tokens():
+    from paper_2312_11462_amd.cascade import Cascade
+    prompt = I.token_ids(16, 512, 23, 1).tolist()
+    table = I.default_next_table(512, 1).cuda()
+    levels = [_gpu_level(TARGET, 1, 0.2), _gpu_level(DRAFT1, 2, 0.2)]
+    outs = []
+    for _ in range(2):
+        u = iter(I.uniforms(4000, 77, 3).tolist())
+        got, _ = Cascade(levels, table, [[3, 3], [0, 2]], MAX_CTX, lenience=2.0, mode=0).generate(prompt, 30, u)
+        outs.append(got)
+    assert outs[0] == outs[1]
+    assert all(0 <= t < 512 for t in outs[0])
