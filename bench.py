@@ -214,9 +214,17 @@ def main():
         pr = O.probs_f32(lg)
         on, ot = O.accept(pr, None, hb[:, 1:], u_acc[:1].cpu().numpy(), u_samp[:1].cpu().numpy(), 1.0, mode)
         cpu_s = time.perf_counter() - c0
+        # in-run parity of sequence 0 (untimed): the forward within the logit tolerance, and the accept
+        # decision bit-identical when both sides are given the same distributions (the GPU's)
+        g_lg, g_pr = model.verify_block(block[:1].contiguous(), cache_len[:1].contiguous(), want_probs=True)
+        torch.cuda.synchronize()
+        dl = float(np.abs(g_lg[0].cpu().numpy().astype(np.float64) - lg[0]).max())
+        gn, gt = O.accept((g_lg if mode == 1 else g_pr).cpu().numpy(), None, hb[:, 1:], u_acc[:1].cpu().numpy(), u_samp[:1].cpu().numpy(), 1.0, mode)
         cpu = {"value": round(k / cpu_s, 3), "unit": "verified tokens/s", "cores": O.threads(), "kind": "oracle",
                "sample": f"one whole step of sequence 0 (k={k} drafts, {t}-row cache): {cpu_s:.2f} s",
-               "agrees_with_gpu": bool(int(on[0]) == int(n_acc[0].item()) and int(ot[0]) == int(nxt[0].item()))}
+               "max_abs_dlogit_vs_gpu": round(dl, 6),
+               "accept_identical_on_same_probs": bool(int(gn[0]) == int(n_acc[0].item()) and int(gt[0]) == int(nxt[0].item()))}
+        del on, ot
 
     out = {
         "metric": "verified tokens/s per verify+accept step, 7B-shaped bf16; % HBM/MFMA roofline" if args.workload.startswith("target7b")
