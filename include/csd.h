@@ -161,6 +161,9 @@ int32_t csd_verify_block(csd_model *model, void *kv, const int32_t *tokens, cons
  *           (p must then hold probabilities), q_i(x_i) <= fl32(l*p_i(x_i)); emit the arg-max
  *           of the row after the kept drafts.
  * n_accepted[B] in [0,k]; next_token[B].  1 <= lenience <= 256; k >= 0; V >= 1.
+ * A draft id outside [0, V) cannot be checked on the host (the drafts are on the device): the
+ * kernel treats it as a rejection at that position and draws the replacement from p_i.
+ * next_token is -1 for a row of p that is not a distribution (all weights zero).
  */
 int32_t csd_accept(const float *p, const float *q, const uint8_t *q_onehot, const int32_t *draft,
                    const float *u_acc, const float *u_samp, int32_t B, int32_t k, int32_t V,

@@ -105,3 +105,27 @@ def test_identical_draft_accepts_all_and_errors_are_reported(P):
     assert (gn.cpu().numpy() == k).all()
     with pytest.raises(P.CsdError):
         P.accept(p.cuda(), None, draft.cuda(), u.cuda(), torch.zeros(B).cuda(), lenience=0.5)
+
+
+def test_accept_long_blocks_odd_vocab_and_invalid_draft_ids(P):
+    """More drafts than one wave of acceptance tests (k = 70) and a vocabulary that is not a multiple of 4
+    (rows are not 16-byte aligned), against the oracle; then draft ids outside the vocabulary, which the
+    kernel's bounds check turns into a rejection at that position (the oracle refuses such input)."""
+    O = _O()
+    V, B, k = 1001, 3, 70
+    seed = 4242
+    p = _rand_dist((B, k + 1, V), seed, 1, 3.0)
+    draft = p[:, :k].argmax(-1).int().contiguous()          # likely accepted: long accepted prefixes
+    u_acc = (I.uniforms(B * k, seed, 4).reshape(B, k) * 0.05).contiguous()
+    u_s = I.uniforms(B, seed, 5)
+    for mode, lenience in [(0, 1.0), (0, 2.0), (1, 1.0)]:
+        wn, wt = O.accept(p.numpy(), None, draft.numpy(), u_acc.numpy(), u_s.numpy(), lenience, mode)
+        gn, gt = P.accept(p.cuda(), None, draft.cuda(), u_acc.cuda(), u_s.cuda(), lenience, mode)
+        assert np.array_equal(gn.cpu().numpy(), wn) and np.array_equal(gt.cpu().numpy(), wt), (mode, lenience)
+    assert wn.max() > 64                                       # the second batch of 64 acceptance tests was reached
+    bad = draft.clone()
+    bad[1, 66] = V + 5
+    bad[2, 0] = -1
+    gn, gt = P.accept(p.cuda(), None, bad.cuda(), torch.zeros((B, k)).cuda(), u_s.cuda(), 1.0, 0)
+    gn, gt = gn.cpu().numpy(), gt.cpu().numpy()
+    assert gn[1] == 66 and gn[2] == 0 and (0 <= gt).all() and (gt < V).all()
