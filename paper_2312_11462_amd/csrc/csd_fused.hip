@@ -889,6 +889,12 @@ __device__ __noinline__ void phase_trace(CParams &P, int slot, int wg, int nwg) 
 #define DOWN 1, EPI_RESID, false, 4, 4
 #define LMH2 2, EPI_LOGITS, true, 4, 4
 #define LMH1 1, EPI_LOGITS, true, 4, 8
+// the same phases with the activations read from L2 (blocks whose rows do not fit LDS): half the ring for weights
+#define QKVL 1, EPI_QKV, false, 4, 4
+#define OPRL 1, EPI_RESID, false, 4, 4
+#define GUPL 2, EPI_SWIGLU, false, 4, 2
+#define LM2L 2, EPI_LOGITS, false, 4, 2
+#define LM1L 1, EPI_LOGITS, false, 4, 4
 
 __device__ __forceinline__ GemmArgs gemm_args(CParams &P, const PhaseBufs &X, int phase, int layer) {
     GemmArgs A;
@@ -937,6 +943,7 @@ __device__ __forceinline__ GemmArgs gemm_args(CParams &P, const PhaseBufs &X, in
 }
 
 // issue the first weight batches of a GEMM phase (nothing for the other phases)
+template <bool L2B>
 __device__ __forceinline__ void prefetch_phase(CParams &P, int phase, int layer, int wg, int nwg, u32x4 (&W)[W_RING]) {
     if (phase != PH_QKV && phase != PH_O && phase != PH_GU && phase != PH_DOWN && phase != PH_LM) return;
     const PhaseBufs X{};      // only the weight side of the arguments is used here
@@ -949,7 +956,19 @@ __device__ __forceinline__ void prefetch_phase(CParams &P, int phase, int layer,
         ws.init(A.Wp, A.KS, A.n_items, wg, nwg);             \
         ws.prefetch(W, 0, P.pf);                             \
     }
-    if (phase == PH_QKV) {
+    if (L2B) {
+        if (phase == PH_QKV) {
+            FUSED_PF(QKVL)
+        } else if (phase == PH_O) {
+            FUSED_PF(OPRL)
+        } else if (phase == PH_GU) {
+            FUSED_PF(GUPL)
+        } else if (phase == PH_DOWN) {
+            FUSED_PF(DOWN)
+        } else {
+            if (P.tg_lm == 2) FUSED_PF(LM2L) else FUSED_PF(LM1L)
+        }
+    } else if (phase == PH_QKV) {
         if (P.tg_qkv == 3) FUSED_PF(QKV3) else FUSED_PF(QKV1)
     } else if (phase == PH_O) {
         FUSED_PF(OPRJ)
@@ -964,7 +983,7 @@ __device__ __forceinline__ void prefetch_phase(CParams &P, int phase, int layer,
 #undef FUSED_PF_I
 }
 
-template <int DH>
+template <int DH, bool L2B>
 __device__ __forceinline__ void run_phase(CParams &P, const PhaseBufs &X, int phase, int layer, char *smem, int wg, int nwg, u32x4 (&W)[W_RING],
                           int prefetched) {
     if (phase == PH_EMBED) {
@@ -975,7 +994,22 @@ __device__ __forceinline__ void run_phase(CParams &P, const PhaseBufs &X, int ph
         phase_trace(P, layer, wg, nwg);
     } else {
         const GemmArgs A = gemm_args(P, X, phase, layer);
-        if (phase == PH_QKV) {
+        if (L2B) {
+            if (phase == PH_QKV) {
+                gemm_phase<QKVL>(P, X, A, smem, wg, nwg, W, prefetched);
+            } else if (phase == PH_O) {
+                gemm_phase<OPRL>(P, X, A, smem, wg, nwg, W, prefetched);
+            } else if (phase == PH_GU) {
+                gemm_phase<GUPL>(P, X, A, smem, wg, nwg, W, prefetched);
+            } else if (phase == PH_DOWN) {
+                gemm_phase<DOWN>(P, X, A, smem, wg, nwg, W, prefetched);
+            } else if (phase == PH_LM) {
+                if (P.tg_lm == 2)
+                    gemm_phase<LM2L>(P, X, A, smem, wg, nwg, W, prefetched);
+                else
+                    gemm_phase<LM1L>(P, X, A, smem, wg, nwg, W, prefetched);
+            }
+        } else if (phase == PH_QKV) {
             if (P.tg_qkv == 3)
                 gemm_phase<QKV3>(P, X, A, smem, wg, nwg, W, prefetched);
             else
@@ -996,17 +1030,17 @@ __device__ __forceinline__ void run_phase(CParams &P, const PhaseBufs &X, int ph
 }
 
 // one launch per phase
-template <int DH>
+template <int DH, bool L2B>
 __global__ __launch_bounds__(FUSED_THREADS, 1) void k_fused_phase(const FusedParams P_arg, int phase, int layer) {
     extern __shared__ __align__(16) char smem[];
     CParams &P = P_arg;
     u32x4 W[W_RING];
     const PhaseBufs X = make_bufs(P, phase, layer, 0);
-    run_phase<DH>(P, X, phase, layer, smem, blockIdx.x, gridDim.x, W, 0);
+    run_phase<DH, L2B>(P, X, phase, layer, smem, blockIdx.x, gridDim.x, W, 0);
 }
 
 // the whole forward in one launch
-template <int DH>
+template <int DH, bool L2B>
 __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(const FusedParams P_arg) {
     extern __shared__ __align__(16) char smem[];
     CParams &P = P_arg;
@@ -1024,11 +1058,11 @@ __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(const Fu
     {                                                                  \
         const PhaseBufs X = make_bufs(P, PHASE, LAYER, ts_slot);       \
         ts_mark(P, X, TS_START);                                       \
-        run_phase<DH>(P, X, PHASE, LAYER, smem, wg, nwg, W, (PRE) ? P.pf : 0); \
+        run_phase<DH, L2B>(P, X, PHASE, LAYER, smem, wg, nwg, W, (PRE) ? P.pf : 0); \
         ts_mark(P, X, TS_EPILOGUE);                                    \
         grid_arrive(P, ++epoch, GEMM);                                 \
         if (P.arrive_first) lds_sync();   /* the flag store is issued before this compute unit's prefetch burst */ \
-        prefetch_phase(P, NEXT_PHASE, NEXT_LAYER, wg, nwg, W);         \
+        prefetch_phase<L2B>(P, NEXT_PHASE, NEXT_LAYER, wg, nwg, W);         \
         grid_wait(P, epoch);                                           \
         ts_mark(P, X, TS_BARRIER);                                     \
         ts_slot += TS_PER_PHASE;                                       \
@@ -1055,7 +1089,7 @@ __global__ __launch_bounds__(FUSED_THREADS, 1) void k_verify_persistent(const Fu
     {
         const PhaseBufs X = make_bufs(P, PH_LM, 0, ts_slot);
         ts_mark(P, X, TS_START);
-        run_phase<DH>(P, X, PH_LM, 0, smem, wg, nwg, W, P.pf);
+        run_phase<DH, L2B>(P, X, PH_LM, 0, smem, wg, nwg, W, P.pf);
         ts_mark(P, X, TS_EPILOGUE);
     }
 }
@@ -1076,7 +1110,8 @@ struct FusedState {
     int lds_red_off = 0, lds_rstd_off = 0;
     float *xh = nullptr, *xssq = nullptr;
     bf16_t *xhg = nullptr, *xq = nullptr, *xattn = nullptr, *xffn = nullptr;
-    int m_limit = 0;
+    int m_limit = 0;       // most rows B*m whose activation fragments fit LDS
+    int m_limit_l2b = 0;   // most rows of the variant that reads them from L2 instead
     int fresh = 1;     // tuning knob (env CSD_FUSED_FRESH)
     int pf = 64;       // tuning knob (env CSD_FUSED_PF): ring slots prefetched across a barrier
     int mode = 2;      // 0: off, 1: one launch per phase, 2: persistent
@@ -1141,7 +1176,9 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     if (const char *e = getenv("CSD_FUSED_FRESH")) fs->fresh = atoi(e) ? 1 : 0;
     if (const char *e = getenv("CSD_FUSED_ARRIVE_FIRST")) fs->arrive_first = atoi(e) ? 1 : 0;
     if (const char *e = getenv("CSD_FUSED_PF")) fs->pf = atoi(e) < 0 ? 0 : atoi(e);
+    if (const char *e = getenv("CSD_FUSED_M_LDS")) m_limit = atoi(e) < m_limit ? (atoi(e) < 1 ? 1 : atoi(e)) : m_limit;   // test knob
     fs->m_limit = m_limit < mod->m_max ? m_limit : mod->m_max;
+    fs->m_limit_l2b = getenv("CSD_FUSED_NO_L2B") ? 0 : (16 < mod->m_max ? 16 : mod->m_max);
     const int m_cap = fs->m_limit;
     size_t act_bytes = (size_t)m_cap * kmax * 4;
     if (act_bytes < (size_t)attn_bytes) act_bytes = attn_bytes;
@@ -1181,13 +1218,20 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     // attention partials: [Bmax][H][kg_max][16][dh+4]; reuse the model's buffer when large enough
     const size_t need = sizeof(float) * (size_t)c.max_batch * c.n_heads * fs->kg_max * 16 * (dh + 4);
     if ((rc = fused_alloc(mod, (void **)&mod->fused_attn_part, need, false, st)) != CSD_OK) return rc;
+    const void *kernels[4];
     if (dh == 128) {
-        CSD_HIP(hipFuncSetAttribute((const void *)k_verify_persistent<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fs->lds_bytes));
-        CSD_HIP(hipFuncSetAttribute((const void *)k_fused_phase<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fs->lds_bytes));
+        kernels[0] = (const void *)k_verify_persistent<128, false>;
+        kernels[1] = (const void *)k_verify_persistent<128, true>;
+        kernels[2] = (const void *)k_fused_phase<128, false>;
+        kernels[3] = (const void *)k_fused_phase<128, true>;
     } else {
-        CSD_HIP(hipFuncSetAttribute((const void *)k_verify_persistent<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fs->lds_bytes));
-        CSD_HIP(hipFuncSetAttribute((const void *)k_fused_phase<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fs->lds_bytes));
+        kernels[0] = (const void *)k_verify_persistent<64, false>;
+        kernels[1] = (const void *)k_verify_persistent<64, true>;
+        kernels[2] = (const void *)k_fused_phase<64, false>;
+        kernels[3] = (const void *)k_fused_phase<64, true>;
     }
+    for (const void *kfn : kernels)
+        CSD_HIP(hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fs->lds_bytes));
     mod->fused = fs;
     return CSD_OK;
 }
@@ -1201,7 +1245,9 @@ void csd_fused_free(csd_model *mod) {
 
 bool csd_fused_eligible(const csd_model *mod, int32_t B, int32_t m) {
     const FusedState *fs = (const FusedState *)mod->fused;
-    return fs && B * m <= fs->m_limit && B * m <= 16 && m <= 16;
+    // blocks whose rows fit LDS take the main kernel, blocks of up to 16 rows the variant that reads the
+    // activations from L2
+    return fs && B * m <= (fs->m_limit_l2b > fs->m_limit ? fs->m_limit_l2b : fs->m_limit) && B * m <= 16 && m <= 16;
 }
 
 int32_t csd_fused_path(const csd_model *mod, int32_t B, int32_t m) {
@@ -1236,7 +1282,8 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     P.Bmax = c.max_batch;
     P.kperm = mod->kperm ? 1 : 0;
     P.kg_max = fs->kg_max;
-    P.tg_qkv = fs->tg_qkv;
+    const bool l2b = P.M > fs->m_limit;        // the rows do not fit LDS
+    P.tg_qkv = l2b ? 1 : fs->tg_qkv;
     P.tg_lm = fs->tg_lm;
     P.pf = fs->pf;
     P.fresh = fs->fresh;
@@ -1276,20 +1323,28 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
         P.bar_base = fs->bar_epoch;
         fs->bar_epoch += (unsigned)(1 + 5 * c.n_layers);
         ProfScope ps(mod, st, CSD_PROF_GEMM);
-        if (c.head_dim == 128)
-            hipLaunchKernelGGL((k_verify_persistent<128>), grid, block, fs->lds_bytes, st, P);
+        if (c.head_dim == 128 && !l2b)
+            hipLaunchKernelGGL((k_verify_persistent<128, false>), grid, block, fs->lds_bytes, st, P);
+        else if (c.head_dim == 128)
+            hipLaunchKernelGGL((k_verify_persistent<128, true>), grid, block, fs->lds_bytes, st, P);
+        else if (!l2b)
+            hipLaunchKernelGGL((k_verify_persistent<64, false>), grid, block, fs->lds_bytes, st, P);
         else
-            hipLaunchKernelGGL((k_verify_persistent<64>), grid, block, fs->lds_bytes, st, P);
+            hipLaunchKernelGGL((k_verify_persistent<64, true>), grid, block, fs->lds_bytes, st, P);
         CSD_LAUNCH_CHECK();
         return CSD_OK;
     }
     P.bar_base = 0;
     auto launch = [&](int phase, int layer, int cls) -> int32_t {
         ProfScope ps(mod, st, cls);
-        if (c.head_dim == 128)
-            hipLaunchKernelGGL((k_fused_phase<128>), grid, block, fs->lds_bytes, st, P, phase, layer);
+        if (c.head_dim == 128 && !l2b)
+            hipLaunchKernelGGL((k_fused_phase<128, false>), grid, block, fs->lds_bytes, st, P, phase, layer);
+        else if (c.head_dim == 128)
+            hipLaunchKernelGGL((k_fused_phase<128, true>), grid, block, fs->lds_bytes, st, P, phase, layer);
+        else if (!l2b)
+            hipLaunchKernelGGL((k_fused_phase<64, false>), grid, block, fs->lds_bytes, st, P, phase, layer);
         else
-            hipLaunchKernelGGL((k_fused_phase<64>), grid, block, fs->lds_bytes, st, P, phase, layer);
+            hipLaunchKernelGGL((k_fused_phase<64, true>), grid, block, fs->lds_bytes, st, P, phase, layer);
         CSD_LAUNCH_CHECK();
         return CSD_OK;
     };

@@ -114,6 +114,24 @@ def test_bf16_paths_small_model(shape, gemm, attn, path):
     print(shape.name, gemm, attn, path, "max err", e1, e2)
 
 
+@pytest.mark.parametrize("path", ["phases", "persistent"])
+def test_bf16_single_launch_variant_with_activations_from_l2(path):
+    """Blocks whose rows do not fit LDS (here forced: at most 4 rows in LDS) take the variant of the
+    single-launch kernel that reads the activation fragments from L2: 10 and 16 rows against the oracle."""
+    os.environ["CSD_FUSED_M_LDS"], os.environ["CSD_PATH"] = "4", path
+    try:
+        gm, om = make_pair(BF128, 7, 2, 300, 16, std=0.05)
+    finally:
+        del os.environ["CSD_FUSED_M_LDS"], os.environ["CSD_PATH"]
+    assert gm.path(2, 5) == (2 if path == "persistent" else 1) and gm.path(2, 8) == gm.path(2, 5)
+    toks = I.token_ids(2 * 260, BF128.vocab, 7, 1).reshape(2, 260)
+    prefill_both(gm, om, toks[:, :200], 16)
+    e1 = _check_block(gm, om, toks[:, 200:205].numpy(), [200, 200], 2e-2, 1e-2, "l2b m=5 x2", 5e-3)
+    e2 = _check_block(gm, om, toks[:, 190:198].numpy(), [190, 187], 2e-2, 1e-2, "l2b m=8 x2 ragged", 5e-3)
+    assert gm.error_flag() == 0
+    print("l2b", path, "max err", e1, e2)
+
+
 def test_bf16_block_of_17_rows_two_row_tiles():
     gm, om = make_pair(BF, 9, 1, 200, 17, std=0.05)
     toks = I.token_ids(160, BF.vocab, 9, 1).reshape(1, 160)
