@@ -1,6 +1,7 @@
-// Single-launch review forward for small blocks (M = B*m <= 16 rows): one persistent grid, one
-// workgroup per compute unit, walks through every phase of every layer with a device-wide barrier
-// between phases, so the weights stream from HBM without kernel boundaries in between.
+// Single-launch review forward for small blocks (M = B*m <= 16 rows) of the LLaMA-style decoder: one
+// persistent grid, one workgroup of 8 waves per compute unit, walks through every phase of every layer
+// with a device-wide barrier between phases, so the weights stream from HBM without kernel boundaries
+// in between.
 //
 // Phases of a layer (five barriers):
 //   1. QKV projection; epilogue: scale by the row's RMS factor, rotate q and k (the projection's
@@ -15,13 +16,23 @@
 // RMSNorm is folded around the GEMM: rmsnorm(h)*g @ W = rstd(row) * ((h*g) @ W), so the producer of h
 // writes h*g (two bf16 planes) plus per-tile sums of squares, and the consumer multiplies its output
 // rows by rstd = 1/sqrt(sum/d + eps).  No phase needs a normalisation pass over the activations.
-// A GEMM work item is a group of TG adjacent 16-feature tiles over the whole K; the 8 waves of the
-// workgroup split K, stream their weight fragments through a register ring that runs ahead across
-// items and across the barrier, read the activation fragments (L2-resident) through a second ring,
-// reduce through LDS in a fixed order (deterministic), and one wave per tile applies the epilogue,
-// so no partial sums ever travel through HBM.
+// A GEMM work item is a group of TG adjacent 16-feature tiles over the whole K.  Wave 0 of a workgroup
+// is its service wave (barrier, row scales, reduction and epilogue of each item); waves 1-7 split K,
+// stream their weight fragments through a register ring that runs ahead across items and across the
+// barrier, multiply them with the activation fragments (copied into LDS once per phase, or read from
+// L2 through a second ring where they do not fit), and hand their partial sums to the service wave
+// through LDS, which adds them in a fixed order (deterministic).  No partial sum travels through HBM.
+//
+// Data one workgroup writes for another goes out with write-through stores; every exchanged buffer has
+// one instance per producing phase, so consumers read with ordinary cached loads and no cache has to be
+// invalidated after a barrier.  The barrier itself is a set of one-byte flags in uncached memory, polled
+// with scalar loads.
 //
 // The same phase functions are also launchable one kernel per phase (debugging / comparison).
+// Tuning and test knobs read from the environment at csd_model_create: CSD_PATH=multikernel|phases,
+// CSD_FUSED_PF (ring slots prefetched across a barrier), CSD_FUSED_FRESH=0 (reuse the exchange buffers
+// and invalidate L2 after every barrier), CSD_FUSED_ARRIVE_FIRST=0, CSD_FUSED_VECTOR_POLL,
+// CSD_FUSED_M_LDS (cap on the rows kept in LDS), CSD_FUSED_NO_L2B.
 #include <mutex>
 #include <vector>
 
