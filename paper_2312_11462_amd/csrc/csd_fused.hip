@@ -184,6 +184,15 @@ __device__ __forceinline__ void co_st16(__amdgpu_buffer_rsrc_t r, int off, bf16_
     __builtin_amdgcn_raw_buffer_store_b16(v, r, off, 0, CSD_SC1);
 }
 
+// Workgroup barrier after which every global store issued before it by any wave of the workgroup has
+// been acknowledged.  The compiler's workgroup barrier alone does not give that: waves of a workgroup
+// share one vector cache, so it only waits for LDS traffic, while the write-through stores here must have
+// reached the level other workgroups read from before anything (a counter, a flag) announces them.
+__device__ __forceinline__ void stores_acked_sync() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
+    __syncthreads();
+}
+
 // ------------------------------------------------------------------------------ grid barrier
 
 // Flag barrier without read-modify-write atomics: workgroup w stores the number of the barrier it has
@@ -211,7 +220,7 @@ __device__ __forceinline__ void grid_arrive(CParams &P, unsigned epoch, bool ser
     if (service_only) {
         if (threadIdx.x < 64) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's stores are acknowledged
     } else {
-        __syncthreads();        // all of this workgroup's write-through stores have been acknowledged
+        stores_acked_sync();
     }
     if (threadIdx.x < BAR_REPLICAS) {
         const __amdgpu_buffer_rsrc_t rb = co_rsrc(P.bar, BAR_BYTES);
@@ -697,6 +706,81 @@ __device__ __forceinline__ void gemm_phase(CParams &P, const PhaseBufs &X, const
 #undef FUSED_MMA
 }
 
+#define ATTN_BATCH 16   /* items a workgroup works off before it counts them in */
+
+// Second stage of the attention phase for the n items whose partial states this workgroup has written:
+// wait once for all those stores, count every item into its (sequence, head) counter (one lane each),
+// and for each head where this workgroup was the last key group to finish, merge all its groups and
+// write the attention output.  Doing this once per batch of items, not once per item, keeps the chain
+// store acknowledgement -> counter -> partial loads off the per-item path.
+template <int DH>
+__device__ __forceinline__ void attn_finish(CParams &P, __amdgpu_buffer_rsrc_t ro, const int *s_item, int *s_last, int n) {
+    constexpr int PS = DH + 4;
+    const int tid = threadIdx.x;
+    const size_t part_elems = (size_t)16 * PS;
+    stores_acked_sync();    // the partial states of all n items
+    if (tid < n) {
+        const int item = s_item[tid];
+        const int hh = (item / P.kg_max) % P.H, b = item / (P.kg_max * P.H);
+        const int nk = max(0, min(P.cache_len[b] + P.m, P.seq_pad));
+        const int n_groups = (nk + 255) / 256;
+        const unsigned old = __hip_atomic_fetch_add(P.attn_cnt + b * P.H + hh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last[tid] = (old == (unsigned)(n_groups - 1));
+    }
+    __syncthreads();
+    for (int i = 0; i < n; i++) {
+        if (!s_last[i]) continue;           // uniform
+        const int item = s_item[i];
+        const int hh = (item / P.kg_max) % P.H, b = item / (P.kg_max * P.H);
+        const int nk = max(0, min(P.cache_len[b] + P.m, P.seq_pad));
+        const int n_groups = (nk + 255) / 256;
+        const __amdgpu_buffer_rsrc_t rp =
+            co_rsrc(P.attn_part + (size_t)((b * P.H + hh) * P.kg_max) * part_elems, sizeof(float) * part_elems * P.kg_max);
+        for (int idx = tid; idx < P.m * (DH / 4); idx += FUSED_THREADS) {
+            const int r = idx / (DH / 4), x4 = idx % (DH / 4);
+            // eight groups' states in flight together (one memory round trip for the usual case), groups
+            // combined in index order
+            float mstar = -INFINITY, den = 0.f;
+            f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int c0 = 0; c0 < n_groups; c0 += 8) {
+                float mc[8], dc[8];
+                f32x4 nc[8];
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    const int c = min(c0 + u, n_groups - 1);
+                    const int base = (int)(((size_t)c * part_elems + (size_t)r * PS) * 4);
+                    mc[u] = co_ld32f(rp, base + DH * 4);
+                    dc[u] = co_ld32f(rp, base + (DH + 1) * 4);
+                    nc[u] = co_ld128f(rp, base + x4 * 16);
+                }
+                float mchunk = mstar;
+#pragma unroll
+                for (int u = 0; u < 8; u++)
+                    if (c0 + u < n_groups) mchunk = fmaxf(mchunk, mc[u]);
+                const float a = (mstar == -INFINITY) ? 0.f : expf(mstar - mchunk);
+                num *= a;
+                den *= a;
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    const float wgt = (c0 + u >= n_groups || mc[u] == -INFINITY) ? 0.f : expf(mc[u] - mchunk);
+                    num += nc[u] * wgt;
+                    den += dc[u] * wgt;
+                }
+                mstar = mchunk;
+            }
+            const float inv = den > 0.f ? 1.0f / den : 0.f;
+            float o[4] = {num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
+            u32x2 hi, lo;
+            split4(o, hi, lo);
+            const int off = (int)(((size_t)(b * P.m + r) * P.hd + hh * DH + x4 * 4) * 2);
+            co_st64(ro, off, hi);
+            co_st64(ro, off + (int)(P.q_plane * 2), lo);
+        }
+        if (tid == 0) __hip_atomic_store(P.attn_cnt + b * P.H + hh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();        // s_item / s_last may be reused
+}
+
 // Block attention for one 16-row tile per sequence (m <= 16).
 template <int DH>
 __device__ __noinline__ void phase_attn(CParams &P, int layer, char *smem, int wg, int nwg) {
@@ -705,7 +789,9 @@ __device__ __noinline__ void phase_attn(CParams &P, int layer, char *smem, int w
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int col = lane & 15, g = lane >> 4;
     float *lacc = reinterpret_cast<float *>(smem);              // [8 waves][16 rows][PS]
-    __shared__ int s_last;
+    // items whose partial state this workgroup has written and not yet counted in (see attn_finish)
+    __shared__ int s_item[ATTN_BATCH], s_last[ATTN_BATCH];
+    int n_mine = 0;
     const KvGeom geo{P.Bmax, P.H, P.dh, P.seq_pad, P.L, P.kperm};
     const __amdgpu_buffer_rsrc_t ro = co_rsrc(X.attn_o, 2 * (P.q_plane * 2));
     const int items = P.B * P.H * P.kg_max;
@@ -833,57 +919,15 @@ __device__ __noinline__ void phase_attn(CParams &P, int layer, char *smem, int w
                 co_st32f(rp, (int)(((size_t)kg * part_elems + (size_t)r * PS + DH + 1) * 4), den);
             }
         }
-        __syncthreads();        // every partial store of this workgroup has been acknowledged
-        if (tid == 0) {
-            const unsigned old = __hip_atomic_fetch_add(P.attn_cnt + b * P.H + hh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (old == (unsigned)(n_groups - 1));
+        // the LDS merge area is free again; the partial stores stay in flight while the next item is computed
+        lds_sync();
+        if (tid == 0) s_item[n_mine] = item;
+        if (++n_mine == ATTN_BATCH) {
+            attn_finish<DH>(P, ro, s_item, s_last, n_mine);
+            n_mine = 0;
         }
-        __syncthreads();
-        if (s_last) {           // the last key group to finish merges all of them
-            for (int idx = tid; idx < P.m * (DH / 4); idx += FUSED_THREADS) {
-                const int r = idx / (DH / 4), x4 = idx % (DH / 4);
-                // eight groups' states in flight together (one memory round trip for the usual case), groups
-                // combined in index order
-                float mstar = -INFINITY, den = 0.f;
-                f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
-                for (int c0 = 0; c0 < n_groups; c0 += 8) {
-                    float mc[8], dc[8];
-                    f32x4 nc[8];
-#pragma unroll
-                    for (int u = 0; u < 8; u++) {
-                        const int c = min(c0 + u, n_groups - 1);
-                        const int base = (int)(((size_t)c * part_elems + (size_t)r * PS) * 4);
-                        mc[u] = co_ld32f(rp, base + DH * 4);
-                        dc[u] = co_ld32f(rp, base + (DH + 1) * 4);
-                        nc[u] = co_ld128f(rp, base + x4 * 16);
-                    }
-                    float mchunk = mstar;
-#pragma unroll
-                    for (int u = 0; u < 8; u++)
-                        if (c0 + u < n_groups) mchunk = fmaxf(mchunk, mc[u]);
-                    const float a = (mstar == -INFINITY) ? 0.f : expf(mstar - mchunk);
-                    num *= a;
-                    den *= a;
-#pragma unroll
-                    for (int u = 0; u < 8; u++) {
-                        const float wgt = (c0 + u >= n_groups || mc[u] == -INFINITY) ? 0.f : expf(mc[u] - mchunk);
-                        num += nc[u] * wgt;
-                        den += dc[u] * wgt;
-                    }
-                    mstar = mchunk;
-                }
-                const float inv = den > 0.f ? 1.0f / den : 0.f;
-                float o[4] = {num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
-                u32x2 hi, lo;
-                split4(o, hi, lo);
-                const int off = (int)(((size_t)(b * P.m + r) * P.hd + hh * DH + x4 * 4) * 2);
-                co_st64(ro, off, hi);
-                co_st64(ro, off + (int)(P.q_plane * 2), lo);
-            }
-            if (tid == 0) __hip_atomic_store(P.attn_cnt + b * P.H + hh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __syncthreads();
     }
+    if (n_mine > 0) attn_finish<DH>(P, ro, s_item, s_last, n_mine);
 }
 
 __device__ __noinline__ void phase_trace(CParams &P, int slot, int wg, int nwg) {
