@@ -134,6 +134,129 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp,
     }
 }
 
+// The same contraction for blocks of more than 16 rows (several sequences times several drafts).
+// There the per-wave form above re-reads the activations once per wave; here the 4 waves of a
+// workgroup cover 4 * NT adjacent output tiles of one K slice and share the activation fragments
+// through LDS: per chunk of U k-steps every thread fetches its share of the chunk after next into
+// registers while the matrix cores work on the current one, and LDS holds two chunks
+// ([chunk][u][row tile][hi|lo plane][lane] in MFMA operand order, so a fragment is one conflict-free
+// 16-byte LDS read).  Weights stream from HBM through a two-chunk register ring as above.
+template <int NT, int MT, int U>
+__global__ __launch_bounds__(256) void k_gemm_wg(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
+                                                 float *__restrict__ part, int M, int K, int N, int S) {
+    extern __shared__ __align__(16) char wg_smem[];
+    constexpr int CH = U * MT * 2 * 64;                      // 16-byte fragments per chunk
+    static_assert(CH % 256 == 0, "chunk must divide over the workgroup");
+    constexpr int ST = CH / 256;                             // staging loads per thread and chunk
+    u32x4 *lbuf = reinterpret_cast<u32x4 *>(wg_smem);        // [2][CH]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s = blockIdx.x % S, grp = blockIdx.x / S;
+    const int KS = K / 32, n_tiles = N / 16;
+    const int ks0 = (int)((long long)KS * s / S), ks1 = (int)((long long)KS * (s + 1) / S);
+    const int t = lane & 15, g = lane >> 4;
+    const int tile0 = (grp * 4 + w) * NT;
+
+    const u32x4 *wp[NT];
+    bool tv[NT];
+#pragma unroll
+    for (int j = 0; j < NT; j++) {
+        tv[j] = tile0 + j < n_tiles;
+        wp[j] = Wp + ((size_t)(tv[j] ? tile0 + j : 0) * KS) * 64 + lane;
+    }
+    // staging: fragment i * 256 + tid of a chunk = (u, row tile, plane, lane) in that order
+    const bf16_t *abase = act + (size_t)(w & 1) * plane + 8 * g;
+    int soff[ST], su[ST];
+#pragma unroll
+    for (int i = 0; i < ST; i++) {
+        const int r2 = i * 2 + (w >> 1), mt = r2 % MT, u = r2 / MT, row = mt * 16 + t;
+        su[i] = row < M ? u : (1 << 28);                     // rows past M never pass the k-step test below
+        soff[i] = (row < M ? row : 0) * K + u * 32;
+    }
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 wa[U][NT], wb[U][NT], st[ST];
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+
+#define CSD_WG_LOAD_W(WF, KS_AT)                                                                  \
+    _Pragma("unroll") for (int u = 0; u < U; u++) {                                               \
+        const int ksu_ = (KS_AT) + u;                                                             \
+        _Pragma("unroll") for (int j = 0; j < NT; j++)                                            \
+            WF[u][j] = (ksu_ < ks1 && tv[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero; \
+    }
+#define CSD_WG_LOAD_ACT(KS_AT)                                                                    \
+    _Pragma("unroll") for (int i = 0; i < ST; i++)                                                \
+        st[i] = ((KS_AT) + su[i] < ks1)                                                           \
+                    ? *reinterpret_cast<const u32x4 *>(abase + (size_t)soff[i] + (size_t)(KS_AT) * 32) : zero;
+#define CSD_WG_PUT_ACT(BUF)                                                                       \
+    _Pragma("unroll") for (int i = 0; i < ST; i++) lbuf[(BUF) * CH + i * 256 + tid] = st[i];
+// fragment idx = u * MT + row tile; its two planes are read two fragments ahead of their use, and the
+// scheduling fences keep the compiler from hoisting every LDS read of the chunk to the top (which would
+// not fit the register file for tall blocks)
+#define CSD_WG_MMA(WF, BUF)                                                                       \
+    {                                                                                             \
+        const u32x4 *lb_ = lbuf + (BUF) * CH + lane;                                              \
+        u32x4 b_[3][2];                                                                           \
+        b_[0][0] = lb_[0];                                                                        \
+        b_[0][1] = lb_[64];                                                                       \
+        b_[1][0] = lb_[128];                                                                      \
+        b_[1][1] = lb_[192];                                                                      \
+        _Pragma("unroll") for (int idx = 0; idx < U * MT; idx++) {                                \
+            if (idx + 2 < U * MT) {                                                               \
+                b_[(idx + 2) % 3][0] = lb_[(idx + 2) * 128];                                      \
+                b_[(idx + 2) % 3][1] = lb_[(idx + 2) * 128 + 64];                                 \
+            }                                                                                     \
+            const int u = idx / MT, mt = idx % MT;                                                \
+            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
+                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, b_[idx % 3][0]), acc[mt][j], 0, 0, 0); \
+            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
+                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, b_[idx % 3][1]), acc[mt][j], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0);                                                    \
+        }                                                                                         \
+    }
+
+    CSD_WG_LOAD_ACT(ks0)
+    CSD_WG_LOAD_W(wa, ks0)
+    CSD_WG_PUT_ACT(0)
+    lds_sync();
+    for (int ks = ks0; ks < ks1; ks += 2 * U) {
+        CSD_WG_LOAD_W(wb, ks + U)
+        CSD_WG_LOAD_ACT(ks + U)
+        CSD_WG_MMA(wa, 0)
+        if (ks + U >= ks1) break;                            // uniform
+        CSD_WG_PUT_ACT(1)
+        lds_sync();
+        CSD_WG_LOAD_W(wa, ks + 2 * U)
+        CSD_WG_LOAD_ACT(ks + 2 * U)
+        CSD_WG_MMA(wb, 1)
+        CSD_WG_PUT_ACT(0)
+        lds_sync();
+    }
+#undef CSD_WG_LOAD_W
+#undef CSD_WG_LOAD_ACT
+#undef CSD_WG_PUT_ACT
+#undef CSD_WG_MMA
+
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        const int row = mt * 16 + t;
+        if (row < M) {
+#pragma unroll
+            for (int j = 0; j < NT; j++)
+                if (tv[j]) {
+                    float *o = part + ((size_t)s * M + row) * N + (size_t)(tile0 + j) * 16 + 4 * g;
+                    *reinterpret_cast<f32x4 *>(o) = acc[mt][j];
+                }
+        }
+    }
+}
+
 // Generic GEMM (fp32 models and the debugging path): one thread per output column, fp32
 // activations [M][K], row-major weights [K][N]; writes partial plane 0.
 template <typename TW>
@@ -452,11 +575,70 @@ static void launch_gemm_mfma_nt(const GemmW &w, const bf16_t *act, size_t plane,
         hipLaunchKernelGGL((k_gemm_mfma<NT, 9, 1>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
 }
 
-// act: [M][w.K] in the path's activation type; part: [w.S][M][w.N]
-static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, hipStream_t st) {
+// k-steps per chunk: 4 while the accumulators (16 * MT * NT registers) leave room for a weight ring that
+// deep, 2 for the tallest blocks (which are bound by the matrix cores, not by prefetch depth)
+#define WG_U_MAX 4
+template <int NT, int MT>
+static int32_t launch_gemm_wg_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
+                                 hipStream_t st) {
+    constexpr int WG_U = MT <= 5 ? WG_U_MAX : 2;
+    static bool attr_set = false;                            // per instantiation; the attribute is idempotent
+    const size_t lds = (size_t)2 * WG_U * MT * 2 * 64 * 16;
+    if (!attr_set) {
+        CSD_HIP(hipFuncSetAttribute((const void *)k_gemm_wg<NT, MT, WG_U>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_gemm_wg<NT, MT, WG_U>), dim3(groups * S), dim3(256), lds, st, reinterpret_cast<const u32x4 *>(w.data),
+                       act, plane, part, M, w.K, w.N, S);
+    return CSD_OK;
+}
+
+template <int NT>
+static int32_t launch_gemm_wg_nt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
+                                 hipStream_t st) {
+    switch ((M + 15) / 16) {
+    case 2: return launch_gemm_wg_mt<NT, 2>(w, act, plane, part, M, S, groups, st);
+    case 3: return launch_gemm_wg_mt<NT, 3>(w, act, plane, part, M, S, groups, st);
+    case 4: return launch_gemm_wg_mt<NT, 4>(w, act, plane, part, M, S, groups, st);
+    case 5: return launch_gemm_wg_mt<NT, 5>(w, act, plane, part, M, S, groups, st);
+    case 6: return launch_gemm_wg_mt<NT, 6>(w, act, plane, part, M, S, groups, st);
+    case 7: return launch_gemm_wg_mt<NT, 7>(w, act, plane, part, M, S, groups, st);
+    case 8:
+        if constexpr (NT <= 2) return launch_gemm_wg_mt<NT, 8>(w, act, plane, part, M, S, groups, st);
+        return CSD_ESHAPE;
+    case 9:
+        if constexpr (NT <= 2) return launch_gemm_wg_mt<NT, 9>(w, act, plane, part, M, S, groups, st);
+        return CSD_ESHAPE;
+    default: return CSD_ESHAPE;
+    }
+}
+
+// Tile width and K splits of the workgroup-tiled GEMM: 256 columns per workgroup when that still gives
+// every compute unit a workgroup, else 128; K is split (never finer than the partial-sum buffer was
+// sized for, nor below two chunks per slice) until there is about one workgroup per compute unit.
+static int32_t launch_gemm_wg(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int *S_used, hipStream_t st) {
+    const int n_tiles = w.N / 16, KS = w.K / 32;
+    int nt = 4, groups = (n_tiles + 15) / 16;
+    if (groups * w.S < 256 || M > 112) {                     // 8 or 9 row tiles x 4 column tiles do not fit the registers
+        nt = 2;
+        groups = (n_tiles + 7) / 8;
+    }
+    int S = 1;
+    while (groups * S < 256 && S * 2 <= w.S && KS / (S * 2) >= 2 * WG_U_MAX) S *= 2;
+    *S_used = S;
+    return nt == 4 ? launch_gemm_wg_nt<4>(w, act, plane, part, M, S, groups, st)
+                   : launch_gemm_wg_nt<2>(w, act, plane, part, M, S, groups, st);
+}
+
+// act: [M][w.K] in the path's activation type; part: [S][M][w.N] with S (<= w.S) returned in *S_used
+static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, int *S_used, hipStream_t st) {
     ProfScope ps(mod, st, CSD_PROF_GEMM);
+    *S_used = w.S;
     if (mod->mfma) {
-        if (w.nt == 2)
+        if (M > 16 && M <= 144 && mod->gemm_wg) {
+            const int32_t rc = launch_gemm_wg(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st);
+            if (rc != CSD_OK) return rc;
+        } else if (w.nt == 2)
             launch_gemm_mfma_nt<2, 4>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);
         else
             launch_gemm_mfma_nt<1, 8>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);
@@ -485,6 +667,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     const int lda = d > F ? (d > hd ? d : hd) : (F > hd ? F : hd);   // rows of `act` are reused at several widths
     (void)lda;
     const float scale = 1.0f / sqrtf((float)c.head_dim);
+    int S_g = 1;            // K splits the last GEMM wrote partial sums for
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
@@ -495,10 +678,10 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     for (int l = 0; l < L; l++) {
         const LayerW &lw = mod->layers[l];
         int32_t rc;
-        if ((rc = run_gemm(mod, lw.qkv, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.qkv, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
-            hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, lw.qkv.S, M, m,
+            hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, S_g, M, m,
                                cache_len, geo, l, c.rope_theta, qb, mod->q_plane, (TC *)kv);
             CSD_LAUNCH_CHECK();
         }
@@ -511,25 +694,25 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
                                (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane, AttnMode{});
             CSD_LAUNCH_CHECK();
         }
-        if ((rc = run_gemm(mod, lw.o, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.o, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
-            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, lw.o.S, M, d, lw.ffn_norm,
+            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, lw.ffn_norm,
                                c.rms_eps, mod->h, act, d, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
-        if ((rc = run_gemm(mod, lw.gu, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.gu, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
-            hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, lw.gu.S, M, F,
+            hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, F,
                                mod->mfma ? 1 : 0, act, F, mod->act_plane, 0);
             CSD_LAUNCH_CHECK();
         }
-        if ((rc = run_gemm(mod, lw.down, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.down, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             const float *g = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
-            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, lw.down.S, M, d, g,
+            hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, g,
                                c.rms_eps, mod->h, act, d, mod->act_plane);
             CSD_LAUNCH_CHECK();
         }
@@ -538,10 +721,10 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
                                    hipMemcpyDeviceToDevice, st));
     }
     int32_t rc;
-    if ((rc = run_gemm(mod, mod->lm, act, M, st)) != CSD_OK) return rc;
+    if ((rc = run_gemm(mod, mod->lm, act, M, &S_g, st)) != CSD_OK) return rc;
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
-        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, mod->lm.S, M, V, logits);
+        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, V, logits);
         CSD_LAUNCH_CHECK();
     }
     return CSD_OK;
@@ -581,9 +764,10 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
     self_mode.bucket = mod->rel_bucket;
     cross_mode.fixed_nk = c.enc_len;
     int32_t rc;
-    auto resid_norm = [&](const GemmW &w, const float *gain) -> int32_t {
+    int S_g = 1;            // K splits the last GEMM wrote partial sums for
+    auto resid_norm = [&](const GemmW &, const float *gain) -> int32_t {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
-        hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, w.S, M, d, gain, c.rms_eps, mod->h, act,
+        hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, gain, c.rms_eps, mod->h, act,
                            d, mod->act_plane);
         CSD_LAUNCH_CHECK();
         return CSD_OK;
@@ -597,43 +781,43 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
     for (int l = 0; l < L; l++) {
         const LayerW &lw = mod->layers[l];
-        if ((rc = run_gemm(mod, lw.qkv, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.qkv, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
-            hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, lw.qkv.S, M, m, cache_len,
+            hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, S_g, M, m, cache_len,
                                geo, l, 0.0f, qb, mod->q_plane, (TC *)kv);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = attention_any<TA, TC>(mod, geo, kv, cache_len, B, m, l, 1.0f, self_mode, st)) != CSD_OK) return rc;
-        if ((rc = run_gemm(mod, lw.o, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.o, act, M, &S_g, st)) != CSD_OK) return rc;
         if ((rc = resid_norm(lw.o, lw.cross_norm)) != CSD_OK) return rc;
-        if ((rc = run_gemm(mod, lw.cq, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.cq, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
-            hipLaunchKernelGGL((k_fix_plain<TA>), dim3((hd + 255) / 256, M), dim3(256), 0, st, mod->part, lw.cq.S, M, hd, qb, hd,
+            hipLaunchKernelGGL((k_fix_plain<TA>), dim3((hd + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, hd, qb, hd,
                                mod->q_plane);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = attention_any<TA, TC>(mod, cgeo, kv_cross, cache_len, B, m, l, 1.0f, cross_mode, st)) != CSD_OK) return rc;
-        if ((rc = run_gemm(mod, lw.co, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.co, act, M, &S_g, st)) != CSD_OK) return rc;
         if ((rc = resid_norm(lw.co, lw.ffn_norm)) != CSD_OK) return rc;
-        if ((rc = run_gemm(mod, lw.gu, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.gu, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
-            hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, lw.gu.S, M, F,
+            hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, F,
                                mod->mfma ? 1 : 0, act, F, mod->act_plane, 1);
             CSD_LAUNCH_CHECK();
         }
-        if ((rc = run_gemm(mod, lw.down, act, M, st)) != CSD_OK) return rc;
+        if ((rc = run_gemm(mod, lw.down, act, M, &S_g, st)) != CSD_OK) return rc;
         if ((rc = resid_norm(lw.down, (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm)) != CSD_OK) return rc;
         if (mod->trace)
             CSD_HIP(hipMemcpyAsync(mod->trace + (size_t)(l + 1) * M * d, mod->h, sizeof(float) * (size_t)M * d,
                                    hipMemcpyDeviceToDevice, st));
     }
-    if ((rc = run_gemm(mod, mod->lm, act, M, st)) != CSD_OK) return rc;
+    if ((rc = run_gemm(mod, mod->lm, act, M, &S_g, st)) != CSD_OK) return rc;
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
-        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, mod->lm.S, M, V, logits);
+        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, V, logits);
         CSD_LAUNCH_CHECK();
     }
     return CSD_OK;
@@ -648,6 +832,7 @@ static int32_t cross_init_typed(csd_model *mod, void *kv, const float *enc_out, 
     TC *kvc = (TC *)((char *)kv + csd_self_kv_bytes(mod));
     const int chunk = mod->m_max;       // the activation and partial-sum buffers hold this many rows
     int32_t rc;
+    int S_g = 1;
     for (int b = 0; b < B; b++)
         for (int row0 = 0; row0 < E; row0 += chunk) {
             const int rows = E - row0 < chunk ? E - row0 : chunk;
@@ -660,9 +845,9 @@ static int32_t cross_init_typed(csd_model *mod, void *kv, const float *enc_out, 
             }
             for (int l = 0; l < c.n_layers; l++) {
                 const LayerW &lw = mod->layers[l];
-                if ((rc = run_gemm(mod, lw.ckv, mod->act, rows, st)) != CSD_OK) return rc;
+                if ((rc = run_gemm(mod, lw.ckv, mod->act, rows, &S_g, st)) != CSD_OK) return rc;
                 ProfScope ps(mod, st, CSD_PROF_OTHER);
-                hipLaunchKernelGGL((k_fix_cross_kv<TC>), dim3((hd + 255) / 256, rows), dim3(256), 0, st, mod->part, lw.ckv.S, rows,
+                hipLaunchKernelGGL((k_fix_cross_kv<TC>), dim3((hd + 255) / 256, rows), dim3(256), 0, st, mod->part, S_g, rows,
                                    cgeo, l, b, row0, kvc);
                 CSD_LAUNCH_CHECK();
             }

@@ -157,6 +157,7 @@ struct csd_model {
     csd_model_cfg cfg;
     bool mfma = false;        // bf16 tiles + MFMA GEMMs; otherwise generic kernels on row-major weights
     bool mfma_attn = false;
+    bool gemm_wg = true;      // blocks of more than 16 rows: workgroup-tiled GEMM with activations shared through LDS
     bool kperm = false;       // q / K rows kept in rotary pair order (see KvGeom)
     int hd = 0;               // n_heads * head_dim
     int seq_pad = 0;          // cache rows per sequence, padded to 64

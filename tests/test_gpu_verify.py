@@ -139,6 +139,24 @@ def test_bf16_block_of_17_rows_two_row_tiles():
     _check_block(gm, om, toks[:, 130:147].numpy(), [130], 2e-2, 1e-2, "m=17")
 
 
+WIDE = I.ModelShape("bf_wide_blocks", 0, "bf16", 2, 256, 4, 64, 576, 1040)
+
+
+@pytest.mark.parametrize("B,m", [(4, 5), (4, 9), (4, 13), (4, 17), (8, 12), (8, 14), (8, 16), (8, 17)])
+def test_bf16_blocks_of_2_to_9_row_tiles_workgroup_tiled_gemm(B, m):
+    """B * m = 20 ... 136 rows: every row-tile count of the GEMM that shares activations through LDS; the
+    FFN width (18 k-steps) leaves ragged chunk tails and the vocabulary (65 column tiles) a ragged last
+    workgroup."""
+    gm, om = make_pair(WIDE, 17, B, 96, 17, std=0.05)
+    assert gm.path(B, m) == 0
+    toks = I.token_ids(B * 64, WIDE.vocab, 17, 1).reshape(B, 64)
+    prefill_both(gm, om, toks[:, :32], 16)
+    cl = [32 - (b % 3) for b in range(B)]                  # ragged cache lengths
+    blocks = np.stack([toks[b, cl[b]:cl[b] + m].numpy() for b in range(B)])
+    err = _check_block(gm, om, blocks, cl, 2e-2, 1e-2, f"B={B} m={m}")
+    print("rows", B * m, "max err", err)
+
+
 def test_draft160m_config_synthetic_cache():
     """Configuration 2: 160M-shaped bf16 model, 512 cached rows (seeded stand-in K/V, since the
     oracle needs minutes to prefill them), k = 8 drafts from the Max-Gram model."""
