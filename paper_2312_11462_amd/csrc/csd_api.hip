@@ -28,6 +28,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->mfma = c.dtype == CSD_DTYPE_BF16 && tiles_ok && !env_is("CSD_GEMM", "generic");
     mod->kperm = mod->mfma && c.arch == 0;     // rotary pair order only where there is a rotary embedding
     mod->gemm_wg = !env_is("CSD_GEMM_WG", "0");
+    if (const char *e = getenv("CSD_GEMM_WS_MIN_ROWS")) mod->gemm_ws_min_rows = atoi(e);
     mod->mfma_attn = mod->mfma && (c.head_dim == 64 || c.head_dim == 128) && !env_is("CSD_ATTN", "generic");
     const int keys_pad = mod->seq_pad > mod->enc_pad ? mod->seq_pad : mod->enc_pad;
     if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + keys_pad) > 64 * 1024) return CSD_ESHAPE;

@@ -257,6 +257,152 @@ __global__ __launch_bounds__(256) void k_gemm_wg(const u32x4 *__restrict__ Wp, c
     }
 }
 
+// The workgroup-tiled GEMM with the two jobs given to different waves: waves 0-3 only stream weights and
+// feed the matrix cores (4 * NT column tiles, all row tiles), waves 4-7 only move activation fragments from
+// L2 to LDS, two chunks ahead in registers and one chunk ahead in LDS.  A wave that waits for its oldest
+// load also waits for nothing younger, so with the jobs apart the weight ring and the activation staging
+// each keep their own depth; one workgroup barrier per chunk hands a staged chunk over and frees the other
+// buffer.  Both kinds of waves pass exactly 1 + (number of chunks) barriers.
+template <int NT, int MT, int U>
+__global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
+                                                 float *__restrict__ part, int M, int K, int N, int S) {
+    extern __shared__ __align__(16) char wg_smem[];
+    constexpr int CH = U * MT * 2 * 64;                      // 16-byte fragments per chunk
+    static_assert(CH % 256 == 0, "chunk must divide over the staging waves");
+    constexpr int ST = CH / 256;                             // staging loads per staging thread and chunk
+    constexpr int PD = 4;                                    // LDS fragments are read this many (u, row tile) steps ahead
+    static_assert(U * MT >= PD, "chunk shorter than the LDS prefetch distance");
+    u32x4 *lbuf = reinterpret_cast<u32x4 *>(wg_smem);        // [2][CH]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s = blockIdx.x % S, grp = blockIdx.x / S;
+    const int KS = K / 32, n_tiles = N / 16;
+    const int ks0 = (int)((long long)KS * s / S), ks1 = (int)((long long)KS * (s + 1) / S);
+    const int n_chunks = (ks1 - ks0 + U - 1) / U;
+    const int t = lane & 15, g = lane >> 4;
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+
+    if (w < 4) {
+        // ------------------------------------------------------------ weight stream + matrix cores
+        const int tile0 = (grp * 4 + w) * NT;
+        const u32x4 *wp[NT];
+        bool tv[NT];
+#pragma unroll
+        for (int j = 0; j < NT; j++) {
+            tv[j] = tile0 + j < n_tiles;
+            wp[j] = Wp + ((size_t)(tv[j] ? tile0 + j : 0) * KS) * 64 + lane;
+        }
+        f32x4 acc[MT][NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        u32x4 wa[U][NT], wb[U][NT];
+
+#define CSD_WS_LOAD_W(WF, KS_AT)                                                                  \
+    _Pragma("unroll") for (int u = 0; u < U; u++) {                                               \
+        const int ksu_ = (KS_AT) + u;                                                             \
+        _Pragma("unroll") for (int j = 0; j < NT; j++)                                            \
+            WF[u][j] = (ksu_ < ks1 && tv[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero; \
+    }
+#define CSD_WS_MMA(WF, BUF, KS_NEXT)                                                              \
+    {                                                                                             \
+        const u32x4 *lb_ = lbuf + (BUF) * CH + lane;                                              \
+        u32x4 b_[PD + 1][2];                                                                      \
+        _Pragma("unroll") for (int p = 0; p < PD; p++) {                                          \
+            b_[p][0] = lb_[p * 128];                                                              \
+            b_[p][1] = lb_[p * 128 + 64];                                                         \
+        }                                                                                         \
+        _Pragma("unroll") for (int idx = 0; idx < U * MT; idx++) {                                \
+            if (idx + PD < U * MT) {                                                              \
+                b_[(idx + PD) % (PD + 1)][0] = lb_[(idx + PD) * 128];                             \
+                b_[(idx + PD) % (PD + 1)][1] = lb_[(idx + PD) * 128 + 64];                        \
+            }                                                                                     \
+            const int u = idx / MT, mt = idx % MT;                                                \
+            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
+                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, b_[idx % (PD + 1)][0]), acc[mt][j], 0, 0, 0); \
+            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
+                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, b_[idx % (PD + 1)][1]), acc[mt][j], 0, 0, 0); \
+            if (mt == MT - 1) { /* this k-step's weight registers are free: fetch the k-step 2 * U ahead */ \
+                const int ksn_ = (KS_NEXT) + u;                                                   \
+                _Pragma("unroll") for (int j = 0; j < NT; j++)                                    \
+                    WF[u][j] = (ksn_ < ks1 && tv[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)ksn_ * 64) : zero; \
+            }                                                                                     \
+            __builtin_amdgcn_sched_barrier(0);                                                    \
+        }                                                                                         \
+    }
+
+        // the weight ring holds 2 * U k-steps and is refilled k-step by k-step, so every load is issued
+        // 2 * U k-steps before its use
+        CSD_WS_LOAD_W(wa, ks0)
+        CSD_WS_LOAD_W(wb, ks0 + U)
+        lds_sync();                                          // chunk 0 is in LDS
+        for (int c = 0; c < n_chunks; c += 2) {
+            CSD_WS_MMA(wa, 0, ks0 + (c + 2) * U)
+            lds_sync();                                      // chunk c consumed, chunk c + 1 staged
+            if (c + 1 >= n_chunks) break;
+            CSD_WS_MMA(wb, 1, ks0 + (c + 3) * U)
+            lds_sync();
+        }
+#undef CSD_WS_LOAD_W
+#undef CSD_WS_MMA
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            const int row = mt * 16 + t;
+            if (row < M) {
+#pragma unroll
+                for (int j = 0; j < NT; j++)
+                    if (tv[j]) {
+                        float *o = part + ((size_t)s * M + row) * N + (size_t)(tile0 + j) * 16 + 4 * g;
+                        *reinterpret_cast<f32x4 *>(o) = acc[mt][j];
+                    }
+            }
+        }
+    } else {
+        // ------------------------------------------------------------ activation staging
+        // fragment i * 256 + (tid - 256) of a chunk = (u, row tile, plane, lane) in that order: u, row tile
+        // and plane are the same for a whole wave, so they go into the scalar offset of a buffer load and
+        // the per-lane part (row within the tile, 8 k-values) is one register for all fragments.  Lanes of
+        // rows past M get an offset beyond the buffer: such loads touch no memory and return zeros.
+        const int sw = w - 4, stid = tid - 256;
+        const __amdgpu_buffer_rsrc_t ra =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(act), 0, (int)(2 * plane * sizeof(bf16_t)), 0x00020000);
+        const int voff_in = (t * K + 8 * g) * 2;
+        const int voff_last = ((MT - 1) * 16 + t < M) ? voff_in : (int)0x80000000;   // the last row tile may be ragged
+        const int plane_off = (sw & 1) * (int)(plane * sizeof(bf16_t));
+        u32x4 sa[ST], sb[ST];
+#define CSD_WS_LOAD_ACT(SF, KS_AT)                                                                \
+    _Pragma("unroll") for (int i = 0; i < ST; i++) {                                              \
+        const int r2_ = i * 2 + (sw >> 1), mt_ = r2_ % MT, ksu_ = (KS_AT) + r2_ / MT;             \
+        const int soff_ = plane_off + (mt_ * 16 * K + ksu_ * 32) * 2;                             \
+        SF[i] = zero;                                                                             \
+        if (ksu_ < ks1) /* uniform */                                                             \
+            SF[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(              \
+                ra, mt_ == MT - 1 ? voff_last : voff_in, soff_, 0));                              \
+    }
+#define CSD_WS_PUT_ACT(SF, BUF)                                                                   \
+    _Pragma("unroll") for (int i = 0; i < ST; i++) lbuf[(BUF) * CH + i * 256 + stid] = SF[i];
+
+        CSD_WS_LOAD_ACT(sa, ks0)
+        CSD_WS_LOAD_ACT(sb, ks0 + U)
+        CSD_WS_PUT_ACT(sa, 0)
+        lds_sync();
+        for (int c = 0; c < n_chunks; c += 2) {
+            CSD_WS_LOAD_ACT(sa, ks0 + (c + 2) * U)
+            CSD_WS_PUT_ACT(sb, 1)                            // chunk c + 1, fetched one round ago
+            lds_sync();
+            if (c + 1 >= n_chunks) break;
+            CSD_WS_LOAD_ACT(sb, ks0 + (c + 3) * U)
+            CSD_WS_PUT_ACT(sa, 0)
+            lds_sync();
+        }
+#undef CSD_WS_LOAD_ACT
+#undef CSD_WS_PUT_ACT
+    }
+}
+
 // Generic GEMM (fp32 models and the debugging path): one thread per output column, fp32
 // activations [M][K], row-major weights [K][N]; writes partial plane 0.
 template <typename TW>
@@ -613,6 +759,39 @@ static int32_t launch_gemm_wg_nt(const GemmW &w, const bf16_t *act, size_t plane
     }
 }
 
+template <int MT>
+static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
+                                 hipStream_t st) {
+    static bool attr_set = false;
+    const size_t lds = (size_t)2 * WG_U_MAX * MT * 2 * 64 * 16;
+    if (!attr_set) {
+        CSD_HIP(hipFuncSetAttribute((const void *)k_gemm_ws<2, MT, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_gemm_ws<2, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
+                       act, plane, part, M, w.K, w.N, S);
+    return CSD_OK;
+}
+
+// The variant with separate staging waves: 128 columns per workgroup (wider tiles do not fit the registers
+// next to the staging sets), K split as below.
+static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int *S_used, hipStream_t st) {
+    const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 7) / 8;
+    int S = 1;
+    while (groups * S < 256 && S * 2 <= w.S && KS / (S * 2) >= 2 * WG_U_MAX) S *= 2;
+    *S_used = S;
+    switch ((M + 15) / 16) {
+    case 2: return launch_gemm_ws_mt<2>(w, act, plane, part, M, S, groups, st);
+    case 3: return launch_gemm_ws_mt<3>(w, act, plane, part, M, S, groups, st);
+    case 4: return launch_gemm_ws_mt<4>(w, act, plane, part, M, S, groups, st);
+    case 5: return launch_gemm_ws_mt<5>(w, act, plane, part, M, S, groups, st);
+    case 6: return launch_gemm_ws_mt<6>(w, act, plane, part, M, S, groups, st);
+    case 7: return launch_gemm_ws_mt<7>(w, act, plane, part, M, S, groups, st);
+    case 8: return launch_gemm_ws_mt<8>(w, act, plane, part, M, S, groups, st);
+    default: return CSD_ESHAPE;       // 9 row tiles do not fit the registers here: the caller takes the other form
+    }
+}
+
 // Tile width and K splits of the workgroup-tiled GEMM: 256 columns per workgroup when that still gives
 // every compute unit a workgroup, else 128; K is split (never finer than the partial-sum buffer was
 // sized for, nor below two chunks per slice) until there is about one workgroup per compute unit.
@@ -636,7 +815,9 @@ static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, 
     *S_used = w.S;
     if (mod->mfma) {
         if (M > 16 && M <= 144 && mod->gemm_wg) {
-            const int32_t rc = launch_gemm_wg(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st);
+            const int32_t rc = (M >= mod->gemm_ws_min_rows && M <= 128)
+                                   ? launch_gemm_ws(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st)
+                                   : launch_gemm_wg(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st);
             if (rc != CSD_OK) return rc;
         } else if (w.nt == 2)
             launch_gemm_mfma_nt<2, 4>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);

@@ -158,6 +158,7 @@ struct csd_model {
     bool mfma = false;        // bf16 tiles + MFMA GEMMs; otherwise generic kernels on row-major weights
     bool mfma_attn = false;
     bool gemm_wg = true;      // blocks of more than 16 rows: workgroup-tiled GEMM with activations shared through LDS
+    int gemm_ws_min_rows = 17;   // ... from this many rows on, its variant with separate staging waves
     bool kperm = false;       // q / K rows kept in rotary pair order (see KvGeom)
     int hd = 0;               // n_heads * head_dim
     int seq_pad = 0;          // cache rows per sequence, padded to 64
