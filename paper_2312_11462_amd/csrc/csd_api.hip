@@ -28,7 +28,10 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->mfma = c.dtype == CSD_DTYPE_BF16 && tiles_ok && !env_is("CSD_GEMM", "generic");
     mod->kperm = mod->mfma && c.arch == 0;     // rotary pair order only where there is a rotary embedding
     mod->gemm_wg = !env_is("CSD_GEMM_WG", "0");
-    if (const char *e = getenv("CSD_GEMM_WS_MIN_ROWS")) mod->gemm_ws_min_rows = atoi(e);
+    if (const char *e = getenv("CSD_GEMM_RS_MIN_ROWS")) {
+        mod->gemm_rs_min_rows = atoi(e);
+        if (mod->gemm_rs_min_rows > 129) mod->gemm_rs_min_rows = 129;    // the other form holds at most 8 row tiles
+    }
     mod->mfma_attn = mod->mfma && (c.head_dim == 64 || c.head_dim == 128) && !env_is("CSD_ATTN", "generic");
     const int keys_pad = mod->seq_pad > mod->enc_pad ? mod->seq_pad : mod->enc_pad;
     if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + keys_pad) > 64 * 1024) return CSD_ESHAPE;
@@ -59,6 +62,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->s_max * mod->m_max * nmax));
     mod->allocs.push_back(p);
     mod->part = (float *)p;
+    mod->part_floats = (size_t)mod->s_max * mod->m_max * nmax;
     CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->m_max * V));
     mod->allocs.push_back(p);
     mod->probs = (float *)p;

@@ -134,132 +134,13 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp,
     }
 }
 
-// The same contraction for blocks of more than 16 rows (several sequences times several drafts).
-// There the per-wave form above re-reads the activations once per wave; here the 4 waves of a
-// workgroup cover 4 * NT adjacent output tiles of one K slice and share the activation fragments
-// through LDS: per chunk of U k-steps every thread fetches its share of the chunk after next into
-// registers while the matrix cores work on the current one, and LDS holds two chunks
-// ([chunk][u][row tile][hi|lo plane][lane] in MFMA operand order, so a fragment is one conflict-free
-// 16-byte LDS read).  Weights stream from HBM through a two-chunk register ring as above.
-template <int NT, int MT, int U>
-__global__ __launch_bounds__(256) void k_gemm_wg(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
-                                                 float *__restrict__ part, int M, int K, int N, int S) {
-    extern __shared__ __align__(16) char wg_smem[];
-    constexpr int CH = U * MT * 2 * 64;                      // 16-byte fragments per chunk
-    static_assert(CH % 256 == 0, "chunk must divide over the workgroup");
-    constexpr int ST = CH / 256;                             // staging loads per thread and chunk
-    u32x4 *lbuf = reinterpret_cast<u32x4 *>(wg_smem);        // [2][CH]
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int s = blockIdx.x % S, grp = blockIdx.x / S;
-    const int KS = K / 32, n_tiles = N / 16;
-    const int ks0 = (int)((long long)KS * s / S), ks1 = (int)((long long)KS * (s + 1) / S);
-    const int t = lane & 15, g = lane >> 4;
-    const int tile0 = (grp * 4 + w) * NT;
-
-    const u32x4 *wp[NT];
-    bool tv[NT];
-#pragma unroll
-    for (int j = 0; j < NT; j++) {
-        tv[j] = tile0 + j < n_tiles;
-        wp[j] = Wp + ((size_t)(tv[j] ? tile0 + j : 0) * KS) * 64 + lane;
-    }
-    // staging: fragment i * 256 + tid of a chunk = (u, row tile, plane, lane) in that order
-    const bf16_t *abase = act + (size_t)(w & 1) * plane + 8 * g;
-    int soff[ST], su[ST];
-#pragma unroll
-    for (int i = 0; i < ST; i++) {
-        const int r2 = i * 2 + (w >> 1), mt = r2 % MT, u = r2 / MT, row = mt * 16 + t;
-        su[i] = row < M ? u : (1 << 28);                     // rows past M never pass the k-step test below
-        soff[i] = (row < M ? row : 0) * K + u * 32;
-    }
-
-    f32x4 acc[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    u32x4 wa[U][NT], wb[U][NT], st[ST];
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-
-#define CSD_WG_LOAD_W(WF, KS_AT)                                                                  \
-    _Pragma("unroll") for (int u = 0; u < U; u++) {                                               \
-        const int ksu_ = (KS_AT) + u;                                                             \
-        _Pragma("unroll") for (int j = 0; j < NT; j++)                                            \
-            WF[u][j] = (ksu_ < ks1 && tv[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero; \
-    }
-#define CSD_WG_LOAD_ACT(KS_AT)                                                                    \
-    _Pragma("unroll") for (int i = 0; i < ST; i++)                                                \
-        st[i] = ((KS_AT) + su[i] < ks1)                                                           \
-                    ? *reinterpret_cast<const u32x4 *>(abase + (size_t)soff[i] + (size_t)(KS_AT) * 32) : zero;
-#define CSD_WG_PUT_ACT(BUF)                                                                       \
-    _Pragma("unroll") for (int i = 0; i < ST; i++) lbuf[(BUF) * CH + i * 256 + tid] = st[i];
-// fragment idx = u * MT + row tile; its two planes are read two fragments ahead of their use, and the
-// scheduling fences keep the compiler from hoisting every LDS read of the chunk to the top (which would
-// not fit the register file for tall blocks)
-#define CSD_WG_MMA(WF, BUF)                                                                       \
-    {                                                                                             \
-        const u32x4 *lb_ = lbuf + (BUF) * CH + lane;                                              \
-        u32x4 b_[3][2];                                                                           \
-        b_[0][0] = lb_[0];                                                                        \
-        b_[0][1] = lb_[64];                                                                       \
-        b_[1][0] = lb_[128];                                                                      \
-        b_[1][1] = lb_[192];                                                                      \
-        _Pragma("unroll") for (int idx = 0; idx < U * MT; idx++) {                                \
-            if (idx + 2 < U * MT) {                                                               \
-                b_[(idx + 2) % 3][0] = lb_[(idx + 2) * 128];                                      \
-                b_[(idx + 2) % 3][1] = lb_[(idx + 2) * 128 + 64];                                 \
-            }                                                                                     \
-            const int u = idx / MT, mt = idx % MT;                                                \
-            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
-                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
-                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, b_[idx % 3][0]), acc[mt][j], 0, 0, 0); \
-            _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
-                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
-                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, b_[idx % 3][1]), acc[mt][j], 0, 0, 0); \
-            __builtin_amdgcn_sched_barrier(0);                                                    \
-        }                                                                                         \
-    }
-
-    CSD_WG_LOAD_ACT(ks0)
-    CSD_WG_LOAD_W(wa, ks0)
-    CSD_WG_PUT_ACT(0)
-    lds_sync();
-    for (int ks = ks0; ks < ks1; ks += 2 * U) {
-        CSD_WG_LOAD_W(wb, ks + U)
-        CSD_WG_LOAD_ACT(ks + U)
-        CSD_WG_MMA(wa, 0)
-        if (ks + U >= ks1) break;                            // uniform
-        CSD_WG_PUT_ACT(1)
-        lds_sync();
-        CSD_WG_LOAD_W(wa, ks + 2 * U)
-        CSD_WG_LOAD_ACT(ks + 2 * U)
-        CSD_WG_MMA(wb, 1)
-        CSD_WG_PUT_ACT(0)
-        lds_sync();
-    }
-#undef CSD_WG_LOAD_W
-#undef CSD_WG_LOAD_ACT
-#undef CSD_WG_PUT_ACT
-#undef CSD_WG_MMA
-
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int row = mt * 16 + t;
-        if (row < M) {
-#pragma unroll
-            for (int j = 0; j < NT; j++)
-                if (tv[j]) {
-                    float *o = part + ((size_t)s * M + row) * N + (size_t)(tile0 + j) * 16 + 4 * g;
-                    *reinterpret_cast<f32x4 *>(o) = acc[mt][j];
-                }
-        }
-    }
-}
-
-// The workgroup-tiled GEMM with the two jobs given to different waves: waves 0-3 only stream weights and
-// feed the matrix cores (4 * NT column tiles, all row tiles), waves 4-7 only move activation fragments from
-// L2 to LDS, two chunks ahead in registers and one chunk ahead in LDS.  A wave that waits for its oldest
+// The same contraction for blocks of 17 to 64 rows (several sequences times several drafts).  There the
+// per-wave form above re-reads the activations once per wave; here a workgroup covers 4 * NT adjacent
+// output tiles of one K slice and shares the activation fragments through LDS (two chunks of U k-steps,
+// [chunk][u][row tile][hi|lo plane][lane] in MFMA operand order, so a fragment is one conflict-free 16-byte
+// LDS read).  The two jobs are given to different waves: waves 0-3 only stream weights and feed the matrix
+// cores (all row tiles), waves 4-7 only move activation fragments from L2 to LDS, two chunks ahead in
+// registers and one chunk ahead in LDS.  A wave that waits for its oldest
 // load also waits for nothing younger, so with the jobs apart the weight ring and the activation staging
 // each keep their own depth; one workgroup barrier per chunk hands a staged chunk over and frees the other
 // buffer.  Both kinds of waves pass exactly 1 + (number of chunks) barriers.
@@ -400,6 +281,145 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
         }
 #undef CSD_WS_LOAD_ACT
 #undef CSD_WS_PUT_ACT
+    }
+}
+
+// Tall blocks (5 to 9 row tiles), where the matrix cores and LDS bandwidth matter as much as HBM: the
+// rows are split over the 4 compute waves (RW row tiles each) and the weights are what is shared.  Waves
+// 4-7 stream the weight fragments of CT column tiles from HBM into LDS (two chunks ahead in registers, one
+// in LDS); a compute wave keeps its own rows' activation fragments in registers (fetched from L2 one chunk
+// of k-steps ahead, slot by slot as they are used up) and reads every weight fragment once from LDS for
+// 2 * RW matrix instructions: with two row tiles per wave the matrix cores get four instructions per
+// 16-byte LDS read, where the activation-sharing forms above get two (their LDS reads then take as long as
+// their matrix instructions), and nothing goes through LDS that only one wave needs.
+template <int CT, int RW, int U>
+__global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
+                                                 float *__restrict__ part, int M, int K, int N, int S) {
+    extern __shared__ __align__(16) char wg_smem[];
+    constexpr int CH = U * CT * 64;                          // 16-byte weight fragments (per lane) of a chunk
+    constexpr int ST = CH / 256;                             // staging loads per staging thread and chunk
+    constexpr int PD = 3;                                    // LDS reads run this many column tiles ahead
+    static_assert(CH % 256 == 0 && U * CT > PD, "chunk shape");
+    u32x4 *lbuf = reinterpret_cast<u32x4 *>(wg_smem);        // [2][CH]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s = blockIdx.x % S, grp = blockIdx.x / S;
+    const int KS = K / 32, n_tiles = N / 16;
+    const int ks0 = (int)((long long)KS * s / S), ks1 = (int)((long long)KS * (s + 1) / S);
+    const int n_chunks = (ks1 - ks0 + U - 1) / U;
+    const int t = lane & 15, g = lane >> 4;
+    const int tile0 = grp * CT;
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+
+    if (w < 4) {
+        // ------------------------------------------------------------ own rows x all column tiles
+        const __amdgpu_buffer_rsrc_t ra =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(act), 0, (int)(2 * plane * sizeof(bf16_t)), 0x00020000);
+        const int lo_off = (int)(plane * sizeof(bf16_t));
+        int voff[RW];                                        // rows past M: an offset beyond the buffer (loads give 0)
+#pragma unroll
+        for (int r = 0; r < RW; r++) {
+            const int row = (w * RW + r) * 16 + t;
+            voff[r] = row < M ? (row * K + 8 * g) * 2 : (int)0x80000000;
+        }
+        const bool has_rows = w * RW * 16 < M;               // uniform
+        f32x4 acc[RW][CT];
+#pragma unroll
+        for (int r = 0; r < RW; r++)
+#pragma unroll
+            for (int ct = 0; ct < CT; ct++) acc[r][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+        u32x4 a[U][RW][2];
+
+#define CSD_RS_LOAD_A(UU, KS_AT)                                                                  \
+    {                                                                                             \
+        const int ksa_ = (KS_AT);                                                                 \
+        _Pragma("unroll") for (int r = 0; r < RW; r++) {                                          \
+            a[UU][r][0] = a[UU][r][1] = zero;                                                     \
+            if (ksa_ < ks1) { /* uniform */                                                       \
+                a[UU][r][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, voff[r], ksa_ * 64, 0)); \
+                a[UU][r][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, voff[r], ksa_ * 64 + lo_off, 0)); \
+            }                                                                                     \
+        }                                                                                         \
+    }
+#define CSD_RS_MMA(BUF, KS_NEXT)                                                                  \
+    if (has_rows) {                                                                               \
+        const u32x4 *lb_ = lbuf + (BUF) * CH + lane;                                              \
+        u32x4 wf_[PD + 1];                                                                        \
+        _Pragma("unroll") for (int p = 0; p < PD; p++) wf_[p] = lb_[p * 64];                      \
+        _Pragma("unroll") for (int idx = 0; idx < U * CT; idx++) {                                \
+            if (idx + PD < U * CT) wf_[(idx + PD) % (PD + 1)] = lb_[(idx + PD) * 64];             \
+            const int u = idx / CT, ct = idx % CT;                                                \
+            _Pragma("unroll") for (int r = 0; r < RW; r++)                                        \
+                acc[r][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, wf_[idx % (PD + 1)]), __builtin_bit_cast(bf16x8, a[u][r][0]), acc[r][ct], 0, 0, 0); \
+            _Pragma("unroll") for (int r = 0; r < RW; r++)                                        \
+                acc[r][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+                    __builtin_bit_cast(bf16x8, wf_[idx % (PD + 1)]), __builtin_bit_cast(bf16x8, a[u][r][1]), acc[r][ct], 0, 0, 0); \
+            if (ct == CT - 1) CSD_RS_LOAD_A(u, (KS_NEXT) + u) /* slot u is free: k-step U ahead */  \
+            __builtin_amdgcn_sched_barrier(0);                                                    \
+        }                                                                                         \
+    }
+
+        if (has_rows) {
+#pragma unroll
+            for (int u = 0; u < U; u++) CSD_RS_LOAD_A(u, ks0 + u)
+        }
+        lds_sync();                                          // weight chunk 0 is in LDS
+        for (int c = 0; c < n_chunks; c += 2) {
+            CSD_RS_MMA(0, ks0 + (c + 1) * U)
+            lds_sync();                                      // chunk c consumed, chunk c + 1 staged
+            if (c + 1 >= n_chunks) break;
+            CSD_RS_MMA(1, ks0 + (c + 2) * U)
+            lds_sync();
+        }
+#undef CSD_RS_LOAD_A
+#undef CSD_RS_MMA
+#pragma unroll
+        for (int r = 0; r < RW; r++) {
+            const int row = (w * RW + r) * 16 + t;
+            if (row < M) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ct++)
+                    if (tile0 + ct < n_tiles) {
+                        float *o = part + ((size_t)s * M + row) * N + (size_t)(tile0 + ct) * 16 + 4 * g;
+                        *reinterpret_cast<f32x4 *>(o) = acc[r][ct];
+                    }
+            }
+        }
+    } else {
+        // ------------------------------------------------------------ weight staging
+        // fragment i * 256 + (tid - 256) of a chunk = (u, column tile, lane): u and the tile are the same
+        // for a whole wave and go into the scalar offset
+        const int sw = w - 4, stid = tid - 256;
+        const __amdgpu_buffer_rsrc_t rw =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4 *>(Wp), 0, (int)((size_t)K * N * sizeof(bf16_t)), 0x00020000);
+        const int voff = lane * 16;
+        u32x4 sa[ST], sb[ST];
+#define CSD_RS_LOAD_W(SF, KS_AT)                                                                  \
+    _Pragma("unroll") for (int i = 0; i < ST; i++) {                                              \
+        const int rest_ = i * 4 + sw, tile_ = tile0 + rest_ % CT, ksu_ = (KS_AT) + rest_ / CT;    \
+        SF[i] = zero;                                                                             \
+        if (ksu_ < ks1 && tile_ < n_tiles) /* uniform */                                          \
+            SF[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, voff, (tile_ * KS + ksu_) * 1024, 2)); \
+    }
+#define CSD_RS_PUT_W(SF, BUF)                                                                     \
+    _Pragma("unroll") for (int i = 0; i < ST; i++) lbuf[(BUF) * CH + i * 256 + stid] = SF[i];
+
+        CSD_RS_LOAD_W(sa, ks0)
+        CSD_RS_LOAD_W(sb, ks0 + U)
+        CSD_RS_PUT_W(sa, 0)
+        lds_sync();
+        for (int c = 0; c < n_chunks; c += 2) {
+            CSD_RS_LOAD_W(sa, ks0 + (c + 2) * U)
+            CSD_RS_PUT_W(sb, 1)                              // chunk c + 1, fetched one round ago
+            lds_sync();
+            if (c + 1 >= n_chunks) break;
+            CSD_RS_LOAD_W(sb, ks0 + (c + 3) * U)
+            CSD_RS_PUT_W(sa, 0)
+            lds_sync();
+        }
+#undef CSD_RS_LOAD_W
+#undef CSD_RS_PUT_W
     }
 }
 
@@ -721,44 +741,7 @@ static void launch_gemm_mfma_nt(const GemmW &w, const bf16_t *act, size_t plane,
         hipLaunchKernelGGL((k_gemm_mfma<NT, 9, 1>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
 }
 
-// k-steps per chunk: 4 while the accumulators (16 * MT * NT registers) leave room for a weight ring that
-// deep, 2 for the tallest blocks (which are bound by the matrix cores, not by prefetch depth)
-#define WG_U_MAX 4
-template <int NT, int MT>
-static int32_t launch_gemm_wg_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
-                                 hipStream_t st) {
-    constexpr int WG_U = MT <= 5 ? WG_U_MAX : 2;
-    static bool attr_set = false;                            // per instantiation; the attribute is idempotent
-    const size_t lds = (size_t)2 * WG_U * MT * 2 * 64 * 16;
-    if (!attr_set) {
-        CSD_HIP(hipFuncSetAttribute((const void *)k_gemm_wg<NT, MT, WG_U>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((k_gemm_wg<NT, MT, WG_U>), dim3(groups * S), dim3(256), lds, st, reinterpret_cast<const u32x4 *>(w.data),
-                       act, plane, part, M, w.K, w.N, S);
-    return CSD_OK;
-}
-
-template <int NT>
-static int32_t launch_gemm_wg_nt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
-                                 hipStream_t st) {
-    switch ((M + 15) / 16) {
-    case 2: return launch_gemm_wg_mt<NT, 2>(w, act, plane, part, M, S, groups, st);
-    case 3: return launch_gemm_wg_mt<NT, 3>(w, act, plane, part, M, S, groups, st);
-    case 4: return launch_gemm_wg_mt<NT, 4>(w, act, plane, part, M, S, groups, st);
-    case 5: return launch_gemm_wg_mt<NT, 5>(w, act, plane, part, M, S, groups, st);
-    case 6: return launch_gemm_wg_mt<NT, 6>(w, act, plane, part, M, S, groups, st);
-    case 7: return launch_gemm_wg_mt<NT, 7>(w, act, plane, part, M, S, groups, st);
-    case 8:
-        if constexpr (NT <= 2) return launch_gemm_wg_mt<NT, 8>(w, act, plane, part, M, S, groups, st);
-        return CSD_ESHAPE;
-    case 9:
-        if constexpr (NT <= 2) return launch_gemm_wg_mt<NT, 9>(w, act, plane, part, M, S, groups, st);
-        return CSD_ESHAPE;
-    default: return CSD_ESHAPE;
-    }
-}
-
+#define WG_U_MAX 4      /* k-steps per chunk of the workgroup-tiled GEMMs */
 template <int MT>
 static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
                                  hipStream_t st) {
@@ -788,25 +771,41 @@ static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, f
     case 6: return launch_gemm_ws_mt<6>(w, act, plane, part, M, S, groups, st);
     case 7: return launch_gemm_ws_mt<7>(w, act, plane, part, M, S, groups, st);
     case 8: return launch_gemm_ws_mt<8>(w, act, plane, part, M, S, groups, st);
-    default: return CSD_ESHAPE;       // 9 row tiles do not fit the registers here: the caller takes the other form
+    default: return CSD_ESHAPE;       // 9 row tiles do not fit the registers here: such blocks take the row-split form
     }
 }
 
-// Tile width and K splits of the workgroup-tiled GEMM: 256 columns per workgroup when that still gives
-// every compute unit a workgroup, else 128; K is split (never finer than the partial-sum buffer was
-// sized for, nor below two chunks per slice) until there is about one workgroup per compute unit.
-static int32_t launch_gemm_wg(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int *S_used, hipStream_t st) {
-    const int n_tiles = w.N / 16, KS = w.K / 32;
-    int nt = 4, groups = (n_tiles + 15) / 16;
-    if (groups * w.S < 256 || M > 112) {                     // 8 or 9 row tiles x 4 column tiles do not fit the registers
-        nt = 2;
-        groups = (n_tiles + 7) / 8;
+template <int CT, int RW>
+static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
+                                hipStream_t st) {
+    static bool attr_set = false;
+    const size_t lds = (size_t)2 * WG_U_MAX * CT * 64 * 16;
+    if (!attr_set) {
+        CSD_HIP(hipFuncSetAttribute((const void *)k_gemm_rs<CT, RW, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
     }
+    hipLaunchKernelGGL((k_gemm_rs<CT, RW, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
+                       act, plane, part, M, w.K, w.N, S);
+    return CSD_OK;
+}
+
+// The row-split form: 256 columns per workgroup (128 when every compute wave holds three row tiles).  Its
+// staging waves keep two chunks of weights in flight per workgroup, so half the compute units already
+// saturate HBM: K is split only until there are 128 workgroups, which keeps the partial-sum traffic low.
+static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t *act, size_t plane, float *part, int M,
+                              int *S_used, hipStream_t st) {
+    const int n_tiles = w.N / 16, KS = w.K / 32, MT = (M + 15) / 16;
+    const int rw = (MT + 3) / 4, ct = rw == 3 ? 8 : 16;
+    const int groups = (n_tiles + ct - 1) / ct;
     int S = 1;
-    while (groups * S < 256 && S * 2 <= w.S && KS / (S * 2) >= 2 * WG_U_MAX) S *= 2;
+    while (groups * S < 128 && S < 16 && KS / (S + 1) >= 2 * WG_U_MAX &&
+           (size_t)(S + 1) * M * w.N <= mod->part_floats)
+        S++;
     *S_used = S;
-    return nt == 4 ? launch_gemm_wg_nt<4>(w, act, plane, part, M, S, groups, st)
-                   : launch_gemm_wg_nt<2>(w, act, plane, part, M, S, groups, st);
+    if (rw == 1) return launch_gemm_rs_t<16, 1>(w, act, plane, part, M, S, groups, st);
+    if (rw == 2) return launch_gemm_rs_t<16, 2>(w, act, plane, part, M, S, groups, st);
+    if (rw == 3) return launch_gemm_rs_t<8, 3>(w, act, plane, part, M, S, groups, st);
+    return CSD_ESHAPE;
 }
 
 // act: [M][w.K] in the path's activation type; part: [S][M][w.N] with S (<= w.S) returned in *S_used
@@ -815,9 +814,9 @@ static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, 
     *S_used = w.S;
     if (mod->mfma) {
         if (M > 16 && M <= 144 && mod->gemm_wg) {
-            const int32_t rc = (M >= mod->gemm_ws_min_rows && M <= 128)
-                                   ? launch_gemm_ws(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st)
-                                   : launch_gemm_wg(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st);
+            const int32_t rc = M >= mod->gemm_rs_min_rows
+                                   ? launch_gemm_rs(mod, w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st)
+                                   : launch_gemm_ws(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st);
             if (rc != CSD_OK) return rc;
         } else if (w.nt == 2)
             launch_gemm_mfma_nt<2, 4>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);

@@ -157,8 +157,8 @@ struct csd_model {
     csd_model_cfg cfg;
     bool mfma = false;        // bf16 tiles + MFMA GEMMs; otherwise generic kernels on row-major weights
     bool mfma_attn = false;
-    bool gemm_wg = true;      // blocks of more than 16 rows: workgroup-tiled GEMM with activations shared through LDS
-    int gemm_ws_min_rows = 17;   // ... from this many rows on, its variant with separate staging waves
+    bool gemm_wg = true;      // blocks of more than 16 rows: workgroup-tiled GEMMs (activations shared through LDS)
+    int gemm_rs_min_rows = 65;   // ... from this many rows on (at most 128 otherwise), the form that splits the rows over the waves
     bool kperm = false;       // q / K rows kept in rotary pair order (see KvGeom)
     int hd = 0;               // n_heads * head_dim
     int seq_pad = 0;          // cache rows per sequence, padded to 64
@@ -175,6 +175,7 @@ struct csd_model {
     size_t act_plane = 0;        // elements between the hi and lo planes of act
     size_t q_plane = 0;          // ... and of qbuf
     float *part = nullptr;       // split-K partial sums [s_max][m_max][n_max]
+    size_t part_floats = 0;      // its capacity
     float *attn_part = nullptr;  // attention partials (MFMA attention)
     float *probs = nullptr;      // [m_max][V] when the caller does not want them
     int attn_chunks_max = 0;
