@@ -27,7 +27,6 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     const bool tiles_ok = d % 32 == 0 && hd % 32 == 0 && F % 32 == 0 && V % 16 == 0 && c.head_dim % 16 == 0;
     mod->mfma = c.dtype == CSD_DTYPE_BF16 && tiles_ok && !env_is("CSD_GEMM", "generic");
     mod->kperm = mod->mfma && c.arch == 0;     // rotary pair order only where there is a rotary embedding
-    mod->gemm_wg = !env_is("CSD_GEMM_WG", "0");
     if (const char *e = getenv("CSD_GEMM_RS_MIN_ROWS")) {
         mod->gemm_rs_min_rows = atoi(e);
         if (mod->gemm_rs_min_rows > 129) mod->gemm_rs_min_rows = 129;    // the other form holds at most 8 row tiles

@@ -1,6 +1,6 @@
 // Causal block attention of the drafted block over the cached prefix, on the matrix cores.
 //
-// One wave per (sequence, head, 128-key chunk, 16-row tile of the block).  Both contractions
+// One wave per (sequence, head, chunk of 128 or more keys, 16-row tile of the block).  Both contractions
 // are written transposed so that no operand ever needs a shuffle through LDS:
 //   S^T = K * q^T   A = K rows (16 keys x 32 of dh), B = q (32 of dh x 16 block rows)
 //   O^T = V^T * P^T A = V^T (16 of dh x 32 keys),     B = P^T (32 keys x 16 block rows)
@@ -8,16 +8,19 @@
 // group) becomes the B operand of the second directly, because the keys are assigned to A-rows
 // so that every lane ends up holding 8 consecutive keys; V is cached transposed so that the
 // matching A operand is one 16-byte load.  Chunks keep an online-softmax state (max, sum,
-// un-normalised output) that a small merge kernel combines.
+// un-normalised output) that a small merge kernel combines.  The host doubles the keys per wave
+// (chunk_keys) while there are more waves than the chip holds at once, which shrinks the partial
+// states the merge kernel has to read.  (A form that loads each key tile once for two row tiles of
+// the block was slower: its register need halves the waves in flight.)
 #include "csd_internal.h"
 
-#define ATT_CHUNK 128
+#define ATT_CHUNK 128      /* keys per wave at least (the partial buffer is sized for this) */
 
 template <int DH>
 __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, size_t qplane, int m, int row_tiles,
                                                   const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
                                                   const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
-                                                  int chunks_max, AttnMode mode) {
+                                                  int chunks_max, int chunk_keys, AttnMode mode) {
     constexpr int PS = DH + 4;   // floats per partial row: DH outputs, running max, running sum, pad
     const int c = blockIdx.x, hh = blockIdx.y, b = blockIdx.z / row_tiles, rt = blockIdx.z % row_tiles;
     const int lane = threadIdx.x, col = lane & 15, g = lane >> 4;
@@ -27,7 +30,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
     const int nk = max(0, min(causal ? t + m : mode.fixed_nk, geo.seq_pad));   // cache rows in play for this block
     float *po = part + ((((size_t)b * geo.H + hh) * chunks_max + c) * row_tiles + rt) * 16 * PS;
     float *pr = po + (size_t)col * PS;
-    const int key0 = c * ATT_CHUNK;
+    const int key0 = c * chunk_keys;
     if (key0 >= nk) {                                        // chunk past the end: neutral element
         if (g == 0) {
             pr[DH] = -INFINITY;
@@ -55,7 +58,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
     for (int dt = 0; dt < DH / 16; dt++) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float mrun = -INFINITY, lrun = 0.f;
 
-    for (int sub = 0; sub < ATT_CHUNK / 32; sub++) {
+    for (int sub = 0; sub < chunk_keys / 32; sub++) {
         const int kb = key0 + sub * 32;
         if (kb >= nk) break;
         // scores: A-row r of tile T is key kb + 8*(r/4) + 4*T + r%4, so lane group g ends up with keys kb+8g..kb+8g+7
@@ -139,13 +142,13 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
 template <int DH>
 __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ part, int m, int row_tiles,
                                                    const int32_t *__restrict__ cache_len, int H, int seq_pad,
-                                                   int chunks_max, bf16_t *__restrict__ out, int ldo, size_t plane,
-                                                   int fixed_nk) {
+                                                   int chunks_max, int chunk_keys, bf16_t *__restrict__ out, int ldo,
+                                                   size_t plane, int fixed_nk) {
     constexpr int PS = DH + 4;
     const int r = blockIdx.x, hh = blockIdx.y, x = threadIdx.x;
     const int b = r / m, i = r % m, rt = i / 16, ri = i % 16;
     const int nk = max(1, min(fixed_nk > 0 ? fixed_nk : cache_len[b] + m, seq_pad));
-    const int nch = (nk + ATT_CHUNK - 1) / ATT_CHUNK;
+    const int nch = (nk + chunk_keys - 1) / chunk_keys;
     const float *base = part + (((size_t)b * H + hh) * chunks_max * row_tiles + rt) * 16 * PS + (size_t)ri * PS;
     const size_t cstride = (size_t)row_tiles * 16 * PS;
     float mstar = -INFINITY;
@@ -161,28 +164,33 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
     store_act<bf16_t>(out, plane, (size_t)r * ldo + hh * DH + x, den > 0.f ? num / den : 0.f);
 }
 
+template <int DH>
+static void attn_launch(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m, int layer,
+                        float scale, const AttnMode &mode, hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    const int row_tiles = (m + 15) / 16;
+    // keys per wave: doubled while there are more waves than the chip holds at once (about 16 per compute unit)
+    const int keys = mode.fixed_nk > 0 ? mode.fixed_nk : geo.seq_pad;
+    int chunk_keys = ATT_CHUNK;
+    while (chunk_keys < 1024 && (long long)((keys + chunk_keys - 1) / chunk_keys) * c.n_heads * B * row_tiles > 4096) chunk_keys *= 2;
+    int chunks = (keys + chunk_keys - 1) / chunk_keys;
+    if (chunks > mod->attn_chunks_max) chunks = mod->attn_chunks_max;
+    hipLaunchKernelGGL((k_attn_mfma<DH>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st, (const bf16_t *)mod->qbuf,
+                       mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale, mod->attn_part,
+                       mod->attn_chunks_max, chunk_keys, mode);
+    hipLaunchKernelGGL((k_attn_merge<DH>), dim3(B * m, c.n_heads), dim3(DH), 0, st, mod->attn_part, m, row_tiles, cache_len,
+                       c.n_heads, geo.seq_pad, mod->attn_chunks_max, chunk_keys, (bf16_t *)mod->act, mod->hd, mod->act_plane,
+                       mode.fixed_nk);
+}
+
 // geo / kv: the cache being attended (the self-attention cache, or arch 1's cross-attention part of it)
 int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
                               int layer, float scale, const AttnMode &mode, hipStream_t st) {
-    const csd_model_cfg &c = mod->cfg;
-    const int row_tiles = (m + 15) / 16;
-    const int chunks = mod->attn_chunks_max;
-    const dim3 grid(chunks, c.n_heads, B * row_tiles);
-    const dim3 mgrid(B * m, c.n_heads);
     ProfScope ps(mod, st, CSD_PROF_ATTN);
-    if (c.head_dim == 128) {
-        hipLaunchKernelGGL((k_attn_mfma<128>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo,
-                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks, mode);
-        CSD_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_attn_merge<128>), mgrid, dim3(128), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
-                           geo.seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane, mode.fixed_nk);
-    } else {
-        hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(64), 0, st, (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo,
-                           layer, (const bf16_t *)kv, scale, mod->attn_part, chunks, mode);
-        CSD_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_attn_merge<64>), mgrid, dim3(64), 0, st, mod->attn_part, m, row_tiles, cache_len, c.n_heads,
-                           geo.seq_pad, chunks, (bf16_t *)mod->act, mod->hd, mod->act_plane, mode.fixed_nk);
-    }
+    if (mod->cfg.head_dim == 128)
+        attn_launch<128>(mod, geo, kv, cache_len, B, m, layer, scale, mode, st);
+    else
+        attn_launch<64>(mod, geo, kv, cache_len, B, m, layer, scale, mode, st);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }

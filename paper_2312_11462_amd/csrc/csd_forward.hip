@@ -49,94 +49,15 @@ __global__ void k_copy_cols(const T *__restrict__ src, int K, int N_src, T *__re
 
 // ------------------------------------------------------------------------------------ GEMMs
 
-// Skinny weight-streaming GEMM on the matrix cores.
+// Weight-streaming GEMMs on the matrix cores.
 //   A operand = weight fragment (16 output features x 32 k), B operand = activations
 //   (32 k x 16 block rows), D = 16 features x 16 rows: lane (row = lane%16, features 4g..4g+3).
-// A wave owns NT adjacent output tiles and one K slice; it double-buffers U k-steps of
-// fragments in registers so that 2*U*NT KB per wave are in flight.
-template <int NT, int MT, int U>
-__global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act,
-                                                   size_t plane, float *__restrict__ part, int M, int K, int N, int S) {
-    const int wave = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    const int lane = threadIdx.x & 63;
-    const int n_groups = N / (16 * NT);
-    if (wave >= n_groups * S) return;
-    const int s = wave % S, grp = wave / S;
-    const int KS = K / 32;
-    const int ks0 = (int)((long long)KS * s / S), ks1 = (int)((long long)KS * (s + 1) / S);
-    const int t = lane & 15, g = lane >> 4;
+// Every form writes fp32 partial sums per K split ([S][M][N]); the epilogue kernels reduce them in a
+// fixed order.
 
-    const u32x4 *wp[NT];
-#pragma unroll
-    for (int j = 0; j < NT; j++) wp[j] = Wp + ((size_t)(grp * NT + j) * KS) * 64 + lane;
-    const u32x4 *ap[MT];
-    bool valid[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int row = mt * 16 + t;
-        valid[mt] = row < M;
-        ap[mt] = reinterpret_cast<const u32x4 *>(act + (size_t)(valid[mt] ? row : 0) * K + 8 * g);
-    }
-
-    f32x4 acc[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    u32x4 wa[U][NT], wb[U][NT], ba[U][MT][2], bb[U][MT][2];   // [2]: hi and lo activation planes
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    const size_t plane16 = plane / 8;                         // plane stride in 16-byte units
-
-#define CSD_LOAD_BATCH(WF, BF, KS_AT)                                                             \
-    _Pragma("unroll") for (int u = 0; u < U; u++) {                                               \
-        const int ksu_ = (KS_AT) + u;                                                             \
-        const bool in_ = ksu_ < ks1;                                                              \
-        _Pragma("unroll") for (int j = 0; j < NT; j++)                                            \
-            WF[u][j] = in_ ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero;        \
-        _Pragma("unroll") for (int mt = 0; mt < MT; mt++) {                                       \
-            BF[u][mt][0] = (in_ && valid[mt]) ? ap[mt][(size_t)ksu_ * 4] : zero;                  \
-            BF[u][mt][1] = (in_ && valid[mt]) ? ap[mt][(size_t)ksu_ * 4 + plane16] : zero;        \
-        }                                                                                         \
-    }
-#define CSD_MMA_BATCH(WF, BF)                                                                     \
-    _Pragma("unroll") for (int u = 0; u < U; u++)                                                 \
-        _Pragma("unroll") for (int mt = 0; mt < MT; mt++)                                         \
-            _Pragma("unroll") for (int j = 0; j < NT; j++) {                                      \
-                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
-                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, BF[u][mt][0]), \
-                    acc[mt][j], 0, 0, 0);                                                         \
-                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
-                    __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, BF[u][mt][1]), \
-                    acc[mt][j], 0, 0, 0);                                                         \
-            }
-
-    CSD_LOAD_BATCH(wa, ba, ks0)
-    for (int ks = ks0; ks < ks1; ks += 2 * U) {
-        CSD_LOAD_BATCH(wb, bb, ks + U)
-        CSD_MMA_BATCH(wa, ba)
-        CSD_LOAD_BATCH(wa, ba, ks + 2 * U)
-        CSD_MMA_BATCH(wb, bb)
-    }
-#undef CSD_LOAD_BATCH
-#undef CSD_MMA_BATCH
-
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int row = mt * 16 + t;
-        if (row < M) {
-#pragma unroll
-            for (int j = 0; j < NT; j++) {
-                float *o = part + ((size_t)s * M + row) * N + (size_t)(grp * NT + j) * 16 + 4 * g;
-                *reinterpret_cast<f32x4 *>(o) = acc[mt][j];
-            }
-        }
-    }
-}
-
-// The same contraction for blocks of 17 to 64 rows (several sequences times several drafts).  There the
-// per-wave form above re-reads the activations once per wave; here a workgroup covers 4 * NT adjacent
-// output tiles of one K slice and shares the activation fragments through LDS (two chunks of U k-steps,
+// Blocks of up to 64 rows.  A workgroup covers 4 * NT adjacent output tiles of one K slice and shares the
+// activation fragments through LDS (a form with one independent wave per output tile re-read them from
+// L2 in every wave and was slower from 6 rows on) (two chunks of U k-steps,
 // [chunk][u][row tile][hi|lo plane][lane] in MFMA operand order, so a fragment is one conflict-free 16-byte
 // LDS read).  The two jobs are given to different waves: waves 0-3 only stream weights and feed the matrix
 // cores (all row tiles), waves 4-7 only move activation fragments from L2 to LDS, two chunks ahead in
@@ -146,7 +67,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const u32x4 *__restrict__ Wp,
 // buffer.  Both kinds of waves pass exactly 1 + (number of chunks) barriers.
 template <int NT, int MT, int U>
 __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
-                                                 float *__restrict__ part, int M, int K, int N, int S) {
+                                                 float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
     extern __shared__ __align__(16) char wg_smem[];
     constexpr int CH = U * MT * 2 * 64;                      // 16-byte fragments per chunk
     static_assert(CH % 256 == 0, "chunk must divide over the staging waves");
@@ -236,7 +157,7 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
 #pragma unroll
                 for (int j = 0; j < NT; j++)
                     if (tv[j]) {
-                        float *o = part + ((size_t)s * M + row) * N + (size_t)(tile0 + j) * 16 + 4 * g;
+                        float *o = part + ((size_t)s * Mtot + row) * N + (size_t)(tile0 + j) * 16 + 4 * g;
                         *reinterpret_cast<f32x4 *>(o) = acc[mt][j];
                     }
             }
@@ -294,7 +215,7 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
 // their matrix instructions), and nothing goes through LDS that only one wave needs.
 template <int CT, int RW, int U>
 __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
-                                                 float *__restrict__ part, int M, int K, int N, int S) {
+                                                 float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
     extern __shared__ __align__(16) char wg_smem[];
     constexpr int CH = U * CT * 64;                          // 16-byte weight fragments (per lane) of a chunk
     constexpr int ST = CH / 256;                             // staging loads per staging thread and chunk
@@ -381,7 +302,7 @@ __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, c
 #pragma unroll
                 for (int ct = 0; ct < CT; ct++)
                     if (tile0 + ct < n_tiles) {
-                        float *o = part + ((size_t)s * M + row) * N + (size_t)(tile0 + ct) * 16 + 4 * g;
+                        float *o = part + ((size_t)s * Mtot + row) * N + (size_t)(tile0 + ct) * 16 + 4 * g;
                         *reinterpret_cast<f32x4 *>(o) = acc[r][ct];
                     }
             }
@@ -724,27 +645,10 @@ ProfScope::~ProfScope() {
     m->ev_used += 2;
 }
 
-template <int NT, int U>
-static void launch_gemm_mfma_nt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, hipStream_t st) {
-    const int waves = w.N / (16 * NT) * w.S;
-    const int blocks = (waves + 3) / 4;
-    const int MT = (M + 15) / 16;
-    const u32x4 *Wp = reinterpret_cast<const u32x4 *>(w.data);
-    if (MT <= 1)
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 1, U>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
-    else if (MT <= 2)
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 2, U>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
-    else if (MT <= 4)
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 4, (U > 2 ? U / 2 : U)>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part,
-                           M, w.K, w.N, w.S);
-    else
-        hipLaunchKernelGGL((k_gemm_mfma<NT, 9, 1>), dim3(blocks), dim3(256), 0, st, Wp, act, plane, part, M, w.K, w.N, w.S);
-}
-
 #define WG_U_MAX 4      /* k-steps per chunk of the workgroup-tiled GEMMs */
 template <int MT>
-static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
-                                 hipStream_t st) {
+static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int S,
+                                 int groups, hipStream_t st) {
     static bool attr_set = false;
     const size_t lds = (size_t)2 * WG_U_MAX * MT * 2 * 64 * 16;
     if (!attr_set) {
@@ -752,32 +656,38 @@ static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane
         attr_set = true;
     }
     hipLaunchKernelGGL((k_gemm_ws<2, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
-                       act, plane, part, M, w.K, w.N, S);
+                       act, plane, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
 }
 
-// The variant with separate staging waves: 128 columns per workgroup (wider tiles do not fit the registers
-// next to the staging sets), K split as below.
-static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int *S_used, hipStream_t st) {
+// Blocks of up to 64 rows (of Mtot in the call): 128 columns per workgroup (wider tiles do not fit the
+// registers next to the staging sets); K is split until there is a workgroup per compute unit.  *S_io: the
+// number of K splits, chosen here when 0 (later row chunks of the same call must use the same).
+static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int *S_io,
+                              hipStream_t st) {
     const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 7) / 8;
-    int S = 1;
-    while (groups * S < 256 && S * 2 <= w.S && KS / (S * 2) >= 2 * WG_U_MAX) S *= 2;
-    *S_used = S;
+    int S = *S_io;
+    if (S == 0) {
+        S = 1;
+        while (groups * S < 256 && S * 2 <= w.S && KS / (S * 2) >= 2 * WG_U_MAX) S *= 2;
+        *S_io = S;
+    }
     switch ((M + 15) / 16) {
-    case 2: return launch_gemm_ws_mt<2>(w, act, plane, part, M, S, groups, st);
-    case 3: return launch_gemm_ws_mt<3>(w, act, plane, part, M, S, groups, st);
-    case 4: return launch_gemm_ws_mt<4>(w, act, plane, part, M, S, groups, st);
-    case 5: return launch_gemm_ws_mt<5>(w, act, plane, part, M, S, groups, st);
-    case 6: return launch_gemm_ws_mt<6>(w, act, plane, part, M, S, groups, st);
-    case 7: return launch_gemm_ws_mt<7>(w, act, plane, part, M, S, groups, st);
-    case 8: return launch_gemm_ws_mt<8>(w, act, plane, part, M, S, groups, st);
-    default: return CSD_ESHAPE;       // 9 row tiles do not fit the registers here: such blocks take the row-split form
+    case 1: return launch_gemm_ws_mt<1>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 2: return launch_gemm_ws_mt<2>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 3: return launch_gemm_ws_mt<3>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 4: return launch_gemm_ws_mt<4>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 5: return launch_gemm_ws_mt<5>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 6: return launch_gemm_ws_mt<6>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 7: return launch_gemm_ws_mt<7>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 8: return launch_gemm_ws_mt<8>(w, act, plane, part, M, Mtot, S, groups, st);
+    default: return CSD_ESHAPE;       // more row tiles do not fit the registers here: such blocks take the row-split form
     }
 }
 
 template <int CT, int RW>
-static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int S, int groups,
-                                hipStream_t st) {
+static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int S,
+                                int groups, hipStream_t st) {
     static bool attr_set = false;
     const size_t lds = (size_t)2 * WG_U_MAX * CT * 64 * 16;
     if (!attr_set) {
@@ -785,7 +695,7 @@ static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane,
         attr_set = true;
     }
     hipLaunchKernelGGL((k_gemm_rs<CT, RW, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
-                       act, plane, part, M, w.K, w.N, S);
+                       act, plane, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
 }
 
@@ -793,18 +703,21 @@ static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane,
 // staging waves keep two chunks of weights in flight per workgroup, so half the compute units already
 // saturate HBM: K is split only until there are 128 workgroups, which keeps the partial-sum traffic low.
 static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t *act, size_t plane, float *part, int M,
-                              int *S_used, hipStream_t st) {
+                              int Mtot, int *S_io, hipStream_t st) {
     const int n_tiles = w.N / 16, KS = w.K / 32, MT = (M + 15) / 16;
     const int rw = (MT + 3) / 4, ct = rw == 3 ? 8 : 16;
     const int groups = (n_tiles + ct - 1) / ct;
-    int S = 1;
-    while (groups * S < 128 && S < 16 && KS / (S + 1) >= 2 * WG_U_MAX &&
-           (size_t)(S + 1) * M * w.N <= mod->part_floats)
-        S++;
-    *S_used = S;
-    if (rw == 1) return launch_gemm_rs_t<16, 1>(w, act, plane, part, M, S, groups, st);
-    if (rw == 2) return launch_gemm_rs_t<16, 2>(w, act, plane, part, M, S, groups, st);
-    if (rw == 3) return launch_gemm_rs_t<8, 3>(w, act, plane, part, M, S, groups, st);
+    int S = *S_io;
+    if (S == 0) {
+        S = 1;
+        while (groups * S < 128 && S < 16 && KS / (S + 1) >= 2 * WG_U_MAX &&
+               (size_t)(S + 1) * Mtot * w.N <= mod->part_floats)
+            S++;
+        *S_io = S;
+    }
+    if (rw == 1) return launch_gemm_rs_t<16, 1>(w, act, plane, part, M, Mtot, S, groups, st);
+    if (rw == 2) return launch_gemm_rs_t<16, 2>(w, act, plane, part, M, Mtot, S, groups, st);
+    if (rw == 3) return launch_gemm_rs_t<8, 3>(w, act, plane, part, M, Mtot, S, groups, st);
     return CSD_ESHAPE;
 }
 
@@ -813,15 +726,17 @@ static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, 
     ProfScope ps(mod, st, CSD_PROF_GEMM);
     *S_used = w.S;
     if (mod->mfma) {
-        if (M > 16 && M <= 144 && mod->gemm_wg) {
-            const int32_t rc = M >= mod->gemm_rs_min_rows
-                                   ? launch_gemm_rs(mod, w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st)
-                                   : launch_gemm_ws(w, (const bf16_t *)act, mod->act_plane, mod->part, M, S_used, st);
+        // up to 144 rows in one launch, more in chunks of 128 rows that share the number of K splits
+        *S_used = 0;
+        const int step = M <= 144 ? M : 128;
+        for (int row0 = 0; row0 < M; row0 += step) {
+            const int rows = M - row0 < step ? M - row0 : step;
+            const bf16_t *a = (const bf16_t *)act + (size_t)row0 * w.K;
+            float *p = mod->part + (size_t)row0 * w.N;
+            const int32_t rc = rows >= mod->gemm_rs_min_rows ? launch_gemm_rs(mod, w, a, mod->act_plane, p, rows, M, S_used, st)
+                                                             : launch_gemm_ws(w, a, mod->act_plane, p, rows, M, S_used, st);
             if (rc != CSD_OK) return rc;
-        } else if (w.nt == 2)
-            launch_gemm_mfma_nt<2, 4>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);
-        else
-            launch_gemm_mfma_nt<1, 8>(w, (const bf16_t *)act, mod->act_plane, mod->part, M, st);
+        }
     } else if (mod->cfg.dtype == CSD_DTYPE_BF16) {
         hipLaunchKernelGGL((k_gemm_simple<bf16_t>), dim3((w.N + 255) / 256), dim3(256), 0, st, (const bf16_t *)w.data,
                            (const float *)act, mod->part, M, w.K, w.N);
@@ -1108,14 +1023,12 @@ static int32_t build_gemm(csd_model *mod, GemmW *g, int K, int N, const Piece *p
     int32_t rc;
     if ((rc = dev_alloc(mod, &g->data, (size_t)K * N * esz)) != CSD_OK) return rc;
     if (mod->mfma) {
-        g->nt = (N / 16) % 2 == 0 && (N / 32) >= 512 ? 2 : 1;
-        g->S = pick_splits(N / (16 * g->nt), K / 32);
+        g->S = pick_splits(N / 16, K / 32);
         for (int i = 0; i < n_pieces; i++)
             if ((rc = pack_tiles(pieces[i].src, K, pieces[i].N_src, g->data, pieces[i].base, pieces[i].stride,
                                  mod->kperm ? pieces[i].perm_dh : 0, st)) != CSD_OK)
                 return rc;
     } else {
-        g->nt = 1;
         g->S = 1;
         (void)interleave;
         int col0 = 0;

@@ -32,7 +32,8 @@
 // Tuning and test knobs read from the environment at csd_model_create: CSD_PATH=multikernel|phases,
 // CSD_FUSED_PF (ring slots prefetched across a barrier), CSD_FUSED_FRESH=0 (reuse the exchange buffers
 // and invalidate L2 after every barrier), CSD_FUSED_ARRIVE_FIRST=0, CSD_FUSED_VECTOR_POLL,
-// CSD_FUSED_M_LDS (cap on the rows kept in LDS), CSD_FUSED_NO_L2B.
+// CSD_FUSED_M_LDS (cap on the rows kept in LDS), CSD_FUSED_L2B (enables the variant that reads the
+// activation fragments from L2, for blocks of up to 16 rows that do not fit LDS).
 #include <mutex>
 #include <vector>
 
@@ -1233,7 +1234,8 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     if (const char *e = getenv("CSD_FUSED_PF")) fs->pf = atoi(e) < 0 ? 0 : atoi(e);
     if (const char *e = getenv("CSD_FUSED_M_LDS")) m_limit = atoi(e) < m_limit ? (atoi(e) < 1 ? 1 : atoi(e)) : m_limit;   // test knob
     fs->m_limit = m_limit < mod->m_max ? m_limit : mod->m_max;
-    fs->m_limit_l2b = getenv("CSD_FUSED_NO_L2B") ? 0 : (16 < mod->m_max ? 16 : mod->m_max);
+    // off unless asked for: from 9 rows on the multi-kernel path with its tall-block GEMMs is faster
+    fs->m_limit_l2b = getenv("CSD_FUSED_L2B") ? (16 < mod->m_max ? 16 : mod->m_max) : 0;
     const int m_cap = fs->m_limit;
     size_t act_bytes = (size_t)m_cap * kmax * 4;
     if (act_bytes < (size_t)attn_bytes) act_bytes = attn_bytes;

@@ -128,8 +128,7 @@ extern thread_local int32_t g_csd_last_hip_error;
 struct GemmW {
     void *data = nullptr;   // MFMA path: bf16 tiles [N/16][K/32][64 lanes][8]; generic path: row-major [K][N]
     int K = 0, N = 0;
-    int nt = 1;             // n-tiles (of 16 output features) per wave
-    int S = 1;              // K splits (partial-sum planes)
+    int S = 1;              // most K splits (partial-sum planes) a launch may use
 };
 
 struct LayerW {
@@ -157,8 +156,7 @@ struct csd_model {
     csd_model_cfg cfg;
     bool mfma = false;        // bf16 tiles + MFMA GEMMs; otherwise generic kernels on row-major weights
     bool mfma_attn = false;
-    bool gemm_wg = true;      // blocks of more than 16 rows: workgroup-tiled GEMMs (activations shared through LDS)
-    int gemm_rs_min_rows = 65;   // ... from this many rows on (at most 128 otherwise), the form that splits the rows over the waves
+    int gemm_rs_min_rows = 65;   // blocks of this many rows or more (129 at most) take the GEMM that splits the rows over the waves
     bool kperm = false;       // q / K rows kept in rotary pair order (see KvGeom)
     int hd = 0;               // n_heads * head_dim
     int seq_pad = 0;          // cache rows per sequence, padded to 64

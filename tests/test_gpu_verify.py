@@ -116,13 +116,14 @@ def test_bf16_paths_small_model(shape, gemm, attn, path):
 
 @pytest.mark.parametrize("path", ["phases", "persistent"])
 def test_bf16_single_launch_variant_with_activations_from_l2(path):
-    """Blocks whose rows do not fit LDS (here forced: at most 4 rows in LDS) take the variant of the
-    single-launch kernel that reads the activation fragments from L2: 10 and 16 rows against the oracle."""
-    os.environ["CSD_FUSED_M_LDS"], os.environ["CSD_PATH"] = "4", path
+    """The opt-in variant of the single-launch kernel that reads the activation fragments from L2 (for
+    blocks whose rows do not fit LDS; here forced: at most 4 rows in LDS): 10 and 16 rows against the
+    oracle.  It is off by default because the multi-kernel path is faster at those sizes."""
+    os.environ["CSD_FUSED_M_LDS"], os.environ["CSD_FUSED_L2B"], os.environ["CSD_PATH"] = "4", "1", path
     try:
         gm, om = make_pair(BF128, 7, 2, 300, 16, std=0.05)
     finally:
-        del os.environ["CSD_FUSED_M_LDS"], os.environ["CSD_PATH"]
+        del os.environ["CSD_FUSED_M_LDS"], os.environ["CSD_FUSED_L2B"], os.environ["CSD_PATH"]
     assert gm.path(2, 5) == (2 if path == "persistent" else 1) and gm.path(2, 8) == gm.path(2, 5)
     toks = I.token_ids(2 * 260, BF128.vocab, 7, 1).reshape(2, 260)
     prefill_both(gm, om, toks[:, :200], 16)
@@ -142,11 +143,12 @@ def test_bf16_block_of_17_rows_two_row_tiles():
 WIDE = I.ModelShape("bf_wide_blocks", 0, "bf16", 2, 256, 4, 64, 576, 1040)
 
 
-@pytest.mark.parametrize("B,m", [(4, 5), (4, 9), (4, 13), (4, 17), (8, 12), (8, 14), (8, 16), (8, 17)])
-def test_bf16_blocks_of_2_to_9_row_tiles_workgroup_tiled_gemm(B, m):
-    """B * m = 20 ... 136 rows: every row-tile count of the GEMM that shares activations through LDS; the
-    FFN width (18 k-steps) leaves ragged chunk tails and the vocabulary (65 column tiles) a ragged last
-    workgroup."""
+@pytest.mark.parametrize("B,m", [(4, 5), (4, 9), (4, 13), (4, 17), (8, 12), (8, 14), (8, 16), (8, 17), (10, 16), (12, 17)])
+def test_bf16_blocks_of_2_to_13_row_tiles_workgroup_tiled_gemms(B, m):
+    """B * m = 20 ... 204 rows: every row-tile count of the GEMM that shares activations through LDS (up to
+    64 rows) and of the row-split GEMM (up to 144 rows), and two blocks that go in row chunks of 128 (160
+    rows = 128 + 32, 204 = 128 + 76); the FFN width (18 k-steps) leaves ragged chunk tails and the
+    vocabulary (65 column tiles) a ragged last workgroup."""
     gm, om = make_pair(WIDE, 17, B, 96, 17, std=0.05)
     assert gm.path(B, m) == 0
     toks = I.token_ids(B * 64, WIDE.vocab, 17, 1).reshape(B, 64)
