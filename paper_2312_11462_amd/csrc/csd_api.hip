@@ -36,6 +36,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + keys_pad) > 64 * 1024) return CSD_ESHAPE;
     int32_t rc;
     if ((rc = csd_pack_weights(mod, weights, st)) != CSD_OK) return rc;
+    if (mod->mfma && (rc = csd_gemm_setup()) != CSD_OK) return rc;
 
     const size_t asz = mod->mfma ? 2 : 4;
     const int m_pad = (mod->m_max + 15) / 16 * 16;

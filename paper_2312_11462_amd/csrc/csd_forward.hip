@@ -649,12 +649,7 @@ ProfScope::~ProfScope() {
 template <int MT>
 static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int S,
                                  int groups, hipStream_t st) {
-    static bool attr_set = false;
-    const size_t lds = (size_t)2 * WG_U_MAX * MT * 2 * 64 * 16;
-    if (!attr_set) {
-        CSD_HIP(hipFuncSetAttribute((const void *)k_gemm_ws<2, MT, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    const size_t lds = (size_t)2 * WG_U_MAX * MT * 2 * 64 * 16;      // allowed at csd_gemm_setup
     hipLaunchKernelGGL((k_gemm_ws<2, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
                        act, plane, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
@@ -688,12 +683,7 @@ static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, f
 template <int CT, int RW>
 static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int S,
                                 int groups, hipStream_t st) {
-    static bool attr_set = false;
-    const size_t lds = (size_t)2 * WG_U_MAX * CT * 64 * 16;
-    if (!attr_set) {
-        CSD_HIP(hipFuncSetAttribute((const void *)k_gemm_rs<CT, RW, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    const size_t lds = (size_t)2 * WG_U_MAX * CT * 64 * 16;          // allowed at csd_gemm_setup
     hipLaunchKernelGGL((k_gemm_rs<CT, RW, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
                        act, plane, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
@@ -719,6 +709,33 @@ static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t
     if (rw == 2) return launch_gemm_rs_t<16, 2>(w, act, plane, part, M, Mtot, S, groups, st);
     if (rw == 3) return launch_gemm_rs_t<8, 3>(w, act, plane, part, M, Mtot, S, groups, st);
     return CSD_ESHAPE;
+}
+
+// Once per process and device, at model creation (no runtime call besides launches happens later): allow
+// every GEMM instantiation its dynamic LDS (up to 144 KB).
+template <int MT>
+static hipError_t ws_allow_lds() {
+    return hipFuncSetAttribute((const void *)k_gemm_ws<2, MT, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               2 * WG_U_MAX * MT * 2 * 64 * 16);
+}
+template <int CT, int RW>
+static hipError_t rs_allow_lds() {
+    return hipFuncSetAttribute((const void *)k_gemm_rs<CT, RW, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               2 * WG_U_MAX * CT * 64 * 16);
+}
+int32_t csd_gemm_setup() {
+    CSD_HIP(ws_allow_lds<1>());
+    CSD_HIP(ws_allow_lds<2>());
+    CSD_HIP(ws_allow_lds<3>());
+    CSD_HIP(ws_allow_lds<4>());
+    CSD_HIP(ws_allow_lds<5>());
+    CSD_HIP(ws_allow_lds<6>());
+    CSD_HIP(ws_allow_lds<7>());
+    CSD_HIP(ws_allow_lds<8>());
+    CSD_HIP((rs_allow_lds<16, 1>()));
+    CSD_HIP((rs_allow_lds<16, 2>()));
+    CSD_HIP((rs_allow_lds<8, 3>()));
+    return CSD_OK;
 }
 
 // act: [M][w.K] in the path's activation type; part: [S][M][w.N] with S (<= w.S) returned in *S_used

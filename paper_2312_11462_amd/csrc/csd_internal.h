@@ -199,6 +199,7 @@ struct csd_model {
 int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
                             int32_t B, int32_t m, float *logits, hipStream_t st);
 int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st);
+int32_t csd_gemm_setup();    // MFMA models, at creation: lets the GEMM kernels use their dynamic LDS
 size_t csd_self_kv_bytes(const csd_model *mod);     // the self-attention part of the cache (arch 1 appends the cross part)
 // csd_fused.hip: single-launch forward for small blocks
 int32_t csd_fused_init(csd_model *mod, hipStream_t st);
