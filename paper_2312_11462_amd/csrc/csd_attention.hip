@@ -16,7 +16,11 @@
 
 #define ATT_CHUNK 128      /* keys per wave at least (the partial buffer is sized for this) */
 
-template <int DH>
+// PRE: key tiles (32 keys) whose K and V fragments are requested together before any of them is used.
+// A small grid (few sequences and heads) is bound by the chain of memory round trips of each wave, not by
+// bandwidth: with PRE = 4 a wave has its whole 128-key chunk in flight at once (at the price of registers,
+// i.e. of waves per SIMD, which such a grid does not fill anyway).
+template <int DH, int PRE>
 __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, size_t qplane, int m, int row_tiles,
                                                   const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
                                                   const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
@@ -58,76 +62,102 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
     for (int dt = 0; dt < DH / 16; dt++) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float mrun = -INFINITY, lrun = 0.f;
 
-    for (int sub = 0; sub < chunk_keys / 32; sub++) {
-        const int kb = key0 + sub * 32;
-        if (kb >= nk) break;
-        // scores: A-row r of tile T is key kb + 8*(r/4) + 4*T + r%4, so lane group g ends up with keys kb+8g..kb+8g+7
-        f32x4 sT[2];
+    for (int sub0 = 0; sub0 < chunk_keys / 32; sub0 += PRE) {
+        if (key0 + sub0 * 32 >= nk) break;
+        // A operands of PRE tiles.  K: A-row r of tile T is key kb + 8*(r/4) + 4*T + r%4, so lane group g ends up
+        // with the scores of keys kb+8g..kb+8g+7; V^T: row = feature dt*16 + col, 8 consecutive keys per lane.
+        u32x4 kf[PRE][2][DH / 32], vfr[PRE][DH / 16];
 #pragma unroll
-        for (int T = 0; T < 2; T++) {
-            sT[T] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const int key = kb + 8 * (col >> 2) + 4 * T + (col & 3);
-            const bf16_t *kp = kc + (size_t)key * DH + 8 * g;
+        for (int p = 0; p < PRE; p++) {
+            const int kb = key0 + (sub0 + p) * 32;
+            if (kb < nk && sub0 + p < chunk_keys / 32) {     // uniform
 #pragma unroll
-            for (int s = 0; s < DH / 32; s++) {
-                const u32x4 a = *reinterpret_cast<const u32x4 *>(kp + s * 32);
-                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                                __builtin_bit_cast(bf16x8, qf[s][0]), sT[T], 0, 0, 0);
-                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                                __builtin_bit_cast(bf16x8, qf[s][1]), sT[T], 0, 0, 0);
+                for (int T = 0; T < 2; T++) {
+                    const int key = kb + 8 * (col >> 2) + 4 * T + (col & 3);
+                    const bf16_t *kp = kc + (size_t)key * DH + 8 * g;
+#pragma unroll
+                    for (int s = 0; s < DH / 32; s++) kf[p][T][s] = *reinterpret_cast<const u32x4 *>(kp + s * 32);
+                }
+#pragma unroll
+                for (int dt = 0; dt < DH / 16; dt++)
+                    vfr[p][dt] = *reinterpret_cast<const u32x4 *>(vc + (size_t)(dt * 16 + col) * geo.seq_pad + kb + 8 * g);
+            } else {
+#pragma unroll
+                for (int T = 0; T < 2; T++)
+#pragma unroll
+                    for (int s = 0; s < DH / 32; s++) kf[p][T][s] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int dt = 0; dt < DH / 16; dt++) vfr[p][dt] = u32x4{0u, 0u, 0u, 0u};
             }
         }
-        float sv[8];
-        float mx = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            const int key = kb + 8 * g + j;
-            float s = sT[j >> 2][j & 3] * scale;
-            const bool seen = (!causal || key <= qpos) && key < nk;
-            if (mode.rel_bias && seen) s += mode.rel_bias[mode.bucket[min(qpos - key, 127)] * geo.H + hh];
-            sv[j] = seen ? s : -INFINITY;
-            mx = fmaxf(mx, sv[j]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mnew = fmaxf(mrun, mx);
-        const float alpha = (mnew == -INFINITY) ? 1.0f : expf(mrun - mnew);
-        float pv[8];
-        float psum = 0.f;
+        for (int p = 0; p < PRE; p++) {
+            const int kb = key0 + (sub0 + p) * 32;
+            if (kb >= nk || sub0 + p >= chunk_keys / 32) break;
+            f32x4 sT[2];
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            pv[j] = (sv[j] == -INFINITY) ? 0.f : expf(sv[j] - mnew);
-            psum += pv[j];
-        }
-        psum += __shfl_xor(psum, 16, 64);
-        psum += __shfl_xor(psum, 32, 64);
-        lrun = lrun * alpha + psum;
-        mrun = mnew;
-        u32x4 pf, pl;                                        // hi and lo planes of the probabilities
+            for (int T = 0; T < 2; T++) {
+                sT[T] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int w = 0; w < 4; w++) {
-            const bf16_t h0 = f32_to_bf16(pv[2 * w]), h1 = f32_to_bf16(pv[2 * w + 1]);
-            pf[w] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            pl[w] = (uint32_t)f32_to_bf16(pv[2 * w] - bf16_to_f32(h0)) |
-                    ((uint32_t)f32_to_bf16(pv[2 * w + 1] - bf16_to_f32(h1)) << 16);
-        }
-        const bool tail = kb + 32 > nk;                      // rows past nk may hold anything: zero them
-#pragma unroll
-        for (int dt = 0; dt < DH / 16; dt++) {
-            u32x4 vf = *reinterpret_cast<const u32x4 *>(vc + (size_t)(dt * 16 + col) * geo.seq_pad + kb + 8 * g);
-            if (tail) {
-#pragma unroll
-                for (int w = 0; w < 4; w++) {
-                    const int k0 = kb + 8 * g + 2 * w;
-                    const uint32_t keep = (k0 < nk ? 0x0000FFFFu : 0u) | (k0 + 1 < nk ? 0xFFFF0000u : 0u);
-                    vf[w] &= keep;
+                for (int s = 0; s < DH / 32; s++) {
+                    sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[p][T][s]),
+                                                                    __builtin_bit_cast(bf16x8, qf[s][0]), sT[T], 0, 0, 0);
+                    sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[p][T][s]),
+                                                                    __builtin_bit_cast(bf16x8, qf[s][1]), sT[T], 0, 0, 0);
                 }
             }
-            oacc[dt] = oacc[dt] * alpha;
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
-                                                               __builtin_bit_cast(bf16x8, pf), oacc[dt], 0, 0, 0);
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
-                                                               __builtin_bit_cast(bf16x8, pl), oacc[dt], 0, 0, 0);
+            float sv[8];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const int key = kb + 8 * g + j;
+                float s = sT[j >> 2][j & 3] * scale;
+                const bool seen = (!causal || key <= qpos) && key < nk;
+                if (mode.rel_bias && seen) s += mode.rel_bias[mode.bucket[min(qpos - key, 127)] * geo.H + hh];
+                sv[j] = seen ? s : -INFINITY;
+                mx = fmaxf(mx, sv[j]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mnew = fmaxf(mrun, mx);
+            const float alpha = (mnew == -INFINITY) ? 1.0f : expf(mrun - mnew);
+            float pv[8];
+            float psum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                pv[j] = (sv[j] == -INFINITY) ? 0.f : expf(sv[j] - mnew);
+                psum += pv[j];
+            }
+            psum += __shfl_xor(psum, 16, 64);
+            psum += __shfl_xor(psum, 32, 64);
+            lrun = lrun * alpha + psum;
+            mrun = mnew;
+            u32x4 pf, pl;                                    // hi and lo planes of the probabilities
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                const bf16_t h0 = f32_to_bf16(pv[2 * w]), h1 = f32_to_bf16(pv[2 * w + 1]);
+                pf[w] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                pl[w] = (uint32_t)f32_to_bf16(pv[2 * w] - bf16_to_f32(h0)) |
+                        ((uint32_t)f32_to_bf16(pv[2 * w + 1] - bf16_to_f32(h1)) << 16);
+            }
+            const bool tail = kb + 32 > nk;                  // rows past nk may hold anything: zero them
+#pragma unroll
+            for (int dt = 0; dt < DH / 16; dt++) {
+                u32x4 vf = vfr[p][dt];
+                if (tail) {
+#pragma unroll
+                    for (int w = 0; w < 4; w++) {
+                        const int k0 = kb + 8 * g + 2 * w;
+                        const uint32_t keep = (k0 < nk ? 0x0000FFFFu : 0u) | (k0 + 1 < nk ? 0xFFFF0000u : 0u);
+                        vf[w] &= keep;
+                    }
+                }
+                oacc[dt] = oacc[dt] * alpha;
+                oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                                   __builtin_bit_cast(bf16x8, pf), oacc[dt], 0, 0, 0);
+                oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                                   __builtin_bit_cast(bf16x8, pl), oacc[dt], 0, 0, 0);
+            }
         }
     }
 #pragma unroll
@@ -175,9 +205,15 @@ static void attn_launch(csd_model *mod, const KvGeom &geo, const void *kv, const
     while (chunk_keys < 1024 && (long long)((keys + chunk_keys - 1) / chunk_keys) * c.n_heads * B * row_tiles > 4096) chunk_keys *= 2;
     int chunks = (keys + chunk_keys - 1) / chunk_keys;
     if (chunks > mod->attn_chunks_max) chunks = mod->attn_chunks_max;
-    hipLaunchKernelGGL((k_attn_mfma<DH>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st, (const bf16_t *)mod->qbuf,
-                       mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale, mod->attn_part,
-                       mod->attn_chunks_max, chunk_keys, mode);
+    // a grid the chip holds at one wave per SIMD: each wave requests its whole first 128 keys at once
+    if ((long long)chunks * c.n_heads * B * row_tiles <= 1024)
+        hipLaunchKernelGGL((k_attn_mfma<DH, 4>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st,
+                           (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale,
+                           mod->attn_part, mod->attn_chunks_max, chunk_keys, mode);
+    else
+        hipLaunchKernelGGL((k_attn_mfma<DH, 1>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st,
+                           (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale,
+                           mod->attn_part, mod->attn_chunks_max, chunk_keys, mode);
     hipLaunchKernelGGL((k_attn_merge<DH>), dim3(B * m, c.n_heads), dim3(DH), 0, st, mod->attn_part, m, row_tiles, cache_len,
                        c.n_heads, geo.seq_pad, mod->attn_chunks_max, chunk_keys, (bf16_t *)mod->act, mod->hd, mod->act_plane,
                        mode.fixed_nk);
