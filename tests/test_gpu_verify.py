@@ -157,6 +157,10 @@ def test_bf16_blocks_of_2_to_13_row_tiles_workgroup_tiled_gemms(B, m):
     blocks = np.stack([toks[b, cl[b]:cl[b] + m].numpy() for b in range(B)])
     err = _check_block(gm, om, blocks, cl, 2e-2, 1e-2, f"B={B} m={m}")
     print("rows", B * m, "max err", err)
+    # the K-split partial sums are reduced in a fixed order: a second run gives the same bits
+    a = gm.verify_block(_dev(blocks), _dev(cl)).cpu().numpy().copy()
+    b = gm.verify_block(_dev(blocks), _dev(cl)).cpu().numpy()
+    assert np.array_equal(a, b)
 
 
 def test_draft160m_config_synthetic_cache():
