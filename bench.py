@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="target7b")
+    ap.add_argument("--k", type=int, default=None, help="drafts per sequence instead of the workload's (configuration 5 sweeps it)")
     ap.add_argument("--prof-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy"])
@@ -73,6 +74,9 @@ def main():
     torch.cuda.set_device(0)
     wl = I.WORKLOADS[args.workload]
     shape, B, t, k, seed = wl["shape"], wl["B"], wl["prefix"], wl["k"], wl["seed"]
+    if args.k is not None:
+        k = args.k
+    target_mix = wl.get("draft") == "target_mix"
     m = k + 1
     n_from_draft_model = 2 if args.workload in ("target7b", "t5xxl") else 0     # horizontal cascade: 2 neural drafts, tail from Max-Gram
     k_tail = k - n_from_draft_model
@@ -116,10 +120,41 @@ def main():
     n_acc = torch.zeros(B, dtype=torch.int32, device="cuda")
     nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
     mode = 0 if args.mode == "sample" else 1
+    q_draft = None
+    if target_mix:
+        # Drafts sampled from the reviewer's own next-token distributions perturbed by seeded noise:
+        # q_i = softmax(logits_i + sigma * g_i), x_i ~ q_i, with sigma set (by bisection at the first position)
+        # so that the expected acceptance sum_x min(p_i(x), q_i(x)) is the workload's.  k one-row forwards
+        # at setup; they leave exactly the cache rows the timed block rewrites.
+        V = shape.vocab
+        q_draft = torch.empty((B, k, V), dtype=torch.float32, device="cuda")
+        u_draft = I.uniforms(B * k, seed, 9).reshape(B, k).to(torch.float64).cuda()
+        sigma = None
+        for i in range(k):
+            lg = model.verify_block(block[:, i:i + 1].contiguous(), cache_len + i)[:, 0, :]
+            p_i = torch.softmax(lg, dim=-1)
+            g_i = I.normal((B, V), 1.0, seed, 100 + i, device="cuda")
+            if sigma is None:
+                lo, hi = 0.0, 16.0
+                for _ in range(40):
+                    mid = 0.5 * (lo + hi)
+                    acc = torch.minimum(p_i, torch.softmax(lg + mid * g_i, dim=-1)).sum(-1).mean().item()
+                    lo, hi = (mid, hi) if acc > wl["acceptance"] else (lo, mid)
+                sigma = 0.5 * (lo + hi)
+            q_i = torch.softmax(lg + sigma * g_i, dim=-1)
+            q_draft[:, i, :] = q_i
+            cdf = torch.cumsum(q_i.to(torch.float64), dim=-1)
+            x_i = torch.searchsorted(cdf, (u_draft[:, i] * cdf[:, -1])[:, None], right=True)[:, 0].clamp_(max=V - 1)
+            block[:, i + 1] = x_i.to(torch.int32)
+        onehot = None
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
     def step():
+        if target_mix:   # the drafts and their distributions are inputs of this configuration
+            model.verify_accept(block, cache_len, u_acc, u_samp, q=q_draft, q_onehot=None, mode=mode,
+                                n_accepted=n_acc, next_token=nxt)
+            return
         if B == 1:       # the draft lands directly in the block's tail
             P.bigram_draft(ctx, ctx_len, table, k_tail, want_match_len=False, out=block[:, 1 + n_from_draft_model:])
         else:
@@ -206,20 +241,22 @@ def main():
             om.kv_write(l, 0, 0, K.cpu().numpy(), V.cpu().numpy())
         hctx = ctx[:1].cpu().numpy()
         htab = table.cpu().numpy()
+        hq = q_draft[:1].cpu().numpy() if target_mix else None
         c0 = time.perf_counter()
-        d, _ = O.bigram_draft(hctx, ctx_len[:1].cpu().numpy(), htab, k_tail)
         hb = block[:1].cpu().numpy().copy()
-        hb[:, 1 + n_from_draft_model:] = d
+        if not target_mix:
+            d, _ = O.bigram_draft(hctx, ctx_len[:1].cpu().numpy(), htab, k_tail)
+            hb[:, 1 + n_from_draft_model:] = d
         lg = om.verify_block(hb, [t])
         pr = O.probs_f32(lg)
-        on, ot = O.accept(pr, None, hb[:, 1:], u_acc[:1].cpu().numpy(), u_samp[:1].cpu().numpy(), 1.0, mode)
+        on, ot = O.accept(pr, hq, hb[:, 1:], u_acc[:1].cpu().numpy(), u_samp[:1].cpu().numpy(), 1.0, mode)
         cpu_s = time.perf_counter() - c0
         # in-run parity of sequence 0 (untimed): the forward within the logit tolerance, and the accept
         # decision bit-identical when both sides are given the same distributions (the GPU's)
         g_lg, g_pr = model.verify_block(block[:1].contiguous(), cache_len[:1].contiguous(), want_probs=True)
         torch.cuda.synchronize()
         dl = float(np.abs(g_lg[0].cpu().numpy().astype(np.float64) - lg[0]).max())
-        gn, gt = O.accept((g_lg if mode == 1 else g_pr).cpu().numpy(), None, hb[:, 1:], u_acc[:1].cpu().numpy(), u_samp[:1].cpu().numpy(), 1.0, mode)
+        gn, gt = O.accept((g_lg if mode == 1 else g_pr).cpu().numpy(), hq, hb[:, 1:], u_acc[:1].cpu().numpy(), u_samp[:1].cpu().numpy(), 1.0, mode)
         cpu = {"value": round(k / cpu_s, 3), "unit": "verified tokens/s", "cores": O.threads(), "kind": "oracle",
                "sample": f"one whole step of sequence 0 (k={k} drafts, {t}-row cache): {cpu_s:.2f} s",
                "max_abs_dlogit_vs_gpu": round(dl, 6),
@@ -236,10 +273,13 @@ def main():
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {shape.n_layers} layers, d_model {shape.d_model}, batch {B}, "
                                f"{t}-row KV cache" + (f", {shape.enc_len} encoder rows" if shape.arch == 1 else "") +
-                               f", block of k={k} drafts ({n_from_draft_model} stand-ins for the neural "
-                               f"draft level + {k_tail} from Max-Gram), mode {args.mode}",
+                               (f", block of k={k} drafts sampled from the reviewer's noise-perturbed distributions "
+                                f"(expected acceptance {wl['acceptance']})" if target_mix else
+                                f", block of k={k} drafts ({n_from_draft_model} stand-ins for the neural "
+                                f"draft level + {k_tail} from Max-Gram)") + f", mode {args.mode}",
                    "batch": B, "prefix": t, "k": k},
         "emitted_tokens_per_s": round(emitted / (wall / args.steps), 2),
+        "accepted_drafts_per_sequence": round(float(n_acc.float().mean().item()), 3),
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,

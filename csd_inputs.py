@@ -184,7 +184,9 @@ WORKLOADS = {
     "tiny":        dict(shape=TINY, B=1, prefix=32, k=4, seed=0xC5D00001),
     "draft160m":   dict(shape=DRAFT_160M, B=1, prefix=512, k=8, seed=0xC5D00002),
     "target7b":    dict(shape=TARGET_7B, B=1, prefix=1024, k=5, seed=0xC5D00003),
-    "target7b_b8": dict(shape=TARGET_7B, B=8, prefix=2048, k=16, seed=0xC5D00003),
+    # drafts of this configuration are sampled from the reviewer's own distributions perturbed by seeded
+    # noise so that a draft is accepted with probability about 0.6 (bench.py builds them at setup)
+    "target7b_b8": dict(shape=TARGET_7B, B=8, prefix=2048, k=16, seed=0xC5D00003, draft="target_mix", acceptance=0.6),
     "t5xxl":       dict(shape=T5XXL_DEC, B=1, prefix=256, k=4, seed=0xC5D00004),
 }
 
