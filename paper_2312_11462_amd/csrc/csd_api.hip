@@ -66,6 +66,9 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->m_max * V));
     mod->allocs.push_back(p);
     mod->probs = (float *)p;
+    CSD_HIP(hipMalloc(&p, sizeof(float2) * (size_t)mod->m_max * (c.head_dim / 2 + 1)));
+    mod->allocs.push_back(p);
+    mod->rope = (float2 *)p;
     if (mod->mfma_attn) {
         // per (sequence, head, key chunk): 16*ceil(m/16) rows x (dh accumulators + max + sum)
         mod->attn_chunks_max = (keys_pad + 127) / 128;

@@ -439,12 +439,24 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
         store_act<TA>(a, plane, (size_t)r * lda + x, h[(size_t)r * d + x] * rs * g[x]);
 }
 
-// Sum the QKV partial planes, rotate q and k (half-split pairs, angle pos * theta^(-2x/dh)), write q for
-// the attention kernel and append K (rotated) and V to the cache at position cache_len[b] + i.
+// (cos, sin) of the rotary angle pos * theta^(-2x/dh) of every block row of a call and every pair x < dh/2,
+// evaluated in double precision once per call instead of once per layer and head.
+__global__ void k_rope_table(const int32_t *__restrict__ cache_len, int m, int dh, float theta, float2 *__restrict__ tab) {
+    const int r = blockIdx.x, half = dh / 2;
+    const int pos = cache_len[r / m] + r % m;
+    for (int x = threadIdx.x; x < half; x += blockDim.x) {
+        const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
+        tab[(size_t)r * half + x] = float2{(float)cos(ang), (float)sin(ang)};
+    }
+}
+
+// Sum the QKV partial planes, rotate q and k (half-split pairs, angles from k_rope_table; no table: no
+// rotation), write q for the attention kernel and append K (rotated) and V to the cache at position
+// cache_len[b] + i.
 template <typename TA, typename TC>
 __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, int S, int M, int m,
                                                 const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
-                                                float theta, TA *__restrict__ qout, size_t qplane,
+                                                const float2 *__restrict__ rope, TA *__restrict__ qout, size_t qplane,
                                                 TC *__restrict__ kv) {
     const int r = blockIdx.x, hh = blockIdx.y;
     const int b = r / m, i = r % m;
@@ -465,11 +477,11 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
             v0 += p[2 * hd + x];
             v1 += p[2 * hd + x + half];
         }
-        float c = 1.f, sn = 0.f;                         // theta <= 0: a model without rotary embedding
-        if (theta > 0.f) {
-            const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
-            c = (float)cos(ang);
-            sn = (float)sin(ang);
+        float c = 1.f, sn = 0.f;                         // no table: a model without rotary embedding
+        if (rope) {
+            const float2 cs = rope[(size_t)r * half + x];
+            c = cs.x;
+            sn = cs.y;
         }
         store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p0, q0 * c - q1 * sn);
         store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p1, q0 * sn + q1 * c);
@@ -787,6 +799,11 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         CSD_LAUNCH_CHECK();
     }
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
+    if (c.rope_theta > 0.f) {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        hipLaunchKernelGGL(k_rope_table, dim3(M), dim3(64), 0, st, cache_len, m, c.head_dim, c.rope_theta, mod->rope);
+        CSD_LAUNCH_CHECK();
+    }
     for (int l = 0; l < L; l++) {
         const LayerW &lw = mod->layers[l];
         int32_t rc;
@@ -794,7 +811,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, S_g, M, m,
-                               cache_len, geo, l, c.rope_theta, qb, mod->q_plane, (TC *)kv);
+                               cache_len, geo, l, c.rope_theta > 0.f ? mod->rope : nullptr, qb, mod->q_plane, (TC *)kv);
             CSD_LAUNCH_CHECK();
         }
         if (mod->mfma_attn) {
@@ -897,7 +914,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, S_g, M, m, cache_len,
-                               geo, l, 0.0f, qb, mod->q_plane, (TC *)kv);
+                               geo, l, (const float2 *)nullptr, qb, mod->q_plane, (TC *)kv);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = attention_any<TA, TC>(mod, geo, kv, cache_len, B, m, l, 1.0f, self_mode, st)) != CSD_OK) return rc;

@@ -176,6 +176,7 @@ struct csd_model {
     size_t part_floats = 0;      // its capacity
     float *attn_part = nullptr;  // attention partials (MFMA attention)
     float *probs = nullptr;      // [m_max][V] when the caller does not want them
+    float2 *rope = nullptr;      // (cos, sin) of the rotary angles of the current call [m_max][head_dim / 2]
     int attn_chunks_max = 0;
     // arch 1
     int enc_pad = 0;                 // encoder rows padded to 64
