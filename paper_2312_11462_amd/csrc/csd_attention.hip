@@ -80,7 +80,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
                 }
 #pragma unroll
                 for (int dt = 0; dt < DH / 16; dt++)
-                    vfr[p][dt] = *reinterpret_cast<const u32x4 *>(vc + (size_t)(dt * 16 + col) * geo.seq_pad + kb + 8 * g);
+                    vfr[p][dt] = *reinterpret_cast<const u32x4 *>(vc + kv_v_idx(geo, dt * 16 + col, kb + 8 * g));
             } else {
 #pragma unroll
                 for (int T = 0; T < 2; T++)

@@ -488,8 +488,8 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
         if (pos_ok) {
             kc[(size_t)pos * dh + p0] = from_f32<TC>(k0 * c - k1 * sn);
             kc[(size_t)pos * dh + p1] = from_f32<TC>(k0 * sn + k1 * c);
-            vc[(size_t)x * geo.seq_pad + pos] = from_f32<TC>(v0);
-            vc[(size_t)(x + half) * geo.seq_pad + pos] = from_f32<TC>(v1);
+            vc[kv_v_idx(geo, x, pos)] = from_f32<TC>(v0);
+            vc[kv_v_idx(geo, x + half, pos)] = from_f32<TC>(v1);
         }
     }
 }
@@ -555,7 +555,7 @@ __global__ __launch_bounds__(256) void k_fix_cross_kv(const float *__restrict__ 
     }
     const int hh = j / geo.dh, x = j % geo.dh, pos = row0 + r;
     kvc[kv_k_off(geo, layer, b, hh) + (size_t)pos * geo.dh + x] = from_f32<TC>(k);
-    kvc[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos] = from_f32<TC>(v);
+    kvc[kv_v_off(geo, layer, b, hh) + kv_v_idx(geo, x, pos)] = from_f32<TC>(v);
 }
 
 // a[r][x] = src[r][x] as GEMM input rows (two bf16 planes on the MFMA path)
@@ -611,7 +611,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, in
     const float rz = 1.0f / z;
     for (int x = threadIdx.x; x < dh; x += 64) {
         float o = 0.f;
-        for (int j = 0; j < nk; j++) o = fmaf(sc[j], to_f32<TC>(vc[(size_t)x * geo.seq_pad + j]), o);
+        for (int j = 0; j < nk; j++) o = fmaf(sc[j], to_f32<TC>(vc[kv_v_idx(geo, x, j)]), o);
         store_act<TA>(out, plane, (size_t)r * ldo + hh * dh + x, o * rz);
     }
 }
@@ -625,7 +625,7 @@ __global__ void k_kv_write(TC *__restrict__ kv, KvGeom geo, int layer, int b, in
     if (idx >= (size_t)n * hd) return;
     const int i = (int)(idx / hd), c = (int)(idx % hd), hh = c / geo.dh, x = c % geo.dh;
     kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + rope_perm(x, geo.dh, geo.kperm)] = from_f32<TC>(K[idx]);
-    kv[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos0 + i] = from_f32<TC>(V[idx]);
+    kv[kv_v_off(geo, layer, b, hh) + kv_v_idx(geo, x, pos0 + i)] = from_f32<TC>(V[idx]);
 }
 template <typename TC>
 __global__ void k_kv_read(const TC *__restrict__ kv, KvGeom geo, int layer, int b, int pos0, int n,
@@ -635,7 +635,7 @@ __global__ void k_kv_read(const TC *__restrict__ kv, KvGeom geo, int layer, int 
     if (idx >= (size_t)n * hd) return;
     const int i = (int)(idx / hd), c = (int)(idx % hd), hh = c / geo.dh, x = c % geo.dh;
     K[idx] = to_f32<TC>(kv[kv_k_off(geo, layer, b, hh) + (size_t)(pos0 + i) * geo.dh + rope_perm(x, geo.dh, geo.kperm)]);
-    V[idx] = to_f32<TC>(kv[kv_v_off(geo, layer, b, hh) + (size_t)x * geo.seq_pad + pos0 + i]);
+    V[idx] = to_f32<TC>(kv[kv_v_off(geo, layer, b, hh) + kv_v_idx(geo, x, pos0 + i)]);
 }
 
 // ------------------------------------------------------------------------------- host driver

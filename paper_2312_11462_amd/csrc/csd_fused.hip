@@ -437,7 +437,7 @@ __device__ __forceinline__ void gemm_epilogue(CParams &P, const PhaseBufs &X, co
             const __amdgpu_buffer_rsrc_t rv = co_rsrc(P.kv + kv_v_off(geo, A.layer, b, head), head_bytes);
 #pragma unroll
             for (int r = 0; r < 4; r++)
-                co_st16(rv, (int)(((size_t)(16 * ti + 4 * g + r) * P.seq_pad + pos) * 2), f32_to_bf16(v[r]));
+                co_st16(rv, (int)(kv_v_idx(geo, 16 * ti + 4 * g + r, pos) * 2), f32_to_bf16(v[r]));
         }
     }
 }
@@ -831,7 +831,7 @@ __device__ __noinline__ void phase_attn(CParams &P, int layer, char *smem, int w
             }
 #pragma unroll
             for (int dt = 0; dt < DH / 16; dt++)
-                vf[dt] = *reinterpret_cast<const u32x4 *>(vc + (size_t)(dt * 16 + col) * P.seq_pad + kb + 8 * g);
+                vf[dt] = *reinterpret_cast<const u32x4 *>(vc + kv_v_idx(geo, dt * 16 + col, kb + 8 * g));
             f32x4 sT[2];
 #pragma unroll
             for (int T = 0; T < 2; T++) {

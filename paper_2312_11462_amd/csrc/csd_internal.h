@@ -48,8 +48,11 @@ template <> __device__ __forceinline__ void store_act<bf16_t>(bf16_t *p, size_t 
     p[idx + plane] = f32_to_bf16(v - bf16_to_f32(hi));
 }
 
-// KV cache addressing.  K: [L][Bmax][H][seq_pad][dh];  V is stored transposed, [L][Bmax][H][dh][seq_pad],
-// so that the P*V contraction reads 8 consecutive keys per lane.  When kperm is set (MFMA models), the dh
+// KV cache addressing.  K: [L][Bmax][H][seq_pad][dh];  V is stored transposed in blocks of 32 positions,
+// [L][Bmax][H][seq_pad/32][dh][32], so that the P*V contraction reads 8 consecutive keys per lane and the
+// V fragments a wave needs of a 32-key tile are one contiguous dh * 64 bytes (whole cache lines: with plain
+// [dh][seq_pad] rows every tile used half of each line it touched and the attention kernel fetched 1.5x its
+// bytes).  kv_v_idx gives the element index inside a (layer, sequence, head) region.  When kperm is set (MFMA models), the dh
 // entries of a K row (and of a query row) are stored in "pair order": 16-entry tile ti holds the 8 entries
 // 8ti..8ti+7 of the first half followed by their rotary partners 8ti+dh/2.. of the second half, so that a
 // 16-feature MFMA output tile contains whole rotary pairs.  q.k is invariant under a common permutation.
@@ -60,6 +63,9 @@ __host__ __device__ inline int rope_perm(int x, int dh, int kperm) {
     if (!kperm) return x;
     const int half = dh / 2, xp = x < half ? x : x - half;
     return 16 * (xp / 8) + (xp % 8) + (x < half ? 0 : 8);
+}
+__host__ __device__ inline size_t kv_v_idx(const KvGeom &g, int feature, int pos) {
+    return ((size_t)(pos >> 5) * g.dh + feature) * 32 + (pos & 31);
 }
 __host__ __device__ inline size_t kv_head_elems(const KvGeom &g) { return (size_t)g.seq_pad * g.dh; }
 __host__ __device__ inline size_t kv_k_off(const KvGeom &g, int l, int b, int hh) {
