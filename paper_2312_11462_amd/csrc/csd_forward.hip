@@ -277,7 +277,7 @@ __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, c
                 acc[r][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
                     __builtin_bit_cast(bf16x8, wf_[idx % (PD + 1)]), __builtin_bit_cast(bf16x8, a[u][r][1]), acc[r][ct], 0, 0, 0); \
             if (ct == CT - 1) CSD_RS_LOAD_A(u, (KS_NEXT) + u) /* slot u is free: k-step U ahead */  \
-            __builtin_amdgcn_sched_barrier(0);                                                    \
+            if (RW != 3 || (idx & 3) == 3) __builtin_amdgcn_sched_barrier(0);                    \
         }                                                                                         \
     }
 
