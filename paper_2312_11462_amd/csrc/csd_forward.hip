@@ -55,16 +55,17 @@ __global__ void k_copy_cols(const T *__restrict__ src, int K, int N_src, T *__re
 // Every form writes fp32 partial sums per K split ([S][M][N]); the epilogue kernels reduce them in a
 // fixed order.
 
-// Blocks of up to 64 rows.  A workgroup covers 4 * NT adjacent output tiles of one K slice and shares the
-// activation fragments through LDS (a form with one independent wave per output tile re-read them from
-// L2 in every wave and was slower from 6 rows on) (two chunks of U k-steps,
+// Blocks of up to 64 rows (MT row tiles).  A workgroup covers 4 * NT adjacent output tiles of one K slice
+// and shares the activation fragments through LDS: two chunks of U k-steps, laid out
 // [chunk][u][row tile][hi|lo plane][lane] in MFMA operand order, so a fragment is one conflict-free 16-byte
-// LDS read).  The two jobs are given to different waves: waves 0-3 only stream weights and feed the matrix
-// cores (all row tiles), waves 4-7 only move activation fragments from L2 to LDS, two chunks ahead in
-// registers and one chunk ahead in LDS.  A wave that waits for its oldest
-// load also waits for nothing younger, so with the jobs apart the weight ring and the activation staging
-// each keep their own depth; one workgroup barrier per chunk hands a staged chunk over and frees the other
-// buffer.  Both kinds of waves pass exactly 1 + (number of chunks) barriers.
+// LDS read.  (A form with one independent wave per output tile re-read the activations from L2 in every
+// wave and was slower from 6 rows on.)  The two jobs are given to different waves: waves 0-3 only stream
+// weights (a register ring refilled k-step by k-step) and feed the matrix cores for all row tiles; waves
+// 4-7 only move activation fragments from L2 to LDS, two chunks ahead in registers and one chunk ahead in
+// LDS.  A wave that waits for its oldest load waits for nothing younger, so with the jobs apart the weight
+// ring and the activation staging each keep their own depth.  One workgroup barrier per chunk hands a
+// staged chunk over and frees the other buffer; both kinds of waves pass exactly 1 + (number of chunks)
+// barriers.
 template <int NT, int MT, int U>
 __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
                                                  float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
@@ -211,8 +212,8 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
 // in LDS); a compute wave keeps its own rows' activation fragments in registers (fetched from L2 one chunk
 // of k-steps ahead, slot by slot as they are used up) and reads every weight fragment once from LDS for
 // 2 * RW matrix instructions: with two row tiles per wave the matrix cores get four instructions per
-// 16-byte LDS read, where the activation-sharing forms above get two (their LDS reads then take as long as
-// their matrix instructions), and nothing goes through LDS that only one wave needs.
+// 16-byte LDS read, where the activation-sharing form above gets two (its LDS reads then take as long as
+// its matrix instructions), and nothing goes through LDS that only one wave needs.
 template <int CT, int RW, int U>
 __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
                                                  float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
