@@ -88,12 +88,17 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
     if (w < 4) {
         // ------------------------------------------------------------ weight stream + matrix cores
         const int tile0 = (grp * 4 + w) * NT;
-        const u32x4 *wp[NT];
+        // Every load below is issued unconditionally (the compiler can then count the loads in flight and wait
+        // for exactly the oldest ones); what must not be read gets an offset beyond the buffer instead, which
+        // touches no memory and returns zeros.
+        const __amdgpu_buffer_rsrc_t rw =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4 *>(Wp), 0, (int)((size_t)K * N * sizeof(bf16_t)), 0x00020000);
         bool tv[NT];
+        int wvoff[NT];
 #pragma unroll
         for (int j = 0; j < NT; j++) {
             tv[j] = tile0 + j < n_tiles;
-            wp[j] = Wp + ((size_t)(tv[j] ? tile0 + j : 0) * KS) * 64 + lane;
+            wvoff[j] = tv[j] ? lane * 16 : (int)0x80000000;
         }
         f32x4 acc[MT][NT];
 #pragma unroll
@@ -102,12 +107,16 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
             for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         u32x4 wa[U][NT], wb[U][NT];
 
-#define CSD_WS_LOAD_W(WF, KS_AT)                                                                  \
-    _Pragma("unroll") for (int u = 0; u < U; u++) {                                               \
-        const int ksu_ = (KS_AT) + u;                                                             \
+#define CSD_WS_LOAD_W1(WF, UU, KSU)                                                               \
+    {                                                                                             \
+        const int ksu_ = (KSU);                                                                   \
+        const bool in_ = ksu_ < ks1; /* uniform */                                                \
         _Pragma("unroll") for (int j = 0; j < NT; j++)                                            \
-            WF[u][j] = (ksu_ < ks1 && tv[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)ksu_ * 64) : zero; \
+            WF[UU][j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(          \
+                rw, in_ ? wvoff[j] : (int)0x80000000, in_ && tv[j] ? ((tile0 + j) * KS + ksu_) * 1024 : 0, 2)); \
     }
+#define CSD_WS_LOAD_W(WF, KS_AT)                                                                  \
+    _Pragma("unroll") for (int u = 0; u < U; u++) CSD_WS_LOAD_W1(WF, u, (KS_AT) + u)
 #define CSD_WS_MMA(WF, BUF, KS_NEXT)                                                              \
     {                                                                                             \
         const u32x4 *lb_ = lbuf + (BUF) * CH + lane;                                              \
@@ -128,11 +137,8 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
             _Pragma("unroll") for (int j = 0; j < NT; j++)                                        \
                 acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
                     __builtin_bit_cast(bf16x8, WF[u][j]), __builtin_bit_cast(bf16x8, b_[idx % (PD + 1)][1]), acc[mt][j], 0, 0, 0); \
-            if (mt == MT - 1) { /* this k-step's weight registers are free: fetch the k-step 2 * U ahead */ \
-                const int ksn_ = (KS_NEXT) + u;                                                   \
-                _Pragma("unroll") for (int j = 0; j < NT; j++)                                    \
-                    WF[u][j] = (ksn_ < ks1 && tv[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)ksn_ * 64) : zero; \
-            }                                                                                     \
+            if (mt == MT - 1) /* this k-step's weight registers are free: fetch the k-step 2 * U ahead */ \
+                CSD_WS_LOAD_W1(WF, u, (KS_NEXT) + u)                                              \
             __builtin_amdgcn_sched_barrier(0);                                                    \
         }                                                                                         \
     }
@@ -149,6 +155,7 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
             CSD_WS_MMA(wb, 1, ks0 + (c + 3) * U)
             lds_sync();
         }
+#undef CSD_WS_LOAD_W1
 #undef CSD_WS_LOAD_W
 #undef CSD_WS_MMA
 #pragma unroll
@@ -180,10 +187,9 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
     _Pragma("unroll") for (int i = 0; i < ST; i++) {                                              \
         const int r2_ = i * 2 + (sw >> 1), mt_ = r2_ % MT, ksu_ = (KS_AT) + r2_ / MT;             \
         const int soff_ = plane_off + (mt_ * 16 * K + ksu_ * 32) * 2;                             \
-        SF[i] = zero;                                                                             \
-        if (ksu_ < ks1) /* uniform */                                                             \
-            SF[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(              \
-                ra, mt_ == MT - 1 ? voff_last : voff_in, soff_, 0));                              \
+        const bool in_ = ksu_ < ks1; /* uniform; past the slice: an offset beyond the buffer */   \
+        SF[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                  \
+            ra, !in_ ? (int)0x80000000 : mt_ == MT - 1 ? voff_last : voff_in, in_ ? soff_ : 0, 0)); \
     }
 #define CSD_WS_PUT_ACT(SF, BUF)                                                                   \
     _Pragma("unroll") for (int i = 0; i < ST; i++) lbuf[(BUF) * CH + i * 256 + stid] = SF[i];
@@ -255,12 +261,11 @@ __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, c
 #define CSD_RS_LOAD_A(UU, KS_AT)                                                                  \
     {                                                                                             \
         const int ksa_ = (KS_AT);                                                                 \
+        const bool in_ = ksa_ < ks1; /* uniform; past the slice: an offset beyond the buffer, no branch */ \
         _Pragma("unroll") for (int r = 0; r < RW; r++) {                                          \
-            a[UU][r][0] = a[UU][r][1] = zero;                                                     \
-            if (ksa_ < ks1) { /* uniform */                                                       \
-                a[UU][r][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, voff[r], ksa_ * 64, 0)); \
-                a[UU][r][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, voff[r], ksa_ * 64 + lo_off, 0)); \
-            }                                                                                     \
+            const int vo_ = in_ ? voff[r] : (int)0x80000000;                                      \
+            a[UU][r][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, vo_, in_ ? ksa_ * 64 : 0, 0)); \
+            a[UU][r][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, vo_, in_ ? ksa_ * 64 + lo_off : 0, 0)); \
         }                                                                                         \
     }
 #define CSD_RS_MMA(BUF, KS_NEXT)                                                                  \
@@ -320,9 +325,9 @@ __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, c
 #define CSD_RS_LOAD_W(SF, KS_AT)                                                                  \
     _Pragma("unroll") for (int i = 0; i < ST; i++) {                                              \
         const int rest_ = i * 4 + sw, tile_ = tile0 + rest_ % CT, ksu_ = (KS_AT) + rest_ / CT;    \
-        SF[i] = zero;                                                                             \
-        if (ksu_ < ks1 && tile_ < n_tiles) /* uniform */                                          \
-            SF[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, voff, (tile_ * KS + ksu_) * 1024, 2)); \
+        const bool in_ = ksu_ < ks1 && tile_ < n_tiles; /* uniform; else an offset beyond the buffer */ \
+        SF[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                  \
+            rw, in_ ? voff : (int)0x80000000, in_ ? (tile_ * KS + ksu_) * 1024 : 0, 2));          \
     }
 #define CSD_RS_PUT_W(SF, BUF)                                                                     \
     _Pragma("unroll") for (int i = 0; i < ST; i++) lbuf[(BUF) * CH + i * 256 + stid] = SF[i];
