@@ -181,15 +181,33 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
     const int nch = (nk + chunk_keys - 1) / chunk_keys;
     const float *base = part + (((size_t)b * H + hh) * chunks_max * row_tiles + rt) * 16 * PS + (size_t)ri * PS;
     const size_t cstride = (size_t)row_tiles * 16 * PS;
+    // chunk states are read eight at a time (the index is clamped rather than the load skipped, so all eight
+    // loads are in flight together); the sums run in chunk order
     float mstar = -INFINITY;
-    for (int c = 0; c < nch; c++) mstar = fmaxf(mstar, base[c * cstride + DH]);
+    for (int c0 = 0; c0 < nch; c0 += 8) {
+        float mc[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) mc[u] = base[(size_t)min(c0 + u, nch - 1) * cstride + DH];
+#pragma unroll
+        for (int u = 0; u < 8; u++) mstar = fmaxf(mstar, mc[u]);
+    }
     float num = 0.f, den = 0.f;
-    for (int c = 0; c < nch; c++) {
-        const float mc = base[c * cstride + DH];
-        if (mc == -INFINITY) continue;
-        const float w = expf(mc - mstar);
-        num += base[c * cstride + x] * w;
-        den += base[c * cstride + DH + 1] * w;
+    for (int c0 = 0; c0 < nch; c0 += 8) {
+        float mc[8], ac[8], lc[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const size_t o = (size_t)min(c0 + u, nch - 1) * cstride;
+            mc[u] = base[o + DH];
+            ac[u] = base[o + x];
+            lc[u] = base[o + DH + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            if (c0 + u >= nch || mc[u] == -INFINITY) continue;
+            const float w = expf(mc[u] - mstar);
+            num += ac[u] * w;
+            den += lc[u] * w;
+        }
     }
     store_act<bf16_t>(out, plane, (size_t)r * ldo + hh * DH + x, den > 0.f ? num / den : 0.f);
 }
