@@ -52,6 +52,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->h = (float *)p;
     const int planes = mod->mfma ? 2 : 1;
     mod->act_plane = (size_t)m_pad * wmax;
+    mod->act_mtp = mod->mfma ? m_pad / 16 : 0;
     mod->q_plane = (size_t)m_pad * hd;
     CSD_HIP(hipMalloc(&p, asz * planes * mod->act_plane));
     mod->allocs.push_back(p);

@@ -173,7 +173,7 @@ template <int DH>
 __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ part, int m, int row_tiles,
                                                    const int32_t *__restrict__ cache_len, int H, int seq_pad,
                                                    int chunks_max, int chunk_keys, bf16_t *__restrict__ out, int ldo,
-                                                   size_t plane, int fixed_nk) {
+                                                   size_t plane, int mtp, int fixed_nk) {
     constexpr int PS = DH + 4;
     const int r = blockIdx.x, hh = blockIdx.y, x = threadIdx.x;
     const int b = r / m, i = r % m, rt = i / 16, ri = i % 16;
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
             den += lc[u] * w;
         }
     }
-    store_act<bf16_t>(out, plane, (size_t)r * ldo + hh * DH + x, den > 0.f ? num / den : 0.f);
+    store_act<bf16_t>(out, plane, r, hh * DH + x, ldo, mtp, den > 0.f ? num / den : 0.f);
 }
 
 template <int DH>
@@ -234,7 +234,7 @@ static void attn_launch(csd_model *mod, const KvGeom &geo, const void *kv, const
                            (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale,
                            mod->attn_part, mod->attn_chunks_max, chunk_keys, mode);
     hipLaunchKernelGGL((k_attn_merge<DH>), dim3(B * m, c.n_heads), dim3(DH), 0, st, mod->attn_part, m, row_tiles, cache_len,
-                       c.n_heads, geo.seq_pad, mod->attn_chunks_max, chunk_keys, (bf16_t *)mod->act, mod->hd, mod->act_plane,
+                       c.n_heads, geo.seq_pad, mod->attn_chunks_max, chunk_keys, (bf16_t *)mod->act, mod->hd, mod->act_plane, mod->act_mtp,
                        mode.fixed_nk);
 }
 

@@ -68,7 +68,7 @@ __global__ void k_copy_cols(const T *__restrict__ src, int K, int N_src, T *__re
 // barriers.
 template <int NT, int MT, int U>
 __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
-                                                 float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
+                                                 int mtp, float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
     extern __shared__ __align__(16) char wg_smem[];
     constexpr int CH = U * MT * 2 * 64;                      // 16-byte fragments per chunk
     static_assert(CH % 256 == 0, "chunk must divide over the staging waves");
@@ -173,20 +173,21 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
     } else {
         // ------------------------------------------------------------ activation staging
         // fragment i * 256 + (tid - 256) of a chunk = (u, row tile, plane, lane) in that order: u, row tile
-        // and plane are the same for a whole wave, so they go into the scalar offset of a buffer load and
-        // the per-lane part (row within the tile, 8 k-values) is one register for all fragments.  Lanes of
-        // rows past M get an offset beyond the buffer: such loads touch no memory and return zeros.
+        // and plane are the same for a whole wave, so they go into the scalar offset of a buffer load (the
+        // activations are stored fragment by fragment, see act_tiled_idx) and the per-lane part is one
+        // register for all fragments.  Lanes of rows past M get an offset beyond the buffer: such loads
+        // touch no memory and return zeros.
         const int sw = w - 4, stid = tid - 256;
         const __amdgpu_buffer_rsrc_t ra =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(act), 0, (int)(2 * plane * sizeof(bf16_t)), 0x00020000);
-        const int voff_in = (t * K + 8 * g) * 2;
+        const int voff_in = (4 * t + g) * 16;
         const int voff_last = ((MT - 1) * 16 + t < M) ? voff_in : (int)0x80000000;   // the last row tile may be ragged
         const int plane_off = (sw & 1) * (int)(plane * sizeof(bf16_t));
         u32x4 sa[ST], sb[ST];
 #define CSD_WS_LOAD_ACT(SF, KS_AT)                                                                \
     _Pragma("unroll") for (int i = 0; i < ST; i++) {                                              \
         const int r2_ = i * 2 + (sw >> 1), mt_ = r2_ % MT, ksu_ = (KS_AT) + r2_ / MT;             \
-        const int soff_ = plane_off + (mt_ * 16 * K + ksu_ * 32) * 2;                             \
+        const int soff_ = plane_off + (ksu_ * mtp + mt_) * 1024;                                  \
         const bool in_ = ksu_ < ks1; /* uniform; past the slice: an offset beyond the buffer */   \
         SF[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                  \
             ra, !in_ ? (int)0x80000000 : mt_ == MT - 1 ? voff_last : voff_in, in_ ? soff_ : 0, 0)); \
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
 // its matrix instructions), and nothing goes through LDS that only one wave needs.
 template <int CT, int RW, int U>
 __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, const bf16_t *__restrict__ act, size_t plane,
-                                                 float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
+                                                 int mtp, float *__restrict__ part, int M, int Mtot, int K, int N, int S) {
     extern __shared__ __align__(16) char wg_smem[];
     constexpr int CH = U * CT * 64;                          // 16-byte weight fragments (per lane) of a chunk
     constexpr int ST = CH / 256;                             // staging loads per staging thread and chunk
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, c
 #pragma unroll
         for (int r = 0; r < RW; r++) {
             const int row = (w * RW + r) * 16 + t;
-            voff[r] = row < M ? (row * K + 8 * g) * 2 : (int)0x80000000;
+            voff[r] = row < M ? (4 * t + g) * 16 : (int)0x80000000;
         }
         const bool has_rows = w * RW * 16 < M;               // uniform
         f32x4 acc[RW][CT];
@@ -264,8 +265,9 @@ __global__ __launch_bounds__(512) void k_gemm_rs(const u32x4 *__restrict__ Wp, c
         const bool in_ = ksa_ < ks1; /* uniform; past the slice: an offset beyond the buffer, no branch */ \
         _Pragma("unroll") for (int r = 0; r < RW; r++) {                                          \
             const int vo_ = in_ ? voff[r] : (int)0x80000000;                                      \
-            a[UU][r][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, vo_, in_ ? ksa_ * 64 : 0, 0)); \
-            a[UU][r][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, vo_, in_ ? ksa_ * 64 + lo_off : 0, 0)); \
+            const int so_ = in_ ? (ksa_ * mtp + w * RW + r) * 1024 : 0; /* one stored fragment, see act_tiled_idx */ \
+            a[UU][r][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, vo_, so_, 0)); \
+            a[UU][r][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, vo_, in_ ? so_ + lo_off : 0, 0)); \
         }                                                                                         \
     }
 #define CSD_RS_MMA(BUF, KS_NEXT)                                                                  \
@@ -376,7 +378,7 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const TW *__restrict__ W, c
 template <typename TW, typename TA>
 __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ tokens, const TW *__restrict__ E, int V,
                                                     int d, const float *__restrict__ g, float eps,
-                                                    float *__restrict__ h, TA *__restrict__ a, int lda, size_t plane) {
+                                                    float *__restrict__ h, TA *__restrict__ a, int lda, size_t plane, int mtp) {
     __shared__ float red[16];
     const int r = blockIdx.x;
     const int tok = tokens[r];
@@ -390,7 +392,7 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ 
     ss = block_sum(ss, red);
     const float rs = rsqrtf(ss / (float)d + eps);
     for (int x = threadIdx.x; x < d; x += blockDim.x)
-        store_act<TA>(a, plane, (size_t)r * lda + x, h[(size_t)r * d + x] * rs * g[x]);
+        store_act<TA>(a, plane, r, x, lda, mtp, h[(size_t)r * d + x] * rs * g[x]);
 }
 
 // h[r] += sum_s part[s][r];  a[r] = rmsnorm(h[r]) * g.  One workgroup of 1024 threads per row, four
@@ -401,7 +403,7 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ 
 template <typename TA>
 __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__restrict__ part, int S, int M, int d,
                                                               const float *__restrict__ g, float eps, float *__restrict__ h,
-                                                              TA *__restrict__ a, int lda, size_t plane) {
+                                                              TA *__restrict__ a, int lda, size_t plane, int mtp) {
     __shared__ float red[RN_THREADS / 64];
     const int r = blockIdx.x;
     float ss = 0.f;
@@ -427,7 +429,7 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
             if (x < d) {
                 const f32x4 gv = *reinterpret_cast<const f32x4 *>(g + x);
 #pragma unroll
-                for (int i = 0; i < 4; i++) store_act<TA>(a, plane, (size_t)r * lda + x + i, keep[p][i] * rs * gv[i]);
+                for (int i = 0; i < 4; i++) store_act<TA>(a, plane, r, x + i, lda, mtp, keep[p][i] * rs * gv[i]);
             }
         }
         return;
@@ -442,7 +444,7 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
     ss = block_sum(ss, red);
     const float rs = rsqrtf(ss / (float)d + eps);
     for (int x = threadIdx.x; x < d; x += blockDim.x)
-        store_act<TA>(a, plane, (size_t)r * lda + x, h[(size_t)r * d + x] * rs * g[x]);
+        store_act<TA>(a, plane, r, x, lda, mtp, h[(size_t)r * d + x] * rs * g[x]);
 }
 
 // (cos, sin) of the rotary angle pos * theta^(-2x/dh) of every block row of a call and every pair x < dh/2,
@@ -489,8 +491,8 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
             c = cs.x;
             sn = cs.y;
         }
-        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p0, q0 * c - q1 * sn);
-        store_act<TA>(qout, qplane, (size_t)r * hd + hh * dh + p1, q0 * sn + q1 * c);
+        store_act<TA>(qout, qplane, r, hh * dh + p0, hd, 0, q0 * c - q1 * sn);
+        store_act<TA>(qout, qplane, r, hh * dh + p1, hd, 0, q0 * sn + q1 * c);
         if (pos_ok) {
             kc[(size_t)pos * dh + p0] = from_f32<TC>(k0 * c - k1 * sn);
             kc[(size_t)pos * dh + p1] = from_f32<TC>(k0 * sn + k1 * c);
@@ -504,7 +506,7 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
 // (gate tile j at packed tile 2j, up tile at 2j+1); row-major weights concatenate [gate | up].
 template <typename TA>
 __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, int S, int M, int F, int interleaved,
-                                                TA *__restrict__ f, int ldf, size_t plane, int gelu) {
+                                                TA *__restrict__ f, int ldf, size_t plane, int mtp, int gelu) {
     const int r = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= F) return;
@@ -519,7 +521,7 @@ __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, 
     // gate activation: SiLU, or (arch 1) the tanh form of GELU
     const float sg = gelu ? 0.5f * gsum * (1.0f + tanhf(0.7978845608028654f * (gsum + 0.044715f * gsum * gsum * gsum)))
                           : gsum / (1.0f + expf(-gsum));
-    store_act<TA>(f, plane, (size_t)r * ldf + j, sg * usum);
+    store_act<TA>(f, plane, r, j, ldf, mtp, sg * usum);
 }
 
 __global__ __launch_bounds__(256) void k_fix_logits(const float *__restrict__ part, int S, int M, int V,
@@ -541,7 +543,7 @@ __global__ __launch_bounds__(256) void k_fix_plain(const float *__restrict__ par
     if (j >= N) return;
     float acc = 0.f;
     for (int s = 0; s < S; s++) acc += part[((size_t)s * M + r) * N + j];
-    store_act<TA>(out, plane, (size_t)r * ldo + j, acc);
+    store_act<TA>(out, plane, r, j, ldo, 0, acc);
 }
 
 // arch 1, once per prompt: rows [row0, row0 + M) of the projected encoder output, part[s][r][0..hd) = keys and
@@ -567,10 +569,10 @@ __global__ __launch_bounds__(256) void k_fix_cross_kv(const float *__restrict__ 
 // a[r][x] = src[r][x] as GEMM input rows (two bf16 planes on the MFMA path)
 template <typename TA>
 __global__ __launch_bounds__(256) void k_rows_to_act(const float *__restrict__ src, int M, int d, TA *__restrict__ a, int lda,
-                                                     size_t plane) {
+                                                     size_t plane, int mtp) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)M * d) return;
-    store_act<TA>(a, plane, (idx / d) * lda + idx % d, src[idx]);
+    store_act<TA>(a, plane, (int)(idx / d), (int)(idx % d), lda, mtp, src[idx]);
 }
 
 // Generic causal block attention: one wave per (block row, head).  Scores of the visible cache
@@ -578,7 +580,7 @@ __global__ __launch_bounds__(256) void k_rows_to_act(const float *__restrict__ s
 template <typename TA, typename TC>
 __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, int m, const int32_t *__restrict__ cache_len,
                                                     KvGeom geo, int layer, const TC *__restrict__ kv, float scale,
-                                                    size_t qplane, TA *__restrict__ out, int ldo, size_t plane,
+                                                    size_t qplane, TA *__restrict__ out, int ldo, size_t plane, int mtp,
                                                     AttnMode mode) {
     extern __shared__ float sm[];
     const int r = blockIdx.x, hh = blockIdx.y;
@@ -618,7 +620,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, in
     for (int x = threadIdx.x; x < dh; x += 64) {
         float o = 0.f;
         for (int j = 0; j < nk; j++) o = fmaf(sc[j], to_f32<TC>(vc[kv_v_idx(geo, x, j)]), o);
-        store_act<TA>(out, plane, (size_t)r * ldo + hh * dh + x, o * rz);
+        store_act<TA>(out, plane, r, hh * dh + x, ldo, mtp, o * rz);
     }
 }
 
@@ -665,18 +667,18 @@ ProfScope::~ProfScope() {
 
 #define WG_U_MAX 4      /* k-steps per chunk of the workgroup-tiled GEMMs */
 template <int MT>
-static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int S,
+static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int S,
                                  int groups, hipStream_t st) {
     const size_t lds = (size_t)2 * WG_U_MAX * MT * 2 * 64 * 16;      // allowed at csd_gemm_setup
     hipLaunchKernelGGL((k_gemm_ws<2, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
-                       act, plane, part, M, Mtot, w.K, w.N, S);
+                       act, plane, mtp, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
 }
 
 // Blocks of up to 64 rows (of Mtot in the call): 128 columns per workgroup (wider tiles do not fit the
 // registers next to the staging sets); K is split until there is a workgroup per compute unit.  *S_io: the
 // number of K splits, chosen here when 0 (later row chunks of the same call must use the same).
-static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int *S_io,
+static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int *S_io,
                               hipStream_t st) {
     const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 7) / 8;
     int S = *S_io;
@@ -686,31 +688,31 @@ static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, f
         *S_io = S;
     }
     switch ((M + 15) / 16) {
-    case 1: return launch_gemm_ws_mt<1>(w, act, plane, part, M, Mtot, S, groups, st);
-    case 2: return launch_gemm_ws_mt<2>(w, act, plane, part, M, Mtot, S, groups, st);
-    case 3: return launch_gemm_ws_mt<3>(w, act, plane, part, M, Mtot, S, groups, st);
-    case 4: return launch_gemm_ws_mt<4>(w, act, plane, part, M, Mtot, S, groups, st);
-    case 5: return launch_gemm_ws_mt<5>(w, act, plane, part, M, Mtot, S, groups, st);
-    case 6: return launch_gemm_ws_mt<6>(w, act, plane, part, M, Mtot, S, groups, st);
-    case 7: return launch_gemm_ws_mt<7>(w, act, plane, part, M, Mtot, S, groups, st);
-    case 8: return launch_gemm_ws_mt<8>(w, act, plane, part, M, Mtot, S, groups, st);
+    case 1: return launch_gemm_ws_mt<1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 2: return launch_gemm_ws_mt<2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 3: return launch_gemm_ws_mt<3>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 4: return launch_gemm_ws_mt<4>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 5: return launch_gemm_ws_mt<5>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 6: return launch_gemm_ws_mt<6>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 7: return launch_gemm_ws_mt<7>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 8: return launch_gemm_ws_mt<8>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     default: return CSD_ESHAPE;       // more row tiles do not fit the registers here: such blocks take the row-split form
     }
 }
 
 template <int CT, int RW>
-static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane, float *part, int M, int Mtot, int S,
+static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int S,
                                 int groups, hipStream_t st) {
     const size_t lds = (size_t)2 * WG_U_MAX * CT * 64 * 16;          // allowed at csd_gemm_setup
     hipLaunchKernelGGL((k_gemm_rs<CT, RW, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
-                       act, plane, part, M, Mtot, w.K, w.N, S);
+                       act, plane, mtp, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
 }
 
 // The row-split form: 256 columns per workgroup (128 when every compute wave holds three row tiles).  Its
 // staging waves keep two chunks of weights in flight per workgroup, so half the compute units already
 // saturate HBM: K is split only until there are 128 workgroups, which keeps the partial-sum traffic low.
-static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t *act, size_t plane, float *part, int M,
+static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M,
                               int Mtot, int *S_io, hipStream_t st) {
     const int n_tiles = w.N / 16, KS = w.K / 32, MT = (M + 15) / 16;
     const int rw = (MT + 3) / 4, ct = rw == 3 ? 8 : 16;
@@ -723,9 +725,9 @@ static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t
             S++;
         *S_io = S;
     }
-    if (rw == 1) return launch_gemm_rs_t<16, 1>(w, act, plane, part, M, Mtot, S, groups, st);
-    if (rw == 2) return launch_gemm_rs_t<16, 2>(w, act, plane, part, M, Mtot, S, groups, st);
-    if (rw == 3) return launch_gemm_rs_t<8, 3>(w, act, plane, part, M, Mtot, S, groups, st);
+    if (rw == 1) return launch_gemm_rs_t<16, 1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    if (rw == 2) return launch_gemm_rs_t<16, 2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    if (rw == 3) return launch_gemm_rs_t<8, 3>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     return CSD_ESHAPE;
 }
 
@@ -756,7 +758,7 @@ int32_t csd_gemm_setup() {
     return CSD_OK;
 }
 
-// act: [M][w.K] in the path's activation type; part: [S][M][w.N] with S (<= w.S) returned in *S_used
+// act: M rows of width w.K in the path's activation form; part: [S][M][w.N] with S (<= w.S) returned in *S_used
 static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, int *S_used, hipStream_t st) {
     ProfScope ps(mod, st, CSD_PROF_GEMM);
     *S_used = w.S;
@@ -766,10 +768,11 @@ static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, 
         const int step = M <= 144 ? M : 128;
         for (int row0 = 0; row0 < M; row0 += step) {
             const int rows = M - row0 < step ? M - row0 : step;
-            const bf16_t *a = (const bf16_t *)act + (size_t)row0 * w.K;
+            const bf16_t *a = (const bf16_t *)act + (size_t)(row0 / 16) * 512;   // row tile row0 / 16 of every k-step
             float *p = mod->part + (size_t)row0 * w.N;
-            const int32_t rc = rows >= mod->gemm_rs_min_rows ? launch_gemm_rs(mod, w, a, mod->act_plane, p, rows, M, S_used, st)
-                                                             : launch_gemm_ws(w, a, mod->act_plane, p, rows, M, S_used, st);
+            const int32_t rc = rows >= mod->gemm_rs_min_rows
+                                   ? launch_gemm_rs(mod, w, a, mod->act_plane, mod->act_mtp, p, rows, M, S_used, st)
+                                   : launch_gemm_ws(w, a, mod->act_plane, mod->act_mtp, p, rows, M, S_used, st);
             if (rc != CSD_OK) return rc;
         }
     } else if (mod->cfg.dtype == CSD_DTYPE_BF16) {
@@ -801,7 +804,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
-                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane);
+                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
         CSD_LAUNCH_CHECK();
     }
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
@@ -826,21 +829,21 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
             ProfScope ps(mod, st, CSD_PROF_ATTN);
             const size_t lds = sizeof(float) * (size_t)(c.head_dim + mod->seq_pad);
             hipLaunchKernelGGL((k_attn_simple<TA, TC>), dim3(M, c.n_heads), dim3(64), lds, st, qb, m, cache_len, geo, l,
-                               (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane, AttnMode{});
+                               (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane, mod->act_mtp, AttnMode{});
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.o, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, lw.ffn_norm,
-                               c.rms_eps, mod->h, act, d, mod->act_plane);
+                               c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.gu, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, F,
-                               mod->mfma ? 1 : 0, act, F, mod->act_plane, 0);
+                               mod->mfma ? 1 : 0, act, F, mod->act_plane, mod->act_mtp, 0);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.down, act, M, &S_g, st)) != CSD_OK) return rc;
@@ -848,7 +851,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             const float *g = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
             hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, g,
-                               c.rms_eps, mod->h, act, d, mod->act_plane);
+                               c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
             CSD_LAUNCH_CHECK();
         }
         if (mod->trace)
@@ -877,7 +880,7 @@ static int32_t attention_any(csd_model *mod, const KvGeom &geo, const void *kvba
     const size_t lds = sizeof(float) * (size_t)(mod->cfg.head_dim + geo.seq_pad);
     hipLaunchKernelGGL((k_attn_simple<TA, TC>), dim3(B * m, mod->cfg.n_heads), dim3(64), lds, st, (const TA *)mod->qbuf, m,
                        cache_len, geo, layer, (const TC *)kvbase, scale, mod->q_plane, (TA *)mod->act, mod->hd, mod->act_plane,
-                       mode);
+                       mod->act_mtp, mode);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }
@@ -903,14 +906,14 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
     auto resid_norm = [&](const GemmW &, const float *gain) -> int32_t {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, gain, c.rms_eps, mod->h, act,
-                           d, mod->act_plane);
+                           d, mod->act_plane, mod->act_mtp);
         CSD_LAUNCH_CHECK();
         return CSD_OK;
     };
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
-                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane);
+                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
         CSD_LAUNCH_CHECK();
     }
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
@@ -940,7 +943,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, F,
-                               mod->mfma ? 1 : 0, act, F, mod->act_plane, 1);
+                               mod->mfma ? 1 : 0, act, F, mod->act_plane, mod->act_mtp, 1);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.down, act, M, &S_g, st)) != CSD_OK) return rc;
@@ -975,7 +978,7 @@ static int32_t cross_init_typed(csd_model *mod, void *kv, const float *enc_out, 
                 ProfScope ps(mod, st, CSD_PROF_OTHER);
                 const size_t total = (size_t)rows * d;
                 hipLaunchKernelGGL((k_rows_to_act<TA>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                                   enc_out + ((size_t)b * E + row0) * d, rows, d, (TA *)mod->act, d, mod->act_plane);
+                                   enc_out + ((size_t)b * E + row0) * d, rows, d, (TA *)mod->act, d, mod->act_plane, mod->act_mtp);
                 CSD_LAUNCH_CHECK();
             }
             for (int l = 0; l < c.n_layers; l++) {

@@ -40,9 +40,25 @@ template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return
 // lo = bf16(v - hi): the pair carries ~16 significant bits, and the matrix cores multiply the
 // exact bf16 weights by both planes.  This keeps the forward within the logit tolerance of an
 // exact-arithmetic reference at no cost in HBM traffic (the path is bandwidth-bound).
-template <typename TA> __device__ __forceinline__ void store_act(TA *p, size_t plane, size_t idx, float v);
-template <> __device__ __forceinline__ void store_act<float>(float *p, size_t, size_t idx, float v) { p[idx] = v; }
-template <> __device__ __forceinline__ void store_act<bf16_t>(bf16_t *p, size_t plane, size_t idx, float v) {
+//
+// The bf16 planes that feed the GEMMs are kept fragment by fragment, [k-step][row tile][16 rows][32 columns]
+// with `mtp` row tiles per k-step (the padded row capacity / 16, the same for every row width): the matrix
+// operand of (row tile, k-step) is then 1 KB of consecutive memory, eight full cache lines per load instead
+// of sixteen half-used ones 2 * K bytes apart; lane (t, g) of the operand reads the 16 bytes at (4 t + g) * 16
+// of it, and a writer of one row still stores 64 consecutive bytes per k-step.  mtp = 0: plain row-major
+// [row][ld] (the queries handed to the attention kernels).  fp32 inputs are row-major.
+__device__ __forceinline__ size_t act_tiled_idx(int row, int col, int mtp) {
+    return (((size_t)(col >> 5) * mtp + (row >> 4)) << 9) + ((row & 15) << 5) + (col & 31);
+}
+template <typename TA>
+__device__ __forceinline__ void store_act(TA *p, size_t plane, int row, int col, int ld, int mtp, float v);
+template <>
+__device__ __forceinline__ void store_act<float>(float *p, size_t, int row, int col, int ld, int, float v) {
+    p[(size_t)row * ld + col] = v;
+}
+template <>
+__device__ __forceinline__ void store_act<bf16_t>(bf16_t *p, size_t plane, int row, int col, int ld, int mtp, float v) {
+    const size_t idx = mtp > 0 ? act_tiled_idx(row, col, mtp) : (size_t)row * ld + col;
     const bf16_t hi = f32_to_bf16(v);
     p[idx] = hi;
     p[idx + plane] = f32_to_bf16(v - bf16_to_f32(hi));
@@ -174,8 +190,10 @@ struct csd_model {
     std::vector<LayerW> layers;
     // scratch (device)
     float *h = nullptr;          // residual stream [m_max][d] fp32
-    void *act = nullptr;         // GEMM input rows [m_pad][max(d, F, hd)]: fp32, or two bf16 planes (hi, lo) on the MFMA path
-    void *qbuf = nullptr;        // rotated queries [m_pad][hd], same representation as act
+    void *act = nullptr;         // GEMM input rows [m_pad][max(d, F, hd)]: fp32 row-major, or two bf16 planes (hi, lo) stored
+                                 // fragment by fragment on the MFMA path (act_tiled_idx)
+    int act_mtp = 0;             // row tiles per k-step of that order (m_pad / 16); 0 on the fp32 paths
+    void *qbuf = nullptr;        // rotated queries [m_pad][hd] row-major: fp32, or two bf16 planes
     size_t act_plane = 0;        // elements between the hi and lo planes of act
     size_t q_plane = 0;          // ... and of qbuf
     float *part = nullptr;       // split-K partial sums [s_max][m_max][n_max]
