@@ -177,6 +177,10 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     gpu_ms_per_step = e0.elapsed_time(e1) / args.steps
     emitted = float((n_acc + 1).sum().item())
+    if model.error_flag() != 0:
+        # the single-launch kernel's device-wide barrier has a bounded wait; once it gives up, later launches
+        # run without synchronisation and their results and times mean nothing
+        raise SystemExit("bench.py: a device-wide barrier of the single-launch kernel gave up waiting; no valid measurement")
 
     # ---- per-kernel timing with HIP events on the launch stream (separate loop: the events perturb the step)
     model.prof_enable(True)

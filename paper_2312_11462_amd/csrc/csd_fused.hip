@@ -196,14 +196,20 @@ __device__ __forceinline__ void stores_acked_sync() {
 
 // ------------------------------------------------------------------------------ grid barrier
 
-// Flag barrier without read-modify-write atomics: workgroup w stores the number of the barrier it has
-// reached into its one-byte flag, and the service wave of every workgroup polls all flags with one
+// Flag barrier without read-modify-write atomics: workgroup w records the barrier it has reached in its
+// one-byte flag, and the service wave of every workgroup polls all flags with one
 // 4-byte load per lane (4 flags each, up to 256 workgroups).  Polling is what loads the memory
 // channel that holds the flags, and the weight stream needs every channel, so the flags exist in
 // BAR_REPLICAS copies on different channels: an arriving workgroup writes all copies (one store
 // instruction, one lane per copy) and polls only copy (workgroup index mod BAR_REPLICAS).
-// Barrier numbers only grow (the host passes the number completed by earlier launches) and two
-// workgroups are never more than one barrier apart, so the comparison is done modulo 256.
+// Barrier numbers only grow (the host passes the number completed by earlier launches).  While a
+// workgroup waits for barrier e, another can be one barrier behind (not arrived: e - 1) or one ahead (it
+// saw everyone arrive, had no work in the next phase and has already arrived at e + 1), never more.  A
+// flag therefore holds its barrier number modulo 4 as one of four bits, 1 << (e % 4), and "everyone has
+// arrived at e" is "no flag has the bit of e - 1", a test on the OR of all flags that a faster
+// workgroup's next arrival cannot invalidate.  (Waiting for every flag to equal e would miss that
+// state for good once a flag has moved on to e + 1.)  Flags of workgroups that do not exist stay 0; the
+// flags of those that do start at the bit of barrier 0.
 // The wait is bounded: when it gives up it raises the error flag, which also releases every later
 // wait, so each wave still exits.
 // No cache maintenance is needed here: everything read after a barrier lives in a buffer instance that
@@ -225,7 +231,7 @@ __device__ __forceinline__ void grid_arrive(CParams &P, unsigned epoch, bool ser
     }
     if (threadIdx.x < BAR_REPLICAS) {
         const __amdgpu_buffer_rsrc_t rb = co_rsrc(P.bar, BAR_BYTES);
-        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)epoch, rb, (int)(threadIdx.x * BAR_REPLICA_STRIDE + blockIdx.x), 0,
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(1u << (epoch & 3u)), rb, (int)(threadIdx.x * BAR_REPLICA_STRIDE + blockIdx.x), 0,
                                              CSD_SC1);
     }
 }
@@ -234,18 +240,17 @@ __device__ __forceinline__ void grid_arrive(CParams &P, unsigned epoch, bool ser
 // phase's weights); the closing workgroup barrier orders LDS only, so those loads stay in flight.
 typedef unsigned u32x16 __attribute__((ext_vector_type(16)));
 
-// Are all flags of replica `fp` (64 dwords of 4 one-byte flags) equal to `pat` in their first n_dw dwords?
+// Does no flag of replica `fp` (64 dwords of 4 one-byte flags) have a bit of `pat_prev` set?
 // Read with scalar loads that bypass the scalar cache (glc): they do not go through the vector memory
 // pipeline, so they never queue behind the weight prefetch the compute unit has in flight.  The flag
 // memory is allocated uncached, so the loads reach memory whichever L2 serves them.
-__device__ __forceinline__ bool flags_all_equal_scalar(const unsigned char *fp_any, unsigned pat, int n_dw) {
+__device__ __forceinline__ bool flags_clear_scalar(const unsigned char *fp_any, unsigned pat_prev) {
     // the address is the same in every lane, but the compiler may hold it in vector registers
     const unsigned long long a64 = (unsigned long long)fp_any;
     const unsigned lo32 = __builtin_amdgcn_readfirstlane((unsigned)a64);
     const unsigned hi32 = __builtin_amdgcn_readfirstlane((unsigned)(a64 >> 32));
     const unsigned char *fp = reinterpret_cast<const unsigned char *>(((unsigned long long)hi32 << 32) | lo32);
-    pat = __builtin_amdgcn_readfirstlane(pat);
-    n_dw = __builtin_amdgcn_readfirstlane(n_dw);
+    pat_prev = __builtin_amdgcn_readfirstlane(pat_prev);
     u32x16 a, b, c, d;
     asm volatile("s_load_dwordx16 %0, %4, 0x0 glc\n\t"
                  "s_load_dwordx16 %1, %4, 0x40 glc\n\t"
@@ -255,38 +260,29 @@ __device__ __forceinline__ bool flags_all_equal_scalar(const unsigned char *fp_a
                  : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d)
                  : "s"(fp)
                  : "memory");
-    unsigned diff = 0;
+    const u32x16 o = (a | b) | (c | d);
+    unsigned any = 0;
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-        diff |= (i < n_dw ? a[i] ^ pat : 0u) | (16 + i < n_dw ? b[i] ^ pat : 0u) | (32 + i < n_dw ? c[i] ^ pat : 0u) |
-                (48 + i < n_dw ? d[i] ^ pat : 0u);
-    }
-    return diff == 0u;
+    for (int i = 0; i < 16; i++) any |= o[i];
+    return (any & pat_prev) == 0u;
 }
 
 __device__ __forceinline__ void grid_wait(CParams &P, unsigned epoch) {
     if (threadIdx.x < 64) {
         const int lane = threadIdx.x;
         const __amdgpu_buffer_rsrc_t rb = co_rsrc(P.bar, BAR_BYTES);
-        const int G = gridDim.x;
         const int rep = (int)((blockIdx.x % BAR_REPLICAS) * BAR_REPLICA_STRIDE);
         const int off = rep + lane * 4;
-        // scalar polling needs whole dwords of flags; a workgroup is never more than one barrier ahead of
-        // another, so "every flag has reached the barrier" is "every flag equals its number"
-        const bool scalar = P.bar_scalar && G % 4 == 0;
-        const unsigned pat = (epoch & 0xFFu) * 0x01010101u;
+        const bool scalar = P.bar_scalar != 0;
+        const unsigned pat_prev = (1u << ((epoch - 1u) & 3u)) * 0x01010101u;
         unsigned spins = 0;
         bool give_up = __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
         while (!give_up) {
             if (scalar) {
-                if (flags_all_equal_scalar(P.bar + rep, pat, G / 4)) break;
+                if (flags_clear_scalar(P.bar + rep, pat_prev)) break;
             } else {
                 const unsigned f = __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, CSD_SC1);
-                bool ok = true;
-#pragma unroll
-                for (int i = 0; i < 4; i++)
-                    ok = ok && (4 * lane + i >= G || (signed char)(unsigned char)(((f >> (8 * i)) & 0xFFu) - (epoch & 0xFFu)) >= 0);
-                if (__all(ok)) break;
+                if (__all((f & pat_prev) == 0u)) break;
             }
             ++spins;
             if ((spins & 1023u) == 0u && __hip_atomic_load(P.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
@@ -1271,6 +1267,8 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
         if ((rc = flag_buffer_acquire((void **)&fs->bar, st)) != CSD_OK) return rc;
         fs->bar_scalar = 1;
     }
+    // the flags of the workgroups that exist start at the bit of barrier 0, all others stay 0
+    for (int r = 0; r < BAR_REPLICAS; r++) CSD_HIP(hipMemsetAsync(fs->bar + (size_t)r * BAR_REPLICA_STRIDE, 0x01, fs->grid, st));
     if ((rc = fused_alloc(mod, (void **)&fs->err, 256, true, st)) != CSD_OK) return rc;
     // attention partials: [Bmax][H][kg_max][16][dh+4]; reuse the model's buffer when large enough
     const size_t need = sizeof(float) * (size_t)c.max_batch * c.n_heads * fs->kg_max * 16 * (dh + 4);

@@ -114,6 +114,30 @@ def test_bf16_paths_small_model(shape, gemm, attn, path):
     print(shape.name, gemm, attn, path, "max err", e1, e2)
 
 
+def test_single_launch_kernel_many_calls_on_a_small_model_barrier_never_gives_up():
+    """Regression test of the device-wide barrier's poll: on a small model most workgroups have no work in
+    a phase and run from one barrier straight to the next, so a slower workgroup may poll only after a
+    faster one has already stored the next barrier's number.  400 back-to-back calls: the bounded wait
+    never gives up (the error flag stays 0), every call returns the first call's logits, and those match
+    the oracle."""
+    os.environ["CSD_PATH"] = "persistent"
+    try:
+        gm, om = make_pair(BF, 11, 1, 128, 8, std=0.05)
+    finally:
+        del os.environ["CSD_PATH"]
+    assert gm.path(1, 5) == 2
+    toks = I.token_ids(64, BF.vocab, 11, 1).reshape(1, 64)
+    prefill_both(gm, om, toks[:, :40], 8)
+    _check_block(gm, om, toks[:, 40:45].numpy(), [40], 2e-2, 1e-2, "first call")
+    block, clen = _dev(toks[:, 40:45].numpy()), _dev([40])
+    first = gm.verify_block(block, clen).clone()
+    worst = 0.0
+    for _ in range(400):
+        worst = max(worst, float((gm.verify_block(block, clen) - first).abs().max()))
+    assert gm.error_flag() == 0
+    assert worst <= 1e-5, f"a later call differs from the first by {worst}"
+
+
 @pytest.mark.parametrize("path", ["phases", "persistent"])
 def test_bf16_single_launch_variant_with_activations_from_l2(path):
     """The opt-in variant of the single-launch kernel that reads the activation fragments from L2 (for
