@@ -7,6 +7,8 @@ whole.  Both are checked on the GPU's own outputs (cascade vs plain decoding wit
 and the fp32 configuration also against the CPU oracle's cascade driver."""
 import itertools
 
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -81,8 +83,12 @@ def test_greedy_cascade_bf16_on_the_single_launch_kernel():
     from paper_2312_11462_amd.cascade import Cascade, autoregressive
     prompt = _prompt(1024, 31)
     table = _table(prompt, 1024)
-    target, draft = _gpu_level(TARGET_BF, 5, 0.05), _gpu_level(DRAFT_BF, 6, 0.05)
-    assert target.model.path(1, 9) == 2
+    os.environ["CSD_PATH"] = "persistent"      # models this small take the multi-kernel path unless asked
+    try:
+        target, draft = _gpu_level(TARGET_BF, 5, 0.05), _gpu_level(DRAFT_BF, 6, 0.05)
+    finally:
+        del os.environ["CSD_PATH"]
+    assert target.model.path(1, 9) == 2 and draft.model.path(1, 7) == 2
     want = autoregressive(target, prompt, 32, MAX_CTX)
     got, steps = Cascade([target, draft], table, [[2, 6], [0, 6]], MAX_CTX, lenience=2.0, mode=1).generate(prompt, 32)
     # block shape changes the summation order inside the kernels; an arg-max tie within rounding could
