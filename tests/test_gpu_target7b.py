@@ -93,6 +93,14 @@ def test_target7b_batch1_prefix1024_k5(big):
         top2 = np.sort(ref[0, i])[-2:]
         if top2[1] - top2[0] > 2 * (1e-2 + 2e-2 * abs(top2[1])):
             assert gam[i] == int(np.argmax(ref[0, i]))
+    # the single-launch kernel again, 30 calls in a row: same logits every time, no barrier gave up
+    assert gm.path(1, k + 1) == 2
+    cl, first = torch.tensor([t], dtype=torch.int32).cuda(), lg.clone()
+    worst = 0.0
+    for _ in range(30):
+        worst = max(worst, float((gm.verify_block(block.cuda(), cl) - first).abs().max()))
+    assert worst <= 1e-5, f"a repeated call differs by {worst}"
+    assert gm.error_flag() == 0
 
 
 @pytest.mark.parametrize("k,oracle_b", [(1, 5), (4, 3), (16, 6)])
