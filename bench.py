@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--k", type=int, default=None, help="drafts per sequence instead of the workload's (configuration 5 sweeps it)")
     ap.add_argument("--prof-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cascade-steps", type=int, default=20, metavar="N",
+                    help="workload target7b: also time N whole two-level cascade steps of configuration 3 "
+                         "(the 160M-shaped draft level's reviews + the timed step); 0 = skip")
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy"])
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the benchmark, launch N plain 1 GiB copies (kernel k_copy_calib) so that a "
@@ -223,6 +226,51 @@ def main():
     if TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, path)):
         roofline["traffic"] = TRAFFIC_BYTES_PER_LAUNCH[(args.workload, path)]
 
+    # ---- configuration 3 as a whole (extra, timed apart from `value`): the two tokens that stand in for the
+    # neural draft level are each the outcome of one review by the 160M-shaped draft model of a block of
+    # Max-Gram drafts (vertical cascade), then the target reviews its block (the step timed above)
+    cascade = None
+    if args.workload == "target7b" and args.cascade_steps > 0:
+        dwl = I.WORKLOADS["draft160m"]
+        dshape, dseed, dk = dwl["shape"], dwl["seed"], dwl["k"]
+        dw = I.make_weights(dshape, dseed, device="cuda")
+        draft = P.Model(dshape, dw, max_batch=1, max_seq=t + 64, max_block=dk + 1)
+        del dw
+        for l in range(dshape.n_layers):
+            K, V = I.synthetic_kv(dshape, t, dseed, l, 0, device="cuda")
+            draft.kv_write(l, 0, 0, K, V)
+        dblock = torch.zeros((1, dk + 1), dtype=torch.int32, device="cuda")
+        du_acc = I.uniforms(dk, dseed, 7).reshape(1, dk).contiguous().cuda()
+        du_s = I.uniforms(1, dseed, 8).cuda()
+        done = torch.ones(dk, dtype=torch.uint8, device="cuda")
+        dn, dx = torch.zeros(1, dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda")
+        dlen = [torch.full((1,), t + 1 + j, dtype=torch.int32, device="cuda") for j in range(n_from_draft_model)]
+        dcl = [torch.full((1,), t + j, dtype=torch.int32, device="cuda") for j in range(n_from_draft_model)]
+
+        def cascade_step():
+            for j in range(n_from_draft_model):
+                dblock[:, :1] = ctx[:, t + j:t + j + 1]
+                P.bigram_draft(ctx, dlen[j], table, dk, want_match_len=False, out=dblock[:, 1:])
+                draft.verify_accept(dblock, dcl[j], du_acc, du_s, q=None, q_onehot=done, mode=mode, n_accepted=dn, next_token=dx)
+            step()
+
+        for _ in range(3):
+            cascade_step()
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(args.cascade_steps):
+            cascade_step()
+        c1.record()
+        torch.cuda.synchronize()
+        if draft.error_flag() != 0 or model.error_flag() != 0:
+            raise SystemExit("bench.py: a device-wide barrier gave up waiting during the cascade step")
+        cascade = {"ms": round(c0.elapsed_time(c1) / args.cascade_steps, 4), "steps": args.cascade_steps,
+                   "what": f"{n_from_draft_model} x (Max-Gram drafts {dk} tokens, the {dshape.name} model reviews the "
+                           f"{dk + 1}-row block and accepts) + the timed step; no host synchronisation inside"}
+        del draft
+        torch.cuda.empty_cache()
+
     if args.copy_calibration > 0:
         src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -288,6 +336,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if cascade is not None:
+        out["cascade_step"] = cascade
     print(json.dumps(out))
 
 
