@@ -120,3 +120,68 @@ def test_sampling_cascade_is_reproducible_and_emits_valid_tokens():
         outs.append(got)
     assert outs[0] == outs[1]
     assert all(0 <= t < 512 for t in outs[0])
+
+
+class _FixedGpuLevel:
+    """A level whose next-token distribution does not depend on the context (same interface as Level): its
+    logits and fp32 probabilities are inputs, identical on both sides, so the GPU driver and the oracle
+    driver must then agree token for token in sampling mode (csd_accept is bit-exact on equal inputs)."""
+
+    class _M:
+        def __init__(self, vocab):
+            self.shape = I.ModelShape("fixed", 0, "fp32", 1, 16, 1, 16, 16, vocab)
+
+        def error_flag(self):
+            return 0
+
+    def __init__(self, logits, probs):
+        self.lg = torch.tensor(logits, dtype=torch.float32).cuda()
+        self.pr = torch.tensor(probs, dtype=torch.float32).cuda()
+        self.model = self._M(len(probs))
+        self.cached = 0
+
+    def rows_from(self, ctx, n_tokens, first_row, want_probs=False, temperature=1.0):
+        n = n_tokens - first_row
+        return self.lg.repeat(n, 1), (self.pr.repeat(n, 1) if want_probs else None)
+
+
+class _FixedOracleLevel:
+    def __init__(self, logits):
+        self.logits = np.asarray(logits, np.float64)
+        self.cached = 0
+
+    def rows_from(self, seq, first_row):
+        return np.tile(self.logits, (len(seq) - first_row, 1))
+
+
+def _u24(seed):
+    rs = np.random.RandomState(seed)
+    while True:
+        for u in rs.randint(0, 1 << 24, size=4096):
+            yield float(u) / float(1 << 24)
+
+
+@pytest.mark.parametrize("K,lenience", [
+    ([[3, 2, 0], [0, 0, 0], [0, 0, 0]], 1.0),        # horizontal: 3 tokens of level 1, 2 of level 2
+    ([[4, 0, 0], [0, 3, 0], [0, 0, 0]], 1.0),        # vertical: level 1 reviews level 2's drafts
+    ([[2, 1, 3], [0, 2, 2], [0, 0, 2]], 2.5),        # both, with Max-Gram drafts and lenience between draft levels
+])
+def test_sampling_cascade_matches_the_oracle_driver_token_for_token(K, lenience):
+    from paper_2312_11462_amd.cascade import Cascade
+    from oracle import csd_oracle as O
+    from oracle import cascade as OC
+    V, n_new = 37, 1500
+    rs = np.random.RandomState(5)
+    logits = [np.log(rs.dirichlet(np.full(V, a))) for a in (0.6, 0.8, 2.0)]
+    probs = [O.probs_f32(lg[None])[0] for lg in logits]
+    logits32 = [np.asarray(lg, np.float32) for lg in logits]
+    prompt = _prompt(V, 3)
+    table = _table(prompt, V)
+    glevels = [_FixedGpuLevel(lg, pr) for lg, pr in zip(logits32, probs)]
+    got, steps = Cascade(glevels, table, K, n_new + 64, lenience=lenience, mode=0).generate(prompt, n_new, _u24(17))
+    olevels = [_FixedOracleLevel(lg.astype(np.float64)) for lg in logits32]
+    otable = O.bigram_fit(np.array(prompt, np.int32), V, I.default_next_table(V, 1).numpy())
+    assert np.array_equal(otable, table.cpu().numpy())
+    ogot, osteps = OC.cascade_generate(olevels, otable, prompt, n_new, K, lenience=lenience, mode=0, uniforms=_u24(17))
+    assert steps == osteps
+    assert got == ogot
