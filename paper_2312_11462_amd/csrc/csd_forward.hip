@@ -666,21 +666,24 @@ ProfScope::~ProfScope() {
 }
 
 #define WG_U_MAX 4      /* k-steps per chunk of the workgroup-tiled GEMMs */
-template <int MT>
+template <int MT, int NT = 2>
 static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int S,
                                  int groups, hipStream_t st) {
     const size_t lds = (size_t)2 * WG_U_MAX * MT * 2 * 64 * 16;      // allowed at csd_gemm_setup
-    hipLaunchKernelGGL((k_gemm_ws<2, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
+    hipLaunchKernelGGL((k_gemm_ws<NT, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
                        act, plane, mtp, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
 }
 
-// Blocks of up to 64 rows (of Mtot in the call): 128 columns per workgroup (wider tiles do not fit the
-// registers next to the staging sets); K is split until there is a workgroup per compute unit.  *S_io: the
+// Blocks of up to 64 rows (of Mtot in the call): 128 columns per workgroup (256 at two row tiles; elsewhere
+// wider tiles do not fit the registers); K is split until there is a workgroup per compute unit.  *S_io: the
 // number of K splits, chosen here when 0 (later row chunks of the same call must use the same).
 static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int *S_io,
                               hipStream_t st) {
-    const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 7) / 8;
+    // two row tiles: four column tiles per wave still fit the registers (256 columns per workgroup, twice
+    // the weights in flight per compute unit); with more row tiles they spill
+    const int NT = (M + 15) / 16 == 2 ? 4 : 2;
+    const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 4 * NT - 1) / (4 * NT);
     int S = *S_io;
     if (S == 0) {
         S = 1;
@@ -689,7 +692,7 @@ static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, i
     }
     switch ((M + 15) / 16) {
     case 1: return launch_gemm_ws_mt<1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 2: return launch_gemm_ws_mt<2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 2: return NT == 4 ? launch_gemm_ws_mt<2, 4>(w, act, plane, mtp, part, M, Mtot, S, groups, st) : launch_gemm_ws_mt<2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     case 3: return launch_gemm_ws_mt<3>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     case 4: return launch_gemm_ws_mt<4>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     case 5: return launch_gemm_ws_mt<5>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
@@ -733,9 +736,9 @@ static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t
 
 // Once per process and device, at model creation (no runtime call besides launches happens later): allow
 // every GEMM instantiation its dynamic LDS (up to 144 KB).
-template <int MT>
+template <int MT, int NT = 2>
 static hipError_t ws_allow_lds() {
-    return hipFuncSetAttribute((const void *)k_gemm_ws<2, MT, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    return hipFuncSetAttribute((const void *)k_gemm_ws<NT, MT, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                2 * WG_U_MAX * MT * 2 * 64 * 16);
 }
 template <int CT, int RW>
@@ -752,6 +755,7 @@ int32_t csd_gemm_setup() {
     CSD_HIP(ws_allow_lds<6>());
     CSD_HIP(ws_allow_lds<7>());
     CSD_HIP(ws_allow_lds<8>());
+    CSD_HIP((ws_allow_lds<2, 4>()));
     CSD_HIP((rs_allow_lds<16, 1>()));
     CSD_HIP((rs_allow_lds<16, 2>()));
     CSD_HIP((rs_allow_lds<8, 3>()));
