@@ -67,9 +67,17 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
         // A operands of PRE tiles.  K: A-row r of tile T is key kb + 8*(r/4) + 4*T + r%4, so lane group g ends up
         // with the scores of keys kb+8g..kb+8g+7; V^T: row = feature dt*16 + col, 8 consecutive keys per lane.
         u32x4 kf[PRE][2][DH / 32], vfr[PRE][DH / 16];
+        float bias[PRE][8];                                  // relative-position bias of this lane's 8 keys per tile
 #pragma unroll
         for (int p = 0; p < PRE; p++) {
             const int kb = key0 + (sub0 + p) * 32;
+#pragma unroll
+            for (int j = 0; j < 8; j++) bias[p][j] = 0.f;
+            if (mode.bias_hd && kb < nk && sub0 + p < chunk_keys / 32) {     // uniform; fetched with the tile, ahead of its scores
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    bias[p][j] = mode.bias_hd[hh * 128 + min(max(qpos - (kb + 8 * g + j), 0), 127)];
+            }
             if (kb < nk && sub0 + p < chunk_keys / 32) {     // uniform
 #pragma unroll
                 for (int T = 0; T < 2; T++) {
@@ -113,7 +121,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
                 const int key = kb + 8 * g + j;
                 float s = sT[j >> 2][j & 3] * scale;
                 const bool seen = (!causal || key <= qpos) && key < nk;
-                if (mode.rel_bias && seen) s += mode.rel_bias[mode.bucket[min(qpos - key, 127)] * geo.H + hh];
+                s += bias[p][j];                             // 0 without a bias table; unseen keys are masked next
                 sv[j] = seen ? s : -INFINITY;
                 mx = fmaxf(mx, sv[j]);
             }

@@ -447,6 +447,12 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
         store_act<TA>(a, plane, r, x, lda, mtp, h[(size_t)r * d + x] * rs * g[x]);
 }
 
+// bias_hd[h][n] = rel_bias[bucket[n]][h]: the relative-position bias of head h at look-back distance n
+__global__ void k_bias_table(const float *__restrict__ rel_bias, const int32_t *__restrict__ bucket, int H,
+                             float *__restrict__ bias_hd) {
+    bias_hd[blockIdx.x * 128 + threadIdx.x] = rel_bias[bucket[threadIdx.x] * H + blockIdx.x];
+}
+
 // (cos, sin) of the rotary angle pos * theta^(-2x/dh) of every block row of a call and every pair x < dh/2,
 // evaluated in double precision once per call instead of once per layer and head.
 __global__ void k_rope_table(const int32_t *__restrict__ cache_len, int m, int dh, float theta, float2 *__restrict__ tab) {
@@ -904,6 +910,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
     AttnMode self_mode, cross_mode;
     self_mode.rel_bias = mod->rel_bias;
     self_mode.bucket = mod->rel_bucket;
+    self_mode.bias_hd = mod->rel_bias_hd;
     cross_mode.fixed_nk = c.enc_len;
     int32_t rc;
     int S_g = 1;            // K splits the last GEMM wrote partial sums for
@@ -1147,6 +1154,9 @@ int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st) {
         tab[127] = 31;
         if ((rc = dev_alloc(mod, (void **)&mod->rel_bucket, sizeof(tab))) != CSD_OK) return rc;
         CSD_HIP(hipMemcpy(mod->rel_bucket, tab, sizeof(tab), hipMemcpyHostToDevice));
+        if ((rc = dev_alloc(mod, (void **)&mod->rel_bias_hd, sizeof(float) * 128 * c.n_heads)) != CSD_OK) return rc;
+        hipLaunchKernelGGL(k_bias_table, dim3(c.n_heads), dim3(128), 0, st, mod->rel_bias, mod->rel_bucket, c.n_heads, mod->rel_bias_hd);
+        CSD_LAUNCH_CHECK();
         return CSD_OK;
     }
     for (int l = 0; l < L; l++) {

@@ -166,10 +166,13 @@ struct LayerW {
 // with t cached rows sees rows 0 .. t+i).  fixed_nk > 0: every row sees rows 0 .. fixed_nk-1 (cross-
 // attention).  rel_bias != null: add rel_bias[bucket[min(query pos - key pos, 127)] * H + head] to the
 // scaled score (T5-style relative-position bias; bucket is a 128-entry table, farther keys share entry 127).
+// bias_hd: the same values per head and distance, bias_hd[head * 128 + distance], for the kernels that
+// fetch them ahead of the scores (one load instead of two dependent ones).
 struct AttnMode {
     int fixed_nk = 0;
     const float *rel_bias = nullptr;
     const int32_t *bucket = nullptr;
+    const float *bias_hd = nullptr;
 };
 
 enum { CSD_PROF_GEMM = 0, CSD_PROF_ATTN = 1, CSD_PROF_OTHER = 2, CSD_PROF_CLASSES = 3 };
@@ -206,6 +209,7 @@ struct csd_model {
     int enc_pad = 0;                 // encoder rows padded to 64
     float *rel_bias = nullptr;       // [32][H] fp32
     int32_t *rel_bucket = nullptr;   // [128] bucket of distance n (n >= 127 shares the last entry)
+    float *rel_bias_hd = nullptr;    // [H][128]: rel_bias[rel_bucket[n]][h]
     float *trace = nullptr;
     void *fused = nullptr;           // state of the single-launch path (csd_fused.hip), or null
     float *fused_attn_part = nullptr;
