@@ -408,12 +408,13 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
     const int r = blockIdx.x;
     float ss = 0.f;
     if (d % 4 == 0 && d <= RN_THREADS * 4 * RN_PASSES) {
-        f32x4 keep[RN_PASSES];
+        f32x4 keep[RN_PASSES], gain[RN_PASSES];              // the gains are fetched with the sums, not after the reduction
 #pragma unroll
         for (int p = 0; p < RN_PASSES; p++) {
             const int x = (p * RN_THREADS + (int)threadIdx.x) * 4;
-            keep[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            keep[p] = gain[p] = f32x4{0.f, 0.f, 0.f, 0.f};
             if (x < d) {
+                gain[p] = *reinterpret_cast<const f32x4 *>(g + x);
                 f32x4 v = *reinterpret_cast<const f32x4 *>(h + (size_t)r * d + x);
                 for (int s = 0; s < S; s++) v += *reinterpret_cast<const f32x4 *>(part + ((size_t)s * M + r) * d + x);
                 *reinterpret_cast<f32x4 *>(h + (size_t)r * d + x) = v;
@@ -427,9 +428,7 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
         for (int p = 0; p < RN_PASSES; p++) {
             const int x = (p * RN_THREADS + (int)threadIdx.x) * 4;
             if (x < d) {
-                const f32x4 gv = *reinterpret_cast<const f32x4 *>(g + x);
-#pragma unroll
-                for (int i = 0; i < 4; i++) store_act<TA>(a, plane, r, x + i, lda, mtp, keep[p][i] * rs * gv[i]);
+                store_act4<TA>(a, plane, r, x, lda, mtp, keep[p] * rs * gain[p]);
             }
         }
         return;

@@ -64,6 +64,27 @@ __device__ __forceinline__ void store_act<bf16_t>(bf16_t *p, size_t plane, int r
     p[idx + plane] = f32_to_bf16(v - bf16_to_f32(hi));
 }
 
+// Four consecutive columns (col a multiple of 4: they share a 32-column block) in one store per plane.
+template <typename TA>
+__device__ __forceinline__ void store_act4(TA *p, size_t plane, int row, int col, int ld, int mtp, f32x4 v);
+template <>
+__device__ __forceinline__ void store_act4<float>(float *p, size_t, int row, int col, int ld, int, f32x4 v) {
+    *reinterpret_cast<f32x4 *>(p + (size_t)row * ld + col) = v;
+}
+template <>
+__device__ __forceinline__ void store_act4<bf16_t>(bf16_t *p, size_t plane, int row, int col, int ld, int mtp, f32x4 v) {
+    const size_t idx = mtp > 0 ? act_tiled_idx(row, col, mtp) : (size_t)row * ld + col;
+    u32x2 hi, lo;
+#pragma unroll
+    for (int w = 0; w < 2; w++) {
+        const bf16_t h0 = f32_to_bf16(v[2 * w]), h1 = f32_to_bf16(v[2 * w + 1]);
+        hi[w] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        lo[w] = (uint32_t)f32_to_bf16(v[2 * w] - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(v[2 * w + 1] - bf16_to_f32(h1)) << 16);
+    }
+    *reinterpret_cast<u32x2 *>(p + idx) = hi;
+    *reinterpret_cast<u32x2 *>(p + idx + plane) = lo;
+}
+
 // KV cache addressing.  K: [L][Bmax][H][seq_pad][dh];  V is stored transposed in blocks of 32 positions,
 // [L][Bmax][H][seq_pad/32][dh][32], so that the P*V contraction reads 8 consecutive keys per lane and the
 // V fragments a wave needs of a 32-key tile are one contiguous dh * 64 bytes (whole cache lines: with plain
