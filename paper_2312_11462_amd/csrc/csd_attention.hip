@@ -190,16 +190,9 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
     const float *base = part + (((size_t)b * H + hh) * chunks_max * row_tiles + rt) * 16 * PS + (size_t)ri * PS;
     const size_t cstride = (size_t)row_tiles * 16 * PS;
     // chunk states are read eight at a time (the index is clamped rather than the load skipped, so all eight
-    // loads are in flight together); the sums run in chunk order
-    float mstar = -INFINITY;
-    for (int c0 = 0; c0 < nch; c0 += 8) {
-        float mc[8];
-#pragma unroll
-        for (int u = 0; u < 8; u++) mc[u] = base[(size_t)min(c0 + u, nch - 1) * cstride + DH];
-#pragma unroll
-        for (int u = 0; u < 8; u++) mstar = fmaxf(mstar, mc[u]);
-    }
-    float num = 0.f, den = 0.f;
+    // loads are in flight together) and folded in chunk order with a running maximum: one pass over the
+    // states, one memory round trip per eight chunks
+    float mstar = -INFINITY, num = 0.f, den = 0.f;
     for (int c0 = 0; c0 < nch; c0 += 8) {
         float mc[8], ac[8], lc[8];
 #pragma unroll
@@ -209,13 +202,21 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
             ac[u] = base[o + x];
             lc[u] = base[o + DH + 1];
         }
+        float mnew = mstar;
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (c0 + u < nch) mnew = fmaxf(mnew, mc[u]);
+        const float a = (mstar == -INFINITY) ? 0.f : expf(mstar - mnew);
+        num *= a;
+        den *= a;
 #pragma unroll
         for (int u = 0; u < 8; u++) {
             if (c0 + u >= nch || mc[u] == -INFINITY) continue;
-            const float w = expf(mc[u] - mstar);
+            const float w = expf(mc[u] - mnew);
             num += ac[u] * w;
             den += lc[u] * w;
         }
+        mstar = mnew;
     }
     store_act<bf16_t>(out, plane, r, hh * DH + x, ldo, mtp, den > 0.f ? num / den : 0.f);
 }
