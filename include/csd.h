@@ -195,7 +195,9 @@ int32_t csd_debug_set_timestamps(csd_model *model, uint64_t *marks);
 
 /* Which forward csd_verify_block would run for B sequences of m rows: 0 = one kernel per operation
  * (any shape), 1 = one kernel per phase, 2 = the single-launch persistent kernel (B*m <= 16 rows that
- * fit LDS).  The environment variable CSD_PATH=multikernel|phases at csd_model_create forces 0 or 1. */
+ * fit LDS; chosen by default for bf16 arch-0 models whose layers hold at least 64 MB of weights).  The
+ * environment variable CSD_PATH=multikernel|phases|persistent at csd_model_create forces 0, 1 or 2
+ * (where the model's shape allows it). */
 int32_t csd_debug_path(const csd_model *model, int32_t B, int32_t m);
 
 /* Counter calibration for benchmarks: a plain streaming copy of `bytes` bytes (a multiple of 16; dst and
