@@ -187,12 +187,20 @@ def test_bf16_blocks_of_2_to_13_row_tiles_workgroup_tiled_gemms(B, m):
     assert np.array_equal(a, b)
 
 
-def test_draft160m_config_synthetic_cache():
+@pytest.mark.parametrize("path", [None, "persistent"])
+def test_draft160m_config_synthetic_cache(path):
     """Configuration 2: 160M-shaped bf16 model, 512 cached rows (seeded stand-in K/V, since the
-    oracle needs minutes to prefill them), k = 8 drafts from the Max-Gram model."""
+    oracle needs minutes to prefill them), k = 8 drafts from the Max-Gram model; on the path a model
+    this small takes by default (one kernel per operation) and on the single-launch kernel."""
     wl = I.WORKLOADS["draft160m"]
     shape, seed = wl["shape"], wl["seed"]
-    gm, om = make_pair(shape, seed, 1, 640, 16)
+    if path:
+        os.environ["CSD_PATH"] = path
+    try:
+        gm, om = make_pair(shape, seed, 1, 640, 16)
+    finally:
+        os.environ.pop("CSD_PATH", None)
+    assert gm.path(1, 9) == (2 if path else 0)
     import_synthetic_kv(gm, om, shape, 512, seed)
     import paper_2312_11462_amd as P
     prefix = I.repeat_stream(513, shape.vocab, seed, 1)
@@ -200,6 +208,7 @@ def test_draft160m_config_synthetic_cache():
     draft, _ = P.bigram_draft(prefix.cuda(), _dev([513]), table, 8)
     block = torch.cat([prefix[-1:].cuda(), draft[0]])[None].cpu().numpy()
     err = _check_block(gm, om, block, [512], 2e-2, 1e-2, "160M", 5e-3)
+    assert gm.error_flag() == 0
     print("160M max err", err)
 
 
