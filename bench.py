@@ -207,7 +207,7 @@ def main():
         kernel, launch_bytes = "k_verify_persistent (whole review forward, one launch per step)", ab["total"]
     else:
         kernel = "k_fused_phase (one launch per GEMM phase)" if path == 1 else \
-                 ("k_gemm_rs" if B * m > 64 else "k_gemm_ws" if B * m > 16 else "k_gemm_mfma") + " (all weight-streaming GEMMs of a step)"
+                 ("k_gemm_rs" if B * m > 64 else "k_gemm_ws") + " (all weight-streaming GEMMs of a step)"
         launch_bytes = ab["weights"]
     achieved = launch_bytes / 1e9 / (gemm_ms_step / 1e3) if gemm_ms_step > 0 else 0.0
     roofline = {
