@@ -54,6 +54,8 @@ def main():
     ap.add_argument("--k", type=int, default=None, help="drafts per sequence instead of the workload's (configuration 5 sweeps it)")
     ap.add_argument("--prof-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="skip the peaks measured on the box (a streaming read, a copy, a loop of matrix instructions)")
     ap.add_argument("--cascade-steps", type=int, default=20, metavar="N",
                     help="workload target7b: also time N whole two-level cascade steps of configuration 3 "
                          "(the 160M-shaped draft level's reviews + the timed step); 0 = skip")
@@ -271,6 +273,35 @@ def main():
         del draft
         torch.cuda.empty_cache()
 
+    # ---- what plain kernels reach on this machine (context for the fractions of the published peaks)
+    peaks = None
+    if not args.no_peaks:
+        def timed(fn, reps):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / 1e3 / reps
+        sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")        # 1 GiB
+        dst = torch.empty_like(src)
+        nbytes = src.numel() * 4
+        t_read = timed(lambda: P.debug_read(src, sink), 5)
+        t_copy = timed(lambda: P.debug_copy(dst, src), 5)
+        iters = 20000
+        t_mfma = timed(lambda: P.debug_mfma(iters, sink), 3)
+        peaks = {"hbm_read_GBs": round(nbytes / 1e9 / t_read, 1), "hbm_copy_GBs": round(2 * nbytes / 1e9 / t_copy, 1),
+                 "mfma_bf16_dense_TFLOPs": round(4096 * iters * 8 * 16384 / 1e12 / t_mfma, 1),
+                 "what": "1 GiB streaming read (16-byte loads, 2048 workgroups); 1 GiB copy, read + write counted; "
+                         "4096 waves x 8 independent chains of 16x16x32 bf16 matrix instructions on registers"}
+        del src, dst, sink
+        torch.cuda.empty_cache()
+
     if args.copy_calibration > 0:
         src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -338,6 +369,8 @@ def main():
     }
     if cascade is not None:
         out["cascade_step"] = cascade
+    if peaks is not None:
+        out["measured_peaks"] = peaks
     print(json.dumps(out))
 
 

@@ -206,6 +206,16 @@ int32_t csd_debug_path(const csd_model *model, int32_t B, int32_t m);
  * in the same profiler run as the kernels being measured. */
 int32_t csd_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* Peaks measured on the box, for benchmarks (the roofline fractions are quoted against the published
+ * peaks; these say what a plain kernel reaches).  csd_debug_read: a grid-stride streaming read of `bytes`
+ * bytes (a multiple of 16, src 16-byte aligned; device) with 16-byte loads, 2048 workgroups; each
+ * workgroup stores one word to sink (device, >= 2048 uint32) so that the loads are kept.  csd_debug_mfma:
+ * 1024 workgroups of 4 waves, every wave issues `iters` x 8 independent 16x16x32 bf16 matrix instructions
+ * on registers (no memory traffic), i.e. 4096 x iters x 8 x 16384 flops in all; sink as above.  Both are
+ * asynchronous on `stream`; the caller times them. */
+int32_t csd_debug_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+int32_t csd_debug_mfma(int64_t iters, uint32_t *sink, void *stream);
+
 /* Kernel timing hook for benchmarks.  While enabled, each verify call brackets every kernel
  * it launches with a pair of HIP events on the caller's stream (this perturbs the step, so
  * throughput is timed with the hook off).  After the caller has synchronised the stream,

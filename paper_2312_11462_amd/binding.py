@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
            "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
-           "csd_accept", "csd_verify_accept", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_debug_copy",
+           "csd_accept", "csd_verify_accept", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
            "csd_prof_enable", "csd_prof_read"]
 
 _STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}
@@ -187,6 +187,19 @@ def debug_copy(dst, src):
         raise ValueError("debug_copy: size mismatch")
     _chk(lib().csd_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), C.c_size_t(nbytes), _stream()),
          "csd_debug_copy")
+
+
+def debug_read(src, sink):
+    """Streaming read of src (byte size a multiple of 16); sink: uint32/int32 device tensor of >= 2048 words."""
+    nbytes = src.numel() * src.element_size()
+    _chk(lib().csd_debug_read(C.c_void_p(src.data_ptr()), C.c_size_t(nbytes), C.c_void_p(sink.data_ptr()), _stream()),
+         "csd_debug_read")
+
+
+def debug_mfma(iters, sink):
+    """4096 waves x iters x 8 matrix instructions (16x16x32 bf16) on registers; returns the flops issued."""
+    _chk(lib().csd_debug_mfma(C.c_int64(iters), C.c_void_p(sink.data_ptr()), _stream()), "csd_debug_mfma")
+    return 4096 * iters * 8 * 16384
 
 
 def bigram_fit(tokens, vocab, next_table):

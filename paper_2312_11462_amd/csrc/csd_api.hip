@@ -215,6 +215,49 @@ extern "C" int32_t csd_debug_copy(void *dst, const void *src, size_t bytes, void
     return CSD_OK;
 }
 
+__global__ __launch_bounds__(256) void k_read_calib(const u32x4 *__restrict__ src, size_t n, uint32_t *__restrict__ sink) {
+    u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        acc ^= __builtin_nontemporal_load(src + i);
+    const uint32_t v = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    if (v == 0x9E3779B9u || threadIdx.x == 0) sink[blockIdx.x] = v;      // keeps every lane's loads
+}
+
+extern "C" int32_t csd_debug_read(const void *src, size_t bytes, uint32_t *sink, void *stream) {
+    if (!src || !sink) return CSD_ENULL;
+    if (bytes % 16 || (uintptr_t)src % 16) return CSD_EINVAL;
+    if (bytes == 0) return CSD_OK;
+    hipLaunchKernelGGL(k_read_calib, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)src, bytes / 16, sink);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+__global__ __launch_bounds__(256) void k_mfma_calib(long long iters, uint32_t *__restrict__ sink) {
+    const uint32_t seed = 0x3F803F80u + (threadIdx.x & 7u);              // small bf16 values
+    const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{seed, seed, seed, seed});
+    const bf16x8 b = __builtin_bit_cast(bf16x8, u32x4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u});
+    f32x4 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (long long i = 0; i < iters; i++) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[j], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) t += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3];
+    if (t == -1.0f || threadIdx.x == 0) sink[blockIdx.x] = __float_as_uint(t);
+}
+
+extern "C" int32_t csd_debug_mfma(int64_t iters, uint32_t *sink, void *stream) {
+    if (!sink) return CSD_ENULL;
+    if (iters < 0 || iters > (1ll << 24)) return CSD_EINVAL;
+    if (iters == 0) return CSD_OK;
+    hipLaunchKernelGGL(k_mfma_calib, dim3(1024), dim3(256), 0, (hipStream_t)stream, (long long)iters, sink);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
 extern "C" int32_t csd_prof_enable(csd_model *mod, int32_t on) {
     if (!mod) return CSD_ENULL;
     mod->prof = on != 0;
