@@ -680,14 +680,18 @@ static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane
     return CSD_OK;
 }
 
-// Blocks of up to 64 rows (of Mtot in the call): 128 columns per workgroup (256 at two row tiles; elsewhere
-// wider tiles do not fit the registers); K is split until there is a workgroup per compute unit.  *S_io: the
+// Blocks of up to 64 rows (of Mtot in the call): 128 columns per workgroup (64 at one or two row tiles); K is
+// split until there is a workgroup per compute unit.  *S_io: the
 // number of K splits, chosen here when 0 (later row chunks of the same call must use the same).
 static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int *S_io,
                               hipStream_t st) {
-    // two row tiles: four column tiles per wave still fit the registers (256 columns per workgroup, twice
-    // the weights in flight per compute unit); with more row tiles they spill
-    const int NT = (M + 15) / 16 == 2 ? 4 : 2;
+    // one or two row tiles: one column tile per wave, 64 columns per workgroup.  Twice the workgroups then
+    // reach the target below with half the K splits, so the epilogue kernels read half the partial sums,
+    // and two or three of these light workgroups share a compute unit (measured per step against two
+    // tiles per wave: 4.02 -> 3.86 ms at 6 rows of the 7B shape, 5.83 -> 5.68 ms at 24 rows of batch 8; from
+    // three row tiles on two tiles per wave are as fast or faster, their LDS reads being shared by more
+    // matrix instructions)
+    const int NT = (M + 15) / 16 <= 2 ? 1 : 2;
     const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 4 * NT - 1) / (4 * NT);
     int S = *S_io;
     if (S == 0) {
@@ -696,8 +700,8 @@ static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, i
         *S_io = S;
     }
     switch ((M + 15) / 16) {
-    case 1: return launch_gemm_ws_mt<1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 2: return NT == 4 ? launch_gemm_ws_mt<2, 4>(w, act, plane, mtp, part, M, Mtot, S, groups, st) : launch_gemm_ws_mt<2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 1: return launch_gemm_ws_mt<1, 1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 2: return launch_gemm_ws_mt<2, 1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     case 3: return launch_gemm_ws_mt<3>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     case 4: return launch_gemm_ws_mt<4>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     case 5: return launch_gemm_ws_mt<5>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
@@ -752,15 +756,14 @@ static hipError_t rs_allow_lds() {
                                2 * WG_U_MAX * CT * 64 * 16);
 }
 int32_t csd_gemm_setup() {
-    CSD_HIP(ws_allow_lds<1>());
-    CSD_HIP(ws_allow_lds<2>());
+    CSD_HIP((ws_allow_lds<1, 1>()));
+    CSD_HIP((ws_allow_lds<2, 1>()));
     CSD_HIP(ws_allow_lds<3>());
     CSD_HIP(ws_allow_lds<4>());
     CSD_HIP(ws_allow_lds<5>());
     CSD_HIP(ws_allow_lds<6>());
     CSD_HIP(ws_allow_lds<7>());
     CSD_HIP(ws_allow_lds<8>());
-    CSD_HIP((ws_allow_lds<2, 4>()));
     CSD_HIP((rs_allow_lds<16, 1>()));
     CSD_HIP((rs_allow_lds<16, 2>()));
     CSD_HIP((rs_allow_lds<8, 3>()));
