@@ -1207,7 +1207,7 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     // CSD_PATH = persistent | phases | multikernel picks the path; unset: the single-launch kernel for models
     // whose layers stream at least 64 MB of weights.  It pays a device-wide barrier per phase where the
     // multi-kernel path pays a launch per kernel; measured per verify step, 7B shape (404 MB per layer):
-    // 3.80 against 4.01 ms, 160M shape (14 MB per layer, latency-bound either way): 0.78 against 0.60 ms.
+    // 3.80 against 3.84 ms, 160M shape (14 MB per layer, latency-bound either way): 0.78 against 0.55 ms.
     const char *e = getenv("CSD_PATH");
     const size_t layer_bytes = sizeof(bf16_t) * ((size_t)4 * mod->hd * c.d_model + (size_t)3 * c.d_ffn * c.d_model);
     int mode = layer_bytes >= ((size_t)64 << 20) ? 2 : 0;
