@@ -1204,15 +1204,13 @@ int32_t csd_fused_init(csd_model *mod, hipStream_t st) {
     const csd_model_cfg &c = mod->cfg;
     mod->fused = nullptr;
     if (!mod->mfma || !mod->mfma_attn) return CSD_OK;
-    // CSD_PATH = persistent | phases | multikernel picks the path; unset: the single-launch kernel for models
-    // whose layers stream at least 64 MB of weights.  It pays a device-wide barrier per phase where the
-    // multi-kernel path pays a launch per kernel; measured per verify step, 7B shape (404 MB per layer):
-    // 3.80 against 3.84 ms, 160M shape (14 MB per layer, latency-bound either way): 0.78 against 0.55 ms.
+    // CSD_PATH = persistent | phases | multikernel picks the path; unset: multikernel.  The single-launch
+    // kernel pays a device-wide barrier per phase (and an idle memory system during its attention phase)
+    // where the multi-kernel path pays a launch per kernel; measured per verify step, 7B shape, 6 rows:
+    // 3.80 ms against 3.68 ms; 160M shape (latency-bound either way): 0.78 against 0.55 ms.
     const char *e = getenv("CSD_PATH");
-    const size_t layer_bytes = sizeof(bf16_t) * ((size_t)4 * mod->hd * c.d_model + (size_t)3 * c.d_ffn * c.d_model);
-    int mode = layer_bytes >= ((size_t)64 << 20) ? 2 : 0;
+    int mode = 0;
     if (e && strcmp(e, "persistent") == 0) mode = 2;
-    if (e && strcmp(e, "multikernel") == 0) mode = 0;
     if (e && strcmp(e, "phases") == 0) mode = 1;
     if (mode == 0) return CSD_OK;
     int dev = 0, cus = 0, lds_max = 0;
