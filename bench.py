@@ -23,7 +23,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 counter runs of this same command
 # (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a copy of known size); the
 # summaries and the commands are under profiles/.  Keyed by (workload, forward path).
-TRAFFIC_BYTES_PER_LAUNCH = {("target7b", 2): 14_896_000_000}
+TRAFFIC_BYTES_PER_LAUNCH = {("target7b", 2): 14_896_000_000, ("target7b", 0): 103_707_000}
 
 
 def algorithmic_bytes(shape, B, t, m):
