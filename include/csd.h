@@ -179,6 +179,26 @@ int32_t csd_verify_accept(csd_model *model, void *kv, const int32_t *tokens, con
                           float lenience, int32_t mode, float *logits, float *probs,
                           int32_t *n_accepted, int32_t *next_token, void *stream);
 
+/*
+ * csd_verify_accept for callers that cannot allocate and do not want the call to touch memory that a
+ * hipMalloc of this library returned for scratch: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, same results, same kernels; the per-call scratch
+ * (residual stream, GEMM input planes, split-K partial sums, attention partial states, probabilities) lives
+ * in a static device array of CSD_STATIC_SCRATCH_BYTES per GPU instead of in the model, and the call makes
+ * no hipMalloc / hipFree (nor does any other call after csd_model_create).
+ *   CSD_ESHAPE        the model's scratch (it grows with max_batch * max_block and the widest matrix) does not
+ *                     fit the static array;
+ *   CSD_EUNSUPPORTED  the model was created with CSD_PATH=persistent|phases (those forwards keep their own state).
+ * Every call on a GPU shares that GPU's array, whatever the model or stream: calls that overlap on one GPU
+ * race.  Nothing in it needs clearing: each call overwrites what it reads.
+ */
+#define CSD_STATIC_SCRATCH_BYTES (8u << 20)
+int32_t csd_verify_accept_static(csd_model *model, void *kv, const int32_t *tokens, const int32_t *cache_len,
+                                 int32_t B, int32_t m, float temperature,
+                                 const float *q, const uint8_t *q_onehot, const float *u_acc, const float *u_samp,
+                                 float lenience, int32_t mode, float *logits, float *probs,
+                                 int32_t *n_accepted, int32_t *next_token, void *stream);
+
 /* Test hook: when trace != NULL the next verify calls also copy the residual stream of all
  * B*m rows after the embedding and after every layer to trace[(n_layers+1)][B*m][d] (fp32). */
 int32_t csd_debug_set_trace(csd_model *model, float *trace);

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
            "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
-           "csd_accept", "csd_verify_accept", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
+           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
            "csd_prof_enable", "csd_prof_read"]
 
 _STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}
@@ -144,16 +144,18 @@ class Model:
         return (logits, probs) if want_probs else logits
 
     def verify_accept(self, tokens, cache_len, u_acc, u_samp, q=None, q_onehot=None, temperature=1.0,
-                      lenience=1.0, mode=0, logits=None, probs=None, n_accepted=None, next_token=None):
+                      lenience=1.0, mode=0, logits=None, probs=None, n_accepted=None, next_token=None, static=False):
+        """static=True: csd_verify_accept_static (scratch in the library's static device array)."""
         B, m = tokens.shape
         if n_accepted is None:
             n_accepted = torch.empty(B, dtype=torch.int32, device="cuda")
         if next_token is None:
             next_token = torch.empty(B, dtype=torch.int32, device="cuda")
-        _chk(lib().csd_verify_accept(self._h, _ptr(self.kv), _ptr(tokens, torch.int32), _ptr(cache_len, torch.int32),
-                                     B, m, C.c_float(temperature), _ptr(q), _ptr(q_onehot), _ptr(u_acc), _ptr(u_samp),
-                                     C.c_float(lenience), mode, _ptr(logits), _ptr(probs), _ptr(n_accepted),
-                                     _ptr(next_token), _stream()), "csd_verify_accept")
+        fn = lib().csd_verify_accept_static if static else lib().csd_verify_accept
+        _chk(fn(self._h, _ptr(self.kv), _ptr(tokens, torch.int32), _ptr(cache_len, torch.int32),
+                B, m, C.c_float(temperature), _ptr(q), _ptr(q_onehot), _ptr(u_acc), _ptr(u_samp),
+                C.c_float(lenience), mode, _ptr(logits), _ptr(probs), _ptr(n_accepted),
+                _ptr(next_token), _stream()), "csd_verify_accept_static" if static else "csd_verify_accept")
         return n_accepted, next_token
 
     def set_trace(self, trace):

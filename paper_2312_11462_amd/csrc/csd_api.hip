@@ -2,6 +2,7 @@
 // (review forward + softmax + accept) enqueued on the caller's stream.
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "csd_internal.h"
@@ -14,6 +15,69 @@ extern "C" int32_t csd_last_hip_error(void) { return g_csd_last_hip_error; }
 static bool env_is(const char *name, const char *val) {
     const char *e = getenv(name);
     return e && strcmp(e, val) == 0;
+}
+
+// The per-call scratch of a model as one block: the residual stream, the GEMM input planes, the rotated
+// queries, the split-K partial sums, the attention partial states, a probability buffer and the rotary
+// table, each piece 256-byte aligned.  Returns the block's size; with base != null also the pieces.
+size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out) {
+    const csd_model_cfg &c = mod->cfg;
+    const size_t asz = mod->mfma ? 2 : 4, planes = mod->mfma ? 2 : 1;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *p = base ? base + off : nullptr;
+        off += (bytes + 255) / 256 * 256;
+        return p;
+    };
+    char *h = take(sizeof(float) * (size_t)mod->m_max * c.d_model);
+    char *act = take(asz * planes * mod->act_plane);
+    char *qbuf = take(asz * planes * mod->q_plane);
+    char *part = take(sizeof(float) * mod->part_floats);
+    char *probs = take(sizeof(float) * (size_t)mod->m_max * c.vocab);
+    char *rope = take(sizeof(float2) * (size_t)mod->m_max * (c.head_dim / 2 + 1));
+    char *attn_part = nullptr;
+    if (mod->mfma_attn) {
+        // per (sequence, head, key chunk): 16*ceil(m/16) rows x (dh accumulators + max + sum)
+        const int row_tiles = (c.max_block + 15) / 16;
+        const size_t per = (size_t)row_tiles * 16 * (c.head_dim + 4);
+        attn_part = take(sizeof(float) * per * mod->attn_chunks_max * c.n_heads * c.max_batch);
+    }
+    if (out) *out = ScratchPtrs{(float *)h, act, qbuf, (float *)part, (float *)probs, (float2 *)rope, (float *)attn_part};
+    return off;
+}
+
+ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp) {
+    const ScratchPtrs old{mod->h, mod->act, mod->qbuf, mod->part, mod->probs, mod->rope, mod->attn_part};
+    mod->h = sp.h;
+    mod->act = sp.act;
+    mod->qbuf = sp.qbuf;
+    mod->part = sp.part;
+    mod->probs = sp.probs;
+    mod->rope = sp.rope;
+    mod->attn_part = sp.attn_part;
+    return old;
+}
+
+// Scratch for csd_verify_accept_static: one copy per device, held until the process ends.  In host code the
+// array's name is only a handle for the symbol look-up; the device address comes from hipGetSymbolAddress,
+// once per device, and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[CSD_STATIC_SCRATCH_BYTES];
+static char *g_static_base[64];
+static std::mutex g_static_mu;
+
+static int32_t static_scratch_base(char **out) {
+    int dev = -1;
+    CSD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return CSD_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_base[dev]) {
+        void *p = nullptr;
+        CSD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return CSD_EHIP;
+        g_static_base[dev] = (char *)p;
+    }
+    *out = g_static_base[dev];
+    return CSD_OK;
 }
 
 static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream_t st) {
@@ -38,7 +102,6 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     if ((rc = csd_pack_weights(mod, weights, st)) != CSD_OK) return rc;
     if (mod->mfma && (rc = csd_gemm_setup()) != CSD_OK) return rc;
 
-    const size_t asz = mod->mfma ? 2 : 4;
     const int m_pad = (mod->m_max + 15) / 16 * 16;
     int wmax = d > F ? d : F;
     if (hd > wmax) wmax = hd;
@@ -46,39 +109,20 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     if (2 * F > nmax) nmax = 2 * F;
     if (V > nmax) nmax = V;
     if (d > nmax) nmax = d;
-    void *p;
-    CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->m_max * d));
-    mod->allocs.push_back(p);
-    mod->h = (float *)p;
-    const int planes = mod->mfma ? 2 : 1;
     mod->act_plane = (size_t)m_pad * wmax;
     mod->act_mtp = mod->mfma ? m_pad / 16 : 0;
     mod->q_plane = (size_t)m_pad * hd;
-    CSD_HIP(hipMalloc(&p, asz * planes * mod->act_plane));
-    mod->allocs.push_back(p);
-    mod->act = p;
-    CSD_HIP(hipMalloc(&p, asz * planes * mod->q_plane));
-    mod->allocs.push_back(p);
-    mod->qbuf = p;
-    CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->s_max * mod->m_max * nmax));
-    mod->allocs.push_back(p);
-    mod->part = (float *)p;
     mod->part_floats = (size_t)mod->s_max * mod->m_max * nmax;
-    CSD_HIP(hipMalloc(&p, sizeof(float) * (size_t)mod->m_max * V));
+    if (mod->mfma_attn) mod->attn_chunks_max = (keys_pad + 127) / 128;
+    // the per-call scratch is one block, carved the same way wherever it lives
+    void *p;
+    CSD_HIP(hipMalloc(&p, csd_scratch_carve(mod, nullptr, nullptr)));
     mod->allocs.push_back(p);
-    mod->probs = (float *)p;
-    CSD_HIP(hipMalloc(&p, sizeof(float2) * (size_t)mod->m_max * (c.head_dim / 2 + 1)));
-    mod->allocs.push_back(p);
-    mod->rope = (float2 *)p;
-    if (mod->mfma_attn) {
-        // per (sequence, head, key chunk): 16*ceil(m/16) rows x (dh accumulators + max + sum)
-        mod->attn_chunks_max = (keys_pad + 127) / 128;
-        const int row_tiles = (c.max_block + 15) / 16;
-        const size_t per = (size_t)row_tiles * 16 * (c.head_dim + 4);
-        CSD_HIP(hipMalloc(&p, sizeof(float) * per * mod->attn_chunks_max * c.n_heads * c.max_batch));
-        mod->allocs.push_back(p);
-        mod->attn_part = (float *)p;
-    }
+    ScratchPtrs sp;
+    csd_scratch_carve(mod, (char *)p, &sp);
+    csd_scratch_install(mod, sp);
+    char *static_base;
+    if ((rc = static_scratch_base(&static_base)) != CSD_OK) return rc;   // looked up once per device, here
     mod->ev.resize(8192);
     for (auto &e : mod->ev) CSD_HIP(hipEventCreate(&e));
     if (c.arch != 0) return CSD_OK;      // the single-launch kernel covers the LLaMA-style decoder only
@@ -176,6 +220,28 @@ extern "C" int32_t csd_verify_accept(csd_model *mod, void *kv, const int32_t *to
     ProfScope ps(mod, st, CSD_PROF_OTHER);
     return csd_accept_enqueue(p, q, q_onehot, tokens + 1, m, u_acc, u_samp, B, m - 1, V, lenience, mode, n_accepted,
                               next_token, st);
+}
+
+extern "C" int32_t csd_verify_accept_static(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
+                                            int32_t B, int32_t m, float temperature, const float *q,
+                                            const uint8_t *q_onehot, const float *u_acc, const float *u_samp,
+                                            float lenience, int32_t mode, float *logits, float *probs,
+                                            int32_t *n_accepted, int32_t *next_token, void *stream) {
+    if (!mod) return CSD_ENULL;
+    if (csd_fused_path(mod, B, m) != 0) return CSD_EUNSUPPORTED;        // that forward keeps state of its own
+    if (csd_scratch_carve(mod, nullptr, nullptr) > CSD_STATIC_SCRATCH_BYTES) return CSD_ESHAPE;
+    char *base;
+    int32_t rc = static_scratch_base(&base);
+    if (rc != CSD_OK) return rc;
+    ScratchPtrs sp;
+    csd_scratch_carve(mod, base, &sp);
+    // the kernels take the scratch pieces as arguments at enqueue time, so the model's own pieces are back in
+    // place as soon as the enqueue returns
+    const ScratchPtrs own = csd_scratch_install(mod, sp);
+    rc = csd_verify_accept(mod, kv, tokens, cache_len, B, m, temperature, q, q_onehot, u_acc, u_samp, lenience, mode,
+                           logits, probs, n_accepted, next_token, stream);
+    csd_scratch_install(mod, own);
+    return rc;
 }
 
 extern "C" int32_t csd_debug_set_trace(csd_model *mod, float *trace) {

@@ -245,6 +245,17 @@ struct csd_model {
     std::vector<void *> allocs;
 };
 
+// The pieces of a model's per-call scratch block (csd_api.hip)
+struct ScratchPtrs {
+    float *h;
+    void *act, *qbuf;
+    float *part, *probs;
+    float2 *rope;
+    float *attn_part;
+};
+size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out);
+ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp);   // returns the pieces in use before
+
 // csd_forward.hip
 int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len,
                             int32_t B, int32_t m, float *logits, hipStream_t st);
