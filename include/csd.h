@@ -190,7 +190,7 @@ int32_t csd_verify_accept(csd_model *model, void *kv, const int32_t *tokens, con
  *                     fit the static array;
  *   CSD_EUNSUPPORTED  the model was created with CSD_PATH=persistent|phases (those forwards keep their own state).
  * Every call on a GPU shares that GPU's array, whatever the model or stream: calls that overlap on one GPU
- * race.  Nothing in it needs clearing: each call overwrites what it reads.
+ * race.  The call clears the few counters in it that must start at zero and overwrites everything else it reads.
  */
 #define CSD_STATIC_SCRATCH_BYTES (8u << 20)
 int32_t csd_verify_accept_static(csd_model *model, void *kv, const int32_t *tokens, const int32_t *cache_len,

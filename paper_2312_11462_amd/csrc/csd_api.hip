@@ -42,12 +42,24 @@ size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out) {
         const size_t per = (size_t)row_tiles * 16 * (c.head_dim + 4);
         attn_part = take(sizeof(float) * per * mod->attn_chunks_max * c.n_heads * c.max_batch);
     }
-    if (out) *out = ScratchPtrs{(float *)h, act, qbuf, (float *)part, (float *)probs, (float2 *)rope, (float *)attn_part};
+    char *x[4] = {nullptr, nullptr, nullptr, nullptr}, *ssq[2] = {nullptr, nullptr}, *cnt = nullptr;
+    if (mod->chain_on) {
+        for (int i = 0; i < 4; i++) x[i] = take(2 * 2 * mod->x_plane[i]);
+        for (int i = 0; i < 2; i++) ssq[i] = take(sizeof(float) * (size_t)(c.d_model / 16) * 16);
+        cnt = take(sizeof(unsigned) * (size_t)c.max_batch * c.n_heads);
+    }
+    if (out)
+        *out = ScratchPtrs{(float *)h, act, qbuf, (float *)part, (float *)probs, (float2 *)rope, (float *)attn_part,
+                           {x[0], x[1], x[2], x[3]}, {(float *)ssq[0], (float *)ssq[1]}, (unsigned *)cnt};
     return off;
 }
 
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp) {
-    const ScratchPtrs old{mod->h, mod->act, mod->qbuf, mod->part, mod->probs, mod->rope, mod->attn_part};
+    const ScratchPtrs old{mod->h, mod->act, mod->qbuf, mod->part, mod->probs, mod->rope, mod->attn_part,
+                          {mod->x[0], mod->x[1], mod->x[2], mod->x[3]}, {mod->ssq[0], mod->ssq[1]}, mod->attn_cnt};
+    mod->attn_cnt = sp.attn_cnt;
+    for (int i = 0; i < 4; i++) mod->x[i] = sp.x[i];
+    for (int i = 0; i < 2; i++) mod->ssq[i] = sp.ssq[i];
     mod->h = sp.h;
     mod->act = sp.act;
     mod->qbuf = sp.qbuf;
@@ -56,6 +68,10 @@ ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp) {
     mod->rope = sp.rope;
     mod->attn_part = sp.attn_part;
     return old;
+}
+
+__global__ void k_fill_u32(unsigned *__restrict__ p, unsigned v, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = v;
 }
 
 // Scratch for csd_verify_accept_static: one copy per device, held until the process ends.  In host code the
@@ -114,6 +130,14 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->q_plane = (size_t)m_pad * hd;
     mod->part_floats = (size_t)mod->s_max * mod->m_max * nmax;
     if (mod->mfma_attn) mod->attn_chunks_max = (keys_pad + 127) / 128;
+    // blocks of up to 16 rows of a LLaMA-style bf16 model take the forward of csd_chain.hip (CSD_PATH=multikernel: never)
+    mod->chain_on = mod->mfma && mod->mfma_attn && mod->kperm && !env_is("CSD_PATH", "multikernel") &&
+                    !env_is("CSD_PATH", "persistent") && !env_is("CSD_PATH", "phases");
+    if (mod->chain_on) {
+        const int widths[4] = {d, hd, d, F};
+        for (int i = 0; i < 4; i++) mod->x_plane[i] = (size_t)m_pad * widths[i];
+        if ((rc = csd_chain_setup()) != CSD_OK) return rc;
+    }
     // the per-call scratch is one block, carved the same way wherever it lives
     void *p;
     CSD_HIP(hipMalloc(&p, csd_scratch_carve(mod, nullptr, nullptr)));
@@ -121,6 +145,10 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     ScratchPtrs sp;
     csd_scratch_carve(mod, (char *)p, &sp);
     csd_scratch_install(mod, sp);
+    if (mod->attn_cnt) {     // arrival counters start at zero; every launch leaves them there
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, st, mod->attn_cnt, 0u, c.max_batch * c.n_heads);
+        CSD_LAUNCH_CHECK();
+    }
     char *static_base;
     if ((rc = static_scratch_base(&static_base)) != CSD_OK) return rc;   // looked up once per device, here
     mod->ev.resize(8192);
@@ -238,6 +266,13 @@ extern "C" int32_t csd_verify_accept_static(csd_model *mod, void *kv, const int3
     // the kernels take the scratch pieces as arguments at enqueue time, so the model's own pieces are back in
     // place as soon as the enqueue returns
     const ScratchPtrs own = csd_scratch_install(mod, sp);
+    if (sp.attn_cnt) {
+        // the array keeps whatever the last call on this GPU left (another model lays it out differently): the
+        // attention kernel's arrival counters must start at zero.  A fill kernel, not a memset: the call may be
+        // under graph capture.
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, (hipStream_t)stream, sp.attn_cnt, 0u,
+                           mod->cfg.max_batch * mod->cfg.n_heads);
+    }
     rc = csd_verify_accept(mod, kv, tokens, cache_len, B, m, temperature, q, q_onehot, u_acc, u_samp, lenience, mode,
                            logits, probs, n_accepted, next_token, stream);
     csd_scratch_install(mod, own);
@@ -263,7 +298,8 @@ extern "C" int32_t csd_debug_set_timestamps(csd_model *mod, uint64_t *marks) {
 
 extern "C" int32_t csd_debug_path(const csd_model *mod, int32_t B, int32_t m) {
     if (!mod) return CSD_ENULL;
-    return csd_fused_path(mod, B, m);
+    const int32_t f = csd_fused_path(mod, B, m);
+    return f != 0 ? f : csd_chain_eligible(mod, B, m) ? 3 : 0;
 }
 
 __global__ __launch_bounds__(256) void k_copy_calib(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, size_t n) {

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(DH) void k_attn_merge(const float *__restrict__ par
 
 template <int DH>
 static void attn_launch(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m, int layer,
-                        float scale, const AttnMode &mode, hipStream_t st) {
+                        float scale, const AttnMode &mode, hipStream_t st, bf16_t *out, size_t out_plane) {
     const csd_model_cfg &c = mod->cfg;
     const int row_tiles = (m + 15) / 16;
     // keys per wave: doubled while there are more than 2048 waves (two per SIMD): measured best at batch 8 with 2048
@@ -243,18 +243,23 @@ static void attn_launch(csd_model *mod, const KvGeom &geo, const void *kv, const
                            (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale,
                            mod->attn_part, mod->attn_chunks_max, chunk_keys, mode);
     hipLaunchKernelGGL((k_attn_merge<DH>), dim3(B * m, c.n_heads), dim3(DH), 0, st, mod->attn_part, m, row_tiles, cache_len,
-                       c.n_heads, geo.seq_pad, mod->attn_chunks_max, chunk_keys, (bf16_t *)mod->act, mod->hd, mod->act_plane, mod->act_mtp,
+                       c.n_heads, geo.seq_pad, mod->attn_chunks_max, chunk_keys, out, mod->hd, out_plane, mod->act_mtp,
                        mode.fixed_nk);
 }
 
-// geo / kv: the cache being attended (the self-attention cache, or arch 1's cross-attention part of it)
+// geo / kv: the cache being attended (the self-attention cache, or arch 1's cross-attention part of it);
+// out / out_plane: where the merged rows go (two planes, fragment order), null = the model's shared GEMM input buffer
 int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
-                              int layer, float scale, const AttnMode &mode, hipStream_t st) {
+                              int layer, float scale, const AttnMode &mode, hipStream_t st, bf16_t *out, size_t out_plane) {
     ProfScope ps(mod, st, CSD_PROF_ATTN);
+    if (!out) {
+        out = (bf16_t *)mod->act;
+        out_plane = mod->act_plane;
+    }
     if (mod->cfg.head_dim == 128)
-        attn_launch<128>(mod, geo, kv, cache_len, B, m, layer, scale, mode, st);
+        attn_launch<128>(mod, geo, kv, cache_len, B, m, layer, scale, mode, st, out, out_plane);
     else
-        attn_launch<64>(mod, geo, kv, cache_len, B, m, layer, scale, mode, st);
+        attn_launch<64>(mod, geo, kv, cache_len, B, m, layer, scale, mode, st, out, out_plane);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }

@@ -1,0 +1,684 @@
+// Review forward for blocks of up to 16 rows (Section 2: one run of the reviewer scores every drafted
+// position): five launches per layer, no split-K partial sums in memory, no epilogue kernels.
+//
+//   QKV GEMM   -> rotate q, k; q to the query buffer; K, V appended to the cache   (epilogue)
+//   attention  -> key chunks in parallel, merged by the last chunk to finish
+//   O GEMM     -> h += ; (h * gain) as the next GEMM's input; sum of squares per tile (epilogue)
+//   gate|up    -> silu(rstd * gate) * (rstd * up) as the next GEMM's input              (epilogue)
+//   down GEMM  -> h += ; (h * gain); sum of squares per tile                            (epilogue)
+//
+// A GEMM workgroup owns a few whole 16-feature output tiles and splits K over its eight waves; every wave
+// streams its own K slice of the pre-tiled weights through a register ring and multiplies it with the
+// activation fragments of the same slice (read from L2: no two waves need the same ones), the eight
+// partial tiles are added in LDS in wave order (deterministic), and the epilogue runs in the same kernel
+// on complete sums.  RMSNorm is folded around the GEMM: rmsnorm(h) * g @ W = rstd(row) * ((h * g) @ W);
+// the producer of h writes h * g and one sum of squares per (row, 16-feature tile), the consumer's
+// epilogue scales its output rows by 1 / sqrt(sum / d + eps).
+#include <cmath>
+
+#include "csd_internal.h"
+
+#define CH_WAVES 8
+#define CH_THREADS (CH_WAVES * 64)
+#define CH_OOB ((int)0x80000000)     /* buffer offset beyond any buffer: loads give 0 and touch no memory */
+#define CH_SC1 16                    /* write-through stores: the data is for workgroups on other compute dies */
+
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GU = 2, EPI_LOGITS = 3 };
+
+struct ChainGemm {
+    const u32x4 *Wp;          // tiles [N/16][KS][64 lanes][8 bf16]
+    int KS, n_units, wbytes;  // k-steps of 32; units a workgroup owns whole (a tile; gate|up: a gate tile and its up tile)
+    const bf16_t *a;          // input planes (hi, lo), fragment order (act_tiled_idx)
+    int a_plane_bytes, mtp, M;
+    const float *ssq_in;      // [n_ssq][16]: sum of squares of the input's source rows per 16-feature tile (folded norm) or null
+    int n_ssq;
+    float inv_d, eps;
+    // EPI_RESID: residual stream, next norm's gain, output planes + sums of squares
+    float *h;
+    const float *gain;
+    bf16_t *out;              // output planes (EPI_RESID, EPI_GU), fragment order
+    int out_plane_bytes;
+    float *ssq_out;
+    int d;
+    // EPI_QKV
+    int m, hd, dh, layer;
+    KvGeom geo;
+    const int32_t *cache_len;
+    const float2 *rope;       // (cos, sin) [M][dh/2] or null
+    bf16_t *q;                // rotated queries, two row-major planes [..][hd]
+    int q_plane_bytes;
+    bf16_t *kv;
+    int gelu;                 // EPI_GU: tanh-GELU instead of SiLU
+    float *logits;            // EPI_LOGITS [M][V]
+    int V;
+};
+
+// A buffer descriptor must sit in scalar registers.  Base addresses here are the same in every lane, but the
+// compiler cannot always prove it (64-bit address arithmetic on workgroup indices may end up in vector
+// registers) and then wraps every access in a loop over the distinct descriptors: say so explicitly.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t ch_rsrc(const void *p, size_t bytes) {
+    const unsigned long long a = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    const int n = __builtin_amdgcn_readfirstlane((int)(bytes > 0x7FFFFFFFull ? 0x7FFFFFFFull : bytes));
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(((unsigned long long)hi << 32) | lo), 0, n, 0x00020000);
+}
+
+__device__ __forceinline__ void split4(const float *v, u32x2 &hi, u32x2 &lo) {
+#pragma unroll
+    for (int w = 0; w < 2; w++) {
+        const uint32_t hh = pack_bf16x2(v[2 * w], v[2 * w + 1]);
+        hi[w] = hh;
+        lo[w] = pack_bf16x2(v[2 * w] - __uint_as_float(hh << 16), v[2 * w + 1] - __uint_as_float(hh & 0xFFFF0000u));
+    }
+}
+
+// Four consecutive columns of one row into the two planes of a fragment-ordered activation buffer.
+__device__ __forceinline__ void store_planes4(bf16_t *out, int plane_bytes, int mtp, int row, int col, const float *v) {
+    u32x2 hi, lo;
+    split4(v, hi, lo);
+    const int off = (int)(act_tiled_idx(row, col, mtp) * 2);
+    const __amdgpu_buffer_rsrc_t r = ch_rsrc(out, (size_t)2 * plane_bytes);
+    __builtin_amdgcn_raw_buffer_store_b64(hi, r, off, 0, CH_SC1);
+    __builtin_amdgcn_raw_buffer_store_b64(lo, r, off + plane_bytes, 0, CH_SC1);
+}
+
+template <int NT, int R, int EPI>
+__global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
+    extern __shared__ __align__(16) char ch_smem[];
+    f32x4 *red = reinterpret_cast<f32x4 *>(ch_smem);                          // [8 waves][NT][64 lanes]
+    float *rs_part = reinterpret_cast<float *>(ch_smem + (size_t)CH_WAVES * NT * 64 * 16);   // [8 waves][16 rows]
+    constexpr int UT = EPI == EPI_GU ? 2 : 1;
+    const int lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int wg = blockIdx.x, G = gridDim.x;
+    const int u0 = (int)((long long)P.n_units * wg / G), u1 = (int)((long long)P.n_units * (wg + 1) / G);
+    const int t0 = u0 * UT, nt = (u1 - u0) * UT;                             // this workgroup's tiles [t0, t0 + nt), nt <= NT
+    const int ks0 = P.KS * w / CH_WAVES, ks1 = P.KS * (w + 1) / CH_WAVES;
+    const __amdgpu_buffer_rsrc_t rw = ch_rsrc(P.Wp, (size_t)P.wbytes);
+    const __amdgpu_buffer_rsrc_t ra = ch_rsrc(P.a, (size_t)2 * P.a_plane_bytes);
+    const int voff_w = lane * 16;
+    const int voff_a = t < P.M ? (4 * t + g) * 16 : CH_OOB;
+
+    // partial sums of squares of the rows behind the folded norm: wave w, lane group g take every 32nd tile.
+    // Eight independent loads per turn (a dependent chain of them would hold up the weight ring behind it).
+    float ssq = 0.f;
+    if (P.ssq_in) {
+        const __amdgpu_buffer_rsrc_t rq = ch_rsrc(P.ssq_in, (size_t)P.n_ssq * 64);
+        for (int base = 0; base < P.n_ssq; base += 8 * 4 * CH_WAVES) {
+            float sv[8];
+#pragma unroll
+            for (int n = 0; n < 8; n++) {
+                const int i = base + n * 4 * CH_WAVES + w * 4 + g;
+                sv[n] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rq, i < P.n_ssq ? (i * 16 + t) * 4 : CH_OOB, 0, 0));
+            }
+#pragma unroll
+            for (int n = 0; n < 8; n++) ssq += sv[n];
+        }
+    }
+
+    u32x4 Wr[R][NT], Ar[R][2];
+    f32x4 acc[NT];
+#pragma unroll
+    for (int j = 0; j < NT; j++) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // Every load is issued unconditionally (what must not be read gets an offset beyond the buffer), so the
+    // compiler can count the loads in flight and wait for exactly the oldest.
+#define CH_LOAD_STEP(RR, KS_AT)                                                                                       \
+    {                                                                                                                 \
+        const int ks_ = (KS_AT);                                                                                      \
+        const bool in_ = ks_ < ks1; /* uniform */                                                                     \
+        _Pragma("unroll") for (int j = 0; j < NT; j++) {                                                              \
+            const bool tv_ = in_ && j < nt;                                                                           \
+            Wr[RR][j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                              \
+                rw, tv_ ? voff_w : CH_OOB, tv_ ? ((t0 + j) * P.KS + ks_) * 1024 : 0, 2));                             \
+        }                                                                                                             \
+        Ar[RR][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, in_ ? voff_a : CH_OOB,        \
+                                                                                 in_ ? ks_ * P.mtp * 1024 : 0, 0));   \
+        Ar[RR][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                                  \
+            ra, in_ ? voff_a : CH_OOB, in_ ? P.a_plane_bytes + ks_ * P.mtp * 1024 : 0, 0));                           \
+    }
+#pragma unroll
+    for (int r = 0; r < R; r++) CH_LOAD_STEP(r, ks0 + r)
+
+    // epilogue inputs that do not depend on the sums: fetched now, used after the reduction
+    f32x4 hcur = f32x4{0.f, 0.f, 0.f, 0.f}, gcur = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (EPI == EPI_RESID && w < nt && t < P.M) {
+        const int col = (t0 + w) * 16 + 4 * g;
+        hcur = *reinterpret_cast<const f32x4 *>(P.h + (size_t)t * P.d + col);
+        gcur = *reinterpret_cast<const f32x4 *>(P.gain + col);
+    }
+    float2 cs[4] = {float2{1.f, 0.f}, float2{1.f, 0.f}, float2{1.f, 0.f}, float2{1.f, 0.f}};
+    int pos = -1;
+    if (EPI == EPI_QKV && w < nt && t < P.M) {
+        const int ti = ((t0 + w) % (P.hd / 16)) % (P.dh / 16);
+        pos = P.cache_len[t / P.m] + t % P.m;
+        if (P.rope && (t0 + w) < 2 * (P.hd / 16)) {
+#pragma unroll
+            for (int r = 0; r < 4; r++) cs[r] = P.rope[(size_t)t * (P.dh / 2) + 8 * ti + 4 * (g & 1) + r];
+        }
+    }
+    if (P.ssq_in) {
+        ssq += __shfl_xor(ssq, 16, 64);
+        ssq += __shfl_xor(ssq, 32, 64);
+        if (g == 0) rs_part[w * 16 + t] = ssq;
+    }
+
+    for (int ks = ks0; ks < ks1; ks += R) {
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+#pragma unroll
+            for (int j = 0; j < NT; j++)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Wr[r][j]),
+                                                                 __builtin_bit_cast(bf16x8, Ar[r][0]), acc[j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NT; j++)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Wr[r][j]),
+                                                                 __builtin_bit_cast(bf16x8, Ar[r][1]), acc[j], 0, 0, 0);
+            CH_LOAD_STEP(r, ks + r + R)
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#undef CH_LOAD_STEP
+#pragma unroll
+    for (int j = 0; j < NT; j++) red[(w * NT + j) * 64 + lane] = acc[j];
+    __syncthreads();
+
+    // ------------------------------------------------------------------ epilogue: wave e takes unit e
+    if (w * UT >= nt) return;
+    float rstd = 1.f;
+    if (P.ssq_in) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < CH_WAVES; i++) s += rs_part[i * 16 + t];
+        rstd = rsqrtf(s * P.inv_d + P.eps);
+    }
+    f32x4 v[UT];
+#pragma unroll
+    for (int x = 0; x < UT; x++) {
+        v[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < CH_WAVES; i++) v[x] += red[(i * NT + w * UT + x) * 64 + lane];
+        v[x] *= rstd;
+    }
+    const int T = t0 + w * UT;                                 // global index of the (first) tile
+    const bool valid = t < P.M;
+    if (EPI == EPI_RESID) {
+        const f32x4 hv = hcur + v[0];
+        float ss = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (!valid) return;
+        const int col = T * 16 + 4 * g;
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, hv), ch_rsrc(P.h, (size_t)P.M * P.d * 4),
+                                               (int)(((size_t)t * P.d + col) * 4), 0, CH_SC1);
+        const float o[4] = {hv[0] * gcur[0], hv[1] * gcur[1], hv[2] * gcur[2], hv[3] * gcur[3]};
+        store_planes4(P.out, P.out_plane_bytes, P.mtp, t, col, o);
+        if (g == 0)
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, ss), ch_rsrc(P.ssq_out, (size_t)(P.d / 16) * 64),
+                                                  (T * 16 + t) * 4, 0, CH_SC1);
+    } else if (EPI == EPI_GU) {
+        if (!valid) return;
+        float o[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const float gt = v[0][r], up = v[UT - 1][r];
+            const float a = P.gelu ? 0.5f * gt * (1.0f + tanhf(0.7978845608028654f * (gt + 0.044715f * gt * gt * gt)))
+                                   : gt / (1.0f + expf(-gt));
+            o[r] = a * up;
+        }
+        store_planes4(P.out, P.out_plane_bytes, P.mtp, t, (T / 2) * 16 + 4 * g, o);
+    } else if (EPI == EPI_LOGITS) {
+        if (!valid) return;
+        *reinterpret_cast<f32x4 *>(P.logits + (size_t)t * P.V + T * 16 + 4 * g) = v[0];
+    } else {   // EPI_QKV
+        const int tiles_per_region = P.hd / 16, tiles_per_head = P.dh / 16;
+        const int region = T / tiles_per_region, tr = T % tiles_per_region;
+        const int head = tr / tiles_per_head, ti = tr % tiles_per_head;
+        const int b = valid ? t / P.m : 0;
+        if (region < 2) {
+            // tiles of q and k hold whole rotary pairs: lane groups 0, 1 the first-half entries 8 ti .. 8 ti + 7,
+            // groups 2, 3 their partners; one exchange across the wave brings the pair together
+            float o[4];
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const float other = __shfl_xor(v[0][r], 32, 64);
+                const float c = cs[r].x, s = cs[r].y;
+                o[r] = g < 2 ? v[0][r] * c - other * s : other * s + v[0][r] * c;
+            }
+            if (!valid) return;
+            const int p0 = 16 * ti + 4 * g;                    // place inside the head, pair order
+            if (region == 0) {
+                u32x2 hi, lo;
+                split4(o, hi, lo);
+                const __amdgpu_buffer_rsrc_t rq = ch_rsrc(P.q, (size_t)2 * P.q_plane_bytes);
+                const int off = (int)(((size_t)t * P.hd + head * P.dh + p0) * 2);
+                __builtin_amdgcn_raw_buffer_store_b64(hi, rq, off, 0, CH_SC1);
+                __builtin_amdgcn_raw_buffer_store_b64(lo, rq, off + P.q_plane_bytes, 0, CH_SC1);
+            } else if (pos >= 0 && pos < P.geo.seq_pad) {
+                u32x2 kk;
+                kk[0] = pack_bf16x2(o[0], o[1]);
+                kk[1] = pack_bf16x2(o[2], o[3]);
+                // (the sequence, hence the cache region, differs from lane to lane: plain per-lane addresses)
+                *reinterpret_cast<u32x2 *>(P.kv + kv_k_off(P.geo, P.layer, b, head) + (size_t)pos * P.dh + p0) = kk;
+            }
+        } else if (valid && pos >= 0 && pos < P.geo.seq_pad) {
+            bf16_t *vc = P.kv + kv_v_off(P.geo, P.layer, b, head);
+#pragma unroll
+            for (int r = 0; r < 4; r++) vc[kv_v_idx(P.geo, 16 * ti + 4 * g + r, pos)] = f32_to_bf16(v[0][r]);
+        }
+    }
+}
+
+// Causal attention of a block of up to 16 rows over the cached prefix, one launch per layer.  A workgroup
+// of four waves takes 128 keys of one (sequence, head): each wave one 32-key tile with both products on the
+// matrix cores, transposed so that no operand passes through LDS (S^T = K q^T, O^T = V^T P^T; V is cached
+// transposed), the four softmax states are merged in LDS, and the workgroup writes one partial state per
+// chunk.  The last workgroup of a (sequence, head) to finish (an arrival counter) merges the chunks and
+// writes the rows as the O projection's input; the counter is back at zero when the kernel ends.
+#define CA_KEYS 128
+#define CA_MAX_CHUNKS 128     /* the merge keeps a weight per (chunk, row) in LDS: sequences of up to 16384 cached rows */
+template <int DH>
+__global__ __launch_bounds__(256) void kc_attn(const bf16_t *__restrict__ q, int q_plane, int m, const int32_t *__restrict__ cache_len,
+                                               KvGeom geo, int layer, const bf16_t *__restrict__ kv, float scale,
+                                               float *__restrict__ part, int chunks_max, unsigned *__restrict__ counters,
+                                               bf16_t *__restrict__ out, int out_plane_bytes, int mtp) {
+    constexpr int PS = DH + 4;                               // floats per partial row: DH outputs, max, sum, pad
+    constexpr int DT = DH / 16;
+    __shared__ __align__(16) f32x4 s_o[4][DT][64];
+    __shared__ float s_m[4][16], s_l[4][16];
+    __shared__ float s_mc[CA_MAX_CHUNKS * 16], s_lc[CA_MAX_CHUNKS * 16], s_w[CA_MAX_CHUNKS * 16];   // chunk states and weights of the merge
+    __shared__ unsigned s_old;
+    const int c = blockIdx.x, hh = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, col = lane & 15, g = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int hd = geo.H * DH;
+    const int kb = c * CA_KEYS + wv * 32;                    // this wave's 32 keys
+    // Every load is issued before the cached length is known (their addresses do not depend on it; rows past
+    // the end are masked below, rows past the cache are outside the buffer and read as zeros).
+    const size_t head_bytes = kv_head_elems(geo) * 2;
+    const __amdgpu_buffer_rsrc_t rk = ch_rsrc(kv + kv_k_off(geo, layer, b, hh), head_bytes);
+    const __amdgpu_buffer_rsrc_t rv = ch_rsrc(kv + kv_v_off(geo, layer, b, hh), head_bytes);
+    const __amdgpu_buffer_rsrc_t rqb = ch_rsrc(q, (size_t)4 * q_plane);
+    u32x4 qf[DH / 32][2], kf[2][DH / 32], vf[DT];
+#pragma unroll
+    for (int s = 0; s < DH / 32; s++) {
+        const int qo = col < m ? (int)(((size_t)(b * m + col) * hd + hh * DH + s * 32 + 8 * g) * 2) : CH_OOB;
+        qf[s][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rqb, qo, 0, 0));
+        qf[s][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rqb, qo, q_plane * 2, 0));
+    }
+    // A operands.  K: A-row r of tile T is key kb + 8 (r / 4) + 4 T + r % 4, so lane group g ends up with the
+    // scores of keys kb + 8 g .. + 7; V^T: row = feature dt * 16 + col, 8 consecutive keys per lane.
+#pragma unroll
+    for (int T = 0; T < 2; T++) {
+        const int key = kb + 8 * (col >> 2) + 4 * T + (col & 3);
+#pragma unroll
+        for (int s = 0; s < DH / 32; s++)
+            kf[T][s] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rk, (key * DH + 8 * g + s * 32) * 2, 0, 0));
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+        vf[dt] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rv, (int)(kv_v_idx(geo, dt * 16 + col, kb + 8 * g) * 2), 0, 0));
+    const int t = cache_len[b];
+    const int nk = max(0, min(t + m, geo.seq_pad));          // cache rows in play for this block
+    const int nch = (nk + CA_KEYS - 1) / CA_KEYS;
+    if (c >= nch) return;                                    // chunk past the end: not counted
+    const int qpos = t + col;                                // block row `col` sees cache rows 0 .. qpos
+    float mrun = -INFINITY, lrun = 0.f;
+    f32x4 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (kb < nk) {                                           // uniform
+        f32x4 sT[2];
+#pragma unroll
+        for (int T = 0; T < 2; T++) {
+            sT[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < DH / 32; s++) {
+                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[T][s]),
+                                                                __builtin_bit_cast(bf16x8, qf[s][0]), sT[T], 0, 0, 0);
+                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[T][s]),
+                                                                __builtin_bit_cast(bf16x8, qf[s][1]), sT[T], 0, 0, 0);
+            }
+        }
+        float sv[8], mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int key = kb + 8 * g + j;
+            sv[j] = (key <= qpos && key < nk) ? sT[j >> 2][j & 3] * scale : -INFINITY;
+            mx = fmaxf(mx, sv[j]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        float pv[8], psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            pv[j] = (sv[j] == -INFINITY) ? 0.f : expf(sv[j] - mx);
+            psum += pv[j];
+        }
+        psum += __shfl_xor(psum, 16, 64);
+        psum += __shfl_xor(psum, 32, 64);
+        mrun = mx;
+        lrun = psum;
+        u32x4 pf, pl;                                        // hi and lo planes of the probabilities
+#pragma unroll
+        for (int w2 = 0; w2 < 4; w2++) {
+            const uint32_t hpk = pack_bf16x2(pv[2 * w2], pv[2 * w2 + 1]);
+            pf[w2] = hpk;
+            pl[w2] = pack_bf16x2(pv[2 * w2] - __uint_as_float(hpk << 16), pv[2 * w2 + 1] - __uint_as_float(hpk & 0xFFFF0000u));
+        }
+        const bool tail = kb + 32 > nk;                      // rows past nk may hold anything: zero them
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++) {
+            u32x4 v = vf[dt];
+            if (tail) {
+#pragma unroll
+                for (int w2 = 0; w2 < 4; w2++) {
+                    const int k0 = kb + 8 * g + 2 * w2;
+                    v[w2] &= (k0 < nk ? 0x0000FFFFu : 0u) | (k0 + 1 < nk ? 0xFFFF0000u : 0u);
+                }
+            }
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v), __builtin_bit_cast(bf16x8, pf), oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v), __builtin_bit_cast(bf16x8, pl), oacc[dt], 0, 0, 0);
+        }
+    }
+    // ---- the four tiles of the chunk, merged in LDS; wave wv writes output tiles wv, wv + 4, ...
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) s_o[wv][dt][lane] = oacc[dt];
+    if (g == 0) {
+        s_m[wv][col] = mrun;
+        s_l[wv][col] = lrun;
+    }
+    __syncthreads();
+    float mstar = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; i++) mstar = fmaxf(mstar, s_m[i][col]);
+    float wgt[4], lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        wgt[i] = s_m[i][col] == -INFINITY ? 0.f : expf(s_m[i][col] - mstar);
+        lsum += wgt[i] * s_l[i][col];
+    }
+    float *po = part + (((size_t)b * geo.H + hh) * chunks_max + c) * 16 * PS;
+    const __amdgpu_buffer_rsrc_t rp = ch_rsrc(po, (size_t)16 * PS * 4);
+    for (int dt = wv; dt < DT; dt += 4) {
+        f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; i++) o += s_o[i][dt][lane] * wgt[i];
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rp, (col * PS + dt * 16 + 4 * g) * 4, 0, CH_SC1);
+    }
+    if (wv == 0 && g == 0) {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, mstar), rp, (col * PS + DH) * 4, 0, CH_SC1);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, lsum), rp, (col * PS + DH + 1) * 4, 0, CH_SC1);
+    }
+    // ---- arrival: the stores above are acknowledged before the counter moves
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
+    __syncthreads();
+    unsigned *cnt = counters + b * geo.H + hh;
+    if (threadIdx.x == 0) s_old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_old != (unsigned)(nch - 1)) return;
+    // ---- last to arrive: merge the chunk states of this (sequence, head).  They were written through to memory,
+    // and this compute die's L2 (emptied when the kernel started) cannot hold an older copy of them.
+    const float *pbase = part + ((size_t)b * geo.H + hh) * chunks_max * 16 * PS;
+    const __amdgpu_buffer_rsrc_t rm = ch_rsrc(pbase, (size_t)chunks_max * 16 * PS * 4);
+    // out[r][x] = sum_c weight[c][r] * acc_c[r][x] with weight[c][r] = e^(m_c - m*) / sum_c l_c e^(m_c - m*).  A thread
+    // takes feature x of every (256 / DH)-th row; the accumulators of four rows x sixteen chunks are requested
+    // together, and the first such batch before the states, so that the common case is one memory round trip.
+    const int x = threadIdx.x % DH;
+    constexpr int RG = 256 / DH;
+    const int r_first = threadIdx.x / DH;
+    float ac[4][16];
+#define CA_LOAD_ACC(R0, C0)                                                                                          \
+    _Pragma("unroll") for (int rr = 0; rr < 4; rr++) _Pragma("unroll") for (int u = 0; u < 16; u++) {                \
+        const int r_ = (R0) + rr * RG; /* (the scalar offset operand must be uniform: the per-thread part is the vector offset) */ \
+        ac[rr][u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(                                  \
+                                                  rm, (r_ < m && (C0) + u < nch) ? ((((C0) + u) * 16 + r_) * PS + x) * 4 : CH_OOB, 0, 0)); \
+    }
+    CA_LOAD_ACC(r_first, 0)
+    {
+        const int r = threadIdx.x & 15;
+        for (int cc = threadIdx.x >> 4; cc < nch; cc += 16) {
+            const int o = (cc * 16 + r) * PS * 4;
+            s_mc[cc * 16 + r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, o, DH * 4, 0));
+            s_lc[cc * 16 + r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, o, (DH + 1) * 4, 0));
+        }
+    }
+    __syncthreads();
+    {
+        const int r = threadIdx.x & 15;
+        float mst = -INFINITY;
+        for (int cc = 0; cc < nch; cc++) mst = fmaxf(mst, s_mc[cc * 16 + r]);
+        float den = 0.f;
+        for (int cc = 0; cc < nch; cc++) {
+            const float mc = s_mc[cc * 16 + r];
+            den += (mc == -INFINITY ? 0.f : expf(mc - mst)) * s_lc[cc * 16 + r];       // chunks in order
+        }
+        const float inv = den > 0.f ? 1.0f / den : 0.f;
+        for (int cc = threadIdx.x >> 4; cc < nch; cc += 16) {
+            const float mc = s_mc[cc * 16 + r];
+            s_w[cc * 16 + r] = (mc == -INFINITY ? 0.f : expf(mc - mst)) * inv;
+        }
+    }
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t ro = ch_rsrc(out, (size_t)2 * out_plane_bytes);
+    for (int r0 = r_first; r0 < m; r0 += 4 * RG) {
+        float num[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int c0 = 0; c0 < nch; c0 += 16) {
+            if (r0 != r_first || c0 != 0) CA_LOAD_ACC(r0, c0)
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++)
+#pragma unroll
+                for (int u = 0; u < 16; u++)
+                    if (r0 + rr * RG < m && c0 + u < nch) num[rr] += ac[rr][u] * s_w[(c0 + u) * 16 + r0 + rr * RG];
+        }
+#pragma unroll
+        for (int rr = 0; rr < 4; rr++) {
+            const int r = r0 + rr * RG;
+            if (r >= m) break;
+            const bf16_t hi = f32_to_bf16(num[rr]);
+            const int off = (int)(act_tiled_idx(b * m + r, hh * DH + x, mtp) * 2);
+            __builtin_amdgcn_raw_buffer_store_b16(hi, ro, off, 0, CH_SC1);
+            __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16(num[rr] - bf16_to_f32(hi)), ro, off + out_plane_bytes, 0, CH_SC1);
+        }
+    }
+#undef CA_LOAD_ACC
+    if (threadIdx.x == 0) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// h[r] = E[token[r]]; (h * gain) as the first GEMM's input, the sums of squares per 16-feature tile, and the
+// rotary table of the call's positions.  One workgroup per block row, one thread per 16-feature tile.
+__global__ __launch_bounds__(256) void kc_embed(const int32_t *__restrict__ tokens, const bf16_t *__restrict__ E, int V, int d,
+                                                const float *__restrict__ gain, float *__restrict__ h, bf16_t *__restrict__ out,
+                                                int out_plane_bytes, int mtp, float *__restrict__ ssq_out,
+                                                const int32_t *__restrict__ cache_len, int m, int dh, float theta,
+                                                float2 *__restrict__ rope) {
+    const int r = blockIdx.x;
+    const int tok = tokens[r];
+    const bool ok = tok >= 0 && tok < V;
+    for (int T = threadIdx.x; T < d / 16; T += blockDim.x) {
+        float ss = 0.f;
+#pragma unroll
+        for (int c4 = 0; c4 < 4; c4++) {
+            const int col = T * 16 + c4 * 4;
+            u32x2 e = u32x2{0u, 0u};
+            if (ok) e = *reinterpret_cast<const u32x2 *>(E + (size_t)tok * d + col);
+            const f32x4 hv = f32x4{__uint_as_float(e[0] << 16), __uint_as_float(e[0] & 0xFFFF0000u), __uint_as_float(e[1] << 16),
+                                   __uint_as_float(e[1] & 0xFFFF0000u)};
+            *reinterpret_cast<f32x4 *>(h + (size_t)r * d + col) = hv;
+            const f32x4 gv = *reinterpret_cast<const f32x4 *>(gain + col);
+            const float o[4] = {hv[0] * gv[0], hv[1] * gv[1], hv[2] * gv[2], hv[3] * gv[3]};
+            store_planes4(out, out_plane_bytes, mtp, r, col, o);
+            ss += (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
+        }
+        ssq_out[T * 16 + r] = ss;
+    }
+    if (theta > 0.f) {
+        const int pos = cache_len[r / m] + r % m, half = dh / 2;
+        for (int x = threadIdx.x; x < half; x += blockDim.x) {
+            const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
+            rope[(size_t)r * half + x] = float2{(float)cos(ang), (float)sin(ang)};
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------- host driver
+
+template <int NT, int R, int EPI>
+static hipError_t chain_allow_lds() {
+    return hipFuncSetAttribute((const void *)kc_gemm<NT, R, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               CH_WAVES * NT * 64 * 16 + CH_WAVES * 16 * 4);
+}
+
+#ifndef CH_R1
+#define CH_R1 4
+#endif
+#define CH_FOR_ALL_NT(X, EPI) X(1, CH_R1, EPI) X(2, 6, EPI) X(3, 4, EPI) X(4, 4, EPI) X(6, 2, EPI) X(8, 2, EPI)
+
+int32_t csd_chain_setup() {
+#define CH_ALLOW(NT, R, EPI) CSD_HIP((chain_allow_lds<NT, R, EPI>()));
+    CH_FOR_ALL_NT(CH_ALLOW, EPI_QKV)
+    CH_FOR_ALL_NT(CH_ALLOW, EPI_RESID)
+    CH_FOR_ALL_NT(CH_ALLOW, EPI_LOGITS)
+    CH_ALLOW(2, 6, EPI_GU) CH_ALLOW(4, 4, EPI_GU) CH_ALLOW(6, 2, EPI_GU) CH_ALLOW(8, 2, EPI_GU)
+#undef CH_ALLOW
+    return CSD_OK;
+}
+
+template <int EPI>
+static int32_t chain_launch(ChainGemm &P, int n_tiles, hipStream_t st) {
+    constexpr int UT = EPI == EPI_GU ? 2 : 1;
+    P.n_units = n_tiles / UT;
+    // a workgroup per compute unit, or as many more as keep a workgroup's tiles to eight
+    int G = P.n_units < 256 ? P.n_units : 256;
+    if ((P.n_units + G - 1) / G * UT > 8) G = (P.n_units * UT + 7) / 8;
+    const int per = (P.n_units + G - 1) / G * UT;            // most tiles of a workgroup
+#define CH_LAUNCH(NT, R, E)                                                                                       \
+    if (per <= NT) {                                                                                              \
+        hipLaunchKernelGGL((kc_gemm<NT, R, E>), dim3(G), dim3(CH_THREADS), CH_WAVES * NT * 64 * 16 + CH_WAVES * 16 * 4, st, P); \
+        return CSD_OK;                                                                                            \
+    }
+    if (EPI == EPI_GU) {
+        CH_LAUNCH(2, 6, EPI) CH_LAUNCH(4, 4, EPI) CH_LAUNCH(6, 2, EPI) CH_LAUNCH(8, 2, EPI)
+    } else {
+        CH_LAUNCH(1, CH_R1, EPI) CH_LAUNCH(2, 6, EPI) CH_LAUNCH(3, 4, EPI) CH_LAUNCH(4, 4, EPI) CH_LAUNCH(6, 2, EPI) CH_LAUNCH(8, 2, EPI)
+    }
+#undef CH_LAUNCH
+    return CSD_ESHAPE;
+}
+
+bool csd_chain_eligible(const csd_model *mod, int32_t B, int32_t m) {
+    return mod->chain_on && B * m <= 16 && mod->seq_pad <= CA_KEYS * CA_MAX_CHUNKS;
+}
+
+int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
+                              int layer, float scale, const AttnMode &mode, hipStream_t st, bf16_t *out,
+                              size_t out_plane);   // csd_attention.hip
+
+int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B, int32_t m,
+                          float *logits, hipStream_t st) {
+    const csd_model_cfg &c = mod->cfg;
+    const int M = B * m, d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab, L = c.n_layers;
+    const KvGeom geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, L, 1};
+    const int mtp = mod->act_mtp;
+    const int pb_d = (int)(mod->x_plane[0] * 2), pb_hd = (int)(mod->x_plane[1] * 2), pb_F = (int)(mod->x_plane[3] * 2);
+    bf16_t *X1 = (bf16_t *)mod->x[0], *X2 = (bf16_t *)mod->x[1], *X3 = (bf16_t *)mod->x[2], *X4 = (bf16_t *)mod->x[3];
+    float *ssq1 = mod->ssq[0], *ssq3 = mod->ssq[1];
+    const float scale = 1.0f / sqrtf((float)c.head_dim);
+    {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        hipLaunchKernelGGL(kc_embed, dim3(M), dim3(256), 0, st, tokens, (const bf16_t *)mod->embed, V, d, mod->layers[0].attn_norm,
+                           mod->h, X1, pb_d, mtp, ssq1, cache_len, m, c.head_dim, c.rope_theta, mod->rope);
+        CSD_LAUNCH_CHECK();
+    }
+    if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
+    ChainGemm base{};
+    base.mtp = mtp;
+    base.M = M;
+    base.inv_d = 1.0f / (float)d;
+    base.eps = c.rms_eps;
+    base.h = mod->h;
+    base.d = d;
+    base.m = m;
+    base.hd = hd;
+    base.dh = c.head_dim;
+    base.geo = geo;
+    base.cache_len = cache_len;
+    base.rope = c.rope_theta > 0.f ? mod->rope : nullptr;
+    base.q = (bf16_t *)mod->qbuf;
+    base.q_plane_bytes = (int)(mod->q_plane * 2);
+    base.kv = (bf16_t *)kv;
+    base.n_ssq = d / 16;
+    auto gemm = [&](const GemmW &w, const bf16_t *a, int a_plane_bytes, const float *ssq_in) {
+        ChainGemm P = base;
+        P.Wp = (const u32x4 *)w.data;
+        P.KS = w.K / 32;
+        P.wbytes = (int)((size_t)w.K * w.N * 2);
+        P.a = a;
+        P.a_plane_bytes = a_plane_bytes;
+        P.ssq_in = ssq_in;
+        return P;
+    };
+    int32_t rc;
+    for (int l = 0; l < L; l++) {
+        const LayerW &lw = mod->layers[l];
+        {
+            ProfScope ps(mod, st, CSD_PROF_GEMM);
+            ChainGemm P = gemm(lw.qkv, X1, pb_d, ssq1);
+            P.layer = l;
+            if ((rc = chain_launch<EPI_QKV>(P, lw.qkv.N / 16, st)) != CSD_OK) return rc;
+            CSD_LAUNCH_CHECK();
+        }
+        {
+            ProfScope ps(mod, st, CSD_PROF_ATTN);
+            const int chunks = (mod->seq_pad + CA_KEYS - 1) / CA_KEYS;       // chunks past a sequence's rows leave at once
+            const dim3 grid(chunks, c.n_heads, B);
+            if (c.head_dim == 128)
+                hipLaunchKernelGGL((kc_attn<128>), grid, dim3(256), 0, st, (const bf16_t *)mod->qbuf, (int)mod->q_plane, m, cache_len, geo,
+                                   l, (const bf16_t *)kv, scale, mod->attn_part, mod->attn_chunks_max, mod->attn_cnt, X2, pb_hd, mtp);
+            else
+                hipLaunchKernelGGL((kc_attn<64>), grid, dim3(256), 0, st, (const bf16_t *)mod->qbuf, (int)mod->q_plane, m, cache_len, geo,
+                                   l, (const bf16_t *)kv, scale, mod->attn_part, mod->attn_chunks_max, mod->attn_cnt, X2, pb_hd, mtp);
+            CSD_LAUNCH_CHECK();
+        }
+        {
+            ProfScope ps(mod, st, CSD_PROF_GEMM);
+            ChainGemm P = gemm(lw.o, X2, pb_hd, nullptr);
+            P.gain = lw.ffn_norm;
+            P.out = X3;
+            P.out_plane_bytes = pb_d;
+            P.ssq_out = ssq3;
+            if ((rc = chain_launch<EPI_RESID>(P, lw.o.N / 16, st)) != CSD_OK) return rc;
+            CSD_LAUNCH_CHECK();
+        }
+        {
+            ProfScope ps(mod, st, CSD_PROF_GEMM);
+            ChainGemm P = gemm(lw.gu, X3, pb_d, ssq3);
+            P.out = X4;
+            P.out_plane_bytes = pb_F;
+            if ((rc = chain_launch<EPI_GU>(P, lw.gu.N / 16, st)) != CSD_OK) return rc;
+            CSD_LAUNCH_CHECK();
+        }
+        {
+            ProfScope ps(mod, st, CSD_PROF_GEMM);
+            ChainGemm P = gemm(lw.down, X4, pb_F, nullptr);
+            P.gain = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
+            P.out = X1;
+            P.out_plane_bytes = pb_d;
+            P.ssq_out = ssq1;
+            if ((rc = chain_launch<EPI_RESID>(P, lw.down.N / 16, st)) != CSD_OK) return rc;
+            CSD_LAUNCH_CHECK();
+        }
+        if (mod->trace)
+            CSD_HIP(hipMemcpyAsync(mod->trace + (size_t)(l + 1) * M * d, mod->h, sizeof(float) * (size_t)M * d,
+                                   hipMemcpyDeviceToDevice, st));
+    }
+    {
+        ProfScope ps(mod, st, CSD_PROF_GEMM);
+        ChainGemm P = gemm(mod->lm, X1, pb_d, ssq1);
+        P.logits = logits;
+        P.V = V;
+        if ((rc = chain_launch<EPI_LOGITS>(P, mod->lm.N / 16, st)) != CSD_OK) return rc;
+        CSD_LAUNCH_CHECK();
+    }
+    (void)F;
+    return CSD_OK;
+}

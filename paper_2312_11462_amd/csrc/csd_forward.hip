@@ -802,7 +802,8 @@ static int32_t run_gemm(csd_model *mod, const GemmW &w, const void *act, int M, 
 }
 
 int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
-                              int layer, float scale, const AttnMode &mode, hipStream_t st);   // csd_attention.hip
+                              int layer, float scale, const AttnMode &mode, hipStream_t st, bf16_t *out = nullptr,
+                              size_t out_plane = 0);   // csd_attention.hip
 
 template <typename TW, typename TA, typename TC>
 static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
@@ -1028,6 +1029,7 @@ int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, con
         return forward_t5<bf16_t, float, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
     }
     if (csd_fused_eligible(mod, B, m)) return csd_fused_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
+    if (csd_chain_eligible(mod, B, m)) return csd_chain_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->cfg.dtype == CSD_DTYPE_FP32)
         return forward_typed<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->mfma) return forward_typed<bf16_t, bf16_t, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);

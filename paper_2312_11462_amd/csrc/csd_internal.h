@@ -226,6 +226,14 @@ struct csd_model {
     float *probs = nullptr;      // [m_max][V] when the caller does not want them
     float2 *rope = nullptr;      // (cos, sin) of the rotary angles of the current call [m_max][head_dim / 2]
     int attn_chunks_max = 0;
+    // the forward for blocks of up to 16 rows (csd_chain.hip): one input buffer per GEMM of a layer
+    // (two bf16 planes each, fragment order: QKV input, O input, gate|up input, down input) and the sums of
+    // squares per (16-feature tile, row) behind the two folded norms
+    bool chain_on = false;
+    void *x[4] = {nullptr, nullptr, nullptr, nullptr};
+    size_t x_plane[4] = {0, 0, 0, 0};    // elements between the hi and lo planes
+    float *ssq[2] = {nullptr, nullptr};
+    unsigned *attn_cnt = nullptr;        // arrival counters [max_batch][H] of the attention kernel: zero between launches
     // arch 1
     int enc_pad = 0;                 // encoder rows padded to 64
     float *rel_bias = nullptr;       // [32][H] fp32
@@ -252,6 +260,9 @@ struct ScratchPtrs {
     float *part, *probs;
     float2 *rope;
     float *attn_part;
+    void *x[4];
+    float *ssq[2];
+    unsigned *attn_cnt;
 };
 size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out);
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp);   // returns the pieces in use before
@@ -270,6 +281,11 @@ int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
                           int32_t m, float *logits, hipStream_t st);
 int32_t csd_fused_error(const csd_model *mod, uint32_t *flag);
 int32_t csd_fused_path(const csd_model *mod, int32_t B, int32_t m);
+// csd_chain.hip: forward for blocks of up to 16 rows, epilogues inside the GEMM kernels
+int32_t csd_chain_setup();
+bool csd_chain_eligible(const csd_model *mod, int32_t B, int32_t m);
+int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B, int32_t m,
+                          float *logits, hipStream_t st);
 // csd_accept.hip
 int32_t csd_softmax_enqueue(const float *logits, float *probs, int64_t rows, int32_t V, float temperature,
                             hipStream_t st);

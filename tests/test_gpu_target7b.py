@@ -103,7 +103,7 @@ def test_target7b_batch1_prefix1024_k5(big):
             assert gam[i] == int(np.argmax(ref[0, i]))
     # the same block on the single-launch kernel (CSD_PATH=persistent): within the same tolerance of the
     # oracle; then 30 calls in a row: same logits every time, and no device-wide barrier gave up
-    assert gm.path(1, k + 1) == 0 and gm.single.path(1, k + 1) == 2
+    assert gm.path(1, k + 1) == 3 and gm.single.path(1, k + 1) == 2
     for l in range(shape.n_layers):
         K, V = I.synthetic_kv(shape, t, seed, l, 0, device="cuda")
         gm.single.kv_write(l, 0, 0, K, V)
@@ -126,7 +126,7 @@ def test_target7b_batch8_prefix2048(big, k, oracle_b):
     shares activations through LDS (16, 40 rows) and the row-split GEMM (136 rows); one sampled sequence is
     checked against the oracle."""
     P, O, gm, om, shape, seed = big
-    assert gm.path(8, k + 1) == 0
+    assert gm.path(8, k + 1) == (3 if 8 * (k + 1) <= 16 else 0)
     t, B, m = 2048, 8, k + 1
     _fill(gm, om, shape, seed, t, B, oracle_b)
     block = I.token_ids(B * m, shape.vocab, seed, 200 + k).reshape(B, m).contiguous()

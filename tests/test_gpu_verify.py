@@ -93,19 +93,23 @@ BF128 = I.ModelShape("bf_dh128", 0, "bf16", 2, 256, 2, 128, 512, 1024)
 
 
 @pytest.mark.parametrize("gemm,attn,path", [("generic", "generic", "multikernel"), ("mfma", "generic", "multikernel"),
-                                            ("mfma", "mfma", "multikernel"), ("mfma", "mfma", "phases"),
-                                            ("mfma", "mfma", "persistent")])
+                                            ("mfma", "mfma", "multikernel"), ("mfma", "mfma", "chain"),
+                                            ("mfma", "mfma", "phases"), ("mfma", "mfma", "persistent")])
 @pytest.mark.parametrize("shape", [BF, BF128], ids=["dh64", "dh128"])
 def test_bf16_paths_small_model(shape, gemm, attn, path):
     """Several key chunks and a ragged tail (prefix 200 = 128 + 72 keys; 5 and 13 block rows);
     every forward implementation against the oracle: generic kernels, the per-operation MFMA
-    kernels, one kernel per phase, and the single-launch persistent kernel."""
+    kernels, the forward with the epilogues inside its GEMM kernels (the default for blocks of up to 16
+    rows: the 10-row block here; the 26-row block takes the per-operation kernels), one kernel per phase,
+    and the single-launch persistent kernel."""
     os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"] = gemm, attn, path
     try:
         gm, om = make_pair(shape, 7, 2, 300, 16, std=0.05)
     finally:
         del os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"]
-    assert gm.path(2, 5) == {"multikernel": 0, "phases": 1, "persistent": 2}[path]
+    assert gm.path(2, 5) == {"multikernel": 0, "phases": 1, "persistent": 2, "chain": 3}[path]
+    if gemm == "generic" or attn == "generic":
+        assert gm.path(2, 5) == 0
     toks = I.token_ids(2 * 260, shape.vocab, 7, 1).reshape(2, 260)
     prefill_both(gm, om, toks[:, :200], 16)
     e1 = _check_block(gm, om, toks[:, 200:205].numpy(), [200, 200], 2e-2, 1e-2, f"{gemm}/{attn} m=5", 5e-3)
@@ -187,7 +191,7 @@ def test_bf16_blocks_of_2_to_13_row_tiles_workgroup_tiled_gemms(B, m):
     assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("path", [None, "persistent"])
+@pytest.mark.parametrize("path", [None, "multikernel", "persistent"])
 def test_draft160m_config_synthetic_cache(path):
     """Configuration 2: 160M-shaped bf16 model, 512 cached rows (seeded stand-in K/V, since the
     oracle needs minutes to prefill them), k = 8 drafts from the Max-Gram model; on the path a model
@@ -200,7 +204,7 @@ def test_draft160m_config_synthetic_cache(path):
         gm, om = make_pair(shape, seed, 1, 640, 16)
     finally:
         os.environ.pop("CSD_PATH", None)
-    assert gm.path(1, 9) == (2 if path else 0)
+    assert gm.path(1, 9) == {None: 3, "multikernel": 0, "persistent": 2}[path]
     import_synthetic_kv(gm, om, shape, 512, seed)
     import paper_2312_11462_amd as P
     prefix = I.repeat_stream(513, shape.vocab, seed, 1)
