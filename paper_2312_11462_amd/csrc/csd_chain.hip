@@ -82,25 +82,65 @@ __device__ __forceinline__ void store_planes4(bf16_t *out, int plane_bytes, int 
     __builtin_amdgcn_raw_buffer_store_b64(lo, r, off + plane_bytes, 0, CH_SC1);
 }
 
+// This wave's share of a GEMM: the workgroup's tiles [t0, t0 + nt) (nt <= NT), the wave's k-steps [ks0, ks1).
+struct GemmShare {
+    int t0, nt, ks0, ks1;
+};
+template <int EPI>
+__device__ __forceinline__ GemmShare gemm_share(const ChainGemm &P, int wg, int G, int w) {
+    constexpr int UT = EPI == EPI_GU ? 2 : 1;
+    const int u0 = (int)((long long)P.n_units * wg / G), u1 = (int)((long long)P.n_units * (wg + 1) / G);
+    return GemmShare{u0 * UT, (u1 - u0) * UT, P.KS * w / CH_WAVES, P.KS * (w + 1) / CH_WAVES};
+}
+
+// Every load of the GEMM is issued unconditionally (what must not be read gets an offset beyond the buffer),
+// so the compiler can count the loads in flight and wait for exactly the oldest.
+template <int NT>
+__device__ __forceinline__ void gemm_load_w(u32x4 (&W)[NT], const ChainGemm &P, const GemmShare &S, __amdgpu_buffer_rsrc_t rw, int ks,
+                                            int lane) {
+    const bool in = ks < S.ks1;   // uniform
+#pragma unroll
+    for (int j = 0; j < NT; j++) {
+        const bool tv = in && j < S.nt;
+        W[j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, tv ? lane * 16 : CH_OOB,
+                                                                              tv ? ((S.t0 + j) * P.KS + ks) * 1024 : 0, 2));
+    }
+}
+__device__ __forceinline__ void gemm_load_a(u32x4 (&A)[2], const ChainGemm &P, const GemmShare &S, __amdgpu_buffer_rsrc_t ra, int ks,
+                                            int voff_a) {
+    const bool in = ks < S.ks1;   // uniform
+    A[0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, in ? voff_a : CH_OOB, in ? ks * P.mtp * 1024 : 0, 0));
+    A[1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, in ? voff_a : CH_OOB,
+                                                                          in ? P.a_plane_bytes + ks * P.mtp * 1024 : 0, 0));
+}
+
+// The first R k-steps of a wave's weight stream: they depend on nothing the other workgroups produce, so a
+// kernel that runs several GEMMs may issue them before the device-wide barrier in front of the GEMM.
+template <int NT, int R>
+__device__ __forceinline__ void gemm_prefetch(u32x4 (&Wr)[R][NT], const ChainGemm &P, const GemmShare &S) {
+    const __amdgpu_buffer_rsrc_t rw = ch_rsrc(P.Wp, (size_t)P.wbytes);
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int r = 0; r < R; r++) gemm_load_w<NT>(Wr[r], P, S, rw, S.ks0 + r, lane);
+}
+
+// The GEMM of one workgroup after gemm_prefetch: the wave's k-steps through the rings, the eight partial
+// tiles added in LDS in wave order, the epilogue.  LDS: red [8 waves][NT][64 lanes] 16-byte words, then
+// [8 waves][16 rows] floats.  Every wave of the workgroup must call it (it holds a workgroup barrier).
 template <int NT, int R, int EPI>
-__global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
-    extern __shared__ __align__(16) char ch_smem[];
-    f32x4 *red = reinterpret_cast<f32x4 *>(ch_smem);                          // [8 waves][NT][64 lanes]
-    float *rs_part = reinterpret_cast<float *>(ch_smem + (size_t)CH_WAVES * NT * 64 * 16);   // [8 waves][16 rows]
+__device__ __forceinline__ void gemm_run(u32x4 (&Wr)[R][NT], const ChainGemm &P, const GemmShare &S, char *smem) {
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+    float *rs_part = reinterpret_cast<float *>(smem + (size_t)CH_WAVES * NT * 64 * 16);
     constexpr int UT = EPI == EPI_GU ? 2 : 1;
     const int lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int wg = blockIdx.x, G = gridDim.x;
-    const int u0 = (int)((long long)P.n_units * wg / G), u1 = (int)((long long)P.n_units * (wg + 1) / G);
-    const int t0 = u0 * UT, nt = (u1 - u0) * UT;                             // this workgroup's tiles [t0, t0 + nt), nt <= NT
-    const int ks0 = P.KS * w / CH_WAVES, ks1 = P.KS * (w + 1) / CH_WAVES;
+    const int t0 = S.t0, nt = S.nt, ks0 = S.ks0, ks1 = S.ks1;
     const __amdgpu_buffer_rsrc_t rw = ch_rsrc(P.Wp, (size_t)P.wbytes);
     const __amdgpu_buffer_rsrc_t ra = ch_rsrc(P.a, (size_t)2 * P.a_plane_bytes);
-    const int voff_w = lane * 16;
     const int voff_a = t < P.M ? (4 * t + g) * 16 : CH_OOB;
 
     // partial sums of squares of the rows behind the folded norm: wave w, lane group g take every 32nd tile.
-    // Eight independent loads per turn (a dependent chain of them would hold up the weight ring behind it).
+    // Eight independent loads per turn (a dependent chain of them would hold up the rings behind it).
     float ssq = 0.f;
     if (P.ssq_in) {
         const __amdgpu_buffer_rsrc_t rq = ch_rsrc(P.ssq_in, (size_t)P.n_ssq * 64);
@@ -115,35 +155,19 @@ __global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
             for (int n = 0; n < 8; n++) ssq += sv[n];
         }
     }
-
-    u32x4 Wr[R][NT], Ar[R][2];
+    u32x4 Ar[R][2];
     f32x4 acc[NT];
 #pragma unroll
     for (int j = 0; j < NT; j++) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // Every load is issued unconditionally (what must not be read gets an offset beyond the buffer), so the
-    // compiler can count the loads in flight and wait for exactly the oldest.
-#define CH_LOAD_STEP(RR, KS_AT)                                                                                       \
-    {                                                                                                                 \
-        const int ks_ = (KS_AT);                                                                                      \
-        const bool in_ = ks_ < ks1; /* uniform */                                                                     \
-        _Pragma("unroll") for (int j = 0; j < NT; j++) {                                                              \
-            const bool tv_ = in_ && j < nt;                                                                           \
-            Wr[RR][j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                              \
-                rw, tv_ ? voff_w : CH_OOB, tv_ ? ((t0 + j) * P.KS + ks_) * 1024 : 0, 2));                             \
-        }                                                                                                             \
-        Ar[RR][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, in_ ? voff_a : CH_OOB,        \
-                                                                                 in_ ? ks_ * P.mtp * 1024 : 0, 0));   \
-        Ar[RR][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                                  \
-            ra, in_ ? voff_a : CH_OOB, in_ ? P.a_plane_bytes + ks_ * P.mtp * 1024 : 0, 0));                           \
-    }
 #pragma unroll
-    for (int r = 0; r < R; r++) CH_LOAD_STEP(r, ks0 + r)
+    for (int r = 0; r < R; r++) gemm_load_a(Ar[r], P, S, ra, ks0 + r, voff_a);
 
     // epilogue inputs that do not depend on the sums: fetched now, used after the reduction
     f32x4 hcur = f32x4{0.f, 0.f, 0.f, 0.f}, gcur = f32x4{0.f, 0.f, 0.f, 0.f};
     if (EPI == EPI_RESID && w < nt && t < P.M) {
         const int col = (t0 + w) * 16 + 4 * g;
-        hcur = *reinterpret_cast<const f32x4 *>(P.h + (size_t)t * P.d + col);
+        hcur = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ch_rsrc(P.h, (size_t)P.M * P.d * 4),
+                                                                              (int)(((size_t)t * P.d + col) * 4), 0, 0));
         gcur = *reinterpret_cast<const f32x4 *>(P.gain + col);
     }
     float2 cs[4] = {float2{1.f, 0.f}, float2{1.f, 0.f}, float2{1.f, 0.f}, float2{1.f, 0.f}};
@@ -173,11 +197,11 @@ __global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
             for (int j = 0; j < NT; j++)
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Wr[r][j]),
                                                                  __builtin_bit_cast(bf16x8, Ar[r][1]), acc[j], 0, 0, 0);
-            CH_LOAD_STEP(r, ks + r + R)
+            gemm_load_w<NT>(Wr[r], P, S, rw, ks + r + R, lane);
+            gemm_load_a(Ar[r], P, S, ra, ks + r + R, voff_a);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-#undef CH_LOAD_STEP
 #pragma unroll
     for (int j = 0; j < NT; j++) red[(w * NT + j) * 64 + lane] = acc[j];
     __syncthreads();
@@ -257,15 +281,31 @@ __global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
                 u32x2 kk;
                 kk[0] = pack_bf16x2(o[0], o[1]);
                 kk[1] = pack_bf16x2(o[2], o[3]);
-                // (the sequence, hence the cache region, differs from lane to lane: plain per-lane addresses)
-                *reinterpret_cast<u32x2 *>(P.kv + kv_k_off(P.geo, P.layer, b, head) + (size_t)pos * P.dh + p0) = kk;
+                // (the sequence, hence the head's region, differs from lane to lane: one descriptor for the layer's
+                // keys, the rest in the per-lane offset; written through, the attention step may run on another die)
+                const size_t he = kv_head_elems(P.geo);
+                __builtin_amdgcn_raw_buffer_store_b64(kk, ch_rsrc(P.kv + kv_k_off(P.geo, P.layer, 0, 0), (size_t)P.geo.Bmax * P.geo.H * he * 2),
+                                                      (int)((((size_t)b * P.geo.H + head) * he + (size_t)pos * P.dh + p0) * 2), 0, CH_SC1);
             }
         } else if (valid && pos >= 0 && pos < P.geo.seq_pad) {
-            bf16_t *vc = P.kv + kv_v_off(P.geo, P.layer, b, head);
+            const size_t he = kv_head_elems(P.geo);
+            const __amdgpu_buffer_rsrc_t rv = ch_rsrc(P.kv + kv_v_off(P.geo, P.layer, 0, 0), (size_t)P.geo.Bmax * P.geo.H * he * 2);
 #pragma unroll
-            for (int r = 0; r < 4; r++) vc[kv_v_idx(P.geo, 16 * ti + 4 * g + r, pos)] = f32_to_bf16(v[0][r]);
+            for (int r = 0; r < 4; r++)
+                __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16(v[0][r]), rv,
+                                                      (int)((((size_t)b * P.geo.H + head) * he + kv_v_idx(P.geo, 16 * ti + 4 * g + r, pos)) * 2), 0,
+                                                      CH_SC1);
         }
     }
+}
+
+template <int NT, int R, int EPI>
+__global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
+    extern __shared__ __align__(16) char ch_smem[];
+    const GemmShare S = gemm_share<EPI>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)));
+    u32x4 Wr[R][NT];
+    gemm_prefetch<NT, R>(Wr, P, S);
+    gemm_run<NT, R, EPI>(Wr, P, S, ch_smem);
 }
 
 // Causal attention of a block of up to 16 rows over the cached prefix, one launch per layer.  A workgroup
@@ -276,34 +316,53 @@ __global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
 // writes the rows as the O projection's input; the counter is back at zero when the kernel ends.
 #define CA_KEYS 128
 #define CA_MAX_CHUNKS 128     /* the merge keeps a weight per (chunk, row) in LDS: sequences of up to 16384 cached rows */
+struct AttnArgs {
+    const bf16_t *q;          // rotated queries, two row-major planes [..][hd]
+    int q_plane, m;
+    const int32_t *cache_len;
+    KvGeom geo;
+    int layer;
+    const bf16_t *kv;
+    float scale;
+    float *part;              // chunk states [B][H][chunks_max][16 rows][DH + 4]
+    int chunks_max;
+    unsigned *counters;       // arrivals per (sequence, head): zero between launches
+    bf16_t *out;              // merged rows: the O projection's input planes, fragment order
+    int out_plane_bytes, mtp;
+};
 template <int DH>
-__global__ __launch_bounds__(256) void kc_attn(const bf16_t *__restrict__ q, int q_plane, int m, const int32_t *__restrict__ cache_len,
-                                               KvGeom geo, int layer, const bf16_t *__restrict__ kv, float scale,
-                                               float *__restrict__ part, int chunks_max, unsigned *__restrict__ counters,
-                                               bf16_t *__restrict__ out, int out_plane_bytes, int mtp) {
+struct AttnLds {
+    f32x4 o[4][DH / 16][64];
+    float m[4][16], l[4][16];
+    float mc[CA_MAX_CHUNKS * 16], lc[CA_MAX_CHUNKS * 16], w[CA_MAX_CHUNKS * 16];   // chunk states and weights of the merge
+    unsigned old;
+    unsigned pad[3];
+};
+
+// One chunk of one (sequence, head) by a group of four waves (gtid = thread index in the group, 0 .. 255).
+// Holds five workgroup barriers whatever `have` says, so groups with and without an item stay in step.
+template <int DH>
+__device__ __forceinline__ void attn_item(const AttnArgs &A, AttnLds<DH> &L, bool have, int c, int hh, int b, int gtid) {
     constexpr int PS = DH + 4;                               // floats per partial row: DH outputs, max, sum, pad
     constexpr int DT = DH / 16;
-    __shared__ __align__(16) f32x4 s_o[4][DT][64];
-    __shared__ float s_m[4][16], s_l[4][16];
-    __shared__ float s_mc[CA_MAX_CHUNKS * 16], s_lc[CA_MAX_CHUNKS * 16], s_w[CA_MAX_CHUNKS * 16];   // chunk states and weights of the merge
-    __shared__ unsigned s_old;
-    const int c = blockIdx.x, hh = blockIdx.y, b = blockIdx.z;
-    const int lane = threadIdx.x & 63, col = lane & 15, g = lane >> 4;
-    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const KvGeom &geo = A.geo;
+    const int m = A.m;
+    const int lane = gtid & 63, col = lane & 15, g = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(gtid >> 6);
     const int hd = geo.H * DH;
     const int kb = c * CA_KEYS + wv * 32;                    // this wave's 32 keys
     // Every load is issued before the cached length is known (their addresses do not depend on it; rows past
     // the end are masked below, rows past the cache are outside the buffer and read as zeros).
-    const size_t head_bytes = kv_head_elems(geo) * 2;
-    const __amdgpu_buffer_rsrc_t rk = ch_rsrc(kv + kv_k_off(geo, layer, b, hh), head_bytes);
-    const __amdgpu_buffer_rsrc_t rv = ch_rsrc(kv + kv_v_off(geo, layer, b, hh), head_bytes);
-    const __amdgpu_buffer_rsrc_t rqb = ch_rsrc(q, (size_t)4 * q_plane);
+    const size_t head_bytes = have ? kv_head_elems(geo) * 2 : 0;
+    const __amdgpu_buffer_rsrc_t rk = ch_rsrc(A.kv + kv_k_off(geo, A.layer, b, hh), head_bytes);
+    const __amdgpu_buffer_rsrc_t rv = ch_rsrc(A.kv + kv_v_off(geo, A.layer, b, hh), head_bytes);
+    const __amdgpu_buffer_rsrc_t rqb = ch_rsrc(A.q, have ? (size_t)4 * A.q_plane : 0);
     u32x4 qf[DH / 32][2], kf[2][DH / 32], vf[DT];
 #pragma unroll
     for (int s = 0; s < DH / 32; s++) {
         const int qo = col < m ? (int)(((size_t)(b * m + col) * hd + hh * DH + s * 32 + 8 * g) * 2) : CH_OOB;
         qf[s][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rqb, qo, 0, 0));
-        qf[s][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rqb, qo, q_plane * 2, 0));
+        qf[s][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rqb, qo, A.q_plane * 2, 0));
     }
     // A operands.  K: A-row r of tile T is key kb + 8 (r / 4) + 4 T + r % 4, so lane group g ends up with the
     // scores of keys kb + 8 g .. + 7; V^T: row = feature dt * 16 + col, 8 consecutive keys per lane.
@@ -317,16 +376,16 @@ __global__ __launch_bounds__(256) void kc_attn(const bf16_t *__restrict__ q, int
 #pragma unroll
     for (int dt = 0; dt < DT; dt++)
         vf[dt] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rv, (int)(kv_v_idx(geo, dt * 16 + col, kb + 8 * g) * 2), 0, 0));
-    const int t = cache_len[b];
+    const int t = have ? A.cache_len[b] : 0;
     const int nk = max(0, min(t + m, geo.seq_pad));          // cache rows in play for this block
     const int nch = (nk + CA_KEYS - 1) / CA_KEYS;
-    if (c >= nch) return;                                    // chunk past the end: not counted
+    const bool active = have && c < nch;                     // a chunk past the end is not counted
     const int qpos = t + col;                                // block row `col` sees cache rows 0 .. qpos
     float mrun = -INFINITY, lrun = 0.f;
     f32x4 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; dt++) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (kb < nk) {                                           // uniform
+    if (active && kb < nk) {                                 // uniform over the wave
         f32x4 sT[2];
 #pragma unroll
         for (int T = 0; T < 2; T++) {
@@ -343,7 +402,7 @@ __global__ __launch_bounds__(256) void kc_attn(const bf16_t *__restrict__ q, int
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const int key = kb + 8 * g + j;
-            sv[j] = (key <= qpos && key < nk) ? sT[j >> 2][j & 3] * scale : -INFINITY;
+            sv[j] = (key <= qpos && key < nk) ? sT[j >> 2][j & 3] * A.scale : -INFINITY;
             mx = fmaxf(mx, sv[j]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -382,50 +441,52 @@ __global__ __launch_bounds__(256) void kc_attn(const bf16_t *__restrict__ q, int
     }
     // ---- the four tiles of the chunk, merged in LDS; wave wv writes output tiles wv, wv + 4, ...
 #pragma unroll
-    for (int dt = 0; dt < DT; dt++) s_o[wv][dt][lane] = oacc[dt];
+    for (int dt = 0; dt < DT; dt++) L.o[wv][dt][lane] = oacc[dt];
     if (g == 0) {
-        s_m[wv][col] = mrun;
-        s_l[wv][col] = lrun;
+        L.m[wv][col] = mrun;
+        L.l[wv][col] = lrun;
     }
     __syncthreads();
-    float mstar = -INFINITY;
+    if (active) {
+        float mstar = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < 4; i++) mstar = fmaxf(mstar, s_m[i][col]);
-    float wgt[4], lsum = 0.f;
+        for (int i = 0; i < 4; i++) mstar = fmaxf(mstar, L.m[i][col]);
+        float wgt[4], lsum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        wgt[i] = s_m[i][col] == -INFINITY ? 0.f : expf(s_m[i][col] - mstar);
-        lsum += wgt[i] * s_l[i][col];
-    }
-    float *po = part + (((size_t)b * geo.H + hh) * chunks_max + c) * 16 * PS;
-    const __amdgpu_buffer_rsrc_t rp = ch_rsrc(po, (size_t)16 * PS * 4);
-    for (int dt = wv; dt < DT; dt += 4) {
-        f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < 4; i++) {
+            wgt[i] = L.m[i][col] == -INFINITY ? 0.f : expf(L.m[i][col] - mstar);
+            lsum += wgt[i] * L.l[i][col];
+        }
+        float *po = A.part + (((size_t)b * geo.H + hh) * A.chunks_max + c) * 16 * PS;
+        const __amdgpu_buffer_rsrc_t rp = ch_rsrc(po, (size_t)16 * PS * 4);
+        for (int dt = wv; dt < DT; dt += 4) {
+            f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 4; i++) o += s_o[i][dt][lane] * wgt[i];
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rp, (col * PS + dt * 16 + 4 * g) * 4, 0, CH_SC1);
-    }
-    if (wv == 0 && g == 0) {
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, mstar), rp, (col * PS + DH) * 4, 0, CH_SC1);
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, lsum), rp, (col * PS + DH + 1) * 4, 0, CH_SC1);
+            for (int i = 0; i < 4; i++) o += L.o[i][dt][lane] * wgt[i];
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rp, (col * PS + dt * 16 + 4 * g) * 4, 0, CH_SC1);
+        }
+        if (wv == 0 && g == 0) {
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, mstar), rp, (col * PS + DH) * 4, 0, CH_SC1);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, lsum), rp, (col * PS + DH + 1) * 4, 0, CH_SC1);
+        }
     }
     // ---- arrival: the stores above are acknowledged before the counter moves
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
     __syncthreads();
-    unsigned *cnt = counters + b * geo.H + hh;
-    if (threadIdx.x == 0) s_old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned *cnt = A.counters + b * geo.H + hh;
+    if (gtid == 0) L.old = active ? __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xFFFFFFFFu;
     __syncthreads();
-    if (s_old != (unsigned)(nch - 1)) return;
     // ---- last to arrive: merge the chunk states of this (sequence, head).  They were written through to memory,
     // and this compute die's L2 (emptied when the kernel started) cannot hold an older copy of them.
-    const float *pbase = part + ((size_t)b * geo.H + hh) * chunks_max * 16 * PS;
-    const __amdgpu_buffer_rsrc_t rm = ch_rsrc(pbase, (size_t)chunks_max * 16 * PS * 4);
+    const bool last = active && L.old == (unsigned)(nch - 1);
+    const float *pbase = A.part + ((size_t)b * geo.H + hh) * A.chunks_max * 16 * PS;
+    const __amdgpu_buffer_rsrc_t rm = ch_rsrc(pbase, last ? (size_t)A.chunks_max * 16 * PS * 4 : 0);
     // out[r][x] = sum_c weight[c][r] * acc_c[r][x] with weight[c][r] = e^(m_c - m*) / sum_c l_c e^(m_c - m*).  A thread
     // takes feature x of every (256 / DH)-th row; the accumulators of four rows x sixteen chunks are requested
     // together, and the first such batch before the states, so that the common case is one memory round trip.
-    const int x = threadIdx.x % DH;
+    const int x = gtid % DH;
     constexpr int RG = 256 / DH;
-    const int r_first = threadIdx.x / DH;
+    const int r_first = gtid / DH;
     float ac[4][16];
 #define CA_LOAD_ACC(R0, C0)                                                                                          \
     _Pragma("unroll") for (int rr = 0; rr < 4; rr++) _Pragma("unroll") for (int u = 0; u < 16; u++) {                \
@@ -433,55 +494,69 @@ __global__ __launch_bounds__(256) void kc_attn(const bf16_t *__restrict__ q, int
         ac[rr][u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(                                  \
                                                   rm, (r_ < m && (C0) + u < nch) ? ((((C0) + u) * 16 + r_) * PS + x) * 4 : CH_OOB, 0, 0)); \
     }
-    CA_LOAD_ACC(r_first, 0)
-    {
-        const int r = threadIdx.x & 15;
-        for (int cc = threadIdx.x >> 4; cc < nch; cc += 16) {
+    if (last) {
+        CA_LOAD_ACC(r_first, 0)
+        const int r = gtid & 15;
+        for (int cc = gtid >> 4; cc < nch; cc += 16) {
             const int o = (cc * 16 + r) * PS * 4;
-            s_mc[cc * 16 + r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, o, DH * 4, 0));
-            s_lc[cc * 16 + r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, o, (DH + 1) * 4, 0));
+            L.mc[cc * 16 + r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, o, DH * 4, 0));
+            L.lc[cc * 16 + r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, o, (DH + 1) * 4, 0));
         }
     }
     __syncthreads();
-    {
-        const int r = threadIdx.x & 15;
+    if (last) {
+        const int r = gtid & 15;
         float mst = -INFINITY;
-        for (int cc = 0; cc < nch; cc++) mst = fmaxf(mst, s_mc[cc * 16 + r]);
+        for (int cc = 0; cc < nch; cc++) mst = fmaxf(mst, L.mc[cc * 16 + r]);
         float den = 0.f;
         for (int cc = 0; cc < nch; cc++) {
-            const float mc = s_mc[cc * 16 + r];
-            den += (mc == -INFINITY ? 0.f : expf(mc - mst)) * s_lc[cc * 16 + r];       // chunks in order
+            const float mc = L.mc[cc * 16 + r];
+            den += (mc == -INFINITY ? 0.f : expf(mc - mst)) * L.lc[cc * 16 + r];       // chunks in order
         }
         const float inv = den > 0.f ? 1.0f / den : 0.f;
-        for (int cc = threadIdx.x >> 4; cc < nch; cc += 16) {
-            const float mc = s_mc[cc * 16 + r];
-            s_w[cc * 16 + r] = (mc == -INFINITY ? 0.f : expf(mc - mst)) * inv;
+        for (int cc = gtid >> 4; cc < nch; cc += 16) {
+            const float mc = L.mc[cc * 16 + r];
+            L.w[cc * 16 + r] = (mc == -INFINITY ? 0.f : expf(mc - mst)) * inv;
         }
     }
     __syncthreads();
-    const __amdgpu_buffer_rsrc_t ro = ch_rsrc(out, (size_t)2 * out_plane_bytes);
-    for (int r0 = r_first; r0 < m; r0 += 4 * RG) {
-        float num[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int c0 = 0; c0 < nch; c0 += 16) {
-            if (r0 != r_first || c0 != 0) CA_LOAD_ACC(r0, c0)
+    if (last) {
+        const __amdgpu_buffer_rsrc_t ro = ch_rsrc(A.out, (size_t)2 * A.out_plane_bytes);
+        for (int r0 = r_first; r0 < m; r0 += 4 * RG) {
+            float num[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c0 = 0; c0 < nch; c0 += 16) {
+                if (r0 != r_first || c0 != 0) CA_LOAD_ACC(r0, c0)
 #pragma unroll
-            for (int rr = 0; rr < 4; rr++)
+                for (int rr = 0; rr < 4; rr++)
 #pragma unroll
-                for (int u = 0; u < 16; u++)
-                    if (r0 + rr * RG < m && c0 + u < nch) num[rr] += ac[rr][u] * s_w[(c0 + u) * 16 + r0 + rr * RG];
+                    for (int u = 0; u < 16; u++)
+                        if (r0 + rr * RG < m && c0 + u < nch) num[rr] += ac[rr][u] * L.w[(c0 + u) * 16 + r0 + rr * RG];
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++) {
+                const int r = r0 + rr * RG;
+                if (r >= m) break;
+                const bf16_t hi = f32_to_bf16(num[rr]);
+                const int off = (int)(act_tiled_idx(b * m + r, hh * DH + x, A.mtp) * 2);
+                __builtin_amdgcn_raw_buffer_store_b16(hi, ro, off, 0, CH_SC1);
+                __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16(num[rr] - bf16_to_f32(hi)), ro, off + A.out_plane_bytes, 0, CH_SC1);
+            }
         }
-#pragma unroll
-        for (int rr = 0; rr < 4; rr++) {
-            const int r = r0 + rr * RG;
-            if (r >= m) break;
-            const bf16_t hi = f32_to_bf16(num[rr]);
-            const int off = (int)(act_tiled_idx(b * m + r, hh * DH + x, mtp) * 2);
-            __builtin_amdgcn_raw_buffer_store_b16(hi, ro, off, 0, CH_SC1);
-            __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16(num[rr] - bf16_to_f32(hi)), ro, off + out_plane_bytes, 0, CH_SC1);
-        }
+        if (gtid == 0) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 #undef CA_LOAD_ACC
-    if (threadIdx.x == 0) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Causal attention of a block of up to 16 rows over the cached prefix, one launch per layer.  A workgroup
+// of four waves takes 128 keys of one (sequence, head): each wave one 32-key tile with both products on the
+// matrix cores, transposed so that no operand passes through LDS (S^T = K q^T, O^T = V^T P^T; V is cached
+// transposed), the four softmax states are merged in LDS, and the workgroup writes one partial state per
+// chunk.  The last workgroup of a (sequence, head) to finish (an arrival counter) merges the chunks and
+// writes the rows as the O projection's input; the counter is back at zero when the kernel ends.
+template <int DH>
+__global__ __launch_bounds__(256) void kc_attn(const AttnArgs A) {
+    __shared__ __align__(16) AttnLds<DH> L;
+    attn_item<DH>(A, L, true, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
 }
 
 // h[r] = E[token[r]]; (h * gain) as the first GEMM's input, the sums of squares per 16-feature tile, and the
@@ -550,6 +625,10 @@ static int32_t chain_launch(ChainGemm &P, int n_tiles, hipStream_t st) {
     // a workgroup per compute unit, or as many more as keep a workgroup's tiles to eight
     int G = P.n_units < 256 ? P.n_units : 256;
     if ((P.n_units + G - 1) / G * UT > 8) G = (P.n_units * UT + 7) / 8;
+    if (const char *e = getenv("CSD_CHAIN_UPW")) {      // experiment: units per workgroup by kind of GEMM (digits: qkv, resid, gu, logits)
+        const int upw = e[EPI] - '0';
+        if (upw > 0) G = (P.n_units + upw - 1) / upw;
+    }
     const int per = (P.n_units + G - 1) / G * UT;            // most tiles of a workgroup
 #define CH_LAUNCH(NT, R, E)                                                                                       \
     if (per <= NT) {                                                                                              \
@@ -566,7 +645,9 @@ static int32_t chain_launch(ChainGemm &P, int n_tiles, hipStream_t st) {
 }
 
 bool csd_chain_eligible(const csd_model *mod, int32_t B, int32_t m) {
-    return mod->chain_on && B * m <= 16 && mod->seq_pad <= CA_KEYS * CA_MAX_CHUNKS;
+    // (the cache appends address a layer's keys, or values, through one 32-bit offset)
+    const size_t layer_kv = (size_t)mod->cfg.max_batch * mod->cfg.n_heads * mod->seq_pad * mod->cfg.head_dim * 2;
+    return mod->chain_on && B * m <= 16 && mod->seq_pad <= CA_KEYS * CA_MAX_CHUNKS && layer_kv < (1ull << 31);
 }
 
 int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
@@ -617,55 +698,59 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
         P.ssq_in = ssq_in;
         return P;
     };
+    const AttnArgs attn{(const bf16_t *)mod->qbuf, (int)mod->q_plane, m, cache_len, geo, 0, (const bf16_t *)kv, scale, mod->attn_part,
+                        mod->attn_chunks_max, mod->attn_cnt, X2, pb_hd, mtp};
     int32_t rc;
     for (int l = 0; l < L; l++) {
         const LayerW &lw = mod->layers[l];
+        ChainGemm Pq = gemm(lw.qkv, X1, pb_d, ssq1);
+        Pq.layer = l;
+        ChainGemm Po = gemm(lw.o, X2, pb_hd, nullptr);
+        Po.gain = lw.ffn_norm;
+        Po.out = X3;
+        Po.out_plane_bytes = pb_d;
+        Po.ssq_out = ssq3;
+        ChainGemm Pg = gemm(lw.gu, X3, pb_d, ssq3);
+        Pg.out = X4;
+        Pg.out_plane_bytes = pb_F;
+        ChainGemm Pd = gemm(lw.down, X4, pb_F, nullptr);
+        Pd.gain = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
+        Pd.out = X1;
+        Pd.out_plane_bytes = pb_d;
+        Pd.ssq_out = ssq1;
+        AttnArgs A = attn;
+        A.layer = l;
+        const int chunks = (mod->seq_pad + CA_KEYS - 1) / CA_KEYS;           // chunk slots; those past a sequence's rows leave at once
         {
-            ProfScope ps(mod, st, CSD_PROF_GEMM);
-            ChainGemm P = gemm(lw.qkv, X1, pb_d, ssq1);
-            P.layer = l;
-            if ((rc = chain_launch<EPI_QKV>(P, lw.qkv.N / 16, st)) != CSD_OK) return rc;
-            CSD_LAUNCH_CHECK();
-        }
-        {
-            ProfScope ps(mod, st, CSD_PROF_ATTN);
-            const int chunks = (mod->seq_pad + CA_KEYS - 1) / CA_KEYS;       // chunks past a sequence's rows leave at once
-            const dim3 grid(chunks, c.n_heads, B);
-            if (c.head_dim == 128)
-                hipLaunchKernelGGL((kc_attn<128>), grid, dim3(256), 0, st, (const bf16_t *)mod->qbuf, (int)mod->q_plane, m, cache_len, geo,
-                                   l, (const bf16_t *)kv, scale, mod->attn_part, mod->attn_chunks_max, mod->attn_cnt, X2, pb_hd, mtp);
-            else
-                hipLaunchKernelGGL((kc_attn<64>), grid, dim3(256), 0, st, (const bf16_t *)mod->qbuf, (int)mod->q_plane, m, cache_len, geo,
-                                   l, (const bf16_t *)kv, scale, mod->attn_part, mod->attn_chunks_max, mod->attn_cnt, X2, pb_hd, mtp);
-            CSD_LAUNCH_CHECK();
-        }
-        {
-            ProfScope ps(mod, st, CSD_PROF_GEMM);
-            ChainGemm P = gemm(lw.o, X2, pb_hd, nullptr);
-            P.gain = lw.ffn_norm;
-            P.out = X3;
-            P.out_plane_bytes = pb_d;
-            P.ssq_out = ssq3;
-            if ((rc = chain_launch<EPI_RESID>(P, lw.o.N / 16, st)) != CSD_OK) return rc;
-            CSD_LAUNCH_CHECK();
-        }
-        {
-            ProfScope ps(mod, st, CSD_PROF_GEMM);
-            ChainGemm P = gemm(lw.gu, X3, pb_d, ssq3);
-            P.out = X4;
-            P.out_plane_bytes = pb_F;
-            if ((rc = chain_launch<EPI_GU>(P, lw.gu.N / 16, st)) != CSD_OK) return rc;
-            CSD_LAUNCH_CHECK();
-        }
-        {
-            ProfScope ps(mod, st, CSD_PROF_GEMM);
-            ChainGemm P = gemm(lw.down, X4, pb_F, nullptr);
-            P.gain = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
-            P.out = X1;
-            P.out_plane_bytes = pb_d;
-            P.ssq_out = ssq1;
-            if ((rc = chain_launch<EPI_RESID>(P, lw.down.N / 16, st)) != CSD_OK) return rc;
-            CSD_LAUNCH_CHECK();
+            {
+                ProfScope ps(mod, st, CSD_PROF_GEMM);
+                if ((rc = chain_launch<EPI_QKV>(Pq, lw.qkv.N / 16, st)) != CSD_OK) return rc;
+                CSD_LAUNCH_CHECK();
+            }
+            {
+                ProfScope ps(mod, st, CSD_PROF_ATTN);
+                const dim3 grid(chunks, c.n_heads, B);
+                if (c.head_dim == 128)
+                    hipLaunchKernelGGL((kc_attn<128>), grid, dim3(256), 0, st, A);
+                else
+                    hipLaunchKernelGGL((kc_attn<64>), grid, dim3(256), 0, st, A);
+                CSD_LAUNCH_CHECK();
+            }
+            {
+                ProfScope ps(mod, st, CSD_PROF_GEMM);
+                if ((rc = chain_launch<EPI_RESID>(Po, lw.o.N / 16, st)) != CSD_OK) return rc;
+                CSD_LAUNCH_CHECK();
+            }
+            {
+                ProfScope ps(mod, st, CSD_PROF_GEMM);
+                if ((rc = chain_launch<EPI_GU>(Pg, lw.gu.N / 16, st)) != CSD_OK) return rc;
+                CSD_LAUNCH_CHECK();
+            }
+            {
+                ProfScope ps(mod, st, CSD_PROF_GEMM);
+                if ((rc = chain_launch<EPI_RESID>(Pd, lw.down.N / 16, st)) != CSD_OK) return rc;
+                CSD_LAUNCH_CHECK();
+            }
         }
         if (mod->trace)
             CSD_HIP(hipMemcpyAsync(mod->trace + (size_t)(l + 1) * M * d, mod->h, sizeof(float) * (size_t)M * d,

@@ -283,6 +283,7 @@ int32_t csd_fused_error(const csd_model *mod, uint32_t *flag);
 int32_t csd_fused_path(const csd_model *mod, int32_t B, int32_t m);
 // csd_chain.hip: forward for blocks of up to 16 rows, epilogues inside the GEMM kernels
 int32_t csd_chain_setup();
+
 bool csd_chain_eligible(const csd_model *mod, int32_t B, int32_t m);
 int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B, int32_t m,
                           float *logits, hipStream_t st);

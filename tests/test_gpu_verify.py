@@ -99,9 +99,9 @@ BF128 = I.ModelShape("bf_dh128", 0, "bf16", 2, 256, 2, 128, 512, 1024)
 def test_bf16_paths_small_model(shape, gemm, attn, path):
     """Several key chunks and a ragged tail (prefix 200 = 128 + 72 keys; 5 and 13 block rows);
     every forward implementation against the oracle: generic kernels, the per-operation MFMA
-    kernels, the forward with the epilogues inside its GEMM kernels (the default for blocks of up to 16
-    rows: the 10-row block here; the 26-row block takes the per-operation kernels), one kernel per phase,
-    and the single-launch persistent kernel."""
+    kernels, the forward with the epilogues inside its GEMM kernels (five launches per layer; the default for
+    blocks of up to 16 rows: the 10-row block here; the 26-row block takes the per-operation kernels), one
+    kernel per phase, and the single-launch persistent kernel."""
     os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"] = gemm, attn, path
     try:
         gm, om = make_pair(shape, 7, 2, 300, 16, std=0.05)
