@@ -187,8 +187,7 @@ int32_t csd_verify_accept(csd_model *model, void *kv, const int32_t *tokens, con
  * in a static device array of CSD_STATIC_SCRATCH_BYTES per GPU instead of in the model, and the call makes
  * no hipMalloc / hipFree (nor does any other call after csd_model_create).
  *   CSD_ESHAPE        the model's scratch (it grows with max_batch * max_block and the widest matrix) does not
- *                     fit the static array;
- *   CSD_EUNSUPPORTED  the model was created with CSD_PATH=persistent|phases (those forwards keep their own state).
+ *                     fit the static array.
  * Every call on a GPU shares that GPU's array, whatever the model or stream: calls that overlap on one GPU
  * race.  The call clears the few counters in it that must start at zero and overwrites everything else it reads.
  */
@@ -203,21 +202,10 @@ int32_t csd_verify_accept_static(csd_model *model, void *kv, const int32_t *toke
  * B*m rows after the embedding and after every layer to trace[(n_layers+1)][B*m][d] (fp32). */
 int32_t csd_debug_set_trace(csd_model *model, float *trace);
 
-/* Test hook, synchronous: *flag (HOST) receives 1 if a device-wide barrier of the single-launch
- * path ever gave up waiting (its wait is bounded so that every wave exits), else 0. */
-int32_t csd_debug_error_flag(const csd_model *model, uint32_t *flag);
-
-/* Profiling hook of the single-launch kernel: when marks != NULL (device, uint64
- * [5 * (2 + 5*n_layers)][grid] with grid = number of compute units), workgroup w stores the 100 MHz
- * wall clock at five points of every phase p in marks[5p + i][w]: i = 0 phase start, 1 after the
- * activation prologue, 2 after its last weight tile, 3 after the epilogue, 4 after the barrier. */
-int32_t csd_debug_set_timestamps(csd_model *model, uint64_t *marks);
-
-/* Which forward csd_verify_block would run for B sequences of m rows: 0 = one kernel per operation
- * (any shape), 1 = one kernel per phase, 2 = the single-launch persistent kernel (B*m <= 16 rows that
- * fit LDS; chosen by default for bf16 arch-0 models whose layers hold at least 64 MB of weights).  The
- * environment variable CSD_PATH=multikernel|phases|persistent at csd_model_create forces 0, 1 or 2
- * (where the model's shape allows it). */
+/* Which forward csd_verify_block would run for B sequences of m rows: 0 = one kernel per operation with
+ * split-K partial sums and epilogue kernels (any shape, both architectures), 1 = the forward whose GEMM
+ * kernels own whole output tiles and hold their epilogues (bf16 arch-0 models, B*m <= 16 rows; the default
+ * where it applies).  The environment variable CSD_PATH=multikernel at csd_model_create forces 0. */
 int32_t csd_debug_path(const csd_model *model, int32_t B, int32_t m);
 
 /* Counter calibration for benchmarks: a plain streaming copy of `bytes` bytes (a multiple of 16; dst and

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
            "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
-           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_debug_set_trace", "csd_debug_error_flag", "csd_debug_path", "csd_debug_set_timestamps", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
+           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_debug_set_trace", "csd_debug_path", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
            "csd_prof_enable", "csd_prof_read"]
 
 _STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}
@@ -160,15 +160,6 @@ class Model:
 
     def set_trace(self, trace):
         _chk(lib().csd_debug_set_trace(self._h, _ptr(trace)), "csd_debug_set_trace")
-
-    def error_flag(self):
-        torch.cuda.synchronize()
-        f = C.c_uint32(0)
-        _chk(lib().csd_debug_error_flag(self._h, C.byref(f)), "csd_debug_error_flag")
-        return f.value
-
-    def set_timestamps(self, marks):
-        _chk(lib().csd_debug_set_timestamps(self._h, _ptr(marks)), "csd_debug_set_timestamps")
 
     def path(self, B, m):
         return int(lib().csd_debug_path(self._h, B, m))

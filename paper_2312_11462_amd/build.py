@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcsd.so")
-SOURCES = ["csd_api.hip", "csd_draft.hip", "csd_accept.hip", "csd_forward.hip", "csd_attention.hip", "csd_chain.hip", "csd_fused.hip"]
+SOURCES = ["csd_api.hip", "csd_draft.hip", "csd_accept.hip", "csd_forward.hip", "csd_attention.hip", "csd_chain.hip"]
 
 
 def hipcc() -> str:

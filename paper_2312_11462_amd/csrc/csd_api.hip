@@ -131,8 +131,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->part_floats = (size_t)mod->s_max * mod->m_max * nmax;
     if (mod->mfma_attn) mod->attn_chunks_max = (keys_pad + 127) / 128;
     // blocks of up to 16 rows of a LLaMA-style bf16 model take the forward of csd_chain.hip (CSD_PATH=multikernel: never)
-    mod->chain_on = mod->mfma && mod->mfma_attn && mod->kperm && !env_is("CSD_PATH", "multikernel") &&
-                    !env_is("CSD_PATH", "persistent") && !env_is("CSD_PATH", "phases");
+    mod->chain_on = mod->mfma && mod->mfma_attn && mod->kperm && !env_is("CSD_PATH", "multikernel");
     if (mod->chain_on) {
         const int widths[4] = {d, hd, d, F};
         for (int i = 0; i < 4; i++) mod->x_plane[i] = (size_t)m_pad * widths[i];
@@ -153,8 +152,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     if ((rc = static_scratch_base(&static_base)) != CSD_OK) return rc;   // looked up once per device, here
     mod->ev.resize(8192);
     for (auto &e : mod->ev) CSD_HIP(hipEventCreate(&e));
-    if (c.arch != 0) return CSD_OK;      // the single-launch kernel covers the LLaMA-style decoder only
-    return csd_fused_init(mod, st);
+    return CSD_OK;
 }
 
 extern "C" int32_t csd_model_create(const csd_model_cfg *cfg, const void *const *weight_ptrs, int32_t n_weights,
@@ -187,7 +185,6 @@ extern "C" int32_t csd_model_create(const csd_model_cfg *cfg, const void *const 
 
 extern "C" int32_t csd_model_destroy(csd_model *mod) {
     if (!mod) return CSD_ENULL;
-    csd_fused_free(mod);
     for (void *p : mod->allocs) (void)hipFree(p);
     for (auto &e : mod->ev)
         if (e) (void)hipEventDestroy(e);
@@ -256,7 +253,6 @@ extern "C" int32_t csd_verify_accept_static(csd_model *mod, void *kv, const int3
                                             float lenience, int32_t mode, float *logits, float *probs,
                                             int32_t *n_accepted, int32_t *next_token, void *stream) {
     if (!mod) return CSD_ENULL;
-    if (csd_fused_path(mod, B, m) != 0) return CSD_EUNSUPPORTED;        // that forward keeps state of its own
     if (csd_scratch_carve(mod, nullptr, nullptr) > CSD_STATIC_SCRATCH_BYTES) return CSD_ESHAPE;
     char *base;
     int32_t rc = static_scratch_base(&base);
@@ -285,21 +281,9 @@ extern "C" int32_t csd_debug_set_trace(csd_model *mod, float *trace) {
     return CSD_OK;
 }
 
-extern "C" int32_t csd_debug_error_flag(const csd_model *mod, uint32_t *flag) {
-    if (!mod || !flag) return CSD_ENULL;
-    return csd_fused_error(mod, flag);
-}
-
-extern "C" int32_t csd_debug_set_timestamps(csd_model *mod, uint64_t *marks) {
-    if (!mod) return CSD_ENULL;
-    mod->fused_ts = marks;
-    return CSD_OK;
-}
-
 extern "C" int32_t csd_debug_path(const csd_model *mod, int32_t B, int32_t m) {
     if (!mod) return CSD_ENULL;
-    const int32_t f = csd_fused_path(mod, B, m);
-    return f != 0 ? f : csd_chain_eligible(mod, B, m) ? 3 : 0;
+    return csd_chain_eligible(mod, B, m) ? 1 : 0;
 }
 
 __global__ __launch_bounds__(256) void k_copy_calib(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, size_t n) {

@@ -1028,7 +1028,6 @@ int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, con
         if (mod->mfma) return forward_t5<bf16_t, bf16_t, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
         return forward_t5<bf16_t, float, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
     }
-    if (csd_fused_eligible(mod, B, m)) return csd_fused_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
     if (csd_chain_eligible(mod, B, m)) return csd_chain_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->cfg.dtype == CSD_DTYPE_FP32)
         return forward_typed<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);

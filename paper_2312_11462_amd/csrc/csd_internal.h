@@ -240,9 +240,6 @@ struct csd_model {
     int32_t *rel_bucket = nullptr;   // [128] bucket of distance n (n >= 127 shares the last entry)
     float *rel_bias_hd = nullptr;    // [H][128]: rel_bias[rel_bucket[n]][h]
     float *trace = nullptr;
-    void *fused = nullptr;           // state of the single-launch path (csd_fused.hip), or null
-    float *fused_attn_part = nullptr;
-    void *fused_ts = nullptr;        // optional timing marks of the single-launch kernel (debug hook)
     // profiling
     bool prof = false;
     std::vector<hipEvent_t> ev;
@@ -273,14 +270,6 @@ int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, con
 int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st);
 int32_t csd_gemm_setup();    // MFMA models, at creation: lets the GEMM kernels use their dynamic LDS
 size_t csd_self_kv_bytes(const csd_model *mod);     // the self-attention part of the cache (arch 1 appends the cross part)
-// csd_fused.hip: single-launch forward for small blocks
-int32_t csd_fused_init(csd_model *mod, hipStream_t st);
-void csd_fused_free(csd_model *mod);
-bool csd_fused_eligible(const csd_model *mod, int32_t B, int32_t m);
-int32_t csd_fused_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
-                          int32_t m, float *logits, hipStream_t st);
-int32_t csd_fused_error(const csd_model *mod, uint32_t *flag);
-int32_t csd_fused_path(const csd_model *mod, int32_t B, int32_t m);
 // csd_chain.hip: forward for blocks of up to 16 rows, epilogues inside the GEMM kernels
 int32_t csd_chain_setup();
 

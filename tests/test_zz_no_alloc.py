@@ -38,7 +38,7 @@ def test_static_scratch_entry_point_equals_the_allocating_one():
     seed = 0x5C2A
     w = I.make_weights(shape, seed, device="cuda", std=0.05)
     gm = P.Model(shape, w, max_batch=3, max_seq=160, max_block=8)
-    assert gm.path(3, 8) == 0
+    assert gm.path(3, 8) == 0 and gm.path(1, 3) == 1     # the two calls below take the two forwards
     toks = I.token_ids(3 * 120, shape.vocab, seed, 1).reshape(3, 120).cuda()
     # prefill 96 rows per sequence through the ordinary entry point
     for pos in range(0, 96, 8):
