@@ -133,6 +133,21 @@ int32_t csd_bigram_draft(const int32_t *ctx, const int32_t *ctx_len, int32_t B, 
                          int32_t *out_tokens, int32_t *out_match_len, void *stream);
 
 /*
+ * Max-Gram with a haystack of its own (Appendix A: the listing searches the encoder's ids for the longest
+ * suffix of the decoder's ids; Section 3.3: "the initial input (or existing generation)").  For each sequence:
+ * the longest suffix of needle[0 .. needle_len) that ends at some haystack position e (the left-most e among
+ * the longest; length optionally capped by max_match > 0), then the tokens haystack[e+1 ..] while the haystack
+ * lasts: out_n_copied[B] (optional) receives how many of the k tokens that is, which is exactly what Appendix A
+ * returns (possibly none).  The remaining positions, and all k when even the needle's last token does not occur
+ * in the haystack (out_match_len 0), chain next_table from the last token so far (the bigram fallback of
+ * Section 3.3), so out_tokens[B][k] is always full.  haystack_len >= 0, 1 <= needle_len <= needle_stride.
+ */
+int32_t csd_maxgram_draft(const int32_t *haystack, const int32_t *haystack_len, int32_t haystack_stride,
+                          const int32_t *needle, const int32_t *needle_len, int32_t needle_stride, int32_t B,
+                          const int32_t *next_table, int32_t vocab, int32_t k, int32_t max_match,
+                          int32_t *out_tokens, int32_t *out_match_len, int32_t *out_n_copied, void *stream);
+
+/*
  * Review forward (Section 2: the reviewer scores all drafted positions in one run).
  * tokens[B][m]: row 0 is the last committed token of the sequence (not yet in the cache),
  * rows 1..m-1 are the drafts.  cache_len[B]: rows of the cache that are valid.  Row i sits at

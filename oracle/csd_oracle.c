@@ -560,6 +560,40 @@ int32_t csdo_bigram_draft(const int32_t *ctx, const int32_t *ctx_len, int32_t B,
     return 0;
 }
 
+/* Max-Gram with a separate haystack (Appendix A's signature; Section 3.3).  The longest suffix of the needle
+ * that ends at a haystack position, the left-most such position; the continuation is copied while the
+ * haystack lasts (n_copied tokens: Appendix A's return value), the rest chains the bigram table. */
+int32_t csdo_maxgram_draft(const int32_t *hay, const int32_t *hay_len, int32_t hay_stride, const int32_t *needle,
+                           const int32_t *needle_len, int32_t needle_stride, int32_t B, const int32_t *next_table,
+                           int32_t vocab, int32_t k, int32_t max_match, int32_t *out_tokens, int32_t *out_match_len,
+                           int32_t *out_n_copied) {
+    if (B < 0 || k < 0 || vocab < 1) return -2;
+    for (int b = 0; b < B; b++) {
+        const int32_t *h = hay + (size_t)b * hay_stride, *s = needle + (size_t)b * needle_stride;
+        const int hl = hay_len[b], len = needle_len[b];
+        if (len < 1 || len > needle_stride || hl < 0 || hl > hay_stride) return -2;
+        int best_len = 0, best_e = -1;
+        for (int e = 0; e < hl; e++) {
+            int r = 0;
+            while (r <= e && r < len && (max_match <= 0 || r < max_match) && h[e - r] == s[len - 1 - r]) r++;
+            if (r > best_len) { best_len = r; best_e = e; }       /* strict: keeps the left-most */
+        }
+        int32_t *out = out_tokens + (size_t)b * k;
+        int n_copied = 0;
+        if (best_len > 0)
+            for (int j = 0; j < k && best_e + 1 + j < hl; j++) out[n_copied++] = h[best_e + 1 + j];
+        int32_t cur = n_copied > 0 ? out[n_copied - 1] : s[len - 1];
+        for (int j = n_copied; j < k; j++) {
+            if (cur < 0 || cur >= vocab) return -2;
+            cur = next_table[cur];
+            out[j] = cur;
+        }
+        if (out_match_len) out_match_len[b] = best_len;
+        if (out_n_copied) out_n_copied[b] = n_copied;
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------ accept / resample */
 
 static int32_t sample_fixed_point(const float *r, int V, float u) {

@@ -183,6 +183,26 @@ def bigram_draft(ctx, ctx_len, next_table, k, max_match=0):
     return out, mlen
 
 
+def maxgram_draft(haystack, haystack_len, needle, needle_len, next_table, k, max_match=0):
+    """Max-Gram with a separate haystack -> (tokens [B][k], match_len [B], n_copied [B])."""
+    hay = np.ascontiguousarray(haystack, dtype=np.int32)
+    ned = np.ascontiguousarray(needle, dtype=np.int32)
+    if hay.ndim == 1:
+        hay = hay[None, :]
+    if ned.ndim == 1:
+        ned = ned[None, :]
+    hl = np.ascontiguousarray(haystack_len, dtype=np.int32).reshape(-1)
+    nl = np.ascontiguousarray(needle_len, dtype=np.int32).reshape(-1)
+    table = np.ascontiguousarray(next_table, dtype=np.int32)
+    B = ned.shape[0]
+    out = np.empty((B, k), dtype=np.int32)
+    mlen = np.empty(B, dtype=np.int32)
+    ncp = np.empty(B, dtype=np.int32)
+    _chk(lib().csdo_maxgram_draft(_p(hay), _p(hl), hay.shape[1], _p(ned), _p(nl), ned.shape[1], B, _p(table),
+                                  table.shape[0], k, max_match, _p(out), _p(mlen), _p(ncp)), "maxgram_draft")
+    return out, mlen, ncp
+
+
 def accept(p, q, draft, u_acc, u_samp, lenience=1.0, mode=0, q_onehot=None):
     """p [B][k+1][V] fp32, q [B][k][V] fp32 or None, draft [B][k] -> (n_accepted [B], next_token [B])."""
     p = np.ascontiguousarray(p, dtype=np.float32)

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
-           "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_verify_block",
+           "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_maxgram_draft", "csd_verify_block",
            "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_debug_set_trace", "csd_debug_path", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
            "csd_prof_enable", "csd_prof_read"]
 
@@ -215,6 +215,19 @@ def bigram_draft(ctx, ctx_len, next_table, k, max_match=0, want_match_len=True, 
                                 _ptr(next_table, torch.int32), next_table.shape[0], k, max_match, _ptr(out),
                                 _ptr(mlen), _stream()), "csd_bigram_draft")
     return (out, mlen) if want_match_len else out
+
+
+def maxgram_draft(haystack, haystack_len, needle, needle_len, next_table, k, max_match=0):
+    """Max-Gram with a haystack of its own: returns (tokens [B][k], match_len [B], n_copied [B])."""
+    B, hs = haystack.shape
+    out = torch.empty((B, k), dtype=torch.int32, device="cuda")
+    mlen = torch.empty(B, dtype=torch.int32, device="cuda")
+    ncp = torch.empty(B, dtype=torch.int32, device="cuda")
+    _chk(lib().csd_maxgram_draft(_ptr(haystack, torch.int32), _ptr(haystack_len, torch.int32), hs, _ptr(needle, torch.int32),
+                                 _ptr(needle_len, torch.int32), needle.shape[1], B, _ptr(next_table, torch.int32),
+                                 next_table.shape[0], k, max_match, _ptr(out), _ptr(mlen), _ptr(ncp), _stream()),
+         "csd_maxgram_draft")
+    return out, mlen, ncp
 
 
 def accept(p, q, draft, u_acc, u_samp, lenience=1.0, mode=0, q_onehot=None):

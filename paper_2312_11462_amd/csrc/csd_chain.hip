@@ -727,7 +727,12 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
                 if ((rc = chain_launch<EPI_QKV>(Pq, lw.qkv.N / 16, st)) != CSD_OK) return rc;
                 CSD_LAUNCH_CHECK();
             }
-            {
+            if ((long long)chunks * c.n_heads * B > 1024) {
+                // many sequences or long caches: the attention is bound by bandwidth, not by latency, and the kernel
+                // with longer key runs per wave (and a merge kernel) moves the cache faster
+                if ((rc = csd_attn_mfma_enqueue(mod, geo, kv, cache_len, B, m, l, scale, AttnMode{}, st, X2, mod->x_plane[1])) != CSD_OK)
+                    return rc;
+            } else {
                 ProfScope ps(mod, st, CSD_PROF_ATTN);
                 const dim3 grid(chunks, c.n_heads, B);
                 if (c.head_dim == 128)

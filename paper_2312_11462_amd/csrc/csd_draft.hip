@@ -65,6 +65,54 @@ __global__ __launch_bounds__(DRAFT_THREADS) void k_bigram_draft(
     for (int j = threadIdx.x; j < k; j += blockDim.x) out[j] = s[e + 1 + (j % period)];
 }
 
+// Max-Gram with the haystack apart from the needle (Appendix A's own signature: the encoder's ids are searched
+// for the longest suffix of the decoder's ids).  Candidate match ends are all haystack positions; the key is
+// the same (match length, ~end).  The continuation is copied while the haystack lasts (out_n_copied of the k
+// tokens: what Appendix A returns); the rest chains the bigram table from the last token so far.
+__global__ __launch_bounds__(DRAFT_THREADS) void k_maxgram_enc(
+    const int32_t *__restrict__ hay, const int32_t *__restrict__ hay_len, int32_t hay_stride,
+    const int32_t *__restrict__ needle, const int32_t *__restrict__ needle_len, int32_t needle_stride,
+    const int32_t *__restrict__ next_table, int32_t vocab, int32_t k, int32_t max_match,
+    int32_t *__restrict__ out_tokens, int32_t *__restrict__ out_match_len, int32_t *__restrict__ out_n_copied) {
+    __shared__ unsigned long long red[DRAFT_THREADS / 64];
+    const int b = blockIdx.x;
+    const int32_t *h = hay + (size_t)b * hay_stride;
+    const int32_t *s = needle + (size_t)b * needle_stride;
+    const int hl = hay_len[b], len = needle_len[b];
+    int32_t *out = out_tokens + (size_t)b * k;
+    if (len < 1 || len > needle_stride || hl < 0 || hl > hay_stride) {   // device-side guard: no valid input
+        for (int j = threadIdx.x; j < k; j += blockDim.x) out[j] = -1;
+        if (threadIdx.x == 0) {
+            if (out_match_len) out_match_len[b] = 0;
+            if (out_n_copied) out_n_copied[b] = 0;
+        }
+        return;
+    }
+    unsigned long long best = 0ull;
+    for (int e = threadIdx.x; e < hl; e += blockDim.x) {
+        int r = 0;
+        while (r <= e && r < len && (max_match <= 0 || r < max_match) && h[e - r] == s[len - 1 - r]) r++;
+        if (r > 0) {
+            unsigned long long key = ((unsigned long long)(uint32_t)r << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+            best = key > best ? key : best;
+        }
+    }
+    best = block_max_u64(best, red);
+    const int mlen = (int)(best >> 32);
+    const int e = mlen ? (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull)) : hl - 1;
+    const int n_copied = mlen ? min(k, hl - 1 - e) : 0;
+    for (int j = threadIdx.x; j < n_copied; j += blockDim.x) out[j] = h[e + 1 + j];
+    if (threadIdx.x == 0) {
+        if (out_match_len) out_match_len[b] = mlen;
+        if (out_n_copied) out_n_copied[b] = n_copied;
+        int32_t cur = n_copied > 0 ? h[e + n_copied] : s[len - 1];
+        for (int j = n_copied; j < k; j++) {
+            cur = (cur >= 0 && cur < vocab) ? next_table[cur] : -1;
+            out[j] = cur;
+        }
+    }
+}
+
 // Bigram fit, one workgroup.  Pass 1: for every position i the pair (s[i], s[i+1]) gets the key
 // (count of the pair, index of its last occurrence).  Pass 2: the last occurrence of a pair
 // writes next[a] if no other pair with the same first token has a larger key.
@@ -111,6 +159,21 @@ extern "C" int32_t csd_bigram_draft(const int32_t *ctx, const int32_t *ctx_len, 
     if (B == 0 || (k == 0 && !out_match_len)) return CSD_OK;   // k == 0 still reports match lengths
     hipLaunchKernelGGL(k_bigram_draft, dim3(B), dim3(DRAFT_THREADS), 0, (hipStream_t)stream, ctx, ctx_len, ctx_stride,
                        next_table, vocab, k, max_match, out_tokens, out_match_len);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_maxgram_draft(const int32_t *haystack, const int32_t *haystack_len, int32_t haystack_stride,
+                                     const int32_t *needle, const int32_t *needle_len, int32_t needle_stride, int32_t B,
+                                     const int32_t *next_table, int32_t vocab, int32_t k, int32_t max_match,
+                                     int32_t *out_tokens, int32_t *out_match_len, int32_t *out_n_copied, void *stream) {
+    if (!haystack || !haystack_len || !needle || !needle_len || !next_table) return CSD_ENULL;
+    if (B < 0 || k < 0 || vocab < 1 || haystack_stride < 1 || needle_stride < 1) return CSD_EINVAL;
+    if (k > 0 && !out_tokens) return CSD_ENULL;
+    if (B == 0 || (k == 0 && !out_match_len && !out_n_copied)) return CSD_OK;
+    hipLaunchKernelGGL(k_maxgram_enc, dim3(B), dim3(DRAFT_THREADS), 0, (hipStream_t)stream, haystack, haystack_len,
+                       haystack_stride, needle, needle_len, needle_stride, next_table, vocab, k, max_match, out_tokens,
+                       out_match_len, out_n_copied);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }

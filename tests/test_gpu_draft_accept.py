@@ -43,6 +43,35 @@ def test_bigram_draft_matches_oracle(P):
             assert np.array_equal(glen.cpu().numpy(), wlen), (V, k, cap)
 
 
+def test_maxgram_with_separate_haystack_matches_oracle(P):
+    """Appendix A's own signature: the needle's longest suffix inside a haystack of its own (the prompt /
+    encoder ids), several sequences with ragged lengths, empty haystack, needle longer than the haystack,
+    match cap, k = 0."""
+    O = _O()
+    for V, hs, ns, seed in [(3, 30, 12, 1), (5, 200, 40, 2), (300, 700, 300, 3), (32000, 2048, 600, 4)]:
+        B = 6
+        hay = torch.zeros((B, hs), dtype=torch.int32)
+        ned = torch.zeros((B, ns), dtype=torch.int32)
+        hl, nl = [], []
+        for b in range(B):
+            n = (hs * (b + 1)) // B
+            src = I.repeat_stream(n + ns, V, seed, b) if V > 5 else I.token_ids(n + ns, V, seed, b)
+            hay[b, :n] = src[:n]
+            # the needle: a stretch that recurs in the haystack, followed by a few fresh tokens
+            m = max(1, ns - b)
+            ned[b, :m] = torch.cat([src[max(0, n // 2 - m):n // 2], src[n:n + ns]])[:m] if n >= 2 else src[:m]
+            hl.append(n)
+            nl.append(m)
+        hl[0] = 0                                      # degenerate: nothing to search -> bigram chain
+        table = I.default_next_table(V, seed)
+        for k, cap in [(1, 0), (6, 0), (10, 3), (0, 0)]:
+            want = O.maxgram_draft(hay.numpy(), hl, ned.numpy(), nl, table.numpy(), k, cap)
+            got = P.maxgram_draft(hay.cuda(), torch.tensor(hl, dtype=torch.int32).cuda(), ned.cuda(),
+                                  torch.tensor(nl, dtype=torch.int32).cuda(), table.cuda(), k, cap)
+            for g, w, name in zip(got, want, ("tokens", "match length", "copied")):
+                assert np.array_equal(g.cpu().numpy(), w), (V, k, cap, name)
+
+
 def test_bigram_fit_matches_oracle(P):
     O = _O()
     for V, n, seed in [(8, 50, 1), (64, 1000, 2), (32000, 2048, 3), (32000, 8192, 4), (10, 2, 5), (10, 1, 6)]:

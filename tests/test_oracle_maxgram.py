@@ -148,3 +148,77 @@ def test_fit_on_prefix_makes_fallback_fire_only_for_unseen_tokens():
         if mlen[0] == 0:
             assert out[0, 0] == default[s[n - 1]]
     assert table.shape == (V,)
+
+
+# ---------------------------------------------------------------- separate haystack (Appendix A's signature)
+
+ENC_GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "maxgram_encoder_cases.txt")
+
+
+def _enc_cases():
+    out = []
+    for line in open(ENC_GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        hay, needle, k, exp, mlen = [c.strip() for c in line.split("|")]
+        exp_t = None if exp == "None" else ([] if exp == "-" else [int(x) for x in exp.split()])
+        out.append(([int(x) for x in hay.split()], [int(x) for x in needle.split()], int(k), exp_t, int(mlen)))
+    return out
+
+
+@pytest.mark.parametrize("hay,needle,k,exp,mlen", _enc_cases())
+def test_encoder_side_worked_cases(hay, needle, k, exp, mlen):
+    table = (np.arange(100, dtype=np.int32) + 1) % 100
+    out, got_len, n_copied = O.maxgram_draft(hay, [len(hay)], needle, [len(needle)], table, k)
+    assert got_len[0] == mlen
+    want = [] if exp is None else exp
+    assert n_copied[0] == len(want) and out[0, :len(want)].tolist() == want
+    # what is not copied chains the bigram table from the last token so far
+    cur = want[-1] if want else needle[-1]
+    for j in range(len(want), k):
+        cur = (cur + 1) % 100
+        assert out[0, j] == cur
+
+
+def _enc_brute(hay, needle):
+    """Independent definition: the largest r such that needle[-r:] occurs in hay, and the smallest start."""
+    for r in range(min(len(needle), len(hay)), 0, -1):
+        suf = needle[-r:]
+        for st in range(0, len(hay) - r + 1):
+            if hay[st:st + r] == suf:
+                return r, st + r - 1
+    return 0, -1
+
+
+def test_encoder_side_brute_force_small_alphabet():
+    rng = np.random.default_rng(7)
+    table = np.array([2, 0, 1], np.int32)
+    for _ in range(400):
+        hay = rng.integers(0, 3, size=int(rng.integers(0, 12))).tolist()
+        needle = rng.integers(0, 3, size=int(rng.integers(1, 9))).tolist()
+        k = int(rng.integers(0, 6))
+        hp = hay + [0] * (12 - len(hay))
+        out, mlen, ncp = O.maxgram_draft(np.array(hp, np.int32), [len(hay)], needle, [len(needle)], table, k)
+        r, e = _enc_brute(hay, needle)
+        assert mlen[0] == r
+        copied = hay[e + 1:e + 1 + k] if r else []
+        assert ncp[0] == len(copied) and out[0, :len(copied)].tolist() == copied
+        cur = copied[-1] if copied else needle[-1]
+        for j in range(len(copied), k):
+            cur = int(table[cur])
+            assert out[0, j] == cur
+
+
+def test_encoder_side_match_cap_and_reduction_to_self_search():
+    # with the cap the match length saturates but the left-most rule still holds
+    hay = [1, 2, 3, 9, 1, 2, 3]
+    out, mlen, ncp = O.maxgram_draft(hay, [7], [1, 2, 3], [3], np.zeros(10, np.int32), 2, max_match=2)
+    assert mlen[0] == 2 and out[0].tolist() == [9, 1]
+    # a context searched in itself without its last position is the decoder-only form
+    s = I.repeat_stream(200, 50, 3, 1).numpy()
+    table = I.default_next_table(50, 3).numpy()
+    a, la = O.bigram_draft(s, [200], table, 4)
+    b, lb, nb = O.maxgram_draft(s[:199], [199], s, [200], table, 4)
+    assert la[0] == lb[0]
+    assert a[0, :nb[0]].tolist() == b[0, :nb[0]].tolist()
