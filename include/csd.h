@@ -213,6 +213,68 @@ int32_t csd_verify_accept_static(csd_model *model, void *kv, const int32_t *toke
                                  float lenience, int32_t mode, float *logits, float *probs,
                                  int32_t *n_accepted, int32_t *next_token, void *stream);
 
+/*
+ * Device-resident control of the cascade (Algorithm 1; Sections 3.2, 3.4): the two calls below keep a sequence's
+ * tokens (kept tokens followed by the drafts in flight), its lengths and the draft distributions on the device, so
+ * that a whole multi-level step -- Max-Gram drafts, a draft model's reviews "until k_i tokens exist", the
+ * horizontal cascade's tail, the target's review -- is a chain of enqueues with no host synchronisation.  Every
+ * pointer in csd_review is a device pointer.
+ */
+typedef struct csd_review {
+    int32_t *ctx;                  /* [B][ctx_stride] tokens: kept ++ drafts in flight; the reviewer's token is appended    */
+    int32_t  ctx_stride;
+    int32_t *ctx_len;              /* [B] in/out: tokens present (kept + in flight); out: kept + 1                           */
+    int32_t *cache_len;            /* [B] in/out: rows of this reviewer's cache in use; out: position of its own token      */
+    const int32_t *prefix_len;     /* [B] position of the first draft under review (>= cache_len + 1); < 0: skip sequence    */
+    const float   *q_tab;          /* draft distributions by position, row (pos - q_base[b]) of [B][q_stride][V], or NULL   */
+    const uint8_t *q_onehot_tab;   /* [B][q_stride] nonzero: the draft at that position was deterministic; or NULL           */
+    const int32_t *q_base;         /* [B]                                                                                    */
+    int32_t  q_stride;
+    const float *u_acc_tab;        /* [B][ctx_stride] uniform of the acceptance test of the draft at a position              */
+    const float *u_samp_tab;       /* [B][ctx_stride] uniform of the draw of a review whose first draft sits at a position   */
+    float   *out_q_tab;            /* this reviewer's rows of the tokens it emits, for the level above: row (pos - out_base)  */
+    uint8_t *out_onehot_tab;       /* ... and their flags (0 when sampling, 1 under the greedy rule); either may be NULL      */
+    const int32_t *out_base;       /* [B]                                                                                    */
+    int32_t  out_stride;
+    int32_t *lower_cache_len[4];   /* cache lengths [B] of the levels below: clamped to the kept length                      */
+    int32_t  n_lower;
+    int32_t *n_accepted, *next_token;   /* [B] optional outputs (-1 for a skipped sequence)                                  */
+    int32_t *status;               /* [B] out: 0 reviewed, 1 skipped on request, 2 skipped: the state does not fit the call   */
+    const float *ext_rows;         /* NULL: run the model.  Else [B][m_max][V] reviewer rows given by the caller (block row i) */
+} csd_review;
+
+/*
+ * One review.  Block of sequence b = ctx[b][cache_len[b] .. ctx_len[b]) (at most m_max rows, else status 2): rows the
+ * reviewer has not cached yet, ending with the drafts ctx[b][prefix_len[b] .. ctx_len[b]).  The forward runs over
+ * m_max rows per sequence (zero tokens as padding; their cache rows lie beyond the kept length), then accept /
+ * resample as csd_accept does, with k = ctx_len - prefix_len drafts per sequence, draft distributions and uniforms
+ * taken by position, then the commit: ctx[prefix + n] = the reviewer's token, ctx_len = prefix + n + 1, cache_len =
+ * prefix + n, lower levels' cache lengths = min(theirs, prefix + n), the reviewer's rows of the n + 1 emitted tokens
+ * into out_q_tab.  cache_len + m_max <= max_seq and ctx_len < ctx_stride are the caller's duty (the latter is
+ * checked on the device: status 2).
+ */
+int32_t csd_review_ctx(csd_model *model, void *kv, const csd_review *r, int32_t B, int32_t m_max, float temperature,
+                       float lenience, int32_t mode, void *stream);
+
+/*
+ * csd_bigram_draft that appends: for every sequence with gate == NULL or gate[b] >= 0, draft k tokens continuing
+ * ctx[b][0 .. ctx_len[b]), write them at ctx_len[b], advance ctx_len[b] by k, and set q_onehot_tab[b][pos - q_base[b]]
+ * = 1 for their positions (optional); other sequences are left alone.  ctx_len + k < ctx_stride is checked on the
+ * device (such a sequence is left alone).
+ */
+int32_t csd_bigram_draft_append(int32_t *ctx, int32_t ctx_stride, int32_t *ctx_len, int32_t B, const int32_t *next_table,
+                                int32_t vocab, int32_t k, int32_t max_match, const int32_t *gate, uint8_t *q_onehot_tab,
+                                const int32_t *q_base, int32_t q_stride, void *stream);
+
+/*
+ * The loop condition of Algorithm 1 ("while fewer than k_i tokens exist") on the device: gate[b] = ctx_len[b] if
+ * ctx_len[b] - loop_start[b] < need (loop_start NULL: always) and the enclosing step is active (parent_gate NULL or
+ * parent_gate[b] >= 0), else -1.  The value doubles as the prefix_len of the step it gates: csd_bigram_draft_append and
+ * csd_review_ctx skip sequences whose gate / prefix_len is negative.
+ */
+int32_t csd_cascade_gate(const int32_t *ctx_len, const int32_t *loop_start, int32_t need, const int32_t *parent_gate,
+                         int32_t B, int32_t *gate, void *stream);
+
 /* Test hook: when trace != NULL the next verify calls also copy the residual stream of all
  * B*m rows after the embedding and after every layer to trace[(n_layers+1)][B*m][d] (fp32). */
 int32_t csd_debug_set_trace(csd_model *model, float *trace);

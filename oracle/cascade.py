@@ -63,8 +63,11 @@ def autoregressive(level: Level, prompt, n_new, mode=1, uniforms=None, temperatu
     return seq[len(prompt):]
 
 
-def _step(levels, next_table, seq, K, lenience, mode, uniforms, is_first, max_match):
-    """One CascadeSpeculativeDraftingStep with reviewer levels[0]; returns (tokens, q_rows)."""
+def _step(levels, next_table, seq, K, lenience, mode, uniforms, is_first, max_match, uniform_at=None, depth=0):
+    """One CascadeSpeculativeDraftingStep with reviewer levels[0]; returns (tokens, q_rows).
+    The random numbers are inputs: either an iterator `uniforms` drawn in review order, or a function
+    uniform_at(depth, kind, position) with kind 0 = the acceptance test of the draft at that position and
+    kind 1 = the draw of a review whose first draft sits at that position (depth = the reviewer's level)."""
     reviewer = levels[0]
     n_prefix = len(seq)
     cur = list(seq)
@@ -82,7 +85,8 @@ def _step(levels, next_table, seq, K, lenience, mode, uniforms, is_first, max_ma
                 q_rows += [None] * need
             else:
                 subK = [row[i + 1:] for row in K[i + 1:]]
-                toks, qs = _step(below[i:], next_table, cur, subK, lenience, mode, uniforms, False, max_match)
+                toks, qs = _step(below[i:], next_table, cur, subK, lenience, mode, uniforms, False, max_match,
+                                 uniform_at, depth + 1 + i)
                 cur += toks
                 q_rows += qs
     drafts = cur[n_prefix:]
@@ -99,8 +103,12 @@ def _step(levels, next_table, seq, K, lenience, mode, uniforms, is_first, max_ma
         u_s = np.zeros(1, np.float32)
     else:
         p = O.probs_f32(lg)[None]
-        u_acc = np.array([[next(uniforms) for _ in range(k)]], np.float32)
-        u_s = np.array([next(uniforms)], np.float32)
+        if uniform_at is not None:
+            u_acc = np.array([[uniform_at(depth, 0, n_prefix + j) for j in range(k)]], np.float32)
+            u_s = np.array([uniform_at(depth, 1, n_prefix)], np.float32)
+        else:
+            u_acc = np.array([[next(uniforms) for _ in range(k)]], np.float32)
+            u_s = np.array([next(uniforms)], np.float32)
     q = None
     onehot = None
     if not all_onehot:

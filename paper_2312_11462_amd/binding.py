@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
            "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_maxgram_draft", "csd_verify_block",
-           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_debug_set_trace", "csd_debug_path", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
+           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_review_ctx", "csd_bigram_draft_append", "csd_cascade_gate", "csd_debug_set_trace", "csd_debug_path", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
            "csd_prof_enable", "csd_prof_read"]
 
 _STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}
@@ -33,6 +33,16 @@ class Cfg(C.Structure):
                 ("arch", "dtype", "n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
                  "max_batch", "max_seq", "max_block", "enc_len")] + \
                [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class Review(C.Structure):
+    """csd_review: device pointers of one review with device-resident control."""
+    _fields_ = [("ctx", C.c_void_p), ("ctx_stride", C.c_int32), ("ctx_len", C.c_void_p), ("cache_len", C.c_void_p),
+                ("prefix_len", C.c_void_p), ("q_tab", C.c_void_p), ("q_onehot_tab", C.c_void_p), ("q_base", C.c_void_p),
+                ("q_stride", C.c_int32), ("u_acc_tab", C.c_void_p), ("u_samp_tab", C.c_void_p), ("out_q_tab", C.c_void_p),
+                ("out_onehot_tab", C.c_void_p), ("out_base", C.c_void_p), ("out_stride", C.c_int32),
+                ("lower_cache_len", C.c_void_p * 4), ("n_lower", C.c_int32), ("n_accepted", C.c_void_p),
+                ("next_token", C.c_void_p), ("status", C.c_void_p), ("ext_rows", C.c_void_p)]
 
 
 _lib = None
@@ -158,6 +168,26 @@ class Model:
                 _ptr(next_token), _stream()), "csd_verify_accept_static" if static else "csd_verify_accept")
         return n_accepted, next_token
 
+    def review_ctx(self, ctx, ctx_len, cache_len, prefix_len, m_max, status, q_tab=None, q_onehot_tab=None, q_base=None,
+                   u_acc_tab=None, u_samp_tab=None, out_q_tab=None, out_onehot_tab=None, out_base=None, lower=(),
+                   n_accepted=None, next_token=None, ext_rows=None, temperature=1.0, lenience=1.0, mode=0):
+        """csd_review_ctx: one review with device-resident control (every tensor stays on the device)."""
+        def dp(t):
+            return None if t is None else t.data_ptr()
+        r = Review()
+        r.ctx, r.ctx_stride, r.ctx_len, r.cache_len, r.prefix_len = dp(ctx), ctx.shape[1], dp(ctx_len), dp(cache_len), dp(prefix_len)
+        r.q_tab, r.q_onehot_tab, r.q_base = dp(q_tab), dp(q_onehot_tab), dp(q_base)
+        r.q_stride = (q_onehot_tab if q_onehot_tab is not None else q_tab).shape[1] if (q_tab is not None or q_onehot_tab is not None) else 0
+        r.u_acc_tab, r.u_samp_tab = dp(u_acc_tab), dp(u_samp_tab)
+        r.out_q_tab, r.out_onehot_tab, r.out_base = dp(out_q_tab), dp(out_onehot_tab), dp(out_base)
+        r.out_stride = (out_onehot_tab if out_onehot_tab is not None else out_q_tab).shape[1] if (out_q_tab is not None or out_onehot_tab is not None) else 0
+        for i, t in enumerate(lower):
+            r.lower_cache_len[i] = t.data_ptr()
+        r.n_lower = len(lower)
+        r.n_accepted, r.next_token, r.status, r.ext_rows = dp(n_accepted), dp(next_token), dp(status), dp(ext_rows)
+        _chk(lib().csd_review_ctx(self._h, _ptr(self.kv), C.byref(r), ctx.shape[0], m_max, C.c_float(temperature),
+                                  C.c_float(lenience), mode, _stream()), "csd_review_ctx")
+
     def set_trace(self, trace):
         _chk(lib().csd_debug_set_trace(self._h, _ptr(trace)), "csd_debug_set_trace")
 
@@ -228,6 +258,20 @@ def maxgram_draft(haystack, haystack_len, needle, needle_len, next_table, k, max
                                  next_table.shape[0], k, max_match, _ptr(out), _ptr(mlen), _ptr(ncp), _stream()),
          "csd_maxgram_draft")
     return out, mlen, ncp
+
+
+def bigram_draft_append(ctx, ctx_len, next_table, k, max_match=0, gate=None, q_onehot_tab=None, q_base=None):
+    """csd_bigram_draft_append: Max-Gram drafts written at the end of the device-side sequences."""
+    _chk(lib().csd_bigram_draft_append(_ptr(ctx, torch.int32), ctx.shape[1], _ptr(ctx_len, torch.int32), ctx.shape[0],
+                                       _ptr(next_table, torch.int32), next_table.shape[0], k, max_match, _ptr(gate),
+                                       _ptr(q_onehot_tab), _ptr(q_base), q_onehot_tab.shape[1] if q_onehot_tab is not None else 0,
+                                       _stream()), "csd_bigram_draft_append")
+
+
+def cascade_gate(ctx_len, gate_out, loop_start=None, need=0, parent_gate=None):
+    """csd_cascade_gate: the loop condition of Algorithm 1 evaluated on the device."""
+    _chk(lib().csd_cascade_gate(_ptr(ctx_len, torch.int32), _ptr(loop_start), need, _ptr(parent_gate), ctx_len.shape[0],
+                                _ptr(gate_out, torch.int32), _stream()), "csd_cascade_gate")
 
 
 def accept(p, q, draft, u_acc, u_samp, lenience=1.0, mode=0, q_onehot=None):

@@ -163,3 +163,104 @@ def autoregressive(level: Level, prompt, n_new, max_ctx, mode=1, uniforms=None, 
                 mode=mode, temperature=temperature)
     out, _ = c.generate(prompt, n_new, uniforms)
     return out
+
+
+class ResidentCascade:
+    """Algorithm 1 as a chain of enqueues with device-resident control: the sequence, every length, the loop
+    conditions ("until k_i tokens exist") and the draft distributions handed upward live on the device, and a whole
+    multi-level step runs with no host synchronisation (csd_review_ctx, csd_bigram_draft_append, csd_cascade_gate).
+    A loop of Algorithm 1 whose trip count depends on accepted lengths is enqueued for its worst case (k_i rounds),
+    each round gated per sequence on the device.  One sequence; levels = [target, draft_1, ...] over Max-Gram.
+    Uniforms are taken by position from per-level tables (u_acc[level][pos], u_samp[level][pos]) that the caller
+    fills (sampling mode)."""
+
+    def __init__(self, levels, next_table, K, max_ctx, lenience=1.0, mode=1, temperature=1.0, max_match=0, q_stride=32):
+        n = len(levels)
+        if len(K) != n or any(len(r) != n for r in K):
+            raise ValueError("K must be n x n over the draft levels including Max-Gram")
+        self.levels, self.table, self.K = levels, next_table, K
+        self.lenience, self.mode, self.temperature, self.max_match = float(lenience), mode, temperature, max_match
+        self.V = levels[0].model.shape.vocab
+        dev = "cuda"
+        self.ctx = torch.zeros((1, max_ctx), dtype=torch.int32, device=dev)
+        self.ctx_len = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.cache_len = [torch.zeros(1, dtype=torch.int32, device=dev) for _ in levels]
+        self.status = [torch.zeros(1, dtype=torch.int32, device=dev) for _ in levels]
+        self.n_acc = [torch.zeros(1, dtype=torch.int32, device=dev) for _ in levels]
+        # what each level reviews against: rows and flags by position relative to the start of its step
+        self.q_tab = [torch.zeros((1, q_stride, self.V), dtype=torch.float32, device=dev) if mode == 0 else None for _ in levels]
+        self.onehot = [torch.ones((1, q_stride), dtype=torch.uint8, device=dev) for _ in levels]
+        self.u_acc = [torch.zeros((1, max_ctx), dtype=torch.float32, device=dev) for _ in levels]
+        self.u_samp = [torch.zeros((1, max_ctx), dtype=torch.float32, device=dev) for _ in levels]
+        self._gates = []          # one tensor per call site, created on first use and reused every step
+        self._site = 0
+        self.enqueued_reviews = 0
+
+    def _tensor(self):
+        if self._site == len(self._gates):
+            self._gates.append(torch.zeros(1, dtype=torch.int32, device="cuda"))
+        t = self._gates[self._site]
+        self._site += 1
+        return t
+
+    def start(self, prompt):
+        """Host-driven setup: the prompt into the buffer, every level's cache filled with all but its last token."""
+        n = len(prompt)
+        self.ctx.zero_()
+        self.ctx[0, :n] = torch.tensor(prompt, dtype=torch.int32).cuda()
+        self.ctx_len.fill_(n)
+        cl = torch.zeros(1, dtype=torch.int32, device="cuda")
+        for lv, c in zip(self.levels, self.cache_len):
+            pos = 0
+            while pos < n - 1 and getattr(lv, "ext_rows", None) is None:
+                m = min(lv.max_block, n - 1 - pos)
+                cl.fill_(pos)
+                lv.model.verify_block(self.ctx[:, pos:pos + m].contiguous(), cl)
+                pos += m
+            c.fill_(n - 1)
+
+    def _step(self, li, K, gate, parent):
+        """Enqueue one CascadeSpeculativeDraftingStep with reviewer levels[li] for the sequences whose gate is >= 0;
+        gate holds the step's prefix length.  parent = (q_tab, onehot, base) of the level that will review what this
+        step emits, or None at the top."""
+        n_levels = len(self.levels)
+        n_drafts = n_levels - li
+        for i in range(n_drafts):
+            k_i = K[0][i]
+            if k_i == 0:
+                continue
+            if i == n_drafts - 1:                      # Max-Gram: the base case, k_i tokens at once
+                P.bigram_draft_append(self.ctx, self.ctx_len, self.table, k_i, self.max_match, gate=gate,
+                                      q_onehot_tab=self.onehot[li], q_base=gate)
+            else:
+                loop_start = self._tensor()
+                P.cascade_gate(self.ctx_len, loop_start)                       # the length when the loop starts
+                sub = [row[i + 1:] for row in K[i + 1:]]
+                for _ in range(k_i):                                           # worst case: one token per round
+                    g = self._tensor()
+                    P.cascade_gate(self.ctx_len, g, loop_start=loop_start, need=k_i, parent_gate=gate)
+                    self._step(li + 1 + i, sub, g, (self.q_tab[li], self.onehot[li], gate))
+        lvl_lenience = 1.0 if (li == 0 or li == n_levels - 1) else self.lenience
+        lv = self.levels[li]
+        dense_below = self.mode == 0 and li < n_levels - 1
+        lv.model.review_ctx(self.ctx, self.ctx_len, self.cache_len[li], gate, lv.max_block, self.status[li],
+                            q_tab=self.q_tab[li] if dense_below else None,
+                            q_onehot_tab=self.onehot[li] if dense_below else None, q_base=gate if dense_below else None,
+                            u_acc_tab=self.u_acc[li], u_samp_tab=self.u_samp[li],
+                            out_q_tab=parent[0] if parent else None, out_onehot_tab=parent[1] if parent else None,
+                            out_base=parent[2] if parent else None, lower=self.cache_len[li + 1:],
+                            n_accepted=self.n_acc[li], ext_rows=getattr(lv, "ext_rows", None), temperature=self.temperature,
+                            lenience=lvl_lenience, mode=self.mode)
+        self.enqueued_reviews += 1
+
+    def step(self):
+        """Enqueue one whole step of the target (no synchronisation)."""
+        self._site = 0
+        g0 = self._tensor()
+        P.cascade_gate(self.ctx_len, g0)
+        self._step(0, self.K, g0, None)
+
+    def tokens(self):
+        """The kept sequence (synchronises)."""
+        n = int(self.ctx_len.item())
+        return self.ctx[0, :n].cpu().tolist()

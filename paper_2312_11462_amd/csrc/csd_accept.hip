@@ -116,23 +116,22 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
     return before + incl - mine;
 }
 
-__global__ __launch_bounds__(ACC_THREADS) void k_accept(
-    const float *__restrict__ p, const float *__restrict__ q, const uint8_t *__restrict__ q_onehot,
-    const int32_t *__restrict__ draft, int32_t draft_stride, const float *__restrict__ u_acc,
-    const float *__restrict__ u_samp, int32_t k, int32_t V, float lenience, int32_t mode,
-    int32_t *__restrict__ n_accepted, int32_t *__restrict__ next_token) {
-    __shared__ ArgMax red_am[ACC_THREADS / 64];
-    __shared__ unsigned long long wave_tot[ACC_THREADS / 64];
-    __shared__ int s_n;
-    const int b = blockIdx.x;
-    const float *pb = p + (size_t)b * (k + 1) * V;
-    const float *qb = q ? q + (size_t)b * k * V : nullptr;
-    const int32_t *db = draft + (size_t)b * draft_stride;
-
+// The review of one sequence by one workgroup (every thread calls it; the result is valid in every thread).
+// pb: reviewer rows [k+1][V]; qb: draft rows [k][V] or null; q_onehot: [k] flags or null; db: drafts [k];
+// ua: [k] uniforms of the acceptance tests; us: the uniform of the draw.
+struct AcceptShared {
+    ArgMax red_am[ACC_THREADS / 64];
+    unsigned long long wave_tot[ACC_THREADS / 64];
+    int s_n, s_tok;
+};
+__device__ __forceinline__ void accept_core(AcceptShared &S, const float *__restrict__ pb, const float *__restrict__ qb,
+                                            const uint8_t *__restrict__ q_onehot, const int32_t *__restrict__ db,
+                                            const float *__restrict__ ua, float us, int32_t k, int32_t V, float lenience,
+                                            int32_t mode, int &n_out, int &tok_out) {
     if (mode == CSD_MODE_GREEDY) {
         int n = 0, am = 0;
         for (; n <= k; n++) {
-            am = block_argmax(pb + (size_t)n * V, V, red_am);
+            am = block_argmax(pb + (size_t)n * V, V, S.red_am);
             if (n == k) break;
             const int x = db[n];
             bool ok = (x == am);
@@ -143,13 +142,10 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
             }
             if (!ok) break;
         }
-        if (threadIdx.x == 0) {
-            n_accepted[b] = n;
-            next_token[b] = am;
-        }
+        n_out = n;
+        tok_out = am;
         return;
     }
-
     // acceptance tests of all k positions at once (one lane each); the first failure ends the prefix
     if (threadIdx.x < 64) {
         int n = k;
@@ -162,7 +158,7 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
                 if (x >= 0 && x < V) {                           // an invalid draft id is a rejection
                     const bool dense = qb && !(q_onehot && q_onehot[i]);
                     const float qx = dense ? qb[(size_t)i * V + x] : 1.0f;
-                    const float lhs = __fmul_rn(u_acc[(size_t)b * k + i], qx);
+                    const float lhs = __fmul_rn(ua[i], qx);
                     const float rhs = __fmul_rn(lenience, pb[(size_t)i * V + x]);
                     ok = lhs < rhs;
                 }
@@ -170,14 +166,19 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
             const unsigned long long bad = __ballot(!ok);
             if (bad) n = base + __ffsll((long long)bad) - 1;
         }
-        if (threadIdx.x == 0) s_n = n;
+        if (threadIdx.x == 0) {
+            S.s_n = n;
+            S.s_tok = -1;
+        }
     }
     __syncthreads();
-    const int n = s_n;
+    const int n = S.s_n;
     const float *prow = pb + (size_t)n * V;
     bool residual = n < k;
     int x = residual ? db[n] : -1;
     const float *qrow = nullptr;
+    // a draft id outside [0, V) is a rejection whose replacement is drawn from the reviewer's row itself
+    if (residual && (x < 0 || x >= V)) residual = false;
     if (residual && qb && !(q_onehot && q_onehot[n])) qrow = qb + (size_t)n * V;
     const bool vec = ((uintptr_t)prow % 16 == 0) && (!qrow || (uintptr_t)qrow % 16 == 0);
 
@@ -187,28 +188,41 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
     unsigned long long Z = 0ull, excl = 0ull, mine = 0ull;
     for (int pass = 0; pass < 2; pass++) {
         mine = range_weight(prow, qrow, x, lenience, residual, v0, v1, vec);
-        excl = block_exclusive_scan(mine, wave_tot, Z);
+        excl = block_exclusive_scan(mine, S.wave_tot, Z);
         if (Z != 0ull || !residual) break;
         residual = false;                                    // all-zero residual: draw from the reviewer's row
     }
-    if (Z == 0ull) {                                         // not a distribution: signal with -1
-        if (threadIdx.x == 0) {
-            n_accepted[b] = n;
-            next_token[b] = -1;
+    if (Z != 0ull) {                                         // else not a distribution: the token stays -1
+        // T = floor(floor(u * 2^24) * Z / 2^24), 128-bit product
+        const unsigned long long u24 = fixed40(us) >> 16;
+        const unsigned long long hi = __umul64hi(u24, Z), lo = u24 * Z;
+        const unsigned long long T = (hi << 40) | (lo >> 24);
+        if (T >= excl && T < excl + mine) {                  // exactly one thread owns T
+            unsigned long long cum = excl;
+            int tok = v1 - 1;
+            for (int v = v0; v < v1; v++) {
+                cum += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
+                if (cum > T) { tok = v; break; }
+            }
+            S.s_tok = tok;
         }
-        return;
     }
-    // T = floor(floor(u * 2^24) * Z / 2^24), 128-bit product
-    const unsigned long long u24 = fixed40(u_samp[b]) >> 16;
-    const unsigned long long hi = __umul64hi(u24, Z), lo = u24 * Z;
-    const unsigned long long T = (hi << 40) | (lo >> 24);
-    if (T >= excl && T < excl + mine) {                      // exactly one thread owns T
-        unsigned long long cum = excl;
-        int tok = v1 - 1;
-        for (int v = v0; v < v1; v++) {
-            cum += fixed40(weight_at(prow, qrow, x, lenience, residual, v));
-            if (cum > T) { tok = v; break; }
-        }
+    __syncthreads();
+    n_out = n;
+    tok_out = S.s_tok;
+}
+
+__global__ __launch_bounds__(ACC_THREADS) void k_accept(
+    const float *__restrict__ p, const float *__restrict__ q, const uint8_t *__restrict__ q_onehot,
+    const int32_t *__restrict__ draft, int32_t draft_stride, const float *__restrict__ u_acc,
+    const float *__restrict__ u_samp, int32_t k, int32_t V, float lenience, int32_t mode,
+    int32_t *__restrict__ n_accepted, int32_t *__restrict__ next_token) {
+    __shared__ AcceptShared S;
+    const int b = blockIdx.x;
+    int n, tok;
+    accept_core(S, p + (size_t)b * (k + 1) * V, q ? q + (size_t)b * k * V : nullptr, q_onehot, draft + (size_t)b * draft_stride,
+                u_acc ? u_acc + (size_t)b * k : nullptr, mode == CSD_MODE_SAMPLE ? u_samp[b] : 0.f, k, V, lenience, mode, n, tok);
+    if (threadIdx.x == 0) {
         n_accepted[b] = n;
         next_token[b] = tok;
     }
@@ -291,4 +305,163 @@ extern "C" int32_t csd_accept(const float *p, const float *q, const uint8_t *q_o
     if (mode != CSD_MODE_SAMPLE && mode != CSD_MODE_GREEDY) return CSD_EINVAL;
     return csd_accept_enqueue(p, q, q_onehot, draft, k, u_acc, u_samp, B, k, V, lenience, mode, n_accepted,
                               next_token, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------- device-resident control of the cascade
+//
+// A review that finds its block in the shared token buffer (Algorithm 1; Sections 3.2, 3.4): the reviewer scores the
+// tokens it has not cached yet, ctx[b][cache_len[b] .. ctx_len[b]) = the last kept tokens followed by the drafts in
+// flight, keeps a prefix of the drafts, appends its own token, and leaves the sequence, both lengths, the lower
+// levels' cache lengths and the draft distributions for the level above updated on the device.  A chain of such
+// calls runs a multi-level step with no host synchronisation; what a loop of Algorithm 1 decides on the host
+// ("until k_i tokens exist") is a per-sequence condition that the kernels evaluate themselves.
+
+// block[b][i] = ctx[b][cache_len[b] + i] for the rows the reviewer has not cached yet (zero padding up to m_max);
+// status[b]: 0 = review, 1 = skipped on request (prefix < 0), 2 = skipped because the state does not fit the call
+// (more uncached rows than m_max, a prefix outside the block, draft tables too short)
+__global__ void k_gather_block(const int32_t *__restrict__ ctx, int32_t ctx_stride, const int32_t *__restrict__ ctx_len,
+                               const int32_t *__restrict__ cache_len, const int32_t *__restrict__ prefix_len, int32_t m_max,
+                               const int32_t *__restrict__ q_base, int32_t q_stride, const int32_t *__restrict__ out_base,
+                               int32_t out_stride, int32_t *__restrict__ block, int32_t *__restrict__ status) {
+    const int b = blockIdx.x;
+    const int n = ctx_len[b], cl = cache_len[b], pf = prefix_len[b];
+    const int rows = n - cl;
+    int st = 0;
+    if (pf < 0) st = 1;
+    else if (cl < 0 || rows < 1 || rows > m_max || n >= ctx_stride || pf - 1 < cl || pf > n) st = 2;
+    else if (q_base && (pf - q_base[b] < 0 || n - q_base[b] > q_stride)) st = 2;
+    else if (out_base && (pf - out_base[b] < 0 || n + 1 - out_base[b] > out_stride)) st = 2;
+    for (int i = threadIdx.x; i < m_max; i += blockDim.x)
+        block[(size_t)b * m_max + i] = (st == 0 && i < rows) ? ctx[(size_t)b * ctx_stride + cl + i] : 0;
+    if (threadIdx.x == 0) status[b] = st;
+}
+
+struct ReviewArgs {
+    int32_t *ctx;
+    int32_t ctx_stride;
+    int32_t *ctx_len, *cache_len;
+    const int32_t *prefix_len;
+    const float *q_tab;
+    const uint8_t *q_onehot_tab;
+    const int32_t *q_base;
+    int32_t q_stride;
+    const float *u_acc_tab, *u_samp_tab;
+    float *out_q_tab;
+    uint8_t *out_onehot_tab;
+    const int32_t *out_base;
+    int32_t out_stride;
+    int32_t *lower[4];
+    int32_t n_lower;
+    int32_t *n_accepted, *next_token;
+    const int32_t *status;
+    const float *rows;       // reviewer rows [B][m_max][V]: probabilities, or logits for the plain greedy rule
+    int32_t m_max, V;
+    float lenience;
+    int32_t mode;
+};
+
+// accept / resample over the drafts in flight, then the commit: the reviewer's own token after the kept drafts, the
+// sequence length, this reviewer's cache length, the lower levels' cache lengths (clamped to what is still on the
+// path), and the rows the level above will review the emitted tokens against
+__global__ __launch_bounds__(ACC_THREADS) void k_review_commit(const ReviewArgs A) {
+    __shared__ AcceptShared S;
+    const int b = blockIdx.x;
+    if (A.status[b] != 0) {
+        if (threadIdx.x == 0) {
+            if (A.n_accepted) A.n_accepted[b] = -1;
+            if (A.next_token) A.next_token[b] = -1;
+        }
+        return;
+    }
+    const int n_tok = A.ctx_len[b], cl = A.cache_len[b], pf = A.prefix_len[b];
+    const int k = n_tok - pf, row0 = pf - 1 - cl, V = A.V;
+    const float *pb = A.rows + ((size_t)b * A.m_max + row0) * V;
+    int32_t *seq = A.ctx + (size_t)b * A.ctx_stride;
+    const int qi = A.q_base ? pf - A.q_base[b] : 0;
+    const float *qb = A.q_tab ? A.q_tab + ((size_t)b * A.q_stride + qi) * V : nullptr;
+    const uint8_t *oh = A.q_onehot_tab ? A.q_onehot_tab + (size_t)b * A.q_stride + qi : nullptr;
+    const float *ua = A.u_acc_tab ? A.u_acc_tab + (size_t)b * A.ctx_stride + pf : nullptr;
+    const float us = (A.mode == CSD_MODE_SAMPLE && A.u_samp_tab) ? A.u_samp_tab[(size_t)b * A.ctx_stride + pf] : 0.f;
+    int n, tok;
+    accept_core(S, pb, qb, oh, seq + pf, ua, us, k, V, A.lenience, A.mode, n, tok);
+    __syncthreads();                                         // every thread has read the lengths it needs
+    if (threadIdx.x == 0) {
+        seq[pf + n] = tok;
+        A.ctx_len[b] = pf + n + 1;
+        A.cache_len[b] = pf + n;
+        for (int i = 0; i < A.n_lower; i++) A.lower[i][b] = min(A.lower[i][b], pf + n);
+        if (A.n_accepted) A.n_accepted[b] = n;
+        if (A.next_token) A.next_token[b] = tok;
+    }
+    // the level above reviews the n + 1 emitted tokens against this reviewer's own rows (sampling); under the greedy
+    // rule a draft is its reviewer's arg-max: one-hot
+    if (A.out_onehot_tab && threadIdx.x <= n)
+        A.out_onehot_tab[(size_t)b * A.out_stride + pf + threadIdx.x - A.out_base[b]] = A.mode == CSD_MODE_SAMPLE ? 0 : 1;
+    if (A.out_q_tab && A.mode == CSD_MODE_SAMPLE) {
+        float *dst = A.out_q_tab + ((size_t)b * A.out_stride + pf - A.out_base[b]) * V;
+        const size_t total = (size_t)(n + 1) * V;
+        for (size_t i = threadIdx.x; i < total; i += blockDim.x) dst[i] = pb[i];
+    }
+}
+
+extern "C" int32_t csd_review_ctx(csd_model *mod, void *kv, const csd_review *r, int32_t B, int32_t m_max, float temperature,
+                                  float lenience, int32_t mode, void *stream) {
+    if (!r || !r->ctx || !r->ctx_len || !r->cache_len || !r->prefix_len || !r->status) return CSD_ENULL;
+    if (!mod || (!kv && !r->ext_rows)) return CSD_ENULL;
+    if (B < 1 || m_max < 1 || r->ctx_stride < 2) return CSD_EINVAL;
+    if (B > mod->cfg.max_batch || m_max > mod->cfg.max_block) return CSD_ESHAPE;
+    if (mode != CSD_MODE_SAMPLE && mode != CSD_MODE_GREEDY) return CSD_EINVAL;
+    if (!(lenience >= 1.0f) || lenience > 256.0f) return CSD_EINVAL;
+    const bool need_probs = mode == CSD_MODE_SAMPLE || lenience > 1.0f;
+    if (need_probs && !r->ext_rows && !(temperature > 0.f)) return CSD_EINVAL;
+    if (mode == CSD_MODE_SAMPLE && (!r->u_acc_tab || !r->u_samp_tab)) return CSD_ENULL;
+    if ((r->q_tab || r->q_onehot_tab) && (!r->q_base || r->q_stride < 1)) return CSD_EINVAL;
+    if ((r->out_q_tab || r->out_onehot_tab) && (!r->out_base || r->out_stride < 1)) return CSD_EINVAL;
+    if (r->n_lower < 0 || r->n_lower > 4) return CSD_EINVAL;
+    for (int i = 0; i < r->n_lower; i++)
+        if (!r->lower_cache_len[i]) return CSD_ENULL;
+    hipStream_t st = (hipStream_t)stream;
+    const int V = mod->cfg.vocab;
+    int32_t *block = mod->review_block;
+    hipLaunchKernelGGL(k_gather_block, dim3(B), dim3(64), 0, st, r->ctx, r->ctx_stride, r->ctx_len, r->cache_len, r->prefix_len, m_max,
+                       (r->q_tab || r->q_onehot_tab) ? r->q_base : nullptr, r->q_stride,
+                       (r->out_q_tab || r->out_onehot_tab) ? r->out_base : nullptr, r->out_stride, block, r->status);
+    CSD_LAUNCH_CHECK();
+    const float *rows = r->ext_rows;
+    if (!rows) {
+        int32_t rc;
+        float *lg = mod->probs;                               // logits, then probabilities in place
+        if ((rc = csd_forward_enqueue(mod, kv, block, r->cache_len, B, m_max, lg, st)) != CSD_OK) return rc;
+        if (need_probs && (rc = csd_softmax_enqueue(lg, lg, (int64_t)B * m_max, V, temperature, st)) != CSD_OK) return rc;
+        rows = lg;
+    }
+    ReviewArgs A;
+    A.ctx = r->ctx;
+    A.ctx_stride = r->ctx_stride;
+    A.ctx_len = r->ctx_len;
+    A.cache_len = r->cache_len;
+    A.prefix_len = r->prefix_len;
+    A.q_tab = r->q_tab;
+    A.q_onehot_tab = r->q_onehot_tab;
+    A.q_base = r->q_base;
+    A.q_stride = r->q_stride;
+    A.u_acc_tab = r->u_acc_tab;
+    A.u_samp_tab = r->u_samp_tab;
+    A.out_q_tab = r->out_q_tab;
+    A.out_onehot_tab = r->out_onehot_tab;
+    A.out_base = r->out_base;
+    A.out_stride = r->out_stride;
+    for (int i = 0; i < 4; i++) A.lower[i] = i < r->n_lower ? r->lower_cache_len[i] : nullptr;
+    A.n_lower = r->n_lower;
+    A.n_accepted = r->n_accepted;
+    A.next_token = r->next_token;
+    A.status = r->status;
+    A.rows = rows;
+    A.m_max = m_max;
+    A.V = V;
+    A.lenience = lenience;
+    A.mode = mode;
+    hipLaunchKernelGGL(k_review_commit, dim3(B), dim3(ACC_THREADS), 0, st, A);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
 }

@@ -150,6 +150,9 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     }
     char *static_base;
     if ((rc = static_scratch_base(&static_base)) != CSD_OK) return rc;   // looked up once per device, here
+    CSD_HIP(hipMalloc(&p, sizeof(int32_t) * (size_t)mod->m_max));
+    mod->allocs.push_back(p);
+    mod->review_block = (int32_t *)p;
     mod->ev.resize(8192);
     for (auto &e : mod->ev) CSD_HIP(hipEventCreate(&e));
     return CSD_OK;

@@ -65,6 +65,60 @@ __global__ __launch_bounds__(DRAFT_THREADS) void k_bigram_draft(
     for (int j = threadIdx.x; j < k; j += blockDim.x) out[j] = s[e + 1 + (j % period)];
 }
 
+// k_bigram_draft that appends its drafts to the context itself (device-resident cascade control): sequences whose
+// drafts in flight already number `need` or more (counted from start_len) are left alone.
+__global__ __launch_bounds__(DRAFT_THREADS) void k_bigram_draft_append(
+    int32_t *__restrict__ ctx, int32_t ctx_stride, int32_t *__restrict__ ctx_len, const int32_t *__restrict__ next_table,
+    int32_t vocab, int32_t k, int32_t max_match, const int32_t *__restrict__ gate, uint8_t *__restrict__ q_onehot_tab,
+    const int32_t *__restrict__ q_base, int32_t q_stride) {
+    __shared__ unsigned long long red[DRAFT_THREADS / 64];
+    const int b = blockIdx.x;
+    int32_t *s = ctx + (size_t)b * ctx_stride;
+    const int len = ctx_len[b];
+    bool active = len >= 1 && len + k < ctx_stride && (!gate || gate[b] >= 0);
+    if (active && q_onehot_tab && (len - q_base[b] < 0 || len + k - q_base[b] > q_stride)) active = false;
+    if (!active) return;                                     // uniform over the workgroup
+    unsigned long long best = 0ull;
+    for (int e = threadIdx.x; e <= len - 2; e += blockDim.x) {
+        int r = 0;
+        while (r <= e && (max_match <= 0 || r < max_match) && s[e - r] == s[len - 1 - r]) r++;
+        if (r > 0) {
+            unsigned long long key = ((unsigned long long)(uint32_t)r << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+            best = key > best ? key : best;
+        }
+    }
+    best = block_max_u64(best, red);                         // (its barriers: every thread has read the context by now)
+    const int mlen = (int)(best >> 32);
+    int32_t *out = s + len;
+    if (mlen == 0) {
+        if (threadIdx.x == 0) {                              // bigram chain from the last token
+            int32_t cur = s[len - 1];
+            for (int j = 0; j < k; j++) {
+                cur = (cur >= 0 && cur < vocab) ? next_table[cur] : -1;
+                out[j] = cur;
+            }
+        }
+    } else {
+        const int e = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+        const int period = len - (e + 1);                    // sources s[e + 1 ..  len - 1] lie before the drafts
+        for (int j = threadIdx.x; j < k; j += blockDim.x) out[j] = s[e + 1 + (j % period)];
+    }
+    if (q_onehot_tab)
+        for (int j = threadIdx.x; j < k; j += blockDim.x) q_onehot_tab[(size_t)b * q_stride + len + j - q_base[b]] = 1;
+    if (threadIdx.x == 0) ctx_len[b] = len + k;
+}
+
+// gate[b] = ctx_len[b] when sequence b still needs tokens in the loop that started at loop_start[b] (fewer than `need`
+// exist) and the enclosing step is itself active (parent_gate null or >= 0); else -1.  A step gated with this value
+// reviews drafts that start at that position.
+__global__ void k_cascade_gate(const int32_t *__restrict__ ctx_len, const int32_t *__restrict__ loop_start, int32_t need,
+                               const int32_t *__restrict__ parent_gate, int32_t B, int32_t *__restrict__ gate) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const bool on = (!parent_gate || parent_gate[b] >= 0) && (!loop_start || ctx_len[b] - loop_start[b] < need);
+    gate[b] = on ? ctx_len[b] : -1;
+}
+
 // Max-Gram with the haystack apart from the needle (Appendix A's own signature: the encoder's ids are searched
 // for the longest suffix of the decoder's ids).  Candidate match ends are all haystack positions; the key is
 // the same (match length, ~end).  The continuation is copied while the haystack lasts (out_n_copied of the k
@@ -174,6 +228,31 @@ extern "C" int32_t csd_maxgram_draft(const int32_t *haystack, const int32_t *hay
     hipLaunchKernelGGL(k_maxgram_enc, dim3(B), dim3(DRAFT_THREADS), 0, (hipStream_t)stream, haystack, haystack_len,
                        haystack_stride, needle, needle_len, needle_stride, next_table, vocab, k, max_match, out_tokens,
                        out_match_len, out_n_copied);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_bigram_draft_append(int32_t *ctx, int32_t ctx_stride, int32_t *ctx_len, int32_t B,
+                                           const int32_t *next_table, int32_t vocab, int32_t k, int32_t max_match,
+                                           const int32_t *gate, uint8_t *q_onehot_tab, const int32_t *q_base,
+                                           int32_t q_stride, void *stream) {
+    if (!ctx || !ctx_len || !next_table) return CSD_ENULL;
+    if (B < 0 || k < 0 || vocab < 1 || ctx_stride < 1) return CSD_EINVAL;
+    if (q_onehot_tab && (!q_base || q_stride < 1)) return CSD_EINVAL;
+    if (B == 0) return CSD_OK;
+    hipLaunchKernelGGL(k_bigram_draft_append, dim3(B), dim3(DRAFT_THREADS), 0, (hipStream_t)stream, ctx, ctx_stride, ctx_len,
+                       next_table, vocab, k, max_match, gate, q_onehot_tab, q_base, q_stride);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_cascade_gate(const int32_t *ctx_len, const int32_t *loop_start, int32_t need, const int32_t *parent_gate,
+                                    int32_t B, int32_t *gate, void *stream) {
+    if (!ctx_len || !gate) return CSD_ENULL;
+    if (B < 0) return CSD_EINVAL;
+    if (B == 0) return CSD_OK;
+    hipLaunchKernelGGL(k_cascade_gate, dim3((B + 63) / 64), dim3(64), 0, (hipStream_t)stream, ctx_len, loop_start, need, parent_gate,
+                       B, gate);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }

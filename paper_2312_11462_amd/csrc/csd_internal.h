@@ -240,6 +240,7 @@ struct csd_model {
     int32_t *rel_bucket = nullptr;   // [128] bucket of distance n (n >= 127 shares the last entry)
     float *rel_bias_hd = nullptr;    // [H][128]: rel_bias[rel_bucket[n]][h]
     float *trace = nullptr;
+    int32_t *review_block = nullptr;  // [max_batch][max_block] block tokens gathered by csd_review_ctx
     // profiling
     bool prof = false;
     std::vector<hipEvent_t> ev;

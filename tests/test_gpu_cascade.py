@@ -177,3 +177,96 @@ def test_sampling_cascade_matches_the_oracle_driver_token_for_token(K, lenience)
     ogot, osteps = OC.cascade_generate(olevels, otable, prompt, n_new, K, lenience=lenience, mode=0, uniforms=_u24(17))
     assert steps == osteps
     assert got == ogot
+
+
+# ------------------------------------------------------------------ device-resident control
+
+def _oracle_steps(olevels, otable, prompt, K, lenience, mode, n_steps, uniform_at=None):
+    from oracle import cascade as OC
+    seq = list(prompt)
+    for lv in olevels:
+        lv.cached = 0
+    for _ in range(n_steps):
+        toks, _ = OC._step(olevels, otable, seq, K, lenience, mode, None, True, 0, uniform_at, 0)
+        seq += toks
+    return seq
+
+
+@pytest.mark.parametrize("K,lenience,n_drafts", [
+    ([[4]], 1.0, 0),
+    ([[2, 6], [0, 6]], 1.0, 1),
+    ([[2, 3], [0, 4]], 3.0, 1),
+    ([[2, 2, 3], [0, 1, 3], [0, 0, 3]], 2.0, 2),
+])
+def test_resident_cascade_greedy_equals_the_oracle_driver_step_for_step(K, lenience, n_drafts):
+    """Algorithm 1 as a chain of enqueues with device-resident control (no host synchronisation inside or between
+    steps): after 10 steps the kept sequence equals the oracle driver's after 10 steps, and the target's own greedy
+    continuation."""
+    from paper_2312_11462_amd.cascade import ResidentCascade, autoregressive
+    from oracle import csd_oracle as O
+    from oracle import cascade as OC
+    prompt = _prompt(512, 21)
+    table = _table(prompt, 512)
+    shapes = [TARGET, DRAFT1, DRAFT2][:n_drafts + 1]
+    levels = [_gpu_level(s, 1 + i, 0.2) for i, s in enumerate(shapes)]
+    rc = ResidentCascade(levels, table, K, MAX_CTX, lenience=lenience, mode=1)
+    rc.start(prompt)
+    for _ in range(10):
+        rc.step()
+    got = rc.tokens()
+    assert all(int(st.item()) in (0, 1) for st in rc.status)
+    olevels = []
+    for i, s in enumerate(shapes):
+        w = I.make_weights(s, 1 + i, device="cpu", std=0.2)
+        olevels.append(OC.Level(O.Model(s, w, max_batch=1, max_seq=MAX_CTX, max_block=16), 16))
+    otable = O.bigram_fit(np.array(prompt, np.int32), 512, I.default_next_table(512, 1).numpy())
+    want = _oracle_steps(olevels, otable, prompt, K, lenience, 1, 10)
+    assert got == want
+    assert got[len(prompt):] == autoregressive(levels[0], prompt, len(got) - len(prompt), MAX_CTX)
+
+
+class _FixedResidentLevel:
+    """A level whose reviewer rows are inputs (the same fp32 distribution in every row): csd_review_ctx then runs
+    no forward, only the device-resident accept and commit."""
+
+    def __init__(self, probs, vocab, max_block=16):
+        import paper_2312_11462_amd as P
+        shape = I.ModelShape("fixed", 0, "fp32", 1, 16, 1, 16, 16, vocab)
+        self.model = P.Model(shape, I.make_weights(shape, 1, device="cuda"), max_batch=1, max_seq=64, max_block=max_block)
+        self.max_block = max_block
+        self.ext_rows = torch.tensor(np.tile(probs, (max_block, 1))[None], dtype=torch.float32).cuda().contiguous()
+
+
+@pytest.mark.parametrize("K,lenience", [
+    ([[3, 2, 0], [0, 0, 0], [0, 0, 0]], 1.0),        # horizontal: 3 tokens of level 1, 2 of level 2
+    ([[4, 0, 0], [0, 3, 0], [0, 0, 0]], 1.0),        # vertical: level 1 reviews level 2's drafts
+    ([[2, 1, 3], [0, 2, 2], [0, 0, 2]], 2.5),        # both, with Max-Gram drafts and lenience between draft levels
+])
+def test_resident_cascade_sampling_matches_the_oracle_driver_token_for_token(K, lenience):
+    """Sampling mode with levels whose distributions are inputs, uniforms taken by position on both sides: dense
+    draft distributions handed upward on the device, Max-Gram positions one-hot, gated worst-case rounds."""
+    from paper_2312_11462_amd.cascade import ResidentCascade
+    from oracle import csd_oracle as O
+    V, n_steps, max_ctx = 37, 60, 1024
+    rs = np.random.RandomState(5)
+    logits = [np.log(rs.dirichlet(np.full(V, a))) for a in (0.6, 0.8, 2.0)]
+    probs = [O.probs_f32(lg[None])[0] for lg in logits]
+    logits32 = [np.asarray(lg, np.float32) for lg in logits]
+    prompt = _prompt(V, 3)
+    table = _table(prompt, V)
+    glevels = [_FixedResidentLevel(pr, V) for pr in probs]
+    rc = ResidentCascade(glevels, table, K, max_ctx, lenience=lenience, mode=0)
+    u = np.random.RandomState(17).randint(0, 1 << 24, size=(3, 2, max_ctx)).astype(np.float32) / np.float32(1 << 24)
+    for i in range(3):
+        rc.u_acc[i].copy_(torch.tensor(u[i, 0][None]))
+        rc.u_samp[i].copy_(torch.tensor(u[i, 1][None]))
+    rc.start(prompt)
+    for _ in range(n_steps):
+        rc.step()
+    got = rc.tokens()
+    assert all(int(st.item()) in (0, 1) for st in rc.status)
+    olevels = [_FixedOracleLevel(lg.astype(np.float64)) for lg in logits32]
+    otable = O.bigram_fit(np.array(prompt, np.int32), V, I.default_next_table(V, 1).numpy())
+    want = _oracle_steps(olevels, otable, prompt, K, lenience, 0, n_steps, lambda d, kind, pos: float(u[d, kind, pos]))
+    assert got == want
+    assert len(got) - len(prompt) >= n_steps

@@ -158,3 +158,26 @@ def test_accept_long_blocks_odd_vocab_and_invalid_draft_ids(P):
     gn, gt = P.accept(p.cuda(), None, bad.cuda(), torch.zeros((B, k)).cuda(), u_s.cuda(), 1.0, 0)
     gn, gt = gn.cpu().numpy(), gt.cpu().numpy()
     assert gn[1] == 66 and gn[2] == 0 and (0 <= gt).all() and (gt < V).all()
+
+
+def test_out_of_range_draft_is_a_rejection_drawn_from_the_reviewers_row(P):
+    """A draft id outside [0, V) cannot be validated on the host.  The kernel treats it as a rejection at that
+    position and draws the replacement from the reviewer's row there, with or without dense draft rows: the
+    same outcome as the oracle gives for the block cut before that position (the draw of the extra token
+    from that row with the same uniform)."""
+    O = _O()
+    B, k, V, seed = 3, 5, 300, 31
+    p = _rand_dist((B, k + 1, V), seed, 1, 3.0)
+    q = _rand_dist((B, k, V), seed, 2, 3.0)
+    draft = p[:, :k, :].argmax(-1).to(torch.int32)            # likely accepted drafts
+    u_acc = torch.zeros((B, k), dtype=torch.float32)           # u = 0: every valid draft with p > 0 is accepted
+    u_s = I.uniforms(B, seed, 3)
+    for bad_pos, bad_id in [(0, -1), (2, V), (4, 1 << 30)]:
+        d = draft.clone()
+        d[:, bad_pos] = bad_id
+        for dense in (False, True):
+            gn, gt = P.accept(p.cuda(), q.cuda() if dense else None, d.cuda(), u_acc.cuda(), u_s.cuda())
+            on, ot = O.accept(p[:, :bad_pos + 1].numpy(), q[:, :bad_pos].numpy() if dense else None, d[:, :bad_pos].numpy(),
+                              u_acc[:, :bad_pos].numpy(), u_s.numpy())
+            assert np.array_equal(gn.cpu().numpy(), on) and (on == bad_pos).all()
+            assert np.array_equal(gt.cpu().numpy(), ot)
