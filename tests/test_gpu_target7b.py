@@ -114,3 +114,39 @@ def test_target7b_batch8_prefix2048(big, k, oracle_b):
     _fill(gm, om, shape, seed, t, B, oracle_b)
     block = I.token_ids(B * m, shape.vocab, seed, 200 + k).reshape(B, m).contiguous()
     _compare(gm, om, block, [t] * B, oracle_b, f"7B b8 t2048 k{k} seq{oracle_b}")
+
+
+def test_two_level_step_of_configuration_3_with_device_resident_control(big):
+    """Configuration 3 as one step of Algorithm 1 at full size, K = [[2, 3], [0, 8]], greedy rule: the 160M-shaped
+    level reviews Max-Gram drafts until two of its tokens exist, Max-Gram adds three, the 7B-shaped target reviews;
+    one chain of enqueues with device-resident control.  The kept tokens equal the oracle driver's for the same
+    seeded weights and stand-in caches (1024 rows in both models)."""
+    P, O, gm, om, shape, seed = big
+    from oracle import cascade as OC
+    from paper_2312_11462_amd.cascade import Level, ResidentCascade
+    t = 1024
+    dwl = I.WORKLOADS["draft160m"]
+    dshape, dseed = dwl["shape"], dwl["seed"]
+    dw = I.make_weights(dshape, dseed, device="cuda")
+    gd = P.Model(dshape, dw, max_batch=1, max_seq=t + 64, max_block=16)
+    od = O.Model(dshape, [x.cpu() for x in dw], max_batch=1, max_seq=t + 64, max_block=16)
+    del dw
+    _fill(gm, om, shape, seed, t, 1, 0)
+    _fill(gd, od, dshape, dseed, t, 1, 0)
+    prompt = I.repeat_stream(t + 1, shape.vocab, seed, 10)
+    table = P.bigram_fit(prompt.cuda(), shape.vocab, I.default_next_table(shape.vocab, seed).cuda())
+    K = [[2, 3], [0, 8]]
+    rc = ResidentCascade([Level(gm, 16), Level(gd, 16)], table, K, t + 64, mode=1)
+    rc.ctx[0, :t + 1] = prompt.cuda()
+    rc.ctx_len.fill_(t + 1)
+    rc.cache_len[0].fill_(t)
+    rc.cache_len[1].fill_(t)
+    rc.step()
+    got = rc.tokens()
+    assert [int(s.item()) for s in rc.status] == [0, 0]
+    print("device-resident two-level step: kept", got[t + 1:], "accepted by target / draft level:",
+          int(rc.n_acc[0].item()), int(rc.n_acc[1].item()), flush=True)
+    ot, odl = OC.Level(om, 16), OC.Level(od, 16)
+    ot.cached = odl.cached = t
+    toks, _ = OC._step([ot, odl], table.cpu().numpy(), prompt.tolist(), K, 1.0, 1, None, True, 0)
+    assert got[t + 1:] == toks
