@@ -244,3 +244,57 @@ def softmax(logits, temperature=1.0):
     p = np.empty_like(x)
     lib().csdo_softmax(_p(x), x.shape[0], C.c_double(1.0 / temperature), _p(p))
     return p
+
+
+def accept_margins(p, q, draft, u_acc, u_samp, lenience=1.0, mode=0, q_onehot=None):
+    """How far each decision of accept() on sequence 0 is from flipping (plain Python over the same rule,
+    Section 2 / 3.1), for comparisons between implementations whose probabilities differ within a tolerance:
+      tests: list of (accepted, |u q(x) - l p(x)| / (l p(x))) for every acceptance test that was evaluated;
+      draw:  distance of the draw's threshold to the nearest boundary of the chosen token's CDF interval, as a
+             fraction of the total weight (sampling), or the gap between the two largest entries of the row (greedy).
+    Returns (n_accepted, next_token, tests, draw)."""
+    p = np.asarray(p, dtype=np.float32)
+    _, k1, V = p.shape
+    k = k1 - 1
+    lf = np.float32(lenience)
+    tests = []
+    n = 0
+    if mode == 1:
+        for i in range(k):
+            top2 = np.sort(p[0, i])[-2:]
+            ok = int(draft[0][i]) == int(np.argmax(p[0, i]))
+            tests.append((ok, float(top2[1] - top2[0])))
+            if not ok:
+                break
+            n += 1
+        row = p[0, n]
+        top2 = np.sort(row)[-2:]
+        return n, int(np.argmax(row)), tests, float(top2[1] - top2[0])
+    for i in range(k):
+        x = int(draft[0][i])
+        dense = q is not None and not (q_onehot is not None and q_onehot[i])
+        qx = np.float32(q[0, i, x]) if dense else np.float32(1.0)
+        lhs = np.float32(np.float32(u_acc[0][i]) * qx)
+        rhs = np.float32(lf * p[0, i, x])
+        ok = bool(lhs < rhs)
+        tests.append((ok, float(abs(float(lhs) - float(rhs)) / max(float(rhs), 1e-30))))
+        if not ok:
+            break
+        n += 1
+    row = p[0, n].astype(np.float32)
+    if n < k:
+        x = int(draft[0][n])
+        dense = q is not None and not (q_onehot is not None and q_onehot[n])
+        qrow = q[0, n].astype(np.float32) if dense else np.eye(V, dtype=np.float32)[x]
+        r = np.maximum(np.float32(0), (lf * row).astype(np.float32) - qrow).astype(np.float32)
+        if not (r > 0).any():
+            r = row
+    else:
+        r = row
+    w = np.floor(r.astype(np.float64) * 2.0 ** 40)
+    Z = w.sum()
+    T = np.floor(np.floor(float(u_samp[0]) * 2.0 ** 24) * Z / 2.0 ** 24)
+    cum = np.cumsum(w)
+    tok = int(np.searchsorted(cum, T, side="right"))
+    lo = cum[tok - 1] if tok > 0 else 0.0
+    return n, tok, tests, float(min(T - lo, cum[tok] - T) / Z)

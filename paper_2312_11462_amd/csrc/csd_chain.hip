@@ -625,10 +625,6 @@ static int32_t chain_launch(ChainGemm &P, int n_tiles, hipStream_t st) {
     // a workgroup per compute unit, or as many more as keep a workgroup's tiles to eight
     int G = P.n_units < 256 ? P.n_units : 256;
     if ((P.n_units + G - 1) / G * UT > 8) G = (P.n_units * UT + 7) / 8;
-    if (const char *e = getenv("CSD_CHAIN_UPW")) {      // experiment: units per workgroup by kind of GEMM (digits: qkv, resid, gu, logits)
-        const int upw = e[EPI] - '0';
-        if (upw > 0) G = (P.n_units + upw - 1) / upw;
-    }
     const int per = (P.n_units + G - 1) / G * UT;            // most tiles of a workgroup
 #define CH_LAUNCH(NT, R, E)                                                                                       \
     if (per <= NT) {                                                                                              \

@@ -258,3 +258,27 @@ def test_argument_errors():
         O.accept(p, None, [[5]], [[0.1]], [0.1])          # draft id out of range
     with pytest.raises(RuntimeError):
         O.accept(p, None, [[1]], [[0.1]], [0.1], lenience=0.5)
+
+
+def test_margin_report_reproduces_the_decisions_and_measures_their_distance():
+    """accept_margins walks the same rule in plain Python: its decisions equal accept()'s, a test decided at the
+    boundary has margin 0, and a draw's margin is at most half the chosen token's share of the weight."""
+    rng = np.random.default_rng(3)
+    V, k = 50, 4
+    for trial in range(200):
+        p = rng.dirichlet(np.full(V, 0.3), size=(1, k + 1)).astype(np.float32)
+        q = rng.dirichlet(np.full(V, 0.3), size=(1, k)).astype(np.float32)
+        d = rng.integers(0, V, size=(1, k)).astype(np.int32)
+        u = (rng.integers(0, 1 << 24, size=(1, k)) / float(1 << 24)).astype(np.float32)
+        us = (rng.integers(0, 1 << 24, size=1) / float(1 << 24)).astype(np.float32)
+        for mode, qq in ((0, q), (0, None), (1, None)):
+            n, tok = O.accept(p, qq, d, u, us, 1.0, mode)
+            mn, mtok, tests, draw = O.accept_margins(p, qq, d, u, us, 1.0, mode)
+            assert (mn, mtok) == (int(n[0]), int(tok[0]))
+            assert len(tests) == min(k, mn + 1) and all(t[0] for t in tests[:mn])
+            if mode == 0:
+                assert 0.0 <= draw <= 0.5 + 1e-9
+    # a test exactly on the boundary: u q = l p -> rejected (strict <) with margin 0
+    p = np.full((1, 2, 4), 0.25, np.float32)
+    n, tok, tests, _ = O.accept_margins(p, None, np.array([[1]], np.int32), np.array([[0.25]], np.float32), np.array([0.0], np.float32))
+    assert n == 0 and tests == [(False, 0.0)]
