@@ -22,6 +22,20 @@ __device__ __forceinline__ unsigned long long fixed40(float r) {
     return shift <= -24 ? 0ull : (mant >> (-shift));
 }
 
+// The same number for r in [0, 2^12), without branches or 64-bit shifts, as h * 2^20 + l: h = floor(r * 2^20) (a
+// power-of-two scaling and a truncation, both exact), what is left of r * 2^20 is below one and exact as well
+// (a float minus its own integer part), and its first 20 binary places are l.  Negative values and NaN give 0.
+__device__ __forceinline__ void fixed40_parts(float r, uint32_t &h, uint32_t &l) {
+    const float a = fmaxf(r, 0.0f) * 0x1p20f;
+    h = (uint32_t)a;
+    l = (uint32_t)((a - (float)h) * 0x1p20f);
+}
+__device__ __forceinline__ unsigned long long fixed40_small(float r) {
+    uint32_t h, l;
+    fixed40_parts(r, h, l);
+    return (unsigned long long)h * (1u << 20) + l;
+}
+
 // residual weight of token v at a rejected position: max(0, l*p_v - q_v) in fp32, or p_v itself
 __device__ __forceinline__ float weight_at(const float *__restrict__ prow, const float *__restrict__ qrow, int x,
                                            float lenience, bool residual, int v) {
@@ -228,12 +242,38 @@ __global__ __launch_bounds__(ACC_THREADS) void k_accept(
     }
 }
 
-// one workgroup per row: p = exp((x - max) / T) / sum.  Each thread keeps its SM_PER elements in
-// registers between the three steps (rows longer than SM_THREADS * SM_PER take the generic loop).
+// ------------------------------------------------------------------------------------------------ softmax
+//
+// p = e_v / sum_v e_v with e_v = exp(x_v / T - max).  The sum is taken exactly: every e_v (in [0, 1]) goes to 40-bit
+// fixed point and the integers are added, so the sum, and with it every probability, does not depend on how the
+// row is spread over threads.  Two kernels with different layouts (k_softmax, k_review_rows) therefore produce
+// the same bits.
 #define SM_THREADS 1024
 #define SM_PER 32
+
+__device__ __forceinline__ unsigned long long block_sum_u64(unsigned long long v, unsigned long long *red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    const int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    unsigned long long t = 0ull;
+    for (int i = 0; i < nw; i++) t += red[i];
+    return t;
+}
+__device__ __forceinline__ float scaled_logit(float x, float inv_t) { return x * inv_t; }
+__device__ __forceinline__ float exp_term(float xs, float mx) { return expf(xs - mx); }
+// 1 / sum from the fixed-point total (at most 2^15 terms of at most 2^40 each)
+__device__ __forceinline__ float recip_of_total(unsigned long long total) {
+    return 1.0f / (__ull2float_rn(total) * 0x1p-40f);
+}
+
+// one workgroup per row.  Each thread keeps its SM_PER elements in registers between the three steps (rows
+// longer than SM_THREADS * SM_PER take the generic loop).
 __global__ __launch_bounds__(SM_THREADS) void k_softmax(const float *logits, float *probs, int32_t V, float inv_t) {
     __shared__ float red[SM_THREADS / 64];
+    __shared__ unsigned long long red64[SM_THREADS / 64];
     const float *x = logits + (size_t)blockIdx.x * V;
     float *y = probs + (size_t)blockIdx.x * V;
     if (V <= SM_THREADS * SM_PER) {
@@ -242,18 +282,19 @@ __global__ __launch_bounds__(SM_THREADS) void k_softmax(const float *logits, flo
 #pragma unroll
         for (int i = 0; i < SM_PER; i++) {
             const int v = i * SM_THREADS + (int)threadIdx.x;
-            val[i] = v < V ? x[v] * inv_t : -INFINITY;
+            val[i] = v < V ? scaled_logit(x[v], inv_t) : -INFINITY;
             mx = fmaxf(mx, val[i]);
         }
         mx = block_max(mx, red);
-        float s = 0.f;
+        uint32_t sh = 0, sl = 0;                    // at most 32 terms of at most 2^20 each
 #pragma unroll
         for (int i = 0; i < SM_PER; i++) {
-            val[i] = expf(val[i] - mx);          // exp(-inf) = 0 for the padding
-            s += val[i];
+            val[i] = exp_term(val[i], mx);          // exp(-inf) = 0 for the padding
+            uint32_t h, l;
+            fixed40_parts(val[i], h, l);
+            sh += h, sl += l;
         }
-        s = block_sum(s, red);
-        const float r = 1.0f / s;
+        const float r = recip_of_total(block_sum_u64((unsigned long long)sh * (1u << 20) + sl, red64));
 #pragma unroll
         for (int i = 0; i < SM_PER; i++) {
             const int v = i * SM_THREADS + (int)threadIdx.x;
@@ -262,16 +303,15 @@ __global__ __launch_bounds__(SM_THREADS) void k_softmax(const float *logits, flo
         return;
     }
     float mx = -INFINITY;
-    for (int v = threadIdx.x; v < V; v += blockDim.x) mx = fmaxf(mx, x[v] * inv_t);
+    for (int v = threadIdx.x; v < V; v += blockDim.x) mx = fmaxf(mx, scaled_logit(x[v], inv_t));
     mx = block_max(mx, red);
-    float s = 0.f;
+    unsigned long long s = 0ull;
     for (int v = threadIdx.x; v < V; v += blockDim.x) {
-        const float e = expf(x[v] * inv_t - mx);
+        const float e = exp_term(scaled_logit(x[v], inv_t), mx);
         y[v] = e;
-        s += e;
+        s += fixed40_small(e);
     }
-    s = block_sum(s, red);
-    const float r = 1.0f / s;
+    const float r = recip_of_total(block_sum_u64(s, red64));
     for (int v = threadIdx.x; v < V; v += blockDim.x) y[v] *= r;
 }
 
@@ -279,6 +319,281 @@ int32_t csd_softmax_enqueue(const float *logits, float *probs, int64_t rows, int
                             hipStream_t st) {
     if (rows <= 0) return CSD_OK;
     hipLaunchKernelGGL(k_softmax, dim3((unsigned)rows), dim3(SM_THREADS), 0, st, logits, probs, V, 1.0f / temperature);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
+// ------------------------------------------------------------------------- the review, every row at once
+//
+// The rule of Section 2 / 3.1 walks the drafts in order, but what a row contributes does not depend on the rows
+// before it: whether its draft passes, and which token replaces it if it does not.  So a workgroup per
+// (row, sequence) normalises its row in registers (the same arithmetic as k_softmax), tests its own draft, and, if
+// the draft fails (or the row is the extra one after the drafts), draws the replacement.  It leaves (passed, token)
+// in a record; the last workgroup of a sequence to arrive (a counter) picks the first failing row.  No
+// probability is written unless the caller asks for it, rows are read once, and nothing waits on anything.
+//
+// Wave w holds tokens [4096 w, 4096 w + 4096), and in it lane l holds the 4-token groups at 256 j + 4 l, j = 0..15:
+// every load is a contiguous kilobyte per wave, and token order is (wave, j, lane, position in the group), which
+// is the order the draw's running sum follows.  The result is that of k_softmax + k_accept bit for bit (exact sums
+// on both sides).  V <= RR_THREADS * RR_PER; 512 threads, so that a thread may hold its 64 values and more in registers.
+// raw: greedy review with lenience 1, which compares token ids of the arg max of the logits themselves.
+#define RR_THREADS 512
+#define RR_PER 64
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__global__ __launch_bounds__(RR_THREADS) void k_review_rows(
+    const float *__restrict__ logits, float *__restrict__ probs, unsigned long long *__restrict__ recs,
+    unsigned *__restrict__ counters, float inv_t, const float *__restrict__ q, const uint8_t *__restrict__ q_onehot,
+    const int32_t *__restrict__ draft, int32_t draft_stride, const float *__restrict__ u_acc,
+    const float *__restrict__ u_samp, int32_t k, int32_t V, float lenience, int32_t mode, int32_t raw,
+    int32_t *__restrict__ n_accepted, int32_t *__restrict__ next_token) {
+    constexpr int NG = RR_PER / 4;                               // 4-token groups per thread
+    __shared__ float red[RR_THREADS / 64];
+    __shared__ unsigned long long red64[RR_THREADS / 64];
+    __shared__ ArgMax red_am[RR_THREADS / 64];
+    __shared__ int s_tok;
+    __shared__ unsigned s_old;
+    const int row = blockIdx.x, b = blockIdx.y;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const size_t row_off = ((size_t)b * (k + 1) + row) * V;
+    const float *xr = logits + row_off;
+    const int vbase = wv * (64 * RR_PER) + 4 * lane;             // token of (group j, position c): vbase + 256 j + c
+    // what the test of this row's draft needs, requested first: the draft id leads to two more loads
+    const bool has_draft = row < k;
+    int xd = -1;
+    bool valid = false, dense = false;
+    float x_logit = 0.f, qx = 1.0f, ua = 0.f, us = 0.f;
+    if (has_draft) {
+        xd = draft[(size_t)b * draft_stride + row];
+        valid = xd >= 0 && xd < V;                              // an invalid draft id is a rejection
+        dense = q && !(q_onehot && q_onehot[row]);
+        if (mode == CSD_MODE_SAMPLE) ua = u_acc[(size_t)b * k + row];
+    }
+    if (mode == CSD_MODE_SAMPLE) us = u_samp[b];
+    float val[RR_PER];
+#pragma unroll
+    for (int j = 0; j < NG; j++) {                               // (V is a multiple of 4 and the rows are 16-byte aligned)
+        const int v = vbase + 256 * j;
+        float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        if (v < V) t = *reinterpret_cast<const float4 *>(xr + v);
+        val[4 * j] = t.x, val[4 * j + 1] = t.y, val[4 * j + 2] = t.z, val[4 * j + 3] = t.w;
+    }
+    if (valid) x_logit = xr[xd];                                // behind the row's loads, which do not wait for the id
+    if (valid && dense) qx = q[((size_t)b * k + row) * V + xd];
+    if (threadIdx.x == 0) s_tok = -1;
+
+    ArgMax best = {-INFINITY, 0x7FFFFFFF};
+    if (raw) {          // arg max of the logits (ties: the smaller id; NaN and the -inf padding never win)
+#pragma unroll
+        for (int i = 0; i < RR_PER; i++)
+            if (val[i] > best.v) best = {val[i], vbase + 256 * (i >> 2) + (i & 3)};
+    }
+    float px = x_logit, mx = -INFINITY, r = 1.0f;
+    if (!raw || probs) {
+#pragma unroll
+        for (int i = 0; i < RR_PER; i++) {
+            val[i] = scaled_logit(val[i], inv_t);
+            mx = fmaxf(mx, val[i]);
+        }
+        mx = block_max(mx, red);
+        uint32_t sh = 0, sl = 0;                                 // at most 64 terms of at most 2^20 each
+#pragma unroll
+        for (int i = 0; i < RR_PER; i++) {
+            val[i] = exp_term(val[i], mx);
+            uint32_t h, l;
+            fixed40_parts(val[i], h, l);
+            sh += h, sl += l;
+        }
+        r = recip_of_total(block_sum_u64((unsigned long long)sh * (1u << 20) + sl, red64));
+#pragma unroll
+        for (int i = 0; i < RR_PER; i++) val[i] = val[i] * r;
+        px = exp_term(scaled_logit(x_logit, inv_t), mx) * r;
+        if (probs) {
+            float *yr = probs + row_off;
+#pragma unroll
+            for (int j = 0; j < NG; j++) {
+                const int v = vbase + 256 * j;
+                if (v < V)
+                    *reinterpret_cast<float4 *>(yr + v) = make_float4(val[4 * j], val[4 * j + 1], val[4 * j + 2], val[4 * j + 3]);
+            }
+        }
+    }
+
+    bool ok = false;
+    int tok = -1;
+    if (mode == CSD_MODE_GREEDY) {
+        if (!raw) {
+#pragma unroll
+            for (int i = 0; i < RR_PER; i++)             // (the padding holds 0 at ids above every real one: it loses ties)
+                if (val[i] > best.v) best = {val[i], vbase + 256 * (i >> 2) + (i & 3)};
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            ArgMax other = {__shfl_xor(best.v, o, 64), __shfl_xor(best.i, o, 64)};
+            best = better(best, other);
+        }
+        __syncthreads();
+        if (lane == 0) red_am[wv] = best;
+        __syncthreads();
+        ArgMax t = red_am[0];
+        for (int i = 1; i < RR_THREADS / 64; i++) t = better(t, red_am[i]);
+        tok = t.i == 0x7FFFFFFF ? 0 : min(t.i, V - 1);
+        if (has_draft) {
+            ok = xd == tok;
+            if (!ok && lenience > 1.0f && valid) ok = qx <= __fmul_rn(lenience, px);
+        }
+    } else {
+        if (has_draft && valid) ok = __fmul_rn(ua, qx) < __fmul_rn(lenience, px);
+        if (!ok) {
+            // the replacement: from norm(max(0, l p - q)) after a failed test of a valid draft, else from p itself
+            bool residual = has_draft && valid;
+            const float *qrow = residual && dense ? q + ((size_t)b * k + row) * V : nullptr;
+            if (residual) {                                  // the weights take the probabilities' place
+#pragma unroll
+                for (int j = 0; j < NG; j++) {
+                    float qv[4] = {0.f, 0.f, 0.f, 0.f};
+                    const int v = vbase + 256 * j;
+                    if (qrow) {
+                        if (v < V) {
+                            const float4 t = *reinterpret_cast<const float4 *>(qrow + v);
+                            qv[0] = t.x, qv[1] = t.y, qv[2] = t.z, qv[3] = t.w;
+                        }
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < 4; c++) qv[c] = v + c == xd ? 1.0f : 0.0f;
+                    }
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        const float df = __fsub_rn(__fmul_rn(lenience, val[4 * j + c]), qv[c]);
+                        val[4 * j + c] = df > 0.0f ? df : 0.0f;
+                    }
+                }
+            }
+            unsigned long long Z = 0ull, before = 0ull, wave_total = 0ull;
+            for (int pass = 0; pass < 2; pass++) {
+                unsigned long long mine = 0ull;
+#pragma unroll
+                for (int i = 0; i < RR_PER; i++) mine += fixed40_small(val[i]);     // weights are at most lenience <= 256
+                wave_total = wave_sum_u64(mine);
+                __syncthreads();
+                if (lane == 0) red64[wv] = wave_total;
+                __syncthreads();
+                Z = 0ull;
+                for (int i = 0; i < RR_THREADS / 64; i++) {
+                    if (i == wv) before = Z;
+                    Z += red64[i];
+                }
+                if (Z != 0ull || !residual) break;
+                residual = false;                            // all-zero residual: draw from the reviewer's row, rebuilt
+#pragma unroll
+                for (int j = 0; j < NG; j++) {
+                    const int v = vbase + 256 * j;
+                    float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                    if (v < V) t = *reinterpret_cast<const float4 *>(xr + v);
+                    val[4 * j] = exp_term(scaled_logit(t.x, inv_t), mx) * r, val[4 * j + 1] = exp_term(scaled_logit(t.y, inv_t), mx) * r;
+                    val[4 * j + 2] = exp_term(scaled_logit(t.z, inv_t), mx) * r, val[4 * j + 3] = exp_term(scaled_logit(t.w, inv_t), mx) * r;
+                }
+            }
+            if (Z != 0ull) {                                 // else not a distribution: the token stays -1
+                // T = floor(floor(u * 2^24) * Z / 2^24), 128-bit product
+                const unsigned long long u24 = fixed40(us) >> 16;
+                const unsigned long long hi = __umul64hi(u24, Z), lo = u24 * Z;
+                const unsigned long long T = (hi << 40) | (lo >> 24);
+                if (T >= before && T < before + wave_total) {          // exactly one wave owns T
+                    unsigned long long run = before;
+                    bool found = false;
+#pragma unroll
+                    for (int j = 0; j < NG; j++) {
+                        if (found) continue;                 // (the same in every lane)
+                        unsigned long long gj = 0ull;
+#pragma unroll
+                        for (int c = 0; c < 4; c++) gj += fixed40_small(val[4 * j + c]);
+                        const unsigned long long tot = wave_sum_u64(gj);
+                        if (T >= run + tot) {
+                            run += tot;
+                            continue;
+                        }
+                        found = true;                        // these 256 tokens: the lanes in order
+                        unsigned long long incl = gj;
+#pragma unroll
+                        for (int o = 1; o < 64; o <<= 1) {
+                            const unsigned long long up = __shfl_up(incl, o, 64);
+                            if (lane >= o) incl += up;
+                        }
+                        unsigned long long cum = run + incl - gj;
+                        if (T >= cum && T < cum + gj) {      // exactly one lane
+                            int t = 3;
+#pragma unroll
+                            for (int c = 2; c >= 0; c--) {   // the first position whose running sum passes T
+                                unsigned long long upto = cum;
+#pragma unroll
+                                for (int cc = 0; cc <= c; cc++) upto += fixed40_small(val[4 * j + cc]);
+                                if (upto > T) t = c;
+                            }
+                            s_tok = min(V - 1, vbase + 256 * j + t);
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            tok = s_tok;
+        }
+    }
+
+    // ---- the record of this row, written through to memory and acknowledged before the counter moves
+    unsigned long long *rec = recs + (size_t)b * (k + 1);
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(rec + row, ((unsigned long long)(ok ? 1u : 0u) << 32) | (unsigned)tok, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+        s_old = __hip_atomic_fetch_add(counters + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (s_old != (unsigned)k || threadIdx.x >= 64) return;
+    // ---- last to arrive: the first row whose draft failed decides (device-scope loads: the records come from
+    // workgroups on other compute dies)
+    int n = k;
+    unsigned long long rn = 0ull;
+    bool have = false;
+    for (int base = 0; base <= k; base += 64) {
+        const int i = base + (int)threadIdx.x;
+        unsigned long long ri = 1ull << 32;
+        if (i <= k) ri = __hip_atomic_load(rec + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long bad = __ballot(i < k && (ri >> 32) == 0ull);
+        if (bad) n = base + __ffsll((long long)bad) - 1;
+        if (n >= base && n < base + 64) {                    // the deciding row's record is in this batch of lanes
+            rn = __shfl(ri, n - base, 64);
+            have = true;
+        }
+        if (bad) break;
+    }
+    if (threadIdx.x == 0) {
+        if (!have) rn = __hip_atomic_load(rec + n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        n_accepted[b] = n;
+        next_token[b] = (int32_t)(unsigned)rn;
+        __hip_atomic_store(counters + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    }
+}
+
+// the kernel takes whole 16-byte groups of four tokens
+bool csd_review_rows_fits(const float *logits, const float *probs, const float *q, int32_t V) {
+    return V % 4 == 0 && V <= RR_THREADS * RR_PER && (uintptr_t)logits % 16 == 0 && (uintptr_t)probs % 16 == 0 &&
+           (uintptr_t)q % 16 == 0;
+}
+
+int32_t csd_review_rows_enqueue(const float *logits, float *probs, unsigned long long *recs, unsigned *counters,
+                                float temperature, const float *q, const uint8_t *q_onehot, const int32_t *draft,
+                                int32_t draft_stride, const float *u_acc, const float *u_samp, int32_t B, int32_t k, int32_t V,
+                                float lenience, int32_t mode, int32_t *n_accepted, int32_t *next_token, hipStream_t st) {
+    if (B <= 0) return CSD_OK;
+    if (!csd_review_rows_fits(logits, probs, q, V)) return CSD_ESHAPE;
+    const int32_t raw = mode == CSD_MODE_GREEDY && !(lenience > 1.0f);
+    hipLaunchKernelGGL(k_review_rows, dim3(k + 1, B), dim3(RR_THREADS), 0, st, logits, probs, recs, counters,
+                       1.0f / (temperature > 0.f ? temperature : 1.0f), q, q_onehot, draft, draft_stride, u_acc, u_samp, k, V,
+                       lenience, mode, raw, n_accepted, next_token);
     CSD_LAUNCH_CHECK();
     return CSD_OK;
 }

@@ -48,16 +48,22 @@ size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out) {
         for (int i = 0; i < 2; i++) ssq[i] = take(sizeof(float) * (size_t)(c.d_model / 16) * 16);
         cnt = take(sizeof(unsigned) * (size_t)c.max_batch * c.n_heads);
     }
+    char *tail_rec = take(sizeof(unsigned long long) * (size_t)mod->m_max);
+    char *tail_cnt = take(sizeof(unsigned) * (size_t)c.max_batch);
     if (out)
         *out = ScratchPtrs{(float *)h, act, qbuf, (float *)part, (float *)probs, (float2 *)rope, (float *)attn_part,
-                           {x[0], x[1], x[2], x[3]}, {(float *)ssq[0], (float *)ssq[1]}, (unsigned *)cnt};
+                           {x[0], x[1], x[2], x[3]}, {(float *)ssq[0], (float *)ssq[1]}, (unsigned *)cnt,
+                           (unsigned long long *)tail_rec, (unsigned *)tail_cnt};
     return off;
 }
 
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp) {
     const ScratchPtrs old{mod->h, mod->act, mod->qbuf, mod->part, mod->probs, mod->rope, mod->attn_part,
-                          {mod->x[0], mod->x[1], mod->x[2], mod->x[3]}, {mod->ssq[0], mod->ssq[1]}, mod->attn_cnt};
+                          {mod->x[0], mod->x[1], mod->x[2], mod->x[3]}, {mod->ssq[0], mod->ssq[1]}, mod->attn_cnt,
+                          mod->tail_rec, mod->tail_cnt};
     mod->attn_cnt = sp.attn_cnt;
+    mod->tail_rec = sp.tail_rec;
+    mod->tail_cnt = sp.tail_cnt;
     for (int i = 0; i < 4; i++) mod->x[i] = sp.x[i];
     for (int i = 0; i < 2; i++) mod->ssq[i] = sp.ssq[i];
     mod->h = sp.h;
@@ -114,6 +120,13 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->mfma_attn = mod->mfma && (c.head_dim == 64 || c.head_dim == 128) && !env_is("CSD_ATTN", "generic");
     const int keys_pad = mod->seq_pad > mod->enc_pad ? mod->seq_pad : mod->enc_pad;
     if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + keys_pad) > 64 * 1024) return CSD_ESHAPE;
+    {
+        // the GEMM kernels address a matrix through one buffer descriptor with 32-bit offsets
+        const size_t esz = c.dtype == CSD_DTYPE_BF16 ? 2 : 4;
+        const size_t mats[5] = {(size_t)d * 3 * hd, (size_t)hd * d, (size_t)d * 2 * F, (size_t)F * d, (size_t)d * V};
+        for (size_t n : mats)
+            if (n * esz >= ((size_t)1 << 31)) return CSD_ESHAPE;
+    }
     int32_t rc;
     if ((rc = csd_pack_weights(mod, weights, st)) != CSD_OK) return rc;
     if (mod->mfma && (rc = csd_gemm_setup()) != CSD_OK) return rc;
@@ -148,6 +161,8 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
         hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, st, mod->attn_cnt, 0u, c.max_batch * c.n_heads);
         CSD_LAUNCH_CHECK();
     }
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, st, mod->tail_cnt, 0u, c.max_batch);
+    CSD_LAUNCH_CHECK();
     char *static_base;
     if ((rc = static_scratch_base(&static_base)) != CSD_OK) return rc;   // looked up once per device, here
     CSD_HIP(hipMalloc(&p, sizeof(int32_t) * (size_t)mod->m_max));
@@ -237,6 +252,13 @@ extern "C" int32_t csd_verify_accept(csd_model *mod, void *kv, const int32_t *to
     // logits of this call live in the model's scratch when the caller does not ask for them
     float *lg = logits ? logits : mod->probs;   // softmax may then run in place: each thread rewrites what it read
     if ((rc = csd_forward_enqueue(mod, kv, tokens, cache_len, B, m, lg, st)) != CSD_OK) return rc;
+    if (csd_review_rows_fits(lg, probs, q, V)) {
+        // one launch: every row normalised (if anything needs probabilities), tested and its replacement drawn at
+        // once; probabilities are written only for a caller that asks for them
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        return csd_review_rows_enqueue(lg, probs, mod->tail_rec, mod->tail_cnt, temperature, q, q_onehot, tokens + 1, m, u_acc,
+                                       u_samp, B, m - 1, V, lenience, mode, n_accepted, next_token, st);
+    }
     const float *p = lg;
     if (need_probs || probs) {
         float *pr = probs ? probs : mod->probs;
@@ -272,6 +294,7 @@ extern "C" int32_t csd_verify_accept_static(csd_model *mod, void *kv, const int3
         hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, (hipStream_t)stream, sp.attn_cnt, 0u,
                            mod->cfg.max_batch * mod->cfg.n_heads);
     }
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, (hipStream_t)stream, sp.tail_cnt, 0u, mod->cfg.max_batch);
     rc = csd_verify_accept(mod, kv, tokens, cache_len, B, m, temperature, q, q_onehot, u_acc, u_samp, lenience, mode,
                            logits, probs, n_accepted, next_token, stream);
     csd_scratch_install(mod, own);

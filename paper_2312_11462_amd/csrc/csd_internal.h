@@ -234,6 +234,8 @@ struct csd_model {
     size_t x_plane[4] = {0, 0, 0, 0};    // elements between the hi and lo planes
     float *ssq[2] = {nullptr, nullptr};
     unsigned *attn_cnt = nullptr;        // arrival counters [max_batch][H] of the attention kernel: zero between launches
+    unsigned long long *tail_rec = nullptr;   // [m_max] per-row records of the review that takes every row at once
+    unsigned *tail_cnt = nullptr;        // [max_batch] arrival counters of that review: zero between launches
     // arch 1
     int enc_pad = 0;                 // encoder rows padded to 64
     float *rel_bias = nullptr;       // [32][H] fp32
@@ -261,6 +263,8 @@ struct ScratchPtrs {
     void *x[4];
     float *ssq[2];
     unsigned *attn_cnt;
+    unsigned long long *tail_rec;   // per block row: (passed, token) of the review that takes every row at once
+    unsigned *tail_cnt;      // per sequence: arrival counter of that review, zero between launches
 };
 size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out);
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp);   // returns the pieces in use before
@@ -280,6 +284,11 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
 // csd_accept.hip
 int32_t csd_softmax_enqueue(const float *logits, float *probs, int64_t rows, int32_t V, float temperature,
                             hipStream_t st);
+bool csd_review_rows_fits(const float *logits, const float *probs, const float *q, int32_t V);
+int32_t csd_review_rows_enqueue(const float *logits, float *probs, unsigned long long *recs, unsigned *counters,
+                                float temperature, const float *q, const uint8_t *q_onehot, const int32_t *draft,
+                                int32_t draft_stride, const float *u_acc, const float *u_samp, int32_t B, int32_t k, int32_t V,
+                                float lenience, int32_t mode, int32_t *n_accepted, int32_t *next_token, hipStream_t st);
 int32_t csd_accept_enqueue(const float *p, const float *q, const uint8_t *q_onehot, const int32_t *draft,
                            int32_t draft_stride, const float *u_acc, const float *u_samp, int32_t B, int32_t k,
                            int32_t V, float lenience, int32_t mode, int32_t *n_accepted, int32_t *next_token,

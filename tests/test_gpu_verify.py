@@ -193,21 +193,47 @@ def test_run_to_run_determinism():
     assert np.array_equal(outs[0], outs[1])
 
 
-def test_verify_accept_equals_the_two_calls():
+@pytest.mark.parametrize("shape", [BF, I.ModelShape("odd", 0, "fp32", 2, 48, 3, 16, 100, 301)], ids=["bf16_V1024", "fp32_V301"])
+def test_verify_accept_equals_the_two_calls(shape):
+    """csd_verify_accept (every row normalised, tested and its replacement drawn in one launch, probabilities
+    written only on request) decides exactly as csd_verify_block + csd_accept on the written probabilities, and as
+    the oracle's accept rule on those probabilities (Section 2, Section 3.1), for one-hot and dense draft
+    distributions, several lenience values and temperatures, in both modes; the probabilities it writes on request
+    are those of csd_verify_block bit for bit.  The second shape has a vocabulary that is not a multiple of 4."""
     import paper_2312_11462_amd as P
-    gm, _ = make_pair(BF, 13, 2, 128, 8, std=0.05)
+    from oracle import csd_oracle as O
+    BF = shape
+    gm, _ = make_pair(BF, 13, 2, 128, 8, std=0.05 if shape.dtype == "bf16" else 0.1)
     toks = I.token_ids(2 * 70, BF.vocab, 13, 1).reshape(2, 70)
     for pos in range(0, 64, 8):
         gm.verify_block(toks[:, pos:pos + 8].contiguous().cuda(), _dev([pos, pos]))
     block = toks[:, 64:70].contiguous().cuda()
     cl = _dev([64, 64])
-    u_acc = I.uniforms(10, 13, 2).reshape(2, 5).contiguous().cuda()
-    u_s = I.uniforms(2, 13, 3).cuda()
-    for mode in (0, 1):
-        lg, pr = gm.verify_block(block, cl, want_probs=True)
-        a = P.accept(pr if mode == 0 else lg, None, block[:, 1:].contiguous(), u_acc, u_s, mode=mode)
-        b = gm.verify_accept(block, cl, u_acc, u_s, mode=mode)
-        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    draft = block[:, 1:].contiguous()
+    n_checked = 0
+    for case, (mode, dense, lenience, temperature) in enumerate(
+            [(0, False, 1.0, 1.0), (1, False, 1.0, 1.0), (0, True, 1.0, 1.0), (0, True, 3.0, 0.7), (0, True, 1.0, 1.6),
+             (1, True, 2.0, 1.0), (0, True, 1.5, 1.0)]):
+        u_acc = I.uniforms(10, 13, 20 + case).reshape(2, 5).contiguous().cuda()
+        u_s = I.uniforms(2, 13, 40 + case).cuda()
+        lg, pr = gm.verify_block(block, cl, want_probs=True, temperature=temperature)
+        q = None
+        if dense:      # a draft distribution close to the reviewer's, so that acceptance really depends on u
+            noise = torch.from_numpy(np.random.default_rng(case).normal(0, 0.5, (2, 5, BF.vocab)).astype(np.float32)).cuda()
+            q = pr[:, :5] * torch.exp(noise)
+            q = (q / q.sum(-1, keepdim=True)).contiguous()
+        uses_probs = mode == 0 or lenience > 1.0
+        a = P.accept(pr if uses_probs else lg, q, draft, u_acc, u_s, lenience=lenience, mode=mode)
+        b = gm.verify_accept(block, cl, u_acc, u_s, q=q, temperature=temperature, lenience=lenience, mode=mode)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]), (case, a, b)
+        o = O.accept((pr if uses_probs else lg).cpu().numpy(), None if q is None else q.cpu().numpy(), draft.cpu().numpy(),
+                     u_acc.cpu().numpy(), u_s.cpu().numpy(), lenience, mode)
+        assert np.array_equal(o[0], b[0].cpu().numpy()) and np.array_equal(o[1], b[1].cpu().numpy()), (case, o, b)
+        pr2 = torch.empty_like(pr)
+        c = gm.verify_accept(block, cl, u_acc, u_s, q=q, temperature=temperature, lenience=lenience, mode=mode, probs=pr2)
+        assert torch.equal(c[0], b[0]) and torch.equal(c[1], b[1]) and torch.equal(pr2, pr), case
+        n_checked += int(b[0].sum())
+    assert n_checked > 10          # drafts were kept, so later rows and their statistics took part
 
 
 def test_argument_errors_enqueue_nothing():
