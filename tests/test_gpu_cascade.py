@@ -197,6 +197,7 @@ def _oracle_steps(olevels, otable, prompt, K, lenience, mode, n_steps, uniform_a
     ([[2, 6], [0, 6]], 1.0, 1),
     ([[2, 3], [0, 4]], 3.0, 1),
     ([[2, 2, 3], [0, 1, 3], [0, 0, 3]], 2.0, 2),
+    ([[4, 0], [0, 0]], 1.0, 1),     # plain speculative decoding: four one-row forwards of the draft model, then the review
 ])
 def test_resident_cascade_greedy_equals_the_oracle_driver_step_for_step(K, lenience, n_drafts):
     """Algorithm 1 as a chain of enqueues with device-resident control (no host synchronisation inside or between
