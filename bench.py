@@ -185,6 +185,18 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     gpu_ms_per_step = e0.elapsed_time(e1) / args.steps
+    # the same step timed one at a time (an event pair per step; each pair waits for the GPU to drain, so the
+    # launches of a step no longer hide behind the previous step): the median, reported beside the mean above
+    n_single = min(args.steps, 50)
+    singles = []
+    for _ in range(n_single):
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        step()
+        b_.record()
+        b_.synchronize()
+        singles.append(a.elapsed_time(b_))
+    median_single_ms = sorted(singles)[len(singles) // 2] if singles else None
     emitted = float((n_acc + 1).sum().item())
 
     # ---- per-kernel timing with HIP events on the launch stream (separate loop: the events perturb the step)
@@ -411,6 +423,7 @@ def main():
         "value": round(B * k / (wall / args.steps), 2), "unit": "verified tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "gpu_ms_per_step": round(gpu_ms_per_step, 4),
+        "median_ms_single_step": None if median_single_ms is None else round(median_single_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {shape.n_layers} layers, d_model {shape.d_model}, batch {B}, "

@@ -400,10 +400,12 @@ static int32_t verify_block_t5(csdo_model *mod, double *kv, const int32_t *token
  * cache_len[b] + i, attends cache rows 0 .. cache_len[b] + i, and its K/V are written to
  * the cache at that position.  logits: [B][m][V] fp64; probs: optional softmax(logits / T).
  */
-int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, const int32_t *cache_len,
-                          int32_t B, int32_t m, double temperature, double *logits, double *probs) {
+static int32_t verify_rows(csdo_model *mod, double *kv, const int32_t *tokens, const int32_t *parent,
+                           const int32_t *cache_len, int32_t B, int32_t m, double temperature, double *logits,
+                           double *probs) {
     const csdo_cfg *c = &mod->c;
     if (B < 1 || B > c->max_batch || m < 1) return -2;
+    if (parent && c->arch != 0) return -2;
     const int d = c->d_model, H = c->n_heads, dh = c->head_dim, F = c->d_ffn, V = c->vocab, L = c->n_layers;
     const int hd = H * dh, dt = c->dtype;
     for (int b = 0; b < B; b++) {
@@ -422,9 +424,21 @@ int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, co
     double *t1 = (double *)malloc(sizeof(double) * (size_t)m * (F > d ? F : d));
     double *t2 = (double *)malloc(sizeof(double) * (size_t)m * F);
     double *sc = (double *)malloc(sizeof(double) * (size_t)c->max_seq);
+    int *depth = (int *)malloc(sizeof(int) * (size_t)m);
+    unsigned char *sees = (unsigned char *)malloc((size_t)m * m);   /* sees[i*m + j]: block row j is row i or above it */
     const void **w = mod->w;
     for (int b = 0; b < B; b++) {
         const int t = cache_len[b];
+        /* a plain block is the chain 0 <- 1 <- 2 ...; a tree block names every row's parent (row 0 is the root) */
+        for (int i = 0; i < m; i++) {
+            const int par = parent ? parent[b * m + i] : i - 1;
+            if ((i == 0 && par != -1) || (i > 0 && (par < 0 || par >= i))) {
+                free(h); free(a); free(q); free(kk); free(vv); free(o); free(t1); free(t2); free(sc); free(depth); free(sees);
+                return -2;
+            }
+            depth[i] = i == 0 ? 0 : depth[par] + 1;
+            for (int j = 0; j < m; j++) sees[i * m + j] = (j == i) || (i > 0 && j <= par && sees[par * m + j]);
+        }
         for (int i = 0; i < m; i++)
             for (int x = 0; x < d; x++)
                 h[(size_t)i * d + x] = wval(w[W_EMBED], dt, (size_t)tokens[b * m + i] * d + x);
@@ -438,21 +452,24 @@ int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, co
             matmul(a, m, d, lw[L_WV], dt, hd, vv);
             for (int i = 0; i < m; i++) {
                 for (int hh = 0; hh < H; hh++) {
-                    csdo_rope(q + (size_t)i * hd + hh * dh, dh, t + i, c->rope_theta);
-                    csdo_rope(kk + (size_t)i * hd + hh * dh, dh, t + i, c->rope_theta);
+                    /* the position of a row is how far it is from the root, not where it is stored */
+                    csdo_rope(q + (size_t)i * hd + hh * dh, dh, t + depth[i], c->rope_theta);
+                    csdo_rope(kk + (size_t)i * hd + hh * dh, dh, t + depth[i], c->rope_theta);
                 }
                 for (int x = 0; x < hd; x++) {      /* the cache holds the configuration's storage type */
                     kv_row(mod, kv, 0, l, b, t + i)[x] = to_cache(mod, kk[(size_t)i * hd + x]);
                     kv_row(mod, kv, 1, l, b, t + i)[x] = to_cache(mod, vv[(size_t)i * hd + x]);
                 }
             }
-            /* causal attention: row i sees cache rows 0 .. t+i */
+            /* causal attention: row i sees the cached rows 0 .. t-1 and, of the block (stored at t .. t+i), itself
+             * and the rows above it -- in a plain block that is every row 0 .. t+i */
             for (int i = 0; i < m; i++)
                 for (int hh = 0; hh < H; hh++) {
                     const double *qi = q + (size_t)i * hd + hh * dh;
                     int nk = t + i + 1;
                     double mx = -INFINITY;
                     for (int j = 0; j < nk; j++) {
+                        if (j >= t && !sees[i * m + (j - t)]) continue;
                         const double *kj = kv_row(mod, kv, 0, l, b, j) + hh * dh;
                         double s = 0.0;
                         for (int x = 0; x < dh; x++) s += qi[x] * kj[x];
@@ -460,10 +477,15 @@ int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, co
                         if (sc[j] > mx) mx = sc[j];
                     }
                     double z = 0.0;
-                    for (int j = 0; j < nk; j++) { sc[j] = exp(sc[j] - mx); z += sc[j]; }
+                    for (int j = 0; j < nk; j++) {
+                        if (j >= t && !sees[i * m + (j - t)]) { sc[j] = 0.0; continue; }
+                        sc[j] = exp(sc[j] - mx);
+                        z += sc[j];
+                    }
                     double *oi = o + (size_t)i * hd + hh * dh;
                     for (int x = 0; x < dh; x++) oi[x] = 0.0;
                     for (int j = 0; j < nk; j++) {
+                        if (j >= t && !sees[i * m + (j - t)]) continue;
                         const double *vj = kv_row(mod, kv, 1, l, b, j) + hh * dh;
                         double p = sc[j] / z;
                         for (int x = 0; x < dh; x++) oi[x] += p * vj[x];
@@ -491,7 +513,45 @@ int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, co
                 csdo_softmax(lg + (size_t)i * V, V, 1.0 / temperature, probs + ((size_t)b * m + i) * V);
         }
     }
-    free(h); free(a); free(q); free(kk); free(vv); free(o); free(t1); free(t2); free(sc);
+    free(h); free(a); free(q); free(kk); free(vv); free(o); free(t1); free(t2); free(sc); free(depth); free(sees);
+    return 0;
+}
+
+int32_t csdo_verify_block(csdo_model *mod, double *kv, const int32_t *tokens, const int32_t *cache_len,
+                          int32_t B, int32_t m, double temperature, double *logits, double *probs) {
+    return verify_rows(mod, kv, tokens, NULL, cache_len, B, m, temperature, logits, probs);
+}
+
+/*
+ * Review forward over a tree of drafts (Section 5.1 combines the cascade with tree attention; Appendix B gives
+ * the lead node eight children).  Row 0 is the last kept token; parent[b][i] < i names the row that row i
+ * continues (parent[b][0] = -1).  A row's position is cache_len + its distance from row 0, it attends the cached
+ * rows, the rows above it in the tree and itself, and its K/V are stored at cache row cache_len + i: every
+ * root-to-node path sees exactly what a plain block holding that path would see.  arch 0 only.
+ */
+int32_t csdo_verify_tree(csdo_model *mod, double *kv, const int32_t *tokens, const int32_t *parent,
+                         const int32_t *cache_len, int32_t B, int32_t m, double temperature, double *logits,
+                         double *probs) {
+    if (!parent) return -2;
+    return verify_rows(mod, kv, tokens, parent, cache_len, B, m, temperature, logits, probs);
+}
+
+/*
+ * After a tree review kept the rows path[0 .. n) (a chain below row 0): move their K/V to cache rows
+ * cache_len + 1 .. cache_len + n, where a plain block would have put them, so that the cache again holds one
+ * sequence.  path is increasing and path[j] >= j + 1, so moving in order overwrites nothing still needed.
+ */
+int32_t csdo_tree_commit(const csdo_model *mod, double *kv, int32_t b, int32_t cache_len, const int32_t *path, int32_t n) {
+    const csdo_cfg *c = &mod->c;
+    const int hd = c->n_heads * c->head_dim;
+    if (b < 0 || b >= c->max_batch || cache_len < 0 || n < 0) return -2;
+    for (int j = 0; j < n; j++)
+        if (path[j] < j + 1 || (j > 0 && path[j] <= path[j - 1]) || cache_len + path[j] >= c->max_seq) return -2;
+    for (int l = 0; l < c->n_layers; l++)
+        for (int j = 0; j < n; j++)
+            for (int which = 0; which < 2; which++)
+                memmove(kv_row(mod, kv, which, l, b, cache_len + 1 + j), kv_row(mod, kv, which, l, b, cache_len + path[j]),
+                        sizeof(double) * (size_t)hd);
     return 0;
 }
 
@@ -681,6 +741,42 @@ int32_t csdo_accept(const float *p, const float *q, const uint8_t *q_onehot, con
         next_token[b] = tok;
     }
     free(r);
+    return 0;
+}
+
+/*
+ * Review of a tree of deterministic candidates (the children of a node are tokens the draft side proposes for the
+ * position after it; Section 5.1, Appendix B).  Walk down from row 0: take the reviewer's own token for the position
+ * after the current row -- drawn from its distribution with the walk's next uniform (the same fixed-point inverse
+ * CDF as the review of a chain), or its arg-max in greedy mode -- and if a child of the current row carries that
+ * token, keep the child and go on from it; otherwise that token is what the review emits and the walk ends.
+ * Every emitted token is the reviewer's own draw given what was kept before it, so the output law is the
+ * reviewer's whatever the tree holds.  p [B][m][V] (probabilities; logits will do in greedy mode), tokens,
+ * parent [B][m], u [B][m] (the j-th draw of sequence b uses u[b][j]).  path [B][m] receives the kept rows.
+ * Among children with the same token the lowest row wins.
+ */
+int32_t csdo_tree_accept(const float *p, const int32_t *tokens, const int32_t *parent, const float *u, int32_t B,
+                         int32_t m, int32_t V, int32_t mode, int32_t *n_accepted, int32_t *path, int32_t *next_token) {
+    if (B < 0 || m < 1 || V < 1 || (mode != 0 && mode != 1)) return -2;
+    for (int b = 0; b < B; b++) {
+        const int32_t *par = parent + (size_t)b * m, *tok = tokens + (size_t)b * m;
+        if (par[0] != -1) return -2;
+        for (int i = 1; i < m; i++)
+            if (par[i] < 0 || par[i] >= i) return -2;
+        int node = 0, n = 0;
+        for (;;) {
+            const float *row = p + ((size_t)b * m + node) * V;
+            const int32_t t = mode == 1 ? argmax_first(row, V) : sample_fixed_point(row, V, u[(size_t)b * m + n]);
+            if (t < 0) return -3;                      /* the row sums to zero: not a distribution */
+            int child = -1;
+            for (int j = node + 1; j < m && child < 0; j++)
+                if (par[j] == node && tok[j] == t) child = j;
+            if (child < 0) { next_token[b] = t; break; }
+            path[(size_t)b * m + n++] = child;
+            node = child;
+        }
+        n_accepted[b] = n;
+    }
     return 0;
 }
 

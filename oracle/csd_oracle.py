@@ -128,7 +128,17 @@ class Model:
         x = np.ascontiguousarray(enc_out, dtype=np.float32)
         _chk(lib().csdo_cross_kv_init(self._h, _p(self.kv), _p(x), x.shape[0]), "cross_kv_init")
 
-    def verify_block(self, tokens, cache_len, temperature=1.0, want_probs=False, trace=False):
+    def verify_tree(self, tokens, parent, cache_len, temperature=1.0, want_probs=False):
+        """Tree block (Section 5.1, Appendix B): tokens, parent [B][m] int32 (parent[b][0] = -1, parent[b][i] < i)
+        -> logits [B][m][V] fp64 (and probs); row i is stored at cache row cache_len + i."""
+        return self.verify_block(tokens, cache_len, temperature, want_probs, parent=parent)
+
+    def tree_commit(self, b, cache_len, path):
+        """Move the K/V of the kept rows path (increasing, below row 0) to cache rows cache_len + 1 ..."""
+        path = np.ascontiguousarray(path, dtype=np.int32)
+        _chk(lib().csdo_tree_commit(self._h, _p(self.kv), b, int(cache_len), _p(path), len(path)), "tree_commit")
+
+    def verify_block(self, tokens, cache_len, temperature=1.0, want_probs=False, trace=False, parent=None):
         """tokens [B][m] int32, cache_len [B] -> logits [B][m][V] fp64 (and probs)."""
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)
         cache_len = np.ascontiguousarray(cache_len, dtype=np.int32)
@@ -140,8 +150,13 @@ class Model:
         if trace:
             tr = np.zeros((self.shape.n_layers + 1, m, self.shape.d_model), dtype=np.float64)
             lib().csdo_set_trace(self._h, _p(tr))
-        rc = lib().csdo_verify_block(self._h, _p(self.kv), _p(tokens), _p(cache_len), B, m,
-                                     C.c_double(temperature), _p(logits), _p(probs))
+        if parent is not None:
+            parent = np.ascontiguousarray(parent, dtype=np.int32).reshape(B, m)
+            rc = lib().csdo_verify_tree(self._h, _p(self.kv), _p(tokens), _p(parent), _p(cache_len), B, m,
+                                        C.c_double(temperature), _p(logits), _p(probs))
+        else:
+            rc = lib().csdo_verify_block(self._h, _p(self.kv), _p(tokens), _p(cache_len), B, m,
+                                         C.c_double(temperature), _p(logits), _p(probs))
         if trace:
             lib().csdo_set_trace(self._h, None)
         _chk(rc, "verify_block")
@@ -218,6 +233,21 @@ def accept(p, q, draft, u_acc, u_samp, lenience=1.0, mode=0, q_onehot=None):
     _chk(lib().csdo_accept(_p(p), _p(q), _p(oh), _p(draft), _p(u_acc), _p(u_samp), B, k, V,
                            C.c_float(lenience), mode, _p(n_acc), _p(nxt)), "accept")
     return n_acc, nxt
+
+
+def tree_accept(p, tokens, parent, u, mode=0):
+    """p [B][m][V] fp32, tokens, parent [B][m], u [B][m] -> (n_accepted [B], path [B][m], next_token [B])."""
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    B, m, V = p.shape
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32).reshape(B, m)
+    parent = np.ascontiguousarray(parent, dtype=np.int32).reshape(B, m)
+    u = np.ascontiguousarray(u, dtype=np.float32).reshape(B, m)
+    n_acc = np.empty(B, dtype=np.int32)
+    path = np.full((B, m), -1, dtype=np.int32)
+    nxt = np.empty(B, dtype=np.int32)
+    _chk(lib().csdo_tree_accept(_p(p), _p(tokens), _p(parent), _p(u), B, m, V, mode, _p(n_acc), _p(path), _p(nxt)),
+         "tree_accept")
+    return n_acc, path, nxt
 
 
 def rel_bucket(n):
