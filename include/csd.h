@@ -275,6 +275,43 @@ int32_t csd_bigram_draft_append(int32_t *ctx, int32_t ctx_stride, int32_t *ctx_l
 int32_t csd_cascade_gate(const int32_t *ctx_len, const int32_t *loop_start, int32_t need, const int32_t *parent_gate,
                          int32_t B, int32_t *gate, void *stream);
 
+/*
+ * Review forward over a tree of drafts (Section 5.1: the cascade combined with tree attention; Appendix B: the lead
+ * node has eight children, the other nodes none).  tokens[B][m], parent[B][m] (device): row 0 is the last kept
+ * token (parent -1, not read); parent[b][i] in [0, i) names the row that row i continues (a value outside that range
+ * is read as 0).  A row's position is cache_len[b] + its distance from row 0; it attends the cached rows
+ * [0, cache_len[b]), the rows above it in the tree and itself; its K/V are stored at cache row cache_len[b] + i.
+ * So every root-to-node path is scored exactly as a plain block holding that path would be.  logits[B][m][V]
+ * (and probs, as csd_verify_block).  m <= 64 and <= max_block; arch 0 only (CSD_EUNSUPPORTED otherwise).
+ */
+int32_t csd_verify_tree(csd_model *model, void *kv, const int32_t *tokens, const int32_t *parent,
+                        const int32_t *cache_len, int32_t B, int32_t m, float temperature, float *logits, float *probs,
+                        void *stream);
+
+/*
+ * Review of a tree of deterministic candidates (same passages; the accept rule of Section 2 for drafts whose
+ * distribution is one-hot, taken one level of the tree at a time).  Walk down from row 0: take the reviewer's own
+ * token for the position after the current row (mode CSD_MODE_SAMPLE: the fixed-point inverse-CDF draw of
+ * csd_accept from row `current` of p with the walk's j-th uniform u[b][j]; CSD_MODE_GREEDY: the arg-max, ties to the
+ * smallest id, and p may hold logits); if a child of the current row carries that token (the lowest such row), keep
+ * it and continue from it, else the token is next_token[b] and the walk ends.  Every emitted token is the
+ * reviewer's own, so the output law is the reviewer's whatever the tree holds.  p[B][m][V], tokens, parent as for
+ * csd_verify_tree, u[B][m] (may be NULL in greedy mode).  Outputs: n_accepted[B], path[B][m] (the kept rows, the
+ * first n_accepted entries), next_token[B] (-1 if a row of p is not a distribution).
+ */
+int32_t csd_tree_accept(const float *p, const int32_t *tokens, const int32_t *parent, const float *u, int32_t B,
+                        int32_t m, int32_t V, int32_t mode, int32_t *n_accepted, int32_t *path, int32_t *next_token,
+                        void *stream);
+
+/*
+ * After csd_verify_tree + csd_tree_accept: move the K/V of the kept rows path[b][0 .. n_accepted[b]) to cache rows
+ * cache_len[b] + 1 .., where a plain block would have stored them; the caller then commits
+ * cache_len[b] += 1 + n_accepted[b] as after a plain review.  path must be increasing with path[b][j] >= j + 1 (what
+ * csd_tree_accept writes); an entry that is not cuts the move there.  All layers, one launch.
+ */
+int32_t csd_tree_commit(const csd_model *model, void *kv, const int32_t *cache_len, const int32_t *path,
+                        const int32_t *n_accepted, int32_t B, int32_t m, void *stream);
+
 /* Test hook: when trace != NULL the next verify calls also copy the residual stream of all
  * B*m rows after the embedding and after every layer to trace[(n_layers+1)][B*m][d] (fp32). */
 int32_t csd_debug_set_trace(csd_model *model, float *trace);

@@ -5,6 +5,6 @@ thin ctypes binding over it (argument marshalling only) plus the build step.  Py
 for device memory and streams, nothing else.  There is no CPU fallback: without the built
 library, or without a GPU, the calls raise.
 """
-from .binding import (CsdError, Model, accept, bigram_draft, bigram_draft_append, bigram_fit, cascade_gate, maxgram_draft, debug_copy, debug_mfma, debug_read, lib,  # noqa: F401
+from .binding import (CsdError, Model, accept, bigram_draft, bigram_draft_append, bigram_fit, cascade_gate, maxgram_draft, tree_accept, debug_copy, debug_mfma, debug_read, lib,  # noqa: F401
                       library_path,
                       EXPORTS)

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
            "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_maxgram_draft", "csd_verify_block",
-           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_review_ctx", "csd_bigram_draft_append", "csd_cascade_gate", "csd_debug_set_trace", "csd_debug_path", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
+           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_review_ctx", "csd_bigram_draft_append", "csd_cascade_gate", "csd_verify_tree", "csd_tree_accept", "csd_tree_commit", "csd_debug_set_trace", "csd_debug_path", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
            "csd_prof_enable", "csd_prof_read"]
 
 _STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}
@@ -168,6 +168,25 @@ class Model:
                 _ptr(next_token), _stream()), "csd_verify_accept_static" if static else "csd_verify_accept")
         return n_accepted, next_token
 
+    def verify_tree(self, tokens, parent, cache_len, temperature=1.0, want_probs=False, logits=None, probs=None):
+        """csd_verify_tree: tokens, parent [B][m] int32 (device) -> logits [B][m][V] (and probs)."""
+        B, m = tokens.shape
+        V = self.shape.vocab
+        if logits is None:
+            logits = torch.empty((B, m, V), dtype=torch.float32, device="cuda")
+        if want_probs and probs is None:
+            probs = torch.empty((B, m, V), dtype=torch.float32, device="cuda")
+        _chk(lib().csd_verify_tree(self._h, _ptr(self.kv), _ptr(tokens, torch.int32), _ptr(parent, torch.int32),
+                                   _ptr(cache_len, torch.int32), B, m, C.c_float(temperature), _ptr(logits), _ptr(probs),
+                                   _stream()), "csd_verify_tree")
+        return (logits, probs) if want_probs else logits
+
+    def tree_commit(self, cache_len, path, n_accepted):
+        """csd_tree_commit: the kept rows' K/V move to where a plain block would have stored them."""
+        B, m = path.shape
+        _chk(lib().csd_tree_commit(self._h, _ptr(self.kv), _ptr(cache_len, torch.int32), _ptr(path, torch.int32),
+                                   _ptr(n_accepted, torch.int32), B, m, _stream()), "csd_tree_commit")
+
     def review_ctx(self, ctx, ctx_len, cache_len, prefix_len, m_max, status, q_tab=None, q_onehot_tab=None, q_base=None,
                    u_acc_tab=None, u_samp_tab=None, out_q_tab=None, out_onehot_tab=None, out_base=None, lower=(),
                    n_accepted=None, next_token=None, ext_rows=None, temperature=1.0, lenience=1.0, mode=0):
@@ -258,6 +277,17 @@ def maxgram_draft(haystack, haystack_len, needle, needle_len, next_table, k, max
                                  next_table.shape[0], k, max_match, _ptr(out), _ptr(mlen), _ptr(ncp), _stream()),
          "csd_maxgram_draft")
     return out, mlen, ncp
+
+
+def tree_accept(p, tokens, parent, u=None, mode=0):
+    """csd_tree_accept: p [B][m][V] -> (n_accepted [B], path [B][m], next_token [B])."""
+    B, m, V = p.shape
+    n_acc = torch.empty(B, dtype=torch.int32, device="cuda")
+    path = torch.full((B, m), -1, dtype=torch.int32, device="cuda")
+    nxt = torch.empty(B, dtype=torch.int32, device="cuda")
+    _chk(lib().csd_tree_accept(_ptr(p, torch.float32), _ptr(tokens, torch.int32), _ptr(parent, torch.int32), _ptr(u), B, m, V,
+                               mode, _ptr(n_acc), _ptr(path), _ptr(nxt), _stream()), "csd_tree_accept")
+    return n_acc, path, nxt
 
 
 def bigram_draft_append(ctx, ctx_len, next_table, k, max_match=0, gate=None, q_onehot_tab=None, q_base=None):

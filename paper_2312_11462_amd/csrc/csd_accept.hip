@@ -622,6 +622,59 @@ extern "C" int32_t csd_accept(const float *p, const float *q, const uint8_t *q_o
                               next_token, (hipStream_t)stream);
 }
 
+// ------------------------------------------------------------------------------------- review of a tree
+//
+// Walk down a tree of deterministic candidates (Section 5.1 combines the cascade with tree attention; Appendix B:
+// the lead node has eight children): at the current row take the reviewer's own token for the next position (a
+// draw from the row with the walk's next uniform, or its arg-max), and if a child of the row carries that token
+// keep the child and go on from it; otherwise the token is what the review emits.  One workgroup per sequence; a
+// walk step is the draw of a plain review with no drafts.  Rows only have children below them, so the walk ends.
+__global__ __launch_bounds__(ACC_THREADS) void k_tree_accept(
+    const float *__restrict__ p, const int32_t *__restrict__ tokens, const int32_t *__restrict__ parent,
+    const float *__restrict__ u, int32_t m, int32_t V, int32_t mode, int32_t *__restrict__ n_accepted,
+    int32_t *__restrict__ path, int32_t *__restrict__ next_token) {
+    __shared__ AcceptShared S;
+    __shared__ int s_child;
+    const int b = blockIdx.x;
+    const int32_t *par = parent + (size_t)b * m, *tk = tokens + (size_t)b * m;
+    int node = 0, n = 0, tok = -1;
+    for (int step = 0; step < m; step++) {
+        int unused;
+        accept_core(S, p + ((size_t)b * m + node) * V, nullptr, nullptr, nullptr, nullptr,
+                    mode == CSD_MODE_SAMPLE ? u[(size_t)b * m + n] : 0.f, 0, V, 1.0f, mode, unused, tok);
+        if (threadIdx.x == 0) s_child = 0x7FFFFFFF;
+        __syncthreads();
+        if (tok >= 0)
+            for (int j = node + 1 + (int)threadIdx.x; j < m; j += blockDim.x)
+                if (par[j] == node && tk[j] == tok) atomicMin(&s_child, j);    // equal tokens: the lowest row
+        __syncthreads();
+        const int child = s_child;
+        __syncthreads();
+        if (child == 0x7FFFFFFF) break;
+        if (threadIdx.x == 0) path[(size_t)b * m + n] = child;
+        n++;
+        node = child;
+    }
+    if (threadIdx.x == 0) {
+        n_accepted[b] = n;
+        next_token[b] = tok;
+    }
+}
+
+extern "C" int32_t csd_tree_accept(const float *p, const int32_t *tokens, const int32_t *parent, const float *u, int32_t B,
+                                   int32_t m, int32_t V, int32_t mode, int32_t *n_accepted, int32_t *path, int32_t *next_token,
+                                   void *stream) {
+    if (!p || !tokens || !parent || !n_accepted || !path || !next_token) return CSD_ENULL;
+    if (mode != CSD_MODE_SAMPLE && mode != CSD_MODE_GREEDY) return CSD_EINVAL;
+    if (mode == CSD_MODE_SAMPLE && !u) return CSD_ENULL;
+    if (B < 0 || m < 1 || V < 1) return CSD_EINVAL;
+    if (B == 0) return CSD_OK;
+    hipLaunchKernelGGL(k_tree_accept, dim3(B), dim3(ACC_THREADS), 0, (hipStream_t)stream, p, tokens, parent, u, m, V, mode,
+                       n_accepted, path, next_token);
+    CSD_LAUNCH_CHECK();
+    return CSD_OK;
+}
+
 // ------------------------------------------------------------------- device-resident control of the cascade
 //
 // A review that finds its block in the shared token buffer (Algorithm 1; Sections 3.2, 3.4): the reviewer scores the

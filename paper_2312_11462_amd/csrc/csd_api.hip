@@ -50,20 +50,25 @@ size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out) {
     }
     char *tail_rec = take(sizeof(unsigned long long) * (size_t)mod->m_max);
     char *tail_cnt = take(sizeof(unsigned) * (size_t)c.max_batch);
+    char *tree_depth = take(sizeof(int32_t) * (size_t)mod->m_max);
+    char *tree_anc = take(sizeof(unsigned long long) * (size_t)mod->m_max);
     if (out)
         *out = ScratchPtrs{(float *)h, act, qbuf, (float *)part, (float *)probs, (float2 *)rope, (float *)attn_part,
                            {x[0], x[1], x[2], x[3]}, {(float *)ssq[0], (float *)ssq[1]}, (unsigned *)cnt,
-                           (unsigned long long *)tail_rec, (unsigned *)tail_cnt};
+                           (unsigned long long *)tail_rec, (unsigned *)tail_cnt, (int32_t *)tree_depth,
+                           (unsigned long long *)tree_anc};
     return off;
 }
 
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp) {
     const ScratchPtrs old{mod->h, mod->act, mod->qbuf, mod->part, mod->probs, mod->rope, mod->attn_part,
                           {mod->x[0], mod->x[1], mod->x[2], mod->x[3]}, {mod->ssq[0], mod->ssq[1]}, mod->attn_cnt,
-                          mod->tail_rec, mod->tail_cnt};
+                          mod->tail_rec, mod->tail_cnt, mod->tree_depth, mod->tree_anc};
     mod->attn_cnt = sp.attn_cnt;
     mod->tail_rec = sp.tail_rec;
     mod->tail_cnt = sp.tail_cnt;
+    mod->tree_depth = sp.tree_depth;
+    mod->tree_anc = sp.tree_anc;
     for (int i = 0; i < 4; i++) mod->x[i] = sp.x[i];
     for (int i = 0; i < 2; i++) mod->ssq[i] = sp.ssq[i];
     mod->h = sp.h;
@@ -231,6 +236,93 @@ extern "C" int32_t csd_verify_block(csd_model *mod, void *kv, const int32_t *tok
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         if ((rc = csd_softmax_enqueue(logits, probs, (int64_t)B * m, mod->cfg.vocab, temperature, st)) != CSD_OK) return rc;
     }
+    return CSD_OK;
+}
+
+// Depth and ancestor mask of every row of a tree block.  parent[b][i] < i names the row that row i continues
+// (row 0 has none); a value outside [0, i) is read as 0, so the walk up always ends at row 0.
+__global__ void k_tree_prepare(const int32_t *__restrict__ parent, int m, int32_t *__restrict__ depth,
+                               unsigned long long *__restrict__ anc) {
+    const int b = blockIdx.x, i = threadIdx.x;
+    if (i >= m) return;
+    const int32_t *par = parent + (size_t)b * m;
+    unsigned long long mask = 1ull << i;
+    int d = 0, r = i;
+    while (r > 0) {
+        int pr = par[r];
+        if (pr < 0 || pr >= r) pr = 0;
+        mask |= 1ull << pr;
+        d++;
+        r = pr;
+    }
+    depth[b * m + i] = d;
+    anc[b * m + i] = mask;
+}
+
+// After a tree review: the K/V of the kept rows path[b][0 .. n) move to cache rows cache_len + 1 .., where a plain
+// block would have stored them.  A thread owns one feature of one (layer, sequence, head) and moves it row by row, in
+// order (path is increasing and path[j] >= j + 1, so nothing still needed is overwritten); a path that is not of
+// that form is cut at the first offending entry.
+template <typename TC>
+__global__ void k_tree_commit(TC *__restrict__ kv, KvGeom geo, const int32_t *__restrict__ cache_len,
+                              const int32_t *__restrict__ path, const int32_t *__restrict__ n_accepted, int m) {
+    const int l = blockIdx.x, b = blockIdx.y, hh = blockIdx.z, x = threadIdx.x;
+    const int t = cache_len[b];
+    int n = n_accepted[b];
+    n = n < 0 ? 0 : (n > m - 1 ? m - 1 : n);
+    TC *kc = kv + kv_k_off(geo, l, b, hh);
+    TC *vc = kv + kv_v_off(geo, l, b, hh);
+    int prev = 0;
+    for (int j = 0; j < n; j++) {
+        const int src = path[(size_t)b * m + j];
+        if (src <= prev || src < j + 1 || src >= m || t < 0 || t + src >= geo.seq_pad) break;
+        prev = src;
+        if (src == j + 1) continue;                          // already where it belongs
+        const int from = t + src, to = t + 1 + j;
+        kc[(size_t)to * geo.dh + x] = kc[(size_t)from * geo.dh + x];
+        vc[kv_v_idx(geo, x, to)] = vc[kv_v_idx(geo, x, from)];
+    }
+}
+
+extern "C" int32_t csd_verify_tree(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *parent,
+                                   const int32_t *cache_len, int32_t B, int32_t m, float temperature, float *logits,
+                                   float *probs, void *stream) {
+    int32_t rc = check_block(mod, kv, tokens, cache_len, B, m);
+    if (rc != CSD_OK) return rc;
+    if (!logits || !parent) return CSD_ENULL;
+    if (mod->cfg.arch != 0) return CSD_EUNSUPPORTED;
+    if (m > 64) return CSD_ESHAPE;                           // a row's ancestors are one 64-bit mask
+    if (probs && !(temperature > 0.f)) return CSD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_tree_prepare, dim3(B), dim3(64), 0, st, parent, m, mod->tree_depth, mod->tree_anc);
+    CSD_LAUNCH_CHECK();
+    mod->tree_call = true;                                   // the kernels take the two arrays as arguments at enqueue time
+    rc = csd_forward_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
+    mod->tree_call = false;
+    if (rc != CSD_OK) return rc;
+    if (probs) {
+        ProfScope ps(mod, st, CSD_PROF_OTHER);
+        if ((rc = csd_softmax_enqueue(logits, probs, (int64_t)B * m, mod->cfg.vocab, temperature, st)) != CSD_OK) return rc;
+    }
+    return CSD_OK;
+}
+
+extern "C" int32_t csd_tree_commit(const csd_model *mod, void *kv, const int32_t *cache_len, const int32_t *path,
+                                   const int32_t *n_accepted, int32_t B, int32_t m, void *stream) {
+    if (!mod || !kv || !cache_len || !path || !n_accepted) return CSD_ENULL;
+    if (B < 1 || m < 1) return CSD_EINVAL;
+    if (B > mod->cfg.max_batch || m > mod->cfg.max_block || m > 64) return CSD_ESHAPE;
+    if (mod->cfg.arch != 0) return CSD_EUNSUPPORTED;
+    const csd_model_cfg &c = mod->cfg;
+    const KvGeom geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, c.n_layers, mod->kperm ? 1 : 0};
+    const dim3 grid(c.n_layers, B, c.n_heads);
+    if (c.dtype == CSD_DTYPE_BF16)
+        hipLaunchKernelGGL((k_tree_commit<bf16_t>), grid, dim3(c.head_dim), 0, (hipStream_t)stream, (bf16_t *)kv, geo, cache_len,
+                           path, n_accepted, m);
+    else
+        hipLaunchKernelGGL((k_tree_commit<float>), grid, dim3(c.head_dim), 0, (hipStream_t)stream, (float *)kv, geo, cache_len,
+                           path, n_accepted, m);
+    CSD_LAUNCH_CHECK();
     return CSD_OK;
 }
 

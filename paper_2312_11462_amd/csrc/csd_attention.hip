@@ -44,6 +44,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
     }
     const int row = rt * 16 + col;                           // this lane's block row
     const int qpos = t + row;                                // it sees cache rows 0..qpos
+    const unsigned long long anc_row = (mode.anc && row < m) ? mode.anc[b * m + row] : 0ull;
     u32x4 qf[DH / 32][2];                                    // hi and lo planes of the query
 #pragma unroll
     for (int s = 0; s < DH / 32; s++) {
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
             for (int j = 0; j < 8; j++) {
                 const int key = kb + 8 * g + j;
                 float s = sT[j >> 2][j & 3] * scale;
-                const bool seen = (!causal || key <= qpos) && key < nk;
+                const bool seen = (mode.anc ? tree_sees(anc_row, key, t) : (!causal || key <= qpos)) && key < nk;
                 s += bias[p][j];                             // 0 without a bias table; unseen keys are masked next
                 sv[j] = seen ? s : -INFINITY;
                 mx = fmaxf(mx, sv[j]);

@@ -327,6 +327,7 @@ struct AttnArgs {
     float *part;              // chunk states [B][H][chunks_max][16 rows][DH + 4]
     int chunks_max;
     unsigned *counters;       // arrivals per (sequence, head): zero between launches
+    const unsigned long long *anc;   // tree block: per block row the rows it sees (see AttnMode), or null
     bf16_t *out;              // merged rows: the O projection's input planes, fragment order
     int out_plane_bytes, mtp;
 };
@@ -381,6 +382,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &A, AttnLds<DH> &L, boo
     const int nch = (nk + CA_KEYS - 1) / CA_KEYS;
     const bool active = have && c < nch;                     // a chunk past the end is not counted
     const int qpos = t + col;                                // block row `col` sees cache rows 0 .. qpos
+    const unsigned long long anc_row = (A.anc && have && col < m) ? A.anc[b * m + col] : 0ull;
     float mrun = -INFINITY, lrun = 0.f;
     f32x4 oacc[DT];
 #pragma unroll
@@ -402,7 +404,8 @@ __device__ __forceinline__ void attn_item(const AttnArgs &A, AttnLds<DH> &L, boo
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const int key = kb + 8 * g + j;
-            sv[j] = (key <= qpos && key < nk) ? sT[j >> 2][j & 3] * A.scale : -INFINITY;
+            const bool seen = (A.anc ? tree_sees(anc_row, key, t) : key <= qpos) && key < nk;
+            sv[j] = seen ? sT[j >> 2][j & 3] * A.scale : -INFINITY;
             mx = fmaxf(mx, sv[j]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -565,7 +568,7 @@ __global__ __launch_bounds__(256) void kc_embed(const int32_t *__restrict__ toke
                                                 const float *__restrict__ gain, float *__restrict__ h, bf16_t *__restrict__ out,
                                                 int out_plane_bytes, int mtp, float *__restrict__ ssq_out,
                                                 const int32_t *__restrict__ cache_len, int m, int dh, float theta,
-                                                float2 *__restrict__ rope) {
+                                                float2 *__restrict__ rope, const int32_t *__restrict__ depth) {
     const int r = blockIdx.x;
     const int tok = tokens[r];
     const bool ok = tok >= 0 && tok < V;
@@ -587,7 +590,8 @@ __global__ __launch_bounds__(256) void kc_embed(const int32_t *__restrict__ toke
         ssq_out[T * 16 + r] = ss;
     }
     if (theta > 0.f) {
-        const int pos = cache_len[r / m] + r % m, half = dh / 2;
+        // the position of a row: where it sits in a plain block, how far it is from row 0 in a tree block
+        const int pos = cache_len[r / m] + (depth ? depth[r] : r % m), half = dh / 2;
         for (int x = threadIdx.x; x < half; x += blockDim.x) {
             const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
             rope[(size_t)r * half + x] = float2{(float)cos(ang), (float)sin(ang)};
@@ -663,7 +667,8 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL(kc_embed, dim3(M), dim3(256), 0, st, tokens, (const bf16_t *)mod->embed, V, d, mod->layers[0].attn_norm,
-                           mod->h, X1, pb_d, mtp, ssq1, cache_len, m, c.head_dim, c.rope_theta, mod->rope);
+                           mod->h, X1, pb_d, mtp, ssq1, cache_len, m, c.head_dim, c.rope_theta, mod->rope,
+                           mod->tree_call ? mod->tree_depth : nullptr);
         CSD_LAUNCH_CHECK();
     }
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
@@ -695,7 +700,7 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
         return P;
     };
     const AttnArgs attn{(const bf16_t *)mod->qbuf, (int)mod->q_plane, m, cache_len, geo, 0, (const bf16_t *)kv, scale, mod->attn_part,
-                        mod->attn_chunks_max, mod->attn_cnt, X2, pb_hd, mtp};
+                        mod->attn_chunks_max, mod->attn_cnt, mod->tree_call ? mod->tree_anc : nullptr, X2, pb_hd, mtp};
     int32_t rc;
     for (int l = 0; l < L; l++) {
         const LayerW &lw = mod->layers[l];
@@ -726,7 +731,9 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
             if ((long long)chunks * c.n_heads * B > 1024) {
                 // many sequences or long caches: the attention is bound by bandwidth, not by latency, and the kernel
                 // with longer key runs per wave (and a merge kernel) moves the cache faster
-                if ((rc = csd_attn_mfma_enqueue(mod, geo, kv, cache_len, B, m, l, scale, AttnMode{}, st, X2, mod->x_plane[1])) != CSD_OK)
+                AttnMode am;
+                if (mod->tree_call) am.anc = mod->tree_anc;
+                if ((rc = csd_attn_mfma_enqueue(mod, geo, kv, cache_len, B, m, l, scale, am, st, X2, mod->x_plane[1])) != CSD_OK)
                     return rc;
             } else {
                 ProfScope ps(mod, st, CSD_PROF_ATTN);

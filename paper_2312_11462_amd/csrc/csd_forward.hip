@@ -454,9 +454,11 @@ __global__ void k_bias_table(const float *__restrict__ rel_bias, const int32_t *
 
 // (cos, sin) of the rotary angle pos * theta^(-2x/dh) of every block row of a call and every pair x < dh/2,
 // evaluated in double precision once per call instead of once per layer and head.
-__global__ void k_rope_table(const int32_t *__restrict__ cache_len, int m, int dh, float theta, float2 *__restrict__ tab) {
+__global__ void k_rope_table(const int32_t *__restrict__ cache_len, int m, int dh, float theta, float2 *__restrict__ tab,
+                             const int32_t *__restrict__ depth) {
     const int r = blockIdx.x, half = dh / 2;
-    const int pos = cache_len[r / m] + r % m;
+    // the position of a row: where it sits in a plain block, how far it is from row 0 in a tree block
+    const int pos = cache_len[r / m] + (depth ? depth[r] : r % m);
     for (int x = threadIdx.x; x < half; x += blockDim.x) {
         const double ang = (double)pos * pow((double)theta, -2.0 * (double)x / (double)dh);
         tab[(size_t)r * half + x] = float2{(float)cos(ang), (float)sin(ang)};
@@ -596,6 +598,8 @@ __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, in
     const int qpos = mode.fixed_nk > 0 ? 0 : cache_len[b] + i;
     int nk = mode.fixed_nk > 0 ? mode.fixed_nk : qpos + 1;
     nk = max(1, min(nk, geo.seq_pad));
+    const unsigned long long anc_row = mode.anc ? mode.anc[r] : 0ull;
+    const int t0 = qpos - i;
     const TC *kc = kv + kv_k_off(geo, layer, b, hh);
     const TC *vc = kv + kv_v_off(geo, layer, b, hh);
     for (int x = threadIdx.x; x < dh; x += 64) {
@@ -609,6 +613,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const TA *__restrict__ q, in
         for (int x = 0; x < dh; x++) s = fmaf(qs[x], to_f32<TC>(kc[(size_t)j * dh + x]), s);
         s *= scale;
         if (mode.rel_bias) s += mode.rel_bias[mode.bucket[min(qpos - j, 127)] * geo.H + hh];
+        if (mode.anc && !tree_sees(anc_row, j, t0)) s = -INFINITY;     // a row of the block that is not above this one
         sc[j] = s;
         mx = fmaxf(mx, s);
     }
@@ -826,7 +831,8 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
     if (c.rope_theta > 0.f) {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
-        hipLaunchKernelGGL(k_rope_table, dim3(M), dim3(64), 0, st, cache_len, m, c.head_dim, c.rope_theta, mod->rope);
+        hipLaunchKernelGGL(k_rope_table, dim3(M), dim3(64), 0, st, cache_len, m, c.head_dim, c.rope_theta, mod->rope,
+                           mod->tree_call ? mod->tree_depth : nullptr);
         CSD_LAUNCH_CHECK();
     }
     for (int l = 0; l < L; l++) {
@@ -839,13 +845,15 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
                                cache_len, geo, l, c.rope_theta > 0.f ? mod->rope : nullptr, qb, mod->q_plane, (TC *)kv);
             CSD_LAUNCH_CHECK();
         }
+        AttnMode am;
+        if (mod->tree_call) am.anc = mod->tree_anc;
         if (mod->mfma_attn) {
-            if ((rc = csd_attn_mfma_enqueue(mod, geo, kv, cache_len, B, m, l, scale, AttnMode{}, st)) != CSD_OK) return rc;
+            if ((rc = csd_attn_mfma_enqueue(mod, geo, kv, cache_len, B, m, l, scale, am, st)) != CSD_OK) return rc;
         } else {
             ProfScope ps(mod, st, CSD_PROF_ATTN);
             const size_t lds = sizeof(float) * (size_t)(c.head_dim + mod->seq_pad);
             hipLaunchKernelGGL((k_attn_simple<TA, TC>), dim3(M, c.n_heads), dim3(64), lds, st, qb, m, cache_len, geo, l,
-                               (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane, mod->act_mtp, AttnMode{});
+                               (const TC *)kv, scale, mod->q_plane, act, hd, mod->act_plane, mod->act_mtp, am);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.o, act, M, &S_g, st)) != CSD_OK) return rc;

@@ -194,7 +194,15 @@ struct AttnMode {
     const float *rel_bias = nullptr;
     const int32_t *bucket = nullptr;
     const float *bias_hd = nullptr;
+    // tree block: per block row, bit j set = block row j is that row or above it in the tree (null: a plain block,
+    // where a row sees every row before it)
+    const unsigned long long *anc = nullptr;
 };
+
+// which keys a block row sees: the cached rows [0, t), and of the block (stored from t on) the rows its mask names
+__device__ __forceinline__ bool tree_sees(unsigned long long anc_row, int key, int t) {
+    return key < t || (key - t < 64 && ((anc_row >> (key - t)) & 1ull));
+}
 
 enum { CSD_PROF_GEMM = 0, CSD_PROF_ATTN = 1, CSD_PROF_OTHER = 2, CSD_PROF_CLASSES = 3 };
 
@@ -234,6 +242,9 @@ struct csd_model {
     size_t x_plane[4] = {0, 0, 0, 0};    // elements between the hi and lo planes
     float *ssq[2] = {nullptr, nullptr};
     unsigned *attn_cnt = nullptr;        // arrival counters [max_batch][H] of the attention kernel: zero between launches
+    int32_t *tree_depth = nullptr;            // [m_max] scratch: depth of every row of a tree block
+    unsigned long long *tree_anc = nullptr;   // [m_max] scratch: ancestor masks of a tree block
+    bool tree_call = false;                   // the forward being enqueued is over a tree block (csd_verify_tree)
     unsigned long long *tail_rec = nullptr;   // [m_max] per-row records of the review that takes every row at once
     unsigned *tail_cnt = nullptr;        // [max_batch] arrival counters of that review: zero between launches
     // arch 1
@@ -265,6 +276,8 @@ struct ScratchPtrs {
     unsigned *attn_cnt;
     unsigned long long *tail_rec;   // per block row: (passed, token) of the review that takes every row at once
     unsigned *tail_cnt;      // per sequence: arrival counter of that review, zero between launches
+    int32_t *tree_depth;
+    unsigned long long *tree_anc;
 };
 size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out);
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp);   // returns the pieces in use before
