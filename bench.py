@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--cascade-steps", type=int, default=20, metavar="N",
                     help="workload target7b: also time N whole two-level cascade steps of configuration 3 "
                          "(the 160M-shaped draft level's reviews + the timed step); 0 = skip")
+    ap.add_argument("--tree-steps", type=int, default=10, metavar="N",
+                    help="workload target7b: also time N reviews of a tree block of Appendix B's shape (a lead chain of 4 "
+                         "with 8 children per lead node = 33 rows: forward, walk, commit); 0 = skip")
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy"])
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the benchmark, launch N plain 1 GiB copies (kernel k_copy_calib) so that a "
@@ -101,6 +104,9 @@ def main():
     host_w = None
     if not args.no_cpu_baseline:
         host_w = [x.cpu() for x in w]
+    tree_model = None
+    if args.workload == "target7b" and args.tree_steps > 0:      # a model of its own: blocks of up to 33 rows
+        tree_model = P.Model(shape, w, max_batch=1, max_seq=t + 64, max_block=33)
     del w
     torch.cuda.empty_cache()
     for l in range(shape.n_layers):
@@ -244,6 +250,48 @@ def main():
     roofline["note"] = ("frac: GEMM launches only, weights only, timed live with HIP events around every launch; "
                         "trace_frac: the same with the launch duration of the committed rocprofv3 kernel trace; "
                         "step_frac: all algorithmic bytes of the step over the whole step's time")
+
+    # ---- a review over a tree of drafts (extra, timed apart from `value`): Section 5.1 / Appendix B's shape, a lead chain
+    # of 4 (1 token of the draft level + 3 of Max-Gram in the paper's K matrix) with 8 candidates per lead node
+    tree = None
+    if tree_model is not None:
+        for l in range(shape.n_layers):
+            K, V = I.synthetic_kv(shape, t, seed, l, 0, device="cuda")
+            tree_model.kv_write(l, 0, 0, K, V)
+        depth, kids = 4, 8
+        par, lead = [-1], 0
+        for _ in range(depth):
+            first = len(par)
+            par += [lead] * kids
+            lead = first
+        rows = len(par)
+        t_parent = torch.tensor([par], dtype=torch.int32).cuda()
+        t_tokens = I.token_ids(rows, shape.vocab, seed, 4242).reshape(1, rows).contiguous().cuda()
+        t_tokens[0, 0] = ctx[0, t]
+        t_u = I.uniforms(rows, seed, 4243).reshape(1, rows).contiguous().cuda()
+        t_cl = cache_len[:1].clone()
+        t_lg = torch.empty((1, rows, shape.vocab), dtype=torch.float32, device="cuda")
+        t_pr = torch.empty_like(t_lg)
+
+        def tree_step():
+            tree_model.verify_tree(t_tokens, t_parent, t_cl, want_probs=(mode == 0), logits=t_lg, probs=t_pr if mode == 0 else None)
+            n_, path_, _ = P.tree_accept(t_pr if mode == 0 else t_lg, t_tokens, t_parent, t_u, mode=mode)
+            tree_model.tree_commit(t_cl, path_, n_)
+
+        for _ in range(3):
+            tree_step()
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(args.tree_steps):
+            tree_step()
+        c1.record()
+        torch.cuda.synchronize()
+        tree = {"ms": round(c0.elapsed_time(c1) / args.tree_steps, 4), "steps": args.tree_steps, "rows": rows,
+                "what": f"csd_verify_tree + csd_tree_accept + csd_tree_commit over a tree block of {rows} rows (lead chain of "
+                        f"{depth}, {kids} candidates per lead node, seeded random candidates), batch 1, {t}-row cache"}
+        del tree_model
+        torch.cuda.empty_cache()
 
     # ---- configuration 3 as a whole (extra, timed apart from `value`): one step of Algorithm 1 with K = [[2, k_tail],
     # [0, dk]] and device-resident control: the 160M-shaped level reviews Max-Gram drafts until two of its tokens
@@ -441,6 +489,8 @@ def main():
     }
     if cascade is not None:
         out["cascade_step"] = cascade
+    if tree is not None:
+        out["tree_step"] = tree
     if peaks is not None:
         out["measured_peaks"] = peaks
     print(json.dumps(out))

@@ -184,3 +184,37 @@ def test_target7b_block_over_rows_the_gpu_prefilled_itself(big):
     assert np.abs(Vg.cpu().numpy() - Vo).max() < 2e-2 * np.abs(Vo).max()
     block = toks[extra:][None].contiguous()
     _compare(gm, om, block, [t0 + extra], 0, "7B b1, 64 of 1024 cached rows from the GPU's own prefill, k5")
+
+
+def test_target7b_tree_of_17_rows_appendix_b_shape(big):
+    """A tree block at the full shape (Section 5.1, Appendix B: eight children per lead node): root + 2 levels x 8
+    children = 17 rows over the 1024-row cache.  All 17 x 32000 logits against the oracle's tree forward; the walk on
+    the GPU's probabilities equals the oracle's walk on the same probabilities; after the commit of a two-row path the
+    next plain block's logits match the oracle, which committed the same path."""
+    P, O, gm, om, shape, seed = big
+    t = 1024
+    _fill(gm, om, shape, seed, t, 1, 0)
+    parent = np.array([[-1] + [0] * 8 + [1] * 8], np.int32)
+    tokens = I.token_ids(17, shape.vocab, seed, 555)[None].contiguous()
+    cl = torch.tensor([t], dtype=torch.int32).cuda()
+    assert gm.path(1, 17) == 0
+    lg, pr = gm.verify_tree(tokens.cuda(), torch.from_numpy(parent).cuda(), cl, want_probs=True)
+    torch.cuda.synchronize()
+    print("tree: gpu done; oracle running", flush=True)
+    ref = om.verify_tree(tokens.numpy(), parent, [t])
+    ok, err = tol_ok(lg.cpu().numpy().astype(np.float64), ref, 2e-2, 1e-2)
+    print(f"7B tree of 17 rows: max |dlogit| {err:.3e}", flush=True)
+    assert ok, err
+    for mode in (0, 1):
+        u = I.uniforms(17, seed, 777 + mode).reshape(1, 17)
+        src = pr if mode == 0 else lg
+        n, path, nxt = P.tree_accept(src, tokens.cuda(), torch.from_numpy(parent).cuda(), u.cuda(), mode=mode)
+        on, opath, onxt = O.tree_accept(src.cpu().numpy(), tokens.numpy(), parent, u.numpy(), mode=mode)
+        assert int(n.item()) == int(on[0]) and int(nxt.item()) == int(onxt[0])
+    # keep the lead child and one of its children, as a review that accepted two candidates would
+    path = torch.full((1, 17), -1, dtype=torch.int32)
+    path[0, :2] = torch.tensor([1, 12], dtype=torch.int32)
+    gm.tree_commit(cl, path.cuda(), torch.tensor([2], dtype=torch.int32).cuda())
+    om.tree_commit(0, t, [1, 12])
+    nxt_block = I.token_ids(6, shape.vocab, seed, 556)[None].contiguous()
+    _compare(gm, om, nxt_block, [t + 3], 0, "7B b1, plain block after a tree commit")
