@@ -45,7 +45,7 @@ size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out) {
     char *x[4] = {nullptr, nullptr, nullptr, nullptr}, *ssq[2] = {nullptr, nullptr}, *cnt = nullptr;
     if (mod->chain_on) {
         for (int i = 0; i < 4; i++) x[i] = take(2 * 2 * mod->x_plane[i]);
-        for (int i = 0; i < 2; i++) ssq[i] = take(sizeof(float) * (size_t)(c.d_model / 16) * 16);
+        for (int i = 0; i < 2; i++) ssq[i] = take(sizeof(float) * (size_t)(c.d_model / 16) * 48);     // up to three row tiles
         cnt = take(sizeof(unsigned) * (size_t)c.max_batch * c.n_heads);
     }
     char *tail_rec = take(sizeof(unsigned long long) * (size_t)mod->m_max);

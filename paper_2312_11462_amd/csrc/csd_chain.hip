@@ -30,8 +30,8 @@ struct ChainGemm {
     int KS, n_units, wbytes;  // k-steps of 32; units a workgroup owns whole (a tile; gate|up: a gate tile and its up tile)
     const bf16_t *a;          // input planes (hi, lo), fragment order (act_tiled_idx)
     int a_plane_bytes, mtp, M;
-    const float *ssq_in;      // [n_ssq][16]: sum of squares of the input's source rows per 16-feature tile (folded norm) or null
-    int n_ssq;
+    const float *ssq_in;      // [n_ssq][ssq_rows]: sum of squares of the input's source rows per 16-feature tile (folded norm) or null
+    int n_ssq, ssq_rows;      // ssq_rows: 16 * (row tiles of the call), for ssq_in and ssq_out alike
     float inv_d, eps;
     // EPI_RESID: residual stream, next norm's gain, output planes + sums of squares
     float *h;
@@ -106,12 +106,17 @@ __device__ __forceinline__ void gemm_load_w(u32x4 (&W)[NT], const ChainGemm &P, 
                                                                               tv ? ((S.t0 + j) * P.KS + ks) * 1024 : 0, 2));
     }
 }
-__device__ __forceinline__ void gemm_load_a(u32x4 (&A)[2], const ChainGemm &P, const GemmShare &S, __amdgpu_buffer_rsrc_t ra, int ks,
-                                            int voff_a) {
+template <int MT>
+__device__ __forceinline__ void gemm_load_a(u32x4 (&A)[MT][2], const ChainGemm &P, const GemmShare &S, __amdgpu_buffer_rsrc_t ra, int ks,
+                                            const int (&voff_a)[MT]) {
     const bool in = ks < S.ks1;   // uniform
-    A[0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, in ? voff_a : CH_OOB, in ? ks * P.mtp * 1024 : 0, 0));
-    A[1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, in ? voff_a : CH_OOB,
-                                                                          in ? P.a_plane_bytes + ks * P.mtp * 1024 : 0, 0));
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        A[mt][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, in ? voff_a[mt] : CH_OOB,
+                                                                                  in ? (ks * P.mtp + mt) * 1024 : 0, 0));
+        A[mt][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                 ra, in ? voff_a[mt] : CH_OOB, in ? P.a_plane_bytes + (ks * P.mtp + mt) * 1024 : 0, 0));
+    }
 }
 
 // The first R k-steps of a wave's weight stream: they depend on nothing the other workgroups produce, so a
@@ -124,121 +129,33 @@ __device__ __forceinline__ void gemm_prefetch(u32x4 (&Wr)[R][NT], const ChainGem
     for (int r = 0; r < R; r++) gemm_load_w<NT>(Wr[r], P, S, rw, S.ks0 + r, lane);
 }
 
-// The GEMM of one workgroup after gemm_prefetch: the wave's k-steps through the rings, the eight partial
-// tiles added in LDS in wave order, the epilogue.  LDS: red [8 waves][NT][64 lanes] 16-byte words, then
-// [8 waves][16 rows] floats.  Every wave of the workgroup must call it (it holds a workgroup barrier).
-template <int NT, int R, int EPI>
-__device__ __forceinline__ void gemm_run(u32x4 (&Wr)[R][NT], const ChainGemm &P, const GemmShare &S, char *smem) {
-    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
-    float *rs_part = reinterpret_cast<float *>(smem + (size_t)CH_WAVES * NT * 64 * 16);
+// What the epilogue of one (tile, row tile) needs besides the sums, fetched before the main loop.
+struct EpiIn {
+    f32x4 hcur, gcur;
+    float2 cs[4];
+    int pos;
+};
+
+// The epilogue of one output tile (gate|up: a gate tile and its up tile) for the 16 rows of one row tile, on complete,
+// rstd-scaled sums v.  row: this lane's block row; T: global index of the (first) tile.  No workgroup barrier inside.
+template <int EPI>
+__device__ __forceinline__ void gemm_epilogue(const ChainGemm &P, const f32x4 *v, const EpiIn &E, int row, int T, int g) {
     constexpr int UT = EPI == EPI_GU ? 2 : 1;
-    const int lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
-    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int t0 = S.t0, nt = S.nt, ks0 = S.ks0, ks1 = S.ks1;
-    const __amdgpu_buffer_rsrc_t rw = ch_rsrc(P.Wp, (size_t)P.wbytes);
-    const __amdgpu_buffer_rsrc_t ra = ch_rsrc(P.a, (size_t)2 * P.a_plane_bytes);
-    const int voff_a = t < P.M ? (4 * t + g) * 16 : CH_OOB;
-
-    // partial sums of squares of the rows behind the folded norm: wave w, lane group g take every 32nd tile.
-    // Eight independent loads per turn (a dependent chain of them would hold up the rings behind it).
-    float ssq = 0.f;
-    if (P.ssq_in) {
-        const __amdgpu_buffer_rsrc_t rq = ch_rsrc(P.ssq_in, (size_t)P.n_ssq * 64);
-        for (int base = 0; base < P.n_ssq; base += 8 * 4 * CH_WAVES) {
-            float sv[8];
-#pragma unroll
-            for (int n = 0; n < 8; n++) {
-                const int i = base + n * 4 * CH_WAVES + w * 4 + g;
-                sv[n] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rq, i < P.n_ssq ? (i * 16 + t) * 4 : CH_OOB, 0, 0));
-            }
-#pragma unroll
-            for (int n = 0; n < 8; n++) ssq += sv[n];
-        }
-    }
-    u32x4 Ar[R][2];
-    f32x4 acc[NT];
-#pragma unroll
-    for (int j = 0; j < NT; j++) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int r = 0; r < R; r++) gemm_load_a(Ar[r], P, S, ra, ks0 + r, voff_a);
-
-    // epilogue inputs that do not depend on the sums: fetched now, used after the reduction
-    f32x4 hcur = f32x4{0.f, 0.f, 0.f, 0.f}, gcur = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (EPI == EPI_RESID && w < nt && t < P.M) {
-        const int col = (t0 + w) * 16 + 4 * g;
-        hcur = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ch_rsrc(P.h, (size_t)P.M * P.d * 4),
-                                                                              (int)(((size_t)t * P.d + col) * 4), 0, 0));
-        gcur = *reinterpret_cast<const f32x4 *>(P.gain + col);
-    }
-    float2 cs[4] = {float2{1.f, 0.f}, float2{1.f, 0.f}, float2{1.f, 0.f}, float2{1.f, 0.f}};
-    int pos = -1;
-    if (EPI == EPI_QKV && w < nt && t < P.M) {
-        const int ti = ((t0 + w) % (P.hd / 16)) % (P.dh / 16);
-        pos = P.cache_len[t / P.m] + t % P.m;
-        if (P.rope && (t0 + w) < 2 * (P.hd / 16)) {
-#pragma unroll
-            for (int r = 0; r < 4; r++) cs[r] = P.rope[(size_t)t * (P.dh / 2) + 8 * ti + 4 * (g & 1) + r];
-        }
-    }
-    if (P.ssq_in) {
-        ssq += __shfl_xor(ssq, 16, 64);
-        ssq += __shfl_xor(ssq, 32, 64);
-        if (g == 0) rs_part[w * 16 + t] = ssq;
-    }
-
-    for (int ks = ks0; ks < ks1; ks += R) {
-#pragma unroll
-        for (int r = 0; r < R; r++) {
-#pragma unroll
-            for (int j = 0; j < NT; j++)
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Wr[r][j]),
-                                                                 __builtin_bit_cast(bf16x8, Ar[r][0]), acc[j], 0, 0, 0);
-#pragma unroll
-            for (int j = 0; j < NT; j++)
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Wr[r][j]),
-                                                                 __builtin_bit_cast(bf16x8, Ar[r][1]), acc[j], 0, 0, 0);
-            gemm_load_w<NT>(Wr[r], P, S, rw, ks + r + R, lane);
-            gemm_load_a(Ar[r], P, S, ra, ks + r + R, voff_a);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < NT; j++) red[(w * NT + j) * 64 + lane] = acc[j];
-    __syncthreads();
-
-    // ------------------------------------------------------------------ epilogue: wave e takes unit e
-    if (w * UT >= nt) return;
-    float rstd = 1.f;
-    if (P.ssq_in) {
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < CH_WAVES; i++) s += rs_part[i * 16 + t];
-        rstd = rsqrtf(s * P.inv_d + P.eps);
-    }
-    f32x4 v[UT];
-#pragma unroll
-    for (int x = 0; x < UT; x++) {
-        v[x] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < CH_WAVES; i++) v[x] += red[(i * NT + w * UT + x) * 64 + lane];
-        v[x] *= rstd;
-    }
-    const int T = t0 + w * UT;                                 // global index of the (first) tile
-    const bool valid = t < P.M;
+    const bool valid = row < P.M;
     if (EPI == EPI_RESID) {
-        const f32x4 hv = hcur + v[0];
+        const f32x4 hv = E.hcur + v[0];
         float ss = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
         ss += __shfl_xor(ss, 16, 64);
         ss += __shfl_xor(ss, 32, 64);
         if (!valid) return;
         const int col = T * 16 + 4 * g;
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, hv), ch_rsrc(P.h, (size_t)P.M * P.d * 4),
-                                               (int)(((size_t)t * P.d + col) * 4), 0, CH_SC1);
-        const float o[4] = {hv[0] * gcur[0], hv[1] * gcur[1], hv[2] * gcur[2], hv[3] * gcur[3]};
-        store_planes4(P.out, P.out_plane_bytes, P.mtp, t, col, o);
+                                               (int)(((size_t)row * P.d + col) * 4), 0, CH_SC1);
+        const float o[4] = {hv[0] * E.gcur[0], hv[1] * E.gcur[1], hv[2] * E.gcur[2], hv[3] * E.gcur[3]};
+        store_planes4(P.out, P.out_plane_bytes, P.mtp, row, col, o);
         if (g == 0)
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, ss), ch_rsrc(P.ssq_out, (size_t)(P.d / 16) * 64),
-                                                  (T * 16 + t) * 4, 0, CH_SC1);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, ss),
+                                                  ch_rsrc(P.ssq_out, (size_t)(P.d / 16) * P.ssq_rows * 4), (T * P.ssq_rows + row) * 4, 0, CH_SC1);
     } else if (EPI == EPI_GU) {
         if (!valid) return;
         float o[4];
@@ -249,15 +166,16 @@ __device__ __forceinline__ void gemm_run(u32x4 (&Wr)[R][NT], const ChainGemm &P,
                                    : gt / (1.0f + expf(-gt));
             o[r] = a * up;
         }
-        store_planes4(P.out, P.out_plane_bytes, P.mtp, t, (T / 2) * 16 + 4 * g, o);
+        store_planes4(P.out, P.out_plane_bytes, P.mtp, row, (T / 2) * 16 + 4 * g, o);
     } else if (EPI == EPI_LOGITS) {
         if (!valid) return;
-        *reinterpret_cast<f32x4 *>(P.logits + (size_t)t * P.V + T * 16 + 4 * g) = v[0];
+        *reinterpret_cast<f32x4 *>(P.logits + (size_t)row * P.V + T * 16 + 4 * g) = v[0];
     } else {   // EPI_QKV
         const int tiles_per_region = P.hd / 16, tiles_per_head = P.dh / 16;
         const int region = T / tiles_per_region, tr = T % tiles_per_region;
         const int head = tr / tiles_per_head, ti = tr % tiles_per_head;
-        const int b = valid ? t / P.m : 0;
+        const int b = valid ? row / P.m : 0;
+        const int pos = E.pos;
         if (region < 2) {
             // tiles of q and k hold whole rotary pairs: lane groups 0, 1 the first-half entries 8 ti .. 8 ti + 7,
             // groups 2, 3 their partners; one exchange across the wave brings the pair together
@@ -265,7 +183,7 @@ __device__ __forceinline__ void gemm_run(u32x4 (&Wr)[R][NT], const ChainGemm &P,
 #pragma unroll
             for (int r = 0; r < 4; r++) {
                 const float other = __shfl_xor(v[0][r], 32, 64);
-                const float c = cs[r].x, s = cs[r].y;
+                const float c = E.cs[r].x, s = E.cs[r].y;
                 o[r] = g < 2 ? v[0][r] * c - other * s : other * s + v[0][r] * c;
             }
             if (!valid) return;
@@ -274,7 +192,7 @@ __device__ __forceinline__ void gemm_run(u32x4 (&Wr)[R][NT], const ChainGemm &P,
                 u32x2 hi, lo;
                 split4(o, hi, lo);
                 const __amdgpu_buffer_rsrc_t rq = ch_rsrc(P.q, (size_t)2 * P.q_plane_bytes);
-                const int off = (int)(((size_t)t * P.hd + head * P.dh + p0) * 2);
+                const int off = (int)(((size_t)row * P.hd + head * P.dh + p0) * 2);
                 __builtin_amdgcn_raw_buffer_store_b64(hi, rq, off, 0, CH_SC1);
                 __builtin_amdgcn_raw_buffer_store_b64(lo, rq, off + P.q_plane_bytes, 0, CH_SC1);
             } else if (pos >= 0 && pos < P.geo.seq_pad) {
@@ -299,13 +217,145 @@ __device__ __forceinline__ void gemm_run(u32x4 (&Wr)[R][NT], const ChainGemm &P,
     }
 }
 
-template <int NT, int R, int EPI>
+// The GEMM of one workgroup after gemm_prefetch: the wave's k-steps through the rings for MT row tiles of 16 rows, the
+// eight partial tiles added in LDS in wave order (one row tile at a time), the epilogue.  LDS: red [8 waves][NT][64 lanes]
+// 16-byte words, then [8 waves][16 MT rows] floats.  Every wave of the workgroup must call it (it holds workgroup barriers).
+template <int NT, int R, int EPI, int MT>
+__device__ __forceinline__ void gemm_run(u32x4 (&Wr)[R][NT], const ChainGemm &P, const GemmShare &S, char *smem) {
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+    float *rs_part = reinterpret_cast<float *>(smem + (size_t)CH_WAVES * NT * 64 * 16);
+    constexpr int UT = EPI == EPI_GU ? 2 : 1;
+    const int lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int t0 = S.t0, nt = S.nt, ks0 = S.ks0, ks1 = S.ks1;
+    const __amdgpu_buffer_rsrc_t rw = ch_rsrc(P.Wp, (size_t)P.wbytes);
+    const __amdgpu_buffer_rsrc_t ra = ch_rsrc(P.a, (size_t)2 * P.a_plane_bytes);
+    int voff_a[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) voff_a[mt] = mt * 16 + t < P.M ? (4 * t + g) * 16 : CH_OOB;
+
+    // partial sums of squares of the rows behind the folded norm: wave w, lane group g take every 32nd tile.
+    // Eight independent loads per row tile and turn (a dependent chain of them would hold up the rings behind it).
+    float ssq[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) ssq[mt] = 0.f;
+    if (P.ssq_in) {
+        const __amdgpu_buffer_rsrc_t rq = ch_rsrc(P.ssq_in, (size_t)P.n_ssq * P.ssq_rows * 4);
+        for (int base = 0; base < P.n_ssq; base += 8 * 4 * CH_WAVES) {
+            float sv[MT][8];
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int n = 0; n < 8; n++) {
+                    const int i = base + n * 4 * CH_WAVES + w * 4 + g;
+                    sv[mt][n] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                              rq, i < P.n_ssq ? (i * P.ssq_rows + mt * 16 + t) * 4 : CH_OOB, 0, 0));
+                }
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int n = 0; n < 8; n++) ssq[mt] += sv[mt][n];
+        }
+    }
+    u32x4 Ar[R][MT][2];
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int j = 0; j < NT; j++) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < R; r++) gemm_load_a<MT>(Ar[r], P, S, ra, ks0 + r, voff_a);
+
+    // epilogue inputs that do not depend on the sums: fetched now, used after the reduction
+    EpiIn E[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        const int row = mt * 16 + t;
+        E[mt].hcur = E[mt].gcur = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; r++) E[mt].cs[r] = float2{1.f, 0.f};
+        E[mt].pos = -1;
+        if (EPI == EPI_RESID && w < nt && row < P.M) {
+            const int col = (t0 + w) * 16 + 4 * g;
+            E[mt].hcur = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ch_rsrc(P.h, (size_t)P.M * P.d * 4),
+                                                                                        (int)(((size_t)row * P.d + col) * 4), 0, 0));
+            E[mt].gcur = *reinterpret_cast<const f32x4 *>(P.gain + col);
+        }
+        if (EPI == EPI_QKV && w < nt && row < P.M) {
+            const int ti = ((t0 + w) % (P.hd / 16)) % (P.dh / 16);
+            E[mt].pos = P.cache_len[row / P.m] + row % P.m;
+            if (P.rope && (t0 + w) < 2 * (P.hd / 16)) {
+#pragma unroll
+                for (int r = 0; r < 4; r++) E[mt].cs[r] = P.rope[(size_t)row * (P.dh / 2) + 8 * ti + 4 * (g & 1) + r];
+            }
+        }
+    }
+    if (P.ssq_in) {
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            float s = ssq[mt];
+            s += __shfl_xor(s, 16, 64);
+            s += __shfl_xor(s, 32, 64);
+            if (g == 0) rs_part[(w * MT + mt) * 16 + t] = s;
+        }
+    }
+
+    for (int ks = ks0; ks < ks1; ks += R) {
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+#pragma unroll
+                for (int j = 0; j < NT; j++)
+                    acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Wr[r][j]),
+                                                                         __builtin_bit_cast(bf16x8, Ar[r][mt][0]), acc[mt][j], 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < NT; j++)
+                    acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Wr[r][j]),
+                                                                         __builtin_bit_cast(bf16x8, Ar[r][mt][1]), acc[mt][j], 0, 0, 0);
+            }
+            gemm_load_w<NT>(Wr[r], P, S, rw, ks + r + R, lane);
+            gemm_load_a<MT>(Ar[r], P, S, ra, ks + r + R, voff_a);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // ------------------------------------------------------------------ reduction and epilogue, a row tile at a time:
+    // wave e takes unit e
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        if (mt > 0) __syncthreads();                           // the sums of the row tile before have been read
+#pragma unroll
+        for (int j = 0; j < NT; j++) red[(w * NT + j) * 64 + lane] = acc[mt][j];
+        __syncthreads();
+        if (w * UT < nt) {
+            float rstd = 1.f;
+            if (P.ssq_in) {
+                float s = 0.f;
+#pragma unroll
+                for (int i = 0; i < CH_WAVES; i++) s += rs_part[(i * MT + mt) * 16 + t];
+                rstd = rsqrtf(s * P.inv_d + P.eps);
+            }
+            f32x4 v[UT];
+#pragma unroll
+            for (int x = 0; x < UT; x++) {
+                v[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int i = 0; i < CH_WAVES; i++) v[x] += red[(i * NT + w * UT + x) * 64 + lane];
+                v[x] *= rstd;
+            }
+            gemm_epilogue<EPI>(P, v, E[mt], mt * 16 + t, t0 + w * UT, g);
+        }
+    }
+}
+
+template <int NT, int R, int EPI, int MT>
 __global__ __launch_bounds__(CH_THREADS) void kc_gemm(const ChainGemm P) {
     extern __shared__ __align__(16) char ch_smem[];
     const GemmShare S = gemm_share<EPI>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)));
     u32x4 Wr[R][NT];
     gemm_prefetch<NT, R>(Wr, P, S);
-    gemm_run<NT, R, EPI>(Wr, P, S, ch_smem);
+    gemm_run<NT, R, EPI, MT>(Wr, P, S, ch_smem);
 }
 
 // Causal attention of a block of up to 16 rows over the cached prefix, one launch per layer.  A workgroup
@@ -567,7 +617,7 @@ __global__ __launch_bounds__(256) void kc_attn(const AttnArgs A) {
 __global__ __launch_bounds__(256) void kc_embed(const int32_t *__restrict__ tokens, const bf16_t *__restrict__ E, int V, int d,
                                                 const float *__restrict__ gain, float *__restrict__ h, bf16_t *__restrict__ out,
                                                 int out_plane_bytes, int mtp, float *__restrict__ ssq_out,
-                                                const int32_t *__restrict__ cache_len, int m, int dh, float theta,
+                                                int ssq_rows, const int32_t *__restrict__ cache_len, int m, int dh, float theta,
                                                 float2 *__restrict__ rope, const int32_t *__restrict__ depth) {
     const int r = blockIdx.x;
     const int tok = tokens[r];
@@ -587,7 +637,7 @@ __global__ __launch_bounds__(256) void kc_embed(const int32_t *__restrict__ toke
             store_planes4(out, out_plane_bytes, mtp, r, col, o);
             ss += (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
         }
-        ssq_out[T * 16 + r] = ss;
+        ssq_out[T * ssq_rows + r] = ss;
     }
     if (theta > 0.f) {
         // the position of a row: where it sits in a plain block, how far it is from row 0 in a tree block
@@ -601,25 +651,61 @@ __global__ __launch_bounds__(256) void kc_embed(const int32_t *__restrict__ toke
 
 // ------------------------------------------------------------------------------- host driver
 
-template <int NT, int R, int EPI>
+#define CH_MT_MAX 3          /* row tiles of 16 rows a launch covers: blocks of up to 48 rows */
+
+template <int NT, int R, int EPI, int MT>
 static hipError_t chain_allow_lds() {
-    return hipFuncSetAttribute((const void *)kc_gemm<NT, R, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               CH_WAVES * NT * 64 * 16 + CH_WAVES * 16 * 4);
+    return hipFuncSetAttribute((const void *)kc_gemm<NT, R, EPI, MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               CH_WAVES * NT * 64 * 16 + CH_WAVES * MT * 16 * 4);
 }
 
 #ifndef CH_R1
 #define CH_R1 4
 #endif
-#define CH_FOR_ALL_NT(X, EPI) X(1, CH_R1, EPI) X(2, 6, EPI) X(3, 4, EPI) X(4, 4, EPI) X(6, 2, EPI) X(8, 2, EPI)
+// (tiles per workgroup, ring depth): one row tile; and two or three row tiles, where the accumulators and the
+// activation ring take more registers and the rings are shallower
+#define CH_FOR_ALL_NT(X, EPI, MT) X(1, CH_R1, EPI, MT) X(2, 6, EPI, MT) X(3, 4, EPI, MT) X(4, 4, EPI, MT) X(6, 2, EPI, MT) X(8, 2, EPI, MT)
+#define CH_FOR_ALL_NT_TALL(X, EPI, MT) X(1, 4, EPI, MT) X(2, 3, EPI, MT) X(3, 2, EPI, MT) X(4, 2, EPI, MT) X(6, 2, EPI, MT) X(8, 2, EPI, MT)
+#define CH_FOR_GU(X, MT) X(2, 6, EPI_GU, MT) X(4, 4, EPI_GU, MT) X(6, 2, EPI_GU, MT) X(8, 2, EPI_GU, MT)
+#define CH_FOR_GU_TALL(X, MT) X(2, 3, EPI_GU, MT) X(4, 2, EPI_GU, MT) X(6, 2, EPI_GU, MT) X(8, 2, EPI_GU, MT)
 
 int32_t csd_chain_setup() {
-#define CH_ALLOW(NT, R, EPI) CSD_HIP((chain_allow_lds<NT, R, EPI>()));
-    CH_FOR_ALL_NT(CH_ALLOW, EPI_QKV)
-    CH_FOR_ALL_NT(CH_ALLOW, EPI_RESID)
-    CH_FOR_ALL_NT(CH_ALLOW, EPI_LOGITS)
-    CH_ALLOW(2, 6, EPI_GU) CH_ALLOW(4, 4, EPI_GU) CH_ALLOW(6, 2, EPI_GU) CH_ALLOW(8, 2, EPI_GU)
+#define CH_ALLOW(NT, R, EPI, MT) CSD_HIP((chain_allow_lds<NT, R, EPI, MT>()));
+    CH_FOR_ALL_NT(CH_ALLOW, EPI_QKV, 1)
+    CH_FOR_ALL_NT(CH_ALLOW, EPI_RESID, 1)
+    CH_FOR_ALL_NT(CH_ALLOW, EPI_LOGITS, 1)
+    CH_FOR_GU(CH_ALLOW, 1)
+    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_QKV, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_QKV, 3)
+    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_RESID, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_RESID, 3)
+    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_LOGITS, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_LOGITS, 3)
+    CH_FOR_GU_TALL(CH_ALLOW, 2) CH_FOR_GU_TALL(CH_ALLOW, 3)
 #undef CH_ALLOW
     return CSD_OK;
+}
+
+template <int EPI, int MT>
+static int32_t chain_launch_mt(ChainGemm &P, int G, int per, hipStream_t st) {
+#define CH_LAUNCH(NT, R, E, MT_)                                                                                   \
+    if (per <= NT) {                                                                                              \
+        hipLaunchKernelGGL((kc_gemm<NT, R, E, MT_>), dim3(G), dim3(CH_THREADS),                                    \
+                           CH_WAVES * NT * 64 * 16 + CH_WAVES * MT_ * 16 * 4, st, P);                              \
+        return CSD_OK;                                                                                            \
+    }
+    if constexpr (MT == 1) {
+        if constexpr (EPI == EPI_GU) {
+            CH_FOR_GU(CH_LAUNCH, MT)
+        } else {
+            CH_FOR_ALL_NT(CH_LAUNCH, EPI, MT)
+        }
+    } else {
+        if constexpr (EPI == EPI_GU) {
+            CH_FOR_GU_TALL(CH_LAUNCH, MT)
+        } else {
+            CH_FOR_ALL_NT_TALL(CH_LAUNCH, EPI, MT)
+        }
+    }
+#undef CH_LAUNCH
+    return CSD_ESHAPE;
 }
 
 template <int EPI>
@@ -630,24 +716,17 @@ static int32_t chain_launch(ChainGemm &P, int n_tiles, hipStream_t st) {
     int G = P.n_units < 256 ? P.n_units : 256;
     if ((P.n_units + G - 1) / G * UT > 8) G = (P.n_units * UT + 7) / 8;
     const int per = (P.n_units + G - 1) / G * UT;            // most tiles of a workgroup
-#define CH_LAUNCH(NT, R, E)                                                                                       \
-    if (per <= NT) {                                                                                              \
-        hipLaunchKernelGGL((kc_gemm<NT, R, E>), dim3(G), dim3(CH_THREADS), CH_WAVES * NT * 64 * 16 + CH_WAVES * 16 * 4, st, P); \
-        return CSD_OK;                                                                                            \
-    }
-    if (EPI == EPI_GU) {
-        CH_LAUNCH(2, 6, EPI) CH_LAUNCH(4, 4, EPI) CH_LAUNCH(6, 2, EPI) CH_LAUNCH(8, 2, EPI)
-    } else {
-        CH_LAUNCH(1, CH_R1, EPI) CH_LAUNCH(2, 6, EPI) CH_LAUNCH(3, 4, EPI) CH_LAUNCH(4, 4, EPI) CH_LAUNCH(6, 2, EPI) CH_LAUNCH(8, 2, EPI)
-    }
-#undef CH_LAUNCH
+    const int mt = (P.M + 15) / 16;
+    if (mt == 1) return chain_launch_mt<EPI, 1>(P, G, per, st);
+    if (mt == 2) return chain_launch_mt<EPI, 2>(P, G, per, st);
+    if (mt == 3) return chain_launch_mt<EPI, 3>(P, G, per, st);
     return CSD_ESHAPE;
 }
 
 bool csd_chain_eligible(const csd_model *mod, int32_t B, int32_t m) {
     // (the cache appends address a layer's keys, or values, through one 32-bit offset)
     const size_t layer_kv = (size_t)mod->cfg.max_batch * mod->cfg.n_heads * mod->seq_pad * mod->cfg.head_dim * 2;
-    return mod->chain_on && B * m <= 16 && mod->seq_pad <= CA_KEYS * CA_MAX_CHUNKS && layer_kv < (1ull << 31);
+    return mod->chain_on && B * m <= 16 * CH_MT_MAX && mod->seq_pad <= CA_KEYS * CA_MAX_CHUNKS && layer_kv < (1ull << 31);
 }
 
 int32_t csd_attn_mfma_enqueue(csd_model *mod, const KvGeom &geo, const void *kv, const int32_t *cache_len, int B, int m,
@@ -664,10 +743,11 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     bf16_t *X1 = (bf16_t *)mod->x[0], *X2 = (bf16_t *)mod->x[1], *X3 = (bf16_t *)mod->x[2], *X4 = (bf16_t *)mod->x[3];
     float *ssq1 = mod->ssq[0], *ssq3 = mod->ssq[1];
     const float scale = 1.0f / sqrtf((float)c.head_dim);
+    const int ssq_rows = (M + 15) / 16 * 16;
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL(kc_embed, dim3(M), dim3(256), 0, st, tokens, (const bf16_t *)mod->embed, V, d, mod->layers[0].attn_norm,
-                           mod->h, X1, pb_d, mtp, ssq1, cache_len, m, c.head_dim, c.rope_theta, mod->rope,
+                           mod->h, X1, pb_d, mtp, ssq1, ssq_rows, cache_len, m, c.head_dim, c.rope_theta, mod->rope,
                            mod->tree_call ? mod->tree_depth : nullptr);
         CSD_LAUNCH_CHECK();
     }
@@ -689,6 +769,7 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     base.q_plane_bytes = (int)(mod->q_plane * 2);
     base.kv = (bf16_t *)kv;
     base.n_ssq = d / 16;
+    base.ssq_rows = ssq_rows;
     auto gemm = [&](const GemmW &w, const bf16_t *a, int a_plane_bytes, const float *ssq_in) {
         ChainGemm P = base;
         P.Wp = (const u32x4 *)w.data;
@@ -728,9 +809,10 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
                 if ((rc = chain_launch<EPI_QKV>(Pq, lw.qkv.N / 16, st)) != CSD_OK) return rc;
                 CSD_LAUNCH_CHECK();
             }
-            if ((long long)chunks * c.n_heads * B > 1024) {
+            if ((long long)chunks * c.n_heads * B > 1024 || m > 16) {
                 // many sequences or long caches: the attention is bound by bandwidth, not by latency, and the kernel
-                // with longer key runs per wave (and a merge kernel) moves the cache faster
+                // with longer key runs per wave (and a merge kernel) moves the cache faster; it also takes the blocks of
+                // more than 16 rows per sequence
                 AttnMode am;
                 if (mod->tree_call) am.anc = mod->tree_anc;
                 if ((rc = csd_attn_mfma_enqueue(mod, geo, kv, cache_len, B, m, l, scale, am, st, X2, mod->x_plane[1])) != CSD_OK)

@@ -37,17 +37,17 @@ def test_static_scratch_entry_point_equals_the_allocating_one():
     shape = I.ModelShape("noalloc", 0, "bf16", 3, 256, 4, 64, 704, 1024)
     seed = 0x5C2A
     w = I.make_weights(shape, seed, device="cuda", std=0.05)
-    gm = P.Model(shape, w, max_batch=3, max_seq=160, max_block=8)
-    assert gm.path(3, 8) == 0 and gm.path(1, 3) == 1     # the two calls below take the two forwards
-    toks = I.token_ids(3 * 120, shape.vocab, seed, 1).reshape(3, 120).cuda()
+    gm = P.Model(shape, w, max_batch=7, max_seq=160, max_block=8)
+    assert gm.path(7, 8) == 0 and gm.path(1, 3) == 1     # the two calls below take the two forwards
+    toks = I.token_ids(7 * 120, shape.vocab, seed, 1).reshape(7, 120).cuda()
     # prefill 96 rows per sequence through the ordinary entry point
     for pos in range(0, 96, 8):
-        gm.verify_block(toks[:, pos:pos + 8].contiguous(), torch.full((3,), pos, dtype=torch.int32, device="cuda"))
+        gm.verify_block(toks[:, pos:pos + 8].contiguous(), torch.full((7,), pos, dtype=torch.int32, device="cuda"))
     torch.cuda.synchronize()
     kv0 = gm.kv.clone()
     V = shape.vocab
-    # call 1: 3 sequences x 8 rows, dense draft distributions; call 2: 1 sequence x 3 rows, deterministic drafts
-    calls = [(toks[:, 96:104].contiguous(), torch.tensor([96, 90, 77], dtype=torch.int32, device="cuda"), True),
+    # call 1: 7 sequences x 8 rows, dense draft distributions; call 2: 1 sequence x 3 rows, deterministic drafts
+    calls = [(toks[:, 96:104].contiguous(), torch.tensor([96, 90, 77, 96, 81, 64, 95], dtype=torch.int32, device="cuda"), True),
              (toks[:1, 100:103].contiguous(), torch.tensor([41], dtype=torch.int32, device="cuda"), False)]
     results = {}
     for static in (False, True):
