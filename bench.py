@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--tree-steps", type=int, default=10, metavar="N",
                     help="workload target7b: also time N reviews of a tree block of Appendix B's shape (a lead chain of 4 "
                          "with 8 children per lead node = 33 rows: forward, walk, commit); 0 = skip")
+    ap.add_argument("--eager", action="store_true", help="time plain launches instead of replays of the captured step")
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy"])
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the benchmark, launch N plain 1 GiB copies (kernel k_copy_calib) so that a "
@@ -181,24 +182,46 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    gpu_ms_per_step = e0.elapsed_time(e1) / args.steps
-    # the same step timed one at a time (an event pair per step; each pair waits for the GPU to drain, so the
-    # launches of a step no longer hide behind the previous step): the median, reported beside the mean above
+    # The timed step is launched the way a serving loop on this hardware would launch it: captured once in a HIP graph
+    # (draft, forward and review: the same kernels on the same buffers; the library allocates nothing per call and
+    # clears its counters with kernels, so its calls can be captured as they are) and replayed.  --eager times plain
+    # launches instead; the other figure is reported beside `value` either way.
+    graph = None
+    if not args.eager:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            for _ in range(3):
+                graph.replay()
+            torch.cuda.synchronize()
+        except Exception as e:      # noqa: BLE001  (a capture failure must not take the benchmark line with it)
+            print("graph capture failed, timing eager launches:", e, file=sys.stderr)
+            graph = None
+    run = graph.replay if graph is not None else step
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n, e0.elapsed_time(e1) / n
+
+    ms_per_step, gpu_ms_per_step = timed(run, args.steps)
+    wall = ms_per_step * args.steps / 1e3
+    other_ms = timed(step if graph is not None else run, min(args.steps, 50))[1]    # eager launches when `value` is the graph's
+    eager_ms_per_step = other_ms if graph is not None else gpu_ms_per_step
+    # the same step timed one at a time (an event pair per step, each waited for): the median
     n_single = min(args.steps, 50)
     singles = []
     for _ in range(n_single):
         a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        step()
+        run()
         b_.record()
         b_.synchronize()
         singles.append(a.elapsed_time(b_))
@@ -472,6 +495,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "gpu_ms_per_step": round(gpu_ms_per_step, 4),
         "median_ms_single_step": None if median_single_ms is None else round(median_single_ms, 4),
+        "launch": "hip graph replay" if graph is not None else "eager",
+        "eager_ms_per_step": round(eager_ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {shape.n_layers} layers, d_model {shape.d_model}, batch {B}, "

@@ -1,4 +1,4 @@
-// Review forward for blocks of up to 16 rows (Section 2: one run of the reviewer scores every drafted
+// Review forward for blocks of up to 48 rows (Section 2: one run of the reviewer scores every drafted
 // position): five launches per layer, no split-K partial sums in memory, no epilogue kernels.
 //
 //   QKV GEMM   -> rotate q, k; q to the query buffer; K, V appended to the cache   (epilogue)
@@ -7,7 +7,8 @@
 //   gate|up    -> silu(rstd * gate) * (rstd * up) as the next GEMM's input              (epilogue)
 //   down GEMM  -> h += ; (h * gain); sum of squares per tile                            (epilogue)
 //
-// A GEMM workgroup owns a few whole 16-feature output tiles and splits K over its eight waves; every wave
+// A GEMM workgroup owns a few whole 16-feature output tiles (for one, two or three 16-row tiles of the block) and
+// splits K over its eight waves; every wave
 // streams its own K slice of the pre-tiled weights through a register ring and multiplies it with the
 // activation fragments of the same slice (read from L2: no two waves need the same ones), the eight
 // partial tiles are added in LDS in wave order (deterministic), and the epilogue runs in the same kernel
