@@ -23,10 +23,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 counter runs of this same command
 # (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a copy of known size); the
 # summaries and the commands are under profiles/.  Keyed by (workload, forward path).
-TRAFFIC_BYTES_PER_LAUNCH = {("target7b", 0): 103_707_000, ("target7b", 1): 104_086_000}
+TRAFFIC_BYTES_PER_LAUNCH = {("target7b", 1): 104_085_000}
 # Average duration of the same launches in the rocprofv3 kernel trace of this command (the HIP events that
 # bench.py puts around every launch add about 1.5 us each): profiles/, same key.
-TRACE_LAUNCH_US = {("target7b", 1): 21.41}
+TRACE_LAUNCH_US = {("target7b", 1): 21.61}
 
 
 def algorithmic_bytes(shape, B, t, m):
