@@ -236,6 +236,40 @@ def test_verify_accept_equals_the_two_calls(shape):
     assert n_checked > 10          # drafts were kept, so later rows and their statistics took part
 
 
+@pytest.mark.parametrize("B,m", [(1, 1), (3, 1), (3, 16), (5, 12)])
+def test_verify_accept_block_shapes_one_row_to_sixteen(B, m):
+    """The fused call at the edges of its launch shape: no drafts at all (m = 1: only the extra token is drawn), full
+    16-row blocks, several sequences with ragged cache lengths; decisions equal csd_verify_block + csd_accept and the
+    oracle's rule on the same probabilities, in both modes, one-hot and dense drafts."""
+    import paper_2312_11462_amd as P
+    from oracle import csd_oracle as O
+    gm, _ = make_pair(BF, 21, B, 128, 16, std=0.05)
+    toks = I.token_ids(B * 100, BF.vocab, 21, 1).reshape(B, 100)
+    for pos in range(0, 64, 16):
+        gm.verify_block(toks[:, pos:pos + 16].contiguous().cuda(), _dev([pos] * B))
+    cl_host = [64 - 3 * b for b in range(B)]
+    block = torch.stack([toks[b, cl_host[b]:cl_host[b] + m] for b in range(B)]).contiguous().cuda()
+    cl = _dev(cl_host)
+    k = m - 1
+    draft = block[:, 1:].contiguous()
+    for case, (mode, dense) in enumerate([(0, False), (0, True), (1, False)]):
+        u_acc = I.uniforms(B * max(k, 1), 21, 60 + case).reshape(B, max(k, 1))[:, :k].contiguous().cuda()
+        u_s = I.uniforms(B, 21, 80 + case).cuda()
+        lg, pr = gm.verify_block(block, cl, want_probs=True)
+        q = None
+        if dense and k > 0:
+            noise = torch.from_numpy(np.random.default_rng(case).normal(0, 0.5, (B, k, BF.vocab)).astype(np.float32)).cuda()
+            q = pr[:, :k] * torch.exp(noise)
+            q = (q / q.sum(-1, keepdim=True)).contiguous()
+        src = pr if mode == 0 else lg
+        a = P.accept(src, q, draft, u_acc, u_s, mode=mode)
+        b = gm.verify_accept(block, cl, u_acc, u_s, q=q, mode=mode)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]), (case, a, b)
+        o = O.accept(src.cpu().numpy(), None if q is None else q.cpu().numpy(), draft.cpu().numpy().reshape(B, k),
+                     u_acc.cpu().numpy().reshape(B, k), u_s.cpu().numpy(), 1.0, mode)
+        assert np.array_equal(o[0], b[0].cpu().numpy()) and np.array_equal(o[1], b[1].cpu().numpy()), (case, o, b)
+
+
 def test_argument_errors_enqueue_nothing():
     import paper_2312_11462_amd as P
     gm, _ = make_pair(I.TINY, 1, 1, 64, 8)
