@@ -148,8 +148,8 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->q_plane = (size_t)m_pad * hd;
     mod->part_floats = (size_t)mod->s_max * mod->m_max * nmax;
     if (mod->mfma_attn) mod->attn_chunks_max = (keys_pad + 127) / 128;
-    // blocks of up to 48 rows of a LLaMA-style bf16 model take the forward of csd_chain.hip (CSD_PATH=multikernel: never)
-    mod->chain_on = mod->mfma && mod->mfma_attn && mod->kperm && !env_is("CSD_PATH", "multikernel");
+    // blocks of up to 48 rows of a bf16 model (either architecture) take the forward of csd_chain.hip (CSD_PATH=multikernel: never)
+    mod->chain_on = mod->mfma && mod->mfma_attn && (mod->kperm || c.arch == 1) && !env_is("CSD_PATH", "multikernel");
     if (mod->chain_on) {
         const int widths[4] = {d, hd, d, F};
         for (int i = 0; i < 4; i++) mod->x_plane[i] = (size_t)m_pad * widths[i];

@@ -379,6 +379,8 @@ struct AttnArgs {
     int chunks_max;
     unsigned *counters;       // arrivals per (sequence, head): zero between launches
     const unsigned long long *anc;   // tree block: per block row the rows it sees (see AttnMode), or null
+    const float *bias_hd;     // arch 1 self-attention: [H][128] bias by distance query - key (127: that or more), or null
+    int fixed_nk;             // > 0 (arch 1 cross-attention): every row sees keys [0, fixed_nk), whatever cache_len says
     bf16_t *out;              // merged rows: the O projection's input planes, fragment order
     int out_plane_bytes, mtp;
 };
@@ -428,12 +430,19 @@ __device__ __forceinline__ void attn_item(const AttnArgs &A, AttnLds<DH> &L, boo
 #pragma unroll
     for (int dt = 0; dt < DT; dt++)
         vf[dt] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rv, (int)(kv_v_idx(geo, dt * 16 + col, kb + 8 * g) * 2), 0, 0));
-    const int t = have ? A.cache_len[b] : 0;
-    const int nk = max(0, min(t + m, geo.seq_pad));          // cache rows in play for this block
+    const bool causal = A.fixed_nk <= 0;
+    const int t = (have && causal) ? A.cache_len[b] : 0;
+    const int nk = max(0, min(causal ? t + m : A.fixed_nk, geo.seq_pad));   // cache rows in play for this block
     const int nch = (nk + CA_KEYS - 1) / CA_KEYS;
     const bool active = have && c < nch;                     // a chunk past the end is not counted
     const int qpos = t + col;                                // block row `col` sees cache rows 0 .. qpos
     const unsigned long long anc_row = (A.anc && have && col < m) ? A.anc[b * m + col] : 0ull;
+    float bias[8];                                           // requested ahead of the scores they are added to
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        const int dist = qpos - (kb + 8 * g + j);
+        bias[j] = (A.bias_hd && have && dist >= 0) ? A.bias_hd[hh * 128 + min(dist, 127)] : 0.f;
+    }
     float mrun = -INFINITY, lrun = 0.f;
     f32x4 oacc[DT];
 #pragma unroll
@@ -455,8 +464,8 @@ __device__ __forceinline__ void attn_item(const AttnArgs &A, AttnLds<DH> &L, boo
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const int key = kb + 8 * g + j;
-            const bool seen = (A.anc ? tree_sees(anc_row, key, t) : key <= qpos) && key < nk;
-            sv[j] = seen ? sT[j >> 2][j & 3] * A.scale : -INFINITY;
+            const bool seen = (A.anc ? tree_sees(anc_row, key, t) : (!causal || key <= qpos)) && key < nk;
+            sv[j] = seen ? sT[j >> 2][j & 3] * A.scale + bias[j] : -INFINITY;
             mx = fmaxf(mx, sv[j]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -738,17 +747,18 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
                           float *logits, hipStream_t st) {
     const csd_model_cfg &c = mod->cfg;
     const int M = B * m, d = c.d_model, F = c.d_ffn, hd = mod->hd, V = c.vocab, L = c.n_layers;
-    const KvGeom geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, L, 1};
+    const bool t5 = c.arch == 1;     // T5-style decoder: no rotary embedding, biased unscaled scores, a cross-attention sub-layer
+    const KvGeom geo{c.max_batch, c.n_heads, c.head_dim, mod->seq_pad, L, mod->kperm ? 1 : 0};
     const int mtp = mod->act_mtp;
     const int pb_d = (int)(mod->x_plane[0] * 2), pb_hd = (int)(mod->x_plane[1] * 2), pb_F = (int)(mod->x_plane[3] * 2);
     bf16_t *X1 = (bf16_t *)mod->x[0], *X2 = (bf16_t *)mod->x[1], *X3 = (bf16_t *)mod->x[2], *X4 = (bf16_t *)mod->x[3];
     float *ssq1 = mod->ssq[0], *ssq3 = mod->ssq[1];
-    const float scale = 1.0f / sqrtf((float)c.head_dim);
+    const float scale = t5 ? 1.0f : 1.0f / sqrtf((float)c.head_dim);
     const int ssq_rows = (M + 15) / 16 * 16;
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL(kc_embed, dim3(M), dim3(256), 0, st, tokens, (const bf16_t *)mod->embed, V, d, mod->layers[0].attn_norm,
-                           mod->h, X1, pb_d, mtp, ssq1, ssq_rows, cache_len, m, c.head_dim, c.rope_theta, mod->rope,
+                           mod->h, X1, pb_d, mtp, ssq1, ssq_rows, cache_len, m, c.head_dim, t5 ? 0.f : c.rope_theta, mod->rope,
                            mod->tree_call ? mod->tree_depth : nullptr);
         CSD_LAUNCH_CHECK();
     }
@@ -765,7 +775,7 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
     base.dh = c.head_dim;
     base.geo = geo;
     base.cache_len = cache_len;
-    base.rope = c.rope_theta > 0.f ? mod->rope : nullptr;
+    base.rope = (!t5 && c.rope_theta > 0.f) ? mod->rope : nullptr;
     base.q = (bf16_t *)mod->qbuf;
     base.q_plane_bytes = (int)(mod->q_plane * 2);
     base.kv = (bf16_t *)kv;
@@ -782,7 +792,7 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
         return P;
     };
     const AttnArgs attn{(const bf16_t *)mod->qbuf, (int)mod->q_plane, m, cache_len, geo, 0, (const bf16_t *)kv, scale, mod->attn_part,
-                        mod->attn_chunks_max, mod->attn_cnt, mod->tree_call ? mod->tree_anc : nullptr, X2, pb_hd, mtp};
+                        mod->attn_chunks_max, mod->attn_cnt, mod->tree_call ? mod->tree_anc : nullptr, nullptr, 0, X2, pb_hd, mtp};
     int32_t rc;
     for (int l = 0; l < L; l++) {
         const LayerW &lw = mod->layers[l];
@@ -801,6 +811,66 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
         Pd.out = X1;
         Pd.out_plane_bytes = pb_d;
         Pd.ssq_out = ssq1;
+        if (t5) {
+            // QKV -> self-attention (bias by relative position) -> O (+h) -> cross-q -> cross-attention over the projected
+            // encoder rows -> cross-O (+h) -> gate|up (tanh-GELU) -> down (+h): eight launches and two attention pairs
+            AttnMode self_mode, cross_mode;
+            self_mode.rel_bias = mod->rel_bias;
+            self_mode.bucket = mod->rel_bucket;
+            self_mode.bias_hd = mod->rel_bias_hd;
+            cross_mode.fixed_nk = c.enc_len;
+            const KvGeom cgeo{c.max_batch, c.n_heads, c.head_dim, mod->enc_pad, L, 0};
+            const void *kv_cross = (const char *)kv + csd_self_kv_bytes(mod);
+            Po.gain = lw.cross_norm;                           // the O projection feeds the cross-attention's norm
+            ChainGemm Pcq = gemm(lw.cq, X3, pb_d, ssq3);       // queries only: the epilogue of QKV with one region
+            Pcq.layer = l;
+            ChainGemm Pco = gemm(lw.co, X2, pb_hd, nullptr);
+            Pco.gain = lw.ffn_norm;
+            Pco.out = X3;
+            Pco.out_plane_bytes = pb_d;
+            Pco.ssq_out = ssq3;
+            Pg.gelu = 1;
+#define CH_STEP(EPI_, P_, W_)                                                                   \
+    {                                                                                           \
+        ProfScope ps(mod, st, CSD_PROF_GEMM);                                                   \
+        if ((rc = chain_launch<EPI_>(P_, (W_).N / 16, st)) != CSD_OK) return rc;               \
+        CSD_LAUNCH_CHECK();                                                                     \
+    }
+            // either attention: the kernel whose last chunk merges, or (more than 16 rows per sequence, or so many chunks
+            // that bandwidth rather than latency binds) the one with longer key runs and a merge kernel
+            auto attention = [&](const KvGeom &g_, const void *kv_, int keys_pad, const AttnMode &mode) -> int32_t {
+                const int chunks = (keys_pad + CA_KEYS - 1) / CA_KEYS;
+                if ((long long)chunks * c.n_heads * B > 1024 || m > 16 || chunks > CA_MAX_CHUNKS)
+                    return csd_attn_mfma_enqueue(mod, g_, kv_, cache_len, B, m, l, scale, mode, st, X2, mod->x_plane[1]);
+                ProfScope ps(mod, st, CSD_PROF_ATTN);
+                AttnArgs A = attn;
+                A.geo = g_;
+                A.kv = (const bf16_t *)kv_;
+                A.layer = l;
+                A.bias_hd = mode.bias_hd;
+                A.fixed_nk = mode.fixed_nk;
+                const dim3 grid(chunks, c.n_heads, B);
+                if (c.head_dim == 128)
+                    hipLaunchKernelGGL((kc_attn<128>), grid, dim3(256), 0, st, A);
+                else
+                    hipLaunchKernelGGL((kc_attn<64>), grid, dim3(256), 0, st, A);
+                CSD_LAUNCH_CHECK();
+                return CSD_OK;
+            };
+            CH_STEP(EPI_QKV, Pq, lw.qkv)
+            if ((rc = attention(geo, kv, mod->seq_pad, self_mode)) != CSD_OK) return rc;
+            CH_STEP(EPI_RESID, Po, lw.o)
+            CH_STEP(EPI_QKV, Pcq, lw.cq)
+            if ((rc = attention(cgeo, kv_cross, mod->enc_pad, cross_mode)) != CSD_OK) return rc;
+            CH_STEP(EPI_RESID, Pco, lw.co)
+            CH_STEP(EPI_GU, Pg, lw.gu)
+            CH_STEP(EPI_RESID, Pd, lw.down)
+#undef CH_STEP
+            if (mod->trace)
+                CSD_HIP(hipMemcpyAsync(mod->trace + (size_t)(l + 1) * M * d, mod->h, sizeof(float) * (size_t)M * d,
+                                       hipMemcpyDeviceToDevice, st));
+            continue;
+        }
         AttnArgs A = attn;
         A.layer = l;
         const int chunks = (mod->seq_pad + CA_KEYS - 1) / CA_KEYS;           // chunk slots; those past a sequence's rows leave at once

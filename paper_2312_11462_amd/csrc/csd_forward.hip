@@ -1031,12 +1031,12 @@ extern "C" int32_t csd_cross_kv_init(csd_model *mod, void *kv, const float *enc_
 
 int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const int32_t *cache_len, int32_t B,
                             int32_t m, float *logits, hipStream_t st) {
+    if (csd_chain_eligible(mod, B, m)) return csd_chain_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->cfg.arch == 1) {
         if (mod->cfg.dtype == CSD_DTYPE_FP32) return forward_t5<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);
         if (mod->mfma) return forward_t5<bf16_t, bf16_t, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
         return forward_t5<bf16_t, float, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);
     }
-    if (csd_chain_eligible(mod, B, m)) return csd_chain_enqueue(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->cfg.dtype == CSD_DTYPE_FP32)
         return forward_typed<float, float, float>(mod, kv, tokens, cache_len, B, m, logits, st);
     if (mod->mfma) return forward_typed<bf16_t, bf16_t, bf16_t>(mod, kv, tokens, cache_len, B, m, logits, st);

@@ -47,16 +47,18 @@ def test_t5_tiny_fp32_generic_kernels():
 BF_T5 = I.ModelShape("t5_bf_small", 1, "bf16", 2, 256, 4, 64, 512, 1024, rms_eps=1e-6, enc_len=96)
 
 
-@pytest.mark.parametrize("gemm,attn", [("generic", "generic"), ("mfma", "generic"), ("mfma", "mfma")])
-def test_t5_bf16_small_every_kernel_combination(gemm, attn):
+@pytest.mark.parametrize("gemm,attn,path", [("generic", "generic", "multikernel"), ("mfma", "generic", "multikernel"),
+                                            ("mfma", "mfma", "multikernel"), ("mfma", "mfma", "default")])
+def test_t5_bf16_small_every_kernel_combination(gemm, attn, path):
     """Prefix of 200 rows: distances beyond 128 share the last bias bucket; 96 encoder rows are not a
-    multiple of the 128-key attention chunk; 5 and 13 block rows, the second call ragged."""
-    os.environ["CSD_GEMM"], os.environ["CSD_ATTN"] = gemm, attn
+    multiple of the 128-key attention chunk; 5 and 13 block rows (one and two row tiles), the second call ragged.
+    The last combination is the forward with the epilogues inside its GEMM kernels (the default)."""
+    os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"] = gemm, attn, path
     try:
         gm, om = make_pair(BF_T5, 23, 2, 300, 16, std=0.05)
     finally:
-        del os.environ["CSD_GEMM"], os.environ["CSD_ATTN"]
-    assert gm.path(2, 5) == 0          # the single-launch kernel covers arch 0 only
+        del os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"]
+    assert gm.path(2, 5) == (1 if path == "default" else 0)
     _cross_init(gm, om, BF_T5, 2, 23)
     toks = I.token_ids(2 * 260, BF_T5.vocab, 23, 1).reshape(2, 260)
     prefill_both(gm, om, toks[:, :200], 16)
@@ -74,6 +76,7 @@ def test_t5xxl_decoder_shape_block_of_k4_against_oracle():
     shape, seed, t, k = wl["shape"], wl["seed"], wl["prefix"], wl["k"]
     w = I.make_weights(shape, seed, device="cuda")
     gm = P.Model(shape, w, max_batch=1, max_seq=t + 64, max_block=8)
+    assert gm.path(1, k + 1) == 1      # the forward with in-kernel epilogues, as bench.py times it
     host = [x.cpu() for x in w]
     del w
     torch.cuda.empty_cache()
