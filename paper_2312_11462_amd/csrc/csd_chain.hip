@@ -90,6 +90,11 @@ struct GemmShare {
 template <int EPI>
 __device__ __forceinline__ GemmShare gemm_share(const ChainGemm &P, int wg, int G, int w) {
     constexpr int UT = EPI == EPI_GU ? 2 : 1;
+    // Workgroups go to the eight compute dies round-robin, and what a die can pull from memory is what bounds the
+    // launch: the units are dealt so that every die gets the same number (consecutive shares to the workgroups of one
+    // die), not merely every workgroup within one of the next (688 units over 256 workgroups gave three dies 96 units
+    // and five dies 80, and the launch lasted as long as the dies with 96).
+    if (G % 8 == 0) wg = (wg & 7) * (G >> 3) + (wg >> 3);
     const int u0 = (int)((long long)P.n_units * wg / G), u1 = (int)((long long)P.n_units * (wg + 1) / G);
     return GemmShare{u0 * UT, (u1 - u0) * UT, P.KS * w / CH_WAVES, P.KS * (w + 1) / CH_WAVES};
 }
