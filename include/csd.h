@@ -186,7 +186,11 @@ int32_t csd_accept(const float *p, const float *q, const uint8_t *q_onehot, cons
 
 /*
  * csd_verify_block followed by csd_accept on the block's own rows, in one enqueue
- * (k = m-1 drafts = tokens[b][1..m-1]).  logits and probs are optional outputs here.
+ * (k = m-1 drafts = tokens[b][1..m-1]): the same decisions, bit for bit, as the two calls on the
+ * probabilities csd_verify_block would write (Section 2: the review of a block is one run of the
+ * reviewer followed by the accept rule).  logits and probs are optional outputs here: without probs
+ * no probability is written anywhere (softmax, the tests of all rows and the draw run in one launch
+ * behind the forward; vocabularies above 32768 or not a multiple of 4 take softmax and review as two).
  */
 int32_t csd_verify_accept(csd_model *model, void *kv, const int32_t *tokens, const int32_t *cache_len,
                           int32_t B, int32_t m, float temperature,
