@@ -81,7 +81,9 @@ int32_t csd_last_hip_error(void);
  * Matrices are row-major [in][out] in cfg->dtype; norm gains are fp32.  The weights are
  * copied (re-tiled for the MFMA kernels when dtype is bf16); the caller may free its tensors
  * once the stream has passed this call.  Allocates weights + scratch; this is the only
- * allocating call besides destroy.  n_weights must be 3 + 9*n_layers.
+ * allocating call besides destroy.  n_weights must be 3 + 9*n_layers.  The packing kernels and the
+ * clearing of the model's counters run on `stream`: later calls that use the model must be ordered behind
+ * this one on the device (the same stream, or an event).
  * arch 1: per layer self_norm[d], wq, wk, wv, wo, cross_norm[d], cq[d][H*dh], ck, cv, co[H*dh][d],
  * ffn_norm[d], w0[d][F] (through the GELU), w1[d][F], w_out[F][d]; then final_norm[d], lm_head[d][V],
  * rel_bias[32][H] (fp32 whatever dtype is); n_weights must be 4 + 14*n_layers.
