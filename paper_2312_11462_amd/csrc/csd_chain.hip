@@ -681,6 +681,9 @@ static hipError_t chain_allow_lds() {
 // activation ring take more registers and the rings are shallower
 #define CH_FOR_ALL_NT(X, EPI, MT) X(1, CH_R1, EPI, MT) X(2, 6, EPI, MT) X(3, 4, EPI, MT) X(4, 4, EPI, MT) X(6, 2, EPI, MT) X(8, 2, EPI, MT)
 #define CH_FOR_ALL_NT_TALL(X, EPI, MT) X(1, 4, EPI, MT) X(2, 3, EPI, MT) X(3, 2, EPI, MT) X(4, 2, EPI, MT) X(6, 2, EPI, MT) X(8, 2, EPI, MT)
+// (the QKV epilogue holds the most state: eight tiles with two or three row tiles do not fit the registers, and a model
+// whose QKV matrix has more than 6 * 256 column tiles takes the per-operation kernels for such blocks)
+#define CH_FOR_QKV_TALL(X, MT) X(1, 4, EPI_QKV, MT) X(2, 3, EPI_QKV, MT) X(3, 2, EPI_QKV, MT) X(4, 2, EPI_QKV, MT) X(6, 2, EPI_QKV, MT)
 #define CH_FOR_GU(X, MT) X(2, 6, EPI_GU, MT) X(4, 4, EPI_GU, MT) X(6, 2, EPI_GU, MT) X(8, 2, EPI_GU, MT)
 #define CH_FOR_GU_TALL(X, MT) X(2, 3, EPI_GU, MT) X(4, 2, EPI_GU, MT) X(6, 2, EPI_GU, MT) X(8, 2, EPI_GU, MT)
 
@@ -690,7 +693,7 @@ int32_t csd_chain_setup() {
     CH_FOR_ALL_NT(CH_ALLOW, EPI_RESID, 1)
     CH_FOR_ALL_NT(CH_ALLOW, EPI_LOGITS, 1)
     CH_FOR_GU(CH_ALLOW, 1)
-    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_QKV, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_QKV, 3)
+    CH_FOR_QKV_TALL(CH_ALLOW, 2) CH_FOR_QKV_TALL(CH_ALLOW, 3)
     CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_RESID, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_RESID, 3)
     CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_LOGITS, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_LOGITS, 3)
     CH_FOR_GU_TALL(CH_ALLOW, 2) CH_FOR_GU_TALL(CH_ALLOW, 3)
@@ -715,6 +718,8 @@ static int32_t chain_launch_mt(ChainGemm &P, int G, int per, hipStream_t st) {
     } else {
         if constexpr (EPI == EPI_GU) {
             CH_FOR_GU_TALL(CH_LAUNCH, MT)
+        } else if constexpr (EPI == EPI_QKV) {
+            CH_FOR_QKV_TALL(CH_LAUNCH, MT)
         } else {
             CH_FOR_ALL_NT_TALL(CH_LAUNCH, EPI, MT)
         }
@@ -741,6 +746,7 @@ static int32_t chain_launch(ChainGemm &P, int n_tiles, hipStream_t st) {
 bool csd_chain_eligible(const csd_model *mod, int32_t B, int32_t m) {
     // (the cache appends address a layer's keys, or values, through one 32-bit offset)
     const size_t layer_kv = (size_t)mod->cfg.max_batch * mod->cfg.n_heads * mod->seq_pad * mod->cfg.head_dim * 2;
+    if (B * m > 16 && 3 * mod->hd / 16 > 6 * 256) return false;
     return mod->chain_on && B * m <= 16 * CH_MT_MAX && mod->seq_pad <= CA_KEYS * CA_MAX_CHUNKS && layer_kv < (1ull << 31);
 }
 
