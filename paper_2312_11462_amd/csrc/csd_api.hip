@@ -52,23 +52,25 @@ size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out) {
     char *tail_cnt = take(sizeof(unsigned) * (size_t)c.max_batch);
     char *tree_depth = take(sizeof(int32_t) * (size_t)mod->m_max);
     char *tree_anc = take(sizeof(unsigned long long) * (size_t)mod->m_max);
+    char *rstd = take(sizeof(float) * (size_t)mod->m_max);
     if (out)
         *out = ScratchPtrs{(float *)h, act, qbuf, (float *)part, (float *)probs, (float2 *)rope, (float *)attn_part,
                            {x[0], x[1], x[2], x[3]}, {(float *)ssq[0], (float *)ssq[1]}, (unsigned *)cnt,
                            (unsigned long long *)tail_rec, (unsigned *)tail_cnt, (int32_t *)tree_depth,
-                           (unsigned long long *)tree_anc};
+                           (unsigned long long *)tree_anc, (float *)rstd};
     return off;
 }
 
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp) {
     const ScratchPtrs old{mod->h, mod->act, mod->qbuf, mod->part, mod->probs, mod->rope, mod->attn_part,
                           {mod->x[0], mod->x[1], mod->x[2], mod->x[3]}, {mod->ssq[0], mod->ssq[1]}, mod->attn_cnt,
-                          mod->tail_rec, mod->tail_cnt, mod->tree_depth, mod->tree_anc};
+                          mod->tail_rec, mod->tail_cnt, mod->tree_depth, mod->tree_anc, mod->rstd};
     mod->attn_cnt = sp.attn_cnt;
     mod->tail_rec = sp.tail_rec;
     mod->tail_cnt = sp.tail_cnt;
     mod->tree_depth = sp.tree_depth;
     mod->tree_anc = sp.tree_anc;
+    mod->rstd = sp.rstd;
     for (int i = 0; i < 4; i++) mod->x[i] = sp.x[i];
     for (int i = 0; i < 2; i++) mod->ssq[i] = sp.ssq[i];
     mod->h = sp.h;

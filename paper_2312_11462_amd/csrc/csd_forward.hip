@@ -374,11 +374,14 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const TW *__restrict__ W, c
 
 // ------------------------------------------------------------------------------- epilogues
 
-// h[r] = E[token[r]];  a[r] = rmsnorm(h[r]) * g
+// h[r] = E[token[r]];  a[r] = h[r] * g and rstd[r] = 1 / sqrt(mean(h[r]^2) + eps): the norm is folded around the
+// GEMM that follows, rmsnorm(h) * g @ W = rstd * ((h * g) @ W), so that what is rounded to the two bf16 planes is
+// h * g (exact for embedding rows with unit gains) and the scale is applied to fp32 sums by the GEMM's epilogue kernel.
 template <typename TW, typename TA>
 __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ tokens, const TW *__restrict__ E, int V,
                                                     int d, const float *__restrict__ g, float eps,
-                                                    float *__restrict__ h, TA *__restrict__ a, int lda, size_t plane, int mtp) {
+                                                    float *__restrict__ h, TA *__restrict__ a, int lda, size_t plane, int mtp,
+                                                    float *__restrict__ rstd) {
     __shared__ float red[16];
     const int r = blockIdx.x;
     const int tok = tokens[r];
@@ -390,12 +393,12 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ 
         ss += v * v;
     }
     ss = block_sum(ss, red);
-    const float rs = rsqrtf(ss / (float)d + eps);
+    if (threadIdx.x == 0) rstd[r] = rsqrtf(ss / (float)d + eps);
     for (int x = threadIdx.x; x < d; x += blockDim.x)
-        store_act<TA>(a, plane, r, x, lda, mtp, h[(size_t)r * d + x] * rs * g[x]);
+        store_act<TA>(a, plane, r, x, lda, mtp, h[(size_t)r * d + x] * g[x]);
 }
 
-// h[r] += sum_s part[s][r];  a[r] = rmsnorm(h[r]) * g.  One workgroup of 1024 threads per row, four
+// h[r] += sum_s part[s][r];  a[r] = h[r] * g, rstd[r] as above.  One workgroup of 1024 threads per row, four
 // consecutive features per thread and pass (16-byte loads when d allows), the new h kept in registers
 // between the sum of squares and the scaling for rows of up to RN_THREADS * 4 * RN_PASSES features.
 #define RN_THREADS 1024
@@ -403,7 +406,8 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *__restrict__ 
 template <typename TA>
 __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__restrict__ part, int S, int M, int d,
                                                               const float *__restrict__ g, float eps, float *__restrict__ h,
-                                                              TA *__restrict__ a, int lda, size_t plane, int mtp) {
+                                                              TA *__restrict__ a, int lda, size_t plane, int mtp,
+                                                              float *__restrict__ rstd) {
     __shared__ float red[RN_THREADS / 64];
     const int r = blockIdx.x;
     float ss = 0.f;
@@ -423,12 +427,12 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
             }
         }
         ss = block_sum(ss, red);
-        const float rs = rsqrtf(ss / (float)d + eps);
+        if (threadIdx.x == 0) rstd[r] = rsqrtf(ss / (float)d + eps);
 #pragma unroll
         for (int p = 0; p < RN_PASSES; p++) {
             const int x = (p * RN_THREADS + (int)threadIdx.x) * 4;
             if (x < d) {
-                store_act4<TA>(a, plane, r, x, lda, mtp, keep[p] * rs * gain[p]);
+                store_act4<TA>(a, plane, r, x, lda, mtp, keep[p] * gain[p]);
             }
         }
         return;
@@ -441,9 +445,9 @@ __global__ __launch_bounds__(RN_THREADS) void k_residual_norm(const float *__res
         ss += v * v;
     }
     ss = block_sum(ss, red);
-    const float rs = rsqrtf(ss / (float)d + eps);
+    if (threadIdx.x == 0) rstd[r] = rsqrtf(ss / (float)d + eps);
     for (int x = threadIdx.x; x < d; x += blockDim.x)
-        store_act<TA>(a, plane, r, x, lda, mtp, h[(size_t)r * d + x] * rs * g[x]);
+        store_act<TA>(a, plane, r, x, lda, mtp, h[(size_t)r * d + x] * g[x]);
 }
 
 // bias_hd[h][n] = rel_bias[bucket[n]][h]: the relative-position bias of head h at look-back distance n
@@ -472,8 +476,9 @@ template <typename TA, typename TC>
 __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, int S, int M, int m,
                                                 const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
                                                 const float2 *__restrict__ rope, TA *__restrict__ qout, size_t qplane,
-                                                TC *__restrict__ kv) {
+                                                TC *__restrict__ kv, const float *__restrict__ rstd) {
     const int r = blockIdx.x, hh = blockIdx.y;
+    const float rs = rstd[r];                            // the norm folded around the GEMM: scale its fp32 sums
     const int b = r / m, i = r % m;
     const int dh = geo.dh, half = dh / 2, hd = geo.H * dh, N = 3 * hd;
     const int pos = cache_len[b] + i;
@@ -492,6 +497,7 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
             v0 += p[2 * hd + x];
             v1 += p[2 * hd + x + half];
         }
+        q0 *= rs, q1 *= rs, k0 *= rs, k1 *= rs, v0 *= rs, v1 *= rs;
         float c = 1.f, sn = 0.f;                         // no table: a model without rotary embedding
         if (rope) {
             const float2 cs = rope[(size_t)r * half + x];
@@ -513,7 +519,8 @@ __global__ __launch_bounds__(64) void k_fix_qkv(const float *__restrict__ part, 
 // (gate tile j at packed tile 2j, up tile at 2j+1); row-major weights concatenate [gate | up].
 template <typename TA>
 __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, int S, int M, int F, int interleaved,
-                                                TA *__restrict__ f, int ldf, size_t plane, int mtp, int gelu) {
+                                                TA *__restrict__ f, int ldf, size_t plane, int mtp, int gelu,
+                                                const float *__restrict__ rstd) {
     const int r = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= F) return;
@@ -525,6 +532,7 @@ __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, 
         gsum += p[gc];
         usum += p[uc];
     }
+    gsum *= rstd[r], usum *= rstd[r];                    // the folded norm
     // gate activation: SiLU, or (arch 1) the tanh form of GELU
     const float sg = gelu ? 0.5f * gsum * (1.0f + tanhf(0.7978845608028654f * (gsum + 0.044715f * gsum * gsum * gsum)))
                           : gsum / (1.0f + expf(-gsum));
@@ -532,25 +540,25 @@ __global__ __launch_bounds__(256) void k_fix_gu(const float *__restrict__ part, 
 }
 
 __global__ __launch_bounds__(256) void k_fix_logits(const float *__restrict__ part, int S, int M, int V,
-                                                    float *__restrict__ logits) {
+                                                    float *__restrict__ logits, const float *__restrict__ rstd) {
     const int r = blockIdx.y;
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= V) return;
     float acc = 0.f;
     for (int s = 0; s < S; s++) acc += part[((size_t)s * M + r) * V + v];
-    logits[(size_t)r * V + v] = acc;
+    logits[(size_t)r * V + v] = acc * rstd[r];           // the folded final norm
 }
 
 // out[r][j] = sum_s part[s][r][j] (two bf16 planes on the MFMA path): the cross-attention queries of arch 1
 template <typename TA>
 __global__ __launch_bounds__(256) void k_fix_plain(const float *__restrict__ part, int S, int M, int N, TA *__restrict__ out,
-                                                   int ldo, size_t plane) {
+                                                   int ldo, size_t plane, const float *__restrict__ rstd) {
     const int r = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= N) return;
     float acc = 0.f;
     for (int s = 0; s < S; s++) acc += part[((size_t)s * M + r) * N + j];
-    store_act<TA>(out, plane, r, j, ldo, 0, acc);
+    store_act<TA>(out, plane, r, j, ldo, 0, acc * rstd[r]);      // the folded norm
 }
 
 // arch 1, once per prompt: rows [row0, row0 + M) of the projected encoder output, part[s][r][0..hd) = keys and
@@ -825,7 +833,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
-                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
+                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp, mod->rstd);
         CSD_LAUNCH_CHECK();
     }
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
@@ -842,7 +850,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, S_g, M, m,
-                               cache_len, geo, l, c.rope_theta > 0.f ? mod->rope : nullptr, qb, mod->q_plane, (TC *)kv);
+                               cache_len, geo, l, c.rope_theta > 0.f ? mod->rope : nullptr, qb, mod->q_plane, (TC *)kv, mod->rstd);
             CSD_LAUNCH_CHECK();
         }
         AttnMode am;
@@ -860,14 +868,14 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, lw.ffn_norm,
-                               c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
+                               c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp, mod->rstd);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.gu, act, M, &S_g, st)) != CSD_OK) return rc;
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, F,
-                               mod->mfma ? 1 : 0, act, F, mod->act_plane, mod->act_mtp, 0);
+                               mod->mfma ? 1 : 0, act, F, mod->act_plane, mod->act_mtp, 0, mod->rstd);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.down, act, M, &S_g, st)) != CSD_OK) return rc;
@@ -875,7 +883,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             const float *g = (l + 1 < L) ? mod->layers[l + 1].attn_norm : mod->final_norm;
             hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, g,
-                               c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
+                               c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp, mod->rstd);
             CSD_LAUNCH_CHECK();
         }
         if (mod->trace)
@@ -886,7 +894,7 @@ static int32_t forward_typed(csd_model *mod, void *kv, const int32_t *tokens, co
     if ((rc = run_gemm(mod, mod->lm, act, M, &S_g, st)) != CSD_OK) return rc;
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
-        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, V, logits);
+        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, V, logits, mod->rstd);
         CSD_LAUNCH_CHECK();
     }
     return CSD_OK;
@@ -931,14 +939,14 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
     auto resid_norm = [&](const GemmW &, const float *gain) -> int32_t {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_residual_norm<TA>), dim3(M), dim3(RN_THREADS), 0, st, mod->part, S_g, M, d, gain, c.rms_eps, mod->h, act,
-                           d, mod->act_plane, mod->act_mtp);
+                           d, mod->act_plane, mod->act_mtp, mod->rstd);
         CSD_LAUNCH_CHECK();
         return CSD_OK;
     };
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
         hipLaunchKernelGGL((k_embed_norm<TW, TA>), dim3(M), dim3(256), 0, st, tokens, (const TW *)mod->embed, V, d,
-                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp);
+                           mod->layers[0].attn_norm, c.rms_eps, mod->h, act, d, mod->act_plane, mod->act_mtp, mod->rstd);
         CSD_LAUNCH_CHECK();
     }
     if (mod->trace) CSD_HIP(hipMemcpyAsync(mod->trace, mod->h, sizeof(float) * (size_t)M * d, hipMemcpyDeviceToDevice, st));
@@ -948,7 +956,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_qkv<TA, TC>), dim3(M, c.n_heads), dim3(64), 0, st, mod->part, S_g, M, m, cache_len,
-                               geo, l, (const float2 *)nullptr, qb, mod->q_plane, (TC *)kv);
+                               geo, l, (const float2 *)nullptr, qb, mod->q_plane, (TC *)kv, mod->rstd);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = attention_any<TA, TC>(mod, geo, kv, cache_len, B, m, l, 1.0f, self_mode, st)) != CSD_OK) return rc;
@@ -958,7 +966,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_plain<TA>), dim3((hd + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, hd, qb, hd,
-                               mod->q_plane);
+                               mod->q_plane, mod->rstd);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = attention_any<TA, TC>(mod, cgeo, kv_cross, cache_len, B, m, l, 1.0f, cross_mode, st)) != CSD_OK) return rc;
@@ -968,7 +976,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
         {
             ProfScope ps(mod, st, CSD_PROF_OTHER);
             hipLaunchKernelGGL((k_fix_gu<TA>), dim3((F + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, F,
-                               mod->mfma ? 1 : 0, act, F, mod->act_plane, mod->act_mtp, 1);
+                               mod->mfma ? 1 : 0, act, F, mod->act_plane, mod->act_mtp, 1, mod->rstd);
             CSD_LAUNCH_CHECK();
         }
         if ((rc = run_gemm(mod, lw.down, act, M, &S_g, st)) != CSD_OK) return rc;
@@ -980,7 +988,7 @@ static int32_t forward_t5(csd_model *mod, void *kv, const int32_t *tokens, const
     if ((rc = run_gemm(mod, mod->lm, act, M, &S_g, st)) != CSD_OK) return rc;
     {
         ProfScope ps(mod, st, CSD_PROF_OTHER);
-        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, V, logits);
+        hipLaunchKernelGGL(k_fix_logits, dim3((V + 255) / 256, M), dim3(256), 0, st, mod->part, S_g, M, V, logits, mod->rstd);
         CSD_LAUNCH_CHECK();
     }
     return CSD_OK;

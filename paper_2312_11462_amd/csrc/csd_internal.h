@@ -242,6 +242,7 @@ struct csd_model {
     size_t x_plane[4] = {0, 0, 0, 0};    // elements between the hi and lo planes
     float *ssq[2] = {nullptr, nullptr};
     unsigned *attn_cnt = nullptr;        // arrival counters [max_batch][H] of the attention kernel: zero between launches
+    float *rstd = nullptr;                    // [m_max] scratch: 1 / rms of every row's residual stream (per-operation forward)
     int32_t *tree_depth = nullptr;            // [m_max] scratch: depth of every row of a tree block
     unsigned long long *tree_anc = nullptr;   // [m_max] scratch: ancestor masks of a tree block
     bool tree_call = false;                   // the forward being enqueued is over a tree block (csd_verify_tree)
@@ -278,6 +279,7 @@ struct ScratchPtrs {
     unsigned *tail_cnt;      // per sequence: arrival counter of that review, zero between launches
     int32_t *tree_depth;
     unsigned long long *tree_anc;
+    float *rstd;
 };
 size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out);
 ScratchPtrs csd_scratch_install(csd_model *mod, const ScratchPtrs &sp);   // returns the pieces in use before
