@@ -324,7 +324,7 @@ int32_t csd_debug_set_trace(csd_model *model, float *trace);
 
 /* Which forward csd_verify_block would run for B sequences of m rows: 0 = one kernel per operation with
  * split-K partial sums and epilogue kernels (any shape, both architectures), 1 = the forward whose GEMM
- * kernels own whole output tiles and hold their epilogues (bf16 models of either architecture, B*m <= 48 rows; the default
+ * kernels own whole output tiles and hold their epilogues (bf16 models of either architecture, B*m <= 32 rows; the default
  * where it applies).  The environment variable CSD_PATH=multikernel at csd_model_create forces 0. */
 int32_t csd_debug_path(const csd_model *model, int32_t B, int32_t m);
 

@@ -45,7 +45,7 @@ size_t csd_scratch_carve(const csd_model *mod, char *base, ScratchPtrs *out) {
     char *x[4] = {nullptr, nullptr, nullptr, nullptr}, *ssq[2] = {nullptr, nullptr}, *cnt = nullptr;
     if (mod->chain_on) {
         for (int i = 0; i < 4; i++) x[i] = take(2 * 2 * mod->x_plane[i]);
-        for (int i = 0; i < 2; i++) ssq[i] = take(sizeof(float) * (size_t)(c.d_model / 16) * 48);     // up to three row tiles
+        for (int i = 0; i < 2; i++) ssq[i] = take(sizeof(float) * (size_t)(c.d_model / 16) * 32);     // up to two row tiles
         cnt = take(sizeof(unsigned) * (size_t)c.max_batch * c.n_heads);
     }
     char *tail_rec = take(sizeof(unsigned long long) * (size_t)mod->m_max);
@@ -120,10 +120,6 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     const bool tiles_ok = d % 32 == 0 && hd % 32 == 0 && F % 32 == 0 && V % 16 == 0 && c.head_dim % 16 == 0;
     mod->mfma = c.dtype == CSD_DTYPE_BF16 && tiles_ok && !env_is("CSD_GEMM", "generic");
     mod->kperm = mod->mfma && c.arch == 0;     // rotary pair order only where there is a rotary embedding
-    if (const char *e = getenv("CSD_GEMM_RS_MIN_ROWS")) {
-        mod->gemm_rs_min_rows = atoi(e);
-        if (mod->gemm_rs_min_rows > 129) mod->gemm_rs_min_rows = 129;    // the other form holds at most 8 row tiles
-    }
     mod->mfma_attn = mod->mfma && (c.head_dim == 64 || c.head_dim == 128) && !env_is("CSD_ATTN", "generic");
     const int keys_pad = mod->seq_pad > mod->enc_pad ? mod->seq_pad : mod->enc_pad;
     if (!mod->mfma_attn && sizeof(float) * (size_t)(c.head_dim + keys_pad) > 64 * 1024) return CSD_ESHAPE;
@@ -150,7 +146,7 @@ static int32_t create_impl(csd_model *mod, const void *const *weights, hipStream
     mod->q_plane = (size_t)m_pad * hd;
     mod->part_floats = (size_t)mod->s_max * mod->m_max * nmax;
     if (mod->mfma_attn) mod->attn_chunks_max = (keys_pad + 127) / 128;
-    // blocks of up to 48 rows of a bf16 model (either architecture) take the forward of csd_chain.hip (CSD_PATH=multikernel: never)
+    // blocks of up to 32 rows of a bf16 model (either architecture) take the forward of csd_chain.hip (CSD_PATH=multikernel: never)
     mod->chain_on = mod->mfma && mod->mfma_attn && (mod->kperm || c.arch == 1) && !env_is("CSD_PATH", "multikernel");
     if (mod->chain_on) {
         const int widths[4] = {d, hd, d, F};

@@ -1,4 +1,4 @@
-// Review forward for blocks of up to 48 rows (Section 2: one run of the reviewer scores every drafted
+// Review forward for blocks of up to 32 rows (Section 2: one run of the reviewer scores every drafted
 // position): five launches per layer, no split-K partial sums in memory, no epilogue kernels.
 //
 //   QKV GEMM   -> rotate q, k; q to the query buffer; K, V appended to the cache   (epilogue)
@@ -7,7 +7,7 @@
 //   gate|up    -> silu(rstd * gate) * (rstd * up) as the next GEMM's input              (epilogue)
 //   down GEMM  -> h += ; (h * gain); sum of squares per tile                            (epilogue)
 //
-// A GEMM workgroup owns a few whole 16-feature output tiles (for one, two or three 16-row tiles of the block) and
+// A GEMM workgroup owns a few whole 16-feature output tiles (for one or two 16-row tiles of the block) and
 // splits K over its eight waves; every wave
 // streams its own K slice of the pre-tiled weights through a register ring and multiplies it with the
 // activation fragments of the same slice (read from L2: no two waves need the same ones), the eight
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(256) void kc_embed(const int32_t *__restrict__ toke
 
 // ------------------------------------------------------------------------------- host driver
 
-#define CH_MT_MAX 3          /* row tiles of 16 rows a launch covers: blocks of up to 48 rows */
+#define CH_MT_MAX 2          /* row tiles of 16 rows a launch covers: blocks of up to 32 rows */
 
 template <int NT, int R, int EPI, int MT>
 static hipError_t chain_allow_lds() {
@@ -677,11 +677,11 @@ static hipError_t chain_allow_lds() {
 #ifndef CH_R1
 #define CH_R1 4
 #endif
-// (tiles per workgroup, ring depth): one row tile; and two or three row tiles, where the accumulators and the
+// (tiles per workgroup, ring depth): one row tile; and two row tiles, where the accumulators and the
 // activation ring take more registers and the rings are shallower
 #define CH_FOR_ALL_NT(X, EPI, MT) X(1, CH_R1, EPI, MT) X(2, 6, EPI, MT) X(3, 4, EPI, MT) X(4, 4, EPI, MT) X(6, 2, EPI, MT) X(8, 2, EPI, MT)
 #define CH_FOR_ALL_NT_TALL(X, EPI, MT) X(1, 4, EPI, MT) X(2, 3, EPI, MT) X(3, 2, EPI, MT) X(4, 2, EPI, MT) X(6, 2, EPI, MT) X(8, 2, EPI, MT)
-// (the QKV epilogue holds the most state: eight tiles with two or three row tiles do not fit the registers, and a model
+// (the QKV epilogue holds the most state: eight tiles with two row tiles do not fit the registers, and a model
 // whose QKV matrix has more than 6 * 256 column tiles takes the per-operation kernels for such blocks)
 #define CH_FOR_QKV_TALL(X, MT) X(1, 4, EPI_QKV, MT) X(2, 3, EPI_QKV, MT) X(3, 2, EPI_QKV, MT) X(4, 2, EPI_QKV, MT) X(6, 2, EPI_QKV, MT)
 #define CH_FOR_GU(X, MT) X(2, 6, EPI_GU, MT) X(4, 4, EPI_GU, MT) X(6, 2, EPI_GU, MT) X(8, 2, EPI_GU, MT)
@@ -693,10 +693,10 @@ int32_t csd_chain_setup() {
     CH_FOR_ALL_NT(CH_ALLOW, EPI_RESID, 1)
     CH_FOR_ALL_NT(CH_ALLOW, EPI_LOGITS, 1)
     CH_FOR_GU(CH_ALLOW, 1)
-    CH_FOR_QKV_TALL(CH_ALLOW, 2) CH_FOR_QKV_TALL(CH_ALLOW, 3)
-    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_RESID, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_RESID, 3)
-    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_LOGITS, 2) CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_LOGITS, 3)
-    CH_FOR_GU_TALL(CH_ALLOW, 2) CH_FOR_GU_TALL(CH_ALLOW, 3)
+    CH_FOR_QKV_TALL(CH_ALLOW, 2)
+    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_RESID, 2)
+    CH_FOR_ALL_NT_TALL(CH_ALLOW, EPI_LOGITS, 2)
+    CH_FOR_GU_TALL(CH_ALLOW, 2)
 #undef CH_ALLOW
     return CSD_OK;
 }
@@ -739,7 +739,6 @@ static int32_t chain_launch(ChainGemm &P, int n_tiles, hipStream_t st) {
     const int mt = (P.M + 15) / 16;
     if (mt == 1) return chain_launch_mt<EPI, 1>(P, G, per, st);
     if (mt == 2) return chain_launch_mt<EPI, 2>(P, G, per, st);
-    if (mt == 3) return chain_launch_mt<EPI, 3>(P, G, per, st);
     return CSD_ESHAPE;
 }
 

@@ -684,47 +684,34 @@ ProfScope::~ProfScope() {
 }
 
 #define WG_U_MAX 4      /* k-steps per chunk of the workgroup-tiled GEMMs */
-template <int MT, int NT = 2>
+template <int MT>
 static int32_t launch_gemm_ws_mt(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int S,
                                  int groups, hipStream_t st) {
     const size_t lds = (size_t)2 * WG_U_MAX * MT * 2 * 64 * 16;      // allowed at csd_gemm_setup
-    hipLaunchKernelGGL((k_gemm_ws<NT, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
+    hipLaunchKernelGGL((k_gemm_ws<1, MT, WG_U_MAX>), dim3(groups * S), dim3(512), lds, st, reinterpret_cast<const u32x4 *>(w.data),
                        act, plane, mtp, part, M, Mtot, w.K, w.N, S);
     return CSD_OK;
 }
 
-// Blocks of up to 64 rows (of Mtot in the call): 128 columns per workgroup (64 at one or two row tiles); K is
-// split until there is a workgroup per compute unit (two at one or two row tiles).  *S_io: the
-// number of K splits, chosen here when 0 (later row chunks of the same call must use the same).
+// Blocks of up to 32 rows (of Mtot in the call): one column tile per wave, 64 columns per workgroup; K is split
+// until there are two workgroups per compute unit: the light workgroups share a compute unit, and two per unit stream
+// faster than one (measured: 3.84 -> 3.69 ms per step at 6 rows of the 7B shape; beyond 512 the partial sums cost
+// more).  Two column tiles per wave, 128 columns per workgroup, were slower here (4.02 against 3.86 ms at 6 rows,
+// 5.83 against 5.68 ms at 24 rows of batch 8).  *S_io: the number of K splits, chosen here when 0 (later row chunks
+// of the same call must use the same).
 static int32_t launch_gemm_ws(const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M, int Mtot, int *S_io,
                               hipStream_t st) {
-    // one or two row tiles: one column tile per wave, 64 columns per workgroup.  Twice the workgroups then
-    // reach the target below with half the K splits, so the epilogue kernels read half the partial sums,
-    // and two or three of these light workgroups share a compute unit (measured per step against two
-    // tiles per wave: 4.02 -> 3.86 ms at 6 rows of the 7B shape, 5.83 -> 5.68 ms at 24 rows of batch 8; from
-    // three row tiles on two tiles per wave are as fast or faster, their LDS reads being shared by more
-    // matrix instructions)
-    const int NT = (M + 15) / 16 <= 2 ? 1 : 2;
-    const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 4 * NT - 1) / (4 * NT);
+    const int n_tiles = w.N / 16, KS = w.K / 32, groups = (n_tiles + 3) / 4;
     int S = *S_io;
     if (S == 0) {
         S = 1;
-        // the light one-tile-per-wave workgroups share a compute unit, and two per unit stream faster than one
-        // (measured: 3.84 -> 3.69 ms per step at 6 rows of the 7B shape; beyond 512 the partial sums cost more)
-        const int wgs_min = NT == 1 ? 512 : 256;
-        while (groups * S < wgs_min && S * 2 <= w.S && KS / (S * 2) >= 2 * WG_U_MAX) S *= 2;
+        while (groups * S < 512 && S * 2 <= w.S && KS / (S * 2) >= 2 * WG_U_MAX) S *= 2;
         *S_io = S;
     }
     switch ((M + 15) / 16) {
-    case 1: return launch_gemm_ws_mt<1, 1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 2: return launch_gemm_ws_mt<2, 1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 3: return launch_gemm_ws_mt<3>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 4: return launch_gemm_ws_mt<4>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 5: return launch_gemm_ws_mt<5>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 6: return launch_gemm_ws_mt<6>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 7: return launch_gemm_ws_mt<7>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    case 8: return launch_gemm_ws_mt<8>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    default: return CSD_ESHAPE;       // more row tiles do not fit the registers here: such blocks take the row-split form
+    case 1: return launch_gemm_ws_mt<1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    case 2: return launch_gemm_ws_mt<2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    default: return CSD_ESHAPE;       // taller blocks take the row-split form
     }
 }
 
@@ -737,33 +724,51 @@ static int32_t launch_gemm_rs_t(const GemmW &w, const bf16_t *act, size_t plane,
     return CSD_OK;
 }
 
-// The row-split form: 256 columns per workgroup (128 when every compute wave holds three row tiles).  Its
-// staging waves keep two chunks of weights in flight per workgroup, so half the compute units already
-// saturate HBM: K is split only until there are 128 workgroups, which keeps the partial-sum traffic low.
+// The row-split form.  Its launches are bound by the matrix instructions of the busiest compute wave, so what
+// matters is how many compute units have a workgroup: the column tiles per workgroup (CT) and the K splits (S, at most
+// 8: the partial sums are traffic too) are chosen per matrix so that the launch comes as close to one workgroup per
+// compute unit as the shape allows, the wider workgroup winning a tie (it reads the activation rows less often).
+// Measured per launch at 128 rows of the 7B shape, against 16 tiles and 128 workgroups for every matrix: QKV 40.6 ->
+// 33.1 us (12 tiles, 4 splits, 256 workgroups), O and down 30.6 -> 23.6 (8, 8, 256), gate|up 57.2 -> 49.1 (11, 2, 252).
+static int rs_splits(int groups, int KS, int Mtot, int N, size_t part_floats) {
+    int S = 1;
+    while (groups * (S + 1) <= 256 && S < 8 && KS / (S + 1) >= 2 * WG_U_MAX && (size_t)(S + 1) * Mtot * N <= part_floats) S++;
+    return S;
+}
 static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M,
                               int Mtot, int *S_io, hipStream_t st) {
     const int n_tiles = w.N / 16, KS = w.K / 32, MT = (M + 15) / 16;
-    const int rw = (MT + 3) / 4, ct = rw == 3 ? 8 : 16;
-    const int groups = (n_tiles + ct - 1) / ct;
-    int S = *S_io;
-    if (S == 0) {
-        S = 1;
-        while (groups * S < 128 && S < 16 && KS / (S + 1) >= 2 * WG_U_MAX &&
-               (size_t)(S + 1) * Mtot * w.N <= mod->part_floats)
-            S++;
-        *S_io = S;
+    const int rw = MT <= 8 ? 2 : 3;          // row tiles per compute wave: waves past the block's rows only pass the barriers
+    static const int cts2[] = {16, 12, 11, 8, 6, 0}, cts3[] = {8, 6, 0};
+    const int *cts = rw == 2 ? cts2 : cts3;
+    int ct = cts[0], S = *S_io;
+    double best = -1.0;
+    for (int i = 0; cts[i]; i++) {
+        const int groups = (n_tiles + cts[i] - 1) / cts[i];
+        const int s = *S_io ? *S_io : rs_splits(groups, KS, Mtot, w.N, mod->part_floats);
+        const int wgs = groups * s;
+        const double fill = (double)wgs / (256.0 * ((wgs + 255) / 256));
+        if (fill > best) best = fill, ct = cts[i], S = s;
     }
-    if (rw == 1) return launch_gemm_rs_t<16, 1>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    if (rw == 2) return launch_gemm_rs_t<16, 2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
-    if (rw == 3) return launch_gemm_rs_t<8, 3>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    *S_io = S;
+    const int groups = (n_tiles + ct - 1) / ct;
+    if (rw == 2) switch (ct) {
+        case 16: return launch_gemm_rs_t<16, 2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+        case 12: return launch_gemm_rs_t<12, 2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+        case 11: return launch_gemm_rs_t<11, 2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+        case 8: return launch_gemm_rs_t<8, 2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+        default: return launch_gemm_rs_t<6, 2>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
+    }
+    if (MT <= 12) return ct == 8 ? launch_gemm_rs_t<8, 3>(w, act, plane, mtp, part, M, Mtot, S, groups, st)
+                                : launch_gemm_rs_t<6, 3>(w, act, plane, mtp, part, M, Mtot, S, groups, st);
     return CSD_ESHAPE;
 }
 
 // Once per process and device, at model creation (no runtime call besides launches happens later): allow
 // every GEMM instantiation its dynamic LDS (up to 144 KB).
-template <int MT, int NT = 2>
+template <int MT>
 static hipError_t ws_allow_lds() {
-    return hipFuncSetAttribute((const void *)k_gemm_ws<NT, MT, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    return hipFuncSetAttribute((const void *)k_gemm_ws<1, MT, WG_U_MAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                2 * WG_U_MAX * MT * 2 * 64 * 16);
 }
 template <int CT, int RW>
@@ -772,17 +777,15 @@ static hipError_t rs_allow_lds() {
                                2 * WG_U_MAX * CT * 64 * 16);
 }
 int32_t csd_gemm_setup() {
-    CSD_HIP((ws_allow_lds<1, 1>()));
-    CSD_HIP((ws_allow_lds<2, 1>()));
-    CSD_HIP(ws_allow_lds<3>());
-    CSD_HIP(ws_allow_lds<4>());
-    CSD_HIP(ws_allow_lds<5>());
-    CSD_HIP(ws_allow_lds<6>());
-    CSD_HIP(ws_allow_lds<7>());
-    CSD_HIP(ws_allow_lds<8>());
-    CSD_HIP((rs_allow_lds<16, 1>()));
+    CSD_HIP(ws_allow_lds<1>());
+    CSD_HIP(ws_allow_lds<2>());
     CSD_HIP((rs_allow_lds<16, 2>()));
+    CSD_HIP((rs_allow_lds<12, 2>()));
+    CSD_HIP((rs_allow_lds<11, 2>()));
+    CSD_HIP((rs_allow_lds<8, 2>()));
+    CSD_HIP((rs_allow_lds<6, 2>()));
     CSD_HIP((rs_allow_lds<8, 3>()));
+    CSD_HIP((rs_allow_lds<6, 3>()));
     return CSD_OK;
 }
 

@@ -210,7 +210,7 @@ struct csd_model {
     csd_model_cfg cfg;
     bool mfma = false;        // bf16 tiles + MFMA GEMMs; otherwise generic kernels on row-major weights
     bool mfma_attn = false;
-    int gemm_rs_min_rows = 65;   // blocks of this many rows or more (129 at most) take the GEMM that splits the rows over the waves
+    int gemm_rs_min_rows = 33;   // blocks of this many rows or more take the GEMM that splits the rows over the waves
     bool kperm = false;       // q / K rows kept in rotary pair order (see KvGeom)
     int hd = 0;               // n_heads * head_dim
     int seq_pad = 0;          // cache rows per sequence, padded to 64
@@ -234,7 +234,7 @@ struct csd_model {
     float *probs = nullptr;      // [m_max][V] when the caller does not want them
     float2 *rope = nullptr;      // (cos, sin) of the rotary angles of the current call [m_max][head_dim / 2]
     int attn_chunks_max = 0;
-    // the forward for blocks of up to 48 rows (csd_chain.hip): one input buffer per GEMM of a layer
+    // the forward for blocks of up to 32 rows (csd_chain.hip): one input buffer per GEMM of a layer
     // (two bf16 planes each, fragment order: QKV input, O input, gate|up input, down input) and the sums of
     // squares per (16-feature tile, row) behind the two folded norms
     bool chain_on = false;
@@ -290,7 +290,7 @@ int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, con
 int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st);
 int32_t csd_gemm_setup();    // MFMA models, at creation: lets the GEMM kernels use their dynamic LDS
 size_t csd_self_kv_bytes(const csd_model *mod);     // the self-attention part of the cache (arch 1 appends the cross part)
-// csd_chain.hip: forward for blocks of up to 48 rows, epilogues inside the GEMM kernels
+// csd_chain.hip: forward for blocks of up to 32 rows, epilogues inside the GEMM kernels
 int32_t csd_chain_setup();
 
 bool csd_chain_eligible(const csd_model *mod, int32_t B, int32_t m);

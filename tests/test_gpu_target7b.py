@@ -120,7 +120,7 @@ def test_target7b_batch8_prefix2048(big, k, oracle_b):
     activations through LDS (40 rows) and the row-split GEMM (136 rows); one sampled sequence is checked
     against the oracle."""
     P, O, gm, om, shape, seed = big
-    assert gm.path(8, k + 1) == (1 if 8 * (k + 1) <= 48 else 0)
+    assert gm.path(8, k + 1) == (1 if 8 * (k + 1) <= 32 else 0)
     t, B, m = 2048, 8, k + 1
     _fill(gm, om, shape, seed, t, B, oracle_b)
     block = I.token_ids(B * m, shape.vocab, seed, 200 + k).reshape(B, m).contiguous()

@@ -99,7 +99,7 @@ def test_bf16_paths_small_model(shape, gemm, attn, path):
     """Several key chunks and a ragged tail (prefix 200 = 128 + 72 keys; 5 and 13 block rows);
     every forward implementation against the oracle: generic kernels, the per-operation MFMA
     kernels, and the forward with the epilogues inside its GEMM kernels (the default for blocks of up to
-    48 rows: the 10-row block with one row tile, the 26-row block with two)."""
+    32 rows: the 10-row block with one row tile, the 26-row block with two)."""
     os.environ["CSD_GEMM"], os.environ["CSD_ATTN"], os.environ["CSD_PATH"] = gemm, attn, path
     try:
         gm, om = make_pair(shape, 7, 2, 300, 16, std=0.05)
@@ -144,7 +144,7 @@ def test_bf16_blocks_of_2_to_13_row_tiles_workgroup_tiled_gemms(B, m):
     rows = 128 + 32, 204 = 128 + 76); the FFN width (18 k-steps) leaves ragged chunk tails and the
     vocabulary (65 column tiles) a ragged last workgroup."""
     gm, om = make_pair(WIDE, 17, B, 96, 17, std=0.05)
-    assert gm.path(B, m) == (1 if B * m <= 48 else 0)
+    assert gm.path(B, m) == (1 if B * m <= 32 else 0)
     toks = I.token_ids(B * 64, WIDE.vocab, 17, 1).reshape(B, 64)
     prefill_both(gm, om, toks[:, :32], 16)
     cl = [32 - (b % 3) for b in range(B)]                  # ragged cache lengths
