@@ -67,6 +67,22 @@ def test_t5_bf16_small_every_kernel_combination(gemm, attn, path):
     print("t5 bf16", gemm, attn, "max err", e1, e2)
 
 
+@pytest.mark.parametrize("B,m", [(3, 13), (3, 17)])
+def test_t5_bf16_blocks_of_39_and_51_rows_row_split_gemm(B, m):
+    """More than 32 rows: the per-operation kernels with the GEMM that splits the rows over its waves (two row
+    tiles per wave, the fourth wave without rows), the cross-attention over 96 encoder rows and, at 17 rows per
+    sequence, a second row tile in both attentions; ragged cache lengths."""
+    gm, om = make_pair(BF_T5, 29, B, 300, 17, std=0.05)
+    assert gm.path(B, m) == 0
+    _cross_init(gm, om, BF_T5, B, 29)
+    toks = I.token_ids(B * 260, BF_T5.vocab, 29, 1).reshape(B, 260)
+    prefill_both(gm, om, toks[:, :160], 16)
+    cl = [160 - 3 * b for b in range(B)]
+    block = np.stack([toks[b, cl[b]:cl[b] + m].numpy() for b in range(B)])
+    err = _check(gm, om, block, cl, 2e-2, 1e-2, f"t5 B={B} m={m}")
+    print("t5 bf16 rows", B * m, "max err", err)
+
+
 def test_t5xxl_decoder_shape_block_of_k4_against_oracle():
     """Configuration 4 at full size: 24 layers, d_model 4096, 64 heads of 64, gated-GELU FFN 10240, vocab
     32128, 512 encoder rows projected by csd_cross_kv_init on both sides, 256 seeded cache rows, k = 4."""
