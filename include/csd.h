@@ -328,6 +328,13 @@ int32_t csd_debug_set_trace(csd_model *model, float *trace);
  * where it applies).  The environment variable CSD_PATH=multikernel at csd_model_create forces 0. */
 int32_t csd_debug_path(const csd_model *model, int32_t B, int32_t m);
 
+/* Test hook, host only (no device call): the launch plan of the GEMM that serves blocks of 33 to 144 rows, for an
+ * N x K weight matrix (N a multiple of 16, K of 32) and a block of `rows` rows when the partial-sum buffer holds
+ * max_splits planes of rows x N floats: *ct = 16-column tiles per workgroup, *S = K splits.  The plan comes as close
+ * to one workgroup per compute unit (256) as ceil(N / 16 / ct) * S allows, S <= 8, the wider workgroup on a tie.
+ * CSD_EINVAL for other shapes or rows outside [1, 144]. */
+int32_t csd_debug_gemm_plan(int32_t N, int32_t K, int32_t rows, int32_t max_splits, int32_t *ct, int32_t *S);
+
 /* Counter calibration for benchmarks: a plain streaming copy of `bytes` bytes (a multiple of 16; dst and
  * src are device pointers, 16-byte aligned, not overlapping), launched as kernel k_copy_calib, so that a
  * hardware counter's reading for exactly 2 x bytes of HBM traffic (one read, one write) can be taken

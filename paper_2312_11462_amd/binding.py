@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libcsd.so")
 
 EXPORTS = ["csd_version", "csd_last_hip_error", "csd_model_create", "csd_model_destroy", "csd_kv_bytes",
            "csd_kv_write", "csd_kv_read", "csd_cross_kv_init", "csd_bigram_fit", "csd_bigram_draft", "csd_maxgram_draft", "csd_verify_block",
-           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_review_ctx", "csd_bigram_draft_append", "csd_cascade_gate", "csd_verify_tree", "csd_tree_accept", "csd_tree_commit", "csd_debug_set_trace", "csd_debug_path", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
+           "csd_accept", "csd_verify_accept", "csd_verify_accept_static", "csd_review_ctx", "csd_bigram_draft_append", "csd_cascade_gate", "csd_verify_tree", "csd_tree_accept", "csd_tree_commit", "csd_debug_set_trace", "csd_debug_path", "csd_debug_gemm_plan", "csd_debug_copy", "csd_debug_read", "csd_debug_mfma",
            "csd_prof_enable", "csd_prof_read"]
 
 _STATUS = {-1: "CSD_EINVAL", -2: "CSD_ESHAPE", -3: "CSD_ENULL", -4: "CSD_EHIP", -5: "CSD_EUNSUPPORTED"}

@@ -402,6 +402,11 @@ extern "C" int32_t csd_debug_path(const csd_model *mod, int32_t B, int32_t m) {
     return csd_chain_eligible(mod, B, m) ? 1 : 0;
 }
 
+extern "C" int32_t csd_debug_gemm_plan(int32_t N, int32_t K, int32_t rows, int32_t max_splits, int32_t *ct, int32_t *S) {
+    if (max_splits < 1) return CSD_EINVAL;
+    return csd_rs_plan_host(N, K, rows, (size_t)max_splits * (size_t)rows * (size_t)N, ct, S);
+}
+
 __global__ __launch_bounds__(256) void k_copy_calib(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, size_t n) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);

@@ -735,21 +735,40 @@ static int rs_splits(int groups, int KS, int Mtot, int N, size_t part_floats) {
     while (groups * (S + 1) <= 256 && S < 8 && KS / (S + 1) >= 2 * WG_U_MAX && (size_t)(S + 1) * Mtot * N <= part_floats) S++;
     return S;
 }
-static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M,
-                              int Mtot, int *S_io, hipStream_t st) {
-    const int n_tiles = w.N / 16, KS = w.K / 32, MT = (M + 15) / 16;
+// rows: the rows of this launch (33 to 144), Mtot: the rows of the whole call (the partial-sum buffer holds S x Mtot x N
+// floats), S_fixed: the number of splits when an earlier row chunk of the call has chosen it, else 0.
+static void rs_plan(int N, int K, int rows, int Mtot, size_t part_floats, int S_fixed, int *ct_out, int *S_out) {
+    const int n_tiles = N / 16, KS = K / 32, MT = (rows + 15) / 16;
     const int rw = MT <= 8 ? 2 : 3;          // row tiles per compute wave: waves past the block's rows only pass the barriers
     static const int cts2[] = {16, 12, 11, 8, 6, 0}, cts3[] = {8, 6, 0};
     const int *cts = rw == 2 ? cts2 : cts3;
-    int ct = cts[0], S = *S_io;
+    int ct = cts[0], S = S_fixed;
     double best = -1.0;
     for (int i = 0; cts[i]; i++) {
         const int groups = (n_tiles + cts[i] - 1) / cts[i];
-        const int s = *S_io ? *S_io : rs_splits(groups, KS, Mtot, w.N, mod->part_floats);
+        const int s = S_fixed ? S_fixed : rs_splits(groups, KS, Mtot, N, part_floats);
         const int wgs = groups * s;
         const double fill = (double)wgs / (256.0 * ((wgs + 255) / 256));
         if (fill > best) best = fill, ct = cts[i], S = s;
     }
+    *ct_out = ct;
+    *S_out = S;
+}
+int32_t csd_rs_plan_host(int32_t N, int32_t K, int32_t rows, size_t part_floats, int32_t *ct, int32_t *S) {
+    if (!ct || !S) return CSD_ENULL;
+    if (N <= 0 || K <= 0 || N % 16 || K % 32 || rows < 1 || rows > 144) return CSD_EINVAL;
+    int c = 0, s = 0;
+    rs_plan(N, K, rows, rows, part_floats, 0, &c, &s);
+    *ct = c;
+    *S = s;
+    return CSD_OK;
+}
+static int32_t launch_gemm_rs(const csd_model *mod, const GemmW &w, const bf16_t *act, size_t plane, int mtp, float *part, int M,
+                              int Mtot, int *S_io, hipStream_t st) {
+    const int n_tiles = w.N / 16, MT = (M + 15) / 16;
+    const int rw = MT <= 8 ? 2 : 3;
+    int ct = 0, S = 0;
+    rs_plan(w.N, w.K, M, Mtot, mod->part_floats, *S_io, &ct, &S);
     *S_io = S;
     const int groups = (n_tiles + ct - 1) / ct;
     if (rw == 2) switch (ct) {

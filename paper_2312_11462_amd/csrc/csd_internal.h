@@ -289,6 +289,8 @@ int32_t csd_forward_enqueue(csd_model *mod, void *kv, const int32_t *tokens, con
                             int32_t B, int32_t m, float *logits, hipStream_t st);
 int32_t csd_pack_weights(csd_model *mod, const void *const *w, hipStream_t st);
 int32_t csd_gemm_setup();    // MFMA models, at creation: lets the GEMM kernels use their dynamic LDS
+// host only: column tiles per workgroup and K splits the row-split GEMM takes for an N x K matrix and a block of `rows` rows
+int32_t csd_rs_plan_host(int32_t N, int32_t K, int32_t rows, size_t part_floats, int32_t *ct, int32_t *S);
 size_t csd_self_kv_bytes(const csd_model *mod);     // the self-attention part of the cache (arch 1 appends the cross part)
 // csd_chain.hip: forward for blocks of up to 32 rows, epilogues inside the GEMM kernels
 int32_t csd_chain_setup();

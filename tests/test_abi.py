@@ -63,3 +63,35 @@ def test_null_and_domain_errors_without_a_device(L):
     assert L.csd_bigram_draft(one, one, 1, 0, one, 10, 2, 0, one, None, None) == -1
     assert L.csd_kv_bytes(None) == 0
     assert L.csd_verify_block(None, one, one, one, 1, 1, C.c_float(1.0), one, None, None) == -3
+
+
+def test_gemm_plan_of_tall_blocks_fills_the_compute_units(L):
+    """Host logic only: for blocks of 33 to 144 rows the row-split GEMM picks column tiles per workgroup and K
+    splits per matrix.  Properties that hold for every shape, and the plans of the 7B-shaped matrices at 128 and
+    136 rows (the launches the batch-8 profiles name)."""
+    def plan(N, K, rows, max_splits=16):
+        ct, S = C.c_int32(), C.c_int32()
+        assert L.csd_debug_gemm_plan(N, K, rows, max_splits, C.byref(ct), C.byref(S)) == 0
+        return ct.value, S.value
+    d, F, V = 4096, 11008, 32000
+    assert plan(3 * d, d, 128) == (12, 4)       # QKV: 64 groups x 4 = 256 workgroups
+    assert plan(d, d, 128) == (8, 8)            # O: 32 x 8 = 256
+    assert plan(d, F, 128) == (8, 8)            # down
+    assert plan(2 * F, d, 128) == (11, 2)       # gate|up: 126 x 2 = 252
+    assert plan(V, d, 128) == (16, 2)           # LM head: 125 x 2 = 250, the wider workgroup wins the tie with (8, 1)
+    assert plan(3 * d, d, 136) == (6, 2) and plan(2 * F, d, 136) == (6, 1) and plan(d, d, 136) == (8, 8)
+    assert plan(3 * d, d, 40) == plan(3 * d, d, 128)          # two row tiles per wave from 33 to 128 rows
+    for N, K in [(3 * d, d), (d, d), (d, F), (2 * F, d), (V, d), (768 * 3, 768), (768, 3072), (1040, 256), (16, 32)]:
+        for rows in (33, 64, 100, 128, 129, 144):
+            for ms in (1, 2, 16):
+                ct, S = plan(N, K, rows, ms)
+                assert ct in ((16, 12, 11, 8, 6) if rows <= 128 else (8, 6))
+                assert 1 <= S <= min(8, ms)
+                assert S == 1 or (K // 32) // S >= 8                     # a K slice holds at least two chunks of four k-steps
+                groups = -(-(N // 16) // ct)
+                assert S == 1 or groups * S <= 256                       # K is split only while the chip has room
+    bad = C.c_int32()
+    assert L.csd_debug_gemm_plan(100, 64, 128, 4, C.byref(bad), C.byref(bad)) == -1
+    assert L.csd_debug_gemm_plan(64, 64, 145, 4, C.byref(bad), C.byref(bad)) == -1
+    assert L.csd_debug_gemm_plan(64, 64, 64, 4, None, C.byref(bad)) == -3
+
