@@ -16,11 +16,20 @@
 
 #define ATT_CHUNK 128      /* keys per wave at least (the partial buffer is sized for this) */
 
+// ONCE: this launch reads every cache row once (one 16-row tile per sequence), so the rows are loaded non-temporally and
+// do not push each other out of the caches on their way through (batch 8 over 2048 rows: 55.7 -> 51.4 us per layer);
+// with more row tiles the later passes find part of the rows in the caches and plain loads are kept.
+template <bool ONCE>
+__device__ __forceinline__ u32x4 attn_load(const bf16_t *p) {
+    if constexpr (ONCE) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    else return *reinterpret_cast<const u32x4 *>(p);
+}
+
 // PRE: key tiles (32 keys) whose K and V fragments are requested together before any of them is used.
 // A small grid (few sequences and heads) is bound by the chain of memory round trips of each wave, not by
 // bandwidth: with PRE = 4 a wave has its whole 128-key chunk in flight at once (at the price of registers,
 // i.e. of waves per SIMD, which such a grid does not fill anyway).
-template <int DH, int PRE>
+template <int DH, int PRE, bool ONCE>
 __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, size_t qplane, int m, int row_tiles,
                                                   const int32_t *__restrict__ cache_len, KvGeom geo, int layer,
                                                   const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
@@ -85,11 +94,11 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
                     const int key = kb + 8 * (col >> 2) + 4 * T + (col & 3);
                     const bf16_t *kp = kc + (size_t)key * DH + 8 * g;
 #pragma unroll
-                    for (int s = 0; s < DH / 32; s++) kf[p][T][s] = *reinterpret_cast<const u32x4 *>(kp + s * 32);
+                    for (int s = 0; s < DH / 32; s++) kf[p][T][s] = attn_load<ONCE>(kp + s * 32);
                 }
 #pragma unroll
                 for (int dt = 0; dt < DH / 16; dt++)
-                    vfr[p][dt] = *reinterpret_cast<const u32x4 *>(vc + kv_v_idx(geo, dt * 16 + col, kb + 8 * g));
+                    vfr[p][dt] = attn_load<ONCE>(vc + kv_v_idx(geo, dt * 16 + col, kb + 8 * g));
             } else {
 #pragma unroll
                 for (int T = 0; T < 2; T++)
@@ -227,22 +236,26 @@ static void attn_launch(csd_model *mod, const KvGeom &geo, const void *kv, const
                         float scale, const AttnMode &mode, hipStream_t st, bf16_t *out, size_t out_plane) {
     const csd_model_cfg &c = mod->cfg;
     const int row_tiles = (m + 15) / 16;
-    // keys per wave: doubled while there are more than 2048 waves (two per SIMD): measured best at batch 8 with 2048
-    // cached rows (1.99 ms of attention per step against 2.47 at 4096 and 2.53 at 1024)
+    // keys per wave: doubled while there are more than 2048 waves (the kernel's registers allow two per SIMD, and waves
+    // beyond that wait for a second round): measured best at batch 8 with 2048 cached rows (1.99 ms of attention per
+    // step against 2.47 at 4096 and 2.53 at 1024)
     const int keys = mode.fixed_nk > 0 ? mode.fixed_nk : geo.seq_pad;
     int chunk_keys = ATT_CHUNK;
     while (chunk_keys < 1024 && (long long)((keys + chunk_keys - 1) / chunk_keys) * c.n_heads * B * row_tiles > 2048) chunk_keys *= 2;
     int chunks = (keys + chunk_keys - 1) / chunk_keys;
     if (chunks > mod->attn_chunks_max) chunks = mod->attn_chunks_max;
     // a grid the chip holds at one wave per SIMD: each wave requests its whole first 128 keys at once
+#define ATT_LAUNCH(PRE_, ONCE_)                                                                                        \
+    hipLaunchKernelGGL((k_attn_mfma<DH, PRE_, ONCE_>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st,             \
+                       (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale, \
+                       mod->attn_part, mod->attn_chunks_max, chunk_keys, mode)
     if ((long long)chunks * c.n_heads * B * row_tiles <= 1024)
-        hipLaunchKernelGGL((k_attn_mfma<DH, 4>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st,
-                           (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale,
-                           mod->attn_part, mod->attn_chunks_max, chunk_keys, mode);
+        ATT_LAUNCH(4, false);
+    else if (row_tiles == 1)
+        ATT_LAUNCH(1, true);
     else
-        hipLaunchKernelGGL((k_attn_mfma<DH, 1>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st,
-                           (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale,
-                           mod->attn_part, mod->attn_chunks_max, chunk_keys, mode);
+        ATT_LAUNCH(1, false);
+#undef ATT_LAUNCH
     hipLaunchKernelGGL((k_attn_merge<DH>), dim3(B * m, c.n_heads), dim3(DH), 0, st, mod->attn_part, m, row_tiles, cache_len,
                        c.n_heads, geo.seq_pad, mod->attn_chunks_max, chunk_keys, out, mod->hd, out_plane, mod->act_mtp,
                        mode.fixed_nk);
