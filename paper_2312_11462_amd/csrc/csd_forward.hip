@@ -55,7 +55,7 @@ __global__ void k_copy_cols(const T *__restrict__ src, int K, int N_src, T *__re
 // Every form writes fp32 partial sums per K split ([S][M][N]); the epilogue kernels reduce them in a
 // fixed order.
 
-// Blocks of up to 64 rows (MT row tiles).  A workgroup covers 4 * NT adjacent output tiles of one K slice
+// Blocks of up to 32 rows (MT row tiles; the launcher instantiates NT = 1, MT = 1 and 2).  A workgroup covers 4 * NT adjacent output tiles of one K slice
 // and shares the activation fragments through LDS: two chunks of U k-steps, laid out
 // [chunk][u][row tile][hi|lo plane][lane] in MFMA operand order, so a fragment is one conflict-free 16-byte
 // LDS read.  (A form with one independent wave per output tile re-read the activations from L2 in every
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(512) void k_gemm_ws(const u32x4 *__restrict__ Wp, c
     }
 }
 
-// Tall blocks (5 to 9 row tiles), where the matrix cores and LDS bandwidth matter as much as HBM: the
+// Blocks of 33 to 144 rows (3 to 9 row tiles), where the matrix cores and LDS bandwidth matter as much as HBM: the
 // rows are split over the 4 compute waves (RW row tiles each) and the weights are what is shared.  Waves
 // 4-7 stream the weight fragments of CT column tiles from HBM into LDS (two chunks ahead in registers, one
 // in LDS); a compute wave keeps its own rows' activation fragments in registers (fetched from L2 one chunk

@@ -139,10 +139,10 @@ WIDE = I.ModelShape("bf_wide_blocks", 0, "bf16", 2, 256, 4, 64, 576, 1040)
 
 @pytest.mark.parametrize("B,m", [(4, 5), (4, 9), (4, 13), (4, 17), (8, 12), (8, 14), (8, 16), (8, 17), (10, 16), (12, 17)])
 def test_bf16_blocks_of_2_to_13_row_tiles_workgroup_tiled_gemms(B, m):
-    """B * m = 20 ... 204 rows: every row-tile count of the GEMM that shares activations through LDS (up to
-    64 rows) and of the row-split GEMM (up to 144 rows), and two blocks that go in row chunks of 128 (160
-    rows = 128 + 32, 204 = 128 + 76); the FFN width (18 k-steps) leaves ragged chunk tails and the
-    vocabulary (65 column tiles) a ragged last workgroup."""
+    """B * m = 20 ... 204 rows: two row tiles on the forward with in-kernel epilogues, every row-tile count of the
+    row-split GEMM (33 to 144 rows: 3 to 9 row tiles, two or three per compute wave), and two blocks that go in row
+    chunks of 128 (160 rows = 128 + 32, the rest on the GEMM that shares activations through LDS; 204 = 128 + 76);
+    the FFN width (18 k-steps) leaves ragged chunk tails and the vocabulary (65 column tiles) a ragged last workgroup."""
     gm, om = make_pair(WIDE, 17, B, 96, 17, std=0.05)
     assert gm.path(B, m) == (1 if B * m <= 32 else 0)
     toks = I.token_ids(B * 64, WIDE.vocab, 17, 1).reshape(B, 64)
