@@ -35,7 +35,10 @@ __global__ __launch_bounds__(64) void k_attn_mfma(const bf16_t *__restrict__ q, 
                                                   const bf16_t *__restrict__ kv, float scale, float *__restrict__ part,
                                                   int chunks_max, int chunk_keys, AttnMode mode) {
     constexpr int PS = DH + 4;   // floats per partial row: DH outputs, running max, running sum, pad
-    const int c = blockIdx.x, hh = blockIdx.y, b = blockIdx.z / row_tiles, rt = blockIdx.z % row_tiles;
+    // the chunk index is the slowest grid dimension: the last chunk of every (sequence, head) holds the block's own few
+    // rows and little else, and with those short waves dispatched last the long ones land one per SIMD, four per
+    // compute unit (dispatched every fifth, they left one SIMD of most compute units with two long waves and one with none)
+    const int hh = blockIdx.x, b = blockIdx.y / row_tiles, rt = blockIdx.y % row_tiles, c = blockIdx.z;
     const int lane = threadIdx.x, col = lane & 15, g = lane >> 4;
     const int hd = geo.H * DH;
     const bool causal = mode.fixed_nk <= 0;
@@ -236,20 +239,26 @@ static void attn_launch(csd_model *mod, const KvGeom &geo, const void *kv, const
                         float scale, const AttnMode &mode, hipStream_t st, bf16_t *out, size_t out_plane) {
     const csd_model_cfg &c = mod->cfg;
     const int row_tiles = (m + 15) / 16;
-    // keys per wave: doubled while there are more than 2048 waves (the kernel's registers allow two per SIMD, and waves
-    // beyond that wait for a second round): measured best at batch 8 with 2048 cached rows (1.99 ms of attention per
-    // step against 2.47 at 4096 and 2.53 at 1024)
+    // Keys per wave.  The kernel's registers allow two waves per SIMD, and waves beyond 2048 would wait for a second
+    // round: chunks of 128 keys when that many waves fit; otherwise as many equal chunks per (sequence, head, row tile)
+    // as fit, of at least 512 keys (measured at batch 8 with 2048 cached rows, one row tile: 1.88 ms of attention per
+    // step with 4 to 6 chunks per head against 2.04 with 8; two row tiles: 2.40 ms with 4 equal chunks against 2.91
+    // with two of 1024 keys and a short third).
     const int keys = mode.fixed_nk > 0 ? mode.fixed_nk : geo.seq_pad;
-    int chunk_keys = ATT_CHUNK;
-    while (chunk_keys < 1024 && (long long)((keys + chunk_keys - 1) / chunk_keys) * c.n_heads * B * row_tiles > 2048) chunk_keys *= 2;
+    const long long items = (long long)c.n_heads * B * row_tiles;
+    const int n_max = (keys + ATT_CHUNK - 1) / ATT_CHUNK;
+    int n_c = (int)(2048 / items < n_max ? 2048 / items : n_max);
+    if (n_c < n_max && n_c > keys / 512) n_c = keys / 512;
+    if (n_c < 1) n_c = 1;
+    const int chunk_keys = n_c == n_max ? ATT_CHUNK : ((keys + n_c - 1) / n_c + 31) / 32 * 32;
     int chunks = (keys + chunk_keys - 1) / chunk_keys;
     if (chunks > mod->attn_chunks_max) chunks = mod->attn_chunks_max;
     // a grid the chip holds at one wave per SIMD: each wave requests its whole first 128 keys at once
 #define ATT_LAUNCH(PRE_, ONCE_)                                                                                        \
-    hipLaunchKernelGGL((k_attn_mfma<DH, PRE_, ONCE_>), dim3(chunks, c.n_heads, B * row_tiles), dim3(64), 0, st,             \
+    hipLaunchKernelGGL((k_attn_mfma<DH, PRE_, ONCE_>), dim3(c.n_heads, B * row_tiles, chunks), dim3(64), 0, st,             \
                        (const bf16_t *)mod->qbuf, mod->q_plane, m, row_tiles, cache_len, geo, layer, (const bf16_t *)kv, scale, \
                        mod->attn_part, mod->attn_chunks_max, chunk_keys, mode)
-    if ((long long)chunks * c.n_heads * B * row_tiles <= 1024)
+    if (chunk_keys == ATT_CHUNK && chunks * items <= 1024)
         ATT_LAUNCH(4, false);
     else if (row_tiles == 1)
         ATT_LAUNCH(1, true);
