@@ -624,7 +624,9 @@ __device__ __forceinline__ void attn_item(const AttnArgs &A, AttnLds<DH> &L, boo
 template <int DH>
 __global__ __launch_bounds__(256) void kc_attn(const AttnArgs A) {
     __shared__ __align__(16) AttnLds<DH> L;
-    attn_item<DH>(A, L, true, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
+    // Grid (head, sequence, chunk): the last chunk of a head holds little besides the block's own rows, and with the chunk
+    // index slowest those short workgroups are dispatched after every long one has a compute unit of its own.
+    attn_item<DH>(A, L, true, blockIdx.z, blockIdx.x, blockIdx.y, threadIdx.x);
 }
 
 // h[r] = E[token[r]]; (h * gain) as the first GEMM's input, the sums of squares per 16-feature tile, and the
@@ -859,7 +861,7 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
                 A.layer = l;
                 A.bias_hd = mode.bias_hd;
                 A.fixed_nk = mode.fixed_nk;
-                const dim3 grid(chunks, c.n_heads, B);
+                const dim3 grid(c.n_heads, B, chunks);     // chunk index slowest: see kc_attn
                 if (c.head_dim == 128)
                     hipLaunchKernelGGL((kc_attn<128>), grid, dim3(256), 0, st, A);
                 else
@@ -900,7 +902,7 @@ int32_t csd_chain_enqueue(csd_model *mod, void *kv, const int32_t *tokens, const
                     return rc;
             } else {
                 ProfScope ps(mod, st, CSD_PROF_ATTN);
-                const dim3 grid(chunks, c.n_heads, B);
+                const dim3 grid(c.n_heads, B, chunks);     // chunk index slowest: see kc_attn
                 if (c.head_dim == 128)
                     hipLaunchKernelGGL((kc_attn<128>), grid, dim3(256), 0, st, A);
                 else
