@@ -247,7 +247,7 @@ def main():
     # the dominant kernel: the weight-streaming GEMM.  One launch streams one matrix; the per-launch figures are
     # the step's weights over the step's GEMM launches.
     kernel = ("kc_gemm (GEMMs that own whole output tiles and hold their epilogues)" if path == 1 else
-              ("k_gemm_rs" if B * m > 64 else "k_gemm_ws") + " (split-K GEMMs with epilogue kernels)") + \
+              ("k_gemm_rs" if B * m > 32 else "k_gemm_ws") + " (split-K GEMMs with epilogue kernels)") + \
              ": all weight-streaming GEMM launches of a step"
     launch_bytes = ab["weights"]
     achieved = launch_bytes / 1e9 / (gemm_ms_step / 1e3) if gemm_ms_step > 0 else 0.0
@@ -266,7 +266,7 @@ def main():
     }
     if TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, path)):
         roofline["traffic"] = TRAFFIC_BYTES_PER_LAUNCH[(args.workload, path)]
-    if TRACE_LAUNCH_US.get((args.workload, path)):
+    if TRACE_LAUNCH_US.get((args.workload, path)) and gemm_launches_step > 0:
         us = TRACE_LAUNCH_US[(args.workload, path)]
         roofline["trace_avg_launch_us"] = us
         roofline["trace_frac"] = round(roofline["bytes_per_launch"] / 1e3 / us / HBM_PEAK_GBS, 4)
@@ -350,19 +350,36 @@ def main():
             for _ in range(3):
                 one()
             torch.cuda.synchronize()
-            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            c0.record()
-            for _ in range(args.cascade_steps):
-                one()
-            c1.record()
-            torch.cuda.synchronize()
+
+            def timed_loop(fn):
+                c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                c0.record()
+                for _ in range(args.cascade_steps):
+                    fn()
+                c1.record()
+                torch.cuda.synchronize()
+                return c0.elapsed_time(c1) / args.cascade_steps
+            eager_ms = timed_loop(one)
+            # the step holds no host synchronisation, so it is captured as it is, like the main step (--eager: not)
+            graph_ms = None
+            if not args.eager:
+                try:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        one()
+                    for _ in range(3):
+                        g.replay()
+                    torch.cuda.synchronize()
+                    graph_ms = timed_loop(g.replay)
+                except Exception as e:      # noqa: BLE001
+                    print("cascade step: graph capture failed, eager launches only:", e, file=sys.stderr)
             bad = [int(x.item()) for x in rc.status if int(x.item()) not in (0, 1)]
             if bad:
                 raise SystemExit("bench.py: a device-resident review did not fit its launch shape")
-            return c0.elapsed_time(c1) / args.cascade_steps, int(rc.ctx_len.item()) - (t + 1)
+            return (graph_ms if graph_ms is not None else eager_ms), int(rc.ctx_len.item()) - (t + 1), eager_ms, graph_ms is not None
 
-        csd_ms, csd_emitted = timed_chain([[n_from_draft_model, k_tail], [0, dk]])
-        sd_ms, sd_emitted = timed_chain([[k, 0], [0, 0]])
+        csd_ms, csd_emitted, csd_eager_ms, csd_graph = timed_chain([[n_from_draft_model, k_tail], [0, dk]])
+        sd_ms, sd_emitted, sd_eager_ms, sd_graph = timed_chain([[k, 0], [0, 0]])
         # tokens per target review under Section 4's i.i.d. acceptance model at synthetic rates (random-init models
         # accept next to nothing, so the measured step times are combined with assumed rates; the rates are inputs)
         a_td, a_dm, a_tm = 0.6, 0.4, 0.3     # target keeps a draft-model token / draft model keeps a Max-Gram token / target keeps a Max-Gram token
@@ -397,6 +414,7 @@ def main():
         csd_tokens = tot / trials
         sd_tokens = ewif.expected_tokens(a_td, k)
         cascade = {"ms": round(csd_ms, 4), "steps": args.cascade_steps,
+                   "launch": "hip graph replay" if csd_graph else "eager", "eager_ms": round(csd_eager_ms, 4),
                    "what": f"one step of Algorithm 1, K = [[{n_from_draft_model}, {k_tail}], [0, {dk}]]: the {dshape.name} model "
                            f"reviews {dk} Max-Gram drafts (twice when its first review yields one token; gated on the device), "
                            f"Max-Gram adds {k_tail}, the target reviews up to 16 rows against the draft level's own rows; "
@@ -404,7 +422,8 @@ def main():
                    "emitted_tokens_this_input": csd_emitted,
                    "sd_vs_csd": {"sd_ms": round(sd_ms, 4), "sd_what": f"plain speculative decoding: {k} one-row forwards of the "
                                  f"{dshape.name} model, then the target's review",
-                                 "csd_ms": round(csd_ms, 4),
+                                 "csd_ms": round(csd_ms, 4), "sd_eager_ms": round(sd_eager_ms, 4),
+                                 "sd_launch": "hip graph replay" if sd_graph else "eager",
                                  "assumed_acceptance": {"target_vs_draft_model": a_td, "draft_model_vs_maxgram": a_dm,
                                                         "target_vs_maxgram": a_tm},
                                  "tokens_per_review_sd": round(sd_tokens, 3), "tokens_per_review_csd": round(csd_tokens, 3),
