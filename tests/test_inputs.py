@@ -45,3 +45,25 @@ def test_repeat_stream_has_repeats():
     assert len(s) == 500 and s.min() >= 0 and s.max() < 32000
     bigrams = set(zip(s[:-1], s[1:]))
     assert len(bigrams) < 0.9 * 499
+
+
+def test_t5_recipe_keeps_unscaled_scores_of_order_one():
+    """arch 1 has no 1/sqrt(head_dim) in its scores (the family folds it into the query projection's initialisation), so
+    the recipe draws the query projections with std 0.02/sqrt(head_dim).  For unit-variance normalised rows the
+    score of a (query, key) pair has std  s_q * s_k * d * sqrt(head_dim): measured here on a one-layer shape of
+    width 1024, and evaluated for the T5-XXL-decoder shape with and without the smaller query std (13 against 1.6:
+    with 13 a random-init softmax is near one-hot and rounding differences double per layer)."""
+    shp = I.ModelShape("t5probe", 1, "fp32", 1, 1024, 16, 64, 64, 64, rms_eps=1e-6, enc_len=8)
+    w = dict(zip(I.weight_names(shp), I.make_weights(shp, 3)))
+    x = I.normal((256, 1024), 1.0, 3, 77)
+    H, dh = shp.n_heads, shp.head_dim
+    q = (x @ w["l0.wq"]).reshape(256, H, dh)
+    k = (x @ w["l0.wk"]).reshape(256, H, dh)
+    s = torch.einsum("ihd,jhd->hij", q, k)
+    want = (0.02 / dh ** 0.5) * 0.02 * 1024 * dh ** 0.5
+    off_diag = s[:, ~torch.eye(256, dtype=torch.bool)]
+    assert abs(off_diag.std().item() / want - 1.0) < 0.05, (off_diag.std().item(), want)
+    assert abs(w["l0.cq"].std().item() - 0.02 / 8) < 1e-4 and abs(w["l0.wk"].std().item() - 0.02) < 2e-4
+    xxl = I.WORKLOADS["t5xxl"]["shape"]
+    full = lambda s_q: s_q * 0.02 * xxl.d_model * xxl.head_dim ** 0.5
+    assert 12.5 < full(0.02) < 13.5 and 1.5 < full(0.02 / xxl.head_dim ** 0.5) < 1.8
