@@ -52,7 +52,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=400,
+                    help="untimed steps before the timed ones (default 400, about 1.3 s at the headline shape: the step time "
+                         "settles only after some tenths of a second of load, 3.19 ms after 20 steps against 3.12 after 400)")
     ap.add_argument("--workload", default="target7b")
     ap.add_argument("--k", type=int, default=None, help="drafts per sequence instead of the workload's (configuration 5 sweeps it)")
     ap.add_argument("--prof-steps", type=int, default=10)
