@@ -52,9 +52,11 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=400,
-                    help="untimed steps before the timed ones (default 400, about 1.3 s at the headline shape: the step time "
-                         "settles only after some tenths of a second of load, 3.19 ms after 20 steps against 3.12 after 400)")
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--settle-ms", type=float, default=1000.0,
+                    help="before the warm-up steps, run untimed steps for this long (part of the setup): the step time of a "
+                         "chip that comes from idle settles only after some tenths of a second of load (3.19 ms for 200 steps "
+                         "right after 20 warm-up steps, 3.12 after a second of load); 0 = none")
     ap.add_argument("--workload", default="target7b")
     ap.add_argument("--k", type=int, default=None, help="drafts per sequence instead of the workload's (configuration 5 sweeps it)")
     ap.add_argument("--prof-steps", type=int, default=10)
@@ -181,6 +183,12 @@ def main():
         model.verify_accept(block, cache_len, u_acc, u_samp, q=None, q_onehot=onehot, mode=mode,
                             n_accepted=n_acc, next_token=nxt)
 
+    if args.settle_ms > 0:
+        t_settle = time.perf_counter()
+        while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+            for _ in range(10):
+                step()
+            torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -516,7 +524,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "gpu_ms_per_step": round(gpu_ms_per_step, 4),
         "median_ms_single_step": None if median_single_ms is None else round(median_single_ms, 4),
-        "launch": "hip graph replay" if graph is not None else "eager",
+        "launch": "hip graph replay" if graph is not None else "eager", "settle_ms": args.settle_ms,
         "eager_ms_per_step": round(eager_ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
